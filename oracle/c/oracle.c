@@ -1,0 +1,268 @@
+/* CPU oracle in plain C for the HAC / sHAC formats and their dot procedures.
+ *
+ * TEST INFRASTRUCTURE.  Written from the paper (arXiv 2108.12704, Sect. IV);
+ * shares nothing with the HIP library.  Same readings as the Python oracle:
+ * b = 32-bit words, first stream bit = most significant bit of word 0,
+ * decoders stop on the symbol count, fp64 accumulation.
+ *
+ * The Huffman code itself is built by the Python oracle and handed in as
+ *   - values[k], code[k], len[k]      for encoding (H_W), and
+ *   - left[k-1 or 1], right[..], root for decoding (H_W^-1 as a binary tree:
+ *     node ids < k are leaves, internal node id i has children left[i-k],
+ *     right[i-k]).
+ *
+ * Build: gcc -O2 -shared -fPIC -pthread oracle.c -o liboracle.so
+ */
+#include <pthread.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---- bit writer: append `len` bits of `code`, most significant first ---- */
+typedef struct {
+    uint32_t *words;
+    int64_t cap;      /* capacity in words */
+    int64_t nbits;    /* bits written so far */
+    int overflow;
+} bitwriter;
+
+static void put_bits(bitwriter *bw, uint32_t code, int len)
+{
+    for (int t = len - 1; t >= 0; --t) {
+        int64_t w = bw->nbits / 32;
+        int pos = (int)(bw->nbits % 32);          /* 0 = most significant bit */
+        if (w >= bw->cap) { bw->overflow = 1; return; }
+        if ((code >> t) & 1u) bw->words[w] |= (uint32_t)1 << (31 - pos);
+        bw->nbits++;
+    }
+}
+
+static int find_symbol(const float *values, int k, float v)
+{
+    for (int i = 0; i < k; ++i)
+        if (values[i] == v) return i;
+    return -1;
+}
+
+/* HAC(W) (Sect. IV-B): all n*m entries in column order, zeros included.
+ * W is row-major with leading dimension m.  words[] must be zero-filled by
+ * the caller (that is the zero padding).  Returns 0, or -1 on a value outside
+ * the alphabet, -2 on overflow of words[]. */
+int oracle_hac_encode(const float *W, int64_t n, int64_t m,
+                      const float *values, const uint32_t *code, const int32_t *len, int32_t k,
+                      uint32_t *words, int64_t cap_words, int64_t *nbits_out)
+{
+    bitwriter bw = { words, cap_words, 0, 0 };
+    for (int64_t j = 0; j < m; ++j)
+        for (int64_t i = 0; i < n; ++i) {
+            int z = find_symbol(values, k, W[i * m + j]);
+            if (z < 0) return -1;
+            put_bits(&bw, code[z], len[z]);
+            if (bw.overflow) return -2;
+        }
+    *nbits_out = bw.nbits;
+    return 0;
+}
+
+/* sHAC(W) (Sect. IV-C): CSC arrays, nz Huffman-coded without the symbol 0.
+ * ri has room for cap_nz entries, cb for m+1. */
+int oracle_shac_encode(const float *W, int64_t n, int64_t m,
+                       const float *values, const uint32_t *code, const int32_t *len, int32_t k,
+                       uint32_t *words, int64_t cap_words, int64_t *nbits_out,
+                       int64_t *ri, int64_t cap_nz, int64_t *cb)
+{
+    bitwriter bw = { words, cap_words, 0, 0 };
+    int64_t q = 0;
+    cb[0] = 0;
+    for (int64_t j = 0; j < m; ++j) {
+        for (int64_t i = 0; i < n; ++i) {
+            float v = W[i * m + j];
+            if (v == 0.0f) continue;
+            int z = find_symbol(values, k, v);
+            if (z < 0) return -1;
+            if (q >= cap_nz) return -2;
+            put_bits(&bw, code[z], len[z]);
+            if (bw.overflow) return -2;
+            ri[q++] = i;
+        }
+        cb[j + 1] = q;
+    }
+    *nbits_out = bw.nbits;
+    return 0;
+}
+
+/* ---- next code word: walk the tree one bit at a time ----
+ * `node` plays the role of `rem` (what has been read of a codeword that is
+ * not complete yet); `oset` is the bit offset inside the current word S.
+ * Returns the symbol, or -1 ("null") when S is used up first. */
+typedef struct { const int32_t *left, *right; int32_t k, root; } tree_t;
+
+static int ncw(uint32_t S, int *oset, int32_t *node, const tree_t *t)
+{
+    while (*oset < 32) {
+        int bit = (S >> (31 - *oset)) & 1u;
+        (*oset)++;
+        *node = bit ? t->right[*node - t->k] : t->left[*node - t->k];
+        if (*node < t->k) {
+            int z = *node;
+            *node = t->root;
+            return z;
+        }
+    }
+    return -1;
+}
+
+int oracle_unpack(const uint32_t *words, int64_t N, int64_t count,
+                  const int32_t *left, const int32_t *right, int32_t k, int32_t root,
+                  int32_t *sym_out)
+{
+    tree_t t = { left, right, k, root };
+    int32_t node = root;
+    int64_t got = 0;
+    for (int64_t i = 0; i < N && got < count; ++i) {
+        int oset = 0, z;
+        while (got < count && (z = ncw(words[i], &oset, &node, &t)) >= 0)
+            sym_out[got++] = z;
+    }
+    return got == count ? 0 : -1;
+}
+
+/* Algorithm 1 (Dot_HAC): out[m] = x^T W, x has n entries. */
+int oracle_dot_hac(const uint32_t *C, int64_t N,
+                   const int32_t *left, const int32_t *right, int32_t k, int32_t root,
+                   const float *Hinv_values, const float *x, int64_t n, int64_t m, double *out)
+{
+    tree_t t = { left, right, k, root };
+    int64_t row = 0, col = 0, remaining = n * m;
+    double sum = 0.0;
+    int32_t node = root;
+    for (int64_t j = 0; j < m; ++j) out[j] = 0.0;
+    for (int64_t i = 0; i < N && remaining > 0; ++i) {
+        uint32_t S = C[i];
+        int oset = 0, z;
+        while (remaining > 0 && (z = ncw(S, &oset, &node, &t)) >= 0) {
+            remaining--;
+            sum += (double)x[row] * (double)Hinv_values[z];
+            row++;
+            if (row == n) {
+                row = 0;
+                out[col] = sum;
+                col++;
+                sum = 0.0;
+            }
+        }
+    }
+    return remaining == 0 ? 0 : -1;
+}
+
+/* Algorithm 2 (Dot_sHAC). */
+int oracle_dot_shac(const uint32_t *C, int64_t N1, const int64_t *ri, const int64_t *cb,
+                    const int32_t *left, const int32_t *right, int32_t k, int32_t root,
+                    const float *Hinv_values, const float *x, int64_t n, int64_t m, double *out)
+{
+    tree_t t = { left, right, k, root };
+    int64_t pos = 0, col = 0, q = cb[m];
+    double sum = 0.0;
+    int32_t node = root;
+    (void)n;
+    for (int64_t j = 0; j < m; ++j) out[j] = 0.0;
+    for (int64_t i = 0; i < N1 && pos < q; ++i) {
+        uint32_t S = C[i];
+        int oset = 0, z;
+        while (pos < q && (z = ncw(S, &oset, &node, &t)) >= 0) {
+            while (cb[col + 1] == pos) col++;              /* empty columns */
+            sum += (double)x[ri[pos]] * (double)Hinv_values[z];
+            pos++;
+            if (cb[col + 1] == pos) {
+                out[col] = sum;
+                sum = 0.0;
+                col++;
+            }
+        }
+    }
+    return pos == q ? 0 : -1;
+}
+
+/* Algorithm 3 (ParDot): rows of X in q chunks of ceil(rows/q), one thread per
+ * chunk, each row through Dot on the whole compressed matrix. */
+typedef struct {
+    int shac;
+    const uint32_t *C; int64_t N;
+    const int64_t *ri, *cb;
+    const int32_t *left, *right; int32_t k, root;
+    const float *values;
+    const float *X; int64_t ldx;
+    int64_t n, m;
+    double *out;
+    int64_t start, end;
+    int status;
+} par_job;
+
+static void *par_worker(void *arg)
+{
+    par_job *j = (par_job *)arg;
+    for (int64_t i = j->start; i < j->end; ++i) {
+        const float *x = j->X + i * j->ldx;
+        double *y = j->out + i * j->m;
+        int rc = j->shac
+            ? oracle_dot_shac(j->C, j->N, j->ri, j->cb, j->left, j->right, j->k, j->root,
+                              j->values, x, j->n, j->m, y)
+            : oracle_dot_hac(j->C, j->N, j->left, j->right, j->k, j->root,
+                             j->values, x, j->n, j->m, y);
+        if (rc) j->status = rc;
+    }
+    return NULL;
+}
+
+static int pardot(par_job proto, int64_t rows, int32_t q)
+{
+    if (rows <= 0) return 0;
+    if (q < 1) q = 1;
+    int64_t chunk = (rows + q - 1) / q;
+    pthread_t *th = (pthread_t *)malloc(sizeof(pthread_t) * (size_t)q);
+    par_job *jobs = (par_job *)malloc(sizeof(par_job) * (size_t)q);
+    if (!th || !jobs) { free(th); free(jobs); return -3; }
+    int started = 0, rc = 0;
+    for (int32_t t = 0; t < q; ++t) {
+        int64_t s = (int64_t)t * chunk, e = s + chunk < rows ? s + chunk : rows;
+        if (s >= rows) break;
+        jobs[started] = proto;
+        jobs[started].start = s;
+        jobs[started].end = e;
+        jobs[started].status = 0;
+        if (pthread_create(&th[started], NULL, par_worker, &jobs[started])) { rc = -3; break; }
+        started++;
+    }
+    for (int t = 0; t < started; ++t) {
+        pthread_join(th[t], NULL);
+        if (jobs[t].status) rc = jobs[t].status;
+    }
+    free(th);
+    free(jobs);
+    return rc;
+}
+
+int oracle_pardot_hac(const uint32_t *C, int64_t N,
+                      const int32_t *left, const int32_t *right, int32_t k, int32_t root,
+                      const float *values, const float *X, int64_t rows, int64_t ldx,
+                      int64_t n, int64_t m, int32_t q, double *out)
+{
+    par_job p;
+    memset(&p, 0, sizeof p);
+    p.shac = 0; p.C = C; p.N = N; p.left = left; p.right = right; p.k = k; p.root = root;
+    p.values = values; p.X = X; p.ldx = ldx; p.n = n; p.m = m; p.out = out;
+    return pardot(p, rows, q);
+}
+
+int oracle_pardot_shac(const uint32_t *C, int64_t N1, const int64_t *ri, const int64_t *cb,
+                       const int32_t *left, const int32_t *right, int32_t k, int32_t root,
+                       const float *values, const float *X, int64_t rows, int64_t ldx,
+                       int64_t n, int64_t m, int32_t q, double *out)
+{
+    par_job p;
+    memset(&p, 0, sizeof p);
+    p.shac = 1; p.C = C; p.N = N1; p.ri = ri; p.cb = cb;
+    p.left = left; p.right = right; p.k = k; p.root = root;
+    p.values = values; p.X = X; p.ldx = ldx; p.n = n; p.m = m; p.out = out;
+    return pardot(p, rows, q);
+}
