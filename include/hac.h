@@ -1,0 +1,216 @@
+/* hac.h -- C ABI of libhac: HAC / sHAC compressed layer matrices and the
+ * product Y = X.W computed straight from the compressed form on an MI355X.
+ *
+ * Source of the definitions: "Compact representations of convolutional neural
+ * networks via weight pruning and quantization" (arXiv 2108.12704), Sect. IV.
+ *   HAC  (Sect. IV-B): all n*m entries of W, zeros included, in column order,
+ *        each replaced by its Huffman codeword; the bit stream is cut into
+ *        32-bit words, the last one zero-padded.
+ *   sHAC (Sect. IV-C): CSC form (nz, ri, cb of Sect. IV-A); nz Huffman-coded
+ *        without the symbol 0; ri and cb stored beside it.
+ *   dot  (Algorithms 1-3): Y = X.W where W is the decoded matrix; X holds one
+ *        input vector per row.
+ *
+ * Conventions
+ *   - W is n x m (n input features, m outputs).  X is B x n, Y is B x m, both
+ *     row-major fp32 with leading dimensions ldx >= n, ldy >= m (in elements).
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
+ *     memory of the current device.  The library never allocates or frees
+ *     device memory and never synchronises a stream.
+ *   - Every function returns HAC_OK (0) or a negative hac_status; nothing
+ *     throws across this boundary.  No global mutable state; calls on distinct
+ *     arguments may run concurrently from several threads.
+ *   - A blob is one flat, relocatable byte buffer: a 256-byte header
+ *     (hac_desc_t) followed by 256-byte-aligned sections.  Copy it to the
+ *     device verbatim (any 256-byte-aligned address); keep the header on the
+ *     host and pass it to the device calls as `desc`.
+ *
+ * Stream bit order: the first bit of the stream is bit 31 of word 0 (Sect.
+ * IV-B leaves the order inside a word open).  The code is a canonical Huffman
+ * code: optimal lengths, codewords assigned in order of (length, symbol) --
+ * any optimal prefix code is a valid H_W.  Symbols number the distinct fp32
+ * values that occur in W: 0.0 first when it occurs, then ascending.
+ */
+#ifndef HAC_H
+#define HAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HAC_OK         =  0,
+    HAC_EINVAL     = -1,   /* null pointer, bad size, wrong format for this call        */
+    HAC_ENOMEM     = -2,   /* host allocation failed                                     */
+    HAC_EFORMAT    = -3,   /* blob fails validation (magic, bounds, index, code tables)  */
+    HAC_ERANGE     = -4,   /* codeword > 32 bits, or a count exceeds the format's limits */
+    HAC_EHIP       = -5,   /* a HIP call failed; see hac_last_hip_error()                */
+    HAC_EWORKSPACE = -6    /* workspace missing or smaller than hac_workspace_bytes()    */
+} hac_status;
+
+enum { HAC_FORMAT_HAC = 1, HAC_FORMAT_SHAC = 2 };
+
+/* A hipStream_t, spelled without pulling in the HIP headers. */
+typedef void *hac_stream_t;
+
+/* Encoder options; pass NULL for the defaults given in brackets. */
+typedef struct {
+    uint32_t chunk_rows;  /* HAC: rows of one column per index entry [512]; 0 = default   */
+    uint32_t chunk_nnz;   /* sHAC: non-zeros per index entry, restarting at every column
+                             [32]; 0 = default                                             */
+    uint32_t ri_bits;     /* sHAC row-index field width: 0 = ceil(log2 n) (footnote of
+                             Sect. IV-A), 32 = one word per index as in Corollary 2        */
+    uint32_t lut_bits;    /* width of the first-level decode table, 1..12 [min(Lmax,11)]  */
+} hac_opts_t;
+
+/* Blob header == descriptor.  All offsets are bytes from the start of the blob. */
+typedef struct {
+    uint32_t magic;        /* 'HAC1' = 0x31434148                                          */
+    uint32_t version;      /* 1                                                            */
+    uint32_t format;       /* HAC_FORMAT_HAC / HAC_FORMAT_SHAC                             */
+    uint32_t header_bytes; /* 256                                                          */
+    uint64_t n, m;         /* shape of W                                                   */
+    uint64_t nnz;          /* q: entries different from 0.0                                */
+    uint64_t total_bits;   /* |HAC(W)| resp. |HAC(nz)|: exact stream length                */
+    uint64_t n_words;      /* N resp. N1 = ceil(total_bits / 32)                           */
+    uint32_t k_sym;        /* alphabet size (HAC counts the value 0 when it occurs)        */
+    uint32_t lmax;         /* longest codeword, <= 32                                      */
+    uint32_t lut_bits;     /* first-level table has 2^lut_bits entries                     */
+    uint32_t has_zero;     /* HAC: 1 when 0.0 occurs in W; it is then symbol 0             */
+    uint32_t zero_len;     /* HAC: codeword length of symbol 0 when that codeword is all
+                              zero bits (it is one of the shortest), else 0                */
+    uint32_t chunk;        /* HAC: rows per chunk; sHAC: non-zeros per chunk               */
+    uint32_t ri_bits;      /* sHAC: width of one row-index field                           */
+    uint32_t chunks_per_col; /* HAC: ceil(n / chunk)                                       */
+    uint64_t n_chunks;     /* number of index entries (the index arrays hold one more)     */
+    uint64_t off_codebook; /* float[k_sym]: symbol -> shared value (H^-1's values)         */
+    uint64_t off_codelen;  /* uint8[k_sym]: codeword length per symbol                     */
+    uint64_t off_canon;    /* uint32[3][33]: first_code[l], count[l], first_index[l]       */
+    uint64_t off_symsort;  /* uint32[k_sym]: symbols in (length, symbol) order             */
+    uint64_t off_lut;      /* uint32[2^lut_bits]: (symbol << 6) | length, 0 = longer code  */
+    uint64_t off_stream;   /* uint32[n_words], followed by >= 16 bytes of zeros            */
+    uint64_t off_chunk_bit;/* uint32[n_chunks + 1]: bit offset where each chunk starts     */
+    uint64_t off_chunk_pos;/* HAC: uint32[n_chunks + 1]: non-zeros before each chunk       */
+    uint64_t off_col_chunk;/* sHAC: uint32[m + 1]: first chunk of each column              */
+    uint64_t off_cb;       /* sHAC: uint32[m + 1]: column begins, 0-based, cb[m] = nnz     */
+    uint64_t off_ri;       /* sHAC: row indices, ri_bits-wide fields packed MSB-first into
+                              uint32 words, followed by >= 16 bytes of zeros               */
+    uint64_t blob_bytes;   /* total size                                                   */
+    uint64_t reserved[8];
+} hac_desc_t;
+
+/* Sizes as the paper accounts for them (Sect. IV-B/IV-C) next to the real ones. */
+typedef struct {
+    uint64_t stream_bits;      /* exact |HAC(.)|                                           */
+    uint64_t stream_bytes;     /* 4 * n_words                                              */
+    uint64_t table_bytes;      /* codebook + lengths + canonical tables + first-level table*/
+    uint64_t index_bytes;      /* chunk index added for the GPU (not part of the format)   */
+    uint64_t ri_bytes, cb_bytes;
+    uint64_t blob_bytes;
+    uint64_t paper_bits;       /* 32*N + 6*32*k (+ 32*(q + m + 1) for sHAC): the quantity
+                                  bounded by Corollary 1 / Corollary 2                     */
+    double   bound_bits;       /* Corollary 1 / Corollary 2 with b = 32                    */
+    double   entropy_bits;     /* source entropy H per symbol                              */
+    double   avg_code_bits;    /* total_bits / symbols, H <= avg <= H + 1                  */
+    double   psi;              /* blob_bytes / (4 n m): occupancy ratio of what is stored  */
+} hac_stats_t;
+
+/* Optional launch overrides for the dot calls (NULL = library defaults).  Any
+ * field left 0 keeps its default.  Values outside the documented range give
+ * HAC_EINVAL; they never change the result, only how the work is split. */
+typedef struct {
+    uint32_t cols_per_wave;   /* columns of W one wavefront handles, 1..64                 */
+    uint32_t waves_per_block; /* 1..16                                                     */
+    uint32_t variant;         /* 0 = default kernel choice; other values select a named
+                                 variant, see hac_dot                                      */
+    uint32_t reserved[5];
+} hac_launch_t;
+
+/* ---- host side ------------------------------------------------------------ */
+
+/* Encode W (host, row-major, leading dimension ldw >= m) into a HAC blob
+ * (Sect. IV-B).  -0.0 is stored as +0.0; NaN/Inf give HAC_EINVAL.  n, m >= 1.
+ * On success *blob is malloc'ed by the library (release with hac_free) and
+ * *blob_bytes is its size. */
+int hac_encode(const float *W, int64_t n, int64_t m, int64_t ldw,
+               const hac_opts_t *opts, void **blob, size_t *blob_bytes);
+
+/* Same for sHAC (Sect. IV-C): CSC with Huffman-coded nz, packed ri, cb. */
+int shac_encode(const float *W, int64_t n, int64_t m, int64_t ldw,
+                const hac_opts_t *opts, void **blob, size_t *blob_bytes);
+
+/* Release a blob returned by an encode call (NULL is allowed). */
+void hac_free(void *blob);
+
+/* Check a host blob: header, section bounds, code tables (Kraft equality,
+ * canonical order, first-level table), monotone index, cb monotone with
+ * cb[m] = nnz.  With deep != 0 the stream is also decoded from bit 0 and every
+ * index entry, symbol count and row index (< n, ascending in a column) is
+ * checked against it.  Never reads outside [blob, blob + bytes). */
+int hac_validate(const void *blob, size_t bytes, int deep);
+
+/* Copy the header of a validated host blob into *desc (header checks only). */
+int hac_describe(const void *blob, size_t bytes, hac_desc_t *desc);
+
+/* Size accounting for a host blob. */
+int hac_stats(const void *blob, size_t bytes, hac_stats_t *out);
+
+/* The library's own sequential CPU decoder (it ignores the chunk index).
+ * HAC : W_out (n*m, row-major, may be NULL), sym_out (n*m symbols in column
+ *       order, may be NULL); row_out, col_out must be NULL.
+ * sHAC: W_out as above; sym_out, row_out, col_out (each nnz entries, CSC
+ *       order, each may be NULL). */
+int hac_decode_host(const void *blob, size_t bytes, float *W_out, int32_t *sym_out,
+                    int32_t *row_out, int32_t *col_out);
+
+/* ---- device side (asynchronous on `stream`) -------------------------------- */
+
+/* Bytes of device workspace hac_dot / shac_dot need for a batch of B rows
+ * (0 when none is needed).  The workspace holds X re-laid out feature-major. */
+size_t hac_workspace_bytes(const hac_desc_t *desc, int64_t B);
+
+/* Y[B x m] = X[B x n] . W with W given as a HAC blob on the device
+ * (Algorithm 1 for every row of X as in Algorithm 3; the stream is decoded
+ * once per launch, not once per row).  Y is overwritten.  d_blob must be
+ * 256-byte aligned, d_ws 256-byte aligned and >= hac_workspace_bytes().
+ * B = 0 is a no-op.  fp32 accumulation; the order of the additions is fixed,
+ * so results are bitwise reproducible run to run. */
+int hac_dot(const hac_desc_t *desc, const void *d_blob,
+            const float *d_X, int64_t B, int64_t ldx,
+            float *d_Y, int64_t ldy,
+            void *d_ws, size_t ws_bytes,
+            const hac_launch_t *launch, hac_stream_t stream);
+
+/* Same for an sHAC blob (Algorithm 2): also unpacks the row-index fields and
+ * writes 0 to the columns that hold no non-zero. */
+int shac_dot(const hac_desc_t *desc, const void *d_blob,
+             const float *d_X, int64_t B, int64_t ldx,
+             float *d_Y, int64_t ldy,
+             void *d_ws, size_t ws_bytes,
+             const hac_launch_t *launch, hac_stream_t stream);
+
+/* TEST ONLY: materialise what the device decoder sees.
+ * d_W  : n*m floats, row-major (every entry written);
+ * d_sym: n*m int32 symbols in column order (every entry written). */
+int hac_decode_dev(const hac_desc_t *desc, const void *d_blob,
+                   float *d_W, int32_t *d_sym, hac_stream_t stream);
+
+/* TEST ONLY: d_nz, d_sym, d_row, d_col each hold nnz entries in CSC order. */
+int shac_decode_dev(const hac_desc_t *desc, const void *d_blob,
+                    float *d_nz, int32_t *d_sym, int32_t *d_row, int32_t *d_col,
+                    hac_stream_t stream);
+
+/* Text for a status code; never NULL. */
+const char *hac_strerror(int status);
+
+/* hipError_t value of the most recent HIP failure on the calling thread
+ * (0 if none); cleared by the next successful device call of that thread. */
+int hac_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HAC_H */

@@ -1,0 +1,784 @@
+// Host side of libhac: encoders, blob validation, size accounting and a
+// sequential decoder.  Definitions follow arXiv 2108.12704 Sect. IV-A (CSC),
+// IV-B (HAC) and IV-C (sHAC); the chunk index is this library's addition for
+// the GPU (the paper's conclusions only suggest per-column offsets).
+#include "../../include/hac.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <functional>
+#include <new>
+#include <queue>
+#include <utility>
+#include <vector>
+
+static_assert(sizeof(hac_desc_t) == 256, "blob header must be 256 bytes");
+
+namespace {
+
+constexpr uint32_t kMagic = 0x31434148u;   // "HAC1"
+constexpr uint32_t kVersion = 1;
+constexpr uint64_t kAlign = 256;
+constexpr uint64_t kTailPad = 16;          // zero bytes after stream / ri for window over-reads
+
+inline uint64_t align_up(uint64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+inline uint32_t float_bits(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
+
+// ---- small open-addressing map: fp32 bit pattern -> dense id --------------------
+struct ValueMap {
+    std::vector<uint32_t> keys;
+    std::vector<uint32_t> ids;
+    std::vector<uint8_t> used;
+    uint32_t mask = 0;
+    uint32_t count = 0;
+
+    void init(uint32_t cap_pow2) {
+        keys.assign(cap_pow2, 0); ids.assign(cap_pow2, 0); used.assign(cap_pow2, 0);
+        mask = cap_pow2 - 1; count = 0;
+    }
+    static uint32_t hash(uint32_t k) { k ^= k >> 16; k *= 0x7feb352du; k ^= k >> 15; k *= 0x846ca68bu; k ^= k >> 16; return k; }
+    void grow() {
+        ValueMap bigger; bigger.init((mask + 1) * 2);
+        for (uint32_t i = 0; i <= mask; ++i) if (used[i]) bigger.insert(keys[i], ids[i]);
+        *this = std::move(bigger);
+    }
+    void insert(uint32_t key, uint32_t id) {
+        uint32_t h = hash(key) & mask;
+        while (used[h]) h = (h + 1) & mask;
+        used[h] = 1; keys[h] = key; ids[h] = id; ++count;
+    }
+    // returns id, inserting a fresh one (= current count) when absent
+    uint32_t find_or_add(uint32_t key) {
+        uint32_t h = hash(key) & mask;
+        while (used[h]) { if (keys[h] == key) return ids[h]; h = (h + 1) & mask; }
+        if ((count + 1) * 2 > mask + 1) { grow(); return find_or_add(key); }
+        used[h] = 1; keys[h] = key; ids[h] = count;
+        return count++;
+    }
+};
+
+// ---- Huffman code lengths: merge the two least frequent nodes (Huffman 1952) ---
+// Ties: lower (weight, node id) first; leaves are numbered by symbol, internal
+// nodes after them in creation order.  A one-symbol alphabet gets length 1.
+bool huffman_lengths(const std::vector<uint64_t>& freq, std::vector<uint8_t>& len, uint32_t& lmax)
+{
+    const size_t k = freq.size();
+    len.assign(k, 0);
+    lmax = 0;
+    if (k == 0) return true;
+    if (k == 1) { len[0] = 1; lmax = 1; return true; }
+    typedef std::pair<uint64_t, uint32_t> node;                  // (weight, id)
+    std::priority_queue<node, std::vector<node>, std::greater<node> > pq;
+    for (size_t i = 0; i < k; ++i) pq.push(node(freq[i], (uint32_t)i));
+    std::vector<uint32_t> parent(2 * k - 1, 0);
+    uint32_t next = (uint32_t)k;
+    while (pq.size() > 1) {
+        node a = pq.top(); pq.pop();
+        node b = pq.top(); pq.pop();
+        parent[a.second] = next; parent[b.second] = next;
+        pq.push(node(a.first + b.first, next));
+        ++next;
+    }
+    const uint32_t root = next - 1;
+    std::vector<uint32_t> depth(2 * k - 1, 0);
+    for (uint32_t v = root; v-- > 0;) depth[v] = depth[parent[v]] + 1;   // parents have larger ids
+    for (size_t i = 0; i < k; ++i) {
+        if (depth[i] > 32) return false;
+        len[i] = (uint8_t)depth[i];
+        lmax = std::max<uint32_t>(lmax, depth[i]);
+    }
+    return true;
+}
+
+struct CodeTables {
+    std::vector<uint32_t> code;        // canonical codeword per symbol (right-justified)
+    std::vector<uint32_t> symsort;     // symbols in (length, symbol) order
+    uint32_t first_code[33], count[33], first_index[33];
+};
+
+void canonical_codes(const std::vector<uint8_t>& len, CodeTables& t)
+{
+    const size_t k = len.size();
+    t.code.assign(k, 0);
+    t.symsort.resize(k);
+    for (int l = 0; l <= 32; ++l) t.first_code[l] = t.count[l] = t.first_index[l] = 0;
+    for (size_t i = 0; i < k; ++i) t.count[len[i]]++;
+    uint32_t idx = 0;
+    uint64_t c = 0;
+    for (int l = 1; l <= 32; ++l) {
+        c <<= 1;
+        t.first_code[l] = (uint32_t)c;
+        t.first_index[l] = idx;
+        c += t.count[l];
+        idx += t.count[l];
+    }
+    std::vector<uint32_t> fill(33, 0);
+    for (size_t i = 0; i < k; ++i) {                    // ascending symbol within a length
+        const uint32_t l = len[i];
+        const uint32_t r = fill[l]++;
+        t.code[i] = t.first_code[l] + r;
+        t.symsort[t.first_index[l] + r] = (uint32_t)i;
+    }
+}
+
+void build_lut(const std::vector<uint8_t>& len, const CodeTables& t, uint32_t lut_bits,
+               std::vector<uint32_t>& lut)
+{
+    lut.assign((size_t)1 << lut_bits, 0);
+    for (size_t s = 0; s < len.size(); ++s) {
+        const uint32_t l = len[s];
+        if (l > lut_bits) continue;
+        const uint32_t lo = t.code[s] << (lut_bits - l);
+        const uint32_t span = 1u << (lut_bits - l);
+        for (uint32_t e = 0; e < span; ++e) lut[lo + e] = ((uint32_t)s << 6) | l;
+    }
+}
+
+// ---- bit writer: MSB-first into uint32 words; the buffer starts zeroed ----------
+struct BitWriter {
+    uint32_t* words;
+    uint64_t bitpos;
+    inline void put(uint32_t code, uint32_t len) {
+        const uint64_t w = bitpos >> 5;
+        const uint32_t off = (uint32_t)(bitpos & 31);
+        const uint64_t v = (uint64_t)code << (64 - len - off);   // len <= 32, off <= 31
+        words[w] |= (uint32_t)(v >> 32);
+        const uint32_t lo = (uint32_t)v;
+        if (lo) words[w + 1] |= lo;
+        bitpos += len;
+    }
+    inline void skip(uint64_t bits) { bitpos += bits; }          // run of zero bits
+};
+
+// ---- CSC-like intermediate shared by both encoders ------------------------------
+struct Scan {
+    int64_t n = 0, m = 0;
+    std::vector<float> values;         // alphabet of the non-zero values, ascending
+    std::vector<uint64_t> freq;        // their counts
+    uint64_t zeros = 0;
+    std::vector<uint64_t> cb;          // m + 1
+    std::vector<uint32_t> ri;          // nnz
+    std::vector<uint32_t> sym;         // nnz: index into `values`
+};
+
+int scan_matrix(const float* W, int64_t n, int64_t m, int64_t ldw, Scan& s)
+{
+    s.n = n; s.m = m;
+    ValueMap map; map.init(1024);
+    std::vector<uint32_t> raw_keys;
+    std::vector<uint64_t> colcount((size_t)m, 0);
+    uint64_t nnz = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        const float* row = W + i * ldw;
+        for (int64_t j = 0; j < m; ++j) {
+            const float v = row[j];
+            if (v == 0.0f) continue;                       // +0.0 and -0.0 both count as null
+            if (!std::isfinite(v)) return HAC_EINVAL;
+            colcount[(size_t)j]++; nnz++;
+        }
+    }
+    if (nnz > 0xfffffff0ull) return HAC_ERANGE;
+    s.zeros = (uint64_t)n * (uint64_t)m - nnz;
+    s.cb.assign((size_t)m + 1, 0);
+    for (int64_t j = 0; j < m; ++j) s.cb[(size_t)j + 1] = s.cb[(size_t)j] + colcount[(size_t)j];
+    s.ri.resize((size_t)nnz);
+    s.sym.resize((size_t)nnz);
+    std::vector<uint64_t> cursor(s.cb.begin(), s.cb.end() - 1);
+    std::vector<uint64_t> rawfreq;
+    for (int64_t i = 0; i < n; ++i) {                      // ascending i keeps rows sorted per column
+        const float* row = W + i * ldw;
+        for (int64_t j = 0; j < m; ++j) {
+            const float v = row[j];
+            if (v == 0.0f) continue;
+            const uint32_t id = map.find_or_add(float_bits(v));
+            if (id == rawfreq.size()) { rawfreq.push_back(0); raw_keys.push_back(float_bits(v)); }
+            rawfreq[id]++;
+            const uint64_t p = cursor[(size_t)j]++;
+            s.ri[(size_t)p] = (uint32_t)i;
+            s.sym[(size_t)p] = id;
+        }
+    }
+    // renumber ids so that values ascend
+    const size_t k = rawfreq.size();
+    std::vector<uint32_t> order(k);
+    for (size_t i = 0; i < k; ++i) order[i] = (uint32_t)i;
+    std::vector<float> rawval(k);
+    for (size_t i = 0; i < k; ++i) std::memcpy(&rawval[i], &raw_keys[i], 4);
+    std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return rawval[a] < rawval[b]; });
+    std::vector<uint32_t> rank(k);
+    s.values.resize(k); s.freq.resize(k);
+    for (size_t r = 0; r < k; ++r) { rank[order[r]] = (uint32_t)r; s.values[r] = rawval[order[r]]; s.freq[r] = rawfreq[order[r]]; }
+    for (size_t p = 0; p < s.sym.size(); ++p) s.sym[p] = rank[s.sym[p]];
+    return HAC_OK;
+}
+
+struct Section { uint64_t off, bytes; };
+
+struct Layout {
+    hac_desc_t d;
+    uint64_t cursor;
+    Layout() { std::memset(&d, 0, sizeof d); cursor = sizeof(hac_desc_t); }
+    uint64_t place(uint64_t bytes) { uint64_t o = align_up(cursor); cursor = o + bytes; return o; }
+};
+
+uint32_t ceil_log2(uint64_t v) { uint32_t b = 0; while (((uint64_t)1 << b) < v) ++b; return b; }
+
+int check_args(const float* W, int64_t n, int64_t m, int64_t ldw, void** blob, size_t* bytes)
+{
+    if (!W || !blob || !bytes) return HAC_EINVAL;
+    if (n < 1 || m < 1 || ldw < m) return HAC_EINVAL;
+    if (n > 0x7fffffffll || m > 0x7fffffffll) return HAC_ERANGE;
+    return HAC_OK;
+}
+
+// Fills the sections common to both formats (tables) and returns the blob.
+int write_tables(uint8_t* base, const hac_desc_t& d, const std::vector<float>& codebook,
+                 const std::vector<uint8_t>& len, const CodeTables& t, const std::vector<uint32_t>& lut)
+{
+    if (!codebook.empty()) std::memcpy(base + d.off_codebook, codebook.data(), codebook.size() * 4);
+    if (!len.empty()) std::memcpy(base + d.off_codelen, len.data(), len.size());
+    uint32_t* canon = reinterpret_cast<uint32_t*>(base + d.off_canon);
+    std::memcpy(canon, t.first_code, 33 * 4);
+    std::memcpy(canon + 33, t.count, 33 * 4);
+    std::memcpy(canon + 66, t.first_index, 33 * 4);
+    if (!t.symsort.empty()) std::memcpy(base + d.off_symsort, t.symsort.data(), t.symsort.size() * 4);
+    std::memcpy(base + d.off_lut, lut.data(), lut.size() * 4);
+    return HAC_OK;
+}
+
+uint32_t pick_lut_bits(const hac_opts_t* opts, uint32_t lmax)
+{
+    uint32_t b = opts && opts->lut_bits ? opts->lut_bits : std::min<uint32_t>(std::max<uint32_t>(lmax, 1), 11);
+    return b;
+}
+
+} // namespace
+
+// =================================================================================
+// HAC encoder (Sect. IV-B)
+// =================================================================================
+extern "C" int hac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
+                          const hac_opts_t* opts, void** blob, size_t* blob_bytes)
+{
+    int rc = check_args(W, n, m, ldw, blob, blob_bytes);
+    if (rc) return rc;
+    *blob = nullptr; *blob_bytes = 0;
+    if (opts && (opts->lut_bits > 12 || (opts->chunk_rows && opts->chunk_rows > 65536))) return HAC_EINVAL;
+    try {
+        Scan s;
+        rc = scan_matrix(W, n, m, ldw, s);
+        if (rc) return rc;
+        const uint64_t nnz = s.ri.size();
+        const bool has_zero = s.zeros > 0;
+        // alphabet: 0.0 first when it occurs, then the non-zero values ascending
+        std::vector<float> codebook;
+        std::vector<uint64_t> freq;
+        if (has_zero) { codebook.push_back(0.0f); freq.push_back(s.zeros); }
+        codebook.insert(codebook.end(), s.values.begin(), s.values.end());
+        freq.insert(freq.end(), s.freq.begin(), s.freq.end());
+        const uint32_t shift = has_zero ? 1u : 0u;           // symbol of non-zero value v = shift + index
+        std::vector<uint8_t> len; uint32_t lmax = 0;
+        if (!huffman_lengths(freq, len, lmax)) return HAC_ERANGE;
+        CodeTables t; canonical_codes(len, t);
+        uint64_t total_bits = 0;
+        for (size_t i = 0; i < freq.size(); ++i) total_bits += freq[i] * len[i];
+        if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
+        const uint32_t lut_bits = pick_lut_bits(opts, lmax);
+        if (lut_bits < 1 || lut_bits > 12) return HAC_EINVAL;
+        std::vector<uint32_t> lut; build_lut(len, t, lut_bits, lut);
+
+        const uint32_t R = opts && opts->chunk_rows ? opts->chunk_rows : 512;
+        const uint64_t cpc = ((uint64_t)n + R - 1) / R;
+        const uint64_t n_chunks = cpc * (uint64_t)m;
+        if (n_chunks > 0xfffffff0ull) return HAC_ERANGE;
+        const uint64_t n_words = (total_bits + 31) / 32;
+        const uint32_t zero_len = (has_zero && t.code[0] == 0) ? len[0] : 0;   // canonical: all-zero word <=> a shortest one
+
+        Layout L;
+        hac_desc_t& d = L.d;
+        d.magic = kMagic; d.version = kVersion; d.format = HAC_FORMAT_HAC; d.header_bytes = 256;
+        d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = nnz; d.total_bits = total_bits; d.n_words = n_words;
+        d.k_sym = (uint32_t)codebook.size(); d.lmax = lmax; d.lut_bits = lut_bits;
+        d.has_zero = has_zero; d.zero_len = zero_len; d.chunk = R; d.ri_bits = 0;
+        d.chunks_per_col = (uint32_t)cpc; d.n_chunks = n_chunks;
+        d.off_codebook = L.place(4ull * d.k_sym);
+        d.off_codelen = L.place(d.k_sym);
+        d.off_canon = L.place(3 * 33 * 4);
+        d.off_symsort = L.place(4ull * d.k_sym);
+        d.off_lut = L.place(4ull << lut_bits);
+        d.off_stream = L.place(4 * n_words + kTailPad);
+        d.off_chunk_bit = L.place(4 * (n_chunks + 1));
+        d.off_chunk_pos = L.place(4 * (n_chunks + 1));
+        d.blob_bytes = align_up(L.cursor);
+
+        uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
+        if (!base) return HAC_ENOMEM;
+        std::memcpy(base, &d, sizeof d);
+        write_tables(base, d, codebook, len, t, lut);
+
+        BitWriter bw = { reinterpret_cast<uint32_t*>(base + d.off_stream), 0 };
+        uint32_t* cbit = reinterpret_cast<uint32_t*>(base + d.off_chunk_bit);
+        uint32_t* cpos = reinterpret_cast<uint32_t*>(base + d.off_chunk_pos);
+        const uint32_t zcode = has_zero ? t.code[0] : 0, zlen = has_zero ? len[0] : 0;
+        auto put_zeros = [&](uint64_t count) {
+            if (!count) return;
+            if (zcode == 0) bw.skip(count * zlen);              // zero bits are already there
+            else for (uint64_t r = 0; r < count; ++r) bw.put(zcode, zlen);
+        };
+        uint64_t chunk = 0;
+        for (int64_t j = 0; j < m; ++j) {
+            uint64_t row = 0;                                    // next row to be written
+            uint64_t p = s.cb[(size_t)j];
+            const uint64_t pend = s.cb[(size_t)j + 1];
+            for (uint64_t c = 0; c < cpc; ++c, ++chunk) {
+                const uint64_t rend = std::min<uint64_t>((c + 1) * R, (uint64_t)n);
+                cbit[chunk] = (uint32_t)bw.bitpos;
+                cpos[chunk] = (uint32_t)p;
+                while (p < pend && s.ri[(size_t)p] < rend) {
+                    put_zeros(s.ri[(size_t)p] - row);
+                    const uint32_t sy = s.sym[(size_t)p] + shift;
+                    bw.put(t.code[sy], len[sy]);
+                    row = (uint64_t)s.ri[(size_t)p] + 1;
+                    ++p;
+                }
+                put_zeros(rend - row);
+                row = rend;
+            }
+        }
+        cbit[n_chunks] = (uint32_t)bw.bitpos;
+        cpos[n_chunks] = (uint32_t)nnz;
+        if (bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
+        *blob = base; *blob_bytes = (size_t)d.blob_bytes;
+        return HAC_OK;
+    } catch (const std::bad_alloc&) {
+        return HAC_ENOMEM;
+    }
+}
+
+// =================================================================================
+// sHAC encoder (Sect. IV-C)
+// =================================================================================
+extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
+                           const hac_opts_t* opts, void** blob, size_t* blob_bytes)
+{
+    int rc = check_args(W, n, m, ldw, blob, blob_bytes);
+    if (rc) return rc;
+    *blob = nullptr; *blob_bytes = 0;
+    if (opts && (opts->lut_bits > 12 || opts->chunk_nnz > 65536)) return HAC_EINVAL;
+    const uint32_t need_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
+    uint32_t ri_bits = opts && opts->ri_bits ? opts->ri_bits : need_bits;
+    if (ri_bits < need_bits || ri_bits > 32) return HAC_EINVAL;
+    try {
+        Scan s;
+        rc = scan_matrix(W, n, m, ldw, s);
+        if (rc) return rc;
+        const uint64_t nnz = s.ri.size();
+        std::vector<uint8_t> len; uint32_t lmax = 0;
+        if (!huffman_lengths(s.freq, len, lmax)) return HAC_ERANGE;
+        CodeTables t; canonical_codes(len, t);
+        uint64_t total_bits = 0;
+        for (size_t i = 0; i < s.freq.size(); ++i) total_bits += s.freq[i] * len[i];
+        if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
+        const uint32_t lut_bits = pick_lut_bits(opts, lmax);
+        if (lut_bits < 1 || lut_bits > 12) return HAC_EINVAL;
+        std::vector<uint32_t> lut; build_lut(len, t, lut_bits, lut);
+
+        const uint32_t Cn = opts && opts->chunk_nnz ? opts->chunk_nnz : 32;
+        std::vector<uint32_t> col_chunk((size_t)m + 1, 0);
+        uint64_t n_chunks = 0;
+        for (int64_t j = 0; j < m; ++j) {
+            col_chunk[(size_t)j] = (uint32_t)n_chunks;
+            n_chunks += (s.cb[(size_t)j + 1] - s.cb[(size_t)j] + Cn - 1) / Cn;
+        }
+        col_chunk[(size_t)m] = (uint32_t)n_chunks;
+        const uint64_t n_words = (total_bits + 31) / 32;
+        const uint64_t ri_words = (nnz * ri_bits + 31) / 32;
+        if (nnz * (uint64_t)ri_bits > 0xfffffff0ull * 32ull) return HAC_ERANGE;
+
+        Layout L;
+        hac_desc_t& d = L.d;
+        d.magic = kMagic; d.version = kVersion; d.format = HAC_FORMAT_SHAC; d.header_bytes = 256;
+        d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = nnz; d.total_bits = total_bits; d.n_words = n_words;
+        d.k_sym = (uint32_t)s.values.size(); d.lmax = lmax; d.lut_bits = lut_bits;
+        d.has_zero = 0; d.zero_len = 0; d.chunk = Cn; d.ri_bits = ri_bits;
+        d.chunks_per_col = 0; d.n_chunks = n_chunks;
+        d.off_codebook = L.place(4ull * d.k_sym);
+        d.off_codelen = L.place(d.k_sym);
+        d.off_canon = L.place(3 * 33 * 4);
+        d.off_symsort = L.place(4ull * d.k_sym);
+        d.off_lut = L.place(4ull << lut_bits);
+        d.off_stream = L.place(4 * n_words + kTailPad);
+        d.off_chunk_bit = L.place(4 * (n_chunks + 1));
+        d.off_col_chunk = L.place(4 * ((uint64_t)m + 1));
+        d.off_cb = L.place(4 * ((uint64_t)m + 1));
+        d.off_ri = L.place(4 * ri_words + kTailPad);
+        d.blob_bytes = align_up(L.cursor);
+
+        uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
+        if (!base) return HAC_ENOMEM;
+        std::memcpy(base, &d, sizeof d);
+        write_tables(base, d, s.values, len, t, lut);
+
+        BitWriter bw = { reinterpret_cast<uint32_t*>(base + d.off_stream), 0 };
+        BitWriter rw = { reinterpret_cast<uint32_t*>(base + d.off_ri), 0 };
+        uint32_t* cbit = reinterpret_cast<uint32_t*>(base + d.off_chunk_bit);
+        uint32_t* cc = reinterpret_cast<uint32_t*>(base + d.off_col_chunk);
+        uint32_t* cb = reinterpret_cast<uint32_t*>(base + d.off_cb);
+        uint64_t chunk = 0;
+        for (int64_t j = 0; j < m; ++j) {
+            cc[j] = col_chunk[(size_t)j];
+            cb[j] = (uint32_t)s.cb[(size_t)j];
+            for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) {
+                if ((p - s.cb[(size_t)j]) % Cn == 0) cbit[chunk++] = (uint32_t)bw.bitpos;
+                const uint32_t sy = s.sym[(size_t)p];
+                bw.put(t.code[sy], len[sy]);
+                rw.put(s.ri[(size_t)p], ri_bits);
+            }
+        }
+        cc[m] = col_chunk[(size_t)m];
+        cb[m] = (uint32_t)nnz;
+        cbit[n_chunks] = (uint32_t)bw.bitpos;
+        if (chunk != n_chunks || bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
+        *blob = base; *blob_bytes = (size_t)d.blob_bytes;
+        return HAC_OK;
+    } catch (const std::bad_alloc&) {
+        return HAC_ENOMEM;
+    }
+}
+
+extern "C" void hac_free(void* blob) { std::free(blob); }
+
+// =================================================================================
+// validation / description
+// =================================================================================
+namespace {
+
+bool section_ok(const hac_desc_t& d, uint64_t off, uint64_t bytes, size_t total)
+{
+    if (off < sizeof(hac_desc_t) || off % kAlign) return false;
+    if (bytes > total || off > total - bytes) return false;
+    return off + bytes <= d.blob_bytes;
+}
+
+int check_header(const void* blob, size_t bytes, hac_desc_t& d)
+{
+    if (!blob) return HAC_EINVAL;
+    if (bytes < sizeof(hac_desc_t)) return HAC_EFORMAT;
+    std::memcpy(&d, blob, sizeof d);
+    if (d.magic != kMagic || d.version != kVersion || d.header_bytes != 256) return HAC_EFORMAT;
+    if (d.format != HAC_FORMAT_HAC && d.format != HAC_FORMAT_SHAC) return HAC_EFORMAT;
+    if (d.blob_bytes > bytes || d.blob_bytes < sizeof(hac_desc_t)) return HAC_EFORMAT;
+    if (d.n < 1 || d.m < 1 || d.n > 0x7fffffffull || d.m > 0x7fffffffull) return HAC_EFORMAT;
+    if (d.nnz > d.n * d.m || d.nnz > 0xfffffff0ull || d.total_bits > 0xfffffff0ull) return HAC_EFORMAT;
+    if (d.n_words != (d.total_bits + 31) / 32) return HAC_EFORMAT;
+    if (d.lmax > 32 || d.lut_bits < 1 || d.lut_bits > 12) return HAC_EFORMAT;
+    if (d.k_sym > d.n * d.m) return HAC_EFORMAT;
+    if ((d.k_sym == 0) != (d.total_bits == 0)) return HAC_EFORMAT;
+    if (d.k_sym > 0 && (d.lmax < 1)) return HAC_EFORMAT;
+    if (d.chunk < 1 || d.chunk > 65536) return HAC_EFORMAT;
+    const size_t tot = (size_t)d.blob_bytes;
+    if (!section_ok(d, d.off_codebook, 4ull * d.k_sym, tot)) return HAC_EFORMAT;
+    if (!section_ok(d, d.off_codelen, d.k_sym, tot)) return HAC_EFORMAT;
+    if (!section_ok(d, d.off_canon, 3 * 33 * 4, tot)) return HAC_EFORMAT;
+    if (!section_ok(d, d.off_symsort, 4ull * d.k_sym, tot)) return HAC_EFORMAT;
+    if (!section_ok(d, d.off_lut, 4ull << d.lut_bits, tot)) return HAC_EFORMAT;
+    if (!section_ok(d, d.off_stream, 4 * d.n_words + kTailPad, tot)) return HAC_EFORMAT;
+    if (!section_ok(d, d.off_chunk_bit, 4 * (d.n_chunks + 1), tot)) return HAC_EFORMAT;
+    if (d.format == HAC_FORMAT_HAC) {
+        if (d.chunks_per_col != (d.n + d.chunk - 1) / d.chunk) return HAC_EFORMAT;
+        if (d.n_chunks != (uint64_t)d.chunks_per_col * d.m) return HAC_EFORMAT;
+        if (!section_ok(d, d.off_chunk_pos, 4 * (d.n_chunks + 1), tot)) return HAC_EFORMAT;
+        if (d.has_zero > 1) return HAC_EFORMAT;
+        if (d.has_zero != (d.nnz < d.n * d.m ? 1u : 0u)) return HAC_EFORMAT;
+    } else {
+        const uint32_t need = std::max<uint32_t>(ceil_log2(d.n), 1);
+        if (d.ri_bits < need || d.ri_bits > 32) return HAC_EFORMAT;
+        if (d.has_zero || d.zero_len) return HAC_EFORMAT;
+        if (!section_ok(d, d.off_col_chunk, 4 * (d.m + 1), tot)) return HAC_EFORMAT;
+        if (!section_ok(d, d.off_cb, 4 * (d.m + 1), tot)) return HAC_EFORMAT;
+        if (!section_ok(d, d.off_ri, 4 * ((d.nnz * d.ri_bits + 31) / 32) + kTailPad, tot)) return HAC_EFORMAT;
+    }
+    return HAC_OK;
+}
+
+struct View {
+    hac_desc_t d;
+    const uint8_t* base;
+    const float* codebook; const uint8_t* codelen; const uint32_t* canon; const uint32_t* symsort;
+    const uint32_t* lut; const uint32_t* stream; const uint32_t* cbit; const uint32_t* cpos;
+    const uint32_t* colchunk; const uint32_t* cb; const uint32_t* ri;
+};
+
+void make_view(const void* blob, const hac_desc_t& d, View& v)
+{
+    v.d = d; v.base = static_cast<const uint8_t*>(blob);
+    v.codebook = reinterpret_cast<const float*>(v.base + d.off_codebook);
+    v.codelen = v.base + d.off_codelen;
+    v.canon = reinterpret_cast<const uint32_t*>(v.base + d.off_canon);
+    v.symsort = reinterpret_cast<const uint32_t*>(v.base + d.off_symsort);
+    v.lut = reinterpret_cast<const uint32_t*>(v.base + d.off_lut);
+    v.stream = reinterpret_cast<const uint32_t*>(v.base + d.off_stream);
+    v.cbit = reinterpret_cast<const uint32_t*>(v.base + d.off_chunk_bit);
+    v.cpos = d.format == HAC_FORMAT_HAC ? reinterpret_cast<const uint32_t*>(v.base + d.off_chunk_pos) : nullptr;
+    v.colchunk = d.format == HAC_FORMAT_SHAC ? reinterpret_cast<const uint32_t*>(v.base + d.off_col_chunk) : nullptr;
+    v.cb = d.format == HAC_FORMAT_SHAC ? reinterpret_cast<const uint32_t*>(v.base + d.off_cb) : nullptr;
+    v.ri = d.format == HAC_FORMAT_SHAC ? reinterpret_cast<const uint32_t*>(v.base + d.off_ri) : nullptr;
+}
+
+// code tables must describe a complete canonical prefix code consistent with the lengths
+int check_tables(const View& v)
+{
+    const hac_desc_t& d = v.d;
+    if (d.k_sym == 0) return HAC_OK;
+    std::vector<uint8_t> len(v.codelen, v.codelen + d.k_sym);
+    uint32_t lmax = 0;
+    unsigned __int128 kraft = 0;
+    for (uint32_t s = 0; s < d.k_sym; ++s) {
+        if (len[s] < 1 || len[s] > 32) return HAC_EFORMAT;
+        lmax = std::max<uint32_t>(lmax, len[s]);
+        kraft += (unsigned __int128)1 << (32 - len[s]);
+    }
+    if (lmax != d.lmax) return HAC_EFORMAT;
+    const unsigned __int128 one = (unsigned __int128)1 << 32;
+    if (d.k_sym == 1 ? (len[0] != 1) : (kraft != one)) return HAC_EFORMAT;
+    CodeTables t; canonical_codes(len, t);
+    if (std::memcmp(v.canon, t.first_code, 33 * 4) || std::memcmp(v.canon + 33, t.count, 33 * 4) ||
+        std::memcmp(v.canon + 66, t.first_index, 33 * 4)) return HAC_EFORMAT;
+    if (std::memcmp(v.symsort, t.symsort.data(), 4ull * d.k_sym)) return HAC_EFORMAT;
+    std::vector<uint32_t> lut; build_lut(len, t, d.lut_bits, lut);
+    if (std::memcmp(v.lut, lut.data(), lut.size() * 4)) return HAC_EFORMAT;
+    for (uint32_t s = 0; s < d.k_sym; ++s) {
+        if (!std::isfinite(v.codebook[s])) return HAC_EFORMAT;
+        if (s > (d.has_zero ? 1u : 0u) && !(v.codebook[s - 1] < v.codebook[s])) return HAC_EFORMAT;
+    }
+    if (d.format == HAC_FORMAT_HAC) {
+        if (d.has_zero && float_bits(v.codebook[0]) != 0) return HAC_EFORMAT;
+        for (uint32_t s = d.has_zero; s < d.k_sym; ++s) if (v.codebook[s] == 0.0f) return HAC_EFORMAT;
+        const uint32_t zl = (d.has_zero && t.code[0] == 0) ? len[0] : 0;
+        if (zl != d.zero_len) return HAC_EFORMAT;
+    } else {
+        for (uint32_t s = 0; s < d.k_sym; ++s) if (v.codebook[s] == 0.0f) return HAC_EFORMAT;
+    }
+    return HAC_OK;
+}
+
+// sequential canonical decoder over the stream
+struct SeqDecoder {
+    const View& v;
+    uint64_t bitpos = 0;
+    explicit SeqDecoder(const View& vv) : v(vv) {}
+    inline uint32_t window() const {
+        const uint64_t w = bitpos >> 5; const uint32_t off = (uint32_t)(bitpos & 31);
+        const uint64_t two = ((uint64_t)v.stream[w] << 32) | v.stream[w + 1];   // tail padding keeps w+1 in bounds
+        return (uint32_t)((two << off) >> 32);
+    }
+    // returns symbol or -1 (no codeword matches / past the end)
+    inline int64_t next() {
+        if (bitpos >= v.d.total_bits) return -1;
+        const uint32_t win = window();
+        const uint32_t e = v.lut[win >> (32 - v.d.lut_bits)];
+        uint32_t l = e & 63, s = e >> 6;
+        if (l == 0) {
+            bool found = false;
+            for (l = v.d.lut_bits + 1; l <= v.d.lmax; ++l) {
+                const uint32_t c = win >> (32 - l);
+                const uint32_t rel = c - v.canon[l];
+                if (rel < v.canon[33 + l]) { s = v.symsort[v.canon[66 + l] + rel]; found = true; break; }
+            }
+            if (!found) return -1;
+        }
+        if (bitpos + l > v.d.total_bits) return -1;
+        bitpos += l;
+        return (int64_t)s;
+    }
+};
+
+inline uint32_t ri_field(const uint32_t* ri, uint64_t p, uint32_t bits)
+{
+    const uint64_t bp = p * bits; const uint64_t w = bp >> 5; const uint32_t off = (uint32_t)(bp & 31);
+    const uint64_t two = ((uint64_t)ri[w] << 32) | ri[w + 1];
+    return (uint32_t)((two << off) >> (64 - bits));
+}
+
+int check_index_shallow(const View& v)
+{
+    const hac_desc_t& d = v.d;
+    if (v.cbit[d.n_chunks] != d.total_bits) return HAC_EFORMAT;
+    for (uint64_t c = 0; c < d.n_chunks; ++c) if (v.cbit[c] > v.cbit[c + 1]) return HAC_EFORMAT;
+    if (d.n_chunks && v.cbit[0] != 0) return HAC_EFORMAT;
+    if (d.format == HAC_FORMAT_HAC) {
+        if (v.cpos[d.n_chunks] != d.nnz) return HAC_EFORMAT;
+        for (uint64_t c = 0; c < d.n_chunks; ++c) {
+            if (v.cpos[c] > v.cpos[c + 1]) return HAC_EFORMAT;
+            if (v.cpos[c + 1] - v.cpos[c] > d.chunk) return HAC_EFORMAT;
+        }
+        if (v.cpos[0] != 0) return HAC_EFORMAT;
+    } else {
+        if (v.cb[0] != 0 || v.cb[d.m] != d.nnz) return HAC_EFORMAT;
+        if (v.colchunk[0] != 0 || v.colchunk[d.m] != d.n_chunks) return HAC_EFORMAT;
+        for (uint64_t j = 0; j < d.m; ++j) {
+            if (v.cb[j] > v.cb[j + 1]) return HAC_EFORMAT;
+            const uint64_t cnt = v.cb[j + 1] - v.cb[j];
+            if (cnt > d.n) return HAC_EFORMAT;
+            if ((uint64_t)v.colchunk[j + 1] - v.colchunk[j] != (cnt + d.chunk - 1) / d.chunk) return HAC_EFORMAT;
+        }
+    }
+    return HAC_OK;
+}
+
+int check_deep(const View& v)
+{
+    const hac_desc_t& d = v.d;
+    SeqDecoder dec(v);
+    if (d.format == HAC_FORMAT_HAC) {
+        uint64_t chunk = 0, pos = 0;
+        for (uint64_t j = 0; j < d.m; ++j)
+            for (uint64_t i = 0; i < d.n; ++i) {
+                if (i % d.chunk == 0) {
+                    if (v.cbit[chunk] != dec.bitpos || v.cpos[chunk] != pos) return HAC_EFORMAT;
+                    ++chunk;
+                }
+                const int64_t s = dec.next();
+                if (s < 0) return HAC_EFORMAT;
+                if (!(d.has_zero && s == 0)) ++pos;
+            }
+        if (pos != d.nnz || dec.bitpos != d.total_bits) return HAC_EFORMAT;
+    } else {
+        uint64_t chunk = 0;
+        for (uint64_t j = 0; j < d.m; ++j) {
+            int64_t prev = -1;
+            for (uint64_t p = v.cb[j]; p < v.cb[j + 1]; ++p) {
+                if ((p - v.cb[j]) % d.chunk == 0) {
+                    if (v.cbit[chunk] != dec.bitpos) return HAC_EFORMAT;
+                    ++chunk;
+                }
+                if (dec.next() < 0) return HAC_EFORMAT;
+                const uint32_t r = ri_field(v.ri, p, d.ri_bits);
+                if (r >= d.n || (int64_t)r <= prev) return HAC_EFORMAT;
+                prev = r;
+            }
+        }
+        if (dec.bitpos != d.total_bits) return HAC_EFORMAT;
+    }
+    return HAC_OK;
+}
+
+} // namespace
+
+extern "C" int hac_validate(const void* blob, size_t bytes, int deep)
+{
+    hac_desc_t d;
+    int rc = check_header(blob, bytes, d);
+    if (rc) return rc;
+    try {
+        View v; make_view(blob, d, v);
+        if ((rc = check_tables(v))) return rc;
+        if ((rc = check_index_shallow(v))) return rc;
+        if (deep && (rc = check_deep(v))) return rc;
+    } catch (const std::bad_alloc&) {
+        return HAC_ENOMEM;
+    }
+    return HAC_OK;
+}
+
+extern "C" int hac_describe(const void* blob, size_t bytes, hac_desc_t* desc)
+{
+    if (!desc) return HAC_EINVAL;
+    return check_header(blob, bytes, *desc);
+}
+
+extern "C" int hac_stats(const void* blob, size_t bytes, hac_stats_t* out)
+{
+    if (!out) return HAC_EINVAL;
+    hac_desc_t d;
+    int rc = check_header(blob, bytes, d);
+    if (rc) return rc;
+    View v; make_view(blob, d, v);
+    std::memset(out, 0, sizeof *out);
+    out->stream_bits = d.total_bits;
+    out->stream_bytes = 4 * d.n_words;
+    out->table_bytes = 4ull * d.k_sym + d.k_sym + 3 * 33 * 4 + 4ull * d.k_sym + (4ull << d.lut_bits);
+    out->blob_bytes = d.blob_bytes;
+    const double nm = (double)d.n * (double)d.m;
+    const double k = (double)std::max<uint32_t>(d.k_sym, 1);
+    if (d.format == HAC_FORMAT_HAC) {
+        out->index_bytes = 8 * (d.n_chunks + 1);
+        out->paper_bits = 32 * d.n_words + 6ull * 32 * d.k_sym;
+        out->bound_bits = nm * (1.0 + std::log2(k)) + 6.0 * k * 32.0;
+    } else {
+        out->index_bytes = 4 * (d.n_chunks + 1) + 4 * (d.m + 1);
+        out->ri_bytes = 4 * ((d.nnz * d.ri_bits + 31) / 32);
+        out->cb_bytes = 4 * (d.m + 1);
+        out->paper_bits = 32 * d.n_words + 6ull * 32 * d.k_sym + 32 * (d.nnz + d.m + 1);
+        out->bound_bits = (double)d.nnz * (1.0 + std::log2(k)) + 32.0 * (6.0 * k + (double)d.nnz + (double)d.m + 1.0);
+    }
+    // entropy from the code lengths is not available; recompute symbol counts by a sequential decode
+    std::vector<uint64_t> cnt(d.k_sym, 0);
+    SeqDecoder dec(v);
+    const uint64_t symbols = d.format == HAC_FORMAT_HAC ? d.n * d.m : d.nnz;
+    for (uint64_t i = 0; i < symbols; ++i) {
+        const int64_t s = dec.next();
+        if (s < 0) return HAC_EFORMAT;
+        cnt[(size_t)s]++;
+    }
+    double H = 0.0;
+    for (uint32_t s = 0; s < d.k_sym; ++s)
+        if (cnt[s]) { const double p = (double)cnt[s] / (double)symbols; H -= p * std::log2(p); }
+    out->entropy_bits = H;
+    out->avg_code_bits = symbols ? (double)d.total_bits / (double)symbols : 0.0;
+    out->psi = (double)d.blob_bytes / (4.0 * nm);
+    return HAC_OK;
+}
+
+extern "C" int hac_decode_host(const void* blob, size_t bytes, float* W_out, int32_t* sym_out,
+                               int32_t* row_out, int32_t* col_out)
+{
+    hac_desc_t d;
+    int rc = check_header(blob, bytes, d);
+    if (rc) return rc;
+    View v; make_view(blob, d, v);
+    if ((rc = check_tables(v))) return rc;
+    if ((rc = check_index_shallow(v))) return rc;
+    SeqDecoder dec(v);
+    if (d.format == HAC_FORMAT_HAC) {
+        if (row_out || col_out) return HAC_EINVAL;
+        for (uint64_t j = 0; j < d.m; ++j)
+            for (uint64_t i = 0; i < d.n; ++i) {
+                const int64_t s = dec.next();
+                if (s < 0) return HAC_EFORMAT;
+                if (sym_out) sym_out[j * d.n + i] = (int32_t)s;
+                if (W_out) W_out[i * d.m + j] = v.codebook[s];
+            }
+    } else {
+        if (W_out) std::memset(W_out, 0, sizeof(float) * (size_t)(d.n * d.m));
+        for (uint64_t j = 0; j < d.m; ++j)
+            for (uint64_t p = v.cb[j]; p < v.cb[j + 1]; ++p) {
+                const int64_t s = dec.next();
+                if (s < 0) return HAC_EFORMAT;
+                const uint32_t r = ri_field(v.ri, p, d.ri_bits);
+                if (r >= d.n) return HAC_EFORMAT;
+                if (sym_out) sym_out[p] = (int32_t)s;
+                if (row_out) row_out[p] = (int32_t)r;
+                if (col_out) col_out[p] = (int32_t)j;
+                if (W_out) W_out[(uint64_t)r * d.m + j] = v.codebook[s];
+            }
+    }
+    return HAC_OK;
+}
+
+extern "C" const char* hac_strerror(int status)
+{
+    switch (status) {
+    case HAC_OK: return "ok";
+    case HAC_EINVAL: return "invalid argument";
+    case HAC_ENOMEM: return "out of host memory";
+    case HAC_EFORMAT: return "blob fails validation";
+    case HAC_ERANGE: return "value outside the limits of the format (codeword > 32 bits or count too large)";
+    case HAC_EHIP: return "HIP call failed";
+    case HAC_EWORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+    }
+}

@@ -1,0 +1,196 @@
+"""GPU parity: the HIP path against the CPU oracle, through the C ABI.
+
+Decoded symbols, values and indices must match the oracle bit for bit.
+Y must satisfy, with fp32 accumulation,
+    |Y - Yref|_ij <= 1e-5 * (|X| . |W|)_ij      (componentwise), and
+    max |Y - Yref| <= 1e-5 * max |Yref|,
+where Yref is the dense fp64 product with the matrix that was encoded.
+"""
+import numpy as np
+import pytest
+
+import workloads
+from oracle import dot as odot
+from oracle import formats
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def hac():
+    import paper_2108_12704_amd as lib
+    lib.load_library()
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    return lib
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def check_y(Y, X, W, what=""):
+    ref = odot.dense_dot(X, W)
+    scale = odot.abs_dot(X, W)
+    got = Y.detach().cpu().numpy().astype(np.float64)
+    assert got.shape == ref.shape, what
+    err = np.abs(got - ref)
+    bad = err > TOL * scale + 1e-37
+    assert not bad.any(), f"{what}: {int(bad.sum())} entries off, worst {float((err / (scale + 1e-300)).max()):.3e}"
+    if ref.size and np.abs(ref).max() > 0:
+        assert err.max() <= TOL * np.abs(ref).max(), what
+
+
+def layer_cases():
+    yield "cfg1", workloads.layer(1)
+    yield "cfg2-700x129", workloads.scaled(2, 700, 129)
+    yield "cfg3-1100x70", workloads.scaled(3, 1100, 70)
+    yield "cfg4-3000x65", workloads.scaled(4, 3000, 65)
+    yield "cfg5-640x33", workloads.scaled(5, 640, 33)
+    for name, W in workloads.edge_cases().items():
+        yield name, W
+
+
+CASES = list(layer_cases())
+CASE_IDS = [c[0] for c in CASES]
+
+
+@pytest.mark.parametrize("name,W", CASES, ids=CASE_IDS)
+def test_hac_decode_bit_exact(hac, name, W):
+    print(f"[case] hac_decode {name} {W.shape}", flush=True)
+    values, sym = formats.hac_symbols(W)
+    for kw in (dict(), dict(chunk_rows=37), dict(lut_bits=3)):
+        blob = hac.hac_encode(W, **kw)
+        Wd, symd = hac.hac_decode_dev(blob.to_device(dev()))
+        torch.cuda.synchronize()
+        assert np.array_equal(Wd.cpu().numpy().view(np.uint32), W.view(np.uint32)), kw
+        assert np.array_equal(symd.cpu().numpy().astype(np.int64), sym), kw
+
+
+@pytest.mark.parametrize("name,W", CASES, ids=CASE_IDS)
+def test_shac_decode_bit_exact(hac, name, W):
+    print(f"[case] shac_decode {name} {W.shape}", flush=True)
+    values, sym, row, col = formats.shac_symbols(W)
+    for kw in (dict(), dict(chunk_nnz=5), dict(ri_bits=32), dict(lut_bits=2)):
+        blob = hac.shac_encode(W, **kw)
+        nz, symd, rowd, cold = hac.shac_decode_dev(blob.to_device(dev()))
+        torch.cuda.synchronize()
+        assert np.array_equal(symd.cpu().numpy().astype(np.int64), sym), kw
+        assert np.array_equal(rowd.cpu().numpy().astype(np.int64), row), kw
+        assert np.array_equal(cold.cpu().numpy().astype(np.int64), col), kw
+        assert np.array_equal(nz.cpu().numpy().view(np.uint32), values[sym].view(np.uint32)), kw
+
+
+BATCHES = [1, 2, 3, 8, 31, 32, 64, 65, 128, 200, 256, 300]
+
+
+@pytest.mark.parametrize("name,W", CASES, ids=CASE_IDS)
+def test_dot_parity_small(hac, name, W):
+    n, m = W.shape
+    hb = hac.hac_encode(W).to_device(dev())
+    sb = hac.shac_encode(W).to_device(dev())
+    for B in BATCHES:
+        print(f"[case] dot {name} {W.shape} B={B}", flush=True)
+        X = workloads.make_batch(B, n, 77 + B) - np.float32(0.125)      # a few negative inputs too
+        Xd = torch.from_numpy(X).to(dev())
+        Yh = hac.hac_dot(hb, Xd)
+        Ys = hac.shac_dot(sb, Xd)
+        torch.cuda.synchronize()
+        check_y(Yh, X, W, f"hac {name} B={B}")
+        check_y(Ys, X, W, f"shac {name} B={B}")
+
+
+def test_dot_other_encoder_options(hac):
+    W = workloads.scaled(3, 1500, 90)
+    n, m = W.shape
+    X8 = workloads.make_batch(8, n, 3)
+    blobs = [(hac.hac_dot, hac.hac_encode(W, chunk_rows=100)),
+             (hac.hac_dot, hac.hac_encode(W, chunk_rows=4096, lut_bits=2)),
+             (hac.shac_dot, hac.shac_encode(W, chunk_nnz=3)),
+             (hac.shac_dot, hac.shac_encode(W, chunk_nnz=1000, ri_bits=32, lut_bits=4))]
+    for f, blob in blobs:
+        db = blob.to_device(dev())
+        for X in (X8[:1], X8):
+            print(f"[case] options {f.__name__} chunk={blob.desc.chunk} B={X.shape[0]}", flush=True)
+            Y = f(db, torch.from_numpy(X).to(dev()))
+            torch.cuda.synchronize()
+            check_y(Y, X, W, f.__name__)
+
+
+def test_launch_overrides_do_not_change_the_result(hac):
+    W = workloads.scaled(5, 900, 77)          # ~360 non-zeros per column
+    n, m = W.shape
+    X = workloads.make_batch(40, n, 9)
+    Xd = torch.from_numpy(X).to(dev())
+    for enc, f in ((hac.hac_encode, hac.hac_dot), (hac.shac_encode, hac.shac_dot)):
+        db = enc(W).to_device(dev())
+        for cpw, wpb, cap in ((1, 1, 64), (3, 2, 64), (7, 4, 128), (64, 4, 4096), (2, 3, 1024)):
+            print(f"[case] launch {f.__name__} cpw={cpw} wpb={wpb} cap={cap}", flush=True)
+            launch = hac.Launch(cols_per_wave=cpw, waves_per_block=wpb)
+            launch.reserved[0] = cap                        # list capacity: forces several windows per column
+            Y = f(db, Xd, launch=launch)
+            Y1 = f(db, Xd[:1], launch=hac.Launch(cols_per_wave=cpw, waves_per_block=wpb))
+            torch.cuda.synchronize()
+            check_y(Y, X, W, f"{f.__name__} cpw={cpw}")
+            check_y(Y1, X[:1], W, f"{f.__name__} B=1 cpw={cpw}")
+
+
+def test_identity_batch_recovers_w_bit_exact(hac):
+    W = workloads.scaled(2, 96, 50)
+    eye = torch.eye(96, dtype=torch.float32, device=dev())
+    for enc, f in ((hac.hac_encode, hac.hac_dot), (hac.shac_encode, hac.shac_dot)):
+        Y = f(enc(W).to_device(dev()), eye)
+        torch.cuda.synchronize()
+        assert np.array_equal(Y.cpu().numpy().view(np.uint32), W.view(np.uint32))
+
+
+def test_results_are_bitwise_reproducible(hac):
+    W = workloads.scaled(4, 2048, 128)
+    X = torch.from_numpy(workloads.make_batch(32, 2048, 1)).to(dev())
+    for enc, f in ((hac.hac_encode, hac.hac_dot), (hac.shac_encode, hac.shac_dot)):
+        db = enc(W).to_device(dev())
+        for Xb in (X, X[:1]):
+            a = f(db, Xb).clone()
+            b = f(db, Xb).clone()
+            torch.cuda.synchronize()
+            assert torch.equal(a, b)
+
+
+def test_strided_x_and_y(hac):
+    W = workloads.scaled(1, 200, 40)
+    Xbig = torch.from_numpy(workloads.make_batch(16, 260, 4)).to(dev())
+    X = Xbig[:, 30:230]                                   # ldx = 260
+    Ybig = torch.full((16, 64), 7.0, device=dev())
+    Y = Ybig[:, 8:48]                                     # ldy = 64
+    for enc, f in ((hac.hac_encode, hac.hac_dot), (hac.shac_encode, hac.shac_dot)):
+        f(enc(W).to_device(dev()), X, Y=Y)
+        torch.cuda.synchronize()
+        check_y(Y, X.cpu().numpy(), W, f.__name__)
+        assert torch.all(Ybig[:, :8] == 7.0) and torch.all(Ybig[:, 48:] == 7.0)
+
+
+def test_error_paths(hac):
+    import ctypes as C
+    lib = hac.load_library()
+    W = workloads.scaled(1, 100, 20)
+    hb = hac.hac_encode(W).to_device(dev())
+    sb = hac.shac_encode(W).to_device(dev())
+    X = torch.zeros((4, 100), device=dev())
+    with pytest.raises(hac.HacError) as e:
+        hac.shac_dot(hb, X)                                # HAC blob given to the sHAC entry point
+    assert e.value.status == -1
+    with pytest.raises(hac.HacError) as e:
+        hac.hac_dot(sb, X)
+    assert e.value.status == -1
+    small = torch.empty(256, dtype=torch.uint8, device=dev())
+    with pytest.raises(hac.HacError) as e:
+        hac.hac_dot(hb, X, workspace=small)
+    assert e.value.status == -6
+    Y = torch.empty((4, 20), device=dev())
+    args = (C.byref(hb.desc), hb.tensor.data_ptr(), X.data_ptr(), 4, 50, Y.data_ptr(), 20, None, 0, None, None)
+    assert lib.hac_dot(*args) == -1                        # ldx < n
+    # B = 0 is a no-op
+    assert lib.hac_dot(C.byref(hb.desc), hb.tensor.data_ptr(), None, 0, 100, None, 20, None, 0, None, None) == 0
+    torch.cuda.synchronize()
