@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the compressed dot product Y = X.W on one MI355X.
+
+Workload: the VGG16-FC1-shaped layer (25088 x 4096, 98 % pruned, k = 32 shared
+values by uniform binning), synthetic and seeded.  One *step* is one pass of
+the whole hot path over that layer: hac_dot and shac_dot for each of the three
+batch sizes the configuration names (B = 1, 32, 256) -- six products, each
+decoding its compressed stream on the fly.
+
+Metric: algorithmic HBM bytes moved per second,
+    bytes(call) = stream + code tables + chunk index (+ ri + cb) + 4*B*n + 4*B*m,
+each counted once, summed over the six calls of a step and divided by the step
+time.  Inputs are resident in device memory before the timed region.  To keep
+the 256 MB last-level cache from serving everything, the step rotates through
+enough distinct copies of the blobs and of X / Y to exceed it.
+
+Timing: HIP events on the launch stream around exactly K steps (each step is
+replayed from a captured HIP graph so the host's launch rate is not what is
+measured; --no-graph times eager launches instead).  The dominant kernel's own
+average duration is measured the same way on a graph that holds only that
+kernel, and is what `roofline.achieved` is computed from.
+
+The CPU oracle (Algorithms 1-3 taken literally, oracle/c) is timed beside it on
+a bounded sample as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0                 # MI355X HBM3E
+LLC_BYTES = 256 << 20                 # last-level (Infinity) cache to rotate past
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="workload id (4 = VGG16-FC1-shaped layer)")
+    ap.add_argument("--batches", type=str, default="", help="comma list; default: the config's batch sizes")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hot", action="store_true", help="no rotation: same buffers every step (cache-resident)")
+    ap.add_argument("--chunk-rows", type=int, default=0)
+    ap.add_argument("--chunk-nnz", type=int, default=0)
+    ap.add_argument("--only", type=str, default="", help="restrict the step to 'hac' or 'shac'")
+    ap.add_argument("--detail", action="store_true", help="also time every (format, B) call on its own")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(stats, desc, B):
+    blob = stats.stream_bytes + stats.table_bytes + stats.index_bytes + stats.ri_bytes + stats.cb_bytes
+    return int(blob + 4 * B * int(desc.n) + 4 * B * int(desc.m))
+
+
+class Call:
+    """One (format, B) product with its rotating device buffers."""
+
+    def __init__(self, hac, fmt, blob, B, rot, Xhost, dev, torch):
+        self.fmt, self.B = fmt, B
+        self.fn = hac.hac_dot if fmt == "hac" else hac.shac_dot
+        self.stats = blob.stats()
+        self.desc = blob.desc
+        self.bytes = algorithmic_bytes(self.stats, blob.desc, B)
+        self.blobs = [blob.to_device(dev) for _ in range(rot)]
+        self.X = [torch.from_numpy(Xhost[:B]).to(dev).clone() for _ in range(rot)]
+        self.Y = [torch.empty((B, int(blob.desc.m)), dtype=torch.float32, device=dev) for _ in range(rot)]
+        need = hac.hac_workspace_bytes(blob.desc, B)
+        self.ws = [torch.empty(max(need, 256), dtype=torch.uint8, device=dev) for _ in range(rot)]
+        self.rot = rot
+
+    def run(self, i, launch=None):
+        j = i % self.rot
+        self.fn(self.blobs[j], self.X[j], Y=self.Y[j], workspace=self.ws[j], launch=launch)
+
+
+def time_region(torch, body, iters, warmup, use_graph, rot):
+    """Average milliseconds per body(i) call over `iters` calls, HIP events on the current stream."""
+    stream = torch.cuda.current_stream()
+    for i in range(warmup):
+        body(i)
+    torch.cuda.synchronize()
+    graphs = None
+    if use_graph:
+        graphs = []
+        for j in range(rot):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                body(j)
+            graphs.append(g)
+        for g in graphs:
+            g.replay()
+        torch.cuda.synchronize()
+    t0 = torch.cuda.Event(enable_timing=True)
+    t1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0.record(stream)
+    if graphs is not None:
+        for i in range(iters):
+            graphs[i % rot].replay()
+    else:
+        for i in range(iters):
+            body(i)
+    t1.record(stream)
+    torch.cuda.synchronize()
+    return t0.elapsed_time(t1) / iters
+
+
+def cpu_baseline(W, Xs, cores):
+    """The oracle's literal Algorithm 3 (q = cores threads) on `cores` rows of X, both formats."""
+    from oracle import cnative
+    oh = cnative.hac_encode(W)
+    osh = cnative.shac_encode(W)
+    n, m = W.shape
+    rows = cores
+    X = np.ascontiguousarray(Xs[:rows])
+    t = time.perf_counter()
+    cnative.pardot(oh, X, q=cores)
+    th = time.perf_counter() - t
+    t = time.perf_counter()
+    cnative.pardot(osh, X, q=cores)
+    ts = time.perf_counter() - t
+    k_h, k_s = len(oh.values), len(osh.values)
+    # bytes on the oracle's own structures: stream words + codebook/tree + (ri, cb as stored) + X + Y
+    bh = 4 * oh.N + 12 * k_h + 4 * rows * n + 8 * rows * m
+    bs = 4 * osh.N1 + 12 * k_s + 8 * osh.q + 8 * (m + 1) + 4 * rows * n + 8 * rows * m
+    return {
+        "value": round((bh + bs) / (th + ts) / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "sample": f"Algorithm 3 with q={cores} threads over {rows} rows of X, literal Algorithm 1 (HAC, "
+                  f"{th:.2f} s) and Algorithm 2 (sHAC, {ts:.2f} s) on the full layer; W is re-decoded per row",
+        "hac_ms_per_row_per_core": round(1e3 * th * min(cores, rows) / rows, 2),
+        "shac_ms_per_row_per_core": round(1e3 * ts * min(cores, rows) / rows, 2),
+        "dense_equiv_gflops": round(2.0 * 2 * rows * n * m / (th + ts) / 1e9, 3),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); no multi-GPU path exists", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2108_12704_amd as hac
+    import workloads
+
+    hac.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = workloads.CONFIGS[args.config]
+    batches = [int(b) for b in args.batches.split(",")] if args.batches else list(cfg.batches)
+    t_start = time.perf_counter()
+    W = workloads.layer(args.config)
+    Xhost = workloads.make_batch(max(batches), cfg.n, 1000 * cfg.cfg + 1)
+    hb = hac.hac_encode(W, chunk_rows=args.chunk_rows)
+    sb = hac.shac_encode(W, chunk_nnz=args.chunk_nnz)
+    t_prep = time.perf_counter() - t_start
+
+    fmts = [f for f in ("hac", "shac") if not args.only or f == args.only]
+    per_set = sum((hb.nbytes if f == "hac" else sb.nbytes) for f in fmts) * len(batches) + \
+        sum(4 * B * (cfg.n + cfg.m) * len(fmts) for B in batches)
+    rot = 1 if args.hot else max(2, -(-int(1.25 * LLC_BYTES) // per_set))
+    calls = [Call(hac, f, hb if f == "hac" else sb, B, rot, Xhost, dev, torch) for B in batches for f in fmts]
+    use_graph = not args.no_graph
+    # graphs cannot be captured on the default stream: all launches and events go to this one
+    work_stream = torch.cuda.Stream(device=dev)
+    torch.cuda.synchronize()
+    torch.cuda.set_stream(work_stream)
+
+    def step(i):
+        for c in calls:
+            c.run(i)
+
+    ms_step = time_region(torch, step, args.steps, args.warmup, use_graph, rot)
+    step_bytes = sum(c.bytes for c in calls)
+    value = step_bytes / (ms_step * 1e-3) / 1e9
+    dense_flop = sum(2.0 * c.B * cfg.n * cfg.m for c in calls)
+    true_flop = sum(2.0 * c.B * int(c.desc.nnz) for c in calls)
+
+    # every call on its own, same protocol (graph of that call only)
+    detail = []
+    for c in calls:
+        ms = time_region(torch, lambda i, c=c: c.run(i), max(args.steps, 50), 5, use_graph, rot)
+        reuse = hac.Launch()
+        reuse.variant = 0x100                       # feature-major X already in the workspace: dot kernel alone
+        ms_k = ms if c.B == 1 else time_region(torch, lambda i, c=c: c.run(i, reuse), max(args.steps, 50), 5,
+                                               use_graph, rot)
+        detail.append({
+            "format": c.fmt, "B": c.B, "ms": round(ms, 5), "kernel_ms": round(ms_k, 5),
+            "bytes": c.bytes, "GBps": round(c.bytes / ms / 1e6, 1),
+            "hbm_frac": round(c.bytes / ms / 1e6 / HBM_PEAK_GBS, 4),
+            "kernel_hbm_frac": round(c.bytes / ms_k / 1e6 / HBM_PEAK_GBS, 4),
+            "dense_equiv_gflops": round(2.0 * c.B * cfg.n * cfg.m / ms / 1e6, 1),
+            "true_gflops": round(2.0 * c.B * int(c.desc.nnz) / ms / 1e6, 1),
+        })
+    dom = max(detail, key=lambda d: d["kernel_ms"])
+    kname = ("dot_b1_kernel" if dom["B"] == 1 else "dot_batch_kernel") + ("<sHAC>" if dom["format"] == "shac" else "<HAC>")
+    roofline = {
+        "bound": "hbm", "kernel": f"{kname} B={dom['B']}",
+        "achieved": round(dom["bytes"] / dom["kernel_ms"] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(dom["bytes"] / dom["kernel_ms"] / 1e6 / HBM_PEAK_GBS, 4),
+        "traffic": None,
+        "launch_ms": dom["kernel_ms"], "algorithmic_bytes": dom["bytes"],
+    }
+
+    out = {
+        "metric": "compressed X.W throughput: algorithmic HBM GB/s", "value": round(value, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": f"cfg{cfg.cfg} {cfg.name}: W {cfg.n}x{cfg.m} N(0,{cfg.sigma}) pruned {cfg.prune:.0%}, "
+                        f"k={cfg.k} {cfg.quant}; X ReLU(N(0,1)) fp32; step = " +
+                        " + ".join(f"{f}_dot(B={B})" for B in batches for f in fmts),
+            "batches": batches, "formats": fmts, "rotation_sets": rot, "graph_replay": use_graph,
+            "hac_chunk_rows": int(hb.desc.chunk), "shac_chunk_nnz": int(sb.desc.chunk),
+            "shac_ri_bits": int(sb.desc.ri_bits),
+            "hac_blob_bytes": hb.nbytes, "shac_blob_bytes": sb.nbytes, "nnz": int(hb.desc.nnz),
+        },
+        "hbm_frac": round(value / HBM_PEAK_GBS, 4),
+        "dense_equiv_gflops": round(dense_flop / ms_step / 1e6, 1),
+        "true_gflops": round(true_flop / ms_step / 1e6, 1),
+        "roofline": roofline,
+        "detail": detail,
+        "prep_seconds": round(t_prep, 2),
+    }
+    if not args.no_cpu_baseline:
+        cores = min(len(os.sched_getaffinity(0)), 16)
+        out["cpu_baseline"] = cpu_baseline(W, Xhost, cores)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

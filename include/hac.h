@@ -63,7 +63,7 @@ typedef struct {
                              [32]; 0 = default                                             */
     uint32_t ri_bits;     /* sHAC row-index field width: 0 = ceil(log2 n) (footnote of
                              Sect. IV-A), 32 = one word per index as in Corollary 2        */
-    uint32_t lut_bits;    /* width of the first-level decode table, 1..12 [min(Lmax,11)]  */
+    uint32_t lut_bits;    /* width of the first-level decode table, 1..12 [min(Lmax,10)]  */
 } hac_opts_t;
 
 /* Blob header == descriptor.  All offsets are bytes from the start of the blob. */
@@ -91,15 +91,17 @@ typedef struct {
     uint64_t off_canon;    /* uint32[3][33]: first_code[l], count[l], first_index[l]       */
     uint64_t off_symsort;  /* uint32[k_sym]: symbols in (length, symbol) order             */
     uint64_t off_lut;      /* uint32[2^lut_bits]: (symbol << 6) | length, 0 = longer code  */
-    uint64_t off_stream;   /* uint32[n_words], followed by >= 16 bytes of zeros            */
+    uint64_t off_stream;   /* uint32[n_words], followed by >= 64 bytes of zeros            */
     uint64_t off_chunk_bit;/* uint32[n_chunks + 1]: bit offset where each chunk starts     */
     uint64_t off_chunk_pos;/* HAC: uint32[n_chunks + 1]: non-zeros before each chunk       */
     uint64_t off_col_chunk;/* sHAC: uint32[m + 1]: first chunk of each column              */
     uint64_t off_cb;       /* sHAC: uint32[m + 1]: column begins, 0-based, cb[m] = nnz     */
     uint64_t off_ri;       /* sHAC: row indices, ri_bits-wide fields packed MSB-first into
-                              uint32 words, followed by >= 16 bytes of zeros               */
+                              uint32 words, followed by >= 64 bytes of zeros               */
     uint64_t blob_bytes;   /* total size                                                   */
-    uint64_t reserved[8];
+    uint64_t max_col_bits; /* longest stretch of stream bits that one column occupies      */
+    uint64_t max_col_nnz;  /* most non-zeros in one column                                 */
+    uint64_t reserved[6];
 } hac_desc_t;
 
 /* Sizes as the paper accounts for them (Sect. IV-B/IV-C) next to the real ones. */
@@ -122,12 +124,21 @@ typedef struct {
  * field left 0 keeps its default.  Values outside the documented range give
  * HAC_EINVAL; they never change the result, only how the work is split. */
 typedef struct {
-    uint32_t cols_per_wave;   /* columns of W one wavefront handles, 1..64                 */
+    uint32_t cols_per_wave;   /* columns of W one wavefront handles, 1..32                 */
     uint32_t waves_per_block; /* 1..16                                                     */
-    uint32_t variant;         /* 0 = default kernel choice; other values select a named
-                                 variant, see hac_dot                                      */
-    uint32_t reserved[5];
+    uint32_t variant;         /* low byte: 0 = default kernel choice, 1 = for B = 1 the
+                                 kernel that multiplies while decoding with x held in LDS;
+                                 may be or-ed with HAC_LAUNCH_REUSE_XT                      */
+    uint32_t reserved[5];     /* [0]: entries of the per-wavefront non-zero list, 64..4096;
+                                 [1]: words of the per-wavefront stream staging buffer,
+                                 16..8192, multiple of 4; 0 = sized from the blob header;
+                                 the others must be 0                                      */
 } hac_launch_t;
+
+/* The workspace already holds the feature-major copy of this very X (same B,
+ * same n) left there by an earlier call: skip the re-layout pass.  Meant for
+ * one X multiplied with several compressed matrices of the same height. */
+#define HAC_LAUNCH_REUSE_XT 0x100u
 
 /* ---- host side ------------------------------------------------------------ */
 

@@ -54,7 +54,8 @@ class Desc(C.Structure):
                 ("off_symsort", C.c_uint64), ("off_lut", C.c_uint64), ("off_stream", C.c_uint64),
                 ("off_chunk_bit", C.c_uint64), ("off_chunk_pos", C.c_uint64),
                 ("off_col_chunk", C.c_uint64), ("off_cb", C.c_uint64), ("off_ri", C.c_uint64),
-                ("blob_bytes", C.c_uint64), ("reserved", C.c_uint64 * 8)]
+                ("blob_bytes", C.c_uint64), ("max_col_bits", C.c_uint64), ("max_col_nnz", C.c_uint64),
+                ("reserved", C.c_uint64 * 6)]
 
 
 class Stats(C.Structure):

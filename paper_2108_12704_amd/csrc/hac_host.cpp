@@ -21,7 +21,7 @@ namespace {
 constexpr uint32_t kMagic = 0x31434148u;   // "HAC1"
 constexpr uint32_t kVersion = 1;
 constexpr uint64_t kAlign = 256;
-constexpr uint64_t kTailPad = 16;          // zero bytes after stream / ri for window over-reads
+constexpr uint64_t kTailPad = 64;          // zero bytes after stream / ri for window over-reads
 
 inline uint64_t align_up(uint64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -251,7 +251,7 @@ int write_tables(uint8_t* base, const hac_desc_t& d, const std::vector<float>& c
 
 uint32_t pick_lut_bits(const hac_opts_t* opts, uint32_t lmax)
 {
-    uint32_t b = opts && opts->lut_bits ? opts->lut_bits : std::min<uint32_t>(std::max<uint32_t>(lmax, 1), 11);
+    uint32_t b = opts && opts->lut_bits ? opts->lut_bits : std::min<uint32_t>(std::max<uint32_t>(lmax, 1), 10);
     return b;
 }
 
@@ -328,11 +328,13 @@ extern "C" int hac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
             if (zcode == 0) bw.skip(count * zlen);              // zero bits are already there
             else for (uint64_t r = 0; r < count; ++r) bw.put(zcode, zlen);
         };
-        uint64_t chunk = 0;
+        uint64_t chunk = 0, max_col_bits = 0, max_col_nnz = 0;
         for (int64_t j = 0; j < m; ++j) {
             uint64_t row = 0;                                    // next row to be written
             uint64_t p = s.cb[(size_t)j];
             const uint64_t pend = s.cb[(size_t)j + 1];
+            const uint64_t col_bit0 = bw.bitpos;
+            max_col_nnz = std::max(max_col_nnz, pend - p);
             for (uint64_t c = 0; c < cpc; ++c, ++chunk) {
                 const uint64_t rend = std::min<uint64_t>((c + 1) * R, (uint64_t)n);
                 cbit[chunk] = (uint32_t)bw.bitpos;
@@ -347,9 +349,12 @@ extern "C" int hac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
                 put_zeros(rend - row);
                 row = rend;
             }
+            max_col_bits = std::max(max_col_bits, bw.bitpos - col_bit0);
         }
         cbit[n_chunks] = (uint32_t)bw.bitpos;
         cpos[n_chunks] = (uint32_t)nnz;
+        reinterpret_cast<hac_desc_t*>(base)->max_col_bits = max_col_bits;
+        reinterpret_cast<hac_desc_t*>(base)->max_col_nnz = max_col_nnz;
         if (bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
         *blob = base; *blob_bytes = (size_t)d.blob_bytes;
         return HAC_OK;
@@ -427,17 +432,22 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         uint32_t* cbit = reinterpret_cast<uint32_t*>(base + d.off_chunk_bit);
         uint32_t* cc = reinterpret_cast<uint32_t*>(base + d.off_col_chunk);
         uint32_t* cb = reinterpret_cast<uint32_t*>(base + d.off_cb);
-        uint64_t chunk = 0;
+        uint64_t chunk = 0, max_col_bits = 0, max_col_nnz = 0;
         for (int64_t j = 0; j < m; ++j) {
             cc[j] = col_chunk[(size_t)j];
             cb[j] = (uint32_t)s.cb[(size_t)j];
+            const uint64_t col_bit0 = bw.bitpos;
+            max_col_nnz = std::max(max_col_nnz, s.cb[(size_t)j + 1] - s.cb[(size_t)j]);
             for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) {
                 if ((p - s.cb[(size_t)j]) % Cn == 0) cbit[chunk++] = (uint32_t)bw.bitpos;
                 const uint32_t sy = s.sym[(size_t)p];
                 bw.put(t.code[sy], len[sy]);
                 rw.put(s.ri[(size_t)p], ri_bits);
             }
+            max_col_bits = std::max(max_col_bits, bw.bitpos - col_bit0);
         }
+        reinterpret_cast<hac_desc_t*>(base)->max_col_bits = max_col_bits;
+        reinterpret_cast<hac_desc_t*>(base)->max_col_nnz = max_col_nnz;
         cc[m] = col_chunk[(size_t)m];
         cb[m] = (uint32_t)nnz;
         cbit[n_chunks] = (uint32_t)bw.bitpos;
@@ -479,6 +489,7 @@ int check_header(const void* blob, size_t bytes, hac_desc_t& d)
     if ((d.k_sym == 0) != (d.total_bits == 0)) return HAC_EFORMAT;
     if (d.k_sym > 0 && (d.lmax < 1)) return HAC_EFORMAT;
     if (d.chunk < 1 || d.chunk > 65536) return HAC_EFORMAT;
+    if (d.max_col_bits > d.total_bits || d.max_col_nnz > d.nnz || d.max_col_nnz > d.n) return HAC_EFORMAT;
     const size_t tot = (size_t)d.blob_bytes;
     if (!section_ok(d, d.off_codebook, 4ull * d.k_sym, tot)) return HAC_EFORMAT;
     if (!section_ok(d, d.off_codelen, d.k_sym, tot)) return HAC_EFORMAT;
@@ -697,6 +708,8 @@ extern "C" int hac_stats(const void* blob, size_t bytes, hac_stats_t* out)
     int rc = check_header(blob, bytes, d);
     if (rc) return rc;
     View v; make_view(blob, d, v);
+    if ((rc = check_tables(v))) return rc;
+    if ((rc = check_index_shallow(v))) return rc;
     std::memset(out, 0, sizeof *out);
     out->stream_bits = d.total_bits;
     out->stream_bytes = 4 * d.n_words;

@@ -21,6 +21,15 @@
 
 #include "../../include/hac.h"
 
+// Optional phase timing (build with -DHAC_PHASE_TIMING): lane 0 of each wave of the batch
+// kernel stores the shader clock at phase boundaries; hac_debug_phases() copies them out.
+#ifdef HAC_PHASE_TIMING
+__device__ unsigned long long g_phase[16384 * 8];
+#define HAC_MARK(k) do { if (lane == 0 && wave < 16384) g_phase[wave * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define HAC_MARK(k) do { } while (0)
+#endif
+
 namespace {
 
 constexpr int kWave = 64;
@@ -41,24 +50,34 @@ struct DevBlob {
 };
 
 // ---------------------------------------------------------------------------
-// bit reader: a 96-bit sliding register window over an MSB-first uint32 stream
+// bit reader: a 96-bit sliding register window over an MSB-first uint32 stream.
+// The words come either from global memory (word index = stream index) or from
+// a copy staged in LDS that starts at stream word `wbase`.
 // ---------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
+
+template <bool LDS>
 struct BitReader {
     const uint32_t* w;
+    uint32_t wbase;
     uint32_t widx;
     uint32_t a, b, c;
 
-    __device__ __forceinline__ void seek(const uint32_t* words, uint32_t bp) {
-        w = words;
+    __device__ __forceinline__ uint32_t word(uint32_t i) const {
+        if (LDS) return ((lds_cu32*)w)[i - wbase];
+        return w[i];
+    }
+    __device__ __forceinline__ void seek(const uint32_t* words, uint32_t base, uint32_t bp) {
+        w = words; wbase = base;
         widx = bp >> 5;
-        a = w[widx]; b = w[widx + 1]; c = w[widx + 2];
+        a = word(widx); b = word(widx + 1); c = word(widx + 2);
     }
     // bits [bp, bp + 64) left-aligned; bp never moves backwards
     __device__ __forceinline__ uint64_t window(uint32_t bp) {
         const uint32_t wi = bp >> 5;
         if (wi != widx) {
-            if (wi == widx + 1) { a = b; b = c; c = w[wi + 2]; }
-            else { a = w[wi]; b = w[wi + 1]; c = w[wi + 2]; }
+            if (wi == widx + 1) { a = b; b = c; c = word(wi + 2); }
+            else { a = word(wi); b = word(wi + 1); c = word(wi + 2); }
             widx = wi;
         }
         const uint32_t off = bp & 31;
@@ -67,25 +86,42 @@ struct BitReader {
     }
 };
 
+// Decode tables of one block in LDS.  Layout (uint32 words):
+//   lut[2^lut_bits] | canon[99] (+1 pad) | codebook[k4] | symsort[k4]     k4 = k_sym rounded up to 4
+// The last two only when k_sym <= kCodebookLdsMax; otherwise they are read from the blob.
+struct Tables {
+    const uint32_t* lut;        // LDS
+    const uint32_t* canon;      // LDS: first_code[33], count[33], first_index[33]
+    const float* cb;            // LDS when small, else the blob's copy
+    const uint32_t* symsort;    // likewise
+    bool small;                 // k_sym <= kCodebookLdsMax (uniform)
+};
+
 // Code longer than the first-level table: canonical search by length.
-__device__ __noinline__ uint32_t decode_long(const DevBlob& d, uint32_t top, uint32_t& len)
+// Returns (symbol << 6) | length.
+__device__ __noinline__ uint32_t decode_long(const uint32_t* canon_, const uint32_t* symsort, bool small,
+                                             uint32_t top, uint32_t lut_bits, uint32_t lmax)
 {
-    for (uint32_t l = d.lut_bits + 1; l <= d.lmax; ++l) {
+    lds_cu32* canon = (lds_cu32*)canon_;
+    for (uint32_t l = lut_bits + 1; l <= lmax; ++l) {
         const uint32_t code = top >> (32 - l);
-        const uint32_t rel = code - d.canon[l];
-        if (rel < d.canon[33 + l]) { len = l; return d.symsort[d.canon[66 + l] + rel]; }
+        const uint32_t rel = code - canon[l];
+        if (rel < canon[33 + l]) {
+            const uint32_t idx = canon[66 + l] + rel;
+            const uint32_t sy = small ? ((lds_cu32*)symsort)[idx] : symsort[idx];
+            return (sy << 6) | l;
+        }
     }
-    len = d.lmax ? d.lmax : 1;      // unreachable for a validated blob; still makes progress
-    return 0;
+    return lmax ? lmax : 1;          // unreachable for a validated blob; still makes progress (symbol 0)
 }
 
-__device__ __forceinline__ uint32_t decode_symbol(const DevBlob& d, const uint32_t* s_lut,
+__device__ __forceinline__ uint32_t decode_symbol(const DevBlob& d, const Tables& t,
                                                   uint32_t top, uint32_t& len)
 {
-    const uint32_t e = s_lut[top >> (32 - d.lut_bits)];
+    uint32_t e = ((lds_cu32*)t.lut)[top >> (32 - d.lut_bits)];
+    if ((e & 63u) == 0) e = decode_long(t.canon, t.symsort, t.small, top, d.lut_bits, d.lmax);
     len = e & 63u;
-    if (len) return e >> 6;
-    return decode_long(d, top, len);
+    return e >> 6;
 }
 
 __device__ __forceinline__ uint32_t ri_field(const uint32_t* ri, uint32_t p, uint32_t bits)
@@ -100,7 +136,6 @@ __device__ __forceinline__ uint32_t ri_field(const uint32_t* ri, uint32_t p, uin
 // one lane's progress through one chunk
 // ---------------------------------------------------------------------------
 struct ChunkState {
-    BitReader rd;
     uint32_t bp;      // next stream bit
     uint32_t row;     // HAC: row of the next symbol
     uint32_t wpos;    // CSC position of the next non-zero this lane will emit
@@ -108,13 +143,13 @@ struct ChunkState {
 };
 
 // HAC: emit non-zeros until wpos reaches `limit` (<= wend).  Zeros only move `row`.
-template <class Emit>
-__device__ __forceinline__ void hac_advance(const DevBlob& d, const uint32_t* s_lut,
+template <class Reader, class Emit>
+__device__ __forceinline__ void hac_advance(const DevBlob& d, const Tables& tb, Reader& rd,
                                             ChunkState& st, uint32_t limit, Emit emit)
 {
     const bool zfast = d.zero_len == 1;
     while (st.wpos < limit) {
-        uint64_t win = st.rd.window(st.bp);
+        uint64_t win = rd.window(st.bp);
         if (zfast) {
             const uint32_t z = win ? (uint32_t)__builtin_clzll(win) : 64u;   // a non-zero follows, so the run ends
             st.bp += z; st.row += z;
@@ -122,7 +157,7 @@ __device__ __forceinline__ void hac_advance(const DevBlob& d, const uint32_t* s_
             win <<= z;
         }
         uint32_t len;
-        const uint32_t s = decode_symbol(d, s_lut, (uint32_t)(win >> 32), len);
+        const uint32_t s = decode_symbol(d, tb, (uint32_t)(win >> 32), len);
         st.bp += len;
         if (d.has_zero && s == 0) { st.row++; continue; }
         emit(st.wpos, st.row, s);
@@ -131,27 +166,27 @@ __device__ __forceinline__ void hac_advance(const DevBlob& d, const uint32_t* s_
 }
 
 // sHAC: every symbol is a non-zero; the row comes from the packed ri fields.
-template <class Emit>
-__device__ __forceinline__ void shac_advance(const DevBlob& d, const uint32_t* s_lut,
+template <bool WANT_ROW, class Reader, class Emit>
+__device__ __forceinline__ void shac_advance(const DevBlob& d, const Tables& tb, Reader& rd,
                                              ChunkState& st, uint32_t limit, Emit emit)
 {
     while (st.wpos < limit) {
-        const uint64_t win = st.rd.window(st.bp);
+        const uint64_t win = rd.window(st.bp);
         uint32_t len;
-        const uint32_t s = decode_symbol(d, s_lut, (uint32_t)(win >> 32), len);
+        const uint32_t s = decode_symbol(d, tb, (uint32_t)(win >> 32), len);
         st.bp += len;
-        emit(st.wpos, ri_field(d.ri, st.wpos, d.ri_bits), s);
+        emit(st.wpos, WANT_ROW ? ri_field(d.ri, st.wpos, d.ri_bits) : 0u, s);
         st.wpos++;
     }
 }
 
-__device__ __forceinline__ void hac_open(const DevBlob& d, uint32_t g, ChunkState& st)
+__device__ __forceinline__ void hac_open(const DevBlob& d, uint32_t g, ChunkState& st, BitReader<false>& rd)
 {
     st.bp = d.cbit[g];
     st.row = (g % d.cpc) * d.chunk;
     st.wpos = d.cpos[g];
     st.wend = d.cpos[g + 1];
-    if (st.wpos < st.wend) st.rd.seek(d.stream, st.bp);
+    if (st.wpos < st.wend) rd.seek(d.stream, 0, st.bp);
 }
 
 // column that owns sHAC chunk g, searched in [c0, c1)
@@ -165,27 +200,49 @@ __device__ __forceinline__ uint32_t shac_col_of(const DevBlob& d, uint32_t g, ui
     return lo;
 }
 
-__device__ __forceinline__ void shac_open(const DevBlob& d, uint32_t g, uint32_t col, ChunkState& st)
+__device__ __forceinline__ void shac_open(const DevBlob& d, uint32_t g, uint32_t col, ChunkState& st,
+                                          BitReader<false>& rd)
 {
     st.bp = d.cbit[g];
     st.row = 0;
     st.wpos = d.cb[col] + (g - d.colchunk[col]) * d.chunk;
     const uint32_t cend = d.cb[col + 1];
     st.wend = st.wpos + d.chunk < cend ? st.wpos + d.chunk : cend;
-    st.rd.seek(d.stream, st.bp);
+    rd.seek(d.stream, 0, st.bp);
 }
 
-__device__ __forceinline__ void load_tables(const DevBlob& d, uint32_t* s_lut, float* s_cb)
+__device__ __forceinline__ uint32_t table_words_dev(const DevBlob& d)
+{
+    const uint32_t k4 = (d.k_sym + 3u) & ~3u;
+    return ((1u << d.lut_bits) + 100u + (d.k_sym <= kCodebookLdsMax ? 2u * k4 : 0u) + 3u) & ~3u;
+}
+
+// All threads of the block copy the tables; the caller synchronises afterwards.
+__device__ __forceinline__ Tables load_tables(const DevBlob& d, uint32_t* smem)
 {
     const uint32_t nl = 1u << d.lut_bits;
+    const uint32_t k4 = (d.k_sym + 3u) & ~3u;
+    uint32_t* s_lut = smem;
+    uint32_t* s_canon = smem + nl;
+    float* s_cb = reinterpret_cast<float*>(s_canon + 100);
+    uint32_t* s_sort = reinterpret_cast<uint32_t*>(s_cb) + k4;
     for (uint32_t i = threadIdx.x; i < nl; i += blockDim.x) s_lut[i] = d.lut[i];
-    if (d.k_sym <= kCodebookLdsMax)
-        for (uint32_t i = threadIdx.x; i < d.k_sym; i += blockDim.x) s_cb[i] = d.codebook[i];
+    for (uint32_t i = threadIdx.x; i < 99u; i += blockDim.x) s_canon[i] = d.canon[i];
+    Tables t;
+    t.lut = s_lut; t.canon = s_canon; t.small = d.k_sym <= kCodebookLdsMax;
+    if (d.k_sym <= kCodebookLdsMax) {
+        for (uint32_t i = threadIdx.x; i < d.k_sym; i += blockDim.x) { s_cb[i] = d.codebook[i]; s_sort[i] = d.symsort[i]; }
+        t.cb = s_cb; t.symsort = s_sort;
+    } else {
+        t.cb = d.codebook; t.symsort = d.symsort;
+    }
+    return t;
 }
 
-__device__ __forceinline__ float value_of(const DevBlob& d, const float* s_cb, uint32_t s)
+typedef __attribute__((address_space(3))) const float lds_cf32;
+__device__ __forceinline__ float value_of(const Tables& t, uint32_t s)
 {
-    return d.k_sym <= kCodebookLdsMax ? s_cb[s] : d.codebook[s];
+    return t.small ? ((lds_cf32*)t.cb)[s] : t.cb[s];
 }
 
 // XCD-aware block order: hardware deals consecutive block ids round-robin to the
@@ -210,18 +267,17 @@ __global__ void __launch_bounds__(256)
 hac_decode_kernel(DevBlob d, float* W, int32_t* sym)
 {
     extern __shared__ uint32_t smem[];
-    uint32_t* s_lut = smem;
-    float* s_cb = reinterpret_cast<float*>(smem + (1u << d.lut_bits));
-    load_tables(d, s_lut, s_cb);
+    const Tables tb = load_tables(d, smem);
     __syncthreads();
     const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= d.n_chunks) return;
     const uint32_t col = g / d.cpc;
     ChunkState st;
-    hac_open(d, g, st);
-    hac_advance(d, s_lut, st, st.wend, [&](uint32_t, uint32_t row, uint32_t s) {
+    BitReader<false> rd;
+    hac_open(d, g, st, rd);
+    hac_advance(d, tb, rd, st, st.wend, [&](uint32_t, uint32_t row, uint32_t s) {
         if (sym) sym[(uint64_t)col * d.n + row] = (int32_t)s;
-        if (W) W[(uint64_t)row * d.m + col] = value_of(d, s_cb, s);
+        if (W) W[(uint64_t)row * d.m + col] = value_of(tb, s);
     });
 }
 
@@ -229,18 +285,17 @@ __global__ void __launch_bounds__(256)
 shac_decode_kernel(DevBlob d, float* nz, int32_t* sym, int32_t* row_out, int32_t* col_out)
 {
     extern __shared__ uint32_t smem[];
-    uint32_t* s_lut = smem;
-    float* s_cb = reinterpret_cast<float*>(smem + (1u << d.lut_bits));
-    load_tables(d, s_lut, s_cb);
+    const Tables tb = load_tables(d, smem);
     __syncthreads();
     const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= d.n_chunks) return;
     const uint32_t col = shac_col_of(d, g, 0, d.m);
     ChunkState st;
-    shac_open(d, g, col, st);
-    shac_advance(d, s_lut, st, st.wend, [&](uint32_t p, uint32_t row, uint32_t s) {
+    BitReader<false> rd;
+    shac_open(d, g, col, st, rd);
+    shac_advance<true>(d, tb, rd, st, st.wend, [&](uint32_t p, uint32_t row, uint32_t s) {
         if (sym) sym[p] = (int32_t)s;
-        if (nz) nz[p] = value_of(d, s_cb, s);
+        if (nz) nz[p] = value_of(tb, s);
         if (row_out) row_out[p] = (int32_t)row;
         if (col_out) col_out[p] = (int32_t)col;
     });
@@ -282,10 +337,8 @@ dot_b1_kernel(DevBlob d, const float* __restrict__ x, float* __restrict__ y,
               uint32_t cpw, uint32_t nblocks)
 {
     extern __shared__ uint32_t smem[];
-    uint32_t* s_lut = smem;
-    float* s_cb = reinterpret_cast<float*>(smem + (1u << d.lut_bits));
-    float* s_x = s_cb + (d.k_sym <= kCodebookLdsMax ? ((d.k_sym + 3u) & ~3u) : 0u);
-    load_tables(d, s_lut, s_cb);
+    const Tables tb = load_tables(d, smem);
+    float* s_x = reinterpret_cast<float*>(smem + table_words_dev(d));
     if (X_LDS)
         for (uint32_t i = threadIdx.x; i < d.n; i += blockDim.x) s_x[i] = x[i];
     __syncthreads();
@@ -305,14 +358,15 @@ dot_b1_kernel(DevBlob d, const float* __restrict__ x, float* __restrict__ y,
         uint32_t col = 0xffffffffu;
         if (g < g1) {
             ChunkState st;
-            if (SHAC) { col = shac_col_of(d, g, c0, c1); shac_open(d, g, col, st); }
-            else { col = g / d.cpc; hac_open(d, g, st); }
+            BitReader<false> rd;
+            if (SHAC) { col = shac_col_of(d, g, c0, c1); shac_open(d, g, col, st, rd); }
+            else { col = g / d.cpc; hac_open(d, g, st, rd); }
             auto emit = [&](uint32_t, uint32_t row, uint32_t s) {
                 const float xv = X_LDS ? s_x[row] : x[row];
-                part = fmaf(xv, value_of(d, s_cb, s), part);
+                part = fmaf(xv, value_of(tb, s), part);
             };
-            if (SHAC) shac_advance(d, s_lut, st, st.wend, emit);
-            else hac_advance(d, s_lut, st, st.wend, emit);
+            if (SHAC) shac_advance<true>(d, tb, rd, st, st.wend, emit);
+            else hac_advance(d, tb, rd, st, st.wend, emit);
         }
         // chunk ids ascend with the lane, so the columns present form a range
         const uint32_t last = (g1 - gb < (uint32_t)kWave ? g1 - gb : (uint32_t)kWave) - 1;
@@ -333,59 +387,183 @@ template <> struct VecLoad<1> { static __device__ __forceinline__ void ld(const 
 template <> struct VecLoad<2> { static __device__ __forceinline__ void ld(const float* p, float* v) { const float2 t = *reinterpret_cast<const float2*>(p); v[0] = t.x; v[1] = t.y; } };
 template <> struct VecLoad<4> { static __device__ __forceinline__ void ld(const float* p, float* v) { const float4 t = *reinterpret_cast<const float4*>(p); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; } };
 
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// FMA phase building blocks.  A lane group takes every ng-th list entry; the
+// loads of kPipe entries are issued together before the first multiply, so that
+// many row fetches are in flight per wave.  UNI: one group spans the wave, an entry
+// is wave-uniform and travels in scalar registers.
+
+template <int NB, int kPipe>
+struct EntryGroup {
+    uint2 e[kPipe];
+    float x[kPipe][NB];
+};
+
+template <int NB, bool UNI, int kPipe>
+__device__ __forceinline__ void group_load(EntryGroup<NB, kPipe>& G, const uint2* list, uint32_t idx, uint32_t ng,
+                                           const float* xt, uint32_t Bp)
+{
+#pragma unroll
+    for (int k = 0; k < kPipe; ++k) {
+        G.e[k] = list[idx + k * ng];
+        if (UNI) { G.e[k].x = __builtin_amdgcn_readfirstlane(G.e[k].x); G.e[k].y = __builtin_amdgcn_readfirstlane(G.e[k].y); }
+    }
+#pragma unroll
+    for (int k = 0; k < kPipe; ++k) VecLoad<NB>::ld(xt + (uint64_t)G.e[k].x * Bp, G.x[k]);
+}
+
+template <int NB, int kPipe>
+__device__ __forceinline__ void group_fma(const EntryGroup<NB, kPipe>& G, float (&acc)[NB])
+{
+#pragma unroll
+    for (int k = 0; k < kPipe; ++k) {
+        const float wv = __uint_as_float(G.e[k].y);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) acc[i] = fmaf(G.x[k][i], wv, acc[i]);
+    }
+}
+
+// Accumulate list entries with CSC positions [lo, hi) (list index = position - winbase).
+template <int NB, bool UNI, int kPipe>
+__device__ __forceinline__ void fma_entries(const uint2* list, uint32_t winbase, uint32_t lo, uint32_t hi,
+                                            uint32_t ng, uint32_t grp, const float* xt, uint32_t Bp,
+                                            float (&acc)[NB])
+{
+    const uint32_t first = lo + grp;
+    const uint32_t count = first < hi ? (hi - first + ng - 1) / ng : 0u;     // entries of this lane group
+    const uint32_t full = count / kPipe;
+    uint32_t idx = first - winbase;
+    const uint32_t step = kPipe * ng;
+    for (uint32_t i = 0; i < full; ++i, idx += step) {
+        EntryGroup<NB, kPipe> G;
+        group_load<NB, UNI, kPipe>(G, list, idx, ng, xt, Bp);
+        group_fma<NB, kPipe>(G, acc);
+    }
+    // last, partial group: entries past the end read entry `idx` again and are not added
+    const uint32_t rest = count - full * kPipe;
+    if (rest) {
+        EntryGroup<NB, kPipe> G;
+#pragma unroll
+        for (int k = 0; k < kPipe; ++k) {
+            G.e[k] = list[idx + ((uint32_t)k < rest ? k * ng : 0u)];
+            if (UNI) { G.e[k].x = __builtin_amdgcn_readfirstlane(G.e[k].x); G.e[k].y = __builtin_amdgcn_readfirstlane(G.e[k].y); }
+        }
+#pragma unroll
+        for (int k = 0; k < kPipe; ++k) VecLoad<NB>::ld(xt + (uint64_t)G.e[k].x * Bp, G.x[k]);
+#pragma unroll
+        for (int k = 0; k < kPipe; ++k) {
+            if ((uint32_t)k < rest) {
+                const float wv = __uint_as_float(G.e[k].y);
+#pragma unroll
+                for (int i = 0; i < NB; ++i) acc[i] = fmaf(G.x[k][i], wv, acc[i]);
+            }
+        }
+    }
+}
+
+// Index entries of one lane's chunk.
+struct LaneChunk {
+    uint32_t bp, bit1;      // first stream bit of the chunk, first bit after it
+    uint32_t wpos, wend;    // CSC positions of its non-zeros
+    uint32_t row;           // HAC: first row
+};
+
+// Lane `lane` takes chunk gb + lane (if below g1).  sHAC: colchunk_l / cbeg_l hold
+// colchunk[c0 + l] and cb[c0 + l] of lane l (l <= ncols); all lanes must call this together.
+template <bool SHAC>
+__device__ __forceinline__ LaneChunk load_lane_chunk(const DevBlob& d, uint32_t gb, uint32_t g1, uint32_t lane,
+                                                     uint32_t ncols, uint32_t colchunk_l, uint32_t cbeg_l)
+{
+    LaneChunk c;
+    c.bp = c.bit1 = c.wpos = c.wend = c.row = 0;
+    const uint32_t g = gb + lane;
+    const bool active = g < g1;
+    if (active) { c.bp = d.cbit[g]; c.bit1 = d.cbit[g + 1]; }
+    if (SHAC) {
+        uint32_t rel = 0;                                    // column of chunk g, relative to c0
+        for (uint32_t k = 1; k < ncols; ++k) rel += (uint32_t)__shfl((int)colchunk_l, (int)k, kWave) <= g ? 1u : 0u;
+        const uint32_t cc0 = (uint32_t)__shfl((int)colchunk_l, (int)rel, kWave);
+        const uint32_t p0 = (uint32_t)__shfl((int)cbeg_l, (int)rel, kWave);
+        const uint32_t p1 = (uint32_t)__shfl((int)cbeg_l, (int)rel + 1, kWave);
+        if (active) {
+            c.wpos = p0 + (g - cc0) * d.chunk;
+            c.wend = c.wpos + d.chunk < p1 ? c.wpos + d.chunk : p1;
+        }
+    } else if (active) {
+        c.wpos = d.cpos[g];
+        c.wend = d.cpos[g + 1];
+        c.row = (g % d.cpc) * d.chunk;
+    }
+    return c;
+}
+
 // gw: lanes per group (power of two, gw * NB = batch columns handled per pass);
 // 64 / gw groups walk the list interleaved and are added together at a column's end.
-template <bool SHAC, int NB>
-__global__ void __launch_bounds__(256)
+template <int NB, bool UNI> struct BatchTraits {
+    static constexpr int kPipe = (NB == 4 && !UNI) ? 8 : 16;        // row fetches in flight per lane group
+    static constexpr int kMaxThreads = 1024;
+};
+
+template <bool SHAC, int NB, bool UNI>
+__global__ void __launch_bounds__((BatchTraits<NB, UNI>::kMaxThreads))
 dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t B,
                  float* __restrict__ Y, uint64_t ldy, uint32_t cpw, uint32_t gw,
-                 uint32_t list_cap, uint32_t nblocks)
+                 uint32_t list_cap, uint32_t sbuf_words, uint32_t nblocks)
 {
     extern __shared__ uint32_t smem[];
-    uint32_t* s_lut = smem;
-    float* s_cb = reinterpret_cast<float*>(smem + (1u << d.lut_bits));
-    uint2* s_lists = reinterpret_cast<uint2*>(s_cb + (d.k_sym <= kCodebookLdsMax ? ((d.k_sym + 3u) & ~3u) : 0u));
-    load_tables(d, s_lut, s_cb);
-    __syncthreads();
-    const uint32_t lb = logical_block(gridDim.x);
-    if (lb >= nblocks) return;
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    uint2* list = s_lists + (uint64_t)wib * list_cap;
+    const uint32_t lb = logical_block(gridDim.x);
     const uint32_t wave = lb * (blockDim.x / kWave) + wib;
     const uint32_t c0 = wave * cpw;
-    if (c0 >= d.m) return;
-    const uint32_t c1 = c0 + cpw < d.m ? c0 + cpw : d.m;
-    const uint32_t g1 = SHAC ? d.colchunk[c1] : c1 * d.cpc;
-    const uint32_t posbase = SHAC ? d.cb[c0] : d.cpos[c0 * d.cpc];
-    const uint32_t posend = SHAC ? d.cb[c1] : d.cpos[c1 * d.cpc];
-
-    const uint32_t ng = kWave / gw;                 // groups
-    const uint32_t grp = lane / gw, lig = lane % gw;
-    const uint32_t boff = blockIdx.y * 256u + lig * NB;   // first batch column of this lane
-    const float* xt = XT + boff;
-
-    // decode state of this lane
-    uint32_t g = (SHAC ? d.colchunk[c0] : c0 * d.cpc) + lane;
-    bool have = false;
-    ChunkState st;
-    auto open_next = [&]() {
-        have = false;
-        while (g < g1) {
-            if (SHAC) shac_open(d, g, shac_col_of(d, g, c0, c1), st); else hac_open(d, g, st);
-            if (st.wpos < st.wend) { have = true; return; }
-            g += kWave;                              // chunk without non-zeros
+    const bool live = lb < nblocks && c0 < d.m;
+    HAC_MARK(0);
+    uint32_t c1 = 0, ncols = 0, gfirst = 0, g1 = 0;
+    uint32_t colend_l = 0, colchunk_l = 0, cbeg_l = 0;
+    LaneChunk nxt;
+    nxt.bp = nxt.bit1 = nxt.wpos = nxt.wend = nxt.row = 0;
+    // The index of the first batch of chunks is requested before the decode tables,
+    // so that both round trips to memory overlap.
+    if (live) {
+        c1 = c0 + cpw < d.m ? c0 + cpw : d.m;
+        ncols = c1 - c0;
+        if (SHAC) {
+            if (lane <= ncols) { colchunk_l = d.colchunk[c0 + lane]; cbeg_l = d.cb[c0 + lane]; }
+            gfirst = (uint32_t)__shfl((int)colchunk_l, 0, kWave);
+            g1 = (uint32_t)__shfl((int)colchunk_l, (int)ncols, kWave);
+        } else {
+            gfirst = c0 * d.cpc;
+            g1 = c1 * d.cpc;
+            if (lane < ncols) colend_l = d.cpos[(c0 + lane + 1) * d.cpc];
         }
-    };
-    open_next();
+        nxt = load_lane_chunk<SHAC>(d, gfirst, g1, lane, ncols, colchunk_l, cbeg_l);
+    }
+    const Tables tb = load_tables(d, smem);
+    __syncthreads();
+    if (!live) return;
+    HAC_MARK(1);
+
+    uint32_t* sbuf = smem + table_words_dev(d) + (uint64_t)wib * (sbuf_words + 2 * list_cap);   // staged stream
+    uint2* list = reinterpret_cast<uint2*>(sbuf + sbuf_words);                                  // (row, value)
+    const uint32_t ng = kWave / gw;
+    const uint32_t grp = lane / gw, lig = lane % gw;
+    const uint32_t boff = blockIdx.y * 256u + lig * NB;      // first batch column of this lane
+    const float* xt = XT + boff;
 
     float acc[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) acc[i] = 0.0f;
-    uint32_t cc = c0;                                // column being accumulated (wave-uniform)
+    uint32_t cc = c0;                                        // column being accumulated (wave-uniform)
+    uint32_t t = 0;                                          // next CSC position to consume
+    bool t_set = false;
 
     auto flush = [&]() {
-        // add the groups together in a fixed order, then group 0 stores Y[b][cc]
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             float v = acc[i];
@@ -396,44 +574,74 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
         }
     };
 
-    for (uint32_t winbase = posbase; winbase < posend; winbase += list_cap) {
-        const uint32_t winend = winbase + list_cap < posend ? winbase + list_cap : posend;
-        // ---- decode phase ----
-        while (have) {
+    for (uint32_t gb = gfirst; gb < g1; gb += kWave) {
+        const uint32_t nact = g1 - gb < (uint32_t)kWave ? g1 - gb : (uint32_t)kWave;
+        const bool active = lane < nact;
+        const LaneChunk cur = nxt;
+        if (gb + kWave < g1) nxt = load_lane_chunk<SHAC>(d, gb + kWave, g1, lane, ncols, colchunk_l, cbeg_l);
+        ChunkState st;
+        st.bp = cur.bp; st.row = cur.row; st.wpos = cur.wpos; st.wend = cur.wend;
+        const uint32_t blo = (uint32_t)__shfl((int)cur.bp, 0, kWave);
+        const uint32_t bhi = (uint32_t)__shfl((int)cur.bit1, (int)(nact - 1), kWave);
+        const uint32_t pbeg = (uint32_t)__shfl((int)cur.wpos, 0, kWave);
+        const uint32_t pend = (uint32_t)__shfl((int)cur.wend, (int)(nact - 1), kWave);
+        if (pbeg == pend) continue;                          // these chunks hold zeros only
+        if (!t_set) { t = pbeg; t_set = true; }
+        // ---- stage the stream words of these chunks in LDS (coalesced 128-bit loads) ----
+        const uint32_t wlo = (blo >> 5) & ~3u;
+        const uint32_t nw = ((bhi >> 5) + 3) - wlo + 1;      // the reader looks two words past the current one
+        const bool staged = nw <= sbuf_words;
+        if (staged) {
+            const uint4* src = reinterpret_cast<const uint4*>(d.stream + wlo);
+            uint4* dst = reinterpret_cast<uint4*>(sbuf);
+            for (uint32_t i = lane; i * 4 < nw; i += kWave) dst[i] = src[i];
+        }
+        wave_sync();
+        HAC_MARK(2);
+        bool opened = false;
+        BitReader<true> rl;
+        BitReader<false> rg;
+        for (uint32_t winbase = pbeg; winbase < pend; winbase += list_cap) {
+            const uint32_t winend = winbase + list_cap < pend ? winbase + list_cap : pend;
+            // ---- decode phase: lanes = chunks ----
             const uint32_t lim = st.wend < winend ? st.wend : winend;
-            auto emit = [&](uint32_t p, uint32_t row, uint32_t s) {
-                list[p - winbase] = make_uint2(row, __float_as_uint(value_of(d, s_cb, s)));
-            };
-            if (SHAC) shac_advance(d, s_lut, st, lim, emit); else hac_advance(d, s_lut, st, lim, emit);
-            if (st.wpos == st.wend) { g += kWave; open_next(); }
-            else break;                              // the window is full for this lane
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // ---- FMA phase ----
-        uint32_t t = winbase;
-        while (cc < c1) {
-            const uint32_t pe = SHAC ? d.cb[cc + 1] : d.cpos[(cc + 1) * d.cpc];
-            const uint32_t hi = pe < winend ? pe : winend;
-#pragma unroll 4
-            for (uint32_t u = t + grp; u < hi; u += ng) {
-                const uint2 e = list[u - winbase];
-                float xv[NB];
-                VecLoad<NB>::ld(xt + (uint64_t)e.x * Bp, xv);
-                const float wv = __uint_as_float(e.y);
-#pragma unroll
-                for (int i = 0; i < NB; ++i) acc[i] = fmaf(xv[i], wv, acc[i]);
+            if (active && st.wpos < lim) {
+                auto emit = [&](uint32_t p, uint32_t row, uint32_t s) {
+                    if (SHAC) list[p - winbase].y = __float_as_uint(value_of(tb, s));
+                    else list[p - winbase] = make_uint2(row, __float_as_uint(value_of(tb, s)));
+                };
+                if (staged) {
+                    if (!opened) { rl.seek(sbuf, wlo, st.bp); opened = true; }
+                    if (SHAC) shac_advance<false>(d, tb, rl, st, lim, emit); else hac_advance(d, tb, rl, st, lim, emit);
+                } else {
+                    if (!opened) { rg.seek(d.stream, 0, st.bp); opened = true; }
+                    if (SHAC) shac_advance<false>(d, tb, rg, st, lim, emit); else hac_advance(d, tb, rg, st, lim, emit);
+                }
             }
-            t = hi;
-            if (pe <= winend) { flush(); ++cc; }
-            else break;                              // column continues in the next window
+            HAC_MARK(3);
+            if (SHAC) {
+                // row indices: fixed-width fields, unpacked by all lanes side by side
+                for (uint32_t p = winbase + lane; p < winend; p += kWave)
+                    list[p - winbase].x = ri_field(d.ri, p, d.ri_bits);
+            }
+            wave_sync();
+            HAC_MARK(4);
+            // ---- FMA phase: lanes = batch ----
+            while (cc < c1) {
+                const uint32_t pe = SHAC ? (uint32_t)__shfl((int)cbeg_l, (int)(cc - c0 + 1), kWave)
+                                         : (uint32_t)__shfl((int)colend_l, (int)(cc - c0), kWave);
+                const uint32_t hi = pe < winend ? pe : winend;
+                if (t < hi) fma_entries<NB, UNI, BatchTraits<NB, UNI>::kPipe>(list, winbase, t, hi, ng, grp, xt, Bp, acc);
+                t = hi > t ? hi : t;
+                if (pe <= winend) { flush(); ++cc; }
+                else break;                                  // column continues in the next window
+            }
+            wave_sync();
+            HAC_MARK(5);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
-    while (cc < c1) { flush(); ++cc; }               // trailing columns without non-zeros
+    while (cc < c1) { flush(); ++cc; }                       // trailing columns without non-zeros
+    HAC_MARK(6);
 }
 
 // ---------------------------------------------------------------------------
@@ -471,17 +679,23 @@ int make_dev(const hac_desc_t* desc, const void* d_blob, uint32_t format, DevBlo
 
 uint32_t table_words(const DevBlob& d)
 {
-    return (1u << d.lut_bits) + (d.k_sym <= kCodebookLdsMax ? ((d.k_sym + 3u) & ~3u) : 0u);
+    const uint32_t k4 = (d.k_sym + 3u) & ~3u;
+    return ((1u << d.lut_bits) + 100u + (d.k_sym <= kCodebookLdsMax ? 2u * k4 : 0u) + 3u) & ~3u;
 }
 
 struct BatchShape { uint32_t gw, nb, Bp, tiles; };
 
+// Bp: padded batch width of the feature-major copy; a wave pass covers gw * nb
+// batch columns (at most 256); wider batches take several passes (grid.y).
 BatchShape batch_shape(int64_t B)
 {
     BatchShape s;
-    if (B <= 64) { uint32_t g = 1; while (g < (uint32_t)B) g <<= 1; s.gw = g; s.nb = 1; s.Bp = g; s.tiles = 1; }
-    else if (B <= 128) { s.gw = 64; s.nb = 2; s.Bp = 128; s.tiles = 1; }
-    else { s.gw = 64; s.nb = 4; s.Bp = (uint32_t)((B + 255) / 256 * 256); s.tiles = s.Bp / 256; }
+    uint32_t p = 1;
+    while (p < (uint32_t)(B < 256 ? B : 256)) p <<= 1;
+    s.nb = p < 4 ? p : 4;
+    s.gw = p / s.nb;
+    if (B <= 256) { s.Bp = p; s.tiles = 1; }
+    else { s.Bp = (uint32_t)((B + 255) / 256 * 256); s.tiles = s.Bp / 256; }
     return s;
 }
 
@@ -498,6 +712,19 @@ uint32_t default_cpw(const hac_desc_t* desc)
     return cpw;
 }
 
+uint32_t round_up(uint32_t v, uint32_t q) { return (v + q - 1) / q * q; }
+
+typedef void (*batch_kern_t)(DevBlob, const float*, uint32_t, uint32_t, float*, uint64_t,
+                             uint32_t, uint32_t, uint32_t, uint32_t, uint32_t);
+
+template <bool SHAC>
+batch_kern_t pick_batch_kernel(uint32_t nb, bool uni)
+{
+    if (nb == 1) return uni ? dot_batch_kernel<SHAC, 1, true> : dot_batch_kernel<SHAC, 1, false>;
+    if (nb == 2) return uni ? dot_batch_kernel<SHAC, 2, true> : dot_batch_kernel<SHAC, 2, false>;
+    return uni ? dot_batch_kernel<SHAC, 4, true> : dot_batch_kernel<SHAC, 4, false>;
+}
+
 int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
              const float* d_X, int64_t B, int64_t ldx, float* d_Y, int64_t ldy,
              void* d_ws, size_t ws_bytes, const hac_launch_t* launch, hac_stream_t stream_)
@@ -509,23 +736,29 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     if (B == 0) return HAC_OK;
     if (!d_X || !d_Y || ldx < (int64_t)desc->n || ldy < (int64_t)desc->m) return HAC_EINVAL;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    uint32_t cpw = default_cpw(desc), wpb = 0, list_cap = 1024, variant = 0;
+    uint32_t cpw = default_cpw(desc), wpb = 0, list_cap = 0, sbuf_words = 0, variant = 0;
+    bool reuse_xt = false;
     if (launch) {
-        if (launch->cols_per_wave > 64 || launch->waves_per_block > 16) return HAC_EINVAL;
+        if (launch->cols_per_wave > 32 || launch->waves_per_block > 16) return HAC_EINVAL;
         if (launch->cols_per_wave) cpw = launch->cols_per_wave;
         wpb = launch->waves_per_block;
-        variant = launch->variant;
-        if (launch->reserved[0]) list_cap = launch->reserved[0];
-        if (list_cap < 64 || list_cap > 4096) return HAC_EINVAL;
+        variant = launch->variant & 0xffu;
+        reuse_xt = (launch->variant & HAC_LAUNCH_REUSE_XT) != 0;
+        if (launch->variant & ~(0xffu | HAC_LAUNCH_REUSE_XT)) return HAC_EINVAL;
+        list_cap = launch->reserved[0];
+        sbuf_words = launch->reserved[1];
+        if (list_cap && (list_cap < 64 || list_cap > 4096)) return HAC_EINVAL;
+        if (sbuf_words && (sbuf_words < 16 || sbuf_words > 8192 || sbuf_words % 4)) return HAC_EINVAL;
+        if (launch->reserved[2] || launch->reserved[3] || launch->reserved[4]) return HAC_EINVAL;
     }
     const uint32_t nwaves = (d.m + cpw - 1) / cpw;
     const bool shac = format == HAC_FORMAT_SHAC;
     g_last_hip_error = 0;
 
-    if (B == 1 && variant != 2) {
+    if (B == 1 && variant == 1) {
         if (!wpb) wpb = 16;
         const size_t base = 4ull * table_words(d);
-        const bool x_lds = base + 4ull * d.n <= kLdsLimit - 1024 && variant != 1;
+        const bool x_lds = base + 4ull * d.n <= kLdsLimit - 1024;
         const size_t lds = base + (x_lds ? 4ull * d.n : 0);
         const uint32_t nblocks = (nwaves + wpb - 1) / wpb;
         const uint32_t grid = (nblocks + 7) / 8 * 8;
@@ -543,36 +776,63 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     }
 
     const BatchShape bs = batch_shape(B);
-    const size_t need = 4ull * d.n * bs.Bp;
-    if (!d_ws || ws_bytes < need) return HAC_EWORKSPACE;
-    if (reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
-    float* XT = static_cast<float*>(d_ws);
-    {
-        dim3 grid((d.n + 31) / 32, (bs.Bp + 31) / 32);
-        hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, stream,
-                           d_X, (uint32_t)B, d.n, (uint64_t)ldx, XT, bs.Bp);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return hip_fail(e);
+    const float* XT = d_X;                                   // B = 1: X is its own feature-major copy
+    if (B > 1) {
+        const size_t need = 4ull * d.n * bs.Bp;
+        if (!d_ws || ws_bytes < need) return HAC_EWORKSPACE;
+        if (reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
+        float* xt = static_cast<float*>(d_ws);
+        XT = xt;
+        if (!reuse_xt) {
+            dim3 grid((d.n + 31) / 32, (bs.Bp + 31) / 32);
+            hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, stream,
+                               d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt, bs.Bp);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return hip_fail(e);
+        }
     }
-    if (!wpb) wpb = 4;
-    if (wpb > 4) wpb = 4;                                   // the kernel is bounded to 256 threads
-    const size_t lds = 4ull * table_words(d) + 8ull * list_cap * wpb;
+    // per-wave LDS: stream words of one batch of 64 chunks, and the list of its non-zeros
+    {
+        const double cpcol = (double)desc->n_chunks / (double)desc->m;
+        double cols = cpcol > 0.0 ? 64.0 / cpcol : (double)cpw;
+        if (cols > (double)cpw) cols = (double)cpw;
+        if (!sbuf_words) {
+            const double est = ((double)desc->max_col_bits / 32.0 + 1.0) * cols + 8.0;
+            sbuf_words = round_up((uint32_t)(est < 4096.0 ? est : 4096.0), 64);
+            if (sbuf_words > 4096) sbuf_words = 4096;
+        }
+        if (!list_cap) {
+            const double est = (double)desc->max_col_nnz * cols;
+            list_cap = round_up((uint32_t)(est < 2048.0 ? (est > 1.0 ? est : 1.0) : 2048.0), 64);
+        }
+    }
+    const size_t per_wave = 4ull * sbuf_words + 8ull * list_cap;
+    if (!wpb) {
+        // as many wavefronts per CU as LDS allows (at most 16), in blocks that share one copy of the tables
+        const size_t tbl = 4ull * table_words(d);
+        uint32_t best_waves = 0;
+        for (uint32_t w = 16; w >= 1; w >>= 1) {
+            const size_t blk = tbl + w * per_wave;
+            if (blk > kLdsLimit) continue;
+            uint32_t waves = (uint32_t)(kLdsLimit / blk) * w;
+            if (waves > 16) waves = 16;
+            if (waves > best_waves) { best_waves = waves; wpb = w; }
+        }
+        if (!wpb) wpb = 1;
+    }
+    const size_t lds = 4ull * table_words(d) + (size_t)wpb * per_wave;
     if (lds > kLdsLimit) return HAC_EINVAL;
     const uint32_t nblocks = (nwaves + wpb - 1) / wpb;
     const uint32_t grid = (nblocks + 7) / 8 * 8;
-    typedef void (*kern_t)(DevBlob, const float*, uint32_t, uint32_t, float*, uint64_t,
-                           uint32_t, uint32_t, uint32_t, uint32_t);
-    kern_t k;
-    if (bs.nb == 1) k = shac ? dot_batch_kernel<true, 1> : dot_batch_kernel<false, 1>;
-    else if (bs.nb == 2) k = shac ? dot_batch_kernel<true, 2> : dot_batch_kernel<false, 2>;
-    else k = shac ? dot_batch_kernel<true, 4> : dot_batch_kernel<false, 4>;
+    const bool uni = bs.gw == 64;
+    batch_kern_t k = shac ? pick_batch_kernel<true>(bs.nb, uni) : pick_batch_kernel<false>(bs.nb, uni);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return hip_fail(e);
     }
     hipLaunchKernelGGL(k, dim3(grid, bs.tiles), dim3(wpb * kWave), lds, stream,
-                       d, XT, bs.Bp, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, bs.gw, list_cap, nblocks);
+                       d, XT, bs.Bp, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, bs.gw, list_cap, sbuf_words, nblocks);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? HAC_OK : hip_fail(e);
 }
@@ -582,8 +842,9 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
 extern "C" size_t hac_workspace_bytes(const hac_desc_t* desc, int64_t B)
 {
     if (!desc || B <= 0) return 0;
+    if (B == 1) return 0;                                    // a single row is its own feature-major copy
     const BatchShape bs = batch_shape(B);
-    return (size_t)4 * (size_t)desc->n * bs.Bp;             // B = 1 does not use it, but a variant may
+    return (size_t)4 * (size_t)desc->n * bs.Bp;
 }
 
 extern "C" int hac_dot(const hac_desc_t* desc, const void* d_blob, const float* d_X, int64_t B, int64_t ldx,
@@ -635,3 +896,11 @@ extern "C" int shac_decode_dev(const hac_desc_t* desc, const void* d_blob, float
 }
 
 extern "C" int hac_last_hip_error(void) { return g_last_hip_error; }
+
+#ifdef HAC_PHASE_TIMING
+extern "C" int hac_debug_phases(unsigned long long* out, size_t count)
+{
+    if (count > 16384 * 8) count = 16384 * 8;
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase), count * sizeof(unsigned long long)) == hipSuccess ? 0 : -5;
+}
+#endif

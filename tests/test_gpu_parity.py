@@ -126,15 +126,20 @@ def test_launch_overrides_do_not_change_the_result(hac):
     Xd = torch.from_numpy(X).to(dev())
     for enc, f in ((hac.hac_encode, hac.hac_dot), (hac.shac_encode, hac.shac_dot)):
         db = enc(W).to_device(dev())
-        for cpw, wpb, cap in ((1, 1, 64), (3, 2, 64), (7, 4, 128), (64, 4, 4096), (2, 3, 1024)):
-            print(f"[case] launch {f.__name__} cpw={cpw} wpb={wpb} cap={cap}", flush=True)
+        for cpw, wpb, cap, sbuf in ((1, 1, 64, 0), (3, 2, 64, 16), (7, 4, 128, 64), (32, 4, 2048, 4096), (5, 16, 256, 0),
+                                    (2, 3, 1024, 0)):
+            print(f"[case] launch {f.__name__} cpw={cpw} wpb={wpb} cap={cap} sbuf={sbuf}", flush=True)
             launch = hac.Launch(cols_per_wave=cpw, waves_per_block=wpb)
-            launch.reserved[0] = cap                        # list capacity: forces several windows per column
+            launch.reserved[0] = cap          # list capacity: small values force several windows per column
+            launch.reserved[1] = sbuf         # staging buffer: small values force the unstaged reader
             Y = f(db, Xd, launch=launch)
-            Y1 = f(db, Xd[:1], launch=hac.Launch(cols_per_wave=cpw, waves_per_block=wpb))
+            Y1 = f(db, Xd[:1], launch=launch)
+            fused = hac.Launch(cols_per_wave=cpw, waves_per_block=wpb, variant=1)
+            Y1f = f(db, Xd[:1], launch=fused)
             torch.cuda.synchronize()
             check_y(Y, X, W, f"{f.__name__} cpw={cpw}")
             check_y(Y1, X[:1], W, f"{f.__name__} B=1 cpw={cpw}")
+            check_y(Y1f, X[:1], W, f"{f.__name__} B=1 fused cpw={cpw}")
 
 
 def test_identity_batch_recovers_w_bit_exact(hac):
