@@ -51,7 +51,6 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--hot", action="store_true", help="no rotation: same buffers every step (cache-resident)")
-    ap.add_argument("--chunk-rows", type=int, default=0)
     ap.add_argument("--chunk-nnz", type=int, default=0)
     ap.add_argument("--only", type=str, default="", help="restrict the step to 'hac' or 'shac'")
     ap.add_argument("--detail", action="store_true", help="also time every (format, B) call on its own")
@@ -85,32 +84,34 @@ class Call:
 
 
 def time_region(torch, body, iters, warmup, use_graph, rot):
-    """Average milliseconds per body(i) call over `iters` calls, HIP events on the current stream."""
+    """Average milliseconds per body(i) call over exactly `iters` calls, HIP events on the current stream.
+
+    With graphs, one captured graph holds `rot` consecutive calls (one per buffer set) and is
+    replayed iters // rot times; the remaining iters % rot calls are launched eagerly.
+    """
     stream = torch.cuda.current_stream()
     for i in range(warmup):
         body(i)
     torch.cuda.synchronize()
-    graphs = None
+    graph = None
     if use_graph:
-        graphs = []
-        for j in range(rot):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=stream):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for j in range(rot):
                 body(j)
-            graphs.append(g)
-        for g in graphs:
-            g.replay()
+        graph.replay()
         torch.cuda.synchronize()
     t0 = torch.cuda.Event(enable_timing=True)
     t1 = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0.record(stream)
-    if graphs is not None:
-        for i in range(iters):
-            graphs[i % rot].replay()
-    else:
-        for i in range(iters):
-            body(i)
+    done = 0
+    if graph is not None:
+        for _ in range(iters // rot):
+            graph.replay()
+        done = (iters // rot) * rot
+    for i in range(done, iters):
+        body(i)
     t1.record(stream)
     torch.cuda.synchronize()
     return t0.elapsed_time(t1) / iters
@@ -166,7 +167,7 @@ def main():
     t_start = time.perf_counter()
     W = workloads.layer(args.config)
     Xhost = workloads.make_batch(max(batches), cfg.n, 1000 * cfg.cfg + 1)
-    hb = hac.hac_encode(W, chunk_rows=args.chunk_rows)
+    hb = hac.hac_encode(W, chunk_nnz=args.chunk_nnz)
     sb = hac.shac_encode(W, chunk_nnz=args.chunk_nnz)
     t_prep = time.perf_counter() - t_start
 
@@ -226,7 +227,7 @@ def main():
                         f"k={cfg.k} {cfg.quant}; X ReLU(N(0,1)) fp32; step = " +
                         " + ".join(f"{f}_dot(B={B})" for B in batches for f in fmts),
             "batches": batches, "formats": fmts, "rotation_sets": rot, "graph_replay": use_graph,
-            "hac_chunk_rows": int(hb.desc.chunk), "shac_chunk_nnz": int(sb.desc.chunk),
+            "hac_chunk_nnz": int(hb.desc.chunk), "shac_chunk_nnz": int(sb.desc.chunk),
             "shac_ri_bits": int(sb.desc.ri_bits),
             "hac_blob_bytes": hb.nbytes, "shac_blob_bytes": sb.nbytes, "nnz": int(hb.desc.nnz),
         },

@@ -58,18 +58,29 @@ typedef void *hac_stream_t;
 
 /* Encoder options; pass NULL for the defaults given in brackets. */
 typedef struct {
-    uint32_t chunk_rows;  /* HAC: rows of one column per index entry [512]; 0 = default   */
-    uint32_t chunk_nnz;   /* sHAC: non-zeros per index entry, restarting at every column
-                             [32]; 0 = default                                             */
+    uint32_t chunk_nnz;   /* non-zeros per index entry, restarting at every column; 0 = default
+                             [max(4, ceil(most non-zeros in a column / 64))]: one wavefront
+                             then decodes a whole column side by side                       */
     uint32_t ri_bits;     /* sHAC row-index field width: 0 = ceil(log2 n) (footnote of
                              Sect. IV-A), 32 = one word per index as in Corollary 2        */
     uint32_t lut_bits;    /* width of the first-level decode table, 1..12 [min(Lmax,10)]  */
+    uint32_t reserved;    /* must be 0                                                     */
 } hac_opts_t;
 
-/* Blob header == descriptor.  All offsets are bytes from the start of the blob. */
+/* Blob header == descriptor.  All offsets are bytes from the start of the blob.
+ *
+ * The index added for the GPU (not part of the paper's formats; its conclusions
+ * suggest "the vector of the offsets in the bitstring denoting the beginning of
+ * each column"): per column its first stream bit, its first CSC position and
+ * its first chunk; per chunk of `chunk` consecutive non-zeros of a column the
+ * bit at which its decoding starts, relative to the column's first bit, and
+ * for HAC the row of the first symbol decoded there.  Chunk k of column j
+ * holds the non-zeros col_pos[j] + k*chunk ... and, for HAC, starts right
+ * after the codeword of the non-zero before them (at the column's first bit
+ * for k = 0), so the zeros in front of its first non-zero belong to it. */
 typedef struct {
     uint32_t magic;        /* 'HAC1' = 0x31434148                                          */
-    uint32_t version;      /* 1                                                            */
+    uint32_t version;      /* 2                                                            */
     uint32_t format;       /* HAC_FORMAT_HAC / HAC_FORMAT_SHAC                             */
     uint32_t header_bytes; /* 256                                                          */
     uint64_t n, m;         /* shape of W                                                   */
@@ -82,26 +93,32 @@ typedef struct {
     uint32_t has_zero;     /* HAC: 1 when 0.0 occurs in W; it is then symbol 0             */
     uint32_t zero_len;     /* HAC: codeword length of symbol 0 when that codeword is all
                               zero bits (it is one of the shortest), else 0                */
-    uint32_t chunk;        /* HAC: rows per chunk; sHAC: non-zeros per chunk               */
+    uint32_t chunk;        /* non-zeros per chunk                                          */
     uint32_t ri_bits;      /* sHAC: width of one row-index field                           */
-    uint32_t chunks_per_col; /* HAC: ceil(n / chunk)                                       */
-    uint64_t n_chunks;     /* number of index entries (the index arrays hold one more)     */
+    uint32_t ent_bits;     /* width of one chunk entry: HAC 32 or 64, sHAC 16 or 32        */
+    uint64_t n_chunks;     /* sum over columns of ceil(non-zeros in the column / chunk)    */
     uint64_t off_codebook; /* float[k_sym]: symbol -> shared value (H^-1's values)         */
     uint64_t off_codelen;  /* uint8[k_sym]: codeword length per symbol                     */
     uint64_t off_canon;    /* uint32[3][33]: first_code[l], count[l], first_index[l]       */
     uint64_t off_symsort;  /* uint32[k_sym]: symbols in (length, symbol) order             */
     uint64_t off_lut;      /* uint32[2^lut_bits]: (symbol << 6) | length, 0 = longer code  */
     uint64_t off_stream;   /* uint32[n_words], followed by >= 64 bytes of zeros            */
-    uint64_t off_chunk_bit;/* uint32[n_chunks + 1]: bit offset where each chunk starts     */
-    uint64_t off_chunk_pos;/* HAC: uint32[n_chunks + 1]: non-zeros before each chunk       */
-    uint64_t off_col_chunk;/* sHAC: uint32[m + 1]: first chunk of each column              */
-    uint64_t off_cb;       /* sHAC: uint32[m + 1]: column begins, 0-based, cb[m] = nnz     */
+    uint64_t off_col_chunk;/* uint32[m + 1]: first chunk of each column                    */
+    uint64_t off_col_pos;  /* uint32[m + 1]: CSC position of each column's first non-zero;
+                              for sHAC this is the paper's cb (0-based, cb[m] = nnz)       */
+    uint64_t off_col_bit;  /* uint32[m + 1]: first stream bit of each column               */
+    uint64_t off_chunk_ent;/* n_chunks entries of ent_bits bits (+ >= 8 bytes of zeros):
+                              sHAC: bit offset relative to col_bit[j];
+                              HAC : (relative bit offset << row_bits) | first row, as one
+                              uint32, or as uint32 pair {first row, relative bit offset}   */
     uint64_t off_ri;       /* sHAC: row indices, ri_bits-wide fields packed MSB-first into
                               uint32 words, followed by >= 64 bytes of zeros               */
     uint64_t blob_bytes;   /* total size                                                   */
     uint64_t max_col_bits; /* longest stretch of stream bits that one column occupies      */
     uint64_t max_col_nnz;  /* most non-zeros in one column                                 */
-    uint64_t reserved[6];
+    uint32_t row_bits;     /* HAC, ent_bits = 32: low bits of an entry that hold the row   */
+    uint32_t reserved32;
+    uint64_t reserved[5];
 } hac_desc_t;
 
 /* Sizes as the paper accounts for them (Sect. IV-B/IV-C) next to the real ones. */
@@ -109,8 +126,9 @@ typedef struct {
     uint64_t stream_bits;      /* exact |HAC(.)|                                           */
     uint64_t stream_bytes;     /* 4 * n_words                                              */
     uint64_t table_bytes;      /* codebook + lengths + canonical tables + first-level table*/
-    uint64_t index_bytes;      /* chunk index added for the GPU (not part of the format)   */
-    uint64_t ri_bytes, cb_bytes;
+    uint64_t index_bytes;      /* index added for the GPU (not part of the paper's format):
+                                  col_chunk, col_bit, chunk entries, and for HAC col_pos   */
+    uint64_t ri_bytes, cb_bytes; /* sHAC: packed ri, and cb (= col_pos)                     */
     uint64_t blob_bytes;
     uint64_t paper_bits;       /* 32*N + 6*32*k (+ 32*(q + m + 1) for sHAC): the quantity
                                   bounded by Corollary 1 / Corollary 2                     */
@@ -126,13 +144,11 @@ typedef struct {
 typedef struct {
     uint32_t cols_per_wave;   /* columns of W one wavefront handles, 1..32                 */
     uint32_t waves_per_block; /* 1..16                                                     */
-    uint32_t variant;         /* low byte: 0 = default kernel choice, 1 = for B = 1 the
-                                 kernel that multiplies while decoding with x held in LDS;
-                                 may be or-ed with HAC_LAUNCH_REUSE_XT                      */
+    uint32_t variant;         /* 0, or HAC_LAUNCH_REUSE_XT                                  */
     uint32_t reserved[5];     /* [0]: entries of the per-wavefront non-zero list, 64..4096;
-                                 [1]: words of the per-wavefront stream staging buffer,
-                                 16..8192, multiple of 4; 0 = sized from the blob header;
-                                 the others must be 0                                      */
+                                 [1]: words of the per-wavefront staging buffer for stream
+                                 (and ri) words, 16..16384, multiple of 4;
+                                 0 = sized from the blob header; the others must be 0      */
 } hac_launch_t;
 
 /* The workspace already holds the feature-major copy of this very X (same B,
@@ -157,10 +173,10 @@ int shac_encode(const float *W, int64_t n, int64_t m, int64_t ldw,
 void hac_free(void *blob);
 
 /* Check a host blob: header, section bounds, code tables (Kraft equality,
- * canonical order, first-level table), monotone index, cb monotone with
- * cb[m] = nnz.  With deep != 0 the stream is also decoded from bit 0 and every
- * index entry, symbol count and row index (< n, ascending in a column) is
- * checked against it.  Never reads outside [blob, blob + bytes). */
+ * canonical order, first-level table), monotone column arrays with
+ * col_pos[m] = nnz.  With deep != 0 the stream is also decoded from bit 0 and
+ * every index entry, symbol count and row index (< n, ascending in a column)
+ * is checked against it.  Never reads outside [blob, blob + bytes). */
 int hac_validate(const void *blob, size_t bytes, int deep);
 
 /* Copy the header of a validated host blob into *desc (header checks only). */

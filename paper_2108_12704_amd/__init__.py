@@ -37,8 +37,8 @@ class HacError(RuntimeError):
 
 
 class Opts(C.Structure):
-    _fields_ = [("chunk_rows", C.c_uint32), ("chunk_nnz", C.c_uint32),
-                ("ri_bits", C.c_uint32), ("lut_bits", C.c_uint32)]
+    _fields_ = [("chunk_nnz", C.c_uint32), ("ri_bits", C.c_uint32),
+                ("lut_bits", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class Desc(C.Structure):
@@ -48,14 +48,15 @@ class Desc(C.Structure):
                 ("total_bits", C.c_uint64), ("n_words", C.c_uint64),
                 ("k_sym", C.c_uint32), ("lmax", C.c_uint32), ("lut_bits", C.c_uint32),
                 ("has_zero", C.c_uint32), ("zero_len", C.c_uint32), ("chunk", C.c_uint32),
-                ("ri_bits", C.c_uint32), ("chunks_per_col", C.c_uint32),
+                ("ri_bits", C.c_uint32), ("ent_bits", C.c_uint32),
                 ("n_chunks", C.c_uint64),
                 ("off_codebook", C.c_uint64), ("off_codelen", C.c_uint64), ("off_canon", C.c_uint64),
                 ("off_symsort", C.c_uint64), ("off_lut", C.c_uint64), ("off_stream", C.c_uint64),
-                ("off_chunk_bit", C.c_uint64), ("off_chunk_pos", C.c_uint64),
-                ("off_col_chunk", C.c_uint64), ("off_cb", C.c_uint64), ("off_ri", C.c_uint64),
+                ("off_col_chunk", C.c_uint64), ("off_col_pos", C.c_uint64), ("off_col_bit", C.c_uint64),
+                ("off_chunk_ent", C.c_uint64), ("off_ri", C.c_uint64),
                 ("blob_bytes", C.c_uint64), ("max_col_bits", C.c_uint64), ("max_col_nnz", C.c_uint64),
-                ("reserved", C.c_uint64 * 6)]
+                ("row_bits", C.c_uint32), ("reserved32", C.c_uint32),
+                ("reserved", C.c_uint64 * 5)]
 
 
 class Stats(C.Structure):
@@ -184,7 +185,7 @@ class DeviceBlob:
         return int(self.desc.m)
 
 
-def _encode(fn_name: str, W: np.ndarray, chunk_rows=0, chunk_nnz=0, ri_bits=0, lut_bits=0) -> Blob:
+def _encode(fn_name: str, W: np.ndarray, chunk_nnz=0, ri_bits=0, lut_bits=0) -> Blob:
     lib = load_library()
     W = np.asarray(W)
     if W.dtype != np.float32 or W.ndim != 2:
@@ -192,7 +193,7 @@ def _encode(fn_name: str, W: np.ndarray, chunk_rows=0, chunk_nnz=0, ri_bits=0, l
     if W.strides[1] != 4 or W.strides[0] % 4 or W.strides[0] < 4 * W.shape[1]:
         W = np.ascontiguousarray(W)
     ldw = W.strides[0] // 4
-    opts = Opts(chunk_rows, chunk_nnz, ri_bits, lut_bits)
+    opts = Opts(chunk_nnz, ri_bits, lut_bits, 0)
     out = C.c_void_p()
     size = C.c_size_t()
     rc = getattr(lib, fn_name)(W.ctypes.data_as(C.POINTER(C.c_float)), W.shape[0], W.shape[1], ldw,
@@ -205,9 +206,9 @@ def _encode(fn_name: str, W: np.ndarray, chunk_rows=0, chunk_nnz=0, ri_bits=0, l
     return Blob(data)
 
 
-def hac_encode(W: np.ndarray, chunk_rows: int = 0, lut_bits: int = 0) -> Blob:
+def hac_encode(W: np.ndarray, chunk_nnz: int = 0, lut_bits: int = 0) -> Blob:
     """W (n x m float32, host) -> HAC blob."""
-    return _encode("hac_encode", W, chunk_rows=chunk_rows, lut_bits=lut_bits)
+    return _encode("hac_encode", W, chunk_nnz=chunk_nnz, lut_bits=lut_bits)
 
 
 def shac_encode(W: np.ndarray, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0) -> Blob:

@@ -19,7 +19,7 @@ static_assert(sizeof(hac_desc_t) == 256, "blob header must be 256 bytes");
 namespace {
 
 constexpr uint32_t kMagic = 0x31434148u;   // "HAC1"
-constexpr uint32_t kVersion = 1;
+constexpr uint32_t kVersion = 2;
 constexpr uint64_t kAlign = 256;
 constexpr uint64_t kTailPad = 64;          // zero bytes after stream / ri for window over-reads
 
@@ -255,6 +255,46 @@ uint32_t pick_lut_bits(const hac_opts_t* opts, uint32_t lmax)
     return b;
 }
 
+uint32_t pick_chunk(const hac_opts_t* opts, uint64_t max_col_nnz)
+{
+    if (opts && opts->chunk_nnz) return opts->chunk_nnz;
+    const uint64_t c = (max_col_nnz + 63) / 64;              // a 64-lane wavefront covers any column
+    return (uint32_t)std::min<uint64_t>(std::max<uint64_t>(c, 4), 65536);
+}
+
+int check_opts(const hac_opts_t* opts)
+{
+    if (!opts) return HAC_OK;
+    if (opts->lut_bits > 12 || opts->chunk_nnz > 65536 || opts->reserved) return HAC_EINVAL;
+    return HAC_OK;
+}
+
+// Column-wise chunk bookkeeping shared by both encoders.
+struct ColumnIndex {
+    std::vector<uint32_t> col_chunk, col_pos, col_bit;   // m + 1 each
+    uint64_t n_chunks = 0, max_col_nnz = 0;
+    void build(const Scan& s, uint32_t chunk) {
+        const size_t m = (size_t)s.m;
+        col_chunk.assign(m + 1, 0); col_pos.assign(m + 1, 0); col_bit.assign(m + 1, 0);
+        n_chunks = 0;
+        for (size_t j = 0; j < m; ++j) {
+            const uint64_t cnt = s.cb[j + 1] - s.cb[j];
+            col_chunk[j] = (uint32_t)n_chunks;
+            col_pos[j] = (uint32_t)s.cb[j];
+            n_chunks += (cnt + chunk - 1) / chunk;
+        }
+        col_chunk[m] = (uint32_t)n_chunks;
+        col_pos[m] = (uint32_t)s.cb[m];
+    }
+};
+
+uint64_t max_nnz_per_column(const Scan& s)
+{
+    uint64_t mx = 0;
+    for (size_t j = 0; j + 1 < s.cb.size(); ++j) mx = std::max(mx, s.cb[j + 1] - s.cb[j]);
+    return mx;
+}
+
 } // namespace
 
 // =================================================================================
@@ -266,7 +306,7 @@ extern "C" int hac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
     int rc = check_args(W, n, m, ldw, blob, blob_bytes);
     if (rc) return rc;
     *blob = nullptr; *blob_bytes = 0;
-    if (opts && (opts->lut_bits > 12 || (opts->chunk_rows && opts->chunk_rows > 65536))) return HAC_EINVAL;
+    if ((rc = check_opts(opts))) return rc;
     try {
         Scan s;
         rc = scan_matrix(W, n, m, ldw, s);
@@ -290,28 +330,41 @@ extern "C" int hac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         if (lut_bits < 1 || lut_bits > 12) return HAC_EINVAL;
         std::vector<uint32_t> lut; build_lut(len, t, lut_bits, lut);
 
-        const uint32_t R = opts && opts->chunk_rows ? opts->chunk_rows : 512;
-        const uint64_t cpc = ((uint64_t)n + R - 1) / R;
-        const uint64_t n_chunks = cpc * (uint64_t)m;
-        if (n_chunks > 0xfffffff0ull) return HAC_ERANGE;
+        const uint64_t max_col_nnz = max_nnz_per_column(s);
+        const uint32_t Cn = pick_chunk(opts, max_col_nnz);
+        ColumnIndex ci; ci.build(s, Cn);
+        if (ci.n_chunks > 0xfffffff0ull) return HAC_ERANGE;
+        const uint32_t zlen = has_zero ? len[0] : 0, zcode = has_zero ? t.code[0] : 0;
+        uint64_t max_col_bits = 0;
+        for (int64_t j = 0; j < m; ++j) {
+            uint64_t bits = ((uint64_t)n - (s.cb[(size_t)j + 1] - s.cb[(size_t)j])) * zlen;
+            for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) bits += len[s.sym[(size_t)p] + shift];
+            max_col_bits = std::max(max_col_bits, bits);
+        }
+        const uint32_t row_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
+        const uint32_t brel_bits = std::max<uint32_t>(ceil_log2(max_col_bits + 1), 1);
+        const uint32_t ent_bits = row_bits + brel_bits <= 32 ? 32 : 64;
         const uint64_t n_words = (total_bits + 31) / 32;
-        const uint32_t zero_len = (has_zero && t.code[0] == 0) ? len[0] : 0;   // canonical: all-zero word <=> a shortest one
+        const uint32_t zero_len = (has_zero && zcode == 0) ? zlen : 0;   // canonical: all-zero word <=> a shortest one
 
         Layout L;
         hac_desc_t& d = L.d;
         d.magic = kMagic; d.version = kVersion; d.format = HAC_FORMAT_HAC; d.header_bytes = 256;
         d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = nnz; d.total_bits = total_bits; d.n_words = n_words;
         d.k_sym = (uint32_t)codebook.size(); d.lmax = lmax; d.lut_bits = lut_bits;
-        d.has_zero = has_zero; d.zero_len = zero_len; d.chunk = R; d.ri_bits = 0;
-        d.chunks_per_col = (uint32_t)cpc; d.n_chunks = n_chunks;
+        d.has_zero = has_zero; d.zero_len = zero_len; d.chunk = Cn; d.ri_bits = 0;
+        d.ent_bits = ent_bits; d.row_bits = ent_bits == 32 ? row_bits : 0; d.n_chunks = ci.n_chunks;
+        d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
         d.off_codebook = L.place(4ull * d.k_sym);
         d.off_codelen = L.place(d.k_sym);
         d.off_canon = L.place(3 * 33 * 4);
         d.off_symsort = L.place(4ull * d.k_sym);
         d.off_lut = L.place(4ull << lut_bits);
         d.off_stream = L.place(4 * n_words + kTailPad);
-        d.off_chunk_bit = L.place(4 * (n_chunks + 1));
-        d.off_chunk_pos = L.place(4 * (n_chunks + 1));
+        d.off_col_chunk = L.place(4 * ((uint64_t)m + 1));
+        d.off_col_pos = L.place(4 * ((uint64_t)m + 1));
+        d.off_col_bit = L.place(4 * ((uint64_t)m + 1));
+        d.off_chunk_ent = L.place(ci.n_chunks * (ent_bits / 8) + 8);
         d.blob_bytes = align_up(L.cursor);
 
         uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
@@ -320,42 +373,37 @@ extern "C" int hac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         write_tables(base, d, codebook, len, t, lut);
 
         BitWriter bw = { reinterpret_cast<uint32_t*>(base + d.off_stream), 0 };
-        uint32_t* cbit = reinterpret_cast<uint32_t*>(base + d.off_chunk_bit);
-        uint32_t* cpos = reinterpret_cast<uint32_t*>(base + d.off_chunk_pos);
-        const uint32_t zcode = has_zero ? t.code[0] : 0, zlen = has_zero ? len[0] : 0;
+        uint32_t* ent = reinterpret_cast<uint32_t*>(base + d.off_chunk_ent);
         auto put_zeros = [&](uint64_t count) {
             if (!count) return;
             if (zcode == 0) bw.skip(count * zlen);              // zero bits are already there
             else for (uint64_t r = 0; r < count; ++r) bw.put(zcode, zlen);
         };
-        uint64_t chunk = 0, max_col_bits = 0, max_col_nnz = 0;
+        uint64_t chunk = 0;
         for (int64_t j = 0; j < m; ++j) {
             uint64_t row = 0;                                    // next row to be written
-            uint64_t p = s.cb[(size_t)j];
-            const uint64_t pend = s.cb[(size_t)j + 1];
+            const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
+            ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
             const uint64_t col_bit0 = bw.bitpos;
-            max_col_nnz = std::max(max_col_nnz, pend - p);
-            for (uint64_t c = 0; c < cpc; ++c, ++chunk) {
-                const uint64_t rend = std::min<uint64_t>((c + 1) * R, (uint64_t)n);
-                cbit[chunk] = (uint32_t)bw.bitpos;
-                cpos[chunk] = (uint32_t)p;
-                while (p < pend && s.ri[(size_t)p] < rend) {
-                    put_zeros(s.ri[(size_t)p] - row);
-                    const uint32_t sy = s.sym[(size_t)p] + shift;
-                    bw.put(t.code[sy], len[sy]);
-                    row = (uint64_t)s.ri[(size_t)p] + 1;
-                    ++p;
+            for (uint64_t p = p0; p < pend; ++p) {
+                if ((p - p0) % Cn == 0) {                        // a chunk starts before this non-zero's zero run
+                    const uint64_t rel = bw.bitpos - col_bit0;
+                    if (ent_bits == 32) ent[chunk] = (uint32_t)((rel << row_bits) | row);
+                    else { ent[2 * chunk] = (uint32_t)row; ent[2 * chunk + 1] = (uint32_t)rel; }
+                    ++chunk;
                 }
-                put_zeros(rend - row);
-                row = rend;
+                put_zeros(s.ri[(size_t)p] - row);
+                const uint32_t sy = s.sym[(size_t)p] + shift;
+                bw.put(t.code[sy], len[sy]);
+                row = (uint64_t)s.ri[(size_t)p] + 1;
             }
-            max_col_bits = std::max(max_col_bits, bw.bitpos - col_bit0);
+            put_zeros((uint64_t)n - row);
         }
-        cbit[n_chunks] = (uint32_t)bw.bitpos;
-        cpos[n_chunks] = (uint32_t)nnz;
-        reinterpret_cast<hac_desc_t*>(base)->max_col_bits = max_col_bits;
-        reinterpret_cast<hac_desc_t*>(base)->max_col_nnz = max_col_nnz;
-        if (bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
+        ci.col_bit[(size_t)m] = (uint32_t)bw.bitpos;
+        std::memcpy(base + d.off_col_chunk, ci.col_chunk.data(), 4 * ((size_t)m + 1));
+        std::memcpy(base + d.off_col_pos, ci.col_pos.data(), 4 * ((size_t)m + 1));
+        std::memcpy(base + d.off_col_bit, ci.col_bit.data(), 4 * ((size_t)m + 1));
+        if (chunk != ci.n_chunks || bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
         *blob = base; *blob_bytes = (size_t)d.blob_bytes;
         return HAC_OK;
     } catch (const std::bad_alloc&) {
@@ -372,7 +420,7 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
     int rc = check_args(W, n, m, ldw, blob, blob_bytes);
     if (rc) return rc;
     *blob = nullptr; *blob_bytes = 0;
-    if (opts && (opts->lut_bits > 12 || opts->chunk_nnz > 65536)) return HAC_EINVAL;
+    if ((rc = check_opts(opts))) return rc;
     const uint32_t need_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
     uint32_t ri_bits = opts && opts->ri_bits ? opts->ri_bits : need_bits;
     if (ri_bits < need_bits || ri_bits > 32) return HAC_EINVAL;
@@ -391,14 +439,16 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         if (lut_bits < 1 || lut_bits > 12) return HAC_EINVAL;
         std::vector<uint32_t> lut; build_lut(len, t, lut_bits, lut);
 
-        const uint32_t Cn = opts && opts->chunk_nnz ? opts->chunk_nnz : 32;
-        std::vector<uint32_t> col_chunk((size_t)m + 1, 0);
-        uint64_t n_chunks = 0;
+        const uint64_t max_col_nnz = max_nnz_per_column(s);
+        const uint32_t Cn = pick_chunk(opts, max_col_nnz);
+        ColumnIndex ci; ci.build(s, Cn);
+        uint64_t max_col_bits = 0;
         for (int64_t j = 0; j < m; ++j) {
-            col_chunk[(size_t)j] = (uint32_t)n_chunks;
-            n_chunks += (s.cb[(size_t)j + 1] - s.cb[(size_t)j] + Cn - 1) / Cn;
+            uint64_t bits = 0;
+            for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) bits += len[s.sym[(size_t)p]];
+            max_col_bits = std::max(max_col_bits, bits);
         }
-        col_chunk[(size_t)m] = (uint32_t)n_chunks;
+        const uint32_t ent_bits = max_col_bits < 65536 ? 16 : 32;
         const uint64_t n_words = (total_bits + 31) / 32;
         const uint64_t ri_words = (nnz * ri_bits + 31) / 32;
         if (nnz * (uint64_t)ri_bits > 0xfffffff0ull * 32ull) return HAC_ERANGE;
@@ -409,16 +459,18 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = nnz; d.total_bits = total_bits; d.n_words = n_words;
         d.k_sym = (uint32_t)s.values.size(); d.lmax = lmax; d.lut_bits = lut_bits;
         d.has_zero = 0; d.zero_len = 0; d.chunk = Cn; d.ri_bits = ri_bits;
-        d.chunks_per_col = 0; d.n_chunks = n_chunks;
+        d.ent_bits = ent_bits; d.row_bits = 0; d.n_chunks = ci.n_chunks;
+        d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
         d.off_codebook = L.place(4ull * d.k_sym);
         d.off_codelen = L.place(d.k_sym);
         d.off_canon = L.place(3 * 33 * 4);
         d.off_symsort = L.place(4ull * d.k_sym);
         d.off_lut = L.place(4ull << lut_bits);
         d.off_stream = L.place(4 * n_words + kTailPad);
-        d.off_chunk_bit = L.place(4 * (n_chunks + 1));
         d.off_col_chunk = L.place(4 * ((uint64_t)m + 1));
-        d.off_cb = L.place(4 * ((uint64_t)m + 1));
+        d.off_col_pos = L.place(4 * ((uint64_t)m + 1));
+        d.off_col_bit = L.place(4 * ((uint64_t)m + 1));
+        d.off_chunk_ent = L.place(ci.n_chunks * (ent_bits / 8) + 8);
         d.off_ri = L.place(4 * ri_words + kTailPad);
         d.blob_bytes = align_up(L.cursor);
 
@@ -429,29 +481,29 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
 
         BitWriter bw = { reinterpret_cast<uint32_t*>(base + d.off_stream), 0 };
         BitWriter rw = { reinterpret_cast<uint32_t*>(base + d.off_ri), 0 };
-        uint32_t* cbit = reinterpret_cast<uint32_t*>(base + d.off_chunk_bit);
-        uint32_t* cc = reinterpret_cast<uint32_t*>(base + d.off_col_chunk);
-        uint32_t* cb = reinterpret_cast<uint32_t*>(base + d.off_cb);
-        uint64_t chunk = 0, max_col_bits = 0, max_col_nnz = 0;
+        uint16_t* ent16 = reinterpret_cast<uint16_t*>(base + d.off_chunk_ent);
+        uint32_t* ent32 = reinterpret_cast<uint32_t*>(base + d.off_chunk_ent);
+        uint64_t chunk = 0;
         for (int64_t j = 0; j < m; ++j) {
-            cc[j] = col_chunk[(size_t)j];
-            cb[j] = (uint32_t)s.cb[(size_t)j];
+            const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
+            ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
             const uint64_t col_bit0 = bw.bitpos;
-            max_col_nnz = std::max(max_col_nnz, s.cb[(size_t)j + 1] - s.cb[(size_t)j]);
-            for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) {
-                if ((p - s.cb[(size_t)j]) % Cn == 0) cbit[chunk++] = (uint32_t)bw.bitpos;
+            for (uint64_t p = p0; p < pend; ++p) {
+                if ((p - p0) % Cn == 0) {
+                    const uint64_t rel = bw.bitpos - col_bit0;
+                    if (ent_bits == 16) ent16[chunk] = (uint16_t)rel; else ent32[chunk] = (uint32_t)rel;
+                    ++chunk;
+                }
                 const uint32_t sy = s.sym[(size_t)p];
                 bw.put(t.code[sy], len[sy]);
                 rw.put(s.ri[(size_t)p], ri_bits);
             }
-            max_col_bits = std::max(max_col_bits, bw.bitpos - col_bit0);
         }
-        reinterpret_cast<hac_desc_t*>(base)->max_col_bits = max_col_bits;
-        reinterpret_cast<hac_desc_t*>(base)->max_col_nnz = max_col_nnz;
-        cc[m] = col_chunk[(size_t)m];
-        cb[m] = (uint32_t)nnz;
-        cbit[n_chunks] = (uint32_t)bw.bitpos;
-        if (chunk != n_chunks || bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
+        ci.col_bit[(size_t)m] = (uint32_t)bw.bitpos;
+        std::memcpy(base + d.off_col_chunk, ci.col_chunk.data(), 4 * ((size_t)m + 1));
+        std::memcpy(base + d.off_col_pos, ci.col_pos.data(), 4 * ((size_t)m + 1));
+        std::memcpy(base + d.off_col_bit, ci.col_bit.data(), 4 * ((size_t)m + 1));
+        if (chunk != ci.n_chunks || bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
         *blob = base; *blob_bytes = (size_t)d.blob_bytes;
         return HAC_OK;
     } catch (const std::bad_alloc&) {
@@ -488,7 +540,7 @@ int check_header(const void* blob, size_t bytes, hac_desc_t& d)
     if (d.k_sym > d.n * d.m) return HAC_EFORMAT;
     if ((d.k_sym == 0) != (d.total_bits == 0)) return HAC_EFORMAT;
     if (d.k_sym > 0 && (d.lmax < 1)) return HAC_EFORMAT;
-    if (d.chunk < 1 || d.chunk > 65536) return HAC_EFORMAT;
+    if (d.chunk < 1 || d.chunk > 65536 || d.reserved32) return HAC_EFORMAT;
     if (d.max_col_bits > d.total_bits || d.max_col_nnz > d.nnz || d.max_col_nnz > d.n) return HAC_EFORMAT;
     const size_t tot = (size_t)d.blob_bytes;
     if (!section_ok(d, d.off_codebook, 4ull * d.k_sym, tot)) return HAC_EFORMAT;
@@ -497,21 +549,29 @@ int check_header(const void* blob, size_t bytes, hac_desc_t& d)
     if (!section_ok(d, d.off_symsort, 4ull * d.k_sym, tot)) return HAC_EFORMAT;
     if (!section_ok(d, d.off_lut, 4ull << d.lut_bits, tot)) return HAC_EFORMAT;
     if (!section_ok(d, d.off_stream, 4 * d.n_words + kTailPad, tot)) return HAC_EFORMAT;
-    if (!section_ok(d, d.off_chunk_bit, 4 * (d.n_chunks + 1), tot)) return HAC_EFORMAT;
+    if (!section_ok(d, d.off_col_chunk, 4 * (d.m + 1), tot)) return HAC_EFORMAT;
+    if (!section_ok(d, d.off_col_pos, 4 * (d.m + 1), tot)) return HAC_EFORMAT;
+    if (!section_ok(d, d.off_col_bit, 4 * (d.m + 1), tot)) return HAC_EFORMAT;
+    if (d.n_chunks > d.nnz || d.n_chunks > 0xfffffff0ull) return HAC_EFORMAT;
     if (d.format == HAC_FORMAT_HAC) {
-        if (d.chunks_per_col != (d.n + d.chunk - 1) / d.chunk) return HAC_EFORMAT;
-        if (d.n_chunks != (uint64_t)d.chunks_per_col * d.m) return HAC_EFORMAT;
-        if (!section_ok(d, d.off_chunk_pos, 4 * (d.n_chunks + 1), tot)) return HAC_EFORMAT;
+        if (d.ent_bits != 32 && d.ent_bits != 64) return HAC_EFORMAT;
         if (d.has_zero > 1) return HAC_EFORMAT;
         if (d.has_zero != (d.nnz < d.n * d.m ? 1u : 0u)) return HAC_EFORMAT;
+        const uint32_t need = std::max<uint32_t>(ceil_log2(d.n), 1);
+        if (d.ent_bits == 32) {
+            if (d.row_bits != need) return HAC_EFORMAT;
+            if (d.row_bits + std::max<uint32_t>(ceil_log2(d.max_col_bits + 1), 1) > 32) return HAC_EFORMAT;
+        } else if (d.row_bits != 0) return HAC_EFORMAT;
+        if (d.ri_bits) return HAC_EFORMAT;
     } else {
+        if (d.ent_bits != 16 && d.ent_bits != 32) return HAC_EFORMAT;
+        if (d.ent_bits == 16 && d.max_col_bits >= 65536) return HAC_EFORMAT;
         const uint32_t need = std::max<uint32_t>(ceil_log2(d.n), 1);
         if (d.ri_bits < need || d.ri_bits > 32) return HAC_EFORMAT;
-        if (d.has_zero || d.zero_len) return HAC_EFORMAT;
-        if (!section_ok(d, d.off_col_chunk, 4 * (d.m + 1), tot)) return HAC_EFORMAT;
-        if (!section_ok(d, d.off_cb, 4 * (d.m + 1), tot)) return HAC_EFORMAT;
+        if (d.has_zero || d.zero_len || d.row_bits) return HAC_EFORMAT;
         if (!section_ok(d, d.off_ri, 4 * ((d.nnz * d.ri_bits + 31) / 32) + kTailPad, tot)) return HAC_EFORMAT;
     }
+    if (!section_ok(d, d.off_chunk_ent, d.n_chunks * (d.ent_bits / 8) + 8, tot)) return HAC_EFORMAT;
     return HAC_OK;
 }
 
@@ -519,8 +579,22 @@ struct View {
     hac_desc_t d;
     const uint8_t* base;
     const float* codebook; const uint8_t* codelen; const uint32_t* canon; const uint32_t* symsort;
-    const uint32_t* lut; const uint32_t* stream; const uint32_t* cbit; const uint32_t* cpos;
-    const uint32_t* colchunk; const uint32_t* cb; const uint32_t* ri;
+    const uint32_t* lut; const uint32_t* stream;
+    const uint32_t* colchunk; const uint32_t* colpos; const uint32_t* colbit;
+    const uint8_t* ent; const uint32_t* ri;
+
+    // (relative bit offset, first row) of chunk g
+    void entry(uint64_t g, uint64_t& rel, uint64_t& row) const {
+        row = 0;
+        if (d.format == HAC_FORMAT_HAC) {
+            const uint32_t* e = reinterpret_cast<const uint32_t*>(ent);
+            if (d.ent_bits == 32) { rel = e[g] >> d.row_bits; row = e[g] & ((1u << d.row_bits) - 1u); }
+            else { row = e[2 * g]; rel = e[2 * g + 1]; }
+        } else {
+            rel = d.ent_bits == 16 ? reinterpret_cast<const uint16_t*>(ent)[g]
+                                   : reinterpret_cast<const uint32_t*>(ent)[g];
+        }
+    }
 };
 
 void make_view(const void* blob, const hac_desc_t& d, View& v)
@@ -532,10 +606,10 @@ void make_view(const void* blob, const hac_desc_t& d, View& v)
     v.symsort = reinterpret_cast<const uint32_t*>(v.base + d.off_symsort);
     v.lut = reinterpret_cast<const uint32_t*>(v.base + d.off_lut);
     v.stream = reinterpret_cast<const uint32_t*>(v.base + d.off_stream);
-    v.cbit = reinterpret_cast<const uint32_t*>(v.base + d.off_chunk_bit);
-    v.cpos = d.format == HAC_FORMAT_HAC ? reinterpret_cast<const uint32_t*>(v.base + d.off_chunk_pos) : nullptr;
-    v.colchunk = d.format == HAC_FORMAT_SHAC ? reinterpret_cast<const uint32_t*>(v.base + d.off_col_chunk) : nullptr;
-    v.cb = d.format == HAC_FORMAT_SHAC ? reinterpret_cast<const uint32_t*>(v.base + d.off_cb) : nullptr;
+    v.colchunk = reinterpret_cast<const uint32_t*>(v.base + d.off_col_chunk);
+    v.colpos = reinterpret_cast<const uint32_t*>(v.base + d.off_col_pos);
+    v.colbit = reinterpret_cast<const uint32_t*>(v.base + d.off_col_bit);
+    v.ent = v.base + d.off_chunk_ent;
     v.ri = d.format == HAC_FORMAT_SHAC ? reinterpret_cast<const uint32_t*>(v.base + d.off_ri) : nullptr;
 }
 
@@ -617,26 +691,30 @@ inline uint32_t ri_field(const uint32_t* ri, uint64_t p, uint32_t bits)
 int check_index_shallow(const View& v)
 {
     const hac_desc_t& d = v.d;
-    if (v.cbit[d.n_chunks] != d.total_bits) return HAC_EFORMAT;
-    for (uint64_t c = 0; c < d.n_chunks; ++c) if (v.cbit[c] > v.cbit[c + 1]) return HAC_EFORMAT;
-    if (d.n_chunks && v.cbit[0] != 0) return HAC_EFORMAT;
-    if (d.format == HAC_FORMAT_HAC) {
-        if (v.cpos[d.n_chunks] != d.nnz) return HAC_EFORMAT;
-        for (uint64_t c = 0; c < d.n_chunks; ++c) {
-            if (v.cpos[c] > v.cpos[c + 1]) return HAC_EFORMAT;
-            if (v.cpos[c + 1] - v.cpos[c] > d.chunk) return HAC_EFORMAT;
-        }
-        if (v.cpos[0] != 0) return HAC_EFORMAT;
-    } else {
-        if (v.cb[0] != 0 || v.cb[d.m] != d.nnz) return HAC_EFORMAT;
-        if (v.colchunk[0] != 0 || v.colchunk[d.m] != d.n_chunks) return HAC_EFORMAT;
-        for (uint64_t j = 0; j < d.m; ++j) {
-            if (v.cb[j] > v.cb[j + 1]) return HAC_EFORMAT;
-            const uint64_t cnt = v.cb[j + 1] - v.cb[j];
-            if (cnt > d.n) return HAC_EFORMAT;
-            if ((uint64_t)v.colchunk[j + 1] - v.colchunk[j] != (cnt + d.chunk - 1) / d.chunk) return HAC_EFORMAT;
+    if (v.colpos[0] != 0 || v.colpos[d.m] != d.nnz) return HAC_EFORMAT;
+    if (v.colchunk[0] != 0 || v.colchunk[d.m] != d.n_chunks) return HAC_EFORMAT;
+    if (v.colbit[0] != 0 || v.colbit[d.m] != d.total_bits) return HAC_EFORMAT;
+    uint64_t max_nnz = 0, max_bits = 0;
+    for (uint64_t j = 0; j < d.m; ++j) {
+        if (v.colpos[j] > v.colpos[j + 1] || v.colbit[j] > v.colbit[j + 1]) return HAC_EFORMAT;
+        const uint64_t cnt = v.colpos[j + 1] - v.colpos[j];
+        if (cnt > d.n) return HAC_EFORMAT;
+        if ((uint64_t)v.colchunk[j + 1] - v.colchunk[j] != (cnt + d.chunk - 1) / d.chunk) return HAC_EFORMAT;
+        max_nnz = std::max(max_nnz, cnt);
+        const uint64_t bits = v.colbit[j + 1] - v.colbit[j];
+        max_bits = std::max<uint64_t>(max_bits, bits);
+        // every chunk entry points inside its column, in ascending order
+        uint64_t prev_rel = 0, prev_row = 0;
+        for (uint64_t g = v.colchunk[j]; g < v.colchunk[j + 1]; ++g) {
+            uint64_t rel, row;
+            v.entry(g, rel, row);
+            if (rel >= bits || row >= d.n) return HAC_EFORMAT;
+            if (g == v.colchunk[j] ? (rel != 0 || row != 0) : (rel <= prev_rel || (d.format == HAC_FORMAT_HAC && row <= prev_row)))
+                return HAC_EFORMAT;
+            prev_rel = rel; prev_row = row;
         }
     }
+    if (max_nnz != d.max_col_nnz || max_bits != d.max_col_bits) return HAC_EFORMAT;
     return HAC_OK;
 }
 
@@ -645,26 +723,41 @@ int check_deep(const View& v)
     const hac_desc_t& d = v.d;
     SeqDecoder dec(v);
     if (d.format == HAC_FORMAT_HAC) {
-        uint64_t chunk = 0, pos = 0;
-        for (uint64_t j = 0; j < d.m; ++j)
+        uint64_t pos = 0;
+        for (uint64_t j = 0; j < d.m; ++j) {
+            if (v.colbit[j] != dec.bitpos || v.colpos[j] != pos) return HAC_EFORMAT;
+            uint64_t g = v.colchunk[j];
+            uint64_t last_bit = dec.bitpos, last_row = 0;     // where the next chunk would start
             for (uint64_t i = 0; i < d.n; ++i) {
-                if (i % d.chunk == 0) {
-                    if (v.cbit[chunk] != dec.bitpos || v.cpos[chunk] != pos) return HAC_EFORMAT;
-                    ++chunk;
-                }
+                const uint64_t before = dec.bitpos;
+                (void)before;
                 const int64_t s = dec.next();
                 if (s < 0) return HAC_EFORMAT;
-                if (!(d.has_zero && s == 0)) ++pos;
+                if (d.has_zero && s == 0) continue;
+                if ((pos - v.colpos[j]) % d.chunk == 0) {     // first non-zero of a chunk
+                    uint64_t rel, row;
+                    if (g >= v.colchunk[j + 1]) return HAC_EFORMAT;
+                    v.entry(g, rel, row);
+                    if (rel != last_bit - v.colbit[j] || row != last_row) return HAC_EFORMAT;
+                    ++g;
+                }
+                ++pos;
+                last_bit = dec.bitpos; last_row = i + 1;
             }
+            if (g != v.colchunk[j + 1]) return HAC_EFORMAT;
+        }
         if (pos != d.nnz || dec.bitpos != d.total_bits) return HAC_EFORMAT;
     } else {
-        uint64_t chunk = 0;
         for (uint64_t j = 0; j < d.m; ++j) {
+            if (v.colbit[j] != dec.bitpos) return HAC_EFORMAT;
+            uint64_t g = v.colchunk[j];
             int64_t prev = -1;
-            for (uint64_t p = v.cb[j]; p < v.cb[j + 1]; ++p) {
-                if ((p - v.cb[j]) % d.chunk == 0) {
-                    if (v.cbit[chunk] != dec.bitpos) return HAC_EFORMAT;
-                    ++chunk;
+            for (uint64_t p = v.colpos[j]; p < v.colpos[j + 1]; ++p) {
+                if ((p - v.colpos[j]) % d.chunk == 0) {
+                    uint64_t rel, row;
+                    v.entry(g, rel, row);
+                    if (rel != dec.bitpos - v.colbit[j]) return HAC_EFORMAT;
+                    ++g;
                 }
                 if (dec.next() < 0) return HAC_EFORMAT;
                 const uint32_t r = ri_field(v.ri, p, d.ri_bits);
@@ -717,12 +810,13 @@ extern "C" int hac_stats(const void* blob, size_t bytes, hac_stats_t* out)
     out->blob_bytes = d.blob_bytes;
     const double nm = (double)d.n * (double)d.m;
     const double k = (double)std::max<uint32_t>(d.k_sym, 1);
+    const uint64_t ent_bytes = d.n_chunks * (d.ent_bits / 8);
     if (d.format == HAC_FORMAT_HAC) {
-        out->index_bytes = 8 * (d.n_chunks + 1);
+        out->index_bytes = 3 * 4 * (d.m + 1) + ent_bytes;
         out->paper_bits = 32 * d.n_words + 6ull * 32 * d.k_sym;
         out->bound_bits = nm * (1.0 + std::log2(k)) + 6.0 * k * 32.0;
     } else {
-        out->index_bytes = 4 * (d.n_chunks + 1) + 4 * (d.m + 1);
+        out->index_bytes = 2 * 4 * (d.m + 1) + ent_bytes;
         out->ri_bytes = 4 * ((d.nnz * d.ri_bits + 31) / 32);
         out->cb_bytes = 4 * (d.m + 1);
         out->paper_bits = 32 * d.n_words + 6ull * 32 * d.k_sym + 32 * (d.nnz + d.m + 1);
@@ -768,7 +862,7 @@ extern "C" int hac_decode_host(const void* blob, size_t bytes, float* W_out, int
     } else {
         if (W_out) std::memset(W_out, 0, sizeof(float) * (size_t)(d.n * d.m));
         for (uint64_t j = 0; j < d.m; ++j)
-            for (uint64_t p = v.cb[j]; p < v.cb[j + 1]; ++p) {
+            for (uint64_t p = v.colpos[j]; p < v.colpos[j + 1]; ++p) {
                 const int64_t s = dec.next();
                 if (s < 0) return HAC_EFORMAT;
                 const uint32_t r = ri_field(v.ri, p, d.ri_bits);

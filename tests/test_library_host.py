@@ -36,7 +36,7 @@ def test_header_struct_matches_binding():
     body = text[:text.index("} hac_desc_t;")]
     body = body[body.rindex("typedef struct {") + len("typedef struct {"):]
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
-    fields = re.findall(r"\b([a-z_]+)(?:\[\d+\])?\s*[;,]", body)
+    fields = re.findall(r"\b([a-z_][a-z_0-9]*)(?:\[\d+\])?\s*[;,]", body)
     assert fields == [f[0] for f in hac.Desc._fields_]
 
 
@@ -53,6 +53,21 @@ def codes_from_blob(blob):
             assert lens[s] == l
             words[format(int(canon[l]) + r, "b").zfill(l)] = s
     return lens, words
+
+
+def chunk_entries(blob):
+    """[(relative bit offset, first row)] per chunk, unpacked from the blob."""
+    d = blob.desc
+    nch = int(d.n_chunks)
+    if d.format == hac.HAC_FORMAT_HAC:
+        if d.ent_bits == 32:
+            e = blob.section("off_chunk_ent", np.uint32, nch)
+            rb = int(d.row_bits)
+            return [(int(v) >> rb, int(v) & ((1 << rb) - 1)) for v in e]
+        e = blob.section("off_chunk_ent", np.uint32, 2 * nch).reshape(-1, 2)
+        return [(int(r[1]), int(r[0])) for r in e]
+    dt = np.uint16 if d.ent_bits == 16 else np.uint32
+    return [(int(v), 0) for v in blob.section("off_chunk_ent", dt, nch)]
 
 
 def oracle_decode_bits(stream_words, count, words):
@@ -87,7 +102,7 @@ IDS = [n for n, _ in LAYERS]
 @pytest.mark.parametrize("name,W", LAYERS, ids=IDS)
 def test_hac_blob_against_oracle(name, W):
     n, m = W.shape
-    blob = hac.hac_encode(W, chunk_rows=64)
+    blob = hac.hac_encode(W, chunk_nnz=3)
     assert blob.validate(deep=True) == 0
     d = blob.desc
     values, sym = formats.hac_symbols(W)
@@ -107,15 +122,30 @@ def test_hac_blob_against_oracle(name, W):
     pad = int(d.n_words) * 32 - int(d.total_bits)
     if pad:
         assert int(stream[-1]) & ((1 << pad) - 1) == 0
-    # chunk index: bit offsets equal the running sum of code lengths at every chunk start
-    R = int(d.chunk)
-    cpc = int(d.chunks_per_col)
-    assert cpc == -(-n // R)
+    # index: per column its first bit / first non-zero / first chunk; per chunk of C non-zeros the
+    # bit right after the previous non-zero's codeword (column start for the first) and the row there
+    C = int(d.chunk)
     cum = np.concatenate(([0], np.cumsum(lens[sym])))
-    nzcum = np.concatenate(([0], np.cumsum(values[sym] != 0)))
-    starts = np.array([j * n + c * R for j in range(m) for c in range(cpc)] + [n * m])
-    assert np.array_equal(blob.section("off_chunk_bit", np.uint32, cpc * m + 1), cum[starts])
-    assert np.array_equal(blob.section("off_chunk_pos", np.uint32, cpc * m + 1), nzcum[starts])
+    isnz = values[sym] != 0
+    nzcum = np.concatenate(([0], np.cumsum(isnz)))
+    col_start = np.arange(m + 1) * n
+    col_bit = blob.section("off_col_bit", np.uint32, m + 1)
+    col_pos = blob.section("off_col_pos", np.uint32, m + 1)
+    col_chunk = blob.section("off_col_chunk", np.uint32, m + 1)
+    assert np.array_equal(col_bit, cum[col_start])
+    assert np.array_equal(col_pos, nzcum[col_start])
+    counts = np.diff(nzcum[col_start])
+    assert np.array_equal(np.diff(col_chunk), -(-counts // C))
+    assert int(d.max_col_nnz) == counts.max() and int(d.max_col_bits) == np.diff(cum[col_start]).max()
+    ents = chunk_entries(blob)
+    g = 0
+    for j in range(m):
+        nzidx = np.flatnonzero(isnz[j * n:(j + 1) * n])
+        for k in range(0, len(nzidx), C):
+            start = 0 if k == 0 else nzidx[k - 1] + 1            # first symbol decoded by this chunk
+            assert ents[g] == (cum[j * n + start] - cum[j * n], start), (j, k)
+            g += 1
+    assert g == int(d.n_chunks)
 
 
 @pytest.mark.parametrize("name,W", LAYERS, ids=IDS)
@@ -131,7 +161,18 @@ def test_shac_blob_against_oracle(name, W):
     Wd, symd, rowd, cold = blob.decode_host()
     assert np.array_equal(Wd.view(np.uint32), W.view(np.uint32))
     assert np.array_equal(symd, sym) and np.array_equal(rowd, row) and np.array_equal(cold, col)
-    assert np.array_equal(blob.section("off_cb", np.uint32, m + 1), os_.cb)
+    assert np.array_equal(blob.section("off_col_pos", np.uint32, m + 1), os_.cb)       # the paper's cb
+    lens_s = blob.section("off_codelen", np.uint8, len(values)).astype(int)
+    cum = np.concatenate(([0], np.cumsum(lens_s[sym]))) if os_.q else np.zeros(1, dtype=int)
+    col_bit = blob.section("off_col_bit", np.uint32, m + 1)
+    assert np.array_equal(col_bit, cum[os_.cb])
+    ents = chunk_entries(blob)
+    g = 0
+    for j in range(m):
+        for p in range(int(os_.cb[j]), int(os_.cb[j + 1]), int(d.chunk)):
+            assert ents[g] == (cum[p] - cum[os_.cb[j]], 0)
+            g += 1
+    assert g == int(d.n_chunks)
     assert int(d.ri_bits) == max(1, math.ceil(math.log2(n))) if n > 1 else int(d.ri_bits) == 1
     if os_.q:
         lens, words = codes_from_blob(blob)
@@ -145,7 +186,7 @@ def test_ri_bits_32_and_small_tables_still_round_trip():
         blob = hac.shac_encode(W, **kw)
         assert blob.validate(deep=True) == 0
         assert np.array_equal(blob.decode_host()[0], W)
-    for kw in (dict(lut_bits=1), dict(lut_bits=12), dict(chunk_rows=1), dict(chunk_rows=65536)):
+    for kw in (dict(lut_bits=1), dict(lut_bits=12), dict(chunk_nnz=1), dict(chunk_nnz=65536)):
         blob = hac.hac_encode(W, **kw)
         assert blob.validate(deep=True) == 0
         assert np.array_equal(blob.decode_host()[0], W)
@@ -246,16 +287,17 @@ def test_damaged_blobs_are_rejected(enc):
         return f
 
     assert damaged(poke32(0, 0xdeadbeef)) == -3                              # magic
-    assert damaged(poke32(int(d.off_chunk_bit) + 4, 0x7fffffff)) == -3       # index past the end
+    assert damaged(poke32(int(d.off_col_bit) + 4, 0x7fffffff)) == -3         # column start past the end
+    assert damaged(poke32(int(d.off_chunk_ent), 0x00010001)) == -3           # first chunk not at its column's start
     assert damaged(poke32(int(d.off_codelen), 0x01010101)) == -3             # lengths no longer a complete code
     assert damaged(poke32(int(d.off_lut), 0xffffffff)) == -3                 # first-level table
     off_field = hac.Desc.off_stream.offset
     assert damaged(poke32(off_field, int(d.blob_bytes))) == -3               # section outside the blob
     if d.format == hac.HAC_FORMAT_SHAC:
-        assert damaged(poke32(int(d.off_cb) + 4, int(d.nnz) + 5)) == -3      # cb not monotone
+        assert damaged(poke32(int(d.off_col_pos) + 4, int(d.nnz) + 5)) == -3 # cb not monotone
         assert damaged(poke32(int(d.off_ri), 0xffffffff)) == -3              # row index >= n
     else:
-        assert damaged(poke32(int(d.off_chunk_pos) + 8, 0)) == -3
+        assert damaged(poke32(int(d.off_col_pos) + 8, 0)) == -3
     # flipping stream bits either still decodes to *a* matrix (deep check passes or fails) but never crashes
     b = good.copy()
     b[int(d.off_stream):int(d.off_stream) + 8] ^= 0xff
