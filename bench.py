@@ -53,7 +53,9 @@ def parse_args():
     ap.add_argument("--hot", action="store_true", help="no rotation: same buffers every step (cache-resident)")
     ap.add_argument("--chunk-nnz", type=int, default=0)
     ap.add_argument("--only", type=str, default="", help="restrict the step to 'hac' or 'shac'")
-    ap.add_argument("--detail", action="store_true", help="also time every (format, B) call on its own")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a 256 MiB device-to-device copy 4 times before the timed region "
+                         "(a kernel of known traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -115,6 +117,22 @@ def time_region(torch, body, iters, warmup, use_graph, rot):
     t1.record(stream)
     torch.cuda.synchronize()
     return t0.elapsed_time(t1) / iters
+
+
+def measured_traffic(cfg_id, fmt, B):
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by the copy calibration) from the
+    committed rocprofv3 counter summary, or None when that summary has no line for this kernel."""
+    path = os.path.join(ROOT, "profiles", f"pmc_hbm_traffic_cfg{cfg_id}.md")
+    key = f"| {fmt}_dot | {B} |"
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if line.startswith(key):
+                    cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                    return int(float(cells[-1]))
+    except OSError:
+        return None
+    return None
 
 
 def cpu_baseline(W, Xs, cores):
@@ -182,6 +200,14 @@ def main():
     torch.cuda.synchronize()
     torch.cuda.set_stream(work_stream)
 
+    if args.calibration_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     def step(i):
         for c in calls:
             c.run(i)
@@ -209,12 +235,14 @@ def main():
             "true_gflops": round(2.0 * c.B * int(c.desc.nnz) / ms / 1e6, 1),
         })
     dom = max(detail, key=lambda d: d["kernel_ms"])
-    kname = ("dot_b1_kernel" if dom["B"] == 1 else "dot_batch_kernel") + ("<sHAC>" if dom["format"] == "shac" else "<HAC>")
+    nb = min(4, 1 << max(0, (min(dom["B"], 256) - 1).bit_length()))
+    kname = f"dot_batch_kernel<{'true' if dom['format'] == 'shac' else 'false'}, {nb}, {'true' if dom['B'] > 32 else 'false'}>"
+    traffic = measured_traffic(cfg.cfg, dom["format"], dom["B"])
     roofline = {
-        "bound": "hbm", "kernel": f"{kname} B={dom['B']}",
+        "bound": "hbm", "kernel": f"{kname} ({dom['format']}_dot, B={dom['B']})",
         "achieved": round(dom["bytes"] / dom["kernel_ms"] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(dom["bytes"] / dom["kernel_ms"] / 1e6 / HBM_PEAK_GBS, 4),
-        "traffic": None,
+        "traffic": traffic,
         "launch_ms": dom["kernel_ms"], "algorithmic_bytes": dom["bytes"],
     }
 

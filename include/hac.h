@@ -148,7 +148,11 @@ typedef struct {
     uint32_t reserved[5];     /* [0]: entries of the per-wavefront non-zero list, 64..4096;
                                  [1]: words of the per-wavefront staging buffer for stream
                                  (and ri) words, 16..16384, multiple of 4;
-                                 0 = sized from the blob header; the others must be 0      */
+                                 0 = sized from the blob header;
+                                 [2]: batch columns one pass over the non-zero list
+                                 covers, 32 / 64 / 128 / 256 [32];
+                                 [3]: 1 = do not hold a block's wavefronts on the same pass
+                                 (measurement aid); [4] must be 0                          */
 } hac_launch_t;
 
 /* The workspace already holds the feature-major copy of this very X (same B,

@@ -317,11 +317,13 @@ decode_kernel(DevBlob d, float* vals, int32_t* sym, int32_t* row_out, int32_t* c
 }
 
 // ---------------------------------------------------------------------------
-// X (B x n, row-major) -> XT (n x Bp, feature-major), zero padded for b >= B
+// X (B x n, row-major) -> XT, feature-major in panels of `wp` batch columns:
+// XT[(b / wp) * n * wp + r * wp + b % wp] = X[b][r], zero for B <= b < Bp.
+// One pass of the batch kernel reads one panel: rows of wp floats, contiguous.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 transpose_pad_kernel(const float* __restrict__ X, uint32_t B, uint32_t n, uint64_t ldx,
-                     float* __restrict__ XT, uint32_t Bp)
+                     float* __restrict__ XT, uint32_t Bp, uint32_t wp)
 {
     __shared__ float tile[32][33];
     const uint32_t tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
@@ -333,7 +335,7 @@ transpose_pad_kernel(const float* __restrict__ X, uint32_t B, uint32_t n, uint64
     __syncthreads();
     for (uint32_t k = 0; k < 32; k += 8) {
         const uint32_t r = r0 + ty + k, b = b0 + tx;
-        if (r < n && b < Bp) XT[(uint64_t)r * Bp + b] = tile[tx][ty + k];
+        if (r < n && b < Bp) XT[(uint64_t)(b / wp) * n * wp + (uint64_t)r * wp + (b % wp)] = tile[tx][ty + k];
     }
 }
 
@@ -354,40 +356,15 @@ __device__ __forceinline__ void wave_sync()
 
 // FMA phase building blocks.  A lane group takes every ng-th list entry; the
 // loads of kPipe entries are issued together before the first multiply, so that
-// many row fetches are in flight per wave.  UNI: one group spans the wave, an
-// entry is wave-uniform and travels in scalar registers.
+// many row fetches are in flight per wave.
 template <int NB, int kPipe>
 struct EntryGroup {
     uint2 e[kPipe];
     float x[kPipe][NB];
 };
 
-template <int NB, bool UNI, int kPipe>
-__device__ __forceinline__ void group_load(EntryGroup<NB, kPipe>& G, const uint2* list, uint32_t idx, uint32_t ng,
-                                           const float* xt, uint32_t Bp)
-{
-#pragma unroll
-    for (int k = 0; k < kPipe; ++k) {
-        G.e[k] = list[idx + k * ng];
-        if (UNI) { G.e[k].x = __builtin_amdgcn_readfirstlane(G.e[k].x); G.e[k].y = __builtin_amdgcn_readfirstlane(G.e[k].y); }
-    }
-#pragma unroll
-    for (int k = 0; k < kPipe; ++k) VecLoad<NB>::ld(xt + (uint64_t)G.e[k].x * Bp, G.x[k]);
-}
-
-template <int NB, int kPipe>
-__device__ __forceinline__ void group_fma(const EntryGroup<NB, kPipe>& G, float (&acc)[NB])
-{
-#pragma unroll
-    for (int k = 0; k < kPipe; ++k) {
-        const float wv = __uint_as_float(G.e[k].y);
-#pragma unroll
-        for (int i = 0; i < NB; ++i) acc[i] = fmaf(G.x[k][i], wv, acc[i]);
-    }
-}
-
 // Accumulate list entries with CSC positions [lo, hi) (list index = position - winbase).
-template <int NB, bool UNI, int kPipe>
+template <int NB, int kPipe>
 __device__ __forceinline__ void fma_entries(const uint2* list, uint32_t winbase, uint32_t lo, uint32_t hi,
                                             uint32_t ng, uint32_t grp, const float* xt, uint32_t Bp,
                                             float (&acc)[NB])
@@ -399,18 +376,23 @@ __device__ __forceinline__ void fma_entries(const uint2* list, uint32_t winbase,
     const uint32_t step = kPipe * ng;
     for (uint32_t i = 0; i < full; ++i, idx += step) {
         EntryGroup<NB, kPipe> G;
-        group_load<NB, UNI, kPipe>(G, list, idx, ng, xt, Bp);
-        group_fma<NB, kPipe>(G, acc);
+#pragma unroll
+        for (int k = 0; k < kPipe; ++k) G.e[k] = list[idx + k * ng];
+#pragma unroll
+        for (int k = 0; k < kPipe; ++k) VecLoad<NB>::ld(xt + (uint64_t)G.e[k].x * Bp, G.x[k]);
+#pragma unroll
+        for (int k = 0; k < kPipe; ++k) {
+            const float wv = __uint_as_float(G.e[k].y);
+#pragma unroll
+            for (int i2 = 0; i2 < NB; ++i2) acc[i2] = fmaf(G.x[k][i2], wv, acc[i2]);
+        }
     }
     // last, partial group: entries past the end read entry `idx` again and are not added
     const uint32_t rest = count - full * kPipe;
     if (rest) {
         EntryGroup<NB, kPipe> G;
 #pragma unroll
-        for (int k = 0; k < kPipe; ++k) {
-            G.e[k] = list[idx + ((uint32_t)k < rest ? k * ng : 0u)];
-            if (UNI) { G.e[k].x = __builtin_amdgcn_readfirstlane(G.e[k].x); G.e[k].y = __builtin_amdgcn_readfirstlane(G.e[k].y); }
-        }
+        for (int k = 0; k < kPipe; ++k) G.e[k] = list[idx + ((uint32_t)k < rest ? k * ng : 0u)];
 #pragma unroll
         for (int k = 0; k < kPipe; ++k) VecLoad<NB>::ld(xt + (uint64_t)G.e[k].x * Bp, G.x[k]);
 #pragma unroll
@@ -418,14 +400,14 @@ __device__ __forceinline__ void fma_entries(const uint2* list, uint32_t winbase,
             if ((uint32_t)k < rest) {
                 const float wv = __uint_as_float(G.e[k].y);
 #pragma unroll
-                for (int i = 0; i < NB; ++i) acc[i] = fmaf(G.x[k][i], wv, acc[i]);
+                for (int i2 = 0; i2 < NB; ++i2) acc[i2] = fmaf(G.x[k][i2], wv, acc[i2]);
             }
         }
     }
 }
 
-template <int NB, bool UNI> struct BatchTraits {
-    static constexpr int kPipe = NB == 4 ? 10 : 16;                  // row fetches in flight per lane group
+template <int NB> struct BatchTraits {
+    static constexpr int kPipe = NB == 4 ? 10 : 16;                 // row fetches in flight per lane group
     static constexpr int kMaxThreads = 1024;
 };
 
@@ -437,13 +419,20 @@ __device__ __forceinline__ void stage_words(uint32_t* dst, const uint32_t* src, 
     for (uint32_t i = lane; i * 4 < nw; i += kWave) d4[i] = s4[i];
 }
 
-// gw: lanes per group (power of two, gw * NB = batch columns handled per pass);
-// 64 / gw groups walk the list interleaved and are added together at a column's end.
-template <bool SHAC, int NB, bool UNI>
-__global__ void __launch_bounds__((BatchTraits<NB, UNI>::kMaxThreads))
+// gw: lanes per group (power of two); a pass over the list covers gw * NB batch
+// columns, and npass passes cover this block's share of the batch.  Passes keep
+// the part of the feature-major X that a pass touches small enough to stay in
+// L2 while all wavefronts of an XCD gather from it.  64 / gw groups walk the
+// list interleaved and are added together at a column's end.  part_words: LDS
+// words per wave for partial sums of a column that does not fit one list window
+// (npass * 64 * NB, or 0 when the launch guarantees that no column is split).
+// MP: several passes (npass > 1); the single-pass variant has no pass loop and no barrier.
+template <bool SHAC, int NB, bool MP>
+__global__ void __launch_bounds__((BatchTraits<NB>::kMaxThreads))
 dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t B,
-                 float* __restrict__ Y, uint64_t ldy, uint32_t cpw, uint32_t gw,
-                 uint32_t list_cap, uint32_t sbuf_words, uint32_t nblocks)
+                 float* __restrict__ Y, uint64_t ldy, uint32_t cpw, uint32_t gw, uint32_t npass,
+                 uint32_t list_cap, uint32_t sbuf_words, uint32_t part_words, uint32_t nblocks,
+                 uint32_t sync_passes)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -467,7 +456,11 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
     }
     const Tables tb = load_tables(d, smem);
     __syncthreads();
-    if (!live) return;
+    if (!live) {
+        // sync_passes: every wave of the block meets at a barrier once per pass (see accumulate)
+        if (MP && sync_passes) for (uint32_t p = 0; p < npass; ++p) __syncthreads();
+        return;
+    }
     HAC_MARK(1);
     const uint32_t c1 = c0 + ncols;
     const uint32_t gfirst = (uint32_t)__shfl((int)cchunk_l, 0, kWave);
@@ -477,8 +470,9 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
     const uint32_t bit_lo = (uint32_t)__shfl((int)cbit_l, 0, kWave);
     const uint32_t bit_hi = (uint32_t)__shfl((int)cbit_l, (int)ncols, kWave);
 
-    uint32_t* sbuf = smem + table_words_dev(d) + (uint64_t)wib * (sbuf_words + 2 * list_cap);   // staged words
+    uint32_t* sbuf = smem + table_words_dev(d) + (uint64_t)wib * (sbuf_words + 2 * list_cap + part_words);   // staged words
     uint2* list = reinterpret_cast<uint2*>(sbuf + sbuf_words);                                  // (row, value)
+    float* part = reinterpret_cast<float*>(sbuf + sbuf_words + 2 * list_cap);                   // [pass][NB][lane]
 
     // ---- stage this wave's stream words (and ri words) in LDS ----
     const uint32_t swlo = (bit_lo >> 5) & ~3u;
@@ -503,23 +497,39 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
 
     const uint32_t ng = kWave / gw;
     const uint32_t grp = lane / gw, lig = lane % gw;
-    const uint32_t boff = blockIdx.y * 256u + lig * NB;      // first batch column of this lane
-    const float* xt = XT + boff;
-
-    float acc[NB];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) acc[i] = 0.0f;
+    const uint32_t pass_w = gw * NB;                          // batch columns per pass = width of one panel of XT
+    const uint64_t panel = (uint64_t)d.n * pass_w;            // floats per panel
+    const uint32_t boff = blockIdx.y * (pass_w * npass) + lig * NB;   // first batch column of this lane, pass 0
+    const float* xt = XT + (uint64_t)blockIdx.y * npass * panel + lig * NB;
     uint32_t cc = c0;                                        // column being accumulated (wave-uniform)
     uint32_t t = posbase;                                    // next CSC position to consume
 
-    auto flush = [&]() {
+    // Consume list entries [t, hi) of column cc in every pass.  `carried`: earlier windows already
+    // hold partial sums of this column in `part`; `last`: the column ends here, so the sums are
+    // reduced over the lane groups and stored, else they are parked in `part`.
+    auto accumulate = [&](uint32_t winbase, uint32_t hi, bool carried, bool last) {
+        const uint32_t passes = MP ? npass : 1u;
+        for (uint32_t p = 0; p < passes; ++p) {
+            // Keeping the block's waves on the same pass keeps the panels of XT they gather from few
+            // enough to stay in L2.  Only set when every wave calls this exactly once (one column per
+            // wave, no column split over windows).
+            if (MP && sync_passes) __syncthreads();
+            float a[NB];
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            float v = acc[i];
-            for (uint32_t off = 32; off >= gw; off >>= 1) v += __shfl_xor(v, (int)off, kWave);
-            const uint32_t b = boff + i;
-            if (grp == 0 && b < B) Y[(uint64_t)b * ldy + cc] = v;
-            acc[i] = 0.0f;
+            for (int i = 0; i < NB; ++i) a[i] = (carried && part_words) ? part[(p * NB + i) * kWave + lane] : 0.0f;
+            if (t < hi) fma_entries<NB, BatchTraits<NB>::kPipe>(list, winbase, t, hi, ng, grp, xt + p * panel, pass_w, a);
+            if (last) {
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    float v = a[i];
+                    for (uint32_t off = 32; off >= gw; off >>= 1) v += __shfl_xor(v, (int)off, kWave);
+                    const uint32_t b = boff + p * pass_w + i;
+                    if (grp == 0 && b < B) Y[(uint64_t)b * ldy + cc] = v;
+                }
+            } else if (part_words) {                       // always true here: the host sizes `part` whenever a split can occur
+#pragma unroll
+                for (int i = 0; i < NB; ++i) part[(p * NB + i) * kWave + lane] = a[i];
+            }
         }
     };
 
@@ -574,18 +584,24 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
             HAC_MARK(4);
             // ---- FMA phase: lanes = batch ----
             while (cc < c1) {
+                const uint32_t ps = (uint32_t)__shfl((int)cpos_l, (int)(cc - c0), kWave);
                 const uint32_t pe = (uint32_t)__shfl((int)cpos_l, (int)(cc - c0 + 1), kWave);
                 const uint32_t hi = pe < winend ? pe : winend;
-                if (t < hi) fma_entries<NB, UNI, BatchTraits<NB, UNI>::kPipe>(list, winbase, t, hi, ng, grp, xt, Bp, acc);
+                const bool last = pe <= winend;
+                if (last || t < hi) accumulate(winbase, hi, t > ps, last);
                 t = hi > t ? hi : t;
-                if (pe <= winend) { flush(); ++cc; }
+                if (last) ++cc;
                 else break;                                  // column continues in the next window
             }
             wave_sync();
             HAC_MARK(5);
         }
     }
-    while (cc < c1) { flush(); ++cc; }                       // trailing columns without non-zeros
+    while (cc < c1) {                                        // trailing columns without non-zeros
+        const uint32_t ps = (uint32_t)__shfl((int)cpos_l, (int)(cc - c0), kWave);
+        accumulate(t, t, t > ps, true);
+        ++cc;
+    }
     HAC_MARK(6);
 }
 
@@ -631,17 +647,20 @@ uint32_t table_words(const DevBlob& d)
     return ((2u << d.lut_bits) + 100u + (d.k_sym <= kCodebookLdsMax ? 2u * k4 : 0u) + 3u) & ~3u;
 }
 
-struct BatchShape { uint32_t gw, nb, Bp, tiles; };
+struct BatchShape { uint32_t gw, nb, npass, Bp, tiles; };
 
-// Bp: padded batch width of the feature-major copy; a wave pass covers gw * nb
-// batch columns (at most 256); wider batches take several passes (grid.y).
-BatchShape batch_shape(int64_t B)
+// Bp: padded batch width of the feature-major copy.  One pass covers gw * nb batch
+// columns (at most 32: a pass then touches n * 128 bytes of it); a block runs up to
+// 8 passes (256 batch columns); wider batches take several blocks (grid.y).
+BatchShape batch_shape(int64_t B, uint32_t pass_w)
 {
     BatchShape s;
     uint32_t p = 1;
-    while (p < (uint32_t)(B < 256 ? B : 256)) p <<= 1;
-    s.nb = p < 4 ? p : 4;
-    s.gw = p / s.nb;
+    while (p < (uint32_t)(B < 256 ? B : 256)) p <<= 1;      // batch columns per block, a power of two
+    uint32_t w = p < pass_w ? p : pass_w;                    // batch columns per pass
+    s.nb = w < 4 ? w : 4;
+    s.gw = w / s.nb;
+    s.npass = p / w;
     if (B <= 256) { s.Bp = p; s.tiles = 1; }
     else { s.Bp = (uint32_t)((B + 255) / 256 * 256); s.tiles = s.Bp / 256; }
     return s;
@@ -664,14 +683,14 @@ uint32_t default_cpw(const hac_desc_t* desc)
 }
 
 typedef void (*batch_kern_t)(DevBlob, const float*, uint32_t, uint32_t, float*, uint64_t,
-                             uint32_t, uint32_t, uint32_t, uint32_t, uint32_t);
+                             uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t);
 
 template <bool SHAC>
-batch_kern_t pick_batch_kernel(uint32_t nb, bool uni)
+batch_kern_t pick_batch_kernel(uint32_t nb, bool multipass)
 {
-    if (nb == 1) return uni ? dot_batch_kernel<SHAC, 1, true> : dot_batch_kernel<SHAC, 1, false>;
-    if (nb == 2) return uni ? dot_batch_kernel<SHAC, 2, true> : dot_batch_kernel<SHAC, 2, false>;
-    return uni ? dot_batch_kernel<SHAC, 4, true> : dot_batch_kernel<SHAC, 4, false>;
+    if (nb == 1) return dot_batch_kernel<SHAC, 1, false>;
+    if (nb == 2) return dot_batch_kernel<SHAC, 2, false>;
+    return multipass ? dot_batch_kernel<SHAC, 4, true> : dot_batch_kernel<SHAC, 4, false>;
 }
 
 int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
@@ -685,7 +704,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     if (B == 0) return HAC_OK;
     if (!d_X || !d_Y || ldx < (int64_t)desc->n || ldy < (int64_t)desc->m) return HAC_EINVAL;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    uint32_t cpw = default_cpw(desc), wpb = 0, list_cap = 0, sbuf_words = 0;
+    uint32_t cpw = default_cpw(desc), wpb = 0, list_cap = 0, sbuf_words = 0, pass_w = 32;
     bool reuse_xt = false;
     if (launch) {
         if (launch->cols_per_wave > 32 || launch->waves_per_block > 16) return HAC_EINVAL;
@@ -697,13 +716,15 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         sbuf_words = launch->reserved[1];
         if (list_cap && (list_cap < 64 || list_cap > 4096)) return HAC_EINVAL;
         if (sbuf_words && (sbuf_words < 16 || sbuf_words > 16384 || sbuf_words % 4)) return HAC_EINVAL;
-        if (launch->reserved[2] || launch->reserved[3] || launch->reserved[4]) return HAC_EINVAL;
+        if (launch->reserved[2]) pass_w = launch->reserved[2];
+        if (pass_w != 32 && pass_w != 64 && pass_w != 128 && pass_w != 256) return HAC_EINVAL;
+        if (launch->reserved[3] > 1 || launch->reserved[4]) return HAC_EINVAL;
     }
     const uint32_t nwaves = (d.m + cpw - 1) / cpw;
     const bool shac = format == HAC_FORMAT_SHAC;
     g_last_hip_error = 0;
 
-    const BatchShape bs = batch_shape(B);
+    const BatchShape bs = batch_shape(B, pass_w);
     const float* XT = d_X;                                   // B = 1: X is its own feature-major copy
     if (B > 1) {
         const size_t need = 4ull * d.n * bs.Bp;
@@ -714,7 +735,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         if (!reuse_xt) {
             dim3 grid((d.n + 31) / 32, (bs.Bp + 31) / 32);
             hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, stream,
-                               d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt, bs.Bp);
+                               d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt, bs.Bp, bs.gw * bs.nb);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return hip_fail(e);
         }
@@ -731,7 +752,12 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         if (est > one_batch) est = one_batch;
         list_cap = round_up((uint32_t)(est < 2048.0 ? (est > 1.0 ? est : 1.0) : 2048.0), 64);
     }
-    const size_t per_wave = 4ull * sbuf_words + 8ull * list_cap;
+    // a column that exceeds the list window (or the 64 chunks of one batch) parks partial sums in LDS
+    // (no split is possible when all chunks of a wave fit one batch of 64 and all its non-zeros one window)
+    const uint64_t col_chunks = (desc->max_col_nnz + desc->chunk - 1) / desc->chunk;
+    const bool may_split = (uint64_t)cpw * col_chunks > 64 || (uint64_t)cpw * desc->max_col_nnz > list_cap;
+    const uint32_t part_words = may_split ? bs.npass * bs.nb * 64u : 0u;
+    const size_t per_wave = 4ull * sbuf_words + 8ull * list_cap + 4ull * part_words;
     if (!wpb) {
         // as many wavefronts per CU as LDS allows (at most 16), in blocks that share one copy of the tables
         const size_t tbl = 4ull * table_words(d);
@@ -747,17 +773,19 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     }
     const size_t lds = 4ull * table_words(d) + (size_t)wpb * per_wave;
     if (lds > kLdsLimit) return HAC_EINVAL;
+    uint32_t sync_passes = (bs.npass > 1 && cpw == 1 && !may_split) ? 1u : 0u;
+    if (launch && launch->reserved[3] == 1) sync_passes = 0;           // measurement aid: free-running passes
     const uint32_t nblocks = (nwaves + wpb - 1) / wpb;
     const uint32_t grid = (nblocks + 7) / 8 * 8;
-    const bool uni = bs.gw == 64;
-    batch_kern_t k = shac ? pick_batch_kernel<true>(bs.nb, uni) : pick_batch_kernel<false>(bs.nb, uni);
+    batch_kern_t k = shac ? pick_batch_kernel<true>(bs.nb, bs.npass > 1) : pick_batch_kernel<false>(bs.nb, bs.npass > 1);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return hip_fail(e);
     }
     hipLaunchKernelGGL(k, dim3(grid, bs.tiles), dim3(wpb * kWave), lds, stream,
-                       d, XT, bs.Bp, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, bs.gw, list_cap, sbuf_words, nblocks);
+                       d, XT, bs.Bp, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, bs.gw, bs.npass, list_cap, sbuf_words, part_words, nblocks,
+                       sync_passes);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? HAC_OK : hip_fail(e);
 }
@@ -768,7 +796,7 @@ extern "C" size_t hac_workspace_bytes(const hac_desc_t* desc, int64_t B)
 {
     if (!desc || B <= 0) return 0;
     if (B == 1) return 0;                                    // a single row is its own feature-major copy
-    const BatchShape bs = batch_shape(B);
+    const BatchShape bs = batch_shape(B, 32);
     return (size_t)4 * (size_t)desc->n * bs.Bp;
 }
 

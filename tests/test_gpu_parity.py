@@ -133,6 +133,7 @@ def test_launch_overrides_do_not_change_the_result(hac):
             launch = hac.Launch(cols_per_wave=cpw, waves_per_block=wpb)
             launch.reserved[0] = cap          # list capacity: small values force several windows per column
             launch.reserved[1] = sbuf         # staging buffer: small values force the unstaged reader
+            launch.reserved[2] = 64 if cpw == 7 else 0     # batch columns per pass
             Y = f(db, Xd, launch=launch)
             Y1 = f(db, Xd[:1], launch=launch)
             torch.cuda.synchronize()
