@@ -339,6 +339,30 @@ transpose_pad_kernel(const float* __restrict__ X, uint32_t B, uint32_t n, uint64
     }
 }
 
+// Same re-layout for panels of exactly 32 batch columns: a block turns 32 batch rows x 64
+// features into one contiguous 8 KB piece of a panel (256-byte reads, fully contiguous writes).
+__global__ void __launch_bounds__(256)
+transpose_panel32_kernel(const float* __restrict__ X, uint32_t B, uint32_t n, uint64_t ldx,
+                         float* __restrict__ XT)
+{
+    __shared__ float tile[32][65];
+    const uint32_t r0 = blockIdx.x * 64, b0 = blockIdx.y * 32;
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) {
+        const uint32_t idx = threadIdx.x + 256 * i;
+        const uint32_t b = idx >> 6, r = idx & 63;
+        tile[b][r] = (b0 + b < B && r0 + r < n) ? X[(uint64_t)(b0 + b) * ldx + r0 + r] : 0.0f;
+    }
+    __syncthreads();
+    float* out = XT + (uint64_t)blockIdx.y * n * 32 + (uint64_t)r0 * 32;
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) {
+        const uint32_t idx = threadIdx.x + 256 * i;
+        const uint32_t r = idx >> 5, b = idx & 31;
+        if (r0 + r < n) out[idx] = tile[b][r];
+    }
+}
+
 // ---------------------------------------------------------------------------
 // batch kernel
 // ---------------------------------------------------------------------------
@@ -733,9 +757,15 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         float* xt = static_cast<float*>(d_ws);
         XT = xt;
         if (!reuse_xt) {
-            dim3 grid((d.n + 31) / 32, (bs.Bp + 31) / 32);
-            hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, stream,
-                               d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt, bs.Bp, bs.gw * bs.nb);
+            if (bs.gw * bs.nb == 32) {
+                dim3 grid((d.n + 63) / 64, bs.Bp / 32);
+                hipLaunchKernelGGL(transpose_panel32_kernel, grid, dim3(256), 0, stream,
+                                   d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt);
+            } else {
+                dim3 grid((d.n + 31) / 32, (bs.Bp + 31) / 32);
+                hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, stream,
+                                   d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt, bs.Bp, bs.gw * bs.nb);
+            }
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return hip_fail(e);
         }
