@@ -102,6 +102,36 @@ def test_dot_parity_small(hac, name, W):
         check_y(Ys, X, W, f"shac {name} B={B}")
 
 
+@pytest.mark.parametrize("name", sorted(workloads.stress_cases().keys()))
+def test_stress_cases(hac, name):
+    """Alphabets above 1024 symbols, codewords beyond the first-level table, 64-bit chunk entries,
+    columns with far more than 64 chunks."""
+    W = workloads.stress_cases()[name]
+    n, m = W.shape
+    print(f"[case] stress {name} {W.shape}", flush=True)
+    values, sym = formats.hac_symbols(W)
+    hb, sb = hac.hac_encode(W), hac.shac_encode(W)
+    Wd, symd = hac.hac_decode_dev(hb.to_device(dev()))
+    nz, ssym, srow, scol = hac.shac_decode_dev(sb.to_device(dev()))
+    torch.cuda.synchronize()
+    assert np.array_equal(Wd.cpu().numpy().view(np.uint32), W.view(np.uint32))
+    assert np.array_equal(symd.cpu().numpy().astype(np.int64), sym)
+    svalues, s_sym, s_row, s_col = formats.shac_symbols(W)
+    assert np.array_equal(ssym.cpu().numpy().astype(np.int64), s_sym)
+    assert np.array_equal(srow.cpu().numpy().astype(np.int64), s_row)
+    assert np.array_equal(scol.cpu().numpy().astype(np.int64), s_col)
+    assert np.array_equal(nz.cpu().numpy().view(np.uint32), svalues[s_sym].view(np.uint32))
+    dh, ds = hb.to_device(dev()), sb.to_device(dev())
+    for B in (1, 5, 32, 70):
+        X = workloads.make_batch(B, n, 11 + B) - np.float32(0.25)
+        Xd = torch.from_numpy(X).to(dev())
+        Yh = hac.hac_dot(dh, Xd)
+        Ys = hac.shac_dot(ds, Xd)
+        torch.cuda.synchronize()
+        check_y(Yh, X, W, f"hac {name} B={B}")
+        check_y(Ys, X, W, f"shac {name} B={B}")
+
+
 def test_dot_other_encoder_options(hac):
     W = workloads.scaled(3, 1500, 90)
     n, m = W.shape

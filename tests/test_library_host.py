@@ -206,6 +206,25 @@ def test_long_codewords_use_the_second_level():
     assert np.array_equal(blob.decode_host()[0], W)
 
 
+@pytest.mark.parametrize("name", sorted(workloads.stress_cases().keys()))
+def test_stress_cases_round_trip(name):
+    W = workloads.stress_cases()[name]
+    hb = hac.hac_encode(W)
+    sb = hac.shac_encode(W)
+    assert hb.validate(deep=True) == 0 and sb.validate(deep=True) == 0
+    assert np.array_equal(hb.decode_host()[0].view(np.uint32), W.view(np.uint32))
+    assert np.array_equal(sb.decode_host()[0].view(np.uint32), W.view(np.uint32))
+    oh, os_ = formats.hac_symbols(W), formats.shac_symbols(W)
+    assert np.array_equal(hb.decode_host(want_w=False)[1], oh[1])
+    assert np.array_equal(sb.decode_host(want_w=False)[1], os_[1])
+    if name == "no_repeats_40x30":
+        assert int(hb.desc.k_sym) == 1200                       # above the 1024 symbols kept in LDS
+    if name == "long_codes":
+        assert int(sb.desc.lmax) >= 20 and int(sb.desc.lmax) > int(sb.desc.lut_bits)
+    if name == "tall_dense_70000x2":
+        assert int(hb.desc.ent_bits) == 64 and int(sb.desc.ent_bits) == 32
+
+
 def test_stats_and_corollary_bounds():
     W = workloads.layer(1)
     n, m = W.shape

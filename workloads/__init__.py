@@ -189,6 +189,31 @@ def edge_cases() -> Dict[str, np.ndarray]:
     return out
 
 
+def stress_cases() -> Dict[str, np.ndarray]:
+    """Larger structured matrices that push the format's limits (all deterministic)."""
+    rng = np.random.default_rng(777)
+    out: Dict[str, np.ndarray] = {}
+    # every entry distinct: alphabet of n*m > 1024 symbols (the paper's Fact 1 setting)
+    out["no_repeats_40x30"] = rng.permutation(np.arange(1, 1201, dtype=np.float32)).reshape(40, 30)
+    # Fibonacci-like counts: a path-shaped Huffman tree, codewords up to 23 bits
+    counts = [1, 1]
+    while len(counts) < 24:
+        counts.append(counts[-1] + counts[-2])
+    vals = np.arange(1, len(counts) + 1, dtype=np.float32) * np.float32(0.25)
+    col = np.concatenate([np.full(c, v, dtype=np.float32) for c, v in zip(counts, vals)])
+    pad = (-col.size) % 8
+    col = np.concatenate([col, np.zeros(pad, dtype=np.float32)])
+    out["long_codes"] = rng.permutation(col).reshape(-1, 8)
+    # tall and fairly dense: 17 row bits + > 2^15 stream bits per column (64-bit HAC chunk
+    # entries) and > 2^16 bits of non-zero codes per column (32-bit sHAC chunk entries)
+    tall = np.zeros((70000, 2), dtype=np.float32)
+    mask = rng.random(tall.shape) < 0.5
+    tall[mask] = rng.choice(np.array([-1.5, -0.5, 0.25, 0.75, 1.0, 2.0, 3.5, 4.0, 6.0], dtype=np.float32),
+                            size=int(mask.sum()))
+    out["tall_dense_70000x2"] = tall
+    return out
+
+
 def paper_example_matrix() -> np.ndarray:
     """The 5x5 matrix of the paper's CSC example (Sect. IV-A, Example 1)."""
     return np.array([[1, 0, 4, 0, 0],
