@@ -144,7 +144,7 @@ typedef struct {
 typedef struct {
     uint32_t cols_per_wave;   /* columns of W one wavefront handles, 1..32                 */
     uint32_t waves_per_block; /* 1..16                                                     */
-    uint32_t variant;         /* 0, or HAC_LAUNCH_REUSE_XT                                  */
+    uint32_t variant;         /* 0, or HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_LIST_KERNEL         */
     uint32_t reserved[5];     /* [0]: entries of the per-wavefront non-zero list, 64..4096;
                                  [1]: words of the per-wavefront staging buffer for stream
                                  (and ri) words, 16..16384, multiple of 4;
@@ -152,13 +152,22 @@ typedef struct {
                                  [2]: batch columns one pass over the non-zero list
                                  covers, 32 / 64 / 128 / 256 [32];
                                  [3]: 1 = do not hold a block's wavefronts on the same pass
-                                 (measurement aid); [4] must be 0                          */
+                                 (measurement aid);
+                                 [4]: batch columns one block covers, 32 / 64 / 128 / 256,
+                                 not below [2]; every column of W is decoded once per
+                                 such tile of the batch                                    */
 } hac_launch_t;
 
 /* The workspace already holds the feature-major copy of this very X (same B,
  * same n) left there by an earlier call: skip the re-layout pass.  Meant for
  * one X multiplied with several compressed matrices of the same height. */
 #define HAC_LAUNCH_REUSE_XT 0x100u
+
+/* Batches of at most 4 rows normally run a kernel in which every lane
+ * multiplies the non-zeros it decodes itself; this flag sends them through the
+ * kernel of the larger batches (decoded non-zeros listed in LDS, then shared by
+ * lanes that each own batch columns).  Same result up to summation order. */
+#define HAC_LAUNCH_LIST_KERNEL 0x200u
 
 /* ---- host side ------------------------------------------------------------ */
 

@@ -461,10 +461,16 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
     extern __shared__ uint32_t smem[];
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const uint32_t lb = logical_block(gridDim.x);
+    // Work items are (batch tile, column block) pairs, tile-major; every XCD takes one contiguous
+    // range of them, so the feature-major panels of one tile are fetched into few L2s only.
+    const uint32_t item = logical_block(gridDim.x);
+    const uint32_t tile = item / nblocks;
+    const uint32_t lb = item - tile * nblocks;
     const uint32_t wave = lb * (blockDim.x / kWave) + wib;
     const uint32_t c0 = wave * cpw;
-    const bool live = lb < nblocks && c0 < d.m;
+    const uint32_t tile_b = gw * NB * npass;                 // batch columns per block
+    if (tile * tile_b >= B) return;                          // padding of the grid, or a tile of padding only
+    const bool live = c0 < d.m;
     HAC_MARK(0);
     // Per-column index of this wave's columns: lane l keeps column c0 + l (l <= ncols).
     // Requested before the decode tables so that both trips to memory overlap.
@@ -523,8 +529,8 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
     const uint32_t grp = lane / gw, lig = lane % gw;
     const uint32_t pass_w = gw * NB;                          // batch columns per pass = width of one panel of XT
     const uint64_t panel = (uint64_t)d.n * pass_w;            // floats per panel
-    const uint32_t boff = blockIdx.y * (pass_w * npass) + lig * NB;   // first batch column of this lane, pass 0
-    const float* xt = XT + (uint64_t)blockIdx.y * npass * panel + lig * NB;
+    const uint32_t boff = tile * tile_b + lig * NB;           // first batch column of this lane, pass 0
+    const float* xt = XT + (uint64_t)tile * npass * panel + lig * NB;
     uint32_t cc = c0;                                        // column being accumulated (wave-uniform)
     uint32_t t = posbase;                                    // next CSC position to consume
 
@@ -630,6 +636,133 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
 }
 
 // ---------------------------------------------------------------------------
+// small-batch kernel (at most 4 rows of X)
+// ---------------------------------------------------------------------------
+// With so few batch columns there is nothing to share between lanes, so a lane
+// multiplies the non-zeros it decodes itself: the fetch of X for one non-zero
+// travels while the next codeword is decoded, and no list is written.  XT holds
+// NB floats per row of W (B = 1: X itself).  Lane sums are added over the lanes
+// of a column with a segmented shuffle reduction (columns own contiguous lanes),
+// then over chunk batches in LDS (colsum), always in the same order.
+template <bool SHAC, int NB>
+__global__ void __launch_bounds__(1024)
+dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __restrict__ Y, uint64_t ldy,
+                 uint32_t cpw, uint32_t sbuf_words, uint32_t sum_words, uint32_t nblocks)
+{
+    extern __shared__ uint32_t smem[];
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t lb = logical_block(gridDim.x);
+    const uint32_t wave = lb * (blockDim.x / kWave) + wib;
+    const uint32_t c0 = wave * cpw;
+    const bool live = lb < nblocks && c0 < d.m;
+    uint32_t ncols = 0, cchunk_l = 0, cpos_l = 0, cbit_l = 0;
+    if (live) {
+        const uint32_t cend = c0 + cpw < d.m ? c0 + cpw : d.m;
+        ncols = cend - c0;
+        if (lane <= ncols) {
+            cchunk_l = d.colchunk[c0 + lane];
+            cpos_l = d.colpos[c0 + lane];
+            cbit_l = d.colbit[c0 + lane];
+        }
+    }
+    const Tables tb = load_tables(d, smem);
+    __syncthreads();
+    if (!live) return;
+    const uint32_t gfirst = (uint32_t)__shfl((int)cchunk_l, 0, kWave);
+    const uint32_t g1 = (uint32_t)__shfl((int)cchunk_l, (int)ncols, kWave);
+    const uint32_t posbase = (uint32_t)__shfl((int)cpos_l, 0, kWave);
+    const uint32_t posend = (uint32_t)__shfl((int)cpos_l, (int)ncols, kWave);
+    const uint32_t bit_lo = (uint32_t)__shfl((int)cbit_l, 0, kWave);
+    const uint32_t bit_hi = (uint32_t)__shfl((int)cbit_l, (int)ncols, kWave);
+
+    uint32_t* sbuf = smem + table_words_dev(d) + (uint64_t)wib * (sbuf_words + sum_words);
+    float* colsum = reinterpret_cast<float*>(sbuf + sbuf_words);          // [column][NB]
+    for (uint32_t i = lane; i < ncols * NB; i += kWave) colsum[i] = 0.0f;
+
+    const uint32_t swlo = (bit_lo >> 5) & ~3u;
+    const uint32_t snw = (((bit_hi >> 5) + 4) - swlo + 4) & ~3u;
+    const uint64_t rb_lo = (uint64_t)posbase * d.ri_bits, rb_hi = (uint64_t)posend * d.ri_bits;
+    const uint32_t rwlo = (uint32_t)(rb_lo >> 5) & ~3u;
+    const uint32_t rnw = SHAC ? ((((uint32_t)(rb_hi >> 5) + 2) - rwlo + 4) & ~3u) : 0u;
+    const bool staged = posend > posbase && snw + rnw <= sbuf_words;
+    uint32_t ent_rel = 0, ent_row = 0;
+    if (gfirst + lane < g1) load_entry(d, gfirst + lane, ent_rel, ent_row);
+    if (staged) {
+        stage_words(sbuf, d.stream, swlo, snw, lane);
+        if (SHAC) stage_words(sbuf + snw, d.ri, rwlo, rnw, lane);
+    }
+    wave_sync();
+    const WordSrc<true> s_lds = { sbuf, swlo };
+    const WordSrc<false> s_glb = { d.stream, 0 };
+    const WordSrc<true> r_lds = { sbuf + snw, rwlo };
+    const WordSrc<false> r_glb = { d.ri, 0 };
+
+    for (uint32_t gb = gfirst; gb < g1; gb += kWave) {
+        const uint32_t nact = g1 - gb < (uint32_t)kWave ? g1 - gb : (uint32_t)kWave;
+        const bool active = lane < nact;
+        const uint32_t g = gb + lane;
+        uint32_t rel = 0;
+        for (uint32_t k = 1; k < ncols; ++k) rel += (uint32_t)__shfl((int)cchunk_l, (int)k, kWave) <= g ? 1u : 0u;
+        const uint32_t col_chunk0 = (uint32_t)__shfl((int)cchunk_l, (int)rel, kWave);
+        const uint32_t col_pos0 = (uint32_t)__shfl((int)cpos_l, (int)rel, kWave);
+        const uint32_t col_pos1 = (uint32_t)__shfl((int)cpos_l, (int)rel + 1, kWave);
+        const uint32_t col_bit0 = (uint32_t)__shfl((int)cbit_l, (int)rel, kWave);
+        ChunkState st;
+        st.bp = col_bit0 + ent_rel;
+        st.row = ent_row;
+        st.wpos = col_pos0 + (g - col_chunk0) * d.chunk;
+        st.wend = st.wpos + d.chunk < col_pos1 ? st.wpos + d.chunk : col_pos1;
+        if (!active) { st.wpos = 0; st.wend = 0; }
+        if (gb + kWave + lane < g1) load_entry(d, gb + kWave + lane, ent_rel, ent_row);
+
+        // a[] += pv * px[] is applied when the next non-zero has been decoded, just before px is
+        // fetched again, so the fetch of X for one non-zero travels during a whole decode step
+        float a[NB], px[NB], pv = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) { a[i] = 0.0f; px[i] = 0.0f; }
+        if (active) {
+            auto emit = [&](uint32_t p, uint32_t row, uint32_t, float v) {
+                if (SHAC) {
+                    const uint64_t fb = (uint64_t)p * d.ri_bits;
+                    row = staged ? r_lds.field(fb, d.ri_bits) : r_glb.field(fb, d.ri_bits);
+                }
+#pragma unroll
+                for (int i = 0; i < NB; ++i) a[i] = fmaf(px[i], pv, a[i]);
+                VecLoad<NB>::ld(XT + (uint64_t)row * NB, px);
+                pv = v;
+            };
+            if (staged) {
+                if (SHAC) shac_advance(d, tb, s_lds, st, st.wend, emit);
+                else if (d.zero_len == 1) hac_advance_zrun(d, tb, s_lds, st, st.wend, emit);
+                else hac_advance(d, tb, s_lds, st, st.wend, emit);
+            } else {
+                if (SHAC) shac_advance(d, tb, s_glb, st, st.wend, emit); else hac_advance(d, tb, s_glb, st, st.wend, emit);
+            }
+        }
+        const uint32_t key = active ? rel : 0xffffffffu;
+        const uint32_t key_up = (uint32_t)__shfl_up((int)key, 1, kWave);
+        const bool head = active && (lane == 0 || key_up != key);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            float v = fmaf(px[i], pv, a[i]);
+            for (uint32_t off = 1; off < (uint32_t)kWave; off <<= 1) {
+                const float o = __shfl_down(v, off, kWave);
+                const uint32_t ko = (uint32_t)__shfl_down((int)key, off, kWave);
+                if (lane + off < (uint32_t)kWave && ko == key) v += o;
+            }
+            if (head) colsum[rel * NB + i] += v;
+        }
+        wave_sync();                                         // the next batch may continue the same column
+    }
+    for (uint32_t j = lane; j < ncols; j += kWave) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+            if ((uint32_t)i < B) Y[(uint64_t)i * ldy + c0 + j] = colsum[j * NB + i];
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host-side launch helpers
 // ---------------------------------------------------------------------------
 thread_local int g_last_hip_error = 0;
@@ -673,24 +806,27 @@ uint32_t table_words(const DevBlob& d)
 
 struct BatchShape { uint32_t gw, nb, npass, Bp, tiles; };
 
-// Bp: padded batch width of the feature-major copy.  One pass covers gw * nb batch
-// columns (at most 32: a pass then touches n * 128 bytes of it); a block runs up to
-// 8 passes (256 batch columns); wider batches take several blocks (grid.y).
-BatchShape batch_shape(int64_t B, uint32_t pass_w)
+// Bp: padded batch width of the feature-major copy (a power of two up to 256, else a
+// multiple of 256).  One pass covers gw * nb batch columns (a pass over 32 touches
+// n * 128 bytes of the copy); a block runs the passes of one tile of tile_b batch
+// columns; Bp / tile_b tiles cover the batch.
+BatchShape batch_shape(int64_t B, uint32_t pass_w, uint32_t tile_b)
 {
     BatchShape s;
     uint32_t p = 1;
-    while (p < (uint32_t)(B < 256 ? B : 256)) p <<= 1;      // batch columns per block, a power of two
-    uint32_t w = p < pass_w ? p : pass_w;                    // batch columns per pass
+    while (p < (uint32_t)(B < 256 ? B : 256)) p <<= 1;
+    s.Bp = B <= 256 ? p : (uint32_t)((B + 255) / 256 * 256);
+    uint32_t t = p < tile_b ? p : tile_b;                    // batch columns per block, a power of two
+    uint32_t w = t < pass_w ? t : pass_w;                    // batch columns per pass
     s.nb = w < 4 ? w : 4;
     s.gw = w / s.nb;
-    s.npass = p / w;
-    if (B <= 256) { s.Bp = p; s.tiles = 1; }
-    else { s.Bp = (uint32_t)((B + 255) / 256 * 256); s.tiles = s.Bp / 256; }
+    s.npass = t / w;
+    s.tiles = s.Bp / t;
     return s;
 }
 
 constexpr size_t kLdsLimit = 160 * 1024;
+constexpr uint32_t kDefaultTile = 256;
 
 uint32_t round_up(uint32_t v, uint32_t q) { return (v + q - 1) / q * q; }
 
@@ -728,27 +864,31 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     if (B == 0) return HAC_OK;
     if (!d_X || !d_Y || ldx < (int64_t)desc->n || ldy < (int64_t)desc->m) return HAC_EINVAL;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    uint32_t cpw = default_cpw(desc), wpb = 0, list_cap = 0, sbuf_words = 0, pass_w = 32;
-    bool reuse_xt = false;
+    uint32_t cpw = default_cpw(desc), wpb = 0, list_cap = 0, sbuf_words = 0, pass_w = 32, tile_b = kDefaultTile;
+    bool reuse_xt = false, list_kernel = false;
     if (launch) {
         if (launch->cols_per_wave > 32 || launch->waves_per_block > 16) return HAC_EINVAL;
         if (launch->cols_per_wave) cpw = launch->cols_per_wave;
         wpb = launch->waves_per_block;
         reuse_xt = (launch->variant & HAC_LAUNCH_REUSE_XT) != 0;
-        if (launch->variant & ~HAC_LAUNCH_REUSE_XT) return HAC_EINVAL;
+        list_kernel = (launch->variant & HAC_LAUNCH_LIST_KERNEL) != 0;
+        if (launch->variant & ~(HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_LIST_KERNEL)) return HAC_EINVAL;
         list_cap = launch->reserved[0];
         sbuf_words = launch->reserved[1];
         if (list_cap && (list_cap < 64 || list_cap > 4096)) return HAC_EINVAL;
         if (sbuf_words && (sbuf_words < 16 || sbuf_words > 16384 || sbuf_words % 4)) return HAC_EINVAL;
         if (launch->reserved[2]) pass_w = launch->reserved[2];
         if (pass_w != 32 && pass_w != 64 && pass_w != 128 && pass_w != 256) return HAC_EINVAL;
-        if (launch->reserved[3] > 1 || launch->reserved[4]) return HAC_EINVAL;
+        if (launch->reserved[3] > 1) return HAC_EINVAL;
+        if (launch->reserved[4]) tile_b = launch->reserved[4];
+        if (tile_b != 32 && tile_b != 64 && tile_b != 128 && tile_b != 256) return HAC_EINVAL;
+        if (tile_b < pass_w) return HAC_EINVAL;
     }
     const uint32_t nwaves = (d.m + cpw - 1) / cpw;
     const bool shac = format == HAC_FORMAT_SHAC;
     g_last_hip_error = 0;
 
-    const BatchShape bs = batch_shape(B, pass_w);
+    const BatchShape bs = batch_shape(B, pass_w, tile_b);
     const float* XT = d_X;                                   // B = 1: X is its own feature-major copy
     if (B > 1) {
         const size_t need = 4ull * d.n * bs.Bp;
@@ -782,6 +922,33 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         if (est > one_batch) est = one_batch;
         list_cap = round_up((uint32_t)(est < 2048.0 ? (est > 1.0 ? est : 1.0) : 2048.0), 64);
     }
+    if (bs.gw == 1 && bs.npass == 1 && !list_kernel) {
+        // at most 4 batch columns: lanes multiply what they decode, no list
+        const uint32_t sum_words = round_up(cpw * bs.nb, 4);
+        const size_t per_wave_s = 4ull * (sbuf_words + sum_words);
+        const size_t tbl = 4ull * table_words(d);
+        if (!wpb) {
+            for (wpb = 16; wpb > 1 && tbl + wpb * per_wave_s > kLdsLimit; wpb >>= 1) {}
+        }
+        const size_t lds = tbl + (size_t)wpb * per_wave_s;
+        if (lds > kLdsLimit) return HAC_EINVAL;
+        const uint32_t nblocks = (nwaves + wpb - 1) / wpb;
+        const uint32_t grid = (nblocks + 7) / 8 * 8;
+        typedef void (*small_kern_t)(DevBlob, const float*, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t, uint32_t);
+        small_kern_t k;
+        if (bs.nb == 1) k = shac ? dot_small_kernel<true, 1> : dot_small_kernel<false, 1>;
+        else if (bs.nb == 2) k = shac ? dot_small_kernel<true, 2> : dot_small_kernel<false, 2>;
+        else k = shac ? dot_small_kernel<true, 4> : dot_small_kernel<false, 4>;
+        if (lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        hipLaunchKernelGGL(k, dim3(grid), dim3(wpb * kWave), lds, stream,
+                           d, XT, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, sbuf_words, sum_words, nblocks);
+        hipError_t e = hipGetLastError();
+        return e == hipSuccess ? HAC_OK : hip_fail(e);
+    }
     // a column that exceeds the list window (or the 64 chunks of one batch) parks partial sums in LDS
     // (no split is possible when all chunks of a wave fit one batch of 64 and all its non-zeros one window)
     const uint64_t col_chunks = (desc->max_col_nnz + desc->chunk - 1) / desc->chunk;
@@ -806,14 +973,16 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     uint32_t sync_passes = (bs.npass > 1 && cpw == 1 && !may_split) ? 1u : 0u;
     if (launch && launch->reserved[3] == 1) sync_passes = 0;           // measurement aid: free-running passes
     const uint32_t nblocks = (nwaves + wpb - 1) / wpb;
-    const uint32_t grid = (nblocks + 7) / 8 * 8;
+    const uint64_t items = (uint64_t)nblocks * bs.tiles;
+    if (items > 0x7ffffff0ull) return HAC_EINVAL;
+    const uint32_t grid = (uint32_t)((items + 7) / 8 * 8);
     batch_kern_t k = shac ? pick_batch_kernel<true>(bs.nb, bs.npass > 1) : pick_batch_kernel<false>(bs.nb, bs.npass > 1);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return hip_fail(e);
     }
-    hipLaunchKernelGGL(k, dim3(grid, bs.tiles), dim3(wpb * kWave), lds, stream,
+    hipLaunchKernelGGL(k, dim3(grid), dim3(wpb * kWave), lds, stream,
                        d, XT, bs.Bp, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, bs.gw, bs.npass, list_cap, sbuf_words, part_words, nblocks,
                        sync_passes);
     hipError_t e = hipGetLastError();
@@ -826,7 +995,7 @@ extern "C" size_t hac_workspace_bytes(const hac_desc_t* desc, int64_t B)
 {
     if (!desc || B <= 0) return 0;
     if (B == 1) return 0;                                    // a single row is its own feature-major copy
-    const BatchShape bs = batch_shape(B, 32);
+    const BatchShape bs = batch_shape(B, 32, kDefaultTile);
     return (size_t)4 * (size_t)desc->n * bs.Bp;
 }
 

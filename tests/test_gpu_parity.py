@@ -171,6 +171,24 @@ def test_launch_overrides_do_not_change_the_result(hac):
             check_y(Y1, X[:1], W, f"{f.__name__} B=1 cpw={cpw}")
 
 
+def test_small_batches_through_both_kernels(hac):
+    """B <= 4 has a kernel of its own; the list-based kernel must still serve it on request."""
+    for name, W in (("cfg4-3000x65", workloads.scaled(4, 3000, 65)), ("cfg5-640x33", workloads.scaled(5, 640, 33)),
+                    ("empty_columns", workloads.edge_cases()["empty_columns"])):
+        n, m = W.shape
+        for enc, f, kw in ((hac.hac_encode, hac.hac_dot, dict()), (hac.shac_encode, hac.shac_dot, dict()),
+                           (hac.hac_encode, hac.hac_dot, dict(chunk_nnz=1)), (hac.shac_encode, hac.shac_dot, dict(chunk_nnz=2))):
+            db = enc(W, **kw).to_device(dev())
+            for B in (1, 2, 3, 4):
+                X = workloads.make_batch(B, n, 5 + B) - np.float32(0.5)
+                Xd = torch.from_numpy(X).to(dev())
+                for variant, cpw in ((0, 0), (0x200, 0), (0, 5), (0x200, 3)):
+                    print(f"[case] small {f.__name__} {name} B={B} variant={variant:#x} cpw={cpw} {kw}", flush=True)
+                    Y = f(db, Xd, launch=hac.Launch(cols_per_wave=cpw, variant=variant))
+                    torch.cuda.synchronize()
+                    check_y(Y, X, W, f"{f.__name__} {name} B={B} variant={variant:#x}")
+
+
 def test_identity_batch_recovers_w_bit_exact(hac):
     W = workloads.scaled(2, 96, 50)
     eye = torch.eye(96, dtype=torch.float32, device=dev())
