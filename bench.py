@@ -53,6 +53,9 @@ def parse_args():
     ap.add_argument("--hot", action="store_true", help="no rotation: same buffers every step (cache-resident)")
     ap.add_argument("--chunk-nnz", type=int, default=0)
     ap.add_argument("--only", type=str, default="", help="restrict the step to 'hac' or 'shac'")
+    ap.add_argument("--extras", action="store_true",
+                    help="also report cache-resident timings, the decode-only kernels' symbol rate and CPU context "
+                         "rows (decode once + dense product, numpy dense, scipy CSC); adds about a minute")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a 256 MiB device-to-device copy 4 times before the timed region "
                          "(a kernel of known traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -133,6 +136,72 @@ def measured_traffic(cfg_id, fmt, B):
     except OSError:
         return None
     return None
+
+
+def kernel_name(fmt, B):
+    """Name of the dot kernel a (format, B) call launches with default settings."""
+    shac = "true" if fmt == "shac" else "false"
+    if B <= 4:
+        return f"dot_small_kernel<{shac}, {1 if B == 1 else 2 if B == 2 else 4}>"
+    return f"dot_batch_kernel<{shac}, 4, {'true' if B > 32 else 'false'}>"
+
+
+def extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, iters):
+    """Figures that are context for the headline number, not part of it."""
+    out = {}
+    reuse = hac.Launch()
+    reuse.variant = 0x100
+    hot = []
+    for c in calls:                                    # same buffers every launch: everything cache-resident
+        ms = time_region(torch, lambda i, c=c: c.fn(c.blobs[0], c.X[0], Y=c.Y[0], workspace=c.ws[0],
+                                                    launch=None if c.B == 1 else reuse), iters, 5, use_graph, 8)
+        hot.append({"format": c.fmt, "B": c.B, "kernel_ms": round(ms, 5),
+                    "kernel_hbm_frac": round(c.bytes / ms / 1e6 / HBM_PEAK_GBS, 4)})
+    out["hot"] = hot
+    # decode-only kernels (test entry points): symbols and stream bits per second
+    dec = []
+    for fmt, blob in (("hac", hb), ("shac", sb)):
+        db = blob.to_device(dev)
+        n, m, nnz = int(blob.desc.n), int(blob.desc.m), int(blob.desc.nnz)
+        if fmt == "hac":
+            body = lambda i, db=db: hac.hac_decode_dev(db)
+            symbols = n * m
+        else:
+            body = lambda i, db=db: hac.shac_decode_dev(db)
+            symbols = nnz
+        ms = time_region(torch, body, 20, 3, False, 1)
+        dec.append({"format": fmt, "ms": round(ms, 4), "symbols_per_s": round(symbols / ms * 1e3, 1),
+                    "nonzeros_per_s": round(nnz / ms * 1e3, 1),
+                    "stream_bits_per_s": round(int(blob.desc.total_bits) / ms * 1e3, 1)})
+    out["decode_only"] = dec
+    # CPU context on this host
+    from oracle import cnative
+    import scipy.sparse as sp
+    B = min(32, Xhost.shape[0])
+    X = np.ascontiguousarray(Xhost[:B])
+    oh = cnative.hac_encode(W)
+    n, m = W.shape
+    t = time.perf_counter()
+    sym = cnative.unpack(oh.words, n * m, oh.code)
+    Wdec = np.ascontiguousarray(oh.values[sym].reshape(m, n).T)
+    t_unpack = time.perf_counter() - t
+    t = time.perf_counter()
+    X @ Wdec
+    t_mm = time.perf_counter() - t
+    t = time.perf_counter()
+    X @ W
+    t_dense = time.perf_counter() - t
+    Wc = sp.csc_matrix(W)
+    t = time.perf_counter()
+    (Wc.T @ X.T).T
+    t_csc = time.perf_counter() - t
+    out["cpu_context"] = {
+        "B": B, "decode_once_then_dense_ms": round(1e3 * (t_unpack + t_mm), 2),
+        "decode_once_ms": round(1e3 * t_unpack, 2), "numpy_dense_fp32_ms": round(1e3 * t_dense, 2),
+        "scipy_csc_ms": round(1e3 * t_csc, 2),
+        "note": "decode once = the oracle's tree-walk decoder over the whole HAC stream on one core, then numpy X@W",
+    }
+    return out
 
 
 def cpu_baseline(W, Xs, cores):
@@ -235,8 +304,7 @@ def main():
             "true_gflops": round(2.0 * c.B * int(c.desc.nnz) / ms / 1e6, 1),
         })
     dom = max(detail, key=lambda d: d["kernel_ms"])
-    nb = min(4, 1 << max(0, (min(dom["B"], 256) - 1).bit_length()))
-    kname = f"dot_batch_kernel<{'true' if dom['format'] == 'shac' else 'false'}, {nb}, {'true' if dom['B'] > 32 else 'false'}>"
+    kname = kernel_name(dom["format"], dom["B"])
     traffic = measured_traffic(cfg.cfg, dom["format"], dom["B"])
     roofline = {
         "bound": "hbm", "kernel": f"{kname} ({dom['format']}_dot, B={dom['B']})",
@@ -266,6 +334,8 @@ def main():
         "detail": detail,
         "prep_seconds": round(t_prep, 2),
     }
+    if args.extras:
+        out["extras"] = extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, max(args.steps, 50))
     if not args.no_cpu_baseline:
         cores = min(len(os.sched_getaffinity(0)), 16)
         out["cpu_baseline"] = cpu_baseline(W, Xhost, cores)
