@@ -39,4 +39,8 @@ optimal code lengths on tiny alphabets, Kraft equality and prefix-freeness,
 the entropy sandwich H <= avg <= H+1, equiprobable 2^j alphabets, bit-exact
 round trips, scipy's CSC arrays and product, numpy's dense fp64 product,
 identity batches, linearity, and the space bounds listed above.
+
+gapcode.py holds an extension that is not in the paper (sHAC whose row indices
+are replaced by Golomb-Rice coded gaps); its definition and its own pins are in
+that module's header.
 """
