@@ -158,6 +158,21 @@ def extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, iters):
         hot.append({"format": c.fmt, "B": c.B, "kernel_ms": round(ms, 5),
                     "kernel_hbm_frac": round(c.bytes / ms / 1e6 / HBM_PEAK_GBS, 4)})
     out["hot"] = hot
+    # sHAC with Rice-coded row gaps (an extension beyond the paper's two formats): same protocol as `detail`
+    W_, dev_ = W, dev
+    gb = hac.shac_encode(W_, ri_coding=hac.RI_RICE)
+    rot = calls[0].rot
+    rice = []
+    for B in sorted({c.B for c in calls}):
+        c = Call(hac, "shac", gb, B, rot, Xhost, dev_, torch)
+        ms = time_region(torch, lambda i, c=c: c.run(i), iters, 5, use_graph, rot)
+        ms_k = ms if B == 1 else time_region(torch, lambda i, c=c: c.run(i, reuse), iters, 5, use_graph, rot)
+        rice.append({"B": B, "ms": round(ms, 5), "kernel_ms": round(ms_k, 5), "bytes": c.bytes,
+                     "kernel_hbm_frac": round(c.bytes / ms_k / 1e6 / HBM_PEAK_GBS, 4)})
+        del c
+    out["shac_rice_gaps"] = {"blob_bytes": gb.nbytes, "rice_k": int(gb.desc.rice_k),
+                             "gap_bits_per_nonzero": round(int(gb.desc.gap_bits) / max(int(gb.desc.nnz), 1), 3),
+                             "calls": rice}
     # decode-only kernels (test entry points): symbols and stream bits per second
     dec = []
     for fmt, blob in (("hac", hb), ("shac", sb)):

@@ -11,6 +11,17 @@
  *   dot  (Algorithms 1-3): Y = X.W where W is the decoded matrix; X holds one
  *        input vector per row.
  *
+ * An extension beyond the paper, selected with hac_opts_t.ri_coding =
+ * HAC_RI_RICE: sHAC whose row-index vector ri is replaced by Golomb-Rice coded
+ * row gaps written into the stream itself.  For the non-zero at CSC position p
+ * of column j let d = ri[p] - prev - 1, prev being the row of the non-zero
+ * before it in the same column, or -1 for the column's first.  With q = d >> k:
+ *        q <  31: q bits 0, one bit 1, the k low bits of d (MSB first);
+ *        q >= 31: 31 bits 0, one bit 1, d as 32 bits.
+ * The stream is the concatenation over p of  Rice_k(d_p) | H(nz_p); nz, its
+ * Huffman code and cb are those of sHAC; k (0..15) minimises the gap bits, the
+ * smaller k on ties.  Corollary 2 still bounds the size (there is no ri).
+ *
  * Conventions
  *   - W is n x m (n input features, m outputs).  X is B x n, Y is B x m, both
  *     row-major fp32 with leading dimensions ldx >= n, ldy >= m (in elements).
@@ -64,8 +75,11 @@ typedef struct {
     uint32_t ri_bits;     /* sHAC row-index field width: 0 = ceil(log2 n) (footnote of
                              Sect. IV-A), 32 = one word per index as in Corollary 2        */
     uint32_t lut_bits;    /* width of the first-level decode table, 1..12 [min(Lmax,10)]  */
-    uint32_t reserved;    /* must be 0                                                     */
+    uint32_t ri_coding;   /* sHAC: HAC_RI_FIELDS [default] or HAC_RI_RICE (ri_bits must
+                             then be 0); hac_encode requires 0                             */
 } hac_opts_t;
+
+enum { HAC_RI_FIELDS = 0, HAC_RI_RICE = 1 };
 
 /* Blob header == descriptor.  All offsets are bytes from the start of the blob.
  *
@@ -95,7 +109,8 @@ typedef struct {
                               zero bits (it is one of the shortest), else 0                */
     uint32_t chunk;        /* non-zeros per chunk                                          */
     uint32_t ri_bits;      /* sHAC: width of one row-index field                           */
-    uint32_t ent_bits;     /* width of one chunk entry: HAC 32 or 64, sHAC 16 or 32        */
+    uint32_t ent_bits;     /* width of one chunk entry: HAC and Rice-coded sHAC 32 or 64,
+                              sHAC with ri fields 16 or 32                                 */
     uint64_t n_chunks;     /* sum over columns of ceil(non-zeros in the column / chunk)    */
     uint64_t off_codebook; /* float[k_sym]: symbol -> shared value (H^-1's values)         */
     uint64_t off_codelen;  /* uint8[k_sym]: codeword length per symbol                     */
@@ -110,15 +125,20 @@ typedef struct {
     uint64_t off_chunk_ent;/* n_chunks entries of ent_bits bits (+ >= 8 bytes of zeros):
                               sHAC: bit offset relative to col_bit[j];
                               HAC : (relative bit offset << row_bits) | first row, as one
-                              uint32, or as uint32 pair {first row, relative bit offset}   */
+                              uint32, or as uint32 pair {first row, relative bit offset};
+                              Rice-coded sHAC: as HAC, "first row" being the row from
+                              which the chunk's first gap counts (prev + 1)                */
     uint64_t off_ri;       /* sHAC: row indices, ri_bits-wide fields packed MSB-first into
                               uint32 words, followed by >= 64 bytes of zeros               */
     uint64_t blob_bytes;   /* total size                                                   */
     uint64_t max_col_bits; /* longest stretch of stream bits that one column occupies      */
     uint64_t max_col_nnz;  /* most non-zeros in one column                                 */
-    uint32_t row_bits;     /* HAC, ent_bits = 32: low bits of an entry that hold the row   */
+    uint32_t row_bits;     /* ent_bits = 32 with a row: low bits of an entry that hold it  */
+    uint32_t ri_coding;    /* sHAC: HAC_RI_FIELDS or HAC_RI_RICE                           */
+    uint32_t rice_k;       /* HAC_RI_RICE: the parameter k                                 */
     uint32_t reserved32;
-    uint64_t reserved[5];
+    uint64_t gap_bits;     /* HAC_RI_RICE: part of total_bits spent on the gap codewords   */
+    uint64_t reserved[3];
 } hac_desc_t;
 
 /* Sizes as the paper accounts for them (Sect. IV-B/IV-C) next to the real ones. */
@@ -128,10 +148,11 @@ typedef struct {
     uint64_t table_bytes;      /* codebook + lengths + canonical tables + first-level table*/
     uint64_t index_bytes;      /* index added for the GPU (not part of the paper's format):
                                   col_chunk, col_bit, chunk entries, and for HAC col_pos   */
-    uint64_t ri_bytes, cb_bytes; /* sHAC: packed ri, and cb (= col_pos)                     */
+    uint64_t ri_bytes, cb_bytes; /* sHAC: packed ri (0 when Rice-coded: the gaps are part of
+                                  the stream), and cb (= col_pos)                          */
     uint64_t blob_bytes;
-    uint64_t paper_bits;       /* 32*N + 6*32*k (+ 32*(q + m + 1) for sHAC): the quantity
-                                  bounded by Corollary 1 / Corollary 2                     */
+    uint64_t paper_bits;       /* 32*N + 6*32*k (+ 32*(q + m + 1) for sHAC, 32*(m + 1) when
+                                  Rice-coded): the quantity bounded by Corollary 1 / 2     */
     double   bound_bits;       /* Corollary 1 / Corollary 2 with b = 32                    */
     double   entropy_bits;     /* source entropy H per symbol                              */
     double   avg_code_bits;    /* total_bits / symbols, H <= avg <= H + 1                  */

@@ -38,7 +38,7 @@ class HacError(RuntimeError):
 
 class Opts(C.Structure):
     _fields_ = [("chunk_nnz", C.c_uint32), ("ri_bits", C.c_uint32),
-                ("lut_bits", C.c_uint32), ("reserved", C.c_uint32)]
+                ("lut_bits", C.c_uint32), ("ri_coding", C.c_uint32)]
 
 
 class Desc(C.Structure):
@@ -55,8 +55,9 @@ class Desc(C.Structure):
                 ("off_col_chunk", C.c_uint64), ("off_col_pos", C.c_uint64), ("off_col_bit", C.c_uint64),
                 ("off_chunk_ent", C.c_uint64), ("off_ri", C.c_uint64),
                 ("blob_bytes", C.c_uint64), ("max_col_bits", C.c_uint64), ("max_col_nnz", C.c_uint64),
-                ("row_bits", C.c_uint32), ("reserved32", C.c_uint32),
-                ("reserved", C.c_uint64 * 5)]
+                ("row_bits", C.c_uint32), ("ri_coding", C.c_uint32),
+                ("rice_k", C.c_uint32), ("reserved32", C.c_uint32),
+                ("gap_bits", C.c_uint64), ("reserved", C.c_uint64 * 3)]
 
 
 class Stats(C.Structure):
@@ -185,7 +186,10 @@ class DeviceBlob:
         return int(self.desc.m)
 
 
-def _encode(fn_name: str, W: np.ndarray, chunk_nnz=0, ri_bits=0, lut_bits=0) -> Blob:
+RI_FIELDS, RI_RICE = 0, 1
+
+
+def _encode(fn_name: str, W: np.ndarray, chunk_nnz=0, ri_bits=0, lut_bits=0, ri_coding=0) -> Blob:
     lib = load_library()
     W = np.asarray(W)
     if W.dtype != np.float32 or W.ndim != 2:
@@ -193,7 +197,7 @@ def _encode(fn_name: str, W: np.ndarray, chunk_nnz=0, ri_bits=0, lut_bits=0) -> 
     if W.strides[1] != 4 or W.strides[0] % 4 or W.strides[0] < 4 * W.shape[1]:
         W = np.ascontiguousarray(W)
     ldw = W.strides[0] // 4
-    opts = Opts(chunk_nnz, ri_bits, lut_bits, 0)
+    opts = Opts(chunk_nnz, ri_bits, lut_bits, ri_coding)
     out = C.c_void_p()
     size = C.c_size_t()
     rc = getattr(lib, fn_name)(W.ctypes.data_as(C.POINTER(C.c_float)), W.shape[0], W.shape[1], ldw,
@@ -211,9 +215,10 @@ def hac_encode(W: np.ndarray, chunk_nnz: int = 0, lut_bits: int = 0) -> Blob:
     return _encode("hac_encode", W, chunk_nnz=chunk_nnz, lut_bits=lut_bits)
 
 
-def shac_encode(W: np.ndarray, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0) -> Blob:
+def shac_encode(W: np.ndarray, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0,
+                ri_coding: int = RI_FIELDS) -> Blob:
     """W (n x m float32, host) -> sHAC blob."""
-    return _encode("shac_encode", W, chunk_nnz=chunk_nnz, ri_bits=ri_bits, lut_bits=lut_bits)
+    return _encode("shac_encode", W, chunk_nnz=chunk_nnz, ri_bits=ri_bits, lut_bits=lut_bits, ri_coding=ri_coding)
 
 
 def hac_workspace_bytes(desc: Desc, B: int) -> int:

@@ -265,7 +265,7 @@ uint32_t pick_chunk(const hac_opts_t* opts, uint64_t max_col_nnz)
 int check_opts(const hac_opts_t* opts)
 {
     if (!opts) return HAC_OK;
-    if (opts->lut_bits > 12 || opts->chunk_nnz > 65536 || opts->reserved) return HAC_EINVAL;
+    if (opts->lut_bits > 12 || opts->chunk_nnz > 65536 || opts->ri_coding > HAC_RI_RICE) return HAC_EINVAL;
     return HAC_OK;
 }
 
@@ -288,6 +288,22 @@ struct ColumnIndex {
     }
 };
 
+// ---- Golomb-Rice code of the row gaps (sHAC with ri_coding = HAC_RI_RICE) ----
+constexpr uint32_t kRiceEscape = 31;     // quotients from here on: 31 zeros, a one, the gap in 32 bits
+constexpr uint32_t kRiceKMax = 15;
+
+inline uint32_t rice_length(uint32_t d, uint32_t k)
+{
+    const uint32_t q = d >> k;
+    return q < kRiceEscape ? q + 1 + k : kRiceEscape + 1 + 32;
+}
+
+// gap of CSC position p: rows skipped since the previous non-zero of the column (or its top)
+inline uint32_t gap_at(const Scan& s, uint64_t p, uint64_t col_first)
+{
+    return p == col_first ? s.ri[(size_t)p] : s.ri[(size_t)p] - s.ri[(size_t)p - 1] - 1;
+}
+
 uint64_t max_nnz_per_column(const Scan& s)
 {
     uint64_t mx = 0;
@@ -307,6 +323,7 @@ extern "C" int hac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
     if (rc) return rc;
     *blob = nullptr; *blob_bytes = 0;
     if ((rc = check_opts(opts))) return rc;
+    if (opts && opts->ri_coding) return HAC_EINVAL;          // the address map of HAC is the stream itself
     try {
         Scan s;
         rc = scan_matrix(W, n, m, ldw, s);
@@ -422,6 +439,8 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
     *blob = nullptr; *blob_bytes = 0;
     if ((rc = check_opts(opts))) return rc;
     const uint32_t need_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
+    const bool rice = opts && opts->ri_coding == HAC_RI_RICE;
+    if (rice && opts->ri_bits) return HAC_EINVAL;
     uint32_t ri_bits = opts && opts->ri_bits ? opts->ri_bits : need_bits;
     if (ri_bits < need_bits || ri_bits > 32) return HAC_EINVAL;
     try {
@@ -442,6 +461,93 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         const uint64_t max_col_nnz = max_nnz_per_column(s);
         const uint32_t Cn = pick_chunk(opts, max_col_nnz);
         ColumnIndex ci; ci.build(s, Cn);
+        if (rice) {
+            // ---- gaps in the stream, in front of each value's codeword ----
+            uint32_t k = 0; uint64_t gap_bits = ~0ull;
+            for (uint32_t kk = 0; kk <= kRiceKMax; ++kk) {
+                uint64_t tot = 0;
+                for (int64_t j = 0; j < m; ++j)
+                    for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p)
+                        tot += rice_length(gap_at(s, p, s.cb[(size_t)j]), kk);
+                if (tot < gap_bits) { gap_bits = tot; k = kk; }
+            }
+            if (nnz == 0) gap_bits = 0;
+            total_bits += gap_bits;
+            if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
+            uint64_t max_col_bits = 0;
+            for (int64_t j = 0; j < m; ++j) {
+                uint64_t bits = 0;
+                for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p)
+                    bits += len[s.sym[(size_t)p]] + rice_length(gap_at(s, p, s.cb[(size_t)j]), k);
+                max_col_bits = std::max(max_col_bits, bits);
+            }
+            const uint32_t row_bits = need_bits;
+            const uint32_t brel_bits = std::max<uint32_t>(ceil_log2(max_col_bits + 1), 1);
+            const uint32_t ent_bits = row_bits + brel_bits <= 32 ? 32 : 64;
+            const uint64_t n_words = (total_bits + 31) / 32;
+
+            Layout L;
+            hac_desc_t& d = L.d;
+            d.magic = kMagic; d.version = kVersion; d.format = HAC_FORMAT_SHAC; d.header_bytes = 256;
+            d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = nnz; d.total_bits = total_bits; d.n_words = n_words;
+            d.k_sym = (uint32_t)s.values.size(); d.lmax = lmax; d.lut_bits = lut_bits;
+            d.has_zero = 0; d.zero_len = 0; d.chunk = Cn; d.ri_bits = 0;
+            d.ent_bits = ent_bits; d.row_bits = ent_bits == 32 ? row_bits : 0; d.n_chunks = ci.n_chunks;
+            d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
+            d.ri_coding = HAC_RI_RICE; d.rice_k = k; d.gap_bits = gap_bits;
+            d.off_codebook = L.place(4ull * d.k_sym);
+            d.off_codelen = L.place(d.k_sym);
+            d.off_canon = L.place(3 * 33 * 4);
+            d.off_symsort = L.place(4ull * d.k_sym);
+            d.off_lut = L.place(4ull << lut_bits);
+            d.off_stream = L.place(4 * n_words + kTailPad);
+            d.off_col_chunk = L.place(4 * ((uint64_t)m + 1));
+            d.off_col_pos = L.place(4 * ((uint64_t)m + 1));
+            d.off_col_bit = L.place(4 * ((uint64_t)m + 1));
+            d.off_chunk_ent = L.place(ci.n_chunks * (ent_bits / 8) + 8);
+            d.blob_bytes = align_up(L.cursor);
+
+            uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
+            if (!base) return HAC_ENOMEM;
+            std::memcpy(base, &d, sizeof d);
+            write_tables(base, d, s.values, len, t, lut);
+            BitWriter bw = { reinterpret_cast<uint32_t*>(base + d.off_stream), 0 };
+            uint32_t* ent = reinterpret_cast<uint32_t*>(base + d.off_chunk_ent);
+            uint64_t chunk = 0;
+            for (int64_t j = 0; j < m; ++j) {
+                const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
+                ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
+                const uint64_t col_bit0 = bw.bitpos;
+                for (uint64_t p = p0; p < pend; ++p) {
+                    const uint32_t g = gap_at(s, p, p0);
+                    if ((p - p0) % Cn == 0) {
+                        const uint64_t rel = bw.bitpos - col_bit0;
+                        const uint64_t row = (uint64_t)s.ri[(size_t)p] - g;      // the row the gap counts from
+                        if (ent_bits == 32) ent[chunk] = (uint32_t)((rel << row_bits) | row);
+                        else { ent[2 * chunk] = (uint32_t)row; ent[2 * chunk + 1] = (uint32_t)rel; }
+                        ++chunk;
+                    }
+                    const uint32_t q = g >> k;
+                    if (q < kRiceEscape) {
+                        bw.skip(q);
+                        bw.put((1u << k) | (g & ((1u << k) - 1u)), k + 1);
+                    } else {
+                        bw.skip(kRiceEscape);
+                        bw.put(1u, 1);
+                        bw.put(g, 32);
+                    }
+                    const uint32_t sy = s.sym[(size_t)p];
+                    bw.put(t.code[sy], len[sy]);
+                }
+            }
+            ci.col_bit[(size_t)m] = (uint32_t)bw.bitpos;
+            std::memcpy(base + d.off_col_chunk, ci.col_chunk.data(), 4 * ((size_t)m + 1));
+            std::memcpy(base + d.off_col_pos, ci.col_pos.data(), 4 * ((size_t)m + 1));
+            std::memcpy(base + d.off_col_bit, ci.col_bit.data(), 4 * ((size_t)m + 1));
+            if (chunk != ci.n_chunks || bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
+            *blob = base; *blob_bytes = (size_t)d.blob_bytes;
+            return HAC_OK;
+        }
         uint64_t max_col_bits = 0;
         for (int64_t j = 0; j < m; ++j) {
             uint64_t bits = 0;
@@ -540,7 +646,8 @@ int check_header(const void* blob, size_t bytes, hac_desc_t& d)
     if (d.k_sym > d.n * d.m) return HAC_EFORMAT;
     if ((d.k_sym == 0) != (d.total_bits == 0)) return HAC_EFORMAT;
     if (d.k_sym > 0 && (d.lmax < 1)) return HAC_EFORMAT;
-    if (d.chunk < 1 || d.chunk > 65536 || d.reserved32) return HAC_EFORMAT;
+    if (d.chunk < 1 || d.chunk > 65536 || d.reserved32 || d.reserved[0] || d.reserved[1] || d.reserved[2]) return HAC_EFORMAT;
+    if (d.ri_coding > HAC_RI_RICE) return HAC_EFORMAT;
     if (d.max_col_bits > d.total_bits || d.max_col_nnz > d.nnz || d.max_col_nnz > d.n) return HAC_EFORMAT;
     const size_t tot = (size_t)d.blob_bytes;
     if (!section_ok(d, d.off_codebook, 4ull * d.k_sym, tot)) return HAC_EFORMAT;
@@ -562,8 +669,19 @@ int check_header(const void* blob, size_t bytes, hac_desc_t& d)
             if (d.row_bits != need) return HAC_EFORMAT;
             if (d.row_bits + std::max<uint32_t>(ceil_log2(d.max_col_bits + 1), 1) > 32) return HAC_EFORMAT;
         } else if (d.row_bits != 0) return HAC_EFORMAT;
-        if (d.ri_bits) return HAC_EFORMAT;
+        if (d.ri_bits || d.ri_coding || d.rice_k || d.gap_bits) return HAC_EFORMAT;
+    } else if (d.ri_coding == HAC_RI_RICE) {
+        if (d.ent_bits != 32 && d.ent_bits != 64) return HAC_EFORMAT;
+        const uint32_t need = std::max<uint32_t>(ceil_log2(d.n), 1);
+        if (d.ent_bits == 32) {
+            if (d.row_bits != need) return HAC_EFORMAT;
+            if (d.row_bits + std::max<uint32_t>(ceil_log2(d.max_col_bits + 1), 1) > 32) return HAC_EFORMAT;
+        } else if (d.row_bits != 0) return HAC_EFORMAT;
+        if (d.ri_bits || d.off_ri || d.has_zero || d.zero_len) return HAC_EFORMAT;
+        if (d.rice_k > kRiceKMax || d.gap_bits > d.total_bits) return HAC_EFORMAT;
+        if (d.gap_bits < d.nnz) return HAC_EFORMAT;                      // at least the terminating one per gap
     } else {
+        if (d.rice_k || d.gap_bits) return HAC_EFORMAT;
         if (d.ent_bits != 16 && d.ent_bits != 32) return HAC_EFORMAT;
         if (d.ent_bits == 16 && d.max_col_bits >= 65536) return HAC_EFORMAT;
         const uint32_t need = std::max<uint32_t>(ceil_log2(d.n), 1);
@@ -586,7 +704,7 @@ struct View {
     // (relative bit offset, first row) of chunk g
     void entry(uint64_t g, uint64_t& rel, uint64_t& row) const {
         row = 0;
-        if (d.format == HAC_FORMAT_HAC) {
+        if (d.format == HAC_FORMAT_HAC || d.ri_coding == HAC_RI_RICE) {
             const uint32_t* e = reinterpret_cast<const uint32_t*>(ent);
             if (d.ent_bits == 32) { rel = e[g] >> d.row_bits; row = e[g] & ((1u << d.row_bits) - 1u); }
             else { row = e[2 * g]; rel = e[2 * g + 1]; }
@@ -610,7 +728,8 @@ void make_view(const void* blob, const hac_desc_t& d, View& v)
     v.colpos = reinterpret_cast<const uint32_t*>(v.base + d.off_col_pos);
     v.colbit = reinterpret_cast<const uint32_t*>(v.base + d.off_col_bit);
     v.ent = v.base + d.off_chunk_ent;
-    v.ri = d.format == HAC_FORMAT_SHAC ? reinterpret_cast<const uint32_t*>(v.base + d.off_ri) : nullptr;
+    v.ri = (d.format == HAC_FORMAT_SHAC && d.ri_coding == HAC_RI_FIELDS)
+               ? reinterpret_cast<const uint32_t*>(v.base + d.off_ri) : nullptr;
 }
 
 // code tables must describe a complete canonical prefix code consistent with the lengths
@@ -659,6 +778,19 @@ struct SeqDecoder {
         const uint64_t w = bitpos >> 5; const uint32_t off = (uint32_t)(bitpos & 31);
         const uint64_t two = ((uint64_t)v.stream[w] << 32) | v.stream[w + 1];   // tail padding keeps w+1 in bounds
         return (uint32_t)((two << off) >> 32);
+    }
+    // Rice-coded gap, or -1 (malformed / past the end)
+    inline int64_t next_gap(uint32_t k) {
+        if (bitpos >= v.d.total_bits) return -1;
+        const uint32_t win = window();
+        if (win == 0) return -1;                                  // a one must appear within 32 bits
+        const uint32_t z = (uint32_t)__builtin_clz(win);
+        bitpos += z + 1;
+        const uint32_t bits = z < kRiceEscape ? k : 32;
+        if (bitpos + bits > v.d.total_bits) return -1;
+        uint64_t val = 0;
+        if (bits) { val = window() >> (32 - bits); bitpos += bits; }
+        return z < kRiceEscape ? (int64_t)(((uint64_t)z << k) | val) : (int64_t)val;
     }
     // returns symbol or -1 (no codeword matches / past the end)
     inline int64_t next() {
@@ -709,7 +841,7 @@ int check_index_shallow(const View& v)
             uint64_t rel, row;
             v.entry(g, rel, row);
             if (rel >= bits || row >= d.n) return HAC_EFORMAT;
-            if (g == v.colchunk[j] ? (rel != 0 || row != 0) : (rel <= prev_rel || (d.format == HAC_FORMAT_HAC && row <= prev_row)))
+            if (g == v.colchunk[j] ? (rel != 0 || row != 0) : (rel <= prev_rel || ((d.format == HAC_FORMAT_HAC || d.ri_coding == HAC_RI_RICE) && row <= prev_row)))
                 return HAC_EFORMAT;
             prev_rel = rel; prev_row = row;
         }
@@ -747,6 +879,32 @@ int check_deep(const View& v)
             if (g != v.colchunk[j + 1]) return HAC_EFORMAT;
         }
         if (pos != d.nnz || dec.bitpos != d.total_bits) return HAC_EFORMAT;
+    } else if (d.ri_coding == HAC_RI_RICE) {
+        uint64_t gap_bits = 0;
+        for (uint64_t j = 0; j < d.m; ++j) {
+            if (v.colbit[j] != dec.bitpos) return HAC_EFORMAT;
+            uint64_t g = v.colchunk[j];
+            int64_t prev = -1;
+            for (uint64_t p = v.colpos[j]; p < v.colpos[j + 1]; ++p) {
+                if ((p - v.colpos[j]) % d.chunk == 0) {
+                    uint64_t rel, row;
+                    v.entry(g, rel, row);
+                    if (rel != dec.bitpos - v.colbit[j] || row != (uint64_t)(prev + 1)) return HAC_EFORMAT;
+                    ++g;
+                }
+                const uint64_t before = dec.bitpos;
+                const int64_t gap = dec.next_gap(d.rice_k);
+                if (gap < 0) return HAC_EFORMAT;
+                if (((uint64_t)gap >> d.rice_k) >= kRiceEscape && dec.bitpos - before != kRiceEscape + 1 + 32) return HAC_EFORMAT;
+                if (((uint64_t)gap >> d.rice_k) < kRiceEscape && dec.bitpos - before == kRiceEscape + 1 + 32) return HAC_EFORMAT;
+                gap_bits += dec.bitpos - before;
+                const int64_t r = prev + 1 + gap;
+                if (r >= (int64_t)d.n) return HAC_EFORMAT;
+                prev = r;
+                if (dec.next() < 0) return HAC_EFORMAT;
+            }
+        }
+        if (dec.bitpos != d.total_bits || gap_bits != d.gap_bits) return HAC_EFORMAT;
     } else {
         for (uint64_t j = 0; j < d.m; ++j) {
             if (v.colbit[j] != dec.bitpos) return HAC_EFORMAT;
@@ -816,10 +974,11 @@ extern "C" int hac_stats(const void* blob, size_t bytes, hac_stats_t* out)
         out->paper_bits = 32 * d.n_words + 6ull * 32 * d.k_sym;
         out->bound_bits = nm * (1.0 + std::log2(k)) + 6.0 * k * 32.0;
     } else {
+        const bool rice = d.ri_coding == HAC_RI_RICE;
         out->index_bytes = 2 * 4 * (d.m + 1) + ent_bytes;
-        out->ri_bytes = 4 * ((d.nnz * d.ri_bits + 31) / 32);
+        out->ri_bytes = rice ? 0 : 4 * ((d.nnz * d.ri_bits + 31) / 32);
         out->cb_bytes = 4 * (d.m + 1);
-        out->paper_bits = 32 * d.n_words + 6ull * 32 * d.k_sym + 32 * (d.nnz + d.m + 1);
+        out->paper_bits = 32 * d.n_words + 6ull * 32 * d.k_sym + 32 * ((rice ? 0 : d.nnz) + d.m + 1);
         out->bound_bits = (double)d.nnz * (1.0 + std::log2(k)) + 32.0 * (6.0 * k + (double)d.nnz + (double)d.m + 1.0);
     }
     // entropy from the code lengths is not available; recompute symbol counts by a sequential decode
@@ -827,6 +986,7 @@ extern "C" int hac_stats(const void* blob, size_t bytes, hac_stats_t* out)
     SeqDecoder dec(v);
     const uint64_t symbols = d.format == HAC_FORMAT_HAC ? d.n * d.m : d.nnz;
     for (uint64_t i = 0; i < symbols; ++i) {
+        if (d.ri_coding == HAC_RI_RICE && dec.next_gap(d.rice_k) < 0) return HAC_EFORMAT;
         const int64_t s = dec.next();
         if (s < 0) return HAC_EFORMAT;
         cnt[(size_t)s]++;
@@ -835,7 +995,7 @@ extern "C" int hac_stats(const void* blob, size_t bytes, hac_stats_t* out)
     for (uint32_t s = 0; s < d.k_sym; ++s)
         if (cnt[s]) { const double p = (double)cnt[s] / (double)symbols; H -= p * std::log2(p); }
     out->entropy_bits = H;
-    out->avg_code_bits = symbols ? (double)d.total_bits / (double)symbols : 0.0;
+    out->avg_code_bits = symbols ? (double)(d.total_bits - d.gap_bits) / (double)symbols : 0.0;
     out->psi = (double)d.blob_bytes / (4.0 * nm);
     return HAC_OK;
 }
@@ -861,17 +1021,27 @@ extern "C" int hac_decode_host(const void* blob, size_t bytes, float* W_out, int
             }
     } else {
         if (W_out) std::memset(W_out, 0, sizeof(float) * (size_t)(d.n * d.m));
-        for (uint64_t j = 0; j < d.m; ++j)
+        const bool rice = d.ri_coding == HAC_RI_RICE;
+        for (uint64_t j = 0; j < d.m; ++j) {
+            int64_t prev = -1;
             for (uint64_t p = v.colpos[j]; p < v.colpos[j + 1]; ++p) {
+                uint64_t r;
+                if (rice) {
+                    const int64_t gap = dec.next_gap(d.rice_k);
+                    if (gap < 0) return HAC_EFORMAT;
+                    r = (uint64_t)(prev + 1 + gap);
+                    prev = (int64_t)r;
+                }
                 const int64_t s = dec.next();
                 if (s < 0) return HAC_EFORMAT;
-                const uint32_t r = ri_field(v.ri, p, d.ri_bits);
+                if (!rice) r = ri_field(v.ri, p, d.ri_bits);
                 if (r >= d.n) return HAC_EFORMAT;
                 if (sym_out) sym_out[p] = (int32_t)s;
                 if (row_out) row_out[p] = (int32_t)r;
                 if (col_out) col_out[p] = (int32_t)j;
                 if (W_out) W_out[(uint64_t)r * d.m + j] = v.codebook[s];
             }
+        }
     }
     return HAC_OK;
 }

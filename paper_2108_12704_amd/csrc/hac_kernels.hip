@@ -52,6 +52,7 @@ struct DevBlob {
     const void* ent;            // chunk entries
     const uint32_t* ri;         // sHAC
     uint32_t n, m, nnz, k_sym, lmax, lut_bits, has_zero, zero_len, chunk, ri_bits, ent_bits, row_bits, n_chunks;
+    uint32_t rice, rice_k;      // sHAC whose row gaps are Rice-coded in front of each value's codeword
 };
 
 // (relative bit offset, first row) of chunk g
@@ -251,6 +252,72 @@ __device__ __forceinline__ void shac_advance(const DevBlob& d, const Tables& tb,
     }
 }
 
+// sHAC with Rice-coded row gaps: gap codeword, then the value's codeword.  Gap d with
+// q = d >> k: q zeros, a one, k low bits of d; from q = 31 on: 31 zeros, a one, d in 32 bits.
+// st.row is the row the next gap counts from.  Words staged in LDS: one fetch of 128 bits
+// serves the unary part (count-leading-zeros), the remainder and the value's codeword.
+template <class Emit>
+__device__ __forceinline__ void gap_advance(const DevBlob& d, const Tables& tb, const WordSrc<true>& src,
+                                            ChunkState& st, uint32_t limit, Emit emit)
+{
+    lds_cu32* sw = (lds_cu32*)src.w;
+    const uint32_t k = d.rice_k;
+    while (st.wpos < limit) {
+        const uint32_t wi = (st.bp >> 5) - src.wbase, off = st.bp & 31;
+        const uint32_t w0 = sw[wi], w1 = sw[wi + 1], w2 = sw[wi + 2], w3 = sw[wi + 3];
+        const uint32_t hi = (uint32_t)(((((uint64_t)w0 << 32) | w1) << off) >> 32);
+        const uint32_t mid = (uint32_t)(((((uint64_t)w1 << 32) | w2) << off) >> 32);
+        const uint32_t lo = (uint32_t)(((((uint64_t)w2 << 32) | w3) << off) >> 32);
+        const uint32_t z = hi ? (uint32_t)__builtin_clz(hi) : 31u;        // a valid stream has a one within 32 bits
+        const uint32_t s1 = z + 1;                                        // 1..32
+        const uint32_t p0 = (uint32_t)(((((uint64_t)hi << 32) | mid) << s1) >> 32);
+        const uint32_t p1 = (uint32_t)(((((uint64_t)mid << 32) | lo) << s1) >> 32);
+        uint32_t gapv, top, used;
+        if (z < 31) {
+            const uint64_t w = (((uint64_t)p0 << 32) | p1) << k;          // k <= 15
+            gapv = (z << k) | (uint32_t)(((uint64_t)p0 << k) >> 32);
+            top = (uint32_t)(w >> 32);
+            used = s1 + k;
+        } else {
+            gapv = p0; top = p1; used = s1 + 32;
+        }
+        const Decoded q = decode_symbol(d, tb, top);
+        const uint32_t row = st.row + gapv;
+        st.bp += used + q.len;
+        st.row = row + 1;
+        emit(st.wpos, row, q.sym, q.val);
+        st.wpos++;
+    }
+}
+
+// The same from any word source, one field at a time (streams too long to stage, and the
+// test-only decode kernel).
+template <class Src, class Emit>
+__device__ __forceinline__ void gap_advance_slow(const DevBlob& d, const Tables& tb, const Src& src,
+                                                 ChunkState& st, uint32_t limit, Emit emit)
+{
+    const uint32_t k = d.rice_k;
+    while (st.wpos < limit) {
+        const uint32_t hi = src.peek32(st.bp);
+        const uint32_t z = hi ? (uint32_t)__builtin_clz(hi) : 31u;
+        st.bp += z + 1;
+        uint32_t gapv;
+        if (z < 31) {
+            gapv = (z << k) | (k ? src.peek32(st.bp) >> (32 - k) : 0u);
+            st.bp += k;
+        } else {
+            gapv = src.peek32(st.bp);
+            st.bp += 32;
+        }
+        const Decoded q = decode_symbol(d, tb, src.peek32(st.bp));
+        st.bp += q.len;
+        const uint32_t row = st.row + gapv;
+        st.row = row + 1;
+        emit(st.wpos, row, q.sym, q.val);
+        st.wpos++;
+    }
+}
+
 // column that owns chunk g: largest j with colchunk[j] <= g (global memory search)
 __device__ __forceinline__ uint32_t column_of_chunk(const DevBlob& d, uint32_t g)
 {
@@ -299,7 +366,14 @@ decode_kernel(DevBlob d, float* vals, int32_t* sym, int32_t* row_out, int32_t* c
     const uint32_t cend = d.colpos[col + 1];
     st.wend = st.wpos + d.chunk < cend ? st.wpos + d.chunk : cend;
     WordSrc<false> src = { d.stream, 0 };
-    if (SHAC) {
+    if (SHAC && d.rice) {
+        gap_advance_slow(d, tb, src, st, st.wend, [&](uint32_t p, uint32_t row, uint32_t s, float v) {
+            if (sym) sym[p] = (int32_t)s;
+            if (vals) vals[p] = v;
+            if (row_out) row_out[p] = (int32_t)row;
+            if (col_out) col_out[p] = (int32_t)col;
+        });
+    } else if (SHAC) {
         WordSrc<false> rsrc = { d.ri, 0 };
         shac_advance(d, tb, src, st, st.wend, [&](uint32_t p, uint32_t, uint32_t s, float v) {
             if (sym) sym[p] = (int32_t)s;
@@ -596,10 +670,13 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
                 };
                 if (staged) {
                     if (SHAC) shac_advance(d, tb, s_lds, st, lim, emit);
+                    else if (d.rice) gap_advance(d, tb, s_lds, st, lim, emit);
                     else if (d.zero_len == 1) hac_advance_zrun(d, tb, s_lds, st, lim, emit);
                     else hac_advance(d, tb, s_lds, st, lim, emit);
                 } else {
-                    if (SHAC) shac_advance(d, tb, s_glb, st, lim, emit); else hac_advance(d, tb, s_glb, st, lim, emit);
+                    if (SHAC) shac_advance(d, tb, s_glb, st, lim, emit);
+                    else if (d.rice) gap_advance_slow(d, tb, s_glb, st, lim, emit);
+                    else hac_advance(d, tb, s_glb, st, lim, emit);
                 }
             }
             HAC_MARK(3);
@@ -734,10 +811,13 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __r
             };
             if (staged) {
                 if (SHAC) shac_advance(d, tb, s_lds, st, st.wend, emit);
+                else if (d.rice) gap_advance(d, tb, s_lds, st, st.wend, emit);
                 else if (d.zero_len == 1) hac_advance_zrun(d, tb, s_lds, st, st.wend, emit);
                 else hac_advance(d, tb, s_lds, st, st.wend, emit);
             } else {
-                if (SHAC) shac_advance(d, tb, s_glb, st, st.wend, emit); else hac_advance(d, tb, s_glb, st, st.wend, emit);
+                if (SHAC) shac_advance(d, tb, s_glb, st, st.wend, emit);
+                else if (d.rice) gap_advance_slow(d, tb, s_glb, st, st.wend, emit);
+                else hac_advance(d, tb, s_glb, st, st.wend, emit);
             }
         }
         const uint32_t key = active ? rel : 0xffffffffu;
@@ -779,6 +859,10 @@ int make_dev(const hac_desc_t* desc, const void* d_blob, uint32_t format, DevBlo
         desc->n_chunks > 0xfffffff0ull || desc->chunk < 1 || desc->chunk > 65536) return HAC_EINVAL;
     if (desc->ent_bits != 16 && desc->ent_bits != 32 && desc->ent_bits != 64) return HAC_EINVAL;
     if (desc->row_bits > 31 || desc->ri_bits > 32) return HAC_EINVAL;
+    const bool rice = format == HAC_FORMAT_SHAC && desc->ri_coding == HAC_RI_RICE;
+    if (desc->ri_coding > HAC_RI_RICE || (format == HAC_FORMAT_HAC && desc->ri_coding)) return HAC_EINVAL;
+    if (rice && (desc->rice_k > 15 || desc->ri_bits || desc->ent_bits == 16)) return HAC_EINVAL;
+    if (format == HAC_FORMAT_SHAC && !rice && (desc->ri_bits < 1 || desc->ent_bits == 64)) return HAC_EINVAL;
     const uint8_t* b = static_cast<const uint8_t*>(d_blob);
     d.codebook = reinterpret_cast<const float*>(b + desc->off_codebook);
     d.canon = reinterpret_cast<const uint32_t*>(b + desc->off_canon);
@@ -789,7 +873,8 @@ int make_dev(const hac_desc_t* desc, const void* d_blob, uint32_t format, DevBlo
     d.colpos = reinterpret_cast<const uint32_t*>(b + desc->off_col_pos);
     d.colbit = reinterpret_cast<const uint32_t*>(b + desc->off_col_bit);
     d.ent = b + desc->off_chunk_ent;
-    d.ri = format == HAC_FORMAT_SHAC ? reinterpret_cast<const uint32_t*>(b + desc->off_ri) : nullptr;
+    d.ri = (format == HAC_FORMAT_SHAC && !rice) ? reinterpret_cast<const uint32_t*>(b + desc->off_ri) : nullptr;
+    d.rice = rice ? 1u : 0u; d.rice_k = desc->rice_k;
     d.n = (uint32_t)desc->n; d.m = (uint32_t)desc->m; d.nnz = (uint32_t)desc->nnz;
     d.k_sym = desc->k_sym; d.lmax = desc->lmax; d.lut_bits = desc->lut_bits;
     d.has_zero = desc->has_zero; d.zero_len = desc->zero_len; d.chunk = desc->chunk;
@@ -885,7 +970,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         if (tile_b < pass_w) return HAC_EINVAL;
     }
     const uint32_t nwaves = (d.m + cpw - 1) / cpw;
-    const bool shac = format == HAC_FORMAT_SHAC;
+    const bool shac = format == HAC_FORMAT_SHAC && !d.rice;   // Rice-coded gaps decode like a HAC stream: no ri words
     g_last_hip_error = 0;
 
     const BatchShape bs = batch_shape(B, pass_w, tile_b);

@@ -59,8 +59,9 @@ def test_full_size_dot(hac, cfg):
     cols = np.unique(np.concatenate((cols, [0, c.m - 1])))
     hb = hac.hac_encode(W)
     sb = hac.shac_encode(W)
-    assert hb.validate(deep=False) == 0 and sb.validate(deep=False) == 0
-    dh, ds = hb.to_device(dev), sb.to_device(dev)
+    gb = hac.shac_encode(W, ri_coding=hac.RI_RICE)          # Rice-coded row gaps (extension)
+    assert hb.validate(deep=False) == 0 and sb.validate(deep=False) == 0 and gb.validate(deep=False) == 0
+    dh, ds, dg = hb.to_device(dev), sb.to_device(dev), gb.to_device(dev)
     for B in c.batches:
         print(f"[case] full cfg{cfg} B={B}", flush=True)
         X = workloads.make_batch(B, c.n, 1000 * cfg + 1)
@@ -68,9 +69,14 @@ def test_full_size_dot(hac, cfg):
         Xd = torch.from_numpy(X).to(dev)
         Yh = hac.hac_dot(dh, Xd)
         Ys = hac.shac_dot(ds, Xd)
+        Yg = hac.shac_dot(dg, Xd)
         torch.cuda.synchronize()
         check_sampled(Yh, X, W, cols, rows, f"hac cfg{cfg} B={B}")
         check_sampled(Ys, X, W, cols, rows, f"shac cfg{cfg} B={B}")
+        check_sampled(Yg, X, W, cols, rows, f"shac/rice cfg{cfg} B={B}")
+        assert torch.isfinite(Yg).all()
+        assert (Yh - Yg).abs().max().item() <= 4 * TOL * max(Yh.abs().max().item(), 1e-30)
+        del Yg
         # properties that hold at any size: Y is finite everywhere, and the two formats, which
         # hold the same matrix, agree to rounding on every output (not only the sampled ones)
         assert torch.isfinite(Yh).all() and torch.isfinite(Ys).all()
@@ -95,6 +101,14 @@ def test_full_size_decode(hac, cfg):
     values, sym, row, col = formats.shac_symbols(W)
     sb = hac.shac_encode(W)
     nz, symd, rowd, cold = hac.shac_decode_dev(sb.to_device(dev))
+    torch.cuda.synchronize()
+    assert np.array_equal(symd.cpu().numpy().astype(np.int64), sym)
+    assert np.array_equal(rowd.cpu().numpy().astype(np.int64), row)
+    assert np.array_equal(cold.cpu().numpy().astype(np.int64), col)
+    assert np.array_equal(nz.cpu().numpy().view(np.uint32), values[sym].view(np.uint32))
+    del nz, symd, rowd, cold
+    gb = hac.shac_encode(W, ri_coding=hac.RI_RICE)
+    nz, symd, rowd, cold = hac.shac_decode_dev(gb.to_device(dev))
     torch.cuda.synchronize()
     assert np.array_equal(symd.cpu().numpy().astype(np.int64), sym)
     assert np.array_equal(rowd.cpu().numpy().astype(np.int64), row)

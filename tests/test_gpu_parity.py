@@ -73,7 +73,8 @@ def test_hac_decode_bit_exact(hac, name, W):
 def test_shac_decode_bit_exact(hac, name, W):
     print(f"[case] shac_decode {name} {W.shape}", flush=True)
     values, sym, row, col = formats.shac_symbols(W)
-    for kw in (dict(), dict(chunk_nnz=5), dict(ri_bits=32), dict(lut_bits=2)):
+    for kw in (dict(), dict(chunk_nnz=5), dict(ri_bits=32), dict(lut_bits=2),
+               dict(ri_coding=1), dict(ri_coding=1, chunk_nnz=3), dict(ri_coding=1, lut_bits=2, chunk_nnz=1000)):
         blob = hac.shac_encode(W, **kw)
         nz, symd, rowd, cold = hac.shac_decode_dev(blob.to_device(dev()))
         torch.cuda.synchronize()
@@ -91,15 +92,18 @@ def test_dot_parity_small(hac, name, W):
     n, m = W.shape
     hb = hac.hac_encode(W).to_device(dev())
     sb = hac.shac_encode(W).to_device(dev())
+    gb = hac.shac_encode(W, ri_coding=1).to_device(dev())               # Rice-coded row gaps
     for B in BATCHES:
         print(f"[case] dot {name} {W.shape} B={B}", flush=True)
         X = workloads.make_batch(B, n, 77 + B) - np.float32(0.125)      # a few negative inputs too
         Xd = torch.from_numpy(X).to(dev())
         Yh = hac.hac_dot(hb, Xd)
         Ys = hac.shac_dot(sb, Xd)
+        Yg = hac.shac_dot(gb, Xd)
         torch.cuda.synchronize()
         check_y(Yh, X, W, f"hac {name} B={B}")
         check_y(Ys, X, W, f"shac {name} B={B}")
+        check_y(Yg, X, W, f"shac/rice {name} B={B}")
 
 
 @pytest.mark.parametrize("name", sorted(workloads.stress_cases().keys()))
@@ -121,15 +125,23 @@ def test_stress_cases(hac, name):
     assert np.array_equal(srow.cpu().numpy().astype(np.int64), s_row)
     assert np.array_equal(scol.cpu().numpy().astype(np.int64), s_col)
     assert np.array_equal(nz.cpu().numpy().view(np.uint32), svalues[s_sym].view(np.uint32))
-    dh, ds = hb.to_device(dev()), sb.to_device(dev())
+    gb = hac.shac_encode(W, ri_coding=1)
+    nz, ssym, srow, scol = hac.shac_decode_dev(gb.to_device(dev()))
+    torch.cuda.synchronize()
+    assert np.array_equal(ssym.cpu().numpy().astype(np.int64), s_sym)
+    assert np.array_equal(srow.cpu().numpy().astype(np.int64), s_row)
+    assert np.array_equal(scol.cpu().numpy().astype(np.int64), s_col)
+    dh, ds, dg = hb.to_device(dev()), sb.to_device(dev()), gb.to_device(dev())
     for B in (1, 5, 32, 70):
         X = workloads.make_batch(B, n, 11 + B) - np.float32(0.25)
         Xd = torch.from_numpy(X).to(dev())
         Yh = hac.hac_dot(dh, Xd)
         Ys = hac.shac_dot(ds, Xd)
+        Yg = hac.shac_dot(dg, Xd)
         torch.cuda.synchronize()
         check_y(Yh, X, W, f"hac {name} B={B}")
         check_y(Ys, X, W, f"shac {name} B={B}")
+        check_y(Yg, X, W, f"shac/rice {name} B={B}")
 
 
 def test_dot_other_encoder_options(hac):
@@ -155,7 +167,8 @@ def test_launch_overrides_do_not_change_the_result(hac):
     n, m = W.shape
     X = workloads.make_batch(40, n, 9)
     Xd = torch.from_numpy(X).to(dev())
-    for enc, f in ((hac.hac_encode, hac.hac_dot), (hac.shac_encode, hac.shac_dot)):
+    rice_encode = lambda W: hac.shac_encode(W, ri_coding=1)
+    for enc, f in ((hac.hac_encode, hac.hac_dot), (hac.shac_encode, hac.shac_dot), (rice_encode, hac.shac_dot)):
         db = enc(W).to_device(dev())
         for cpw, wpb, cap, sbuf in ((1, 1, 64, 0), (3, 2, 64, 16), (7, 4, 128, 64), (32, 4, 2048, 4096), (5, 16, 256, 0),
                                     (2, 3, 1024, 0)):
@@ -177,7 +190,9 @@ def test_small_batches_through_both_kernels(hac):
                     ("empty_columns", workloads.edge_cases()["empty_columns"])):
         n, m = W.shape
         for enc, f, kw in ((hac.hac_encode, hac.hac_dot, dict()), (hac.shac_encode, hac.shac_dot, dict()),
-                           (hac.hac_encode, hac.hac_dot, dict(chunk_nnz=1)), (hac.shac_encode, hac.shac_dot, dict(chunk_nnz=2))):
+                           (hac.hac_encode, hac.hac_dot, dict(chunk_nnz=1)), (hac.shac_encode, hac.shac_dot, dict(chunk_nnz=2)),
+                           (hac.shac_encode, hac.shac_dot, dict(ri_coding=1)),
+                           (hac.shac_encode, hac.shac_dot, dict(ri_coding=1, chunk_nnz=2))):
             db = enc(W, **kw).to_device(dev())
             for B in (1, 2, 3, 4):
                 X = workloads.make_batch(B, n, 5 + B) - np.float32(0.5)

@@ -59,7 +59,7 @@ def chunk_entries(blob):
     """[(relative bit offset, first row)] per chunk, unpacked from the blob."""
     d = blob.desc
     nch = int(d.n_chunks)
-    if d.format == hac.HAC_FORMAT_HAC:
+    if d.format == hac.HAC_FORMAT_HAC or d.ri_coding == hac.RI_RICE:
         if d.ent_bits == 32:
             e = blob.section("off_chunk_ent", np.uint32, nch)
             rb = int(d.row_bits)
@@ -178,6 +178,100 @@ def test_shac_blob_against_oracle(name, W):
         lens, words = codes_from_blob(blob)
         stream = blob.section("off_stream", np.uint32, int(d.n_words))
         assert np.array_equal(oracle_decode_bits(stream, os_.q, words), sym)
+
+
+@pytest.mark.parametrize("name,W", LAYERS, ids=IDS)
+def test_rice_coded_shac_blob_against_oracle(name, W):
+    """sHAC with Rice-coded row gaps (extension): same bits, same k, same decoded CSC as the oracle;
+    the stream parses gap by gap with the oracle's codeword strings; index entries point at gap starts."""
+    from oracle import gapcode
+    n, m = W.shape
+    blob = hac.shac_encode(W, chunk_nnz=7, ri_coding=hac.RI_RICE)
+    assert blob.validate(deep=True) == 0
+    d = blob.desc
+    og = gapcode.shacg_encode(W)
+    values, sym, row, col, gaps = gapcode.shacg_symbols(W)
+    assert int(d.ri_coding) == hac.RI_RICE and int(d.ri_bits) == 0 and int(d.off_ri) == 0
+    assert int(d.total_bits) == og.nbits and int(d.gap_bits) == og.gap_bits and int(d.n_words) == og.N
+    assert int(d.rice_k) == og.k and int(d.nnz) == og.q and int(d.k_sym) == len(values)
+    Wd, symd, rowd, cold = blob.decode_host()
+    assert np.array_equal(Wd.view(np.uint32), W.view(np.uint32))
+    assert np.array_equal(symd, sym) and np.array_equal(rowd, row) and np.array_equal(cold, col)
+    assert np.array_equal(blob.section("off_col_pos", np.uint32, m + 1), og.cb)
+    lens_s = blob.section("off_codelen", np.uint8, len(values)).astype(int)
+    per = gapcode.rice_lengths(gaps, og.k) + (lens_s[sym] if og.q else 0)
+    cum = np.concatenate(([0], np.cumsum(per))).astype(np.int64)
+    assert np.array_equal(blob.section("off_col_bit", np.uint32, m + 1), cum[og.cb])
+    ents = chunk_entries(blob)
+    g = 0
+    for j in range(m):
+        for p in range(int(og.cb[j]), int(og.cb[j + 1]), int(d.chunk)):
+            base_row = 0 if p == og.cb[j] else int(row[p - 1]) + 1
+            assert ents[g] == (cum[p] - cum[og.cb[j]], base_row)
+            g += 1
+    assert g == int(d.n_chunks)
+    if og.q:
+        # parse the library's stream with the oracle's gap codewords and the blob's own value codewords
+        lens, words = codes_from_blob(blob)
+        stream = blob.section("off_stream", np.uint32, int(d.n_words))
+        bits = "".join(format(int(w), "032b") for w in stream)
+        pos = 0
+        for p in range(og.q):
+            gw = gapcode.rice_bits(int(gaps[p]), og.k)
+            assert bits.startswith(gw, pos), p
+            pos += len(gw)
+            cur = ""
+            while cur not in words:
+                cur += bits[pos]; pos += 1
+            assert words[cur] == sym[p]
+        assert pos == og.nbits and set(bits[pos:]) <= {"0"}
+    st = blob.stats()
+    assert st.ri_bytes == 0 and st.paper_bits == gapcode.shacg_paper_bits(og)
+    assert st.paper_bits <= st.bound_bits
+    assert blob.nbytes <= hac.shac_encode(W, chunk_nnz=7).nbytes
+
+
+def test_rice_coding_argument_checks_and_damage():
+    import ctypes as C
+    W = workloads.scaled(4, 900, 30)
+    with pytest.raises(hac.HacError):
+        hac.shac_encode(W, ri_coding=2)
+    with pytest.raises(hac.HacError):
+        hac.shac_encode(W, ri_coding=hac.RI_RICE, ri_bits=32)
+    lib = hac.load_library()
+    out, size = C.c_void_p(), C.c_size_t()
+    opts = hac.Opts(0, 0, 0, hac.RI_RICE)
+    Wc = np.ascontiguousarray(W)
+    rc = lib.hac_encode(Wc.ctypes.data_as(C.POINTER(C.c_float)), 900, 30, 30, C.byref(opts), C.byref(out), C.byref(size))
+    assert rc == -1 and not out.value
+    blob = hac.shac_encode(W, ri_coding=hac.RI_RICE)
+    assert blob.validate(deep=True) == 0
+    off = int(blob.desc.off_stream)
+
+    def damaged(at, value=None, flip=0, deep=1):
+        b = blob.data.copy()
+        b[at] = value if value is not None else b[at] ^ flip
+        return lib.hac_validate(b.ctypes.data, b.size, deep)
+
+    for byte in (0, 5, 40):
+        assert damaged(off + byte, flip=0x10) in (0, -3)    # decodes to some other matrix or fails, never crashes
+    assert damaged(off, flip=0x80) == -3                    # first gap codeword now disagrees with the index / counts
+    assert damaged(hac.Desc.rice_k.offset, value=16, deep=0) == -3
+    assert damaged(hac.Desc.gap_bits.offset, flip=1) == -3
+    assert damaged(hac.Desc.ri_coding.offset, value=0) == -3
+
+
+def test_rice_escape_form_for_huge_gaps():
+    from oracle import gapcode
+    W = workloads.stress_cases()["clustered_rows_300000x3"]
+    og = gapcode.shacg_encode(W)
+    values, sym, row, col, gaps = gapcode.shacg_symbols(W)
+    assert int((gaps >> og.k).max()) >= 31                   # the escape form occurs
+    blob = hac.shac_encode(W, ri_coding=hac.RI_RICE)
+    assert blob.validate(deep=True) == 0
+    assert int(blob.desc.total_bits) == og.nbits and int(blob.desc.rice_k) == og.k
+    _, symd, rowd, cold = blob.decode_host(want_w=False)
+    assert np.array_equal(symd, sym) and np.array_equal(rowd, row) and np.array_equal(cold, col)
 
 
 def test_ri_bits_32_and_small_tables_still_round_trip():

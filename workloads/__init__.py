@@ -211,6 +211,13 @@ def stress_cases() -> Dict[str, np.ndarray]:
     tall[mask] = rng.choice(np.array([-1.5, -0.5, 0.25, 0.75, 1.0, 2.0, 3.5, 4.0, 6.0], dtype=np.float32),
                             size=int(mask.sum()))
     out["tall_dense_70000x2"] = tall
+    # dense clusters of rows far apart: small row gaps with a few enormous ones
+    cl = np.zeros((300000, 3), dtype=np.float32)
+    for j, starts in enumerate(((5, 120000, 299000), (0, 250000), (150000,))):
+        for s0 in starts:
+            rows = s0 + np.flatnonzero(rng.random(900) < 0.7)
+            cl[rows, j] = rng.choice(np.array([-2.0, -1.0, 0.5, 1.5], dtype=np.float32), size=rows.size)
+    out["clustered_rows_300000x3"] = cl
     return out
 
 
