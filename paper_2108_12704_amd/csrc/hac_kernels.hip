@@ -23,8 +23,8 @@
 
 #include "../../include/hac.h"
 
-// Optional phase timing (build with -DHAC_PHASE_TIMING): lane 0 of each wave of the batch
-// kernel stores a 100 MHz clock at phase boundaries; hac_debug_phases() copies them out.
+// Optional phase timing (build with -DHAC_PHASE_TIMING): lane 0 of each wave of the dot
+// kernels stores a 100 MHz clock at phase boundaries; hac_debug_phases() copies them out.
 #ifdef HAC_PHASE_TIMING
 __device__ unsigned long long g_phase[16384 * 8];
 #define HAC_MARK(k) do { if (lane == 0 && wave < 16384) g_phase[wave * 8 + (k)] = wall_clock64(); } while (0)
@@ -733,6 +733,7 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __r
     const uint32_t wave = lb * (blockDim.x / kWave) + wib;
     const uint32_t c0 = wave * cpw;
     const bool live = lb < nblocks && c0 < d.m;
+    HAC_MARK(0);
     uint32_t ncols = 0, cchunk_l = 0, cpos_l = 0, cbit_l = 0;
     if (live) {
         const uint32_t cend = c0 + cpw < d.m ? c0 + cpw : d.m;
@@ -746,6 +747,7 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __r
     const Tables tb = load_tables(d, smem);
     __syncthreads();
     if (!live) return;
+    HAC_MARK(1);
     const uint32_t gfirst = (uint32_t)__shfl((int)cchunk_l, 0, kWave);
     const uint32_t g1 = (uint32_t)__shfl((int)cchunk_l, (int)ncols, kWave);
     const uint32_t posbase = (uint32_t)__shfl((int)cpos_l, 0, kWave);
@@ -770,6 +772,7 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __r
         if (SHAC) stage_words(sbuf + snw, d.ri, rwlo, rnw, lane);
     }
     wave_sync();
+    HAC_MARK(2);
     const WordSrc<true> s_lds = { sbuf, swlo };
     const WordSrc<false> s_glb = { d.stream, 0 };
     const WordSrc<true> r_lds = { sbuf + snw, rwlo };
@@ -820,6 +823,7 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __r
                 else hac_advance(d, tb, s_glb, st, st.wend, emit);
             }
         }
+        HAC_MARK(3);
         const uint32_t key = active ? rel : 0xffffffffu;
         const uint32_t key_up = (uint32_t)__shfl_up((int)key, 1, kWave);
         const bool head = active && (lane == 0 || key_up != key);
@@ -834,12 +838,15 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __r
             if (head) colsum[rel * NB + i] += v;
         }
         wave_sync();                                         // the next batch may continue the same column
+        HAC_MARK(4);
     }
     for (uint32_t j = lane; j < ncols; j += kWave) {
 #pragma unroll
         for (int i = 0; i < NB; ++i)
             if ((uint32_t)i < B) Y[(uint64_t)i * ldy + c0 + j] = colsum[j * NB + i];
     }
+    HAC_MARK(5);
+    HAC_MARK(6);
 }
 
 // ---------------------------------------------------------------------------
