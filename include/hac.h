@@ -11,6 +11,12 @@
  *   dot  (Algorithms 1-3): Y = X.W where W is the decoded matrix; X holds one
  *        input vector per row.
  *
+ *   IM   (Sect. III-C1, "index map"): the k representatives in a vector and one
+ *        pointer per entry of W (8 bits for k <= 256, else 16); the form the
+ *        paper uses for quantized, unpruned (convolutional) layers.  Pointers
+ *        number the values like the HAC alphabet: 0.0 first when it occurs,
+ *        then ascending.
+ *
  * An extension beyond the paper, selected with hac_opts_t.ri_coding =
  * HAC_RI_RICE: sHAC whose row-index vector ri is replaced by Golomb-Rice coded
  * row gaps written into the stream itself.  For the non-zero at CSC position p
@@ -62,7 +68,7 @@ typedef enum {
     HAC_EWORKSPACE = -6    /* workspace missing or smaller than hac_workspace_bytes()    */
 } hac_status;
 
-enum { HAC_FORMAT_HAC = 1, HAC_FORMAT_SHAC = 2 };
+enum { HAC_FORMAT_HAC = 1, HAC_FORMAT_SHAC = 2, HAC_FORMAT_IM = 3 };
 
 /* A hipStream_t, spelled without pulling in the HIP headers. */
 typedef void *hac_stream_t;
@@ -138,8 +144,16 @@ typedef struct {
     uint32_t rice_k;       /* HAC_RI_RICE: the parameter k                                 */
     uint32_t reserved32;
     uint64_t gap_bits;     /* HAC_RI_RICE: part of total_bits spent on the gap codewords   */
-    uint64_t reserved[3];
+    uint64_t idx_pitch;    /* IM: elements from one row of the index map to the next, a
+                              multiple of 16; the columns past m hold 0                    */
+    uint64_t reserved[2];
 } hac_desc_t;
+
+/* An IM blob uses the header like this: format = HAC_FORMAT_IM; k_sym
+ * representatives at off_codebook; ent_bits = 8 or 16, the width of a pointer;
+ * the index map at off_stream, n rows of idx_pitch pointers, row-major (followed
+ * by >= 64 bytes of zeros); total_bits = ent_bits * n * m, the paper's bbar*n*m;
+ * has_zero as for HAC.  Every other offset and count is 0. */
 
 /* Sizes as the paper accounts for them (Sect. IV-B/IV-C) next to the real ones. */
 typedef struct {
@@ -190,7 +204,16 @@ typedef struct {
  * lanes that each own batch columns).  Same result up to summation order. */
 #define HAC_LAUNCH_LIST_KERNEL 0x200u
 
+/* Force one of the two routes of hac_dot / shac_dot (not both). */
+#define HAC_LAUNCH_SPARSE_ROUTE 0x400u
+#define HAC_LAUNCH_DENSE_ROUTE  0x800u
+
 /* ---- host side ------------------------------------------------------------ */
+
+/* Encode W as an index map (Sect. III-C1).  opts must be NULL.  Same ownership and
+ * errors as hac_encode; more than 65536 distinct values give HAC_ERANGE. */
+int im_encode(const float *W, int64_t n, int64_t m, int64_t ldw,
+              const hac_opts_t *opts, void **blob, size_t *blob_bytes);
 
 /* Encode W (host, row-major, leading dimension ldw >= m) into a HAC blob
  * (Sect. IV-B).  -0.0 is stored as +0.0; NaN/Inf give HAC_EINVAL.  n, m >= 1.
@@ -229,16 +252,28 @@ int hac_decode_host(const void *blob, size_t bytes, float *W_out, int32_t *sym_o
 
 /* ---- device side (asynchronous on `stream`) -------------------------------- */
 
-/* Bytes of device workspace hac_dot / shac_dot need for a batch of B rows
- * (0 when none is needed).  The workspace holds X re-laid out feature-major. */
+/* Bytes of device workspace hac_dot / shac_dot need for a batch of B rows with
+ * default launch settings (0 when none is needed).  The workspace holds X re-laid
+ * out feature-major, or, on the dense route (see hac_dot), the decoded index map
+ * of W.  A launch that forces the other route may need more: size the workspace
+ * with hac_workspace_bytes_for(). */
 size_t hac_workspace_bytes(const hac_desc_t *desc, int64_t B);
+size_t hac_workspace_bytes_for(const hac_desc_t *desc, int64_t B, const hac_launch_t *launch);
 
 /* Y[B x m] = X[B x n] . W with W given as a HAC blob on the device
  * (Algorithm 1 for every row of X as in Algorithm 3; the stream is decoded
  * once per launch, not once per row).  Y is overwritten.  d_blob must be
  * 256-byte aligned, d_ws 256-byte aligned and >= hac_workspace_bytes().
  * B = 0 is a no-op.  fp32 accumulation; the order of the additions is fixed,
- * so results are bitwise reproducible run to run. */
+ * so results are bitwise reproducible run to run.
+ *
+ * Two routes.  Sparse (default): every non-zero is decoded and applied to the
+ * batch by vector FMAs.  Dense: when at least a fifth of W is non-zero and
+ * B >= 128 the product is a dense contraction in all but name; the stream is
+ * then decoded once into an index map (Sect. III-C1) in the workspace and
+ * multiplied tile by tile on the matrix cores (fp32 MFMA).  The route follows
+ * from desc and B alone; HAC_LAUNCH_SPARSE_ROUTE / HAC_LAUNCH_DENSE_ROUTE in
+ * launch->variant force one (the dense route needs at most 65536 symbols). */
 int hac_dot(const hac_desc_t *desc, const void *d_blob,
             const float *d_X, int64_t B, int64_t ldx,
             float *d_Y, int64_t ldy,
@@ -252,6 +287,16 @@ int shac_dot(const hac_desc_t *desc, const void *d_blob,
              float *d_Y, int64_t ldy,
              void *d_ws, size_t ws_bytes,
              const hac_launch_t *launch, hac_stream_t stream);
+
+/* Y = X . W for an index-map blob (Sect. III-C1): pointers are expanded through
+ * the representatives tile by tile and multiplied on the matrix cores (fp32 in,
+ * fp32 accumulate).  No workspace is used (d_ws may be NULL); launch must be
+ * NULL.  Otherwise as hac_dot. */
+int im_dot(const hac_desc_t *desc, const void *d_blob,
+           const float *d_X, int64_t B, int64_t ldx,
+           float *d_Y, int64_t ldy,
+           void *d_ws, size_t ws_bytes,
+           const hac_launch_t *launch, hac_stream_t stream);
 
 /* TEST ONLY: materialise what the device decoder sees.
  * d_W  : n*m floats, row-major (every entry written);

@@ -18,11 +18,12 @@ _lib: Optional[C.CDLL] = None
 
 HAC_FORMAT_HAC = 1
 HAC_FORMAT_SHAC = 2
+HAC_FORMAT_IM = 3
 
 EXPORTS = (
     "hac_encode", "shac_encode", "hac_free", "hac_validate", "hac_describe", "hac_stats",
-    "hac_decode_host", "hac_workspace_bytes", "hac_dot", "shac_dot", "hac_decode_dev",
-    "shac_decode_dev", "hac_strerror", "hac_last_hip_error",
+    "hac_decode_host", "hac_workspace_bytes", "hac_workspace_bytes_for", "hac_dot", "shac_dot", "hac_decode_dev",
+    "shac_decode_dev", "hac_strerror", "hac_last_hip_error", "im_encode", "im_dot",
 )
 
 
@@ -57,7 +58,7 @@ class Desc(C.Structure):
                 ("blob_bytes", C.c_uint64), ("max_col_bits", C.c_uint64), ("max_col_nnz", C.c_uint64),
                 ("row_bits", C.c_uint32), ("ri_coding", C.c_uint32),
                 ("rice_k", C.c_uint32), ("reserved32", C.c_uint32),
-                ("gap_bits", C.c_uint64), ("reserved", C.c_uint64 * 3)]
+                ("gap_bits", C.c_uint64), ("idx_pitch", C.c_uint64), ("reserved", C.c_uint64 * 2)]
 
 
 class Stats(C.Structure):
@@ -89,6 +90,7 @@ def load_library() -> C.CDLL:
                 C.POINTER(vp), C.POINTER(C.c_size_t)]
     lib.hac_encode.argtypes = enc_args
     lib.shac_encode.argtypes = enc_args
+    lib.im_encode.argtypes = enc_args
     lib.hac_free.argtypes = [vp]
     lib.hac_free.restype = None
     lib.hac_validate.argtypes = [vp, C.c_size_t, C.c_int]
@@ -97,10 +99,13 @@ def load_library() -> C.CDLL:
     lib.hac_decode_host.argtypes = [vp, C.c_size_t, f32p, i32p, i32p, i32p]
     lib.hac_workspace_bytes.argtypes = [C.POINTER(Desc), C.c_int64]
     lib.hac_workspace_bytes.restype = C.c_size_t
+    lib.hac_workspace_bytes_for.argtypes = [C.POINTER(Desc), C.c_int64, C.POINTER(Launch)]
+    lib.hac_workspace_bytes_for.restype = C.c_size_t
     dot_args = [C.POINTER(Desc), vp, vp, C.c_int64, C.c_int64, vp, C.c_int64,
                 vp, C.c_size_t, C.POINTER(Launch), vp]
     lib.hac_dot.argtypes = dot_args
     lib.shac_dot.argtypes = dot_args
+    lib.im_dot.argtypes = dot_args
     lib.hac_decode_dev.argtypes = [C.POINTER(Desc), vp, vp, vp, vp]
     lib.shac_decode_dev.argtypes = [C.POINTER(Desc), vp, vp, vp, vp, vp, vp]
     lib.hac_strerror.argtypes = [C.c_int]
@@ -149,7 +154,7 @@ class Blob:
         W = np.empty((n, m), dtype=np.float32) if want_w else None
         f32p, i32p = C.POINTER(C.c_float), C.POINTER(C.c_int32)
         wp = W.ctypes.data_as(f32p) if want_w else None
-        if d.format == HAC_FORMAT_HAC:
+        if d.format in (HAC_FORMAT_HAC, HAC_FORMAT_IM):
             sym = np.empty(n * m, dtype=np.int32)
             _check(load_library().hac_decode_host(self.data.ctypes.data, self.data.size, wp,
                                                   sym.ctypes.data_as(i32p), None, None), "hac_decode_host")
@@ -221,8 +226,29 @@ def shac_encode(W: np.ndarray, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: i
     return _encode("shac_encode", W, chunk_nnz=chunk_nnz, ri_bits=ri_bits, lut_bits=lut_bits, ri_coding=ri_coding)
 
 
-def hac_workspace_bytes(desc: Desc, B: int) -> int:
-    return int(load_library().hac_workspace_bytes(C.byref(desc), B))
+def im_encode(W: np.ndarray) -> Blob:
+    """W (n x m float32, host) -> index-map blob (Sect. III-C1)."""
+    W = np.asarray(W)
+    if W.dtype != np.float32 or W.ndim != 2:
+        raise TypeError("W must be a 2-D float32 array")
+    W = np.ascontiguousarray(W)
+    lib = load_library()
+    out, size = C.c_void_p(), C.c_size_t()
+    rc = lib.im_encode(W.ctypes.data_as(C.POINTER(C.c_float)), W.shape[0], W.shape[1], W.shape[1], None,
+                       C.byref(out), C.byref(size))
+    _check(rc, "im_encode")
+    try:
+        data = np.ctypeslib.as_array(C.cast(out, C.POINTER(C.c_uint8)), shape=(size.value,)).copy()
+    finally:
+        lib.hac_free(out)
+    return Blob(data)
+
+
+def hac_workspace_bytes(desc: Desc, B: int, launch: Optional["Launch"] = None) -> int:
+    """Workspace bytes of a dot call; with `launch`, for that launch's route."""
+    if launch is None:
+        return int(load_library().hac_workspace_bytes(C.byref(desc), B))
+    return int(load_library().hac_workspace_bytes_for(C.byref(desc), B, C.byref(launch)))
 
 
 def _stream_handle(stream) -> int:
@@ -246,7 +272,7 @@ def _dot(fn_name: str, dblob: DeviceBlob, X, Y=None, workspace=None, launch: Opt
         Y = torch.empty((B, dblob.m), dtype=torch.float32, device=X.device)
     elif Y.dtype != torch.float32 or Y.shape != (B, dblob.m) or Y.stride(1) != 1 or not Y.is_cuda:
         raise TypeError("Y must be a B x m float32 CUDA tensor with unit column stride")
-    need = hac_workspace_bytes(dblob.desc, B)
+    need = hac_workspace_bytes(dblob.desc, B, launch)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
@@ -269,6 +295,11 @@ def hac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=No
 def shac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=None):
     """Y = X . W for an sHAC blob on the device (asynchronous on the stream)."""
     return _dot("shac_dot", dblob, X, Y, workspace, launch, stream)
+
+
+def im_dot(dblob: DeviceBlob, X, Y=None, stream=None):
+    """Y = X . W for an index-map blob on the device (asynchronous on the stream)."""
+    return _dot("im_dot", dblob, X, Y, None, None, stream)
 
 
 def hac_decode_dev(dblob: DeviceBlob, stream=None):

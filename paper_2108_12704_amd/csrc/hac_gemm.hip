@@ -1,0 +1,231 @@
+// Dense-tile product for an index-mapped matrix on gfx950 (MI355X):
+//     Y[b][j] = sum_i X[b][i] * c[Pi[i][j]]
+// (arXiv 2108.12704 Sect. III-C1: representatives in a vector c, pointers to them
+// in the index map Pi; the form the paper uses for layers that are quantized but
+// hardly pruned, where the product really is a dense contraction).
+//
+// The pointers are what is read from memory (1 or 2 bytes per weight); a tile of
+// them is turned into fp32 through a copy of c in LDS and multiplied on the
+// matrix cores with v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate, so the
+// result keeps the accuracy of the vector path).
+//
+// Tiling: a block of 4 wavefronts owns 128 batch rows x 128 columns of Y and walks
+// K = n in steps of 32; wavefront (wm, wn) owns a 64 x 64 quarter as 2 x 2 MFMA
+// tiles (64 accumulator registers).  LDS holds the X tile k-major (lanes read 32
+// consecutive batch rows of one k) and the decoded W tile k-major (32 consecutive
+// columns of one k); both are double buffered, the next tile's global loads are
+// issued before the MFMA loop of the current one and stored after it.
+// Lane layout of the instruction (checked on the device): A operand lane l holds
+// A[i = l % 32][k = l / 32], B operand lane l holds B[k = l / 32][j = l % 32],
+// accumulator register v of lane l is D[(v % 4) + 8 (v / 4) + 4 (l / 32)][l % 32].
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hac_internal.h"
+
+namespace {
+
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int LDA = BM + 4, LDB = BN + 4;          // LDS row pitches (floats)
+constexpr uint32_t kLutLdsMax = 4096;              // representatives kept in LDS
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+template <typename IdxT> struct IdxRegs;
+template <> struct IdxRegs<uint8_t> { uint4 v[1]; };
+template <> struct IdxRegs<uint16_t> { uint4 v[2]; };
+
+__device__ __forceinline__ uint32_t logical_tile(uint32_t tiles_padded)
+{
+    // consecutive logical tiles on one XCD: the column tiles of a row tile share X rows in that L2
+    const uint32_t per = tiles_padded >> 3;
+    return (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
+}
+
+template <typename IdxT, bool LUT_LDS>
+__global__ void __launch_bounds__(256)
+index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
+                  const IdxT* __restrict__ idx, uint64_t pitch,          // pitch in elements, a multiple of 16
+                  const float* __restrict__ codebook, uint32_t k_sym, uint32_t zero_first,
+                  uint32_t n, uint32_t m, float* __restrict__ Y, uint64_t ldy,
+                  uint32_t tiles_n, uint32_t tiles, uint32_t x_vec)
+{
+    extern __shared__ float lds[];
+    float* As = lds;                                   // [2][BK][LDA]
+    float* Bs = lds + 2 * BK * LDA;                    // [2][BK][LDB]
+    float* lut = Bs + 2 * BK * LDB;                    // [k_sym + zero_first] when LUT_LDS
+    const uint32_t tile = logical_tile(gridDim.x);
+    if (tile >= tiles) return;
+    const uint32_t tm = tile / tiles_n, tn = tile - tm * tiles_n;
+    const uint32_t m0 = tm * BM, n0 = tn * BN;
+    const uint32_t t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const uint32_t wm = wave >> 1, wn = wave & 1;
+    const uint32_t l32 = lane & 31, half = lane >> 5;
+
+    // pointer -> value table: entry 0 is 0.0 when the pointers were written with an offset of one
+    const uint32_t k_tot = k_sym + zero_first;
+    if (LUT_LDS) {
+        for (uint32_t i = t; i < k_tot; i += 256)
+            lut[i] = (zero_first && i == 0) ? 0.0f : codebook[i - zero_first];
+    }
+    auto value_of = [&](uint32_t p) -> float {
+        if (LUT_LDS) return lut[p];
+        return (zero_first && p == 0) ? 0.0f : codebook[p - zero_first];
+    };
+
+    // global -> register staging of one K step
+    const uint32_t a_row = t >> 3, a_kq = t & 7;       // rows a_row + 32 r, k = 4 a_kq .. 4 a_kq + 3
+    const uint32_t b_k = t >> 3, b_seg = t & 7;        // idx row b_k, columns 16 b_seg .. 16 b_seg + 15
+    float4 ra[4];
+    IdxRegs<IdxT> rb;
+    auto load_global = [&](uint32_t k0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t row = m0 + a_row + 32 * r, k = k0 + 4 * a_kq;
+            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (row < B) {
+                const float* p = X + (uint64_t)row * ldx + k;
+                if (x_vec && k + 3 < n) v = *reinterpret_cast<const float4*>(p);
+                else {
+                    if (k < n) v.x = p[0];
+                    if (k + 1 < n) v.y = p[1];
+                    if (k + 2 < n) v.z = p[2];
+                    if (k + 3 < n) v.w = p[3];
+                }
+            }
+            ra[r] = v;
+        }
+        const uint32_t k = k0 + b_k, c = n0 + 16 * b_seg;
+        constexpr int NV = sizeof(IdxT) == 1 ? 1 : 2;
+#pragma unroll
+        for (int q = 0; q < NV; ++q) rb.v[q] = make_uint4(0, 0, 0, 0);
+        if (k < n && c < pitch) {
+            const uint4* p = reinterpret_cast<const uint4*>(idx + (uint64_t)k * pitch + c);
+#pragma unroll
+            for (int q = 0; q < NV; ++q) rb.v[q] = p[q];
+        }
+    };
+    auto store_lds = [&](uint32_t buf) {
+        float* a = As + buf * BK * LDA;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t row = a_row + 32 * r;
+            a[(4 * a_kq + 0) * LDA + row] = ra[r].x;
+            a[(4 * a_kq + 1) * LDA + row] = ra[r].y;
+            a[(4 * a_kq + 2) * LDA + row] = ra[r].z;
+            a[(4 * a_kq + 3) * LDA + row] = ra[r].w;
+        }
+        float* b = Bs + buf * BK * LDB + b_k * LDB + 16 * b_seg;
+        constexpr int NW = sizeof(IdxT) == 1 ? 4 : 8;
+        uint32_t w[NW];
+        w[0] = rb.v[0].x; w[1] = rb.v[0].y; w[2] = rb.v[0].z; w[3] = rb.v[0].w;
+        if constexpr (sizeof(IdxT) == 2) { w[4] = rb.v[1].x; w[5] = rb.v[1].y; w[6] = rb.v[1].z; w[7] = rb.v[1].w; }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {                  // four float4 stores of four columns each
+            float4 o;
+            if constexpr (sizeof(IdxT) == 1) {
+                const uint32_t u = w[g];
+                o.x = value_of(u & 255u); o.y = value_of((u >> 8) & 255u);
+                o.z = value_of((u >> 16) & 255u); o.w = value_of(u >> 24);
+            } else {
+                const uint32_t u0 = w[2 * g], u1 = w[2 * g + 1];
+                o.x = value_of(u0 & 65535u); o.y = value_of(u0 >> 16);
+                o.z = value_of(u1 & 65535u); o.w = value_of(u1 >> 16);
+            }
+            *reinterpret_cast<float4*>(b + 4 * g) = o;
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const uint32_t ksteps = (n + BK - 1) / BK;
+    load_global(0);
+    __syncthreads();                                   // the table is complete before the first lookup
+    store_lds(0);
+    __syncthreads();
+    for (uint32_t kt = 0; kt < ksteps; ++kt) {
+        const uint32_t buf = kt & 1;
+        if (kt + 1 < ksteps) load_global((kt + 1) * BK);
+        const float* a = As + buf * BK * LDA + wm * 64 + l32;
+        const float* b = Bs + buf * BK * LDB + wn * 64 + l32;
+#pragma unroll
+        for (int kk = 0; kk < BK / 2; ++kk) {
+            const float a0 = a[(2 * kk + half) * LDA], a1 = a[(2 * kk + half) * LDA + 32];
+            const float b0 = b[(2 * kk + half) * LDB], b1 = b[(2 * kk + half) * LDB + 32];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        if (kt + 1 < ksteps) store_lds(buf ^ 1);       // the other buffer: nobody reads it during this step
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t col = n0 + wn * 64 + j * 32 + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t row = m0 + wm * 64 + i * 32 + (v & 3) + 8 * (v >> 2) + 4 * half;
+                if (row < B && col < m) Y[(uint64_t)row * ldy + col] = acc[i][j][v];
+            }
+        }
+}
+
+} // namespace
+
+namespace hac_internal {
+
+static size_t index_gemm_lds_bytes(uint32_t k_tot)
+{
+    return sizeof(float) * (2 * BK * LDA + 2 * BK * LDB + (k_tot <= kLutLdsMax ? k_tot : 0));
+}
+
+hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const void* d_idx, uint32_t idx_bits,
+                             uint64_t pitch, const float* d_codebook, uint32_t k_sym, uint32_t zero_first,
+                             uint32_t n, uint32_t m, float* d_Y, uint64_t ldy, hipStream_t stream)
+{
+    const uint32_t tiles_m = (B + BM - 1) / BM, tiles_n = (m + BN - 1) / BN;
+    const uint64_t tiles64 = (uint64_t)tiles_m * tiles_n;
+    if (tiles64 > 0x7ffffff0ull) return hipErrorInvalidValue;
+    const uint32_t tiles = (uint32_t)tiles64;
+    const uint32_t grid = (tiles + 7) / 8 * 8;
+    const uint32_t k_tot = k_sym + zero_first;
+    const bool lut_lds = k_tot <= kLutLdsMax;
+    const size_t lds = index_gemm_lds_bytes(k_tot);
+    const uint32_t x_vec = (reinterpret_cast<uintptr_t>(d_X) % 16 == 0 && ldx % 4 == 0) ? 1u : 0u;
+    typedef void (*kern8_t)(const float*, uint64_t, uint32_t, const uint8_t*, uint64_t, const float*, uint32_t, uint32_t,
+                            uint32_t, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t);
+    typedef void (*kern16_t)(const float*, uint64_t, uint32_t, const uint16_t*, uint64_t, const float*, uint32_t, uint32_t,
+                             uint32_t, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t);
+    if (idx_bits == 8) {
+        kern8_t k = lut_lds ? index_gemm_kernel<uint8_t, true> : index_gemm_kernel<uint8_t, false>;
+        if (lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(k, dim3(grid), dim3(256), lds, stream, d_X, ldx, B, static_cast<const uint8_t*>(d_idx), pitch,
+                           d_codebook, k_sym, zero_first, n, m, d_Y, ldy, tiles_n, tiles, x_vec);
+    } else if (idx_bits == 16) {
+        kern16_t k = lut_lds ? index_gemm_kernel<uint16_t, true> : index_gemm_kernel<uint16_t, false>;
+        if (lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(k, dim3(grid), dim3(256), lds, stream, d_X, ldx, B, static_cast<const uint16_t*>(d_idx), pitch,
+                           d_codebook, k_sym, zero_first, n, m, d_Y, ldy, tiles_n, tiles, x_vec);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+} // namespace hac_internal

@@ -617,6 +617,57 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
     }
 }
 
+// =================================================================================
+// index map encoder (Sect. III-C1)
+// =================================================================================
+extern "C" int im_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
+                         const hac_opts_t* opts, void** blob, size_t* blob_bytes)
+{
+    int rc = check_args(W, n, m, ldw, blob, blob_bytes);
+    if (rc) return rc;
+    *blob = nullptr; *blob_bytes = 0;
+    if (opts) return HAC_EINVAL;
+    try {
+        Scan s;
+        rc = scan_matrix(W, n, m, ldw, s);
+        if (rc) return rc;
+        const bool has_zero = s.zeros > 0;
+        const uint64_t k = s.values.size() + (has_zero ? 1 : 0);
+        if (k > 65536) return HAC_ERANGE;
+        const uint32_t bits = k <= 256 ? 8 : 16;
+        const uint64_t pitch = ((uint64_t)m + 15) / 16 * 16;
+        if ((uint64_t)n * pitch * (bits / 8) > 0xffffffff00ull) return HAC_ERANGE;
+        Layout L;
+        hac_desc_t& d = L.d;
+        d.magic = kMagic; d.version = kVersion; d.format = HAC_FORMAT_IM; d.header_bytes = 256;
+        d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = s.ri.size();
+        d.total_bits = (uint64_t)bits * (uint64_t)n * (uint64_t)m;
+        d.k_sym = (uint32_t)k; d.has_zero = has_zero; d.ent_bits = bits; d.idx_pitch = pitch;
+        d.off_codebook = L.place(4 * k);
+        d.off_stream = L.place((uint64_t)n * pitch * (bits / 8) + kTailPad);
+        d.blob_bytes = align_up(L.cursor);
+        uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
+        if (!base) return HAC_ENOMEM;
+        std::memcpy(base, &d, sizeof d);
+        float* cb = reinterpret_cast<float*>(base + d.off_codebook);
+        const uint32_t shift = has_zero ? 1u : 0u;
+        if (has_zero) cb[0] = 0.0f;
+        for (size_t i = 0; i < s.values.size(); ++i) cb[i + shift] = s.values[i];
+        uint8_t* p8 = base + d.off_stream;
+        uint16_t* p16 = reinterpret_cast<uint16_t*>(base + d.off_stream);
+        for (int64_t j = 0; j < m; ++j)
+            for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) {
+                const uint64_t at = (uint64_t)s.ri[(size_t)p] * pitch + (uint64_t)j;
+                const uint32_t v = s.sym[(size_t)p] + shift;
+                if (bits == 8) p8[at] = (uint8_t)v; else p16[at] = (uint16_t)v;
+            }
+        *blob = base; *blob_bytes = (size_t)d.blob_bytes;
+        return HAC_OK;
+    } catch (const std::bad_alloc&) {
+        return HAC_ENOMEM;
+    }
+}
+
 extern "C" void hac_free(void* blob) { std::free(blob); }
 
 // =================================================================================
@@ -637,16 +688,33 @@ int check_header(const void* blob, size_t bytes, hac_desc_t& d)
     if (bytes < sizeof(hac_desc_t)) return HAC_EFORMAT;
     std::memcpy(&d, blob, sizeof d);
     if (d.magic != kMagic || d.version != kVersion || d.header_bytes != 256) return HAC_EFORMAT;
-    if (d.format != HAC_FORMAT_HAC && d.format != HAC_FORMAT_SHAC) return HAC_EFORMAT;
+    if (d.format != HAC_FORMAT_HAC && d.format != HAC_FORMAT_SHAC && d.format != HAC_FORMAT_IM) return HAC_EFORMAT;
     if (d.blob_bytes > bytes || d.blob_bytes < sizeof(hac_desc_t)) return HAC_EFORMAT;
     if (d.n < 1 || d.m < 1 || d.n > 0x7fffffffull || d.m > 0x7fffffffull) return HAC_EFORMAT;
+    if (d.reserved32 || d.reserved[0] || d.reserved[1]) return HAC_EFORMAT;
+    if (d.format == HAC_FORMAT_IM) {
+        if (d.ent_bits != 8 && d.ent_bits != 16) return HAC_EFORMAT;
+        if (d.k_sym < 1 || d.k_sym > (d.ent_bits == 8 ? 256u : 65536u) || d.has_zero > 1) return HAC_EFORMAT;
+        if (d.idx_pitch != (d.m + 15) / 16 * 16) return HAC_EFORMAT;
+        if (d.nnz > d.n * d.m || d.total_bits != (uint64_t)d.ent_bits * d.n * d.m) return HAC_EFORMAT;
+        if (d.n_words || d.lmax || d.lut_bits || d.zero_len || d.chunk || d.ri_bits || d.n_chunks || d.off_codelen ||
+            d.off_canon || d.off_symsort || d.off_lut || d.off_col_chunk || d.off_col_pos || d.off_col_bit ||
+            d.off_chunk_ent || d.off_ri || d.max_col_bits || d.max_col_nnz || d.row_bits || d.ri_coding || d.rice_k ||
+            d.gap_bits) return HAC_EFORMAT;
+        const size_t tot = (size_t)d.blob_bytes;
+        if (!section_ok(d, d.off_codebook, 4ull * d.k_sym, tot)) return HAC_EFORMAT;
+        if (d.n * d.idx_pitch > 0xffffffff00ull) return HAC_EFORMAT;
+        if (!section_ok(d, d.off_stream, d.n * d.idx_pitch * (d.ent_bits / 8) + kTailPad, tot)) return HAC_EFORMAT;
+        return HAC_OK;
+    }
+    if (d.idx_pitch) return HAC_EFORMAT;
     if (d.nnz > d.n * d.m || d.nnz > 0xfffffff0ull || d.total_bits > 0xfffffff0ull) return HAC_EFORMAT;
     if (d.n_words != (d.total_bits + 31) / 32) return HAC_EFORMAT;
     if (d.lmax > 32 || d.lut_bits < 1 || d.lut_bits > 12) return HAC_EFORMAT;
     if (d.k_sym > d.n * d.m) return HAC_EFORMAT;
     if ((d.k_sym == 0) != (d.total_bits == 0)) return HAC_EFORMAT;
     if (d.k_sym > 0 && (d.lmax < 1)) return HAC_EFORMAT;
-    if (d.chunk < 1 || d.chunk > 65536 || d.reserved32 || d.reserved[0] || d.reserved[1] || d.reserved[2]) return HAC_EFORMAT;
+    if (d.chunk < 1 || d.chunk > 65536) return HAC_EFORMAT;
     if (d.ri_coding > HAC_RI_RICE) return HAC_EFORMAT;
     if (d.max_col_bits > d.total_bits || d.max_col_nnz > d.nnz || d.max_col_nnz > d.n) return HAC_EFORMAT;
     const size_t tot = (size_t)d.blob_bytes;
@@ -930,11 +998,47 @@ int check_deep(const View& v)
 
 } // namespace
 
+namespace {
+
+inline uint32_t im_pointer(const hac_desc_t& d, const uint8_t* base, uint64_t i, uint64_t j)
+{
+    const uint64_t at = i * d.idx_pitch + j;
+    return d.ent_bits == 8 ? base[d.off_stream + at]
+                           : reinterpret_cast<const uint16_t*>(base + d.off_stream)[at];
+}
+
+// representatives finite and ascending after the optional 0.0; every pointer below k; padding 0;
+// nnz = number of pointers to a value other than 0.0
+int check_index_map(const void* blob, const hac_desc_t& d, bool deep)
+{
+    const uint8_t* base = static_cast<const uint8_t*>(blob);
+    const float* cb = reinterpret_cast<const float*>(base + d.off_codebook);
+    for (uint32_t s = 0; s < d.k_sym; ++s) {
+        if (!std::isfinite(cb[s])) return HAC_EFORMAT;
+        if (s > d.has_zero && !(cb[s - 1] < cb[s])) return HAC_EFORMAT;
+        if ((cb[s] == 0.0f) != (d.has_zero && s == 0)) return HAC_EFORMAT;
+    }
+    if (d.has_zero && float_bits(cb[0]) != 0) return HAC_EFORMAT;
+    if (!deep) return HAC_OK;
+    uint64_t nnz = 0;
+    for (uint64_t i = 0; i < d.n; ++i)
+        for (uint64_t j = 0; j < d.idx_pitch; ++j) {
+            const uint32_t p = im_pointer(d, base, i, j);
+            if (j >= d.m) { if (p) return HAC_EFORMAT; continue; }
+            if (p >= d.k_sym) return HAC_EFORMAT;
+            if (!(d.has_zero && p == 0)) ++nnz;
+        }
+    return nnz == d.nnz ? HAC_OK : HAC_EFORMAT;
+}
+
+} // namespace
+
 extern "C" int hac_validate(const void* blob, size_t bytes, int deep)
 {
     hac_desc_t d;
     int rc = check_header(blob, bytes, d);
     if (rc) return rc;
+    if (d.format == HAC_FORMAT_IM) return check_index_map(blob, d, deep != 0);
     try {
         View v; make_view(blob, d, v);
         if ((rc = check_tables(v))) return rc;
@@ -958,6 +1062,28 @@ extern "C" int hac_stats(const void* blob, size_t bytes, hac_stats_t* out)
     hac_desc_t d;
     int rc = check_header(blob, bytes, d);
     if (rc) return rc;
+    if (d.format == HAC_FORMAT_IM) {
+        if ((rc = check_index_map(blob, d, true))) return rc;
+        std::memset(out, 0, sizeof *out);
+        const uint8_t* base = static_cast<const uint8_t*>(blob);
+        out->stream_bits = d.total_bits;
+        out->stream_bytes = d.n * d.idx_pitch * (d.ent_bits / 8);
+        out->table_bytes = 4ull * d.k_sym;
+        out->blob_bytes = d.blob_bytes;
+        out->paper_bits = d.total_bits + 32ull * d.k_sym;          // bbar*n*m + k*b
+        out->bound_bits = (double)out->paper_bits;                 // the paper gives this size exactly, not a bound
+        std::vector<uint64_t> cnt(d.k_sym, 0);
+        for (uint64_t i = 0; i < d.n; ++i)
+            for (uint64_t j = 0; j < d.m; ++j) cnt[im_pointer(d, base, i, j)]++;
+        const double nm = (double)d.n * (double)d.m;
+        double H = 0.0;
+        for (uint32_t s = 0; s < d.k_sym; ++s)
+            if (cnt[s]) { const double p = (double)cnt[s] / nm; H -= p * std::log2(p); }
+        out->entropy_bits = H;
+        out->avg_code_bits = (double)d.ent_bits;
+        out->psi = (double)d.blob_bytes / (4.0 * nm);
+        return HAC_OK;
+    }
     View v; make_view(blob, d, v);
     if ((rc = check_tables(v))) return rc;
     if ((rc = check_index_shallow(v))) return rc;
@@ -1006,6 +1132,19 @@ extern "C" int hac_decode_host(const void* blob, size_t bytes, float* W_out, int
     hac_desc_t d;
     int rc = check_header(blob, bytes, d);
     if (rc) return rc;
+    if (d.format == HAC_FORMAT_IM) {
+        if (row_out || col_out) return HAC_EINVAL;
+        if ((rc = check_index_map(blob, d, true))) return rc;
+        const uint8_t* base = static_cast<const uint8_t*>(blob);
+        const float* cb = reinterpret_cast<const float*>(base + d.off_codebook);
+        for (uint64_t i = 0; i < d.n; ++i)
+            for (uint64_t j = 0; j < d.m; ++j) {
+                const uint32_t p = im_pointer(d, base, i, j);
+                if (sym_out) sym_out[j * d.n + i] = (int32_t)p;
+                if (W_out) W_out[i * d.m + j] = cb[p];
+            }
+        return HAC_OK;
+    }
     View v; make_view(blob, d, v);
     if ((rc = check_tables(v))) return rc;
     if ((rc = check_index_shallow(v))) return rc;

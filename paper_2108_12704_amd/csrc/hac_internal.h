@@ -1,0 +1,20 @@
+// Declarations shared by the translation units of libhac (not part of the C ABI).
+#ifndef HAC_INTERNAL_H
+#define HAC_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace hac_internal {
+
+// Y[B x m] = X[B x n] . c[Pi] for an index map Pi of n rows, `pitch` elements apart (a multiple of
+// 16), of idx_bits = 8 or 16 bits each.  zero_first = 1: pointer 0 means 0.0 and pointer p > 0 means
+// c[p - 1].  All pointers are device pointers; d_idx is 16-byte aligned.  Asynchronous on `stream`.
+hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const void* d_idx, uint32_t idx_bits,
+                             uint64_t pitch, const float* d_codebook, uint32_t k_sym, uint32_t zero_first,
+                             uint32_t n, uint32_t m, float* d_Y, uint64_t ldy, hipStream_t stream);
+
+} // namespace hac_internal
+
+#endif

@@ -22,6 +22,7 @@
 #include <stdint.h>
 
 #include "../../include/hac.h"
+#include "hac_internal.h"
 
 // Optional phase timing (build with -DHAC_PHASE_TIMING): lane 0 of each wave of the dot
 // kernels stores a 100 MHz clock at phase boundaries; hac_debug_phases() copies them out.
@@ -386,6 +387,45 @@ decode_kernel(DevBlob d, float* vals, int32_t* sym, int32_t* row_out, int32_t* c
         hac_advance(d, tb, src, st, st.wend, [&](uint32_t, uint32_t row, uint32_t s, float v) {
             if (sym) sym[(uint64_t)col * d.n + row] = (int32_t)s;
             if (vals) vals[(uint64_t)row * d.m + col] = v;
+        });
+    }
+}
+
+// Dense route, step 1: write the pointer of every non-zero into an index map (n rows of
+// `pitch` pointers, pre-filled with 0).  HAC: pointer = symbol (0.0 is symbol 0 when it
+// occurs); sHAC, whose alphabet has no 0.0: pointer = symbol + 1.  One lane per chunk.
+template <typename IdxT>
+__global__ void __launch_bounds__(256)
+decode_to_index_kernel(DevBlob d, IdxT* idx, uint64_t pitch, uint32_t shac)
+{
+    extern __shared__ uint32_t smem[];
+    const Tables tb = load_tables(d, smem);
+    __syncthreads();
+    const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= d.n_chunks) return;
+    const uint32_t col = column_of_chunk(d, g);
+    uint32_t rel, row0;
+    load_entry(d, g, rel, row0);
+    ChunkState st;
+    st.bp = d.colbit[col] + rel;
+    st.row = row0;
+    st.wpos = d.colpos[col] + (g - d.colchunk[col]) * d.chunk;
+    const uint32_t cend = d.colpos[col + 1];
+    st.wend = st.wpos + d.chunk < cend ? st.wpos + d.chunk : cend;
+    WordSrc<false> src = { d.stream, 0 };
+    if (shac && d.rice) {
+        gap_advance_slow(d, tb, src, st, st.wend, [&](uint32_t, uint32_t row, uint32_t s, float) {
+            idx[(uint64_t)row * pitch + col] = (IdxT)(s + 1);
+        });
+    } else if (shac) {
+        WordSrc<false> rsrc = { d.ri, 0 };
+        shac_advance(d, tb, src, st, st.wend, [&](uint32_t p, uint32_t, uint32_t s, float) {
+            const uint32_t row = rsrc.field((uint64_t)p * d.ri_bits, d.ri_bits);
+            idx[(uint64_t)row * pitch + col] = (IdxT)(s + 1);
+        });
+    } else {
+        hac_advance(d, tb, src, st, st.wend, [&](uint32_t, uint32_t row, uint32_t s, float) {
+            idx[(uint64_t)row * pitch + col] = (IdxT)s;
         });
     }
 }
@@ -934,6 +974,26 @@ uint32_t default_cpw(const hac_desc_t* desc)
     return cpw;
 }
 
+// Dense route (decode to an index map, then fp32 MFMA tiles): worth it when the batch is large
+// enough to repay the decode and W is dense enough that gathering per non-zero costs more than
+// multiplying whole tiles.
+struct DenseRoute { bool use; uint32_t idx_bits; uint64_t pitch; size_t bytes; };
+
+DenseRoute dense_route(const hac_desc_t* desc, int64_t B, const hac_launch_t* launch)
+{
+    DenseRoute r = { false, 0, 0, 0 };
+    const uint64_t k_tot = (uint64_t)desc->k_sym + (desc->format == HAC_FORMAT_SHAC ? 1 : 0);
+    if (k_tot > 65536) return r;
+    r.idx_bits = k_tot <= 256 ? 8 : 16;
+    r.pitch = (desc->m + 15) / 16 * 16;
+    r.bytes = (size_t)((desc->n * r.pitch * (r.idx_bits / 8) + 255) / 256 * 256);
+    const uint32_t force = launch ? launch->variant & (HAC_LAUNCH_SPARSE_ROUTE | HAC_LAUNCH_DENSE_ROUTE) : 0u;
+    if (force == HAC_LAUNCH_DENSE_ROUTE) r.use = true;
+    else if (force == HAC_LAUNCH_SPARSE_ROUTE) r.use = false;
+    else r.use = B >= 128 && desc->nnz * 5 >= desc->n * desc->m;
+    return r;
+}
+
 typedef void (*batch_kern_t)(DevBlob, const float*, uint32_t, uint32_t, float*, uint64_t,
                              uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t);
 
@@ -964,7 +1024,9 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         wpb = launch->waves_per_block;
         reuse_xt = (launch->variant & HAC_LAUNCH_REUSE_XT) != 0;
         list_kernel = (launch->variant & HAC_LAUNCH_LIST_KERNEL) != 0;
-        if (launch->variant & ~(HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_LIST_KERNEL)) return HAC_EINVAL;
+        const uint32_t routes = HAC_LAUNCH_SPARSE_ROUTE | HAC_LAUNCH_DENSE_ROUTE;
+        if (launch->variant & ~(HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_LIST_KERNEL | routes)) return HAC_EINVAL;
+        if ((launch->variant & routes) == routes) return HAC_EINVAL;
         list_cap = launch->reserved[0];
         sbuf_words = launch->reserved[1];
         if (list_cap && (list_cap < 64 || list_cap > 4096)) return HAC_EINVAL;
@@ -980,6 +1042,31 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     const bool shac = format == HAC_FORMAT_SHAC && !d.rice;   // Rice-coded gaps decode like a HAC stream: no ri words
     g_last_hip_error = 0;
 
+    const DenseRoute dr = dense_route(desc, B, launch);
+    if (launch && (launch->variant & HAC_LAUNCH_DENSE_ROUTE) && !dr.use) return HAC_EINVAL;   // too many symbols
+    if (dr.use) {
+        if (!d_ws || ws_bytes < dr.bytes) return HAC_EWORKSPACE;
+        if (reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
+        // 1. all pointers 0, 2. the pointer of every non-zero, 3. tiles on the matrix cores
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, stream, static_cast<uint32_t*>(d_ws),
+                           (uint64_t)(dr.bytes / 4), 0u);
+        const size_t lds = 4ull * table_words(d);
+        const uint32_t grid = (d.n_chunks + 255) / 256;
+        const uint32_t is_shac = format == HAC_FORMAT_SHAC ? 1u : 0u;
+        if (grid) {
+            if (dr.idx_bits == 8)
+                hipLaunchKernelGGL(decode_to_index_kernel<uint8_t>, dim3(grid), dim3(256), lds, stream, d,
+                                   static_cast<uint8_t*>(d_ws), dr.pitch, is_shac);
+            else
+                hipLaunchKernelGGL(decode_to_index_kernel<uint16_t>, dim3(grid), dim3(256), lds, stream, d,
+                                   static_cast<uint16_t*>(d_ws), dr.pitch, is_shac);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+        e = hac_internal::launch_index_gemm(d_X, (uint64_t)ldx, (uint32_t)B, d_ws, dr.idx_bits, dr.pitch, d.codebook,
+                                            d.k_sym, is_shac, d.n, d.m, d_Y, (uint64_t)ldy, stream);
+        return e == hipSuccess ? HAC_OK : hip_fail(e);
+    }
     const BatchShape bs = batch_shape(B, pass_w, tile_b);
     const float* XT = d_X;                                   // B = 1: X is its own feature-major copy
     if (B > 1) {
@@ -1083,13 +1170,45 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
 
 } // namespace
 
-extern "C" size_t hac_workspace_bytes(const hac_desc_t* desc, int64_t B)
+extern "C" size_t hac_workspace_bytes_for(const hac_desc_t* desc, int64_t B, const hac_launch_t* launch)
 {
-    if (!desc || B <= 0) return 0;
+    if (!desc || B <= 0 || desc->format == HAC_FORMAT_IM) return 0;
+    const DenseRoute dr = dense_route(desc, B, launch);
+    if (dr.use) return dr.bytes;
     if (B == 1) return 0;                                    // a single row is its own feature-major copy
     const BatchShape bs = batch_shape(B, 32, kDefaultTile);
     return (size_t)4 * (size_t)desc->n * bs.Bp;
 }
+
+extern "C" int im_dot(const hac_desc_t* desc, const void* d_blob, const float* d_X, int64_t B, int64_t ldx,
+                      float* d_Y, int64_t ldy, void* d_ws, size_t ws_bytes,
+                      const hac_launch_t* launch, hac_stream_t stream)
+{
+    (void)d_ws; (void)ws_bytes;
+    if (!desc || !d_blob || launch) return HAC_EINVAL;
+    if (desc->magic != 0x31434148u || desc->version != 2 || desc->format != HAC_FORMAT_IM) return HAC_EINVAL;
+    if (reinterpret_cast<uintptr_t>(d_blob) % 256) return HAC_EINVAL;
+    if (desc->n > 0x7fffffffull || desc->m > 0x7fffffffull) return HAC_EINVAL;
+    if ((desc->ent_bits != 8 && desc->ent_bits != 16) || desc->k_sym < 1 || desc->k_sym > 65536) return HAC_EINVAL;
+    if (desc->idx_pitch != (desc->m + 15) / 16 * 16 || desc->off_stream % 256 || desc->off_codebook % 256) return HAC_EINVAL;
+    if (B < 0 || B > 0x7fffffffll) return HAC_EINVAL;
+    if (B == 0) return HAC_OK;
+    if (!d_X || !d_Y || ldx < (int64_t)desc->n || ldy < (int64_t)desc->m) return HAC_EINVAL;
+    g_last_hip_error = 0;
+    const uint8_t* b = static_cast<const uint8_t*>(d_blob);
+    hipError_t e = hac_internal::launch_index_gemm(d_X, (uint64_t)ldx, (uint32_t)B, b + desc->off_stream, desc->ent_bits,
+                                                   desc->idx_pitch, reinterpret_cast<const float*>(b + desc->off_codebook),
+                                                   desc->k_sym, 0u, (uint32_t)desc->n, (uint32_t)desc->m, d_Y,
+                                                   (uint64_t)ldy, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HAC_OK : hip_fail(e);
+}
+
+extern "C" size_t hac_workspace_bytes(const hac_desc_t* desc, int64_t B)
+{
+    if (!desc || B <= 0) return 0;
+    return hac_workspace_bytes_for(desc, B, nullptr);
+}
+
 
 extern "C" int hac_dot(const hac_desc_t* desc, const void* d_blob, const float* d_X, int64_t B, int64_t ldx,
                        float* d_Y, int64_t ldy, void* d_ws, size_t ws_bytes,
