@@ -20,7 +20,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "hac.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b((?:s?hac)_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:s?hac|im)_[a-z_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -272,6 +272,67 @@ def test_rice_escape_form_for_huge_gaps():
     assert int(blob.desc.total_bits) == og.nbits and int(blob.desc.rice_k) == og.k
     _, symd, rowd, cold = blob.decode_host(want_w=False)
     assert np.array_equal(symd, sym) and np.array_equal(rowd, row) and np.array_equal(cold, col)
+
+
+def im_cases():
+    for name, W in LAYERS:
+        yield name, W
+    yield "no_repeats", workloads.stress_cases()["no_repeats_40x30"]
+    yield "unpruned", workloads.make_layer(130, 77, 0.02, 0.0, 64, "kmeans", 3)
+
+
+@pytest.mark.parametrize("name,W", list(im_cases()), ids=[c[0] for c in im_cases()])
+def test_index_map_blob_against_oracle(name, W):
+    from oracle import indexmap
+    n, m = W.shape
+    blob = hac.im_encode(W)
+    assert blob.validate(deep=True) == 0
+    d = blob.desc
+    im = indexmap.im_encode(W)
+    assert int(d.format) == hac.HAC_FORMAT_IM and int(d.ent_bits) == im.bbar and int(d.k_sym) == im.c.size
+    assert int(d.total_bits) == im.bbar * n * m and int(d.nnz) == np.count_nonzero(W)
+    assert int(d.idx_pitch) == -(-m // 16) * 16
+    assert np.array_equal(blob.section("off_codebook", np.float32, im.c.size), im.c)
+    dt = np.uint8 if im.bbar == 8 else np.uint16
+    pi = blob.section("off_stream", dt, n * int(d.idx_pitch)).reshape(n, int(d.idx_pitch))
+    assert np.array_equal(pi[:, :m], im.pi) and not pi[:, m:].any()
+    Wd, sym = blob.decode_host()
+    assert np.array_equal(Wd.view(np.uint32), (W + np.float32(0)).view(np.uint32))
+    assert np.array_equal(sym.reshape(m, n).T, im.pi.astype(np.int32))
+    st = blob.stats()
+    assert st.paper_bits == indexmap.im_bits(im)
+    assert st.paper_bits / (32.0 * n * m) == pytest.approx(bounds.psi_index_map(n, m, im.c.size, im.bbar))
+    assert st.avg_code_bits == im.bbar and 0.0 <= st.entropy_bits <= im.bbar
+
+
+def test_index_map_argument_checks_and_damage():
+    import ctypes as C
+    lib = hac.load_library()
+    W = workloads.scaled(5, 60, 20)
+    Wc = np.ascontiguousarray(W)
+    out, size = C.c_void_p(), C.c_size_t()
+    opts = hac.Opts(0, 0, 0, 0)
+    f32p = C.POINTER(C.c_float)
+    assert lib.im_encode(Wc.ctypes.data_as(f32p), 60, 20, 20, C.byref(opts), C.byref(out), C.byref(size)) == -1
+    assert lib.im_encode(Wc.ctypes.data_as(f32p), 60, 20, 10, None, C.byref(out), C.byref(size)) == -1
+    bad = Wc.copy(); bad[3, 3] = np.inf
+    assert lib.im_encode(bad.ctypes.data_as(f32p), 60, 20, 20, None, C.byref(out), C.byref(size)) == -1
+    many = np.arange(1, 70001, dtype=np.float32).reshape(700, 100)          # more than 65536 representatives
+    assert lib.im_encode(many.ctypes.data_as(f32p), 700, 100, 100, None, C.byref(out), C.byref(size)) == -4
+    blob = hac.im_encode(W)
+    d = blob.desc
+
+    def damaged(at, value, deep=1):
+        b = blob.data.copy()
+        b[at] = value
+        return lib.hac_validate(b.ctypes.data, b.size, deep)
+
+    assert damaged(int(d.off_stream) + 5, 255) == -3                        # pointer past the representatives
+    assert damaged(int(d.off_stream) + 25, 1) == -3                         # padding column not zero
+    assert damaged(hac.Desc.ent_bits.offset, 12, deep=0) == -3
+    assert damaged(hac.Desc.idx_pitch.offset, 16, deep=0) == -3
+    assert damaged(int(d.off_codebook) + 3, 0x7f, deep=0) == -3             # representatives no longer ascending
+    assert lib.hac_validate(blob.data.ctypes.data, blob.data.size - 256, 1) == -3
 
 
 def test_ri_bits_32_and_small_tables_still_round_trip():
