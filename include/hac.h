@@ -260,6 +260,11 @@ int hac_decode_host(const void *blob, size_t bytes, float *W_out, int32_t *sym_o
 size_t hac_workspace_bytes(const hac_desc_t *desc, int64_t B);
 size_t hac_workspace_bytes_for(const hac_desc_t *desc, int64_t B, const hac_launch_t *launch);
 
+/* Which route hac_dot / shac_dot take for this blob, batch and launch (see
+ * hac_dot): HAC_ROUTE_SPARSE or HAC_ROUTE_DENSE, or HAC_EINVAL. */
+enum { HAC_ROUTE_SPARSE = 0, HAC_ROUTE_DENSE = 1 };
+int hac_dot_route(const hac_desc_t *desc, int64_t B, const hac_launch_t *launch);
+
 /* Y[B x m] = X[B x n] . W with W given as a HAC blob on the device
  * (Algorithm 1 for every row of X as in Algorithm 3; the stream is decoded
  * once per launch, not once per row).  Y is overwritten.  d_blob must be

@@ -22,7 +22,7 @@ HAC_FORMAT_IM = 3
 
 EXPORTS = (
     "hac_encode", "shac_encode", "hac_free", "hac_validate", "hac_describe", "hac_stats",
-    "hac_decode_host", "hac_workspace_bytes", "hac_workspace_bytes_for", "hac_dot", "shac_dot", "hac_decode_dev",
+    "hac_decode_host", "hac_workspace_bytes", "hac_workspace_bytes_for", "hac_dot_route", "hac_dot", "shac_dot", "hac_decode_dev",
     "shac_decode_dev", "hac_strerror", "hac_last_hip_error", "im_encode", "im_dot",
 )
 
@@ -101,6 +101,7 @@ def load_library() -> C.CDLL:
     lib.hac_workspace_bytes.restype = C.c_size_t
     lib.hac_workspace_bytes_for.argtypes = [C.POINTER(Desc), C.c_int64, C.POINTER(Launch)]
     lib.hac_workspace_bytes_for.restype = C.c_size_t
+    lib.hac_dot_route.argtypes = [C.POINTER(Desc), C.c_int64, C.POINTER(Launch)]
     dot_args = [C.POINTER(Desc), vp, vp, C.c_int64, C.c_int64, vp, C.c_int64,
                 vp, C.c_size_t, C.POINTER(Launch), vp]
     lib.hac_dot.argtypes = dot_args
@@ -295,6 +296,14 @@ def hac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=No
 def shac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=None):
     """Y = X . W for an sHAC blob on the device (asynchronous on the stream)."""
     return _dot("shac_dot", dblob, X, Y, workspace, launch, stream)
+
+
+def hac_dot_route(desc: Desc, B: int, launch: Optional["Launch"] = None) -> int:
+    """0 = sparse route (vector FMAs per non-zero), 1 = dense route (index map + matrix cores)."""
+    rc = load_library().hac_dot_route(C.byref(desc), B, C.byref(launch) if launch is not None else None)
+    if rc < 0:
+        _check(rc, "hac_dot_route")
+    return rc
 
 
 def im_dot(dblob: DeviceBlob, X, Y=None, stream=None):

@@ -105,35 +105,31 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
             for (int q = 0; q < NV; ++q) rb.v[q] = p[q];
         }
     };
-    auto store_lds = [&](uint32_t buf) {
+    // registers -> LDS in four quarters (q = 0..3), so that the work can be spread over the MFMA loop
+    auto store_quarter = [&](uint32_t buf, int q) {
         float* a = As + buf * BK * LDA;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint32_t row = a_row + 32 * r;
-            a[(4 * a_kq + 0) * LDA + row] = ra[r].x;
-            a[(4 * a_kq + 1) * LDA + row] = ra[r].y;
-            a[(4 * a_kq + 2) * LDA + row] = ra[r].z;
-            a[(4 * a_kq + 3) * LDA + row] = ra[r].w;
-        }
+        const uint32_t row = a_row + 32 * q;
+        a[(4 * a_kq + 0) * LDA + row] = ra[q].x;
+        a[(4 * a_kq + 1) * LDA + row] = ra[q].y;
+        a[(4 * a_kq + 2) * LDA + row] = ra[q].z;
+        a[(4 * a_kq + 3) * LDA + row] = ra[q].w;
         float* b = Bs + buf * BK * LDB + b_k * LDB + 16 * b_seg;
-        constexpr int NW = sizeof(IdxT) == 1 ? 4 : 8;
-        uint32_t w[NW];
-        w[0] = rb.v[0].x; w[1] = rb.v[0].y; w[2] = rb.v[0].z; w[3] = rb.v[0].w;
-        if constexpr (sizeof(IdxT) == 2) { w[4] = rb.v[1].x; w[5] = rb.v[1].y; w[6] = rb.v[1].z; w[7] = rb.v[1].w; }
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {                  // four float4 stores of four columns each
-            float4 o;
-            if constexpr (sizeof(IdxT) == 1) {
-                const uint32_t u = w[g];
-                o.x = value_of(u & 255u); o.y = value_of((u >> 8) & 255u);
-                o.z = value_of((u >> 16) & 255u); o.w = value_of(u >> 24);
-            } else {
-                const uint32_t u0 = w[2 * g], u1 = w[2 * g + 1];
-                o.x = value_of(u0 & 65535u); o.y = value_of(u0 >> 16);
-                o.z = value_of(u1 & 65535u); o.w = value_of(u1 >> 16);
-            }
-            *reinterpret_cast<float4*>(b + 4 * g) = o;
+        float4 o;
+        if constexpr (sizeof(IdxT) == 1) {
+            const uint32_t u = q == 0 ? rb.v[0].x : q == 1 ? rb.v[0].y : q == 2 ? rb.v[0].z : rb.v[0].w;
+            o.x = value_of(u & 255u); o.y = value_of((u >> 8) & 255u);
+            o.z = value_of((u >> 16) & 255u); o.w = value_of(u >> 24);
+        } else {
+            const uint4 v = rb.v[q >> 1];
+            const uint32_t u0 = (q & 1) ? v.z : v.x, u1 = (q & 1) ? v.w : v.y;
+            o.x = value_of(u0 & 65535u); o.y = value_of(u0 >> 16);
+            o.z = value_of(u1 & 65535u); o.w = value_of(u1 >> 16);
         }
+        *reinterpret_cast<float4*>(b + 4 * q) = o;
+    };
+    auto store_lds = [&](uint32_t buf) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) store_quarter(buf, q);
     };
 
     f32x16 acc[2][2];
@@ -152,18 +148,28 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
     for (uint32_t kt = 0; kt < ksteps; ++kt) {
         const uint32_t buf = kt & 1;
         if (kt + 1 < ksteps) load_global((kt + 1) * BK);
-        const float* a = As + buf * BK * LDA + wm * 64 + l32;
-        const float* b = Bs + buf * BK * LDB + wn * 64 + l32;
+        const float* a = As + buf * BK * LDA + wm * 64 + l32 + half * LDA;
+        const float* b = Bs + buf * BK * LDB + wn * 64 + l32 + half * LDB;
+        // operands of step kk + 1 are fetched from LDS before the matrix instructions of step kk issue
+        float a0 = a[0], a1 = a[32], b0 = b[0], b1 = b[32];
 #pragma unroll
         for (int kk = 0; kk < BK / 2; ++kk) {
-            const float a0 = a[(2 * kk + half) * LDA], a1 = a[(2 * kk + half) * LDA + 32];
-            const float b0 = b[(2 * kk + half) * LDB], b1 = b[(2 * kk + half) * LDB + 32];
+            float na0 = 0.0f, na1 = 0.0f, nb0 = 0.0f, nb1 = 0.0f;
+            if (kk + 1 < BK / 2) {
+                na0 = a[(2 * kk + 2) * LDA]; na1 = a[(2 * kk + 2) * LDA + 32];
+                nb0 = b[(2 * kk + 2) * LDB]; nb1 = b[(2 * kk + 2) * LDB + 32];
+            }
+            __builtin_amdgcn_sched_barrier(0);         // keep these LDS reads ahead of the matrix instructions
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+            // the next tile goes to the other buffer (nobody reads it during this step), a quarter at a
+            // time between the matrix instructions, late in the step so that its global loads have landed
+            if (kk >= 9 && (kk & 1) == 1 && kt + 1 < ksteps) store_quarter(buf ^ 1, (kk - 9) >> 1);
         }
-        if (kt + 1 < ksteps) store_lds(buf ^ 1);       // the other buffer: nobody reads it during this step
         __syncthreads();
     }
 

@@ -1180,6 +1180,12 @@ extern "C" size_t hac_workspace_bytes_for(const hac_desc_t* desc, int64_t B, con
     return (size_t)4 * (size_t)desc->n * bs.Bp;
 }
 
+extern "C" int hac_dot_route(const hac_desc_t* desc, int64_t B, const hac_launch_t* launch)
+{
+    if (!desc || B < 0 || (desc->format != HAC_FORMAT_HAC && desc->format != HAC_FORMAT_SHAC)) return HAC_EINVAL;
+    return dense_route(desc, B, launch).use ? HAC_ROUTE_DENSE : HAC_ROUTE_SPARSE;
+}
+
 extern "C" int im_dot(const hac_desc_t* desc, const void* d_blob, const float* d_X, int64_t B, int64_t ldx,
                       float* d_Y, int64_t ldy, void* d_ws, size_t ws_bytes,
                       const hac_launch_t* launch, hac_stream_t stream)
