@@ -272,13 +272,15 @@ int hac_dot_route(const hac_desc_t *desc, int64_t B, const hac_launch_t *launch)
  * B = 0 is a no-op.  fp32 accumulation; the order of the additions is fixed,
  * so results are bitwise reproducible run to run.
  *
- * Two routes.  Sparse (default): every non-zero is decoded and applied to the
- * batch by vector FMAs.  Dense: when at least a fifth of W is non-zero and
- * B >= 128 the product is a dense contraction in all but name; the stream is
- * then decoded once into an index map (Sect. III-C1) in the workspace and
- * multiplied tile by tile on the matrix cores (fp32 MFMA).  The route follows
- * from desc and B alone; HAC_LAUNCH_SPARSE_ROUTE / HAC_LAUNCH_DENSE_ROUTE in
- * launch->variant force one (the dense route needs at most 65536 symbols). */
+ * Two routes.  Sparse: every non-zero is decoded and applied to the batch by
+ * vector FMAs.  Dense: the stream is decoded once into an index map
+ * (Sect. III-C1) in the workspace and multiplied tile by tile on the matrix
+ * cores (fp32 MFMA); with few output tiles the K loop is split and the parts
+ * are added in a fixed order.  The library estimates both times from desc and
+ * B (the dense route wins for layers that are a fifth or more non-zero at
+ * batches of several hundred rows) and takes the shorter; hac_dot_route() tells
+ * which.  HAC_LAUNCH_SPARSE_ROUTE / HAC_LAUNCH_DENSE_ROUTE in launch->variant
+ * force one (the dense route needs at most 65536 symbols). */
 int hac_dot(const hac_desc_t *desc, const void *d_blob,
             const float *d_X, int64_t B, int64_t ldx,
             float *d_Y, int64_t ldy,
@@ -295,8 +297,9 @@ int shac_dot(const hac_desc_t *desc, const void *d_blob,
 
 /* Y = X . W for an index-map blob (Sect. III-C1): pointers are expanded through
  * the representatives tile by tile and multiplied on the matrix cores (fp32 in,
- * fp32 accumulate).  No workspace is used (d_ws may be NULL); launch must be
- * NULL.  Otherwise as hac_dot. */
+ * fp32 accumulate).  The workspace (hac_workspace_bytes(), 0 for large batches)
+ * holds partial tiles when the K loop is split; launch must be NULL.  Otherwise
+ * as hac_dot. */
 int im_dot(const hac_desc_t *desc, const void *d_blob,
            const float *d_X, int64_t B, int64_t ldx,
            float *d_Y, int64_t ldy,

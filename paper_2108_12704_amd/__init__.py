@@ -306,9 +306,9 @@ def hac_dot_route(desc: Desc, B: int, launch: Optional["Launch"] = None) -> int:
     return rc
 
 
-def im_dot(dblob: DeviceBlob, X, Y=None, stream=None):
+def im_dot(dblob: DeviceBlob, X, Y=None, workspace=None, stream=None):
     """Y = X . W for an index-map blob on the device (asynchronous on the stream)."""
-    return _dot("im_dot", dblob, X, Y, None, None, stream)
+    return _dot("im_dot", dblob, X, Y, workspace, None, stream)
 
 
 def hac_decode_dev(dblob: DeviceBlob, stream=None):

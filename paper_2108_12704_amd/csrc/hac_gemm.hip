@@ -48,14 +48,18 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
                   const IdxT* __restrict__ idx, uint64_t pitch,          // pitch in elements, a multiple of 16
                   const float* __restrict__ codebook, uint32_t k_sym, uint32_t zero_first,
                   uint32_t n, uint32_t m, float* __restrict__ Y, uint64_t ldy,
-                  uint32_t tiles_n, uint32_t tiles, uint32_t x_vec)
+                  uint32_t tiles_n, uint32_t tiles, uint32_t x_vec,
+                  uint32_t splits, uint32_t steps_per_split, float* __restrict__ part)
 {
     extern __shared__ float lds[];
     float* As = lds;                                   // [2][BK][LDA]
     float* Bs = lds + 2 * BK * LDA;                    // [2][BK][LDB]
     float* lut = Bs + 2 * BK * LDB;                    // [k_sym + zero_first] when LUT_LDS
-    const uint32_t tile = logical_tile(gridDim.x);
-    if (tile >= tiles) return;
+    // work item = (tile, K split); with more than one split a block writes its partial tile to
+    // part[split][B][m] and a second kernel adds the splits in order
+    const uint32_t item = logical_tile(gridDim.x);
+    if (item >= tiles * splits) return;
+    const uint32_t tile = item / splits, split = item - tile * splits;
     const uint32_t tm = tile / tiles_n, tn = tile - tm * tiles_n;
     const uint32_t m0 = tm * BM, n0 = tn * BN;
     const uint32_t t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -140,12 +144,14 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    const uint32_t ksteps = (n + BK - 1) / BK;
-    load_global(0);
+    const uint32_t all_steps = (n + BK - 1) / BK;
+    const uint32_t kt0 = split * steps_per_split;
+    const uint32_t ksteps = kt0 + steps_per_split < all_steps ? kt0 + steps_per_split : all_steps;   // one past the last
+    load_global(kt0 * BK);
     __syncthreads();                                   // the table is complete before the first lookup
-    store_lds(0);
+    store_lds(kt0 & 1);
     __syncthreads();
-    for (uint32_t kt = 0; kt < ksteps; ++kt) {
+    for (uint32_t kt = kt0; kt < ksteps; ++kt) {
         const uint32_t buf = kt & 1;
         if (kt + 1 < ksteps) load_global((kt + 1) * BK);
         const float* a = As + buf * BK * LDA + wm * 64 + l32 + half * LDA;
@@ -181,9 +187,27 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const uint32_t row = m0 + wm * 64 + i * 32 + (v & 3) + 8 * (v >> 2) + 4 * half;
-                if (row < B && col < m) Y[(uint64_t)row * ldy + col] = acc[i][j][v];
+                if (row < B && col < m) {
+                    if (splits == 1) Y[(uint64_t)row * ldy + col] = acc[i][j][v];
+                    else part[((uint64_t)split * B + row) * m + col] = acc[i][j][v];
+                }
             }
         }
+}
+
+// Y = part[0] + part[1] + ... in that order (bitwise reproducible).
+__global__ void __launch_bounds__(256)
+splitk_reduce_kernel(const float* __restrict__ part, uint32_t splits, uint32_t B, uint32_t m,
+                     float* __restrict__ Y, uint64_t ldy)
+{
+    const uint64_t total = (uint64_t)B * m;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        float v = part[i];
+        for (uint32_t s = 1; s < splits; ++s) v += part[(uint64_t)s * total + i];
+        const uint64_t row = i / m;
+        Y[row * ldy + (i - row * m)] = v;
+    }
 }
 
 } // namespace
@@ -195,23 +219,47 @@ static size_t index_gemm_lds_bytes(uint32_t k_tot)
     return sizeof(float) * (2 * BK * LDA + 2 * BK * LDB + (k_tot <= kLutLdsMax ? k_tot : 0));
 }
 
+GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m)
+{
+    GemmPlan p;
+    const uint64_t tiles = (uint64_t)((B + BM - 1) / BM) * ((m + BN - 1) / BN);
+    const uint32_t steps = (n + BK - 1) / BK;
+    // a tile's K loop is serial (about 3 us per step of 32): with fewer tiles than CUs, K is split
+    // until there are about two work items per CU, keeping at least 8 steps per split
+    uint32_t splits = 1;
+    if (tiles < 256) {
+        splits = (uint32_t)((512 + tiles - 1) / tiles);
+        const uint32_t most = steps / 8 ? steps / 8 : 1;
+        if (splits > most) splits = most;
+        if (splits > 32) splits = 32;
+    }
+    p.steps_per_split = (steps + splits - 1) / splits;
+    p.splits = (steps + p.steps_per_split - 1) / p.steps_per_split;       // no empty split
+    p.part_bytes = p.splits > 1 ? (size_t)p.splits * B * m * sizeof(float) : 0;
+    p.tiles = tiles;
+    p.steps = steps;
+    return p;
+}
+
 hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const void* d_idx, uint32_t idx_bits,
                              uint64_t pitch, const float* d_codebook, uint32_t k_sym, uint32_t zero_first,
-                             uint32_t n, uint32_t m, float* d_Y, uint64_t ldy, hipStream_t stream)
+                             uint32_t n, uint32_t m, float* d_Y, uint64_t ldy, float* d_part, hipStream_t stream)
 {
-    const uint32_t tiles_m = (B + BM - 1) / BM, tiles_n = (m + BN - 1) / BN;
-    const uint64_t tiles64 = (uint64_t)tiles_m * tiles_n;
-    if (tiles64 > 0x7ffffff0ull) return hipErrorInvalidValue;
-    const uint32_t tiles = (uint32_t)tiles64;
-    const uint32_t grid = (tiles + 7) / 8 * 8;
+    const uint32_t tiles_n = (m + BN - 1) / BN;
+    const GemmPlan plan = plan_index_gemm(B, n, m);
+    const uint64_t items64 = plan.tiles * plan.splits;
+    if (items64 > 0x7ffffff0ull) return hipErrorInvalidValue;
+    if (plan.splits > 1 && !d_part) return hipErrorInvalidValue;
+    const uint32_t tiles = (uint32_t)plan.tiles;
+    const uint32_t grid = ((uint32_t)items64 + 7) / 8 * 8;
     const uint32_t k_tot = k_sym + zero_first;
     const bool lut_lds = k_tot <= kLutLdsMax;
     const size_t lds = index_gemm_lds_bytes(k_tot);
     const uint32_t x_vec = (reinterpret_cast<uintptr_t>(d_X) % 16 == 0 && ldx % 4 == 0) ? 1u : 0u;
     typedef void (*kern8_t)(const float*, uint64_t, uint32_t, const uint8_t*, uint64_t, const float*, uint32_t, uint32_t,
-                            uint32_t, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t);
+                            uint32_t, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, float*);
     typedef void (*kern16_t)(const float*, uint64_t, uint32_t, const uint16_t*, uint64_t, const float*, uint32_t, uint32_t,
-                             uint32_t, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t);
+                             uint32_t, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, float*);
     if (idx_bits == 8) {
         kern8_t k = lut_lds ? index_gemm_kernel<uint8_t, true> : index_gemm_kernel<uint8_t, false>;
         if (lds > 64 * 1024) {
@@ -219,7 +267,8 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
             if (e != hipSuccess) return e;
         }
         hipLaunchKernelGGL(k, dim3(grid), dim3(256), lds, stream, d_X, ldx, B, static_cast<const uint8_t*>(d_idx), pitch,
-                           d_codebook, k_sym, zero_first, n, m, d_Y, ldy, tiles_n, tiles, x_vec);
+                           d_codebook, k_sym, zero_first, n, m, d_Y, ldy, tiles_n, tiles, x_vec,
+                           plan.splits, plan.steps_per_split, d_part);
     } else if (idx_bits == 16) {
         kern16_t k = lut_lds ? index_gemm_kernel<uint16_t, true> : index_gemm_kernel<uint16_t, false>;
         if (lds > 64 * 1024) {
@@ -227,10 +276,16 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
             if (e != hipSuccess) return e;
         }
         hipLaunchKernelGGL(k, dim3(grid), dim3(256), lds, stream, d_X, ldx, B, static_cast<const uint16_t*>(d_idx), pitch,
-                           d_codebook, k_sym, zero_first, n, m, d_Y, ldy, tiles_n, tiles, x_vec);
+                           d_codebook, k_sym, zero_first, n, m, d_Y, ldy, tiles_n, tiles, x_vec,
+                           plan.splits, plan.steps_per_split, d_part);
     } else {
         return hipErrorInvalidValue;
     }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || plan.splits == 1) return e;
+    const uint64_t total = (uint64_t)B * m;
+    const uint32_t rgrid = (uint32_t)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(rgrid), dim3(256), 0, stream, d_part, plan.splits, B, m, d_Y, ldy);
     return hipGetLastError();
 }
 

@@ -8,12 +8,19 @@
 
 namespace hac_internal {
 
+// How launch_index_gemm splits the work: `tiles` output tiles, each K loop of `steps` steps cut into
+// `splits` ranges of steps_per_split; with more than one split the partial tiles go through a buffer
+// of part_bytes bytes (splits x B x m floats) and are added in order by a second kernel.
+struct GemmPlan { uint64_t tiles; uint32_t steps, splits, steps_per_split; size_t part_bytes; };
+GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m);
+
 // Y[B x m] = X[B x n] . c[Pi] for an index map Pi of n rows, `pitch` elements apart (a multiple of
 // 16), of idx_bits = 8 or 16 bits each.  zero_first = 1: pointer 0 means 0.0 and pointer p > 0 means
-// c[p - 1].  All pointers are device pointers; d_idx is 16-byte aligned.  Asynchronous on `stream`.
+// c[p - 1].  All pointers are device pointers; d_idx is 16-byte aligned; d_part holds
+// plan_index_gemm(B, n, m).part_bytes bytes (may be NULL when that is 0).  Asynchronous on `stream`.
 hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const void* d_idx, uint32_t idx_bits,
                              uint64_t pitch, const float* d_codebook, uint32_t k_sym, uint32_t zero_first,
-                             uint32_t n, uint32_t m, float* d_Y, uint64_t ldy, hipStream_t stream);
+                             uint32_t n, uint32_t m, float* d_Y, uint64_t ldy, float* d_part, hipStream_t stream);
 
 } // namespace hac_internal
 

@@ -974,23 +974,40 @@ uint32_t default_cpw(const hac_desc_t* desc)
     return cpw;
 }
 
-// Dense route (decode to an index map, then fp32 MFMA tiles): worth it when the batch is large
-// enough to repay the decode and W is dense enough that gathering per non-zero costs more than
-// multiplying whole tiles.
-struct DenseRoute { bool use; uint32_t idx_bits; uint64_t pitch; size_t bytes; };
+// Dense route (decode to an index map, then fp32 MFMA tiles) or sparse route (vector FMAs per
+// non-zero)?  Decided from rough time estimates, with constants measured on an MI355X:
+//   sparse: every non-zero gathers 4 bytes per batch column (at least 32) through the vector
+//           memory path, about 22 TB/s over the whole chip and 140 GB/s per busy CU (a block covers
+//           16 columns of W and up to 256 batch columns), plus the re-layout of X and ~12 us;
+//   dense : ~35 non-zeros per ns to decode into the index map, then the contraction at about
+//           80 TFLOP/s, but never faster than its serial K loop (3 us per step of 32 per round of
+//           512 work items), plus the pass that adds the K splits.
+struct DenseRoute { bool use; uint32_t idx_bits; uint64_t pitch; size_t idx_bytes, bytes; };
 
 DenseRoute dense_route(const hac_desc_t* desc, int64_t B, const hac_launch_t* launch)
 {
-    DenseRoute r = { false, 0, 0, 0 };
+    DenseRoute r = { false, 0, 0, 0, 0 };
     const uint64_t k_tot = (uint64_t)desc->k_sym + (desc->format == HAC_FORMAT_SHAC ? 1 : 0);
-    if (k_tot > 65536) return r;
+    if (k_tot > 65536 || B < 1) return r;
     r.idx_bits = k_tot <= 256 ? 8 : 16;
     r.pitch = (desc->m + 15) / 16 * 16;
-    r.bytes = (size_t)((desc->n * r.pitch * (r.idx_bits / 8) + 255) / 256 * 256);
+    r.idx_bytes = (size_t)((desc->n * r.pitch * (r.idx_bits / 8) + 255) / 256 * 256);
+    const hac_internal::GemmPlan plan = hac_internal::plan_index_gemm((uint32_t)B, (uint32_t)desc->n, (uint32_t)desc->m);
+    r.bytes = r.idx_bytes + ((plan.part_bytes + 255) / 256 * 256);
     const uint32_t force = launch ? launch->variant & (HAC_LAUNCH_SPARSE_ROUTE | HAC_LAUNCH_DENSE_ROUTE) : 0u;
-    if (force == HAC_LAUNCH_DENSE_ROUTE) r.use = true;
-    else if (force == HAC_LAUNCH_SPARSE_ROUTE) r.use = false;
-    else r.use = B >= 128 && desc->nnz * 5 >= desc->n * desc->m;
+    if (force == HAC_LAUNCH_DENSE_ROUTE) { r.use = true; return r; }
+    if (force == HAC_LAUNCH_SPARSE_ROUTE || B < 32) return r;
+    const double nnz = (double)desc->nnz, n = (double)desc->n, m = (double)desc->m, b = (double)B;
+    const double bp = (double)((B + 31) / 32 * 32);
+    const double blocks = ((m + 15.0) / 16.0) * (double)((B + 255) / 256);
+    const double busy = blocks < 256.0 ? blocks : 256.0;
+    const double rate = busy * 140e3 < 22e6 ? busy * 140e3 : 22e6;             // bytes per us
+    const double sparse_us = 12.0 + nnz * bp * 4.0 / rate + b * n * 8.0 / 3e6;
+    const double items = (double)plan.tiles * plan.splits;
+    const double rounds = (double)(uint64_t)((items + 511.0) / 512.0);
+    const double flops_us = 2.0 * b * n * m / 8e7, serial_us = plan.steps_per_split * 3.0 * rounds;
+    const double dense_us = 10.0 + nnz / 35e3 + (flops_us > serial_us ? flops_us : serial_us) + (double)plan.part_bytes / 2e6;
+    r.use = dense_us < sparse_us;
     return r;
 }
 
@@ -1049,7 +1066,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         if (reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
         // 1. all pointers 0, 2. the pointer of every non-zero, 3. tiles on the matrix cores
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, stream, static_cast<uint32_t*>(d_ws),
-                           (uint64_t)(dr.bytes / 4), 0u);
+                           (uint64_t)(dr.idx_bytes / 4), 0u);
         const size_t lds = 4ull * table_words(d);
         const uint32_t grid = (d.n_chunks + 255) / 256;
         const uint32_t is_shac = format == HAC_FORMAT_SHAC ? 1u : 0u;
@@ -1063,8 +1080,9 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
+        float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(d_ws) + dr.idx_bytes);
         e = hac_internal::launch_index_gemm(d_X, (uint64_t)ldx, (uint32_t)B, d_ws, dr.idx_bits, dr.pitch, d.codebook,
-                                            d.k_sym, is_shac, d.n, d.m, d_Y, (uint64_t)ldy, stream);
+                                            d.k_sym, is_shac, d.n, d.m, d_Y, (uint64_t)ldy, part, stream);
         return e == hipSuccess ? HAC_OK : hip_fail(e);
     }
     const BatchShape bs = batch_shape(B, pass_w, tile_b);
@@ -1172,7 +1190,9 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
 
 extern "C" size_t hac_workspace_bytes_for(const hac_desc_t* desc, int64_t B, const hac_launch_t* launch)
 {
-    if (!desc || B <= 0 || desc->format == HAC_FORMAT_IM) return 0;
+    if (!desc || B <= 0 || B > 0x7fffffffll) return 0;
+    if (desc->format == HAC_FORMAT_IM)
+        return hac_internal::plan_index_gemm((uint32_t)B, (uint32_t)desc->n, (uint32_t)desc->m).part_bytes;
     const DenseRoute dr = dense_route(desc, B, launch);
     if (dr.use) return dr.bytes;
     if (B == 1) return 0;                                    // a single row is its own feature-major copy
@@ -1190,7 +1210,6 @@ extern "C" int im_dot(const hac_desc_t* desc, const void* d_blob, const float* d
                       float* d_Y, int64_t ldy, void* d_ws, size_t ws_bytes,
                       const hac_launch_t* launch, hac_stream_t stream)
 {
-    (void)d_ws; (void)ws_bytes;
     if (!desc || !d_blob || launch) return HAC_EINVAL;
     if (desc->magic != 0x31434148u || desc->version != 2 || desc->format != HAC_FORMAT_IM) return HAC_EINVAL;
     if (reinterpret_cast<uintptr_t>(d_blob) % 256) return HAC_EINVAL;
@@ -1201,11 +1220,14 @@ extern "C" int im_dot(const hac_desc_t* desc, const void* d_blob, const float* d
     if (B == 0) return HAC_OK;
     if (!d_X || !d_Y || ldx < (int64_t)desc->n || ldy < (int64_t)desc->m) return HAC_EINVAL;
     g_last_hip_error = 0;
+    const size_t need = hac_internal::plan_index_gemm((uint32_t)B, (uint32_t)desc->n, (uint32_t)desc->m).part_bytes;
+    if (need && (!d_ws || ws_bytes < need)) return HAC_EWORKSPACE;
+    if (need && reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
     const uint8_t* b = static_cast<const uint8_t*>(d_blob);
     hipError_t e = hac_internal::launch_index_gemm(d_X, (uint64_t)ldx, (uint32_t)B, b + desc->off_stream, desc->ent_bits,
                                                    desc->idx_pitch, reinterpret_cast<const float*>(b + desc->off_codebook),
                                                    desc->k_sym, 0u, (uint32_t)desc->n, (uint32_t)desc->m, d_Y,
-                                                   (uint64_t)ldy, static_cast<hipStream_t>(stream));
+                                                   (uint64_t)ldy, static_cast<float*>(d_ws), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? HAC_OK : hip_fail(e);
 }
 

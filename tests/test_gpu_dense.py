@@ -46,6 +46,7 @@ def dense_layers():
     yield "cfg5-640x33", workloads.scaled(5, 640, 33)
     yield "cfg5-300x129", workloads.scaled(5, 300, 129)
     yield "cfg5-97x200", workloads.scaled(5, 97, 200)
+    yield "cfg5-2100x40", workloads.scaled(5, 2100, 40)                                # K loop split into 8
     yield "unpruned-257x256", workloads.make_layer(257, 256, 0.02, 0.0, 64, "kmeans", 5)
     yield "cfg1", workloads.layer(1)
     yield "no_repeats_40x30", workloads.stress_cases()["no_repeats_40x30"]             # 16-bit pointers
@@ -106,28 +107,38 @@ def test_dense_route_matches_the_oracle(hac, name, W):
 
 
 def test_route_selection_and_workspace(hac):
-    import ctypes as C
-    W = workloads.scaled(5, 640, 70)                         # 40 % non-zero
-    Ws = workloads.scaled(4, 640, 70)                        # 2 % non-zero
+    W = workloads.scaled(5, 2100, 70)                        # 40 % non-zero
+    n, m = W.shape
     pitch = 80
-    for enc in (hac.hac_encode, hac.shac_encode):
+    for enc, f in ((hac.hac_encode, hac.hac_dot), (hac.shac_encode, hac.shac_dot)):
         b = enc(W)
-        assert hac.hac_workspace_bytes(b.desc, 127) == 4 * 640 * 128          # sparse: feature-major X
         bits = 8 if int(b.desc.k_sym) + (0 if enc is hac.hac_encode else 1) <= 256 else 16
-        assert hac.hac_workspace_bytes(b.desc, 128) == (640 * pitch * bits // 8 + 255) // 256 * 256   # dense: the index map
-        assert hac.hac_workspace_bytes(enc(Ws).desc, 4096) == 4 * 640 * 4096  # sparse layers stay on the sparse route
+        idx_bytes = (n * pitch * bits // 8 + 255) // 256 * 256
         db = b.to_device(dev())
-        X = workloads.make_batch(256, 640, 1)
-        Xd = torch.from_numpy(X).to(dev())
-        f = hac.hac_dot if enc is hac.hac_encode else hac.shac_dot
-        Yd = f(db, Xd)                                                         # dense by default
-        Ys = f(db, Xd, launch=hac.Launch(variant=SPARSE))
-        torch.cuda.synchronize()
-        check_y(Yd, X, W, "default")
-        check_y(Ys, X, W, "forced sparse")
+        for B in (40, 256, 700):
+            X = workloads.make_batch(B, n, 1)
+            Xd = torch.from_numpy(X).to(dev())
+            route = hac.hac_dot_route(b.desc, B)
+            need = hac.hac_workspace_bytes(b.desc, B)
+            if route == 0:
+                assert need == 4 * n * (-(-B // 256) * 256 if B > 256 else 1 << (B - 1).bit_length())
+            else:
+                assert need >= idx_bytes                                       # index map (+ partial tiles)
+            dense = hac.Launch(variant=DENSE)
+            assert hac.hac_dot_route(b.desc, B, dense) == 1 and hac.hac_dot_route(b.desc, B, hac.Launch(variant=SPARSE)) == 0
+            assert hac.hac_workspace_bytes(b.desc, B, dense) >= idx_bytes
+            Y0 = f(db, Xd)
+            Yd = f(db, Xd, launch=dense)
+            Ys = f(db, Xd, launch=hac.Launch(variant=SPARSE))
+            torch.cuda.synchronize()
+            for Y, what in ((Y0, "default"), (Yd, "dense"), (Ys, "sparse")):
+                check_y(Y, X, W, f"{f.__name__} {what} B={B}")
+            assert torch.equal(Y0, Yd if route == 1 else Ys)                   # the default is one of the two, bit for bit
+            assert torch.equal(Yd, f(db, Xd, launch=dense))                    # split-K parts are added in a fixed order
+        Xd = torch.from_numpy(workloads.make_batch(256, n, 1)).to(dev())
         small = torch.empty(256, dtype=torch.uint8, device=dev())
         with pytest.raises(hac.HacError) as e:
-            f(db, Xd, workspace=small)
+            f(db, Xd, workspace=small, launch=hac.Launch(variant=DENSE))
         assert e.value.status == -6
         with pytest.raises(hac.HacError) as e:
             f(db, Xd, launch=hac.Launch(variant=SPARSE | DENSE))
@@ -150,4 +161,9 @@ def test_im_dot_argument_checks(hac):
     Y = torch.empty((4, 20), device=dev())
     assert lib.im_dot(C.byref(ib.desc), ib.tensor.data_ptr(), X.data_ptr(), 4, 50, Y.data_ptr(), 20, None, 0, None, None) == -1
     assert lib.im_dot(C.byref(ib.desc), ib.tensor.data_ptr(), None, 0, 100, None, 20, None, 0, None, None) == 0
+    tall = hac.im_encode(workloads.scaled(5, 2100, 20))      # few tiles, long K: partial tiles need a workspace
+    assert hac.hac_workspace_bytes(tall.desc, 4) > 0
+    td = tall.to_device(dev())
+    X = torch.zeros((4, 2100), device=dev())
+    assert lib.im_dot(C.byref(td.desc), td.tensor.data_ptr(), X.data_ptr(), 4, 2100, Y.data_ptr(), 20, None, 0, None, None) == -6
     torch.cuda.synchronize()

@@ -335,6 +335,23 @@ def test_index_map_argument_checks_and_damage():
     assert lib.hac_validate(blob.data.ctypes.data, blob.data.size - 256, 1) == -3
 
 
+def test_route_choice_on_the_full_size_layers():
+    """hac_dot_route is host-side logic: the 40 % dense conv-shaped layer at its batch of 12544 goes
+    to the matrix cores, the 98 % sparse layer never does, and forcing works either way."""
+    b5 = hac.shac_encode(workloads.layer(5))
+    assert hac.hac_dot_route(b5.desc, 12544) == 1
+    assert hac.hac_dot_route(b5.desc, 8) == 0
+    assert hac.hac_workspace_bytes(b5.desc, 12544) == (4608 * 512 * 2 + 255) // 256 * 256      # 257 pointers: 16 bits
+    b4 = hac.shac_encode(workloads.scaled(4, 25088, 256))
+    for B in (1, 32, 256, 4096):
+        assert hac.hac_dot_route(b4.desc, B) == 0
+    assert hac.hac_dot_route(b4.desc, 256, hac.Launch(variant=0x800)) == 1
+    assert hac.hac_dot_route(b5.desc, 12544, hac.Launch(variant=0x400)) == 0
+    im = hac.im_encode(workloads.scaled(5, 300, 40))
+    with pytest.raises(hac.HacError):
+        hac.hac_dot_route(im.desc, 8)
+
+
 def test_ri_bits_32_and_small_tables_still_round_trip():
     W = workloads.scaled(3, 260, 33)
     for kw in (dict(ri_bits=32), dict(lut_bits=2), dict(chunk_nnz=1), dict(chunk_nnz=65536)):
