@@ -453,27 +453,42 @@ transpose_pad_kernel(const float* __restrict__ X, uint32_t B, uint32_t n, uint64
     }
 }
 
-// Same re-layout for panels of exactly 32 batch columns: a block turns 32 batch rows x 64
-// features into one contiguous 8 KB piece of a panel (256-byte reads, fully contiguous writes).
+// Same re-layout for panels of exactly 32 batch columns: a block turns 32 batch rows x 128
+// features into one contiguous 16 KB piece of a panel.  With X 16-byte aligned (vec = 1) the
+// reads are 128-bit (512 bytes per batch row) and so are the writes.
 __global__ void __launch_bounds__(256)
 transpose_panel32_kernel(const float* __restrict__ X, uint32_t B, uint32_t n, uint64_t ldx,
-                         float* __restrict__ XT)
+                         float* __restrict__ XT, uint32_t vec)
 {
-    __shared__ float tile[32][65];
-    const uint32_t r0 = blockIdx.x * 64, b0 = blockIdx.y * 32;
+    __shared__ float tile[32][129];
+    const uint32_t r0 = blockIdx.x * 128, b0 = blockIdx.y * 32;
+    if (vec && r0 + 128 <= n) {
 #pragma unroll
-    for (uint32_t i = 0; i < 8; ++i) {
-        const uint32_t idx = threadIdx.x + 256 * i;
-        const uint32_t b = idx >> 6, r = idx & 63;
-        tile[b][r] = (b0 + b < B && r0 + r < n) ? X[(uint64_t)(b0 + b) * ldx + r0 + r] : 0.0f;
+        for (uint32_t i = 0; i < 4; ++i) {
+            const uint32_t idx = threadIdx.x + 256 * i;          // float4 index: 32 rows x 32 quads
+            const uint32_t b = idx >> 5, q = idx & 31;
+            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (b0 + b < B) v = *reinterpret_cast<const float4*>(X + (uint64_t)(b0 + b) * ldx + r0 + 4 * q);
+            tile[b][4 * q + 0] = v.x; tile[b][4 * q + 1] = v.y; tile[b][4 * q + 2] = v.z; tile[b][4 * q + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (uint32_t i = 0; i < 16; ++i) {
+            const uint32_t idx = threadIdx.x + 256 * i;
+            const uint32_t b = idx >> 7, r = idx & 127;
+            tile[b][r] = (b0 + b < B && r0 + r < n) ? X[(uint64_t)(b0 + b) * ldx + r0 + r] : 0.0f;
+        }
     }
     __syncthreads();
     float* out = XT + (uint64_t)blockIdx.y * n * 32 + (uint64_t)r0 * 32;
 #pragma unroll
-    for (uint32_t i = 0; i < 8; ++i) {
-        const uint32_t idx = threadIdx.x + 256 * i;
-        const uint32_t r = idx >> 5, b = idx & 31;
-        if (r0 + r < n) out[idx] = tile[b][r];
+    for (uint32_t i = 0; i < 4; ++i) {
+        const uint32_t idx = threadIdx.x + 256 * i;              // float4 index: 128 features x 8 quads of batch
+        const uint32_t r = idx >> 3, bq = (idx & 7) * 4;
+        if (r0 + r < n) {
+            const float4 v = make_float4(tile[bq][r], tile[bq + 1][r], tile[bq + 2][r], tile[bq + 3][r]);
+            *reinterpret_cast<float4*>(out + (uint64_t)r * 32 + bq) = v;
+        }
     }
 }
 
@@ -1095,9 +1110,10 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         XT = xt;
         if (!reuse_xt) {
             if (bs.gw * bs.nb == 32) {
-                dim3 grid((d.n + 63) / 64, bs.Bp / 32);
+                dim3 grid((d.n + 127) / 128, bs.Bp / 32);
+                const uint32_t vec = (reinterpret_cast<uintptr_t>(d_X) % 16 == 0 && ldx % 4 == 0) ? 1u : 0u;
                 hipLaunchKernelGGL(transpose_panel32_kernel, grid, dim3(256), 0, stream,
-                                   d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt);
+                                   d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt, vec);
             } else {
                 dim3 grid((d.n + 31) / 32, (bs.Bp + 31) / 32);
                 hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, stream,
