@@ -144,6 +144,26 @@ def test_stress_cases(hac, name):
         check_y(Yg, X, W, f"shac/rice {name} B={B}")
 
 
+def test_randomized_parity(hac):
+    """Seeded sweep: random shapes, densities, alphabets and skews x all formats x a few batch sizes."""
+    rng = np.random.default_rng(99)
+    for name, W in workloads.random_cases(40, seed=77):
+        n, m = W.shape
+        chunk = int(rng.choice([0, 0, 1, 7, 200]))
+        blobs = [(hac.hac_dot, hac.hac_encode(W, chunk_nnz=chunk)), (hac.shac_dot, hac.shac_encode(W, chunk_nnz=chunk)),
+                 (hac.shac_dot, hac.shac_encode(W, chunk_nnz=chunk, ri_coding=1)), (hac.im_dot, hac.im_encode(W))]
+        for B in (1, int(rng.integers(2, 5)), int(rng.integers(5, 140))):
+            print(f"[case] random {name} chunk={chunk} B={B}", flush=True)
+            X = workloads.make_batch(B, n, B + n) - np.float32(0.3)
+            Xd = torch.from_numpy(X).to(dev())
+            variant = int(rng.choice([0, 0x400, 0x800]))
+            for f, blob in blobs:
+                db = blob.to_device(dev())
+                Y = f(db, Xd) if f is hac.im_dot else f(db, Xd, launch=hac.Launch(variant=variant))
+                torch.cuda.synchronize()
+                check_y(Y, X, W, f"{f.__name__} {name} B={B} variant={variant:#x}")
+
+
 def test_dot_other_encoder_options(hac):
     W = workloads.scaled(3, 1500, 90)
     n, m = W.shape

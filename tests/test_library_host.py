@@ -352,6 +352,36 @@ def test_route_choice_on_the_full_size_layers():
         hac.hac_dot_route(im.desc, 8)
 
 
+def test_randomized_blobs_against_oracle():
+    """A seeded sweep over shapes, densities, alphabet sizes and skews: every format's blob validates,
+    holds as many bits as the oracle's encoding, and decodes to the oracle's symbols."""
+    from oracle import gapcode, indexmap
+    for name, W in workloads.random_cases(60):
+        n, m = W.shape
+        opts = dict(chunk_nnz=int(np.random.default_rng(len(name)).choice([0, 1, 5, 64])))
+        hb = hac.hac_encode(W, **opts)
+        sb = hac.shac_encode(W, **opts)
+        gb = hac.shac_encode(W, ri_coding=hac.RI_RICE, **opts)
+        ib = hac.im_encode(W)
+        for b in (hb, sb, gb, ib):
+            assert b.validate(deep=True) == 0, name
+        values, sym = formats.hac_symbols(W)
+        assert int(hb.desc.total_bits) == formats.hac_encode(W).nbits, name
+        Wd, symd = hb.decode_host()
+        assert np.array_equal(Wd.view(np.uint32), W.view(np.uint32)) and np.array_equal(symd, sym), name
+        svalues, ssym, srow, scol = formats.shac_symbols(W)
+        assert int(sb.desc.total_bits) == formats.shac_encode(W).nbits, name
+        for b in (sb, gb):
+            Wd, symd, rowd, cold = b.decode_host()
+            assert np.array_equal(Wd.view(np.uint32), W.view(np.uint32)), name
+            assert np.array_equal(symd, ssym) and np.array_equal(rowd, srow) and np.array_equal(cold, scol), name
+        og = gapcode.shacg_encode(W)
+        assert (int(gb.desc.total_bits), int(gb.desc.rice_k)) == (og.nbits, og.k), name
+        Wd, symd = ib.decode_host()
+        assert np.array_equal(Wd.view(np.uint32), W.view(np.uint32)), name
+        assert np.array_equal(symd.reshape(m, n).T, indexmap.im_encode(W).pi.astype(np.int32)), name
+
+
 def test_ri_bits_32_and_small_tables_still_round_trip():
     W = workloads.scaled(3, 260, 33)
     for kw in (dict(ri_bits=32), dict(lut_bits=2), dict(chunk_nnz=1), dict(chunk_nnz=65536)):

@@ -221,6 +221,27 @@ def stress_cases() -> Dict[str, np.ndarray]:
     return out
 
 
+def random_cases(count: int, seed: int = 2024):
+    """`count` small random matrices of varied shape, density, alphabet size and value skew
+    (a seeded sweep for randomized parity tests): yields (name, W)."""
+    rng = np.random.default_rng(seed)
+    for i in range(count):
+        n = int(rng.integers(1, 400))
+        m = int(rng.integers(1, 90))
+        dens = float(rng.choice([0.0, 0.01, 0.05, 0.3, 0.7, 1.0]))
+        k = int(rng.choice([1, 2, 3, 17, 64, 300]))
+        vals = np.unique(rng.standard_normal(k).astype(np.float32))
+        vals = vals[vals != 0]
+        if vals.size == 0:
+            vals = np.array([1.0], dtype=np.float32)
+        p = rng.random(vals.size) ** float(rng.choice([0.5, 1.0, 4.0]))       # flat to very skewed
+        p /= p.sum()
+        W = np.zeros((n, m), dtype=np.float32)
+        mask = rng.random((n, m)) < dens
+        W[mask] = rng.choice(vals, size=int(mask.sum()), p=p)
+        yield f"rand{i}-{n}x{m}-d{dens}-k{k}", W
+
+
 def paper_example_matrix() -> np.ndarray:
     """The 5x5 matrix of the paper's CSC example (Sect. IV-A, Example 1)."""
     return np.array([[1, 0, 4, 0, 0],
