@@ -9,12 +9,14 @@
 // matrix cores with v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate, so the
 // result keeps the accuracy of the vector path).
 //
-// Tiling: a block of 4 wavefronts owns 128 batch rows x 128 columns of Y and walks
-// K = n in steps of 32; wavefront (wm, wn) owns a 64 x 64 quarter as 2 x 2 MFMA
-// tiles (64 accumulator registers).  LDS holds the X tile k-major (lanes read 32
-// consecutive batch rows of one k) and the decoded W tile k-major (32 consecutive
-// columns of one k); both are double buffered, the next tile's global loads are
-// issued before the MFMA loop of the current one and stored after it.
+// Tiling: a block of 4 wavefronts owns 32 RT batch rows x 128 columns of Y
+// (RT = 2..8, chosen per launch so that the tiles fill the 256 CUs evenly) and
+// walks K = n in steps of 32; wavefront w owns the 32 columns [32 w, 32 w + 32)
+// of the tile and all its rows, as RT MFMA tiles (16 RT accumulator registers).
+// LDS holds the X tile k-major (lanes read 32 consecutive batch rows of one k)
+// and the decoded W tile k-major (32 consecutive columns of one k); both are
+// double buffered, the next tile's global loads are issued before the MFMA loop
+// of the current one and stored during its second half.
 // Lane layout of the instruction (checked on the device): A operand lane l holds
 // A[i = l % 32][k = l / 32], B operand lane l holds B[k = l / 32][j = l % 32],
 // accumulator register v of lane l is D[(v % 4) + 8 (v / 4) + 4 (l / 32)][l % 32].
@@ -25,8 +27,9 @@
 
 namespace {
 
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int LDA = BM + 4, LDB = BN + 4;          // LDS row pitches (floats)
+constexpr int BN = 128, BK = 32;
+constexpr int LDB = BN + 4;                        // LDS row pitch of the W tile (floats)
+constexpr int kMinRT = 2, kMaxRT = 8;              // row tiles of 32 per block
 constexpr uint32_t kLutLdsMax = 4096;              // representatives kept in LDS
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -42,7 +45,7 @@ __device__ __forceinline__ uint32_t logical_tile(uint32_t tiles_padded)
     return (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
 }
 
-template <typename IdxT, bool LUT_LDS>
+template <typename IdxT, bool LUT_LDS, int RT, bool XVEC>
 __global__ void __launch_bounds__(256)
 index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
                   const IdxT* __restrict__ idx, uint64_t pitch,          // pitch in elements, a multiple of 16
@@ -51,6 +54,7 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
                   uint32_t tiles_n, uint32_t tiles, uint32_t x_vec,
                   uint32_t splits, uint32_t steps_per_split, float* __restrict__ part)
 {
+    constexpr int BM = 32 * RT, LDA = BM + 4;
     extern __shared__ float lds[];
     float* As = lds;                                   // [2][BK][LDA]
     float* Bs = lds + 2 * BK * LDA;                    // [2][BK][LDB]
@@ -63,7 +67,6 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
     const uint32_t tm = tile / tiles_n, tn = tile - tm * tiles_n;
     const uint32_t m0 = tm * BM, n0 = tn * BN;
     const uint32_t t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const uint32_t wm = wave >> 1, wn = wave & 1;
     const uint32_t l32 = lane & 31, half = lane >> 5;
 
     // pointer -> value table: entry 0 is 0.0 when the pointers were written with an offset of one
@@ -77,122 +80,179 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
         return (zero_first && p == 0) ? 0.0f : codebook[p - zero_first];
     };
 
-    // global -> register staging of one K step
+    // global -> register staging of one K step; two sets, so that a tile's loads are issued two
+    // steps before the tile is needed (one whole step before its stores to LDS begin)
+    struct Stage { float4 ra[RT]; IdxRegs<IdxT> rb; };
     const uint32_t a_row = t >> 3, a_kq = t & 7;       // rows a_row + 32 r, k = 4 a_kq .. 4 a_kq + 3
     const uint32_t b_k = t >> 3, b_seg = t & 7;        // idx row b_k, columns 16 b_seg .. 16 b_seg + 15
-    float4 ra[4];
-    IdxRegs<IdxT> rb;
-    auto load_global = [&](uint32_t k0) {
+    // Rows past B and index columns past the pitch are read from a clamped, valid address and
+    // masked when they are stored to LDS: a K step that lies wholly inside n then issues the same
+    // loads on every path, and the wait before a tile's stores can leave the younger tile's loads
+    // in flight.  Only the last, partial K step takes the guarded path.
+    bool row_ok[RT];
+    const float* xrow[RT];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint32_t row = m0 + a_row + 32 * r, k = k0 + 4 * a_kq;
-            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (row < B) {
-                const float* p = X + (uint64_t)row * ldx + k;
-                if (x_vec && k + 3 < n) v = *reinterpret_cast<const float4*>(p);
-                else {
-                    if (k < n) v.x = p[0];
-                    if (k + 1 < n) v.y = p[1];
-                    if (k + 2 < n) v.z = p[2];
-                    if (k + 3 < n) v.w = p[3];
-                }
+    for (int r = 0; r < RT; ++r) {
+        const uint32_t row = m0 + a_row + 32 * r;
+        row_ok[r] = row < B;
+        xrow[r] = X + (uint64_t)(row_ok[r] ? row : B - 1) * ldx + 4 * a_kq;
+    }
+    const bool col_ok = n0 + 16 * b_seg < pitch;
+    const IdxT* icol = idx + (col_ok ? n0 + 16 * b_seg : 0);
+    constexpr int NV = sizeof(IdxT) == 1 ? 1 : 2;
+    // a K step that lies wholly inside n: the same loads on every path
+    auto load_full = [&](uint32_t k0, Stage& st) {
+        if (XVEC) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r) st.ra[r] = *reinterpret_cast<const float4*>(xrow[r] + k0);
+        } else {
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                const float* p = xrow[r] + k0;
+                st.ra[r] = make_float4(p[0], p[1], p[2], p[3]);
             }
-            ra[r] = v;
         }
-        const uint32_t k = k0 + b_k, c = n0 + 16 * b_seg;
-        constexpr int NV = sizeof(IdxT) == 1 ? 1 : 2;
+        const uint4* p = reinterpret_cast<const uint4*>(icol + (uint64_t)(k0 + b_k) * pitch);
 #pragma unroll
-        for (int q = 0; q < NV; ++q) rb.v[q] = make_uint4(0, 0, 0, 0);
-        if (k < n && c < pitch) {
-            const uint4* p = reinterpret_cast<const uint4*>(idx + (uint64_t)k * pitch + c);
+        for (int q = 0; q < NV; ++q) st.rb.v[q] = p[q];
+    };
+    // the last, partial K step: guarded element by element
+    auto load_tail = [&](uint32_t k0, Stage& st) {
 #pragma unroll
-            for (int q = 0; q < NV; ++q) rb.v[q] = p[q];
+        for (int r = 0; r < RT; ++r) {
+            const uint32_t k = k0 + 4 * a_kq;
+            const float* p = xrow[r] + k0;
+            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (k < n) v.x = p[0];
+            if (k + 1 < n) v.y = p[1];
+            if (k + 2 < n) v.z = p[2];
+            if (k + 3 < n) v.w = p[3];
+            st.ra[r] = v;
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q) st.rb.v[q] = make_uint4(0, 0, 0, 0);
+        if (k0 + b_k < n) {
+            const uint4* p = reinterpret_cast<const uint4*>(icol + (uint64_t)(k0 + b_k) * pitch);
+#pragma unroll
+            for (int q = 0; q < NV; ++q) st.rb.v[q] = p[q];
         }
     };
-    // registers -> LDS in four quarters (q = 0..3), so that the work can be spread over the MFMA loop
-    auto store_quarter = [&](uint32_t buf, int q) {
+    // registers -> LDS in pieces, so that the work can be spread over the MFMA loop
+    auto store_a = [&](uint32_t buf, int r, const Stage& st) {          // rows a_row + 32 r of the X tile
         float* a = As + buf * BK * LDA;
-        const uint32_t row = a_row + 32 * q;
-        a[(4 * a_kq + 0) * LDA + row] = ra[q].x;
-        a[(4 * a_kq + 1) * LDA + row] = ra[q].y;
-        a[(4 * a_kq + 2) * LDA + row] = ra[q].z;
-        a[(4 * a_kq + 3) * LDA + row] = ra[q].w;
+        const uint32_t row = a_row + 32 * r;
+        a[(4 * a_kq + 0) * LDA + row] = row_ok[r] ? st.ra[r].x : 0.0f;
+        a[(4 * a_kq + 1) * LDA + row] = row_ok[r] ? st.ra[r].y : 0.0f;
+        a[(4 * a_kq + 2) * LDA + row] = row_ok[r] ? st.ra[r].z : 0.0f;
+        a[(4 * a_kq + 3) * LDA + row] = row_ok[r] ? st.ra[r].w : 0.0f;
+    };
+    auto store_b = [&](uint32_t buf, int q, const Stage& st) {          // columns 16 b_seg + 4 q .. + 3 of the W tile
         float* b = Bs + buf * BK * LDB + b_k * LDB + 16 * b_seg;
         float4 o;
         if constexpr (sizeof(IdxT) == 1) {
-            const uint32_t u = q == 0 ? rb.v[0].x : q == 1 ? rb.v[0].y : q == 2 ? rb.v[0].z : rb.v[0].w;
+            const uint32_t u = q == 0 ? st.rb.v[0].x : q == 1 ? st.rb.v[0].y : q == 2 ? st.rb.v[0].z : st.rb.v[0].w;
             o.x = value_of(u & 255u); o.y = value_of((u >> 8) & 255u);
             o.z = value_of((u >> 16) & 255u); o.w = value_of(u >> 24);
         } else {
-            const uint4 v = rb.v[q >> 1];
+            const uint4 v = st.rb.v[q >> 1];
             const uint32_t u0 = (q & 1) ? v.z : v.x, u1 = (q & 1) ? v.w : v.y;
             o.x = value_of(u0 & 65535u); o.y = value_of(u0 >> 16);
             o.z = value_of(u1 & 65535u); o.w = value_of(u1 >> 16);
         }
         *reinterpret_cast<float4*>(b + 4 * q) = o;
     };
-    auto store_lds = [&](uint32_t buf) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) store_quarter(buf, q);
-    };
 
-    f32x16 acc[2][2];
+    f32x16 acc[RT];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
 
     const uint32_t all_steps = (n + BK - 1) / BK;
     const uint32_t kt0 = split * steps_per_split;
     const uint32_t ksteps = kt0 + steps_per_split < all_steps ? kt0 + steps_per_split : all_steps;   // one past the last
-    load_global(kt0 * BK);
-    __syncthreads();                                   // the table is complete before the first lookup
-    store_lds(kt0 & 1);
-    __syncthreads();
-    for (uint32_t kt = kt0; kt < ksteps; ++kt) {
-        const uint32_t buf = kt & 1;
-        if (kt + 1 < ksteps) load_global((kt + 1) * BK);
-        const float* a = As + buf * BK * LDA + wm * 64 + l32 + half * LDA;
-        const float* b = Bs + buf * BK * LDB + wn * 64 + l32 + half * LDB;
+
+    // Multiply the tile in LDS buffer `buf`; with STORE, meanwhile move the tile held in `st` to the
+    // other buffer (nobody reads it during this step), a piece at a time between the matrix
+    // instructions.
+    auto multiply = [&](uint32_t buf, bool store, const Stage& st) {
+        const float* a = As + buf * BK * LDA + l32 + half * LDA;
+        const float* b = Bs + buf * BK * LDB + wave * 32 + l32 + half * LDB;
         // operands of step kk + 1 are fetched from LDS before the matrix instructions of step kk issue
-        float a0 = a[0], a1 = a[32], b0 = b[0], b1 = b[32];
+        float av[RT], bv = b[0];
+#pragma unroll
+        for (int i = 0; i < RT; ++i) av[i] = a[32 * i];
 #pragma unroll
         for (int kk = 0; kk < BK / 2; ++kk) {
-            float na0 = 0.0f, na1 = 0.0f, nb0 = 0.0f, nb1 = 0.0f;
+            float nav[RT], nbv = 0.0f;
+#pragma unroll
+            for (int i = 0; i < RT; ++i) nav[i] = 0.0f;
             if (kk + 1 < BK / 2) {
-                na0 = a[(2 * kk + 2) * LDA]; na1 = a[(2 * kk + 2) * LDA + 32];
-                nb0 = b[(2 * kk + 2) * LDB]; nb1 = b[(2 * kk + 2) * LDB + 32];
+#pragma unroll
+                for (int i = 0; i < RT; ++i) nav[i] = a[(2 * kk + 2) * LDA + 32 * i];
+                nbv = b[(2 * kk + 2) * LDB];
             }
             __builtin_amdgcn_sched_barrier(0);         // keep these LDS reads ahead of the matrix instructions
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < RT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv, acc[i], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
-            // the next tile goes to the other buffer (nobody reads it during this step), a quarter at a
-            // time between the matrix instructions, late in the step so that its global loads have landed
-            if (kk >= 9 && (kk & 1) == 1 && kt + 1 < ksteps) store_quarter(buf ^ 1, (kk - 9) >> 1);
-        }
-        __syncthreads();
-    }
-
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const uint32_t col = n0 + wn * 64 + j * 32 + l32;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const uint32_t row = m0 + wm * 64 + i * 32 + (v & 3) + 8 * (v >> 2) + 4 * half;
-                if (row < B && col < m) {
-                    if (splits == 1) Y[(uint64_t)row * ldy + col] = acc[i][j][v];
-                    else part[((uint64_t)split * B + row) * m + col] = acc[i][j][v];
-                }
+            for (int i = 0; i < RT; ++i) av[i] = nav[i];
+            bv = nbv;
+            if (store) {
+                if (kk >= 4 && kk - 4 < RT) store_a(buf ^ 1, kk - 4, st);
+                if (kk >= 12) store_b(buf ^ 1, kk - 12, st);
             }
         }
+    };
+    auto store_all = [&](uint32_t buf, const Stage& st) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r) store_a(buf, r, st);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) store_b(buf, q, st);
+    };
+
+    // Full K steps [kt0, kfull) are pipelined: while tile kt is multiplied, tile kt + 1 (requested a
+    // step earlier) moves to LDS and tile kt + 2 is requested.  A partial last step follows on its own.
+    const uint32_t nfull = n / BK;
+    const uint32_t kfull = ksteps < nfull ? ksteps : nfull;
+    Stage s0, s1;
+    __syncthreads();                                   // the table is complete before the first lookup
+    if (kt0 < kfull) {
+        load_full(kt0 * BK, s0);
+        if (kt0 + 1 < kfull) load_full((kt0 + 1) * BK, s1);
+        store_all(kt0 & 1, s0);
+        __syncthreads();
+        for (uint32_t kt = kt0; kt < kfull; kt += 2) {
+            if (kt + 2 < kfull) load_full((kt + 2) * BK, s0);
+            multiply(kt & 1, kt + 1 < kfull, s1);
+            __syncthreads();
+            if (kt + 1 < kfull) {
+                if (kt + 3 < kfull) load_full((kt + 3) * BK, s1);
+                multiply((kt + 1) & 1, kt + 2 < kfull, s0);
+                __syncthreads();
+            }
+        }
+    }
+    if (kfull < ksteps && kfull >= kt0) {              // the partial step (n is not a multiple of 32)
+        load_tail(kfull * BK, s0);
+        store_all(kfull & 1, s0);
+        __syncthreads();
+        multiply(kfull & 1, false, s0);
+    }
+
+    const uint32_t col = n0 + wave * 32 + l32;
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t row = m0 + i * 32 + (v & 3) + 8 * (v >> 2) + 4 * half;
+            if (row < B && col < m) {
+                if (splits == 1) Y[(uint64_t)row * ldy + col] = acc[i][v];
+                else part[((uint64_t)split * B + row) * m + col] = acc[i][v];
+            }
+        }
+    }
 }
 
 // Y = part[0] + part[1] + ... in that order (bitwise reproducible).
@@ -214,16 +274,31 @@ splitk_reduce_kernel(const float* __restrict__ part, uint32_t splits, uint32_t B
 
 namespace hac_internal {
 
-static size_t index_gemm_lds_bytes(uint32_t k_tot)
+static size_t index_gemm_lds_bytes(uint32_t k_tot, int rt)
 {
-    return sizeof(float) * (2 * BK * LDA + 2 * BK * LDB + (k_tot <= kLutLdsMax ? k_tot : 0));
+    return sizeof(float) * (2 * BK * (32 * rt + 4) + 2 * BK * LDB + (k_tot <= kLutLdsMax ? k_tot : 0));
 }
 
 GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m)
 {
     GemmPlan p;
-    const uint64_t tiles = (uint64_t)((B + BM - 1) / BM) * ((m + BN - 1) / BN);
+    const uint64_t tiles_n = (m + BN - 1) / BN;
     const uint32_t steps = (n + BK - 1) / BK;
+    // Row tiles per block: the time of a launch goes like (rounds of tiles over the CUs) x (rows per
+    // tile); blocks of up to 4 row tiles fit a CU two at a time and then share its matrix pipes.
+    // Pick the shape with the fewest padded rows per CU, the larger tile on ties (less re-reading
+    // of the index map).
+    int best_rt = kMinRT;
+    double best_cost = 1e300;
+    for (int rt = kMinRT; rt <= kMaxRT; ++rt) {
+        const uint64_t tiles = (uint64_t)((B + 32 * rt - 1) / (32 * rt)) * tiles_n;
+        const uint64_t slots = rt <= 4 ? 512 : 256;
+        const uint64_t rounds = (tiles + slots - 1) / slots;
+        const double cost = (double)rounds * rt * (rt <= 4 ? 2.0 : 1.0);
+        if (cost <= best_cost) { best_cost = cost; best_rt = rt; }
+    }
+    p.rt = (uint32_t)best_rt;
+    const uint64_t tiles = (uint64_t)((B + 32 * best_rt - 1) / (32 * best_rt)) * tiles_n;
     // a tile's K loop is serial (about 3 us per step of 32): with fewer tiles than CUs, K is split
     // until there are about two work items per CU, keeping at least 8 steps per split
     uint32_t splits = 1;
@@ -241,6 +316,43 @@ GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m)
     return p;
 }
 
+namespace {
+
+typedef void (*gemm_kern_t)(const float*, uint64_t, uint32_t, const void*, uint64_t, const float*, uint32_t, uint32_t,
+                            uint32_t, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, float*);
+
+template <typename IdxT, bool LUT_LDS, int RT>
+void launch_one(dim3 grid, size_t lds, hipStream_t stream, hipError_t& err,
+                const float* d_X, uint64_t ldx, uint32_t B, const void* d_idx, uint64_t pitch, const float* d_codebook,
+                uint32_t k_sym, uint32_t zero_first, uint32_t n, uint32_t m, float* d_Y, uint64_t ldy, uint32_t tiles_n,
+                uint32_t tiles, uint32_t x_vec, uint32_t splits, uint32_t steps_per_split, float* d_part)
+{
+    auto k = x_vec ? index_gemm_kernel<IdxT, LUT_LDS, RT, true> : index_gemm_kernel<IdxT, LUT_LDS, RT, false>;
+    if (lds > 64 * 1024) {
+        err = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return;
+    }
+    hipLaunchKernelGGL(k, grid, dim3(256), lds, stream, d_X, ldx, B, static_cast<const IdxT*>(d_idx), pitch, d_codebook,
+                       k_sym, zero_first, n, m, d_Y, ldy, tiles_n, tiles, x_vec, splits, steps_per_split, d_part);
+    err = hipGetLastError();
+}
+
+template <typename IdxT, bool LUT_LDS, typename... Args>
+void launch_rt(uint32_t rt, Args&&... args)
+{
+    switch (rt) {
+    case 2: launch_one<IdxT, LUT_LDS, 2>(args...); break;
+    case 3: launch_one<IdxT, LUT_LDS, 3>(args...); break;
+    case 4: launch_one<IdxT, LUT_LDS, 4>(args...); break;
+    case 5: launch_one<IdxT, LUT_LDS, 5>(args...); break;
+    case 6: launch_one<IdxT, LUT_LDS, 6>(args...); break;
+    case 7: launch_one<IdxT, LUT_LDS, 7>(args...); break;
+    default: launch_one<IdxT, LUT_LDS, 8>(args...); break;
+    }
+}
+
+} // namespace
+
 hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const void* d_idx, uint32_t idx_bits,
                              uint64_t pitch, const float* d_codebook, uint32_t k_sym, uint32_t zero_first,
                              uint32_t n, uint32_t m, float* d_Y, uint64_t ldy, float* d_part, hipStream_t stream)
@@ -250,38 +362,25 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
     const uint64_t items64 = plan.tiles * plan.splits;
     if (items64 > 0x7ffffff0ull) return hipErrorInvalidValue;
     if (plan.splits > 1 && !d_part) return hipErrorInvalidValue;
+    if (idx_bits != 8 && idx_bits != 16) return hipErrorInvalidValue;
     const uint32_t tiles = (uint32_t)plan.tiles;
-    const uint32_t grid = ((uint32_t)items64 + 7) / 8 * 8;
+    const dim3 grid(((uint32_t)items64 + 7) / 8 * 8);
     const uint32_t k_tot = k_sym + zero_first;
     const bool lut_lds = k_tot <= kLutLdsMax;
-    const size_t lds = index_gemm_lds_bytes(k_tot);
+    const size_t lds = index_gemm_lds_bytes(k_tot, (int)plan.rt);
     const uint32_t x_vec = (reinterpret_cast<uintptr_t>(d_X) % 16 == 0 && ldx % 4 == 0) ? 1u : 0u;
-    typedef void (*kern8_t)(const float*, uint64_t, uint32_t, const uint8_t*, uint64_t, const float*, uint32_t, uint32_t,
-                            uint32_t, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, float*);
-    typedef void (*kern16_t)(const float*, uint64_t, uint32_t, const uint16_t*, uint64_t, const float*, uint32_t, uint32_t,
-                             uint32_t, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, float*);
+    hipError_t e = hipSuccess;
     if (idx_bits == 8) {
-        kern8_t k = lut_lds ? index_gemm_kernel<uint8_t, true> : index_gemm_kernel<uint8_t, false>;
-        if (lds > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        hipLaunchKernelGGL(k, dim3(grid), dim3(256), lds, stream, d_X, ldx, B, static_cast<const uint8_t*>(d_idx), pitch,
-                           d_codebook, k_sym, zero_first, n, m, d_Y, ldy, tiles_n, tiles, x_vec,
-                           plan.splits, plan.steps_per_split, d_part);
-    } else if (idx_bits == 16) {
-        kern16_t k = lut_lds ? index_gemm_kernel<uint16_t, true> : index_gemm_kernel<uint16_t, false>;
-        if (lds > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        hipLaunchKernelGGL(k, dim3(grid), dim3(256), lds, stream, d_X, ldx, B, static_cast<const uint16_t*>(d_idx), pitch,
-                           d_codebook, k_sym, zero_first, n, m, d_Y, ldy, tiles_n, tiles, x_vec,
-                           plan.splits, plan.steps_per_split, d_part);
+        if (lut_lds) launch_rt<uint8_t, true>(plan.rt, grid, lds, stream, e, d_X, ldx, B, d_idx, pitch, d_codebook, k_sym, zero_first,
+                                              n, m, d_Y, ldy, tiles_n, tiles, x_vec, plan.splits, plan.steps_per_split, d_part);
+        else launch_rt<uint8_t, false>(plan.rt, grid, lds, stream, e, d_X, ldx, B, d_idx, pitch, d_codebook, k_sym, zero_first,
+                                       n, m, d_Y, ldy, tiles_n, tiles, x_vec, plan.splits, plan.steps_per_split, d_part);
     } else {
-        return hipErrorInvalidValue;
+        if (lut_lds) launch_rt<uint16_t, true>(plan.rt, grid, lds, stream, e, d_X, ldx, B, d_idx, pitch, d_codebook, k_sym, zero_first,
+                                               n, m, d_Y, ldy, tiles_n, tiles, x_vec, plan.splits, plan.steps_per_split, d_part);
+        else launch_rt<uint16_t, false>(plan.rt, grid, lds, stream, e, d_X, ldx, B, d_idx, pitch, d_codebook, k_sym, zero_first,
+                                        n, m, d_Y, ldy, tiles_n, tiles, x_vec, plan.splits, plan.steps_per_split, d_part);
     }
-    hipError_t e = hipGetLastError();
     if (e != hipSuccess || plan.splits == 1) return e;
     const uint64_t total = (uint64_t)B * m;
     const uint32_t rgrid = (uint32_t)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);

@@ -11,7 +11,8 @@ namespace hac_internal {
 // How launch_index_gemm splits the work: `tiles` output tiles, each K loop of `steps` steps cut into
 // `splits` ranges of steps_per_split; with more than one split the partial tiles go through a buffer
 // of part_bytes bytes (splits x B x m floats) and are added in order by a second kernel.
-struct GemmPlan { uint64_t tiles; uint32_t steps, splits, steps_per_split; size_t part_bytes; };
+// A block covers 32 * rt batch rows (rt = 2..8) and 128 columns.
+struct GemmPlan { uint64_t tiles; uint32_t steps, splits, steps_per_split, rt; size_t part_bytes; };
 GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m);
 
 // Y[B x m] = X[B x n] . c[Pi] for an index map Pi of n rows, `pitch` elements apart (a multiple of
