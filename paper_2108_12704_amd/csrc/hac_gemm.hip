@@ -299,10 +299,10 @@ GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m)
     }
     p.rt = (uint32_t)best_rt;
     const uint64_t tiles = (uint64_t)((B + 32 * best_rt - 1) / (32 * best_rt)) * tiles_n;
-    // a tile's K loop is serial (about 3 us per step of 32): with fewer tiles than CUs, K is split
-    // until there are about two work items per CU, keeping at least 8 steps per split
+    // a tile's K loop is serial (about 3 us per step of 32): with tiles for at most half of the
+    // CUs, K is split until there are about two work items per CU, keeping at least 8 steps per split
     uint32_t splits = 1;
-    if (tiles < 256) {
+    if (tiles <= 128) {
         splits = (uint32_t)((512 + tiles - 1) / tiles);
         const uint32_t most = steps / 8 ? steps / 8 : 1;
         if (splits > most) splits = most;
