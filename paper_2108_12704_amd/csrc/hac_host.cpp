@@ -3,6 +3,7 @@
 // IV-B (HAC) and IV-C (sHAC); the chunk index is this library's addition for
 // the GPU (the paper's conclusions only suggest per-column offsets).
 #include "../../include/hac.h"
+#include "hac_hostlib.h"
 
 #include <algorithm>
 #include <cmath>
@@ -16,16 +17,9 @@
 
 static_assert(sizeof(hac_desc_t) == 256, "blob header must be 256 bytes");
 
+using namespace hac_internal;
+
 namespace {
-
-constexpr uint32_t kMagic = 0x31434148u;   // "HAC1"
-constexpr uint32_t kVersion = 2;
-constexpr uint64_t kAlign = 256;
-constexpr uint64_t kTailPad = 64;          // zero bytes after stream / ri for window over-reads
-
-inline uint64_t align_up(uint64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
-
-inline uint32_t float_bits(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
 
 // ---- small open-addressing map: fp32 bit pattern -> dense id --------------------
 struct ValueMap {
@@ -60,6 +54,10 @@ struct ValueMap {
     }
 };
 
+} // namespace
+
+namespace hac_internal {
+
 // ---- Huffman code lengths: merge the two least frequent nodes (Huffman 1952) ---
 // Ties: lower (weight, node id) first; leaves are numbered by symbol, internal
 // nodes after them in creation order.  A one-symbol alphabet gets length 1.
@@ -92,12 +90,6 @@ bool huffman_lengths(const std::vector<uint64_t>& freq, std::vector<uint8_t>& le
     }
     return true;
 }
-
-struct CodeTables {
-    std::vector<uint32_t> code;        // canonical codeword per symbol (right-justified)
-    std::vector<uint32_t> symsort;     // symbols in (length, symbol) order
-    uint32_t first_code[33], count[33], first_index[33];
-};
 
 void canonical_codes(const std::vector<uint8_t>& len, CodeTables& t)
 {
@@ -136,6 +128,10 @@ void build_lut(const std::vector<uint8_t>& len, const CodeTables& t, uint32_t lu
         for (uint32_t e = 0; e < span; ++e) lut[lo + e] = ((uint32_t)s << 6) | l;
     }
 }
+
+} // namespace hac_internal
+
+namespace {
 
 // ---- bit writer: MSB-first into uint32 words; the buffer starts zeroed ----------
 struct BitWriter {
@@ -215,26 +211,34 @@ int scan_matrix(const float* W, int64_t n, int64_t m, int64_t ldw, Scan& s)
     return HAC_OK;
 }
 
-struct Section { uint64_t off, bytes; };
+} // namespace
 
-struct Layout {
-    hac_desc_t d;
-    uint64_t cursor;
-    Layout() { std::memset(&d, 0, sizeof d); cursor = sizeof(hac_desc_t); }
-    uint64_t place(uint64_t bytes) { uint64_t o = align_up(cursor); cursor = o + bytes; return o; }
-};
+namespace hac_internal {
 
 uint32_t ceil_log2(uint64_t v) { uint32_t b = 0; while (((uint64_t)1 << b) < v) ++b; return b; }
 
-int check_args(const float* W, int64_t n, int64_t m, int64_t ldw, void** blob, size_t* bytes)
+// Section offsets and total size from the counts already in the header.  One order for all
+// formats: code tables, stream, per-column arrays, chunk entries, and ri when it is stored as fields.
+void place_sections(hac_desc_t& d)
 {
-    if (!W || !blob || !bytes) return HAC_EINVAL;
-    if (n < 1 || m < 1 || ldw < m) return HAC_EINVAL;
-    if (n > 0x7fffffffll || m > 0x7fffffffll) return HAC_ERANGE;
-    return HAC_OK;
+    uint64_t cursor = sizeof(hac_desc_t);
+    auto place = [&](uint64_t bytes) { const uint64_t o = align_up(cursor); cursor = o + bytes; return o; };
+    d.off_codebook = place(4ull * d.k_sym);
+    d.off_codelen = place(d.k_sym);
+    d.off_canon = place(3 * 33 * 4);
+    d.off_symsort = place(4ull * d.k_sym);
+    d.off_lut = place(4ull << d.lut_bits);
+    d.off_stream = place(4 * d.n_words + kTailPad);
+    d.off_col_chunk = place(4 * (d.m + 1));
+    d.off_col_pos = place(4 * (d.m + 1));
+    d.off_col_bit = place(4 * (d.m + 1));
+    d.off_chunk_ent = place(d.n_chunks * (d.ent_bits / 8) + 8);
+    if (d.format == HAC_FORMAT_SHAC && d.ri_coding == HAC_RI_FIELDS)
+        d.off_ri = place(4 * ((d.nnz * d.ri_bits + 31) / 32) + kTailPad);
+    d.blob_bytes = align_up(cursor);
 }
 
-// Fills the sections common to both formats (tables) and returns the blob.
+// Fills the sections common to all stream formats (tables).
 int write_tables(uint8_t* base, const hac_desc_t& d, const std::vector<float>& codebook,
                  const std::vector<uint8_t>& len, const CodeTables& t, const std::vector<uint32_t>& lut)
 {
@@ -269,6 +273,29 @@ int check_opts(const hac_opts_t* opts)
     return HAC_OK;
 }
 
+uint32_t rice_length(uint32_t d, uint32_t k)
+{
+    const uint32_t q = d >> k;
+    return q < kRiceEscape ? q + 1 + k : kRiceEscape + 1 + 32;
+}
+
+} // namespace hac_internal
+
+namespace {
+
+struct Layout {
+    hac_desc_t d;
+    Layout() { std::memset(&d, 0, sizeof d); }
+};
+
+int check_args(const float* W, int64_t n, int64_t m, int64_t ldw, void** blob, size_t* bytes)
+{
+    if (!W || !blob || !bytes) return HAC_EINVAL;
+    if (n < 1 || m < 1 || ldw < m) return HAC_EINVAL;
+    if (n > 0x7fffffffll || m > 0x7fffffffll) return HAC_ERANGE;
+    return HAC_OK;
+}
+
 // Column-wise chunk bookkeeping shared by both encoders.
 struct ColumnIndex {
     std::vector<uint32_t> col_chunk, col_pos, col_bit;   // m + 1 each
@@ -289,15 +316,6 @@ struct ColumnIndex {
 };
 
 // ---- Golomb-Rice code of the row gaps (sHAC with ri_coding = HAC_RI_RICE) ----
-constexpr uint32_t kRiceEscape = 31;     // quotients from here on: 31 zeros, a one, the gap in 32 bits
-constexpr uint32_t kRiceKMax = 15;
-
-inline uint32_t rice_length(uint32_t d, uint32_t k)
-{
-    const uint32_t q = d >> k;
-    return q < kRiceEscape ? q + 1 + k : kRiceEscape + 1 + 32;
-}
-
 // gap of CSC position p: rows skipped since the previous non-zero of the column (or its top)
 inline uint32_t gap_at(const Scan& s, uint64_t p, uint64_t col_first)
 {
@@ -372,17 +390,7 @@ extern "C" int hac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         d.has_zero = has_zero; d.zero_len = zero_len; d.chunk = Cn; d.ri_bits = 0;
         d.ent_bits = ent_bits; d.row_bits = ent_bits == 32 ? row_bits : 0; d.n_chunks = ci.n_chunks;
         d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
-        d.off_codebook = L.place(4ull * d.k_sym);
-        d.off_codelen = L.place(d.k_sym);
-        d.off_canon = L.place(3 * 33 * 4);
-        d.off_symsort = L.place(4ull * d.k_sym);
-        d.off_lut = L.place(4ull << lut_bits);
-        d.off_stream = L.place(4 * n_words + kTailPad);
-        d.off_col_chunk = L.place(4 * ((uint64_t)m + 1));
-        d.off_col_pos = L.place(4 * ((uint64_t)m + 1));
-        d.off_col_bit = L.place(4 * ((uint64_t)m + 1));
-        d.off_chunk_ent = L.place(ci.n_chunks * (ent_bits / 8) + 8);
-        d.blob_bytes = align_up(L.cursor);
+        place_sections(d);
 
         uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
         if (!base) return HAC_ENOMEM;
@@ -495,17 +503,7 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
             d.ent_bits = ent_bits; d.row_bits = ent_bits == 32 ? row_bits : 0; d.n_chunks = ci.n_chunks;
             d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
             d.ri_coding = HAC_RI_RICE; d.rice_k = k; d.gap_bits = gap_bits;
-            d.off_codebook = L.place(4ull * d.k_sym);
-            d.off_codelen = L.place(d.k_sym);
-            d.off_canon = L.place(3 * 33 * 4);
-            d.off_symsort = L.place(4ull * d.k_sym);
-            d.off_lut = L.place(4ull << lut_bits);
-            d.off_stream = L.place(4 * n_words + kTailPad);
-            d.off_col_chunk = L.place(4 * ((uint64_t)m + 1));
-            d.off_col_pos = L.place(4 * ((uint64_t)m + 1));
-            d.off_col_bit = L.place(4 * ((uint64_t)m + 1));
-            d.off_chunk_ent = L.place(ci.n_chunks * (ent_bits / 8) + 8);
-            d.blob_bytes = align_up(L.cursor);
+            place_sections(d);
 
             uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
             if (!base) return HAC_ENOMEM;
@@ -556,7 +554,6 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         }
         const uint32_t ent_bits = max_col_bits < 65536 ? 16 : 32;
         const uint64_t n_words = (total_bits + 31) / 32;
-        const uint64_t ri_words = (nnz * ri_bits + 31) / 32;
         if (nnz * (uint64_t)ri_bits > 0xfffffff0ull * 32ull) return HAC_ERANGE;
 
         Layout L;
@@ -567,18 +564,7 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         d.has_zero = 0; d.zero_len = 0; d.chunk = Cn; d.ri_bits = ri_bits;
         d.ent_bits = ent_bits; d.row_bits = 0; d.n_chunks = ci.n_chunks;
         d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
-        d.off_codebook = L.place(4ull * d.k_sym);
-        d.off_codelen = L.place(d.k_sym);
-        d.off_canon = L.place(3 * 33 * 4);
-        d.off_symsort = L.place(4ull * d.k_sym);
-        d.off_lut = L.place(4ull << lut_bits);
-        d.off_stream = L.place(4 * n_words + kTailPad);
-        d.off_col_chunk = L.place(4 * ((uint64_t)m + 1));
-        d.off_col_pos = L.place(4 * ((uint64_t)m + 1));
-        d.off_col_bit = L.place(4 * ((uint64_t)m + 1));
-        d.off_chunk_ent = L.place(ci.n_chunks * (ent_bits / 8) + 8);
-        d.off_ri = L.place(4 * ri_words + kTailPad);
-        d.blob_bytes = align_up(L.cursor);
+        place_sections(d);
 
         uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
         if (!base) return HAC_ENOMEM;
@@ -643,9 +629,9 @@ extern "C" int im_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = s.ri.size();
         d.total_bits = (uint64_t)bits * (uint64_t)n * (uint64_t)m;
         d.k_sym = (uint32_t)k; d.has_zero = has_zero; d.ent_bits = bits; d.idx_pitch = pitch;
-        d.off_codebook = L.place(4 * k);
-        d.off_stream = L.place((uint64_t)n * pitch * (bits / 8) + kTailPad);
-        d.blob_bytes = align_up(L.cursor);
+        d.off_codebook = align_up(sizeof(hac_desc_t));
+        d.off_stream = align_up(d.off_codebook + 4 * k);
+        d.blob_bytes = align_up(d.off_stream + (uint64_t)n * pitch * (bits / 8) + kTailPad);
         uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
         if (!base) return HAC_ENOMEM;
         std::memcpy(base, &d, sizeof d);

@@ -1,0 +1,48 @@
+// Host-side pieces of libhac shared by its translation units (not part of the C ABI).
+#ifndef HAC_HOSTLIB_H
+#define HAC_HOSTLIB_H
+
+#include <stdint.h>
+#include <string.h>
+
+#include <vector>
+
+#include "../../include/hac.h"
+
+namespace hac_internal {
+
+constexpr uint32_t kMagic = 0x31434148u;   // "HAC1"
+constexpr uint32_t kVersion = 2;
+constexpr uint64_t kAlign = 256;
+constexpr uint64_t kTailPad = 64;          // zero bytes after stream / ri for window over-reads
+constexpr uint32_t kRiceEscape = 31;       // quotients from here on: 31 zeros, a one, the gap in 32 bits
+constexpr uint32_t kRiceKMax = 15;
+
+inline uint64_t align_up(uint64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline uint32_t float_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+
+// Huffman code lengths by merging the two least frequent nodes; false when a length exceeds 32.
+bool huffman_lengths(const std::vector<uint64_t>& freq, std::vector<uint8_t>& len, uint32_t& lmax);
+
+struct CodeTables {
+    std::vector<uint32_t> code;        // canonical codeword per symbol (right-justified)
+    std::vector<uint32_t> symsort;     // symbols in (length, symbol) order
+    uint32_t first_code[33], count[33], first_index[33];
+};
+void canonical_codes(const std::vector<uint8_t>& len, CodeTables& t);
+void build_lut(const std::vector<uint8_t>& len, const CodeTables& t, uint32_t lut_bits, std::vector<uint32_t>& lut);
+
+uint32_t ceil_log2(uint64_t v);
+uint32_t pick_lut_bits(const hac_opts_t* opts, uint32_t lmax);
+uint32_t pick_chunk(const hac_opts_t* opts, uint64_t max_col_nnz);
+int check_opts(const hac_opts_t* opts);
+uint32_t rice_length(uint32_t d, uint32_t k);
+
+// Offsets of all sections and blob_bytes, from the counts already in the header.
+void place_sections(hac_desc_t& d);
+int write_tables(uint8_t* base, const hac_desc_t& d, const std::vector<float>& codebook,
+                 const std::vector<uint8_t>& len, const CodeTables& t, const std::vector<uint32_t>& lut);
+
+} // namespace hac_internal
+
+#endif
