@@ -252,6 +252,22 @@ int hac_decode_host(const void *blob, size_t bytes, float *W_out, int32_t *sym_o
 
 /* ---- device side (asynchronous on `stream`) -------------------------------- */
 
+/* Encode on the device: W (n x m, row-major, leading dimension ldw >= m) is in
+ * device memory and so is the blob that comes out, byte for byte the blob
+ * hac_encode / shac_encode (format = HAC_FORMAT_HAC / HAC_FORMAT_SHAC) build on
+ * the host with the same options; opts->ri_coding must be HAC_RI_FIELDS.  The
+ * value histogram, the code bits and the bit packing run on the GPU; the Huffman
+ * code and the prefix sums over columns are made on the host in between, so the
+ * call synchronises `stream` (twice) and returns with the blob complete.
+ * d_ws: hac_encode_dev_workspace_bytes(n, m) bytes, 256-byte aligned.  *desc
+ * receives the header.  If d_blob is NULL or blob_capacity < desc->blob_bytes the
+ * call returns HAC_EWORKSPACE with desc filled in: allocate desc->blob_bytes
+ * (256-byte aligned) and call again.  n is limited to 65535 * 1024 rows. */
+size_t hac_encode_dev_workspace_bytes(int64_t n, int64_t m);
+int hac_encode_dev(uint32_t format, const float *d_W, int64_t n, int64_t m, int64_t ldw,
+                   const hac_opts_t *opts, void *d_blob, size_t blob_capacity, hac_desc_t *desc,
+                   void *d_ws, size_t ws_bytes, hac_stream_t stream);
+
 /* Bytes of device workspace hac_dot / shac_dot need for a batch of B rows with
  * default launch settings (0 when none is needed).  The workspace holds X re-laid
  * out feature-major, or, on the dense route (see hac_dot), the decoded index map

@@ -24,6 +24,7 @@ EXPORTS = (
     "hac_encode", "shac_encode", "hac_free", "hac_validate", "hac_describe", "hac_stats",
     "hac_decode_host", "hac_workspace_bytes", "hac_workspace_bytes_for", "hac_dot_route", "hac_dot", "shac_dot", "hac_decode_dev",
     "shac_decode_dev", "hac_strerror", "hac_last_hip_error", "im_encode", "im_dot",
+    "hac_encode_dev", "hac_encode_dev_workspace_bytes",
 )
 
 
@@ -91,6 +92,10 @@ def load_library() -> C.CDLL:
     lib.hac_encode.argtypes = enc_args
     lib.shac_encode.argtypes = enc_args
     lib.im_encode.argtypes = enc_args
+    lib.hac_encode_dev_workspace_bytes.argtypes = [C.c_int64, C.c_int64]
+    lib.hac_encode_dev_workspace_bytes.restype = C.c_size_t
+    lib.hac_encode_dev.argtypes = [C.c_uint32, vp, C.c_int64, C.c_int64, C.c_int64, C.POINTER(Opts), vp, C.c_size_t,
+                                   C.POINTER(Desc), vp, C.c_size_t, vp]
     lib.hac_free.argtypes = [vp]
     lib.hac_free.restype = None
     lib.hac_validate.argtypes = [vp, C.c_size_t, C.c_int]
@@ -296,6 +301,31 @@ def hac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=No
 def shac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=None):
     """Y = X . W for an sHAC blob on the device (asynchronous on the stream)."""
     return _dot("shac_dot", dblob, X, Y, workspace, launch, stream)
+
+
+def hac_encode_dev(W, fmt: int = HAC_FORMAT_HAC, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0,
+                   stream=None) -> DeviceBlob:
+    """Encode a device matrix (2-D float32 CUDA tensor, unit column stride) on the device.
+
+    Calls the library twice: once to learn the blob's size, once to fill it.  Synchronises the stream.
+    """
+    import torch
+    if W.dtype != torch.float32 or W.dim() != 2 or not W.is_cuda or W.stride(1) != 1:
+        raise TypeError("W must be a 2-D float32 CUDA tensor with unit column stride")
+    lib = load_library()
+    n, m = W.shape
+    ldw = W.stride(0) if n > 1 else max(m, 1)
+    ws = torch.empty(lib.hac_encode_dev_workspace_bytes(n, m), dtype=torch.uint8, device=W.device)
+    opts = Opts(chunk_nnz, ri_bits, lut_bits, 0)
+    desc = Desc()
+    sh = _stream_handle(stream)
+    rc = lib.hac_encode_dev(fmt, W.data_ptr(), n, m, ldw, C.byref(opts), None, 0, C.byref(desc), ws.data_ptr(), ws.numel(), sh)
+    if rc != -6:
+        _check(rc, "hac_encode_dev")
+    blob = torch.empty(int(desc.blob_bytes), dtype=torch.uint8, device=W.device)
+    _check(lib.hac_encode_dev(fmt, W.data_ptr(), n, m, ldw, C.byref(opts), blob.data_ptr(), blob.numel(), C.byref(desc),
+                              ws.data_ptr(), ws.numel(), sh), "hac_encode_dev")
+    return DeviceBlob(desc, blob)
 
 
 def hac_dot_route(desc: Desc, B: int, launch: Optional["Launch"] = None) -> int:

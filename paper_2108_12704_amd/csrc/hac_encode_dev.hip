@@ -1,0 +1,405 @@
+// GPU-side encoder: builds a HAC or sHAC blob (arXiv 2108.12704 Sect. IV-B / IV-C) from a matrix
+// that already lives in device memory, byte for byte the blob hac_encode / shac_encode would build
+// on the host.
+//
+// The steps of the host encoder, split between device and host:
+//   1. device  histogram of the distinct fp32 values (a hash table keyed by bit pattern, privatised
+//              in LDS per block) and the number of non-zeros of every (row segment, column);
+//   2. host    alphabet in value order, Huffman lengths, canonical code, decode tables;
+//   3. device  code bits and last non-zero row of every (row segment, column);
+//   4. host    prefix sums along each column: first stream bit / CSC position of every segment and
+//              column, where the non-zero before a segment ended, chunk counts, section offsets;
+//   5. device  one thread per (row segment, column) walks its rows and writes codewords (and
+//              row-index fields) with atomic ORs into the zeroed stream, and the chunk entries.
+// A thread owns one column of a segment of 1024 rows, so the 64 lanes of a wave read 64
+// neighbouring columns of one row: coalesced reads of the row-major matrix in all three passes.
+// The call synchronises the stream twice (steps 2 and 4 need the device's results).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "hac_hostlib.h"
+
+namespace {
+
+using namespace hac_internal;
+
+constexpr uint32_t kHashSlots = 1u << 17;          // distinct values <= 65536 keep the load below 1/2
+constexpr uint32_t kSegRows = 1024;
+constexpr uint32_t kLocalSlots = 1024;
+constexpr uint32_t kFlagNonFinite = 1u, kFlagTableFull = 2u;
+
+__host__ __device__ inline uint32_t mix32(uint32_t k)
+{
+    k ^= k >> 16; k *= 0x7feb352du; k ^= k >> 15; k *= 0x846ca68bu; k ^= k >> 16;
+    return k;
+}
+
+__global__ void fill_zero_kernel(uint32_t* p, uint64_t count)
+{
+    uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) p[i] = 0u;
+}
+
+__device__ void table_add(uint32_t* keys, uint32_t* cnts, uint32_t* flags, uint32_t key, uint32_t add)
+{
+    uint32_t h = mix32(key) & (kHashSlots - 1);
+    for (uint32_t probe = 0; probe < kHashSlots; ++probe) {
+        const uint32_t old = atomicCAS(&keys[h], 0u, key);
+        if (old == 0u || old == key) { atomicAdd(&cnts[h], add); return; }
+        h = (h + 1) & (kHashSlots - 1);
+    }
+    atomicOr(flags, kFlagTableFull);
+}
+
+// step 1
+__global__ void __launch_bounds__(256)
+enc_scan_kernel(const float* __restrict__ W, uint32_t n, uint32_t m, uint64_t ldw,
+                uint32_t* keys, uint32_t* cnts, uint32_t* seg_nnz, uint32_t* flags)
+{
+    __shared__ uint32_t lk[kLocalSlots], lc[kLocalSlots];
+    for (uint32_t i = threadIdx.x; i < kLocalSlots; i += 256) { lk[i] = 0u; lc[i] = 0u; }
+    __syncthreads();
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x, seg = blockIdx.y;
+    const uint32_t r0 = seg * kSegRows, r1 = r0 + kSegRows < n ? r0 + kSegRows : n;
+    uint32_t count = 0;
+    if (j < m) {
+        for (uint32_t r = r0; r < r1; ++r) {
+            const float v = W[(uint64_t)r * ldw + j];
+            if (v == 0.0f) continue;                                 // +0.0 and -0.0 are the null entry
+            if (!isfinite(v)) { atomicOr(flags, kFlagNonFinite); continue; }
+            ++count;
+            const uint32_t key = __float_as_uint(v);
+            uint32_t h = mix32(key) & (kLocalSlots - 1);
+            bool done = false;
+            for (uint32_t probe = 0; probe < 64 && !done; ++probe) {
+                const uint32_t old = atomicCAS(&lk[h], 0u, key);
+                if (old == 0u || old == key) { atomicAdd(&lc[h], 1u); done = true; }
+                h = (h + 1) & (kLocalSlots - 1);
+            }
+            if (!done) table_add(keys, cnts, flags, key, 1u);        // the block's table is crowded
+        }
+        seg_nnz[(uint64_t)seg * m + j] = count;
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < kLocalSlots; i += 256)
+        if (lk[i]) table_add(keys, cnts, flags, lk[i], lc[i]);
+}
+
+__device__ __forceinline__ uint32_t symbol_of(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ slot_sym,
+                                              uint32_t key)
+{
+    uint32_t h = mix32(key) & (kHashSlots - 1);
+    for (uint32_t probe = 0; probe < kHashSlots; ++probe) {         // the key is in the table: step 1 put it there
+        if (keys[h] == key) return slot_sym[h];
+        h = (h + 1) & (kHashSlots - 1);
+    }
+    return 0u;
+}
+
+// step 3
+__global__ void __launch_bounds__(256)
+enc_bits_kernel(const float* __restrict__ W, uint32_t n, uint32_t m, uint64_t ldw,
+                const uint32_t* __restrict__ keys, const uint32_t* __restrict__ slot_sym,
+                const uint8_t* __restrict__ lens, uint32_t* seg_codebits, uint32_t* seg_last)
+{
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x, seg = blockIdx.y;
+    if (j >= m) return;
+    const uint32_t r0 = seg * kSegRows, r1 = r0 + kSegRows < n ? r0 + kSegRows : n;
+    uint32_t bits = 0, last = 0xffffffffu;
+    for (uint32_t r = r0; r < r1; ++r) {
+        const float v = W[(uint64_t)r * ldw + j];
+        if (v == 0.0f) continue;
+        bits += lens[symbol_of(keys, slot_sym, __float_as_uint(v))];
+        last = r;
+    }
+    seg_codebits[(uint64_t)seg * m + j] = bits;
+    seg_last[(uint64_t)seg * m + j] = last;
+}
+
+// `len` bits of `code` (right-justified), MSB first, at stream bit `bit`; the words start zeroed
+__device__ __forceinline__ void put_bits(uint32_t* words, uint64_t bit, uint32_t code, uint32_t len)
+{
+    const uint64_t w = bit >> 5;
+    const uint32_t off = (uint32_t)(bit & 31);
+    const uint64_t v = (uint64_t)code << (64 - len - off);          // 1 <= len <= 32, off <= 31
+    const uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+    if (hi) atomicOr(&words[w], hi);
+    if (lo) atomicOr(&words[w + 1], lo);
+}
+
+struct EmitArgs {
+    const float* W; uint32_t n, m; uint64_t ldw;
+    const uint32_t* keys; const uint32_t* slot_sym; const uint32_t* codes; const uint8_t* lens;
+    const uint32_t* seg_bit0; const uint32_t* seg_pos0; const uint32_t* seg_prev_end; const uint32_t* seg_prev_row1;
+    const uint32_t* col_bit; const uint32_t* col_pos; const uint32_t* col_chunk;
+    uint32_t* stream; void* ent; uint32_t* ri;
+    uint32_t shac, has_zero, zcode, zlen, chunk, ent_bits, row_bits, ri_bits;
+};
+
+// step 5
+__global__ void __launch_bounds__(256) enc_emit_kernel(EmitArgs a)
+{
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x, seg = blockIdx.y;
+    if (j >= a.m) return;
+    const uint32_t r0 = seg * kSegRows, r1 = r0 + kSegRows < a.n ? r0 + kSegRows : a.n;
+    const uint64_t at = (uint64_t)seg * a.m + j;
+    uint32_t bit = a.seg_bit0[at], pos = a.seg_pos0[at];
+    uint32_t pend = a.seg_prev_end[at], prow = a.seg_prev_row1[at];   // HAC: where the non-zero before this one ended
+    const uint32_t cbit0 = a.col_bit[j], cpos0 = a.col_pos[j], cchunk0 = a.col_chunk[j];
+    const uint32_t shift = (!a.shac && a.has_zero) ? 1u : 0u;          // HAC numbers 0.0 as symbol 0
+    for (uint32_t r = r0; r < r1; ++r) {
+        const float v = a.W[(uint64_t)r * a.ldw + j];
+        if (v == 0.0f) {
+            if (!a.shac) {
+                if (a.zcode) put_bits(a.stream, bit, a.zcode, a.zlen);  // an all-zero codeword is already there
+                bit += a.zlen;
+            }
+            continue;
+        }
+        const uint32_t sym = symbol_of(a.keys, a.slot_sym, __float_as_uint(v)) + shift;
+        const uint32_t len = a.lens[sym];
+        const uint32_t q = pos - cpos0;
+        if (q % a.chunk == 0) {
+            const uint32_t g = cchunk0 + q / a.chunk;
+            if (a.shac) {
+                const uint32_t rel = bit - cbit0;
+                if (a.ent_bits == 16) static_cast<uint16_t*>(a.ent)[g] = (uint16_t)rel;
+                else static_cast<uint32_t*>(a.ent)[g] = rel;
+            } else {
+                const uint32_t rel = pend - cbit0;
+                if (a.ent_bits == 32) static_cast<uint32_t*>(a.ent)[g] = (rel << a.row_bits) | prow;
+                else { static_cast<uint32_t*>(a.ent)[2 * (uint64_t)g] = prow; static_cast<uint32_t*>(a.ent)[2 * (uint64_t)g + 1] = rel; }
+            }
+        }
+        put_bits(a.stream, bit, a.codes[sym], len);
+        bit += len;
+        pend = bit; prow = r + 1;
+        if (a.shac) put_bits(a.ri, (uint64_t)pos * a.ri_bits, r, a.ri_bits);
+        ++pos;
+    }
+}
+
+struct WsLayout {
+    size_t keys, cnts, flags, seg_nnz, seg_codebits, seg_last, seg_bit0, seg_pos0, seg_prev_end, seg_prev_row1,
+           slot_sym, codes, lens, total;
+};
+
+WsLayout ws_layout(uint64_t n, uint64_t m)
+{
+    const uint64_t S = (n + kSegRows - 1) / kSegRows;
+    WsLayout L;
+    size_t c = 0;
+    auto take = [&](size_t bytes) { const size_t o = c; c = (c + bytes + 255) / 256 * 256; return o; };
+    L.keys = take(4ull * kHashSlots); L.cnts = take(4ull * kHashSlots); L.flags = take(256);
+    L.seg_nnz = take(4 * S * m); L.seg_codebits = take(4 * S * m); L.seg_last = take(4 * S * m);
+    L.seg_bit0 = take(4 * S * m); L.seg_pos0 = take(4 * S * m); L.seg_prev_end = take(4 * S * m); L.seg_prev_row1 = take(4 * S * m);
+    L.slot_sym = take(4ull * kHashSlots); L.codes = take(4ull * 65537); L.lens = take(65537);
+    L.total = c;
+    return L;
+}
+
+int hip_fail(hipError_t e) { hac_internal::set_last_hip_error((int)e); return HAC_EHIP; }
+
+} // namespace
+
+extern "C" size_t hac_encode_dev_workspace_bytes(int64_t n, int64_t m)
+{
+    if (n < 1 || m < 1 || n > 0x7fffffffll || m > 0x7fffffffll) return 0;
+    return ws_layout((uint64_t)n, (uint64_t)m).total;
+}
+
+extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int64_t m, int64_t ldw,
+                              const hac_opts_t* opts, void* d_blob, size_t blob_capacity, hac_desc_t* desc,
+                              void* d_ws, size_t ws_bytes, hac_stream_t stream_)
+{
+    if (!d_W || !desc || !d_ws) return HAC_EINVAL;
+    if (format != HAC_FORMAT_HAC && format != HAC_FORMAT_SHAC) return HAC_EINVAL;
+    if (n < 1 || m < 1 || ldw < m) return HAC_EINVAL;
+    if (n > 0x7fffffffll || m > 0x7fffffffll) return HAC_ERANGE;
+    if ((n + kSegRows - 1) / kSegRows > 65535) return HAC_ERANGE;     // one grid row per segment of 1024 rows
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    if (opts && opts->ri_coding) return HAC_EINVAL;                   // Rice-coded gaps: host encoder only
+    const bool shac = format == HAC_FORMAT_SHAC;
+    const uint32_t need_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
+    uint32_t ri_bits = 0;
+    if (shac) {
+        ri_bits = opts && opts->ri_bits ? opts->ri_bits : need_bits;
+        if (ri_bits < need_bits || ri_bits > 32) return HAC_EINVAL;
+    }
+    if (reinterpret_cast<uintptr_t>(d_ws) % 256 || (d_blob && reinterpret_cast<uintptr_t>(d_blob) % 256)) return HAC_EINVAL;
+    const WsLayout L = ws_layout((uint64_t)n, (uint64_t)m);
+    if (ws_bytes < L.total) return HAC_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    hac_internal::set_last_hip_error(0);
+    uint8_t* ws = static_cast<uint8_t*>(d_ws);
+    auto dptr = [&](size_t off) { return reinterpret_cast<uint32_t*>(ws + off); };
+    const uint32_t S = (uint32_t)(((uint64_t)n + kSegRows - 1) / kSegRows);
+    const size_t SM = (size_t)S * (size_t)m;
+    const dim3 grid((uint32_t)((m + 255) / 256), S);
+    hipError_t e;
+    try {
+        // ---- step 1 ----
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(512), dim3(256), 0, stream, dptr(L.keys), (uint64_t)(L.seg_nnz - L.keys) / 4);
+        hipLaunchKernelGGL(enc_scan_kernel, grid, dim3(256), 0, stream, d_W, (uint32_t)n, (uint32_t)m, (uint64_t)ldw,
+                           dptr(L.keys), dptr(L.cnts), dptr(L.seg_nnz), dptr(L.flags));
+        if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
+        std::vector<uint32_t> keys(kHashSlots), cnts(kHashSlots), seg_nnz(SM);
+        uint32_t flags = 0;
+        if ((e = hipMemcpyAsync(keys.data(), dptr(L.keys), 4ull * kHashSlots, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(cnts.data(), dptr(L.cnts), 4ull * kHashSlots, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(&flags, dptr(L.flags), 4, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(seg_nnz.data(), dptr(L.seg_nnz), 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
+        if (flags & kFlagNonFinite) return HAC_EINVAL;
+        if (flags & kFlagTableFull) return HAC_ERANGE;
+
+        // ---- step 2 ----
+        struct Val { float v; uint32_t slot; uint64_t f; };
+        std::vector<Val> vals;
+        uint64_t nnz = 0;
+        for (uint32_t h = 0; h < kHashSlots; ++h)
+            if (keys[h]) { Val x; std::memcpy(&x.v, &keys[h], 4); x.slot = h; x.f = cnts[h]; vals.push_back(x); nnz += cnts[h]; }
+        if (vals.size() > 65536) return HAC_ERANGE;
+        if (nnz > 0xfffffff0ull) return HAC_ERANGE;
+        std::sort(vals.begin(), vals.end(), [](const Val& a, const Val& b) { return a.v < b.v; });
+        const uint64_t zeros = (uint64_t)n * (uint64_t)m - nnz;
+        const bool has_zero = !shac && zeros > 0;
+        const uint32_t shift = has_zero ? 1u : 0u;
+        std::vector<float> codebook;
+        std::vector<uint64_t> freq;
+        if (has_zero) { codebook.push_back(0.0f); freq.push_back(zeros); }
+        for (const Val& x : vals) { codebook.push_back(x.v); freq.push_back(x.f); }
+        std::vector<uint8_t> len; uint32_t lmax = 0;
+        if (!huffman_lengths(freq, len, lmax)) return HAC_ERANGE;
+        CodeTables t; canonical_codes(len, t);
+        uint64_t total_bits = 0;
+        for (size_t i = 0; i < freq.size(); ++i) total_bits += freq[i] * len[i];
+        if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
+        const uint32_t lut_bits = pick_lut_bits(opts, lmax);
+        if (lut_bits < 1 || lut_bits > 12) return HAC_EINVAL;
+        std::vector<uint32_t> lut; build_lut(len, t, lut_bits, lut);
+        const uint32_t zlen = has_zero ? len[0] : 0, zcode = has_zero ? t.code[0] : 0;
+
+        std::vector<uint32_t> slot_sym(kHashSlots, 0);
+        for (size_t i = 0; i < vals.size(); ++i) slot_sym[vals[i].slot] = (uint32_t)i;      // index among the non-zero values
+        // the device looks lengths up by "index among the non-zero values" in step 3 and by symbol in step 5
+        std::vector<uint8_t> nz_len(vals.size());
+        for (size_t i = 0; i < vals.size(); ++i) nz_len[i] = len[i + shift];
+        if ((e = hipMemcpyAsync(dptr(L.slot_sym), slot_sym.data(), 4ull * kHashSlots, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if (!nz_len.empty() && (e = hipMemcpyAsync(ws + L.lens, nz_len.data(), nz_len.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+
+        // ---- step 3 ----
+        hipLaunchKernelGGL(enc_bits_kernel, grid, dim3(256), 0, stream, d_W, (uint32_t)n, (uint32_t)m, (uint64_t)ldw,
+                           dptr(L.keys), dptr(L.slot_sym), ws + L.lens, dptr(L.seg_codebits), dptr(L.seg_last));
+        if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
+        std::vector<uint32_t> seg_codebits(SM), seg_last(SM);
+        if ((e = hipMemcpyAsync(seg_codebits.data(), dptr(L.seg_codebits), 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(seg_last.data(), dptr(L.seg_last), 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
+
+        // ---- step 4 ----
+        uint64_t max_col_nnz = 0;
+        std::vector<uint64_t> col_nnz((size_t)m, 0);
+        for (uint32_t s = 0; s < S; ++s)
+            for (int64_t j = 0; j < m; ++j) col_nnz[(size_t)j] += seg_nnz[(size_t)s * m + j];
+        for (int64_t j = 0; j < m; ++j) max_col_nnz = std::max(max_col_nnz, col_nnz[(size_t)j]);
+        const uint32_t Cn = pick_chunk(opts, max_col_nnz);
+        std::vector<uint32_t> col_bit((size_t)m + 1), col_pos((size_t)m + 1), col_chunk((size_t)m + 1);
+        std::vector<uint32_t> seg_bit0(SM), seg_pos0(SM), seg_prev_end(SM), seg_prev_row1(SM);
+        uint64_t bit = 0, pos = 0, chunks = 0, max_col_bits = 0;
+        for (int64_t j = 0; j < m; ++j) {
+            col_bit[(size_t)j] = (uint32_t)bit; col_pos[(size_t)j] = (uint32_t)pos; col_chunk[(size_t)j] = (uint32_t)chunks;
+            const uint64_t bit_j = bit;
+            uint64_t prev_end = bit, prev_row1 = 0;
+            for (uint32_t s = 0; s < S; ++s) {
+                const size_t at = (size_t)s * m + j;
+                const uint64_t r0 = (uint64_t)s * kSegRows, r1 = std::min<uint64_t>(r0 + kSegRows, (uint64_t)n);
+                seg_bit0[at] = (uint32_t)bit; seg_pos0[at] = (uint32_t)pos;
+                seg_prev_end[at] = (uint32_t)prev_end; seg_prev_row1[at] = (uint32_t)prev_row1;
+                const uint64_t cnt = seg_nnz[at];
+                const uint64_t seg_bits = seg_codebits[at] + (shac ? 0 : (r1 - r0 - cnt) * zlen);
+                if (cnt) {
+                    const uint64_t trailing = r1 - 1 - seg_last[at];                 // zeros after the segment's last non-zero
+                    prev_end = bit + seg_bits - (shac ? 0 : trailing * zlen);
+                    prev_row1 = (uint64_t)seg_last[at] + 1;
+                }
+                bit += seg_bits; pos += cnt;
+            }
+            chunks += (col_nnz[(size_t)j] + Cn - 1) / Cn;
+            max_col_bits = std::max(max_col_bits, bit - bit_j);
+        }
+        col_bit[(size_t)m] = (uint32_t)bit; col_pos[(size_t)m] = (uint32_t)pos; col_chunk[(size_t)m] = (uint32_t)chunks;
+        if (bit != total_bits || pos != nnz) return HAC_EFORMAT;
+        if (chunks > 0xfffffff0ull) return HAC_ERANGE;
+
+        hac_desc_t d;
+        std::memset(&d, 0, sizeof d);
+        d.magic = kMagic; d.version = kVersion; d.format = format; d.header_bytes = 256;
+        d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = nnz; d.total_bits = total_bits; d.n_words = (total_bits + 31) / 32;
+        d.k_sym = (uint32_t)codebook.size(); d.lmax = lmax; d.lut_bits = lut_bits;
+        d.chunk = Cn; d.n_chunks = chunks; d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
+        if (shac) {
+            d.ri_bits = ri_bits;
+            d.ent_bits = max_col_bits < 65536 ? 16 : 32;
+            if (nnz * (uint64_t)ri_bits > 0xfffffff0ull * 32ull) return HAC_ERANGE;
+        } else {
+            d.has_zero = has_zero ? 1 : 0;
+            d.zero_len = (has_zero && zcode == 0) ? zlen : 0;
+            const uint32_t brel_bits = std::max<uint32_t>(ceil_log2(max_col_bits + 1), 1);
+            d.ent_bits = need_bits + brel_bits <= 32 ? 32 : 64;
+            d.row_bits = d.ent_bits == 32 ? need_bits : 0;
+        }
+        place_sections(d);
+        *desc = d;
+        if (!d_blob || blob_capacity < d.blob_bytes) return HAC_EWORKSPACE;         // desc->blob_bytes says how much
+
+        // head of the blob (header, tables, per-column arrays) is assembled here and copied over
+        const size_t head_bytes = (size_t)d.off_stream;
+        std::vector<uint8_t> head(head_bytes, 0);
+        std::memcpy(head.data(), &d, sizeof d);
+        write_tables(head.data(), d, codebook, len, t, lut);
+        uint8_t* blob = static_cast<uint8_t*>(d_blob);
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(blob + d.off_stream),
+                           (uint64_t)(d.blob_bytes - d.off_stream) / 4);
+        if ((e = hipMemcpyAsync(blob, head.data(), head_bytes, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(blob + d.off_col_chunk, col_chunk.data(), 4 * ((size_t)m + 1), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(blob + d.off_col_pos, col_pos.data(), 4 * ((size_t)m + 1), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(blob + d.off_col_bit, col_bit.data(), 4 * ((size_t)m + 1), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(dptr(L.seg_bit0), seg_bit0.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(dptr(L.seg_pos0), seg_pos0.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(dptr(L.seg_prev_end), seg_prev_end.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(dptr(L.seg_prev_row1), seg_prev_row1.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        // step 5 looks codes and lengths up by symbol
+        if (!t.code.empty() && (e = hipMemcpyAsync(dptr(L.codes), t.code.data(), 4 * t.code.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if (!len.empty() && (e = hipMemcpyAsync(ws + L.lens, len.data(), len.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+
+        // ---- step 5 ----
+        EmitArgs a;
+        a.W = d_W; a.n = (uint32_t)n; a.m = (uint32_t)m; a.ldw = (uint64_t)ldw;
+        a.keys = dptr(L.keys); a.slot_sym = dptr(L.slot_sym); a.codes = dptr(L.codes); a.lens = ws + L.lens;
+        a.seg_bit0 = dptr(L.seg_bit0); a.seg_pos0 = dptr(L.seg_pos0); a.seg_prev_end = dptr(L.seg_prev_end); a.seg_prev_row1 = dptr(L.seg_prev_row1);
+        a.col_bit = reinterpret_cast<const uint32_t*>(blob + d.off_col_bit);
+        a.col_pos = reinterpret_cast<const uint32_t*>(blob + d.off_col_pos);
+        a.col_chunk = reinterpret_cast<const uint32_t*>(blob + d.off_col_chunk);
+        a.stream = reinterpret_cast<uint32_t*>(blob + d.off_stream);
+        a.ent = blob + d.off_chunk_ent;
+        a.ri = shac ? reinterpret_cast<uint32_t*>(blob + d.off_ri) : nullptr;
+        a.shac = shac ? 1u : 0u; a.has_zero = has_zero ? 1u : 0u; a.zcode = zcode; a.zlen = zlen;
+        a.chunk = Cn; a.ent_bits = d.ent_bits; a.row_bits = d.row_bits; a.ri_bits = ri_bits;
+        hipLaunchKernelGGL(enc_emit_kernel, grid, dim3(256), 0, stream, a);
+        if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
+        // the host vectors above feed asynchronous copies: they must outlive them
+        if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
+        return HAC_OK;
+    } catch (const std::bad_alloc&) {
+        return HAC_ENOMEM;
+    }
+}

@@ -43,6 +43,9 @@ void place_sections(hac_desc_t& d);
 int write_tables(uint8_t* base, const hac_desc_t& d, const std::vector<float>& codebook,
                  const std::vector<uint8_t>& len, const CodeTables& t, const std::vector<uint32_t>& lut);
 
+// what hac_last_hip_error() reports (per thread)
+void set_last_hip_error(int e);
+
 } // namespace hac_internal
 
 #endif

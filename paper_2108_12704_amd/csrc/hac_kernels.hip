@@ -23,6 +23,7 @@
 
 #include "../../include/hac.h"
 #include "hac_internal.h"
+#include "hac_hostlib.h"
 
 // Optional phase timing (build with -DHAC_PHASE_TIMING): lane 0 of each wave of the dot
 // kernels stores a 100 MHz clock at phase boundaries; hac_debug_phases() copies them out.
@@ -1309,6 +1310,8 @@ extern "C" int shac_decode_dev(const hac_desc_t* desc, const void* d_blob, float
 }
 
 extern "C" int hac_last_hip_error(void) { return g_last_hip_error; }
+
+void hac_internal::set_last_hip_error(int e) { g_last_hip_error = e; }
 
 #ifdef HAC_PHASE_TIMING
 extern "C" int hac_debug_phases(unsigned long long* out, size_t count)

@@ -1,0 +1,105 @@
+"""GPU-side encoder: the blob built on the device must equal the host encoder's blob byte for
+byte (both are canonical), and therefore decode to the oracle's symbols like it."""
+import numpy as np
+import pytest
+
+import workloads
+from oracle import formats
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hac():
+    import paper_2108_12704_amd as lib
+    lib.load_library()
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    return lib
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def cases():
+    yield "cfg1", workloads.layer(1)
+    yield "cfg2-2500x129", workloads.scaled(2, 2500, 129)       # three row segments, ragged last one
+    yield "cfg3-1100x300", workloads.scaled(3, 1100, 300)
+    yield "cfg4-3000x65", workloads.scaled(4, 3000, 65)
+    yield "cfg5-640x33", workloads.scaled(5, 640, 33)
+    for name, W in workloads.edge_cases().items():
+        yield name, W
+    for name, W in workloads.stress_cases().items():
+        yield name, W
+    for name, W in workloads.random_cases(12, seed=5):
+        yield name, W
+
+
+CASES = list(cases())
+
+
+@pytest.mark.parametrize("name,W", CASES, ids=[c[0] for c in CASES])
+def test_device_blob_equals_host_blob(hac, name, W):
+    Wd = torch.from_numpy(W).to(dev())
+    for fmt, enc in ((hac.HAC_FORMAT_HAC, hac.hac_encode), (hac.HAC_FORMAT_SHAC, hac.shac_encode)):
+        for kw in (dict(), dict(chunk_nnz=3), dict(lut_bits=2, chunk_nnz=100)):
+            print(f"[case] encode_dev {name} {W.shape} fmt={fmt} {kw}", flush=True)
+            host = enc(W, **kw)
+            dblob = hac.hac_encode_dev(Wd, fmt, **kw)
+            torch.cuda.synchronize()
+            got = dblob.tensor.cpu().numpy()
+            assert got.size == host.nbytes
+            if not np.array_equal(got, host.data):
+                diff = np.flatnonzero(got != host.data)
+                raise AssertionError(f"{name} fmt={fmt} {kw}: {diff.size} bytes differ, first at {int(diff[0])}")
+            assert bytes(dblob.desc) == bytes(host.desc)
+    sb = hac.hac_encode_dev(Wd, hac.HAC_FORMAT_SHAC, ri_bits=32)
+    torch.cuda.synchronize()
+    assert np.array_equal(sb.tensor.cpu().numpy(), hac.shac_encode(W, ri_bits=32).data)
+
+
+def test_device_blob_decodes_to_the_oracle_symbols_and_multiplies(hac):
+    W = workloads.scaled(4, 5000, 200)
+    Wd = torch.from_numpy(W).to(dev())
+    hb = hac.hac_encode_dev(Wd, hac.HAC_FORMAT_HAC)
+    sb = hac.hac_encode_dev(Wd, hac.HAC_FORMAT_SHAC)
+    values, sym = formats.hac_symbols(W)
+    Wdec, symd = hac.hac_decode_dev(hb)
+    nz, ssym, srow, scol = hac.shac_decode_dev(sb)
+    torch.cuda.synchronize()
+    assert np.array_equal(Wdec.cpu().numpy().view(np.uint32), W.view(np.uint32))
+    assert np.array_equal(symd.cpu().numpy().astype(np.int64), sym)
+    svalues, s_sym, s_row, s_col = formats.shac_symbols(W)
+    assert np.array_equal(ssym.cpu().numpy().astype(np.int64), s_sym)
+    assert np.array_equal(srow.cpu().numpy().astype(np.int64), s_row)
+    assert int(hb.desc.total_bits) == formats.hac_encode(W).nbits and int(sb.desc.total_bits) == formats.shac_encode(W).nbits
+    X = torch.from_numpy(workloads.make_batch(16, 5000, 3)).to(dev())
+    Yh, Ys = hac.hac_dot(hb, X), hac.shac_dot(sb, X)
+    Yref = hac.hac_dot(hac.hac_encode(W).to_device(dev()), X)
+    torch.cuda.synchronize()
+    assert torch.equal(Yh, Yref) and torch.allclose(Ys, Yref, rtol=1e-4, atol=1e-6)
+
+
+def test_strided_matrix_and_argument_checks(hac):
+    import ctypes as C
+    lib = hac.load_library()
+    Wbig = torch.from_numpy(workloads.scaled(1, 300, 90)).to(dev())
+    Wv = Wbig[:, 10:70]                                       # ldw = 90
+    got = hac.hac_encode_dev(Wv, hac.HAC_FORMAT_HAC)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.tensor.cpu().numpy(), hac.hac_encode(np.ascontiguousarray(Wv.cpu().numpy())).data)
+    bad = Wbig.clone(); bad[5, 5] = float("nan")
+    with pytest.raises(hac.HacError) as e:
+        hac.hac_encode_dev(bad, hac.HAC_FORMAT_HAC)
+    assert e.value.status == -1
+    n, m = 300, 90
+    ws = torch.empty(lib.hac_encode_dev_workspace_bytes(n, m), dtype=torch.uint8, device=dev())
+    desc = hac.Desc()
+    rice = hac.Opts(0, 0, 0, hac.RI_RICE)
+    assert lib.hac_encode_dev(2, Wbig.data_ptr(), n, m, m, C.byref(rice), None, 0, C.byref(desc), ws.data_ptr(), ws.numel(), None) == -1
+    assert lib.hac_encode_dev(7, Wbig.data_ptr(), n, m, m, None, None, 0, C.byref(desc), ws.data_ptr(), ws.numel(), None) == -1
+    assert lib.hac_encode_dev(1, Wbig.data_ptr(), n, m, m, None, None, 0, C.byref(desc), ws.data_ptr(), 1024, None) == -6
+    assert lib.hac_encode_dev(1, Wbig.data_ptr(), n, m, m, None, None, 0, C.byref(desc), ws.data_ptr(), ws.numel(), None) == -6
+    assert int(desc.blob_bytes) == hac.hac_encode(Wbig.cpu().numpy()).nbytes      # the size to allocate
+    torch.cuda.synchronize()
