@@ -252,6 +252,15 @@ int hac_decode_host(const void *blob, size_t bytes, float *W_out, int32_t *sym_o
 
 /* ---- device side (asynchronous on `stream`) -------------------------------- */
 
+/* Which of the two compressed formats the paper's size bounds favour for an
+ * n x m matrix with nnz non-zeros and k distinct values: sHAC when the non-zero
+ * ratio s = nnz / (n m) is below (a - (m+1)/(n m)) / (1 + a), a = (1 + log2 k) / 32
+ * (the inequality psi_sHAC < psi_HAC at the end of Sect. IV-C, from Eqs. (2) and
+ * (3)), else HAC.  Returns HAC_FORMAT_HAC or HAC_FORMAT_SHAC, or HAC_EINVAL.  The
+ * bounds are loose for HAC (real streams are 2-6 times smaller, Sect. V), so this
+ * is the paper's rule of thumb, not a size guarantee. */
+int hac_choose_format(int64_t n, int64_t m, uint64_t nnz, uint32_t k);
+
 /* Encode on the device: W (n x m, row-major, leading dimension ldw >= m) is in
  * device memory and so is the blob that comes out, byte for byte the blob
  * hac_encode / shac_encode (format = HAC_FORMAT_HAC / HAC_FORMAT_SHAC) build on

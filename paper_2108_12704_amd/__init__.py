@@ -24,7 +24,7 @@ EXPORTS = (
     "hac_encode", "shac_encode", "hac_free", "hac_validate", "hac_describe", "hac_stats",
     "hac_decode_host", "hac_workspace_bytes", "hac_workspace_bytes_for", "hac_dot_route", "hac_dot", "shac_dot", "hac_decode_dev",
     "shac_decode_dev", "hac_strerror", "hac_last_hip_error", "im_encode", "im_dot",
-    "hac_encode_dev", "hac_encode_dev_workspace_bytes",
+    "hac_encode_dev", "hac_encode_dev_workspace_bytes", "hac_choose_format",
 )
 
 
@@ -96,6 +96,7 @@ def load_library() -> C.CDLL:
     lib.hac_encode_dev_workspace_bytes.restype = C.c_size_t
     lib.hac_encode_dev.argtypes = [C.c_uint32, vp, C.c_int64, C.c_int64, C.c_int64, C.POINTER(Opts), vp, C.c_size_t,
                                    C.POINTER(Desc), vp, C.c_size_t, vp]
+    lib.hac_choose_format.argtypes = [C.c_int64, C.c_int64, C.c_uint64, C.c_uint32]
     lib.hac_free.argtypes = [vp]
     lib.hac_free.restype = None
     lib.hac_validate.argtypes = [vp, C.c_size_t, C.c_int]
@@ -326,6 +327,14 @@ def hac_encode_dev(W, fmt: int = HAC_FORMAT_HAC, chunk_nnz: int = 0, ri_bits: in
     _check(lib.hac_encode_dev(fmt, W.data_ptr(), n, m, ldw, C.byref(opts), blob.data_ptr(), blob.numel(), C.byref(desc),
                               ws.data_ptr(), ws.numel(), sh), "hac_encode_dev")
     return DeviceBlob(desc, blob)
+
+
+def hac_choose_format(n: int, m: int, nnz: int, k: int) -> int:
+    """HAC_FORMAT_HAC or HAC_FORMAT_SHAC by the paper's bound-based rule (end of Sect. IV-C)."""
+    rc = load_library().hac_choose_format(n, m, nnz, k)
+    if rc < 0:
+        _check(rc, "hac_choose_format")
+    return rc
 
 
 def hac_dot_route(desc: Desc, B: int, launch: Optional["Launch"] = None) -> int:

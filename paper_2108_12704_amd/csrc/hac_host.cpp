@@ -1171,6 +1171,15 @@ extern "C" int hac_decode_host(const void* blob, size_t bytes, float* W_out, int
     return HAC_OK;
 }
 
+extern "C" int hac_choose_format(int64_t n, int64_t m, uint64_t nnz, uint32_t k)
+{
+    if (n < 1 || m < 1 || k < 1 || (double)nnz > (double)n * (double)m) return HAC_EINVAL;
+    const double nm = (double)n * (double)m;
+    const double a = (1.0 + std::log2((double)k)) / 32.0;
+    const double s_star = (a - ((double)m + 1.0) / nm) / (1.0 + a);
+    return (double)nnz / nm < s_star ? HAC_FORMAT_SHAC : HAC_FORMAT_HAC;
+}
+
 extern "C" const char* hac_strerror(int status)
 {
     switch (status) {

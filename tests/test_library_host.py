@@ -382,6 +382,21 @@ def test_randomized_blobs_against_oracle():
         assert np.array_equal(symd.reshape(m, n).T, indexmap.im_encode(W).pi.astype(np.int32)), name
 
 
+def test_choose_format_follows_the_bound_crossover():
+    """The library's rule against the oracle's closed form and against the two bounds themselves."""
+    for n, m, k in ((500, 300, 16), (4096, 1000, 32), (4096, 4096, 256), (25088, 4096, 32), (64, 64, 2)):
+        s_star = bounds.crossover_sparsity(n, m, k)
+        for s in (0.0, 0.5 * s_star, 0.99 * s_star, 1.01 * s_star, min(1.0, 3 * s_star), 1.0):
+            nnz = int(s * n * m)
+            got = hac.hac_choose_format(n, m, nnz, k)
+            smaller = bounds.psi_shac_bound(n, m, nnz / (n * m), k) < bounds.psi_hac_bound(n, m, k)
+            assert got == (hac.HAC_FORMAT_SHAC if smaller else hac.HAC_FORMAT_HAC), (n, m, k, s)
+    with pytest.raises(hac.HacError):
+        hac.hac_choose_format(0, 5, 0, 2)
+    with pytest.raises(hac.HacError):
+        hac.hac_choose_format(5, 5, 26, 2)
+
+
 def test_ri_bits_32_and_small_tables_still_round_trip():
     W = workloads.scaled(3, 260, 33)
     for kw in (dict(ri_bits=32), dict(lut_bits=2), dict(chunk_nnz=1), dict(chunk_nnz=65536)):
