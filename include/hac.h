@@ -179,18 +179,18 @@ typedef struct {
 typedef struct {
     uint32_t cols_per_wave;   /* columns of W one wavefront handles, 1..32                 */
     uint32_t waves_per_block; /* 1..16                                                     */
-    uint32_t variant;         /* 0, or HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_LIST_KERNEL         */
-    uint32_t reserved[5];     /* [0]: entries of the per-wavefront non-zero list, 64..4096;
-                                 [1]: words of the per-wavefront staging buffer for stream
-                                 (and ri) words, 16..16384, multiple of 4;
-                                 0 = sized from the blob header;
-                                 [2]: batch columns one pass over the non-zero list
-                                 covers, 32 / 64 / 128 / 256 [32];
-                                 [3]: 1 = do not hold a block's wavefronts on the same pass
-                                 (measurement aid);
-                                 [4]: batch columns one block covers, 32 / 64 / 128 / 256,
-                                 not below [2]; every column of W is decoded once per
-                                 such tile of the batch                                    */
+    uint32_t variant;         /* 0, or an OR of the HAC_LAUNCH_* flags below                */
+    uint32_t list_entries;    /* entries of the per-wavefront list of decoded non-zeros,
+                                 64..4096 [sized from the blob header]                     */
+    uint32_t staging_words;   /* words of the per-wavefront LDS buffer for stream (and ri)
+                                 words, 16..16384, a multiple of 4 [from the header]       */
+    uint32_t pass_width;      /* batch columns one pass over the list covers:
+                                 32 / 64 / 128 / 256 [32]                                  */
+    uint32_t free_running;    /* 1 = do not hold a block's wavefronts on the same pass
+                                 (measurement aid) [0]                                     */
+    uint32_t tile_width;      /* batch columns one block covers: 32 / 64 / 128 / 256, not
+                                 below pass_width; every column of W is decoded once per
+                                 such tile of the batch [256]                              */
 } hac_launch_t;
 
 /* The workspace already holds the feature-major copy of this very X (same B,

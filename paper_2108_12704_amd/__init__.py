@@ -72,7 +72,8 @@ class Stats(C.Structure):
 
 class Launch(C.Structure):
     _fields_ = [("cols_per_wave", C.c_uint32), ("waves_per_block", C.c_uint32),
-                ("variant", C.c_uint32), ("reserved", C.c_uint32 * 5)]
+                ("variant", C.c_uint32), ("list_entries", C.c_uint32), ("staging_words", C.c_uint32),
+                ("pass_width", C.c_uint32), ("free_running", C.c_uint32), ("tile_width", C.c_uint32)]
 
 
 assert C.sizeof(Desc) == 256

@@ -1060,14 +1060,14 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         const uint32_t routes = HAC_LAUNCH_SPARSE_ROUTE | HAC_LAUNCH_DENSE_ROUTE;
         if (launch->variant & ~(HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_LIST_KERNEL | routes)) return HAC_EINVAL;
         if ((launch->variant & routes) == routes) return HAC_EINVAL;
-        list_cap = launch->reserved[0];
-        sbuf_words = launch->reserved[1];
+        list_cap = launch->list_entries;
+        sbuf_words = launch->staging_words;
         if (list_cap && (list_cap < 64 || list_cap > 4096)) return HAC_EINVAL;
         if (sbuf_words && (sbuf_words < 16 || sbuf_words > 16384 || sbuf_words % 4)) return HAC_EINVAL;
-        if (launch->reserved[2]) pass_w = launch->reserved[2];
+        if (launch->pass_width) pass_w = launch->pass_width;
         if (pass_w != 32 && pass_w != 64 && pass_w != 128 && pass_w != 256) return HAC_EINVAL;
-        if (launch->reserved[3] > 1) return HAC_EINVAL;
-        if (launch->reserved[4]) tile_b = launch->reserved[4];
+        if (launch->free_running > 1) return HAC_EINVAL;
+        if (launch->tile_width) tile_b = launch->tile_width;
         if (tile_b != 32 && tile_b != 64 && tile_b != 128 && tile_b != 256) return HAC_EINVAL;
         if (tile_b < pass_w) return HAC_EINVAL;
     }
@@ -1190,7 +1190,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     const size_t lds = 4ull * table_words(d) + (size_t)wpb * per_wave;
     if (lds > kLdsLimit) return HAC_EINVAL;
     uint32_t sync_passes = (bs.npass > 1 && cpw == 1 && !may_split) ? 1u : 0u;
-    if (launch && launch->reserved[3] == 1) sync_passes = 0;           // measurement aid: free-running passes
+    if (launch && launch->free_running == 1) sync_passes = 0;           // measurement aid: free-running passes
     const uint32_t nblocks = (nwaves + wpb - 1) / wpb;
     const uint64_t items = (uint64_t)nblocks * bs.tiles;
     if (items > 0x7ffffff0ull) return HAC_EINVAL;

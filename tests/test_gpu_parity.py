@@ -194,9 +194,9 @@ def test_launch_overrides_do_not_change_the_result(hac):
                                     (2, 3, 1024, 0)):
             print(f"[case] launch {f.__name__} cpw={cpw} wpb={wpb} cap={cap} sbuf={sbuf}", flush=True)
             launch = hac.Launch(cols_per_wave=cpw, waves_per_block=wpb)
-            launch.reserved[0] = cap          # list capacity: small values force several windows per column
-            launch.reserved[1] = sbuf         # staging buffer: small values force the unstaged reader
-            launch.reserved[2] = 64 if cpw == 7 else 0     # batch columns per pass
+            launch.list_entries = cap          # list capacity: small values force several windows per column
+            launch.staging_words = sbuf         # staging buffer: small values force the unstaged reader
+            launch.pass_width = 64 if cpw == 7 else 0     # batch columns per pass
             Y = f(db, Xd, launch=launch)
             Y1 = f(db, Xd[:1], launch=launch)
             torch.cuda.synchronize()

@@ -31,13 +31,19 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, name) is not None
 
 
-def test_header_struct_matches_binding():
+def header_fields(struct_name):
     text = open(os.path.join(ROOT, "include", "hac.h")).read()
-    body = text[:text.index("} hac_desc_t;")]
+    body = text[:text.index("} " + struct_name + ";")]
     body = body[body.rindex("typedef struct {") + len("typedef struct {"):]
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
-    fields = re.findall(r"\b([a-z_][a-z_0-9]*)(?:\[\d+\])?\s*[;,]", body)
-    assert fields == [f[0] for f in hac.Desc._fields_]
+    return re.findall(r"\b([a-z_][a-z_0-9]*)(?:\[\d+\])?\s*[;,]", body)
+
+
+def test_header_struct_matches_binding():
+    assert header_fields("hac_desc_t") == [f[0] for f in hac.Desc._fields_]
+    assert header_fields("hac_opts_t") == [f[0] for f in hac.Opts._fields_]
+    assert header_fields("hac_launch_t") == [f[0] for f in hac.Launch._fields_]
+    assert header_fields("hac_stats_t") == [f[0] for f in hac.Stats._fields_]
 
 
 def codes_from_blob(blob):
