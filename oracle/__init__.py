@@ -40,6 +40,10 @@ the entropy sandwich H <= avg <= H+1, equiprobable 2^j alphabets, bit-exact
 round trips, scipy's CSC arrays and product, numpy's dense fp64 product,
 identity batches, linearity, and the space bounds listed above.
 
+unified.py writes out the single dictionary shared by all layers of a network
+(Sect. V-H) on top of `formats`, and a chain of layers X -> act(X.W + b) in fp64
+with a forward error bound; its readings and pins are in that module's header.
+
 gapcode.py holds an extension that is not in the paper (sHAC whose row indices
 are replaced by Golomb-Rice coded gaps); its definition and its own pins are in
 that module's header.
