@@ -283,11 +283,6 @@ uint32_t rice_length(uint32_t d, uint32_t k)
 
 namespace {
 
-struct Layout {
-    hac_desc_t d;
-    Layout() { std::memset(&d, 0, sizeof d); }
-};
-
 int check_args(const float* W, int64_t n, int64_t m, int64_t ldw, void** blob, size_t* bytes)
 {
     if (!W || !blob || !bytes) return HAC_EINVAL;
@@ -329,6 +324,290 @@ uint64_t max_nnz_per_column(const Scan& s)
     return mx;
 }
 
+// ---- one Huffman dictionary: a layer's own, or the one all layers of a network share ----
+struct Dict {
+    std::vector<float> codebook;       // 0.0 first when has_zero, then ascending
+    std::vector<uint64_t> freq;
+    std::vector<uint8_t> len;
+    uint32_t lmax = 0, lut_bits = 0;
+    CodeTables t;
+    std::vector<uint32_t> lut;
+    bool has_zero = false;
+};
+
+int finish_dict(Dict& D, const hac_opts_t* opts)
+{
+    if (!huffman_lengths(D.freq, D.len, D.lmax)) return HAC_ERANGE;
+    canonical_codes(D.len, D.t);
+    D.lut_bits = pick_lut_bits(opts, D.lmax);
+    if (D.lut_bits < 1 || D.lut_bits > 12) return HAC_EINVAL;
+    build_lut(D.len, D.t, D.lut_bits, D.lut);
+    return HAC_OK;
+}
+
+// What one layer needs besides the dictionary: the header with every count filled in (offsets
+// are placed by the caller), the per-column arrays, and the dictionary symbol of each of the
+// layer's own non-zero values.
+struct LayerPlan {
+    hac_desc_t d;
+    ColumnIndex ci;
+    std::vector<uint32_t> map;         // index into Scan::values -> dictionary symbol
+    LayerPlan() { std::memset(&d, 0, sizeof d); }
+};
+
+void plan_common(const Scan& s, const Dict& D, uint32_t format, LayerPlan& P)
+{
+    hac_desc_t& d = P.d;
+    d.magic = kMagic; d.version = kVersion; d.format = format; d.header_bytes = 256;
+    d.n = (uint64_t)s.n; d.m = (uint64_t)s.m; d.nnz = s.ri.size();
+    d.k_sym = (uint32_t)D.codebook.size(); d.lmax = D.lmax; d.lut_bits = D.lut_bits;
+}
+
+// HAC (Sect. IV-B): every entry of W, zeros included, gets a codeword.
+int plan_hac(const Scan& s, const Dict& D, const hac_opts_t* opts, LayerPlan& P)
+{
+    const int64_t n = s.n, m = s.m;
+    if (s.zeros && !D.has_zero) return HAC_EINVAL;
+    const uint32_t zlen = D.has_zero ? D.len[0] : 0, zcode = D.has_zero ? D.t.code[0] : 0;
+    uint64_t total_bits = s.zeros * zlen;
+    for (size_t i = 0; i < s.freq.size(); ++i) total_bits += s.freq[i] * D.len[P.map[i]];
+    if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
+    const uint64_t max_col_nnz = max_nnz_per_column(s);
+    const uint32_t Cn = pick_chunk(opts, max_col_nnz);
+    P.ci.build(s, Cn);
+    if (P.ci.n_chunks > 0xfffffff0ull) return HAC_ERANGE;
+    uint64_t max_col_bits = 0;
+    for (int64_t j = 0; j < m; ++j) {
+        uint64_t bits = ((uint64_t)n - (s.cb[(size_t)j + 1] - s.cb[(size_t)j])) * zlen;
+        for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) bits += D.len[P.map[s.sym[(size_t)p]]];
+        max_col_bits = std::max(max_col_bits, bits);
+    }
+    const uint32_t row_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
+    const uint32_t brel_bits = std::max<uint32_t>(ceil_log2(max_col_bits + 1), 1);
+    const uint32_t ent_bits = row_bits + brel_bits <= 32 ? 32 : 64;
+    plan_common(s, D, HAC_FORMAT_HAC, P);
+    hac_desc_t& d = P.d;
+    d.total_bits = total_bits; d.n_words = (total_bits + 31) / 32;
+    d.has_zero = D.has_zero;
+    d.zero_len = (D.has_zero && zcode == 0) ? zlen : 0;      // canonical: all-zero word <=> a shortest one
+    d.chunk = Cn; d.ri_bits = 0;
+    d.ent_bits = ent_bits; d.row_bits = ent_bits == 32 ? row_bits : 0; d.n_chunks = P.ci.n_chunks;
+    d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
+    return HAC_OK;
+}
+
+void write_column_arrays(uint8_t* base, const hac_desc_t& d, const ColumnIndex& ci)
+{
+    const size_t bytes = 4 * ((size_t)d.m + 1);
+    std::memcpy(base + d.off_col_chunk, ci.col_chunk.data(), bytes);
+    std::memcpy(base + d.off_col_pos, ci.col_pos.data(), bytes);
+    std::memcpy(base + d.off_col_bit, ci.col_bit.data(), bytes);
+}
+
+int write_hac(uint8_t* base, const Scan& s, const Dict& D, LayerPlan& P)
+{
+    const hac_desc_t& d = P.d;
+    const int64_t n = s.n, m = s.m;
+    const uint32_t Cn = d.chunk, ent_bits = d.ent_bits, row_bits = d.row_bits;
+    const uint32_t zlen = D.has_zero ? D.len[0] : 0, zcode = D.has_zero ? D.t.code[0] : 0;
+    BitWriter bw = { reinterpret_cast<uint32_t*>(base + d.off_stream), 0 };
+    uint32_t* ent = reinterpret_cast<uint32_t*>(base + d.off_chunk_ent);
+    auto put_zeros = [&](uint64_t count) {
+        if (!count) return;
+        if (zcode == 0) bw.skip(count * zlen);              // zero bits are already there
+        else for (uint64_t r = 0; r < count; ++r) bw.put(zcode, zlen);
+    };
+    uint64_t chunk = 0;
+    for (int64_t j = 0; j < m; ++j) {
+        uint64_t row = 0;                                    // next row to be written
+        const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
+        P.ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
+        const uint64_t col_bit0 = bw.bitpos;
+        for (uint64_t p = p0; p < pend; ++p) {
+            if ((p - p0) % Cn == 0) {                        // a chunk starts before this non-zero's zero run
+                const uint64_t rel = bw.bitpos - col_bit0;
+                if (ent_bits == 32) ent[chunk] = (uint32_t)((rel << row_bits) | row);
+                else { ent[2 * chunk] = (uint32_t)row; ent[2 * chunk + 1] = (uint32_t)rel; }
+                ++chunk;
+            }
+            put_zeros(s.ri[(size_t)p] - row);
+            const uint32_t sy = P.map[s.sym[(size_t)p]];
+            bw.put(D.t.code[sy], D.len[sy]);
+            row = (uint64_t)s.ri[(size_t)p] + 1;
+        }
+        put_zeros((uint64_t)n - row);
+    }
+    P.ci.col_bit[(size_t)m] = (uint32_t)bw.bitpos;
+    write_column_arrays(base, d, P.ci);
+    return (chunk != P.ci.n_chunks || bw.bitpos != d.total_bits) ? HAC_EFORMAT : HAC_OK;
+}
+
+// sHAC (Sect. IV-C): the non-zeros get codewords; ri is stored as fields, or (the extension)
+// as Rice-coded gaps in front of each codeword.
+int check_shac_opts(const hac_opts_t* opts, int64_t n, bool& rice, uint32_t& ri_bits)
+{
+    const uint32_t need_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
+    rice = opts && opts->ri_coding == HAC_RI_RICE;
+    if (rice && opts->ri_bits) return HAC_EINVAL;
+    ri_bits = opts && opts->ri_bits ? opts->ri_bits : need_bits;
+    if (ri_bits < need_bits || ri_bits > 32) return HAC_EINVAL;
+    return HAC_OK;
+}
+
+int plan_shac(const Scan& s, const Dict& D, const hac_opts_t* opts, LayerPlan& P)
+{
+    const int64_t n = s.n, m = s.m;
+    bool rice; uint32_t ri_bits;
+    int rc = check_shac_opts(opts, n, rice, ri_bits);
+    if (rc) return rc;
+    const uint64_t nnz = s.ri.size();
+    uint64_t total_bits = 0;
+    for (size_t i = 0; i < s.freq.size(); ++i) total_bits += s.freq[i] * D.len[P.map[i]];
+    if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
+    const uint64_t max_col_nnz = max_nnz_per_column(s);
+    const uint32_t Cn = pick_chunk(opts, max_col_nnz);
+    P.ci.build(s, Cn);
+    plan_common(s, D, HAC_FORMAT_SHAC, P);
+    hac_desc_t& d = P.d;
+    d.chunk = Cn; d.n_chunks = P.ci.n_chunks; d.max_col_nnz = max_col_nnz;
+    if (rice) {
+        uint32_t k = 0; uint64_t gap_bits = ~0ull;
+        for (uint32_t kk = 0; kk <= kRiceKMax; ++kk) {
+            uint64_t tot = 0;
+            for (int64_t j = 0; j < m; ++j)
+                for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p)
+                    tot += rice_length(gap_at(s, p, s.cb[(size_t)j]), kk);
+            if (tot < gap_bits) { gap_bits = tot; k = kk; }
+        }
+        if (nnz == 0) gap_bits = 0;
+        total_bits += gap_bits;
+        if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
+        uint64_t max_col_bits = 0;
+        for (int64_t j = 0; j < m; ++j) {
+            uint64_t bits = 0;
+            for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p)
+                bits += D.len[P.map[s.sym[(size_t)p]]] + rice_length(gap_at(s, p, s.cb[(size_t)j]), k);
+            max_col_bits = std::max(max_col_bits, bits);
+        }
+        const uint32_t row_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
+        const uint32_t brel_bits = std::max<uint32_t>(ceil_log2(max_col_bits + 1), 1);
+        const uint32_t ent_bits = row_bits + brel_bits <= 32 ? 32 : 64;
+        d.ri_bits = 0; d.ent_bits = ent_bits; d.row_bits = ent_bits == 32 ? row_bits : 0;
+        d.max_col_bits = max_col_bits;
+        d.ri_coding = HAC_RI_RICE; d.rice_k = k; d.gap_bits = gap_bits;
+    } else {
+        uint64_t max_col_bits = 0;
+        for (int64_t j = 0; j < m; ++j) {
+            uint64_t bits = 0;
+            for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) bits += D.len[P.map[s.sym[(size_t)p]]];
+            max_col_bits = std::max(max_col_bits, bits);
+        }
+        if (nnz * (uint64_t)ri_bits > 0xfffffff0ull * 32ull) return HAC_ERANGE;
+        d.ri_bits = ri_bits; d.ent_bits = max_col_bits < 65536 ? 16 : 32; d.row_bits = 0;
+        d.max_col_bits = max_col_bits;
+    }
+    d.total_bits = total_bits; d.n_words = (total_bits + 31) / 32;
+    return HAC_OK;
+}
+
+int write_shac(uint8_t* base, const Scan& s, const Dict& D, LayerPlan& P)
+{
+    const hac_desc_t& d = P.d;
+    const int64_t m = s.m;
+    const uint32_t Cn = d.chunk, ent_bits = d.ent_bits;
+    BitWriter bw = { reinterpret_cast<uint32_t*>(base + d.off_stream), 0 };
+    uint64_t chunk = 0;
+    if (d.ri_coding == HAC_RI_RICE) {
+        // ---- gaps in the stream, in front of each value's codeword ----
+        const uint32_t k = d.rice_k, row_bits = d.row_bits;
+        uint32_t* ent = reinterpret_cast<uint32_t*>(base + d.off_chunk_ent);
+        for (int64_t j = 0; j < m; ++j) {
+            const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
+            P.ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
+            const uint64_t col_bit0 = bw.bitpos;
+            for (uint64_t p = p0; p < pend; ++p) {
+                const uint32_t g = gap_at(s, p, p0);
+                if ((p - p0) % Cn == 0) {
+                    const uint64_t rel = bw.bitpos - col_bit0;
+                    const uint64_t row = (uint64_t)s.ri[(size_t)p] - g;      // the row the gap counts from
+                    if (ent_bits == 32) ent[chunk] = (uint32_t)((rel << row_bits) | row);
+                    else { ent[2 * chunk] = (uint32_t)row; ent[2 * chunk + 1] = (uint32_t)rel; }
+                    ++chunk;
+                }
+                const uint32_t q = g >> k;
+                if (q < kRiceEscape) {
+                    bw.skip(q);
+                    bw.put((1u << k) | (g & ((1u << k) - 1u)), k + 1);
+                } else {
+                    bw.skip(kRiceEscape);
+                    bw.put(1u, 1);
+                    bw.put(g, 32);
+                }
+                const uint32_t sy = P.map[s.sym[(size_t)p]];
+                bw.put(D.t.code[sy], D.len[sy]);
+            }
+        }
+    } else {
+        BitWriter rw = { reinterpret_cast<uint32_t*>(base + d.off_ri), 0 };
+        uint16_t* ent16 = reinterpret_cast<uint16_t*>(base + d.off_chunk_ent);
+        uint32_t* ent32 = reinterpret_cast<uint32_t*>(base + d.off_chunk_ent);
+        for (int64_t j = 0; j < m; ++j) {
+            const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
+            P.ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
+            const uint64_t col_bit0 = bw.bitpos;
+            for (uint64_t p = p0; p < pend; ++p) {
+                if ((p - p0) % Cn == 0) {
+                    const uint64_t rel = bw.bitpos - col_bit0;
+                    if (ent_bits == 16) ent16[chunk] = (uint16_t)rel; else ent32[chunk] = (uint32_t)rel;
+                    ++chunk;
+                }
+                const uint32_t sy = P.map[s.sym[(size_t)p]];
+                bw.put(D.t.code[sy], D.len[sy]);
+                rw.put(s.ri[(size_t)p], d.ri_bits);
+            }
+        }
+    }
+    P.ci.col_bit[(size_t)m] = (uint32_t)bw.bitpos;
+    write_column_arrays(base, d, P.ci);
+    return (chunk != P.ci.n_chunks || bw.bitpos != d.total_bits) ? HAC_EFORMAT : HAC_OK;
+}
+
+// A layer's own dictionary: HAC numbers 0.0 as symbol 0 when it occurs; sHAC has no symbol for it.
+void own_dict(const Scan& s, bool with_zero, Dict& D, std::vector<uint32_t>& map)
+{
+    D.has_zero = with_zero && s.zeros > 0;
+    if (D.has_zero) { D.codebook.push_back(0.0f); D.freq.push_back(s.zeros); }
+    D.codebook.insert(D.codebook.end(), s.values.begin(), s.values.end());
+    D.freq.insert(D.freq.end(), s.freq.begin(), s.freq.end());
+    const uint32_t shift = D.has_zero ? 1u : 0u;
+    map.resize(s.values.size());
+    for (size_t i = 0; i < map.size(); ++i) map[i] = (uint32_t)i + shift;
+}
+
+// One self-contained blob: header, the layer's own tables, its sections.
+int encode_single(uint32_t format, const float* W, int64_t n, int64_t m, int64_t ldw,
+                  const hac_opts_t* opts, void** blob, size_t* blob_bytes)
+{
+    Scan s;
+    int rc = scan_matrix(W, n, m, ldw, s);
+    if (rc) return rc;
+    Dict D; LayerPlan P;
+    own_dict(s, format == HAC_FORMAT_HAC, D, P.map);
+    if ((rc = finish_dict(D, opts))) return rc;
+    rc = format == HAC_FORMAT_HAC ? plan_hac(s, D, opts, P) : plan_shac(s, D, opts, P);
+    if (rc) return rc;
+    hac_desc_t& d = P.d;
+    place_sections(d);
+    uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
+    if (!base) return HAC_ENOMEM;
+    std::memcpy(base, &d, sizeof d);
+    write_tables(base, d, D.codebook, D.len, D.t, D.lut);
+    rc = format == HAC_FORMAT_HAC ? write_hac(base, s, D, P) : write_shac(base, s, D, P);
+    if (rc) { std::free(base); return rc; }
+    *blob = base; *blob_bytes = (size_t)d.blob_bytes;
+    return HAC_OK;
+}
+
 } // namespace
 
 // =================================================================================
@@ -343,94 +622,7 @@ extern "C" int hac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
     if ((rc = check_opts(opts))) return rc;
     if (opts && opts->ri_coding) return HAC_EINVAL;          // the address map of HAC is the stream itself
     try {
-        Scan s;
-        rc = scan_matrix(W, n, m, ldw, s);
-        if (rc) return rc;
-        const uint64_t nnz = s.ri.size();
-        const bool has_zero = s.zeros > 0;
-        // alphabet: 0.0 first when it occurs, then the non-zero values ascending
-        std::vector<float> codebook;
-        std::vector<uint64_t> freq;
-        if (has_zero) { codebook.push_back(0.0f); freq.push_back(s.zeros); }
-        codebook.insert(codebook.end(), s.values.begin(), s.values.end());
-        freq.insert(freq.end(), s.freq.begin(), s.freq.end());
-        const uint32_t shift = has_zero ? 1u : 0u;           // symbol of non-zero value v = shift + index
-        std::vector<uint8_t> len; uint32_t lmax = 0;
-        if (!huffman_lengths(freq, len, lmax)) return HAC_ERANGE;
-        CodeTables t; canonical_codes(len, t);
-        uint64_t total_bits = 0;
-        for (size_t i = 0; i < freq.size(); ++i) total_bits += freq[i] * len[i];
-        if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
-        const uint32_t lut_bits = pick_lut_bits(opts, lmax);
-        if (lut_bits < 1 || lut_bits > 12) return HAC_EINVAL;
-        std::vector<uint32_t> lut; build_lut(len, t, lut_bits, lut);
-
-        const uint64_t max_col_nnz = max_nnz_per_column(s);
-        const uint32_t Cn = pick_chunk(opts, max_col_nnz);
-        ColumnIndex ci; ci.build(s, Cn);
-        if (ci.n_chunks > 0xfffffff0ull) return HAC_ERANGE;
-        const uint32_t zlen = has_zero ? len[0] : 0, zcode = has_zero ? t.code[0] : 0;
-        uint64_t max_col_bits = 0;
-        for (int64_t j = 0; j < m; ++j) {
-            uint64_t bits = ((uint64_t)n - (s.cb[(size_t)j + 1] - s.cb[(size_t)j])) * zlen;
-            for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) bits += len[s.sym[(size_t)p] + shift];
-            max_col_bits = std::max(max_col_bits, bits);
-        }
-        const uint32_t row_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
-        const uint32_t brel_bits = std::max<uint32_t>(ceil_log2(max_col_bits + 1), 1);
-        const uint32_t ent_bits = row_bits + brel_bits <= 32 ? 32 : 64;
-        const uint64_t n_words = (total_bits + 31) / 32;
-        const uint32_t zero_len = (has_zero && zcode == 0) ? zlen : 0;   // canonical: all-zero word <=> a shortest one
-
-        Layout L;
-        hac_desc_t& d = L.d;
-        d.magic = kMagic; d.version = kVersion; d.format = HAC_FORMAT_HAC; d.header_bytes = 256;
-        d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = nnz; d.total_bits = total_bits; d.n_words = n_words;
-        d.k_sym = (uint32_t)codebook.size(); d.lmax = lmax; d.lut_bits = lut_bits;
-        d.has_zero = has_zero; d.zero_len = zero_len; d.chunk = Cn; d.ri_bits = 0;
-        d.ent_bits = ent_bits; d.row_bits = ent_bits == 32 ? row_bits : 0; d.n_chunks = ci.n_chunks;
-        d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
-        place_sections(d);
-
-        uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
-        if (!base) return HAC_ENOMEM;
-        std::memcpy(base, &d, sizeof d);
-        write_tables(base, d, codebook, len, t, lut);
-
-        BitWriter bw = { reinterpret_cast<uint32_t*>(base + d.off_stream), 0 };
-        uint32_t* ent = reinterpret_cast<uint32_t*>(base + d.off_chunk_ent);
-        auto put_zeros = [&](uint64_t count) {
-            if (!count) return;
-            if (zcode == 0) bw.skip(count * zlen);              // zero bits are already there
-            else for (uint64_t r = 0; r < count; ++r) bw.put(zcode, zlen);
-        };
-        uint64_t chunk = 0;
-        for (int64_t j = 0; j < m; ++j) {
-            uint64_t row = 0;                                    // next row to be written
-            const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
-            ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
-            const uint64_t col_bit0 = bw.bitpos;
-            for (uint64_t p = p0; p < pend; ++p) {
-                if ((p - p0) % Cn == 0) {                        // a chunk starts before this non-zero's zero run
-                    const uint64_t rel = bw.bitpos - col_bit0;
-                    if (ent_bits == 32) ent[chunk] = (uint32_t)((rel << row_bits) | row);
-                    else { ent[2 * chunk] = (uint32_t)row; ent[2 * chunk + 1] = (uint32_t)rel; }
-                    ++chunk;
-                }
-                put_zeros(s.ri[(size_t)p] - row);
-                const uint32_t sy = s.sym[(size_t)p] + shift;
-                bw.put(t.code[sy], len[sy]);
-                row = (uint64_t)s.ri[(size_t)p] + 1;
-            }
-            put_zeros((uint64_t)n - row);
-        }
-        ci.col_bit[(size_t)m] = (uint32_t)bw.bitpos;
-        std::memcpy(base + d.off_col_chunk, ci.col_chunk.data(), 4 * ((size_t)m + 1));
-        std::memcpy(base + d.off_col_pos, ci.col_pos.data(), 4 * ((size_t)m + 1));
-        std::memcpy(base + d.off_col_bit, ci.col_bit.data(), 4 * ((size_t)m + 1));
-        if (chunk != ci.n_chunks || bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
-        *blob = base; *blob_bytes = (size_t)d.blob_bytes;
-        return HAC_OK;
+        return encode_single(HAC_FORMAT_HAC, W, n, m, ldw, opts, blob, blob_bytes);
     } catch (const std::bad_alloc&) {
         return HAC_ENOMEM;
     }
@@ -446,158 +638,10 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
     if (rc) return rc;
     *blob = nullptr; *blob_bytes = 0;
     if ((rc = check_opts(opts))) return rc;
-    const uint32_t need_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
-    const bool rice = opts && opts->ri_coding == HAC_RI_RICE;
-    if (rice && opts->ri_bits) return HAC_EINVAL;
-    uint32_t ri_bits = opts && opts->ri_bits ? opts->ri_bits : need_bits;
-    if (ri_bits < need_bits || ri_bits > 32) return HAC_EINVAL;
+    bool rice; uint32_t ri_bits;
+    if ((rc = check_shac_opts(opts, n, rice, ri_bits))) return rc;
     try {
-        Scan s;
-        rc = scan_matrix(W, n, m, ldw, s);
-        if (rc) return rc;
-        const uint64_t nnz = s.ri.size();
-        std::vector<uint8_t> len; uint32_t lmax = 0;
-        if (!huffman_lengths(s.freq, len, lmax)) return HAC_ERANGE;
-        CodeTables t; canonical_codes(len, t);
-        uint64_t total_bits = 0;
-        for (size_t i = 0; i < s.freq.size(); ++i) total_bits += s.freq[i] * len[i];
-        if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
-        const uint32_t lut_bits = pick_lut_bits(opts, lmax);
-        if (lut_bits < 1 || lut_bits > 12) return HAC_EINVAL;
-        std::vector<uint32_t> lut; build_lut(len, t, lut_bits, lut);
-
-        const uint64_t max_col_nnz = max_nnz_per_column(s);
-        const uint32_t Cn = pick_chunk(opts, max_col_nnz);
-        ColumnIndex ci; ci.build(s, Cn);
-        if (rice) {
-            // ---- gaps in the stream, in front of each value's codeword ----
-            uint32_t k = 0; uint64_t gap_bits = ~0ull;
-            for (uint32_t kk = 0; kk <= kRiceKMax; ++kk) {
-                uint64_t tot = 0;
-                for (int64_t j = 0; j < m; ++j)
-                    for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p)
-                        tot += rice_length(gap_at(s, p, s.cb[(size_t)j]), kk);
-                if (tot < gap_bits) { gap_bits = tot; k = kk; }
-            }
-            if (nnz == 0) gap_bits = 0;
-            total_bits += gap_bits;
-            if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
-            uint64_t max_col_bits = 0;
-            for (int64_t j = 0; j < m; ++j) {
-                uint64_t bits = 0;
-                for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p)
-                    bits += len[s.sym[(size_t)p]] + rice_length(gap_at(s, p, s.cb[(size_t)j]), k);
-                max_col_bits = std::max(max_col_bits, bits);
-            }
-            const uint32_t row_bits = need_bits;
-            const uint32_t brel_bits = std::max<uint32_t>(ceil_log2(max_col_bits + 1), 1);
-            const uint32_t ent_bits = row_bits + brel_bits <= 32 ? 32 : 64;
-            const uint64_t n_words = (total_bits + 31) / 32;
-
-            Layout L;
-            hac_desc_t& d = L.d;
-            d.magic = kMagic; d.version = kVersion; d.format = HAC_FORMAT_SHAC; d.header_bytes = 256;
-            d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = nnz; d.total_bits = total_bits; d.n_words = n_words;
-            d.k_sym = (uint32_t)s.values.size(); d.lmax = lmax; d.lut_bits = lut_bits;
-            d.has_zero = 0; d.zero_len = 0; d.chunk = Cn; d.ri_bits = 0;
-            d.ent_bits = ent_bits; d.row_bits = ent_bits == 32 ? row_bits : 0; d.n_chunks = ci.n_chunks;
-            d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
-            d.ri_coding = HAC_RI_RICE; d.rice_k = k; d.gap_bits = gap_bits;
-            place_sections(d);
-
-            uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
-            if (!base) return HAC_ENOMEM;
-            std::memcpy(base, &d, sizeof d);
-            write_tables(base, d, s.values, len, t, lut);
-            BitWriter bw = { reinterpret_cast<uint32_t*>(base + d.off_stream), 0 };
-            uint32_t* ent = reinterpret_cast<uint32_t*>(base + d.off_chunk_ent);
-            uint64_t chunk = 0;
-            for (int64_t j = 0; j < m; ++j) {
-                const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
-                ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
-                const uint64_t col_bit0 = bw.bitpos;
-                for (uint64_t p = p0; p < pend; ++p) {
-                    const uint32_t g = gap_at(s, p, p0);
-                    if ((p - p0) % Cn == 0) {
-                        const uint64_t rel = bw.bitpos - col_bit0;
-                        const uint64_t row = (uint64_t)s.ri[(size_t)p] - g;      // the row the gap counts from
-                        if (ent_bits == 32) ent[chunk] = (uint32_t)((rel << row_bits) | row);
-                        else { ent[2 * chunk] = (uint32_t)row; ent[2 * chunk + 1] = (uint32_t)rel; }
-                        ++chunk;
-                    }
-                    const uint32_t q = g >> k;
-                    if (q < kRiceEscape) {
-                        bw.skip(q);
-                        bw.put((1u << k) | (g & ((1u << k) - 1u)), k + 1);
-                    } else {
-                        bw.skip(kRiceEscape);
-                        bw.put(1u, 1);
-                        bw.put(g, 32);
-                    }
-                    const uint32_t sy = s.sym[(size_t)p];
-                    bw.put(t.code[sy], len[sy]);
-                }
-            }
-            ci.col_bit[(size_t)m] = (uint32_t)bw.bitpos;
-            std::memcpy(base + d.off_col_chunk, ci.col_chunk.data(), 4 * ((size_t)m + 1));
-            std::memcpy(base + d.off_col_pos, ci.col_pos.data(), 4 * ((size_t)m + 1));
-            std::memcpy(base + d.off_col_bit, ci.col_bit.data(), 4 * ((size_t)m + 1));
-            if (chunk != ci.n_chunks || bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
-            *blob = base; *blob_bytes = (size_t)d.blob_bytes;
-            return HAC_OK;
-        }
-        uint64_t max_col_bits = 0;
-        for (int64_t j = 0; j < m; ++j) {
-            uint64_t bits = 0;
-            for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) bits += len[s.sym[(size_t)p]];
-            max_col_bits = std::max(max_col_bits, bits);
-        }
-        const uint32_t ent_bits = max_col_bits < 65536 ? 16 : 32;
-        const uint64_t n_words = (total_bits + 31) / 32;
-        if (nnz * (uint64_t)ri_bits > 0xfffffff0ull * 32ull) return HAC_ERANGE;
-
-        Layout L;
-        hac_desc_t& d = L.d;
-        d.magic = kMagic; d.version = kVersion; d.format = HAC_FORMAT_SHAC; d.header_bytes = 256;
-        d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = nnz; d.total_bits = total_bits; d.n_words = n_words;
-        d.k_sym = (uint32_t)s.values.size(); d.lmax = lmax; d.lut_bits = lut_bits;
-        d.has_zero = 0; d.zero_len = 0; d.chunk = Cn; d.ri_bits = ri_bits;
-        d.ent_bits = ent_bits; d.row_bits = 0; d.n_chunks = ci.n_chunks;
-        d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
-        place_sections(d);
-
-        uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)d.blob_bytes));
-        if (!base) return HAC_ENOMEM;
-        std::memcpy(base, &d, sizeof d);
-        write_tables(base, d, s.values, len, t, lut);
-
-        BitWriter bw = { reinterpret_cast<uint32_t*>(base + d.off_stream), 0 };
-        BitWriter rw = { reinterpret_cast<uint32_t*>(base + d.off_ri), 0 };
-        uint16_t* ent16 = reinterpret_cast<uint16_t*>(base + d.off_chunk_ent);
-        uint32_t* ent32 = reinterpret_cast<uint32_t*>(base + d.off_chunk_ent);
-        uint64_t chunk = 0;
-        for (int64_t j = 0; j < m; ++j) {
-            const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
-            ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
-            const uint64_t col_bit0 = bw.bitpos;
-            for (uint64_t p = p0; p < pend; ++p) {
-                if ((p - p0) % Cn == 0) {
-                    const uint64_t rel = bw.bitpos - col_bit0;
-                    if (ent_bits == 16) ent16[chunk] = (uint16_t)rel; else ent32[chunk] = (uint32_t)rel;
-                    ++chunk;
-                }
-                const uint32_t sy = s.sym[(size_t)p];
-                bw.put(t.code[sy], len[sy]);
-                rw.put(s.ri[(size_t)p], ri_bits);
-            }
-        }
-        ci.col_bit[(size_t)m] = (uint32_t)bw.bitpos;
-        std::memcpy(base + d.off_col_chunk, ci.col_chunk.data(), 4 * ((size_t)m + 1));
-        std::memcpy(base + d.off_col_pos, ci.col_pos.data(), 4 * ((size_t)m + 1));
-        std::memcpy(base + d.off_col_bit, ci.col_bit.data(), 4 * ((size_t)m + 1));
-        if (chunk != ci.n_chunks || bw.bitpos != total_bits) { std::free(base); return HAC_EFORMAT; }
-        *blob = base; *blob_bytes = (size_t)d.blob_bytes;
-        return HAC_OK;
+        return encode_single(HAC_FORMAT_SHAC, W, n, m, ldw, opts, blob, blob_bytes);
     } catch (const std::bad_alloc&) {
         return HAC_ENOMEM;
     }
@@ -623,8 +667,8 @@ extern "C" int im_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
         const uint32_t bits = k <= 256 ? 8 : 16;
         const uint64_t pitch = ((uint64_t)m + 15) / 16 * 16;
         if ((uint64_t)n * pitch * (bits / 8) > 0xffffffff00ull) return HAC_ERANGE;
-        Layout L;
-        hac_desc_t& d = L.d;
+        hac_desc_t d;
+        std::memset(&d, 0, sizeof d);
         d.magic = kMagic; d.version = kVersion; d.format = HAC_FORMAT_IM; d.header_bytes = 256;
         d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = s.ri.size();
         d.total_bits = (uint64_t)bits * (uint64_t)n * (uint64_t)m;
