@@ -142,7 +142,10 @@ typedef struct {
     uint32_t row_bits;     /* ent_bits = 32 with a row: low bits of an entry that hold it  */
     uint32_t ri_coding;    /* sHAC: HAC_RI_FIELDS or HAC_RI_RICE                           */
     uint32_t rice_k;       /* HAC_RI_RICE: the parameter k                                 */
-    uint32_t reserved32;
+    uint32_t dict_shared;  /* 1 in the headers of a network blob (hac_net_encode): offsets count
+                              from the start of the network blob, the table offsets are those
+                              of the one shared dictionary, k_sym / has_zero describe that
+                              dictionary (a layer need not use every symbol); else 0       */
     uint64_t gap_bits;     /* HAC_RI_RICE: part of total_bits spent on the gap codewords   */
     uint64_t idx_pitch;    /* IM: elements from one row of the index map to the next, a
                               multiple of 16; the columns past m hold 0                    */
@@ -249,6 +252,78 @@ int hac_stats(const void *blob, size_t bytes, hac_stats_t *out);
  *       order, each may be NULL). */
 int hac_decode_host(const void *blob, size_t bytes, float *W_out, int32_t *sym_out,
                     int32_t *row_out, int32_t *col_out);
+
+/* ---- one dictionary for all layers of a network (Sect. V-H) ----------------- */
+
+/* When the layers of a network are quantized together ("unified" quantization,
+ * Sect. V-H; used for whole networks in Sect. V-K) they draw their weights from
+ * one set of representatives, and one dictionary serves all of them.  A network
+ * blob holds L layers, each HAC or sHAC, written with ONE Huffman code: every
+ * layer contributes the symbols it writes into its own stream (all n*m entries
+ * for HAC, the non-zeros for sHAC) to one pooled source; the alphabet numbers
+ * the pooled values as usual (0.0 first when a HAC layer holds a zero, then
+ * ascending) and the code is built from the pooled counts.  (The paper does not
+ * say what is pooled when HAC and sHAC layers are mixed; this makes the code
+ * optimal for all streams together.)
+ *
+ * Layout: this 256-byte header, L layer headers (hac_desc_t with dict_shared =
+ * 1), the shared tables, then every layer's own sections (stream, per-column
+ * arrays, chunk entries, ri).  All offsets count from the start of the network
+ * blob, so a layer is multiplied with
+ *        hac_dot(&layer_desc, d_network_blob, ...)   (or shac_dot)
+ * exactly like a blob of its own, d_network_blob being the device copy of the
+ * whole network blob. */
+typedef struct {
+    uint32_t magic;         /* 'HACN' = 0x4e434148                                         */
+    uint32_t version;       /* 1                                                           */
+    uint32_t header_bytes;  /* 256                                                         */
+    uint32_t n_layers;      /* L >= 1                                                      */
+    uint64_t blob_bytes;    /* total size                                                  */
+    uint64_t off_layers;    /* hac_desc_t[L]                                               */
+    uint64_t off_codebook, off_codelen, off_canon, off_symsort, off_lut;   /* as in hac_desc_t */
+    uint32_t k_sym, lmax, lut_bits, has_zero;                              /* as in hac_desc_t */
+    uint64_t reserved[21];
+} hac_net_t;
+
+typedef struct {
+    uint64_t n_layers;
+    uint64_t entries;          /* sum of n*m                                               */
+    uint64_t nnz;              /* sum of the layers' non-zeros                             */
+    uint64_t symbols;          /* codewords in all streams (the pooled source's length)    */
+    uint64_t stream_bits;      /* sum of the layers' total_bits                            */
+    uint64_t table_bytes;      /* the one dictionary                                       */
+    uint64_t blob_bytes;
+    uint64_t paper_bits;       /* the layers' words (+ ri, cb for sHAC) as in hac_stats_t,
+                                  plus 6*32*k ONCE for the two dictionaries                */
+    double   entropy_bits;     /* entropy of the pooled source per symbol                  */
+    double   avg_code_bits;    /* bits spent on value codewords / symbols: H <= avg <= H+1 */
+    double   psi;              /* blob_bytes / (4 * entries)                               */
+} hac_net_stats_t;
+
+/* Encode L layers with one shared dictionary.  formats[l] is HAC_FORMAT_HAC or
+ * HAC_FORMAT_SHAC; W[l] is n[l] x m[l], row-major, leading dimension ldw[l] (all
+ * host).  opts (may be NULL) applies to every layer: chunk_nnz and ri_bits = 0
+ * are chosen per layer, ri_coding affects the sHAC layers only.  Ownership and
+ * errors as for hac_encode; L > 65536 gives HAC_EINVAL. */
+int hac_net_encode(uint32_t n_layers, const uint32_t *formats, const float *const *W,
+                   const int64_t *n, const int64_t *m, const int64_t *ldw,
+                   const hac_opts_t *opts, void **blob, size_t *blob_bytes);
+
+/* Copy the network header / the header of one layer of a host network blob
+ * (header checks only). */
+int hac_net_describe(const void *blob, size_t bytes, hac_net_t *net);
+int hac_net_layer(const void *blob, size_t bytes, uint32_t layer, hac_desc_t *desc);
+
+/* hac_validate for a network blob: the shared tables once, then every layer;
+ * also that all layers point at the shared tables. */
+int hac_net_validate(const void *blob, size_t bytes, int deep);
+
+/* Size accounting with the dictionary counted once. */
+int hac_net_stats(const void *blob, size_t bytes, hac_net_stats_t *out);
+
+/* hac_decode_host for one layer of a network blob. */
+int hac_net_decode_host(const void *blob, size_t bytes, uint32_t layer, float *W_out,
+                        int32_t *sym_out, int32_t *row_out, int32_t *col_out);
 
 /* ---- device side (asynchronous on `stream`) -------------------------------- */
 

@@ -25,6 +25,8 @@ EXPORTS = (
     "hac_decode_host", "hac_workspace_bytes", "hac_workspace_bytes_for", "hac_dot_route", "hac_dot", "shac_dot", "hac_decode_dev",
     "shac_decode_dev", "hac_strerror", "hac_last_hip_error", "im_encode", "im_dot",
     "hac_encode_dev", "hac_encode_dev_workspace_bytes", "hac_choose_format",
+    "hac_net_encode", "hac_net_describe", "hac_net_layer", "hac_net_validate", "hac_net_stats",
+    "hac_net_decode_host",
 )
 
 
@@ -58,7 +60,7 @@ class Desc(C.Structure):
                 ("off_chunk_ent", C.c_uint64), ("off_ri", C.c_uint64),
                 ("blob_bytes", C.c_uint64), ("max_col_bits", C.c_uint64), ("max_col_nnz", C.c_uint64),
                 ("row_bits", C.c_uint32), ("ri_coding", C.c_uint32),
-                ("rice_k", C.c_uint32), ("reserved32", C.c_uint32),
+                ("rice_k", C.c_uint32), ("dict_shared", C.c_uint32),
                 ("gap_bits", C.c_uint64), ("idx_pitch", C.c_uint64), ("reserved", C.c_uint64 * 2)]
 
 
@@ -68,6 +70,22 @@ class Stats(C.Structure):
                 ("ri_bytes", C.c_uint64), ("cb_bytes", C.c_uint64), ("blob_bytes", C.c_uint64),
                 ("paper_bits", C.c_uint64), ("bound_bits", C.c_double),
                 ("entropy_bits", C.c_double), ("avg_code_bits", C.c_double), ("psi", C.c_double)]
+
+
+class Net(C.Structure):
+    _fields_ = [("magic", C.c_uint32), ("version", C.c_uint32), ("header_bytes", C.c_uint32),
+                ("n_layers", C.c_uint32), ("blob_bytes", C.c_uint64), ("off_layers", C.c_uint64),
+                ("off_codebook", C.c_uint64), ("off_codelen", C.c_uint64), ("off_canon", C.c_uint64),
+                ("off_symsort", C.c_uint64), ("off_lut", C.c_uint64),
+                ("k_sym", C.c_uint32), ("lmax", C.c_uint32), ("lut_bits", C.c_uint32), ("has_zero", C.c_uint32),
+                ("reserved", C.c_uint64 * 21)]
+
+
+class NetStats(C.Structure):
+    _fields_ = [("n_layers", C.c_uint64), ("entries", C.c_uint64), ("nnz", C.c_uint64), ("symbols", C.c_uint64),
+                ("stream_bits", C.c_uint64), ("table_bytes", C.c_uint64), ("blob_bytes", C.c_uint64),
+                ("paper_bits", C.c_uint64), ("entropy_bits", C.c_double), ("avg_code_bits", C.c_double),
+                ("psi", C.c_double)]
 
 
 class Launch(C.Structure):
@@ -98,6 +116,14 @@ def load_library() -> C.CDLL:
     lib.hac_encode_dev.argtypes = [C.c_uint32, vp, C.c_int64, C.c_int64, C.c_int64, C.POINTER(Opts), vp, C.c_size_t,
                                    C.POINTER(Desc), vp, C.c_size_t, vp]
     lib.hac_choose_format.argtypes = [C.c_int64, C.c_int64, C.c_uint64, C.c_uint32]
+    lib.hac_net_encode.argtypes = [C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(f32p), C.POINTER(C.c_int64),
+                                   C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(Opts),
+                                   C.POINTER(vp), C.POINTER(C.c_size_t)]
+    lib.hac_net_describe.argtypes = [vp, C.c_size_t, C.POINTER(Net)]
+    lib.hac_net_layer.argtypes = [vp, C.c_size_t, C.c_uint32, C.POINTER(Desc)]
+    lib.hac_net_validate.argtypes = [vp, C.c_size_t, C.c_int]
+    lib.hac_net_stats.argtypes = [vp, C.c_size_t, C.POINTER(NetStats)]
+    lib.hac_net_decode_host.argtypes = [vp, C.c_size_t, C.c_uint32, f32p, i32p, i32p, i32p]
     lib.hac_free.argtypes = [vp]
     lib.hac_free.restype = None
     lib.hac_validate.argtypes = [vp, C.c_size_t, C.c_int]
@@ -199,7 +225,92 @@ class DeviceBlob:
         return int(self.desc.m)
 
 
+class NetBlob:
+    """A host network blob: L layers written with one shared dictionary (Sect. V-H)."""
+
+    def __init__(self, data: np.ndarray):
+        self.data = np.ascontiguousarray(data, dtype=np.uint8)
+        self.net = Net()
+        lib = load_library()
+        _check(lib.hac_net_describe(self.data.ctypes.data, self.data.size, C.byref(self.net)), "hac_net_describe")
+        self.layers = []
+        for l in range(int(self.net.n_layers)):
+            d = Desc()
+            _check(lib.hac_net_layer(self.data.ctypes.data, self.data.size, l, C.byref(d)), "hac_net_layer")
+            self.layers.append(d)
+
+    @property
+    def nbytes(self) -> int:
+        return int(self.data.size)
+
+    def validate(self, deep: bool = True) -> int:
+        return load_library().hac_net_validate(self.data.ctypes.data, self.data.size, int(deep))
+
+    def stats(self) -> NetStats:
+        st = NetStats()
+        _check(load_library().hac_net_stats(self.data.ctypes.data, self.data.size, C.byref(st)), "hac_net_stats")
+        return st
+
+    def section(self, desc, off_field: str, dtype, count: int) -> np.ndarray:
+        off = int(getattr(desc, off_field))
+        return self.data[off:off + count * np.dtype(dtype).itemsize].view(dtype)
+
+    def decode_host(self, layer: int, want_w: bool = True):
+        """The library's sequential CPU decoder on one layer: (W, sym[, row, col])."""
+        d = self.layers[layer]
+        n, m, q = int(d.n), int(d.m), int(d.nnz)
+        W = np.empty((n, m), dtype=np.float32) if want_w else None
+        f32p, i32p = C.POINTER(C.c_float), C.POINTER(C.c_int32)
+        wp = W.ctypes.data_as(f32p) if want_w else None
+        lib = load_library()
+        if d.format == HAC_FORMAT_HAC:
+            sym = np.empty(n * m, dtype=np.int32)
+            _check(lib.hac_net_decode_host(self.data.ctypes.data, self.data.size, layer, wp,
+                                           sym.ctypes.data_as(i32p), None, None), "hac_net_decode_host")
+            return W, sym
+        sym = np.empty(max(q, 1), dtype=np.int32)
+        row = np.empty(max(q, 1), dtype=np.int32)
+        col = np.empty(max(q, 1), dtype=np.int32)
+        _check(lib.hac_net_decode_host(self.data.ctypes.data, self.data.size, layer, wp, sym.ctypes.data_as(i32p),
+                                       row.ctypes.data_as(i32p), col.ctypes.data_as(i32p)), "hac_net_decode_host")
+        return W, sym[:q], row[:q], col[:q]
+
+    def to_device(self, device=None):
+        """One device copy of the whole blob; returns a DeviceBlob per layer, all sharing it."""
+        import torch
+        t = torch.from_numpy(self.data).to(device if device is not None else "cuda")
+        return [DeviceBlob(d, t) for d in self.layers]
+
+
 RI_FIELDS, RI_RICE = 0, 1
+
+
+def hac_net_encode(Ws, formats, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0,
+                   ri_coding: int = RI_FIELDS) -> NetBlob:
+    """Layers Ws[l] (n_l x m_l float32, host), formats[l] in (HAC_FORMAT_HAC, HAC_FORMAT_SHAC) -> network blob."""
+    lib = load_library()
+    L = len(Ws)
+    if L != len(formats):
+        raise ValueError("one format per layer")
+    keep = []
+    for W in Ws:
+        W = np.asarray(W)
+        if W.dtype != np.float32 or W.ndim != 2:
+            raise TypeError("every W must be a 2-D float32 array")
+        keep.append(np.ascontiguousarray(W))
+    f32p = C.POINTER(C.c_float)
+    ptrs = (f32p * L)(*[W.ctypes.data_as(f32p) for W in keep])
+    fm = (C.c_uint32 * L)(*[int(f) for f in formats])
+    ns = (C.c_int64 * L)(*[W.shape[0] for W in keep])
+    ms = (C.c_int64 * L)(*[W.shape[1] for W in keep])
+    opts = Opts(chunk_nnz, ri_bits, lut_bits, ri_coding)
+    out, size = C.c_void_p(), C.c_size_t()
+    _check(lib.hac_net_encode(L, fm, ptrs, ns, ms, ms, C.byref(opts), C.byref(out), C.byref(size)), "hac_net_encode")
+    try:
+        data = np.ctypeslib.as_array(C.cast(out, C.POINTER(C.c_uint8)), shape=(size.value,)).copy()
+    finally:
+        lib.hac_free(out)
+    return NetBlob(data)
 
 
 def _encode(fn_name: str, W: np.ndarray, chunk_nnz=0, ri_bits=0, lut_bits=0, ri_coding=0) -> Blob:

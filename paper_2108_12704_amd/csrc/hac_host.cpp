@@ -16,6 +16,7 @@
 #include <vector>
 
 static_assert(sizeof(hac_desc_t) == 256, "blob header must be 256 bytes");
+static_assert(sizeof(hac_net_t) == 256, "network header must be 256 bytes");
 
 using namespace hac_internal;
 
@@ -219,15 +220,19 @@ uint32_t ceil_log2(uint64_t v) { uint32_t b = 0; while (((uint64_t)1 << b) < v) 
 
 // Section offsets and total size from the counts already in the header.  One order for all
 // formats: code tables, stream, per-column arrays, chunk entries, and ri when it is stored as fields.
-void place_sections(hac_desc_t& d)
+void place_tables(hac_desc_t& d, uint64_t& cursor)
 {
-    uint64_t cursor = sizeof(hac_desc_t);
     auto place = [&](uint64_t bytes) { const uint64_t o = align_up(cursor); cursor = o + bytes; return o; };
     d.off_codebook = place(4ull * d.k_sym);
     d.off_codelen = place(d.k_sym);
     d.off_canon = place(3 * 33 * 4);
     d.off_symsort = place(4ull * d.k_sym);
     d.off_lut = place(4ull << d.lut_bits);
+}
+
+void place_layer(hac_desc_t& d, uint64_t& cursor)
+{
+    auto place = [&](uint64_t bytes) { const uint64_t o = align_up(cursor); cursor = o + bytes; return o; };
     d.off_stream = place(4 * d.n_words + kTailPad);
     d.off_col_chunk = place(4 * (d.m + 1));
     d.off_col_pos = place(4 * (d.m + 1));
@@ -235,6 +240,13 @@ void place_sections(hac_desc_t& d)
     d.off_chunk_ent = place(d.n_chunks * (d.ent_bits / 8) + 8);
     if (d.format == HAC_FORMAT_SHAC && d.ri_coding == HAC_RI_FIELDS)
         d.off_ri = place(4 * ((d.nnz * d.ri_bits + 31) / 32) + kTailPad);
+}
+
+void place_sections(hac_desc_t& d)
+{
+    uint64_t cursor = sizeof(hac_desc_t);
+    place_tables(d, cursor);
+    place_layer(d, cursor);
     d.blob_bytes = align_up(cursor);
 }
 
@@ -648,6 +660,102 @@ extern "C" int shac_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
 }
 
 // =================================================================================
+// network blob: all layers written with one shared dictionary (Sect. V-H)
+// =================================================================================
+extern "C" int hac_net_encode(uint32_t n_layers, const uint32_t* formats, const float* const* W,
+                              const int64_t* n, const int64_t* m, const int64_t* ldw,
+                              const hac_opts_t* opts, void** blob, size_t* blob_bytes)
+{
+    if (!blob || !blob_bytes) return HAC_EINVAL;
+    *blob = nullptr; *blob_bytes = 0;
+    if (!formats || !W || !n || !m || !ldw || n_layers < 1 || n_layers > 65536) return HAC_EINVAL;
+    int rc = check_opts(opts);
+    if (rc) return rc;
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        if (formats[l] != HAC_FORMAT_HAC && formats[l] != HAC_FORMAT_SHAC) return HAC_EINVAL;
+        void* dummy_blob; size_t dummy_bytes;
+        if ((rc = check_args(W[l], n[l], m[l], ldw[l], &dummy_blob, &dummy_bytes))) return rc;
+        if (formats[l] == HAC_FORMAT_SHAC) {
+            bool rice; uint32_t ri_bits;
+            if ((rc = check_shac_opts(opts, n[l], rice, ri_bits))) return rc;
+        }
+    }
+    try {
+        std::vector<Scan> scans(n_layers);
+        for (uint32_t l = 0; l < n_layers; ++l)
+            if ((rc = scan_matrix(W[l], n[l], m[l], ldw[l], scans[l]))) return rc;
+        // the pooled source: what every layer writes into its stream
+        std::vector<std::pair<float, uint64_t>> pool;
+        uint64_t zeros = 0;
+        for (uint32_t l = 0; l < n_layers; ++l) {
+            const Scan& s = scans[l];
+            if (formats[l] == HAC_FORMAT_HAC) zeros += s.zeros;
+            for (size_t i = 0; i < s.values.size(); ++i) pool.emplace_back(s.values[i], s.freq[i]);
+        }
+        std::sort(pool.begin(), pool.end(), [](const std::pair<float, uint64_t>& a, const std::pair<float, uint64_t>& b) {
+            return a.first < b.first;
+        });
+        Dict D;
+        D.has_zero = zeros > 0;
+        if (D.has_zero) { D.codebook.push_back(0.0f); D.freq.push_back(zeros); }
+        for (size_t i = 0; i < pool.size(); ++i) {
+            if (i && pool[i].first == pool[i - 1].first) D.freq.back() += pool[i].second;
+            else { D.codebook.push_back(pool[i].first); D.freq.push_back(pool[i].second); }
+        }
+        if ((rc = finish_dict(D, opts))) return rc;
+        const uint32_t first = D.has_zero ? 1u : 0u;
+
+        std::vector<LayerPlan> plans(n_layers);
+        for (uint32_t l = 0; l < n_layers; ++l) {
+            const Scan& s = scans[l];
+            LayerPlan& P = plans[l];
+            P.map.resize(s.values.size());
+            for (size_t i = 0; i < s.values.size(); ++i) {
+                const auto it = std::lower_bound(D.codebook.begin() + first, D.codebook.end(), s.values[i]);
+                P.map[i] = (uint32_t)(it - D.codebook.begin());
+            }
+            rc = formats[l] == HAC_FORMAT_HAC ? plan_hac(s, D, opts, P) : plan_shac(s, D, opts, P);
+            if (rc) return rc;
+            P.d.has_zero = D.has_zero;
+            P.d.dict_shared = 1;
+        }
+
+        hac_net_t net;
+        std::memset(&net, 0, sizeof net);
+        net.magic = kNetMagic; net.version = kNetVersion; net.header_bytes = 256; net.n_layers = n_layers;
+        net.off_layers = sizeof(hac_net_t);
+        uint64_t cursor = net.off_layers + (uint64_t)n_layers * sizeof(hac_desc_t);
+        hac_desc_t tables = plans[0].d;
+        place_tables(tables, cursor);
+        net.off_codebook = tables.off_codebook; net.off_codelen = tables.off_codelen; net.off_canon = tables.off_canon;
+        net.off_symsort = tables.off_symsort; net.off_lut = tables.off_lut;
+        net.k_sym = tables.k_sym; net.lmax = D.lmax; net.lut_bits = D.lut_bits; net.has_zero = D.has_zero;
+        for (uint32_t l = 0; l < n_layers; ++l) {
+            hac_desc_t& d = plans[l].d;
+            d.off_codebook = tables.off_codebook; d.off_codelen = tables.off_codelen; d.off_canon = tables.off_canon;
+            d.off_symsort = tables.off_symsort; d.off_lut = tables.off_lut;
+            place_layer(d, cursor);
+        }
+        net.blob_bytes = align_up(cursor);
+        for (uint32_t l = 0; l < n_layers; ++l) plans[l].d.blob_bytes = net.blob_bytes;
+
+        uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)net.blob_bytes));
+        if (!base) return HAC_ENOMEM;
+        std::memcpy(base, &net, sizeof net);
+        write_tables(base, plans[0].d, D.codebook, D.len, D.t, D.lut);
+        for (uint32_t l = 0; l < n_layers; ++l) {
+            std::memcpy(base + net.off_layers + (uint64_t)l * sizeof(hac_desc_t), &plans[l].d, sizeof(hac_desc_t));
+            rc = formats[l] == HAC_FORMAT_HAC ? write_hac(base, scans[l], D, plans[l]) : write_shac(base, scans[l], D, plans[l]);
+            if (rc) { std::free(base); return rc; }
+        }
+        *blob = base; *blob_bytes = (size_t)net.blob_bytes;
+        return HAC_OK;
+    } catch (const std::bad_alloc&) {
+        return HAC_ENOMEM;
+    }
+}
+
+// =================================================================================
 // index map encoder (Sect. III-C1)
 // =================================================================================
 extern "C" int im_encode(const float* W, int64_t n, int64_t m, int64_t ldw,
@@ -712,16 +820,17 @@ bool section_ok(const hac_desc_t& d, uint64_t off, uint64_t bytes, size_t total)
     return off + bytes <= d.blob_bytes;
 }
 
-int check_header(const void* blob, size_t bytes, hac_desc_t& d)
+// A header against the size of the buffer its offsets count from.  in_net: the header of a layer
+// of a network blob, whose k_sym / has_zero are those of the shared dictionary.
+int check_desc(const hac_desc_t& d, size_t bytes, bool in_net)
 {
-    if (!blob) return HAC_EINVAL;
-    if (bytes < sizeof(hac_desc_t)) return HAC_EFORMAT;
-    std::memcpy(&d, blob, sizeof d);
     if (d.magic != kMagic || d.version != kVersion || d.header_bytes != 256) return HAC_EFORMAT;
+    if (d.dict_shared != (in_net ? 1u : 0u)) return HAC_EFORMAT;
+    if (in_net && d.format == HAC_FORMAT_IM) return HAC_EFORMAT;
     if (d.format != HAC_FORMAT_HAC && d.format != HAC_FORMAT_SHAC && d.format != HAC_FORMAT_IM) return HAC_EFORMAT;
     if (d.blob_bytes > bytes || d.blob_bytes < sizeof(hac_desc_t)) return HAC_EFORMAT;
     if (d.n < 1 || d.m < 1 || d.n > 0x7fffffffull || d.m > 0x7fffffffull) return HAC_EFORMAT;
-    if (d.reserved32 || d.reserved[0] || d.reserved[1]) return HAC_EFORMAT;
+    if (d.reserved[0] || d.reserved[1]) return HAC_EFORMAT;
     if (d.format == HAC_FORMAT_IM) {
         if (d.ent_bits != 8 && d.ent_bits != 16) return HAC_EFORMAT;
         if (d.k_sym < 1 || d.k_sym > (d.ent_bits == 8 ? 256u : 65536u) || d.has_zero > 1) return HAC_EFORMAT;
@@ -741,8 +850,8 @@ int check_header(const void* blob, size_t bytes, hac_desc_t& d)
     if (d.nnz > d.n * d.m || d.nnz > 0xfffffff0ull || d.total_bits > 0xfffffff0ull) return HAC_EFORMAT;
     if (d.n_words != (d.total_bits + 31) / 32) return HAC_EFORMAT;
     if (d.lmax > 32 || d.lut_bits < 1 || d.lut_bits > 12) return HAC_EFORMAT;
-    if (d.k_sym > d.n * d.m) return HAC_EFORMAT;
-    if ((d.k_sym == 0) != (d.total_bits == 0)) return HAC_EFORMAT;
+    if (!in_net && d.k_sym > d.n * d.m) return HAC_EFORMAT;
+    if (in_net ? (d.k_sym == 0 && d.total_bits != 0) : ((d.k_sym == 0) != (d.total_bits == 0))) return HAC_EFORMAT;
     if (d.k_sym > 0 && (d.lmax < 1)) return HAC_EFORMAT;
     if (d.chunk < 1 || d.chunk > 65536) return HAC_EFORMAT;
     if (d.ri_coding > HAC_RI_RICE) return HAC_EFORMAT;
@@ -761,7 +870,7 @@ int check_header(const void* blob, size_t bytes, hac_desc_t& d)
     if (d.format == HAC_FORMAT_HAC) {
         if (d.ent_bits != 32 && d.ent_bits != 64) return HAC_EFORMAT;
         if (d.has_zero > 1) return HAC_EFORMAT;
-        if (d.has_zero != (d.nnz < d.n * d.m ? 1u : 0u)) return HAC_EFORMAT;
+        if (in_net ? (d.nnz < d.n * d.m && !d.has_zero) : (d.has_zero != (d.nnz < d.n * d.m ? 1u : 0u))) return HAC_EFORMAT;
         const uint32_t need = std::max<uint32_t>(ceil_log2(d.n), 1);
         if (d.ent_bits == 32) {
             if (d.row_bits != need) return HAC_EFORMAT;
@@ -775,7 +884,7 @@ int check_header(const void* blob, size_t bytes, hac_desc_t& d)
             if (d.row_bits != need) return HAC_EFORMAT;
             if (d.row_bits + std::max<uint32_t>(ceil_log2(d.max_col_bits + 1), 1) > 32) return HAC_EFORMAT;
         } else if (d.row_bits != 0) return HAC_EFORMAT;
-        if (d.ri_bits || d.off_ri || d.has_zero || d.zero_len) return HAC_EFORMAT;
+        if (d.ri_bits || d.off_ri || (d.has_zero && !in_net) || d.has_zero > 1 || d.zero_len) return HAC_EFORMAT;
         if (d.rice_k > kRiceKMax || d.gap_bits > d.total_bits) return HAC_EFORMAT;
         if (d.gap_bits < d.nnz) return HAC_EFORMAT;                      // at least the terminating one per gap
     } else {
@@ -784,11 +893,19 @@ int check_header(const void* blob, size_t bytes, hac_desc_t& d)
         if (d.ent_bits == 16 && d.max_col_bits >= 65536) return HAC_EFORMAT;
         const uint32_t need = std::max<uint32_t>(ceil_log2(d.n), 1);
         if (d.ri_bits < need || d.ri_bits > 32) return HAC_EFORMAT;
-        if (d.has_zero || d.zero_len || d.row_bits) return HAC_EFORMAT;
+        if ((d.has_zero && !in_net) || d.has_zero > 1 || d.zero_len || d.row_bits) return HAC_EFORMAT;
         if (!section_ok(d, d.off_ri, 4 * ((d.nnz * d.ri_bits + 31) / 32) + kTailPad, tot)) return HAC_EFORMAT;
     }
     if (!section_ok(d, d.off_chunk_ent, d.n_chunks * (d.ent_bits / 8) + 8, tot)) return HAC_EFORMAT;
     return HAC_OK;
+}
+
+int check_header(const void* blob, size_t bytes, hac_desc_t& d)
+{
+    if (!blob) return HAC_EINVAL;
+    if (bytes < sizeof(hac_desc_t)) return HAC_EFORMAT;
+    std::memcpy(&d, blob, sizeof d);
+    return check_desc(d, bytes, false);
 }
 
 struct View {
@@ -862,7 +979,9 @@ int check_tables(const View& v)
         const uint32_t zl = (d.has_zero && t.code[0] == 0) ? len[0] : 0;
         if (zl != d.zero_len) return HAC_EFORMAT;
     } else {
-        for (uint32_t s = 0; s < d.k_sym; ++s) if (v.codebook[s] == 0.0f) return HAC_EFORMAT;
+        // an sHAC layer of a network blob may see the shared dictionary's 0.0 (symbol 0), never uses it
+        if (d.has_zero && float_bits(v.codebook[0]) != 0) return HAC_EFORMAT;
+        for (uint32_t s = d.has_zero; s < d.k_sym; ++s) if (v.codebook[s] == 0.0f) return HAC_EFORMAT;
     }
     return HAC_OK;
 }
@@ -1086,6 +1205,74 @@ extern "C" int hac_describe(const void* blob, size_t bytes, hac_desc_t* desc)
     return check_header(blob, bytes, *desc);
 }
 
+namespace {
+
+// how often each symbol occurs in a layer's stream (sequential decode)
+int count_symbols(const View& v, std::vector<uint64_t>& cnt)
+{
+    const hac_desc_t& d = v.d;
+    SeqDecoder dec(v);
+    const uint64_t symbols = d.format == HAC_FORMAT_HAC ? d.n * d.m : d.nnz;
+    for (uint64_t i = 0; i < symbols; ++i) {
+        if (d.ri_coding == HAC_RI_RICE && dec.next_gap(d.rice_k) < 0) return HAC_EFORMAT;
+        const int64_t s = dec.next();
+        if (s < 0) return HAC_EFORMAT;
+        cnt[(size_t)s]++;
+    }
+    return HAC_OK;
+}
+
+// the paper's size of one layer without its dictionaries: words (+ ri and cb for sHAC)
+uint64_t layer_paper_bits(const hac_desc_t& d)
+{
+    if (d.format == HAC_FORMAT_HAC) return 32 * d.n_words;
+    const bool rice = d.ri_coding == HAC_RI_RICE;
+    return 32 * d.n_words + 32 * ((rice ? 0 : d.nnz) + d.m + 1);
+}
+
+// the library's sequential decoder over one validated layer
+int decode_layer(const View& v, float* W_out, int32_t* sym_out, int32_t* row_out, int32_t* col_out)
+{
+    const hac_desc_t& d = v.d;
+    SeqDecoder dec(v);
+    if (d.format == HAC_FORMAT_HAC) {
+        if (row_out || col_out) return HAC_EINVAL;
+        for (uint64_t j = 0; j < d.m; ++j)
+            for (uint64_t i = 0; i < d.n; ++i) {
+                const int64_t s = dec.next();
+                if (s < 0) return HAC_EFORMAT;
+                if (sym_out) sym_out[j * d.n + i] = (int32_t)s;
+                if (W_out) W_out[i * d.m + j] = v.codebook[s];
+            }
+    } else {
+        if (W_out) std::memset(W_out, 0, sizeof(float) * (size_t)(d.n * d.m));
+        const bool rice = d.ri_coding == HAC_RI_RICE;
+        for (uint64_t j = 0; j < d.m; ++j) {
+            int64_t prev = -1;
+            for (uint64_t p = v.colpos[j]; p < v.colpos[j + 1]; ++p) {
+                uint64_t r;
+                if (rice) {
+                    const int64_t gap = dec.next_gap(d.rice_k);
+                    if (gap < 0) return HAC_EFORMAT;
+                    r = (uint64_t)(prev + 1 + gap);
+                    prev = (int64_t)r;
+                }
+                const int64_t s = dec.next();
+                if (s < 0) return HAC_EFORMAT;
+                if (!rice) r = ri_field(v.ri, p, d.ri_bits);
+                if (r >= d.n) return HAC_EFORMAT;
+                if (sym_out) sym_out[p] = (int32_t)s;
+                if (row_out) row_out[p] = (int32_t)r;
+                if (col_out) col_out[p] = (int32_t)j;
+                if (W_out) W_out[(uint64_t)r * d.m + j] = v.codebook[s];
+            }
+        }
+    }
+    return HAC_OK;
+}
+
+} // namespace
+
 extern "C" int hac_stats(const void* blob, size_t bytes, hac_stats_t* out)
 {
     if (!out) return HAC_EINVAL;
@@ -1127,26 +1314,20 @@ extern "C" int hac_stats(const void* blob, size_t bytes, hac_stats_t* out)
     const uint64_t ent_bytes = d.n_chunks * (d.ent_bits / 8);
     if (d.format == HAC_FORMAT_HAC) {
         out->index_bytes = 3 * 4 * (d.m + 1) + ent_bytes;
-        out->paper_bits = 32 * d.n_words + 6ull * 32 * d.k_sym;
+        out->paper_bits = layer_paper_bits(d) + 6ull * 32 * d.k_sym;
         out->bound_bits = nm * (1.0 + std::log2(k)) + 6.0 * k * 32.0;
     } else {
         const bool rice = d.ri_coding == HAC_RI_RICE;
         out->index_bytes = 2 * 4 * (d.m + 1) + ent_bytes;
         out->ri_bytes = rice ? 0 : 4 * ((d.nnz * d.ri_bits + 31) / 32);
         out->cb_bytes = 4 * (d.m + 1);
-        out->paper_bits = 32 * d.n_words + 6ull * 32 * d.k_sym + 32 * ((rice ? 0 : d.nnz) + d.m + 1);
+        out->paper_bits = layer_paper_bits(d) + 6ull * 32 * d.k_sym;
         out->bound_bits = (double)d.nnz * (1.0 + std::log2(k)) + 32.0 * (6.0 * k + (double)d.nnz + (double)d.m + 1.0);
     }
     // entropy from the code lengths is not available; recompute symbol counts by a sequential decode
     std::vector<uint64_t> cnt(d.k_sym, 0);
-    SeqDecoder dec(v);
+    if ((rc = count_symbols(v, cnt))) return rc;
     const uint64_t symbols = d.format == HAC_FORMAT_HAC ? d.n * d.m : d.nnz;
-    for (uint64_t i = 0; i < symbols; ++i) {
-        if (d.ri_coding == HAC_RI_RICE && dec.next_gap(d.rice_k) < 0) return HAC_EFORMAT;
-        const int64_t s = dec.next();
-        if (s < 0) return HAC_EFORMAT;
-        cnt[(size_t)s]++;
-    }
     double H = 0.0;
     for (uint32_t s = 0; s < d.k_sym; ++s)
         if (cnt[s]) { const double p = (double)cnt[s] / (double)symbols; H -= p * std::log2(p); }
@@ -1178,41 +1359,138 @@ extern "C" int hac_decode_host(const void* blob, size_t bytes, float* W_out, int
     View v; make_view(blob, d, v);
     if ((rc = check_tables(v))) return rc;
     if ((rc = check_index_shallow(v))) return rc;
-    SeqDecoder dec(v);
-    if (d.format == HAC_FORMAT_HAC) {
-        if (row_out || col_out) return HAC_EINVAL;
-        for (uint64_t j = 0; j < d.m; ++j)
-            for (uint64_t i = 0; i < d.n; ++i) {
-                const int64_t s = dec.next();
-                if (s < 0) return HAC_EFORMAT;
-                if (sym_out) sym_out[j * d.n + i] = (int32_t)s;
-                if (W_out) W_out[i * d.m + j] = v.codebook[s];
+    return decode_layer(v, W_out, sym_out, row_out, col_out);
+}
+
+// =================================================================================
+// network blob: description, validation, accounting, decode
+// =================================================================================
+namespace {
+
+int check_net_header(const void* blob, size_t bytes, hac_net_t& net)
+{
+    if (!blob) return HAC_EINVAL;
+    if (bytes < sizeof(hac_net_t)) return HAC_EFORMAT;
+    std::memcpy(&net, blob, sizeof net);
+    if (net.magic != kNetMagic || net.version != kNetVersion || net.header_bytes != 256) return HAC_EFORMAT;
+    if (net.n_layers < 1 || net.n_layers > 65536) return HAC_EFORMAT;
+    if (net.blob_bytes > bytes || net.blob_bytes < sizeof(hac_net_t)) return HAC_EFORMAT;
+    for (size_t i = 0; i < sizeof net.reserved / sizeof net.reserved[0]; ++i) if (net.reserved[i]) return HAC_EFORMAT;
+    if (net.off_layers != sizeof(hac_net_t)) return HAC_EFORMAT;
+    if (net.off_layers + (uint64_t)net.n_layers * sizeof(hac_desc_t) > net.blob_bytes) return HAC_EFORMAT;
+    if (net.has_zero > 1 || net.lmax > 32 || net.lut_bits < 1 || net.lut_bits > 12) return HAC_EFORMAT;
+    return HAC_OK;
+}
+
+// header of layer l, checked against the network header
+int net_layer_desc(const void* blob, const hac_net_t& net, uint32_t l, hac_desc_t& d)
+{
+    if (l >= net.n_layers) return HAC_EINVAL;
+    std::memcpy(&d, static_cast<const uint8_t*>(blob) + net.off_layers + (uint64_t)l * sizeof(hac_desc_t), sizeof d);
+    if (d.blob_bytes != net.blob_bytes) return HAC_EFORMAT;
+    int rc = check_desc(d, (size_t)net.blob_bytes, true);
+    if (rc) return rc;
+    if (d.off_codebook != net.off_codebook || d.off_codelen != net.off_codelen || d.off_canon != net.off_canon ||
+        d.off_symsort != net.off_symsort || d.off_lut != net.off_lut || d.k_sym != net.k_sym || d.lmax != net.lmax ||
+        d.lut_bits != net.lut_bits || d.has_zero != net.has_zero) return HAC_EFORMAT;
+    // a layer's own sections lie behind the headers
+    const uint64_t first = net.off_layers + (uint64_t)net.n_layers * sizeof(hac_desc_t);
+    if (d.off_codebook < first || d.off_stream < first || d.off_col_chunk < first || d.off_col_pos < first ||
+        d.off_col_bit < first || d.off_chunk_ent < first || (d.off_ri && d.off_ri < first)) return HAC_EFORMAT;
+    return HAC_OK;
+}
+
+} // namespace
+
+extern "C" int hac_net_describe(const void* blob, size_t bytes, hac_net_t* net)
+{
+    if (!net) return HAC_EINVAL;
+    return check_net_header(blob, bytes, *net);
+}
+
+extern "C" int hac_net_layer(const void* blob, size_t bytes, uint32_t layer, hac_desc_t* desc)
+{
+    if (!desc) return HAC_EINVAL;
+    hac_net_t net;
+    int rc = check_net_header(blob, bytes, net);
+    if (rc) return rc;
+    return net_layer_desc(blob, net, layer, *desc);
+}
+
+extern "C" int hac_net_validate(const void* blob, size_t bytes, int deep)
+{
+    hac_net_t net;
+    int rc = check_net_header(blob, bytes, net);
+    if (rc) return rc;
+    try {
+        for (uint32_t l = 0; l < net.n_layers; ++l) {
+            hac_desc_t d;
+            if ((rc = net_layer_desc(blob, net, l, d))) return rc;
+            View v; make_view(blob, d, v);
+            if (l == 0 || d.format != HAC_FORMAT_SHAC) {          // the tables are the same for every layer;
+                if ((rc = check_tables(v))) return rc;            // zero_len is a HAC header's own field
             }
-    } else {
-        if (W_out) std::memset(W_out, 0, sizeof(float) * (size_t)(d.n * d.m));
-        const bool rice = d.ri_coding == HAC_RI_RICE;
-        for (uint64_t j = 0; j < d.m; ++j) {
-            int64_t prev = -1;
-            for (uint64_t p = v.colpos[j]; p < v.colpos[j + 1]; ++p) {
-                uint64_t r;
-                if (rice) {
-                    const int64_t gap = dec.next_gap(d.rice_k);
-                    if (gap < 0) return HAC_EFORMAT;
-                    r = (uint64_t)(prev + 1 + gap);
-                    prev = (int64_t)r;
-                }
-                const int64_t s = dec.next();
-                if (s < 0) return HAC_EFORMAT;
-                if (!rice) r = ri_field(v.ri, p, d.ri_bits);
-                if (r >= d.n) return HAC_EFORMAT;
-                if (sym_out) sym_out[p] = (int32_t)s;
-                if (row_out) row_out[p] = (int32_t)r;
-                if (col_out) col_out[p] = (int32_t)j;
-                if (W_out) W_out[(uint64_t)r * d.m + j] = v.codebook[s];
-            }
+            if ((rc = check_index_shallow(v))) return rc;
+            if (deep && (rc = check_deep(v))) return rc;
         }
+    } catch (const std::bad_alloc&) {
+        return HAC_ENOMEM;
     }
     return HAC_OK;
+}
+
+extern "C" int hac_net_stats(const void* blob, size_t bytes, hac_net_stats_t* out)
+{
+    if (!out) return HAC_EINVAL;
+    hac_net_t net;
+    int rc = check_net_header(blob, bytes, net);
+    if (rc) return rc;
+    try {
+        std::memset(out, 0, sizeof *out);
+        std::vector<uint64_t> cnt(net.k_sym, 0);
+        uint64_t gap_bits = 0;
+        for (uint32_t l = 0; l < net.n_layers; ++l) {
+            hac_desc_t d;
+            if ((rc = net_layer_desc(blob, net, l, d))) return rc;
+            View v; make_view(blob, d, v);
+            if ((rc = check_tables(v))) return rc;
+            if ((rc = check_index_shallow(v))) return rc;
+            if ((rc = count_symbols(v, cnt))) return rc;
+            out->entries += d.n * d.m;
+            out->nnz += d.nnz;
+            out->symbols += d.format == HAC_FORMAT_HAC ? d.n * d.m : d.nnz;
+            out->stream_bits += d.total_bits;
+            out->paper_bits += layer_paper_bits(d);
+            gap_bits += d.gap_bits;
+        }
+        out->n_layers = net.n_layers;
+        out->paper_bits += 6ull * 32 * net.k_sym;
+        out->table_bytes = 4ull * net.k_sym + net.k_sym + 3 * 33 * 4 + 4ull * net.k_sym + (4ull << net.lut_bits);
+        out->blob_bytes = net.blob_bytes;
+        double H = 0.0;
+        for (uint32_t s = 0; s < net.k_sym; ++s)
+            if (cnt[s]) { const double p = (double)cnt[s] / (double)out->symbols; H -= p * std::log2(p); }
+        out->entropy_bits = H;
+        out->avg_code_bits = out->symbols ? (double)(out->stream_bits - gap_bits) / (double)out->symbols : 0.0;
+        out->psi = (double)net.blob_bytes / (4.0 * (double)out->entries);
+    } catch (const std::bad_alloc&) {
+        return HAC_ENOMEM;
+    }
+    return HAC_OK;
+}
+
+extern "C" int hac_net_decode_host(const void* blob, size_t bytes, uint32_t layer, float* W_out,
+                                   int32_t* sym_out, int32_t* row_out, int32_t* col_out)
+{
+    hac_net_t net;
+    int rc = check_net_header(blob, bytes, net);
+    if (rc) return rc;
+    hac_desc_t d;
+    if ((rc = net_layer_desc(blob, net, layer, d))) return rc;
+    View v; make_view(blob, d, v);
+    if ((rc = check_tables(v))) return rc;
+    if ((rc = check_index_shallow(v))) return rc;
+    return decode_layer(v, W_out, sym_out, row_out, col_out);
 }
 
 extern "C" int hac_choose_format(int64_t n, int64_t m, uint64_t nnz, uint32_t k)

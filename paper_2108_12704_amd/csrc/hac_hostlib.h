@@ -13,6 +13,8 @@ namespace hac_internal {
 
 constexpr uint32_t kMagic = 0x31434148u;   // "HAC1"
 constexpr uint32_t kVersion = 2;
+constexpr uint32_t kNetMagic = 0x4e434148u; // "HACN"
+constexpr uint32_t kNetVersion = 1;
 constexpr uint64_t kAlign = 256;
 constexpr uint64_t kTailPad = 64;          // zero bytes after stream / ri for window over-reads
 constexpr uint32_t kRiceEscape = 31;       // quotients from here on: 31 zeros, a one, the gap in 32 bits
@@ -38,8 +40,11 @@ uint32_t pick_chunk(const hac_opts_t* opts, uint64_t max_col_nnz);
 int check_opts(const hac_opts_t* opts);
 uint32_t rice_length(uint32_t d, uint32_t k);
 
-// Offsets of all sections and blob_bytes, from the counts already in the header.
+// Offsets of all sections and blob_bytes, from the counts already in the header
+// (place_tables, then place_layer, from the end of the header).
 void place_sections(hac_desc_t& d);
+void place_tables(hac_desc_t& d, uint64_t& cursor);
+void place_layer(hac_desc_t& d, uint64_t& cursor);
 int write_tables(uint8_t* base, const hac_desc_t& d, const std::vector<float>& codebook,
                  const std::vector<uint8_t>& len, const CodeTables& t, const std::vector<uint32_t>& lut);
 

@@ -44,6 +44,76 @@ static int exercise(const void* blob, size_t bytes, int n, int m, const std::vec
     return 0;
 }
 
+// the same for a network blob of two layers (n x m, then m x n2)
+static int exercise_net(const void* blob, size_t bytes, const int64_t* ns, const int64_t* ms,
+                        const std::vector<float>* const* expect)
+{
+    hac_net_t net;
+    if (hac_net_describe(blob, bytes, &net) != HAC_OK) return 0;
+    const int ok = hac_net_validate(blob, bytes, 1);
+    hac_net_validate(blob, bytes, 0);
+    hac_net_stats_t st;
+    hac_net_stats(blob, bytes, &st);
+    if (ok != HAC_OK || net.n_layers != 2) return 0;
+    for (uint32_t l = 0; l < 2; ++l) {
+        hac_desc_t d;
+        if (hac_net_layer(blob, bytes, l, &d) != HAC_OK) return 0;
+        if (d.n != (uint64_t)ns[l] || d.m != (uint64_t)ms[l] || d.nnz > d.n * d.m) return 0;
+        const size_t nm = (size_t)(ns[l] * ms[l]);
+        std::vector<float> W(nm, -1.0f);
+        std::vector<int32_t> sym(nm + 1), row(nm + 1), col(nm + 1);
+        const bool csc = d.format == HAC_FORMAT_SHAC;
+        const int rc = hac_net_decode_host(blob, bytes, l, W.data(), sym.data(), csc ? row.data() : nullptr,
+                                           csc ? col.data() : nullptr);
+        if (expect && (rc != HAC_OK || std::memcmp(W.data(), expect[l]->data(), nm * 4) != 0)) {
+            std::fprintf(stderr, "network round trip failed (layer %u, format %u)\n", l, d.format);
+            return 1;
+        }
+    }
+    return 0;
+}
+
+static void fuzz_networks(std::mt19937& rng, int& failures, long& cases)
+{
+    const int shapes[][3] = { {1, 1, 1}, {9, 6, 4}, {40, 33, 7}, {120, 10, 50} };
+    for (const auto& sh : shapes)
+        for (double density : { 0.0, 0.1, 0.7 })
+            for (int k : { 1, 5, 120 })
+                for (int f = 0; f < 6; ++f) {
+                    const int64_t ns[2] = { sh[0], sh[1] }, ms[2] = { sh[1], sh[2] };
+                    std::vector<float> W0 = make_matrix(rng, sh[0], sh[1], density, k);
+                    std::vector<float> W1 = make_matrix(rng, sh[1], sh[2], f % 2 ? density : 1.0 - density, k + 2);
+                    const std::vector<float>* expect[2] = { &W0, &W1 };
+                    const float* Ws[2] = { W0.data(), W1.data() };
+                    const uint32_t fm[2] = { (uint32_t)(f & 1 ? HAC_FORMAT_SHAC : HAC_FORMAT_HAC),
+                                             (uint32_t)(f & 2 ? HAC_FORMAT_SHAC : HAC_FORMAT_HAC) };
+                    hac_opts_t o; std::memset(&o, 0, sizeof o);
+                    o.ri_coding = f >= 4 ? HAC_RI_RICE : HAC_RI_FIELDS;
+                    o.chunk_nnz = (uint32_t)(rng() % 3 == 0 ? 1 + rng() % 9 : 0);
+                    void* blob = nullptr; size_t bytes = 0;
+                    const int rc = hac_net_encode(2, fm, Ws, ns, ms, ms, &o, &blob, &bytes);
+                    if (rc != HAC_OK) { std::fprintf(stderr, "network encode failed: %d\n", rc); ++failures; continue; }
+                    failures += exercise_net(blob, bytes, ns, ms, expect);
+                    ++cases;
+                    std::vector<uint8_t> copy((const uint8_t*)blob, (const uint8_t*)blob + bytes);
+                    for (int t = 0; t < 40; ++t) {
+                        std::vector<uint8_t> bad = copy;
+                        const int kind = (int)(rng() % 4);
+                        if (kind == 0) bad[rng() % bad.size()] ^= (uint8_t)(1u << (rng() % 8));
+                        else if (kind == 1) bad[rng() % 768] = (uint8_t)rng();                       // the three headers
+                        else if (kind == 2) { for (int q = 0; q < 8; ++q) bad[rng() % bad.size()] = (uint8_t)rng(); }
+                        else bad.resize(rng() % bad.size());
+                        uint8_t* heap = (uint8_t*)std::malloc(bad.size() ? bad.size() : 1);
+                        std::memcpy(heap, bad.data(), bad.size());
+                        failures += exercise_net(heap, bad.size(), ns, ms, nullptr);
+                        failures += exercise(heap, bad.size(), sh[0], sh[1], nullptr);               // and as if it were a layer blob
+                        std::free(heap);
+                        ++cases;
+                    }
+                    hac_free(blob);
+                }
+}
+
 int main()
 {
     std::mt19937 rng(12345);
@@ -87,6 +157,7 @@ int main()
             }
         }
     }
+    fuzz_networks(rng, failures, cases);
     std::printf("host fuzz: %ld cases, %d failures\n", cases, failures);
     return failures ? 1 : 0;
 }
