@@ -395,6 +395,36 @@ int shac_dot(const hac_desc_t *desc, const void *d_blob,
              void *d_ws, size_t ws_bytes,
              const hac_launch_t *launch, hac_stream_t stream);
 
+/* A chain of layers (not in the paper, which gives the product of one layer):
+ *     A_0 = X,   A_{l+1} = act_l(A_l . W_l + bias_l),   Y = A_L
+ * with W_l given compressed (HAC, sHAC or IM; layer blobs of their own or the
+ * layers of a network blob), bias_l an optional vector of m_l floats added to
+ * every row, act_l the identity or max(., 0).  Bias and activation are applied
+ * where a sum is finished, and between two layers that both take the sparse
+ * route the activations are written in the feature-major layout the next layer
+ * gathers from, so only X itself is re-laid out.  n of layer l must equal m of
+ * layer l - 1; at most 256 layers.  The result is that of calling the dot of
+ * every layer in turn (same kernels, same order of additions). */
+enum { HAC_ACT_NONE = 0, HAC_ACT_RELU = 1 };
+typedef struct {
+    const hac_desc_t *desc;  /* host: the layer's header                                    */
+    const void *d_blob;      /* device: the blob that header's offsets count from            */
+    const float *d_bias;     /* device: m floats, or NULL                                    */
+    uint32_t activation;     /* HAC_ACT_NONE / HAC_ACT_RELU                                  */
+    uint32_t reserved;       /* 0                                                            */
+} hac_layer_t;
+
+/* Device workspace for hac_forward on a batch of B rows: two activation buffers
+ * and the largest workspace any layer needs (0 on bad arguments or B = 0). */
+size_t hac_forward_workspace_bytes(const hac_layer_t *layers, uint32_t n_layers, int64_t B);
+
+/* Y[B x m_L] = the chain applied to X[B x n_0] (row-major, ldx >= n_0, ldy >= m_L).
+ * d_ws: 256-byte aligned, >= hac_forward_workspace_bytes().  Asynchronous on
+ * `stream`; errors as for hac_dot (HAC_EINVAL also when the shapes do not chain). */
+int hac_forward(const hac_layer_t *layers, uint32_t n_layers,
+                const float *d_X, int64_t B, int64_t ldx, float *d_Y, int64_t ldy,
+                void *d_ws, size_t ws_bytes, hac_stream_t stream);
+
 /* Y = X . W for an index-map blob (Sect. III-C1): pointers are expanded through
  * the representatives tile by tile and multiplied on the matrix cores (fp32 in,
  * fp32 accumulate).  The workspace (hac_workspace_bytes(), 0 for large batches)

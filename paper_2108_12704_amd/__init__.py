@@ -26,7 +26,7 @@ EXPORTS = (
     "shac_decode_dev", "hac_strerror", "hac_last_hip_error", "im_encode", "im_dot",
     "hac_encode_dev", "hac_encode_dev_workspace_bytes", "hac_choose_format",
     "hac_net_encode", "hac_net_describe", "hac_net_layer", "hac_net_validate", "hac_net_stats",
-    "hac_net_decode_host",
+    "hac_net_decode_host", "hac_forward", "hac_forward_workspace_bytes",
 )
 
 
@@ -88,6 +88,14 @@ class NetStats(C.Structure):
                 ("psi", C.c_double)]
 
 
+class Layer(C.Structure):
+    _fields_ = [("desc", C.POINTER(Desc)), ("d_blob", C.c_void_p), ("d_bias", C.c_void_p),
+                ("activation", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+ACT_NONE, ACT_RELU = 0, 1
+
+
 class Launch(C.Structure):
     _fields_ = [("cols_per_wave", C.c_uint32), ("waves_per_block", C.c_uint32),
                 ("variant", C.c_uint32), ("list_entries", C.c_uint32), ("staging_words", C.c_uint32),
@@ -124,6 +132,10 @@ def load_library() -> C.CDLL:
     lib.hac_net_validate.argtypes = [vp, C.c_size_t, C.c_int]
     lib.hac_net_stats.argtypes = [vp, C.c_size_t, C.POINTER(NetStats)]
     lib.hac_net_decode_host.argtypes = [vp, C.c_size_t, C.c_uint32, f32p, i32p, i32p, i32p]
+    lib.hac_forward_workspace_bytes.argtypes = [C.POINTER(Layer), C.c_uint32, C.c_int64]
+    lib.hac_forward_workspace_bytes.restype = C.c_size_t
+    lib.hac_forward.argtypes = [C.POINTER(Layer), C.c_uint32, vp, C.c_int64, C.c_int64, vp, C.c_int64,
+                                vp, C.c_size_t, vp]
     lib.hac_free.argtypes = [vp]
     lib.hac_free.restype = None
     lib.hac_validate.argtypes = [vp, C.c_size_t, C.c_int]
@@ -460,6 +472,54 @@ def hac_dot_route(desc: Desc, B: int, launch: Optional["Launch"] = None) -> int:
 def im_dot(dblob: DeviceBlob, X, Y=None, workspace=None, stream=None):
     """Y = X . W for an index-map blob on the device (asynchronous on the stream)."""
     return _dot("im_dot", dblob, X, Y, workspace, None, stream)
+
+
+def _layer_array(layers):
+    """layers: sequence of (DeviceBlob, bias tensor or None, relu flag)."""
+    import torch
+    arr = (Layer * len(layers))()
+    for i, (dblob, bias, relu) in enumerate(layers):
+        if bias is not None and (bias.dtype != torch.float32 or bias.numel() != dblob.m or not bias.is_contiguous()
+                                 or not bias.is_cuda):
+            raise TypeError("bias must be a contiguous float32 CUDA tensor of m elements")
+        arr[i].desc = C.pointer(dblob.desc)
+        arr[i].d_blob = dblob.tensor.data_ptr()
+        arr[i].d_bias = bias.data_ptr() if bias is not None else None
+        arr[i].activation = ACT_RELU if relu else ACT_NONE
+    return arr
+
+
+def hac_forward_workspace_bytes(layers, B: int) -> int:
+    arr = _layer_array(layers)
+    return int(load_library().hac_forward_workspace_bytes(arr, len(layers), B))
+
+
+def hac_forward(layers, X, Y=None, workspace=None, stream=None):
+    """Y = act_L(... act_0(X . W_0 + b_0) ... . W_L + b_L); layers: (DeviceBlob, bias or None, relu) per layer."""
+    import torch
+    lib = load_library()
+    if X.dtype != torch.float32 or X.dim() != 2 or not X.is_cuda:
+        raise TypeError("X must be a 2-D float32 CUDA tensor")
+    if X.stride(1) != 1:
+        X = X.contiguous()
+    B = X.shape[0]
+    m_out = layers[-1][0].m
+    if Y is None:
+        Y = torch.empty((B, m_out), dtype=torch.float32, device=X.device)
+    elif Y.dtype != torch.float32 or Y.shape != (B, m_out) or Y.stride(1) != 1 or not Y.is_cuda:
+        raise TypeError("Y must be a B x m float32 CUDA tensor with unit column stride")
+    arr = _layer_array(layers)
+    need = int(lib.hac_forward_workspace_bytes(arr, len(layers), B))
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    ldx = X.stride(0) if B > 1 else max(X.shape[1], 1)
+    ldy = Y.stride(0) if B > 1 else max(m_out, 1)
+    rc = lib.hac_forward(arr, len(layers), X.data_ptr(), B, ldx, Y.data_ptr(), ldy, ws_ptr, ws_bytes,
+                         _stream_handle(stream))
+    _check(rc, "hac_forward")
+    return Y
 
 
 def hac_decode_dev(dblob: DeviceBlob, stream=None):

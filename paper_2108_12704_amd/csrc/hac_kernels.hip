@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "../../include/hac.h"
 #include "hac_internal.h"
 #include "hac_hostlib.h"
@@ -508,6 +510,23 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// What happens to a finished sum before it is stored: + bias[column], max(., 0), and where it
+// goes.  yt = nullptr: Y[b * ldy + column].  yt set: the feature-major layout the next layer of
+// a chain reads as its XT, panels of wp batch columns, yt[(b / wp) * m * wp + column * wp + b % wp],
+// with 0 in the padded batch columns.
+struct Epilogue {
+    const float* bias;
+    float* yt;
+    uint32_t relu;
+};
+
+__device__ __forceinline__ float epilogue_apply(const Epilogue& e, float v, uint32_t col)
+{
+    if (e.bias) v += e.bias[col];
+    if (e.relu) v = fmaxf(v, 0.0f);
+    return v;
+}
+
 // FMA phase building blocks.  A lane group takes every ng-th list entry; the
 // loads of kPipe entries are issued together before the first multiply, so that
 // many row fetches are in flight per wave.
@@ -586,7 +605,7 @@ __global__ void __launch_bounds__((BatchTraits<NB>::kMaxThreads))
 dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t B,
                  float* __restrict__ Y, uint64_t ldy, uint32_t cpw, uint32_t gw, uint32_t npass,
                  uint32_t list_cap, uint32_t sbuf_words, uint32_t part_words, uint32_t nblocks,
-                 uint32_t sync_passes)
+                 uint32_t sync_passes, Epilogue epi)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -684,7 +703,12 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
                     float v = a[i];
                     for (uint32_t off = 32; off >= gw; off >>= 1) v += __shfl_xor(v, (int)off, kWave);
                     const uint32_t b = boff + p * pass_w + i;
-                    if (grp == 0 && b < B) Y[(uint64_t)b * ldy + cc] = v;
+                    if (grp == 0) {
+                        if (epi.yt)
+                            epi.yt[((uint64_t)(b / pass_w) * d.m + cc) * pass_w + (b % pass_w)] =
+                                b < B ? epilogue_apply(epi, v, cc) : 0.0f;
+                        else if (b < B) Y[(uint64_t)b * ldy + cc] = epilogue_apply(epi, v, cc);
+                    }
                 }
             } else if (part_words) {                       // always true here: the host sizes `part` whenever a split can occur
 #pragma unroll
@@ -780,7 +804,7 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
 template <bool SHAC, int NB>
 __global__ void __launch_bounds__(1024)
 dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __restrict__ Y, uint64_t ldy,
-                 uint32_t cpw, uint32_t sbuf_words, uint32_t sum_words, uint32_t nblocks)
+                 uint32_t cpw, uint32_t sbuf_words, uint32_t sum_words, uint32_t nblocks, Epilogue epi)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -898,8 +922,10 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __r
     }
     for (uint32_t j = lane; j < ncols; j += kWave) {
 #pragma unroll
-        for (int i = 0; i < NB; ++i)
-            if ((uint32_t)i < B) Y[(uint64_t)i * ldy + c0 + j] = colsum[j * NB + i];
+        for (int i = 0; i < NB; ++i) {
+            if (epi.yt) epi.yt[(uint64_t)(c0 + j) * NB + i] = (uint32_t)i < B ? epilogue_apply(epi, colsum[j * NB + i], c0 + j) : 0.0f;
+            else if ((uint32_t)i < B) Y[(uint64_t)i * ldy + c0 + j] = epilogue_apply(epi, colsum[j * NB + i], c0 + j);
+        }
     }
     HAC_MARK(5);
     HAC_MARK(6);
@@ -1028,7 +1054,39 @@ DenseRoute dense_route(const hac_desc_t* desc, int64_t B, const hac_launch_t* la
 }
 
 typedef void (*batch_kern_t)(DevBlob, const float*, uint32_t, uint32_t, float*, uint64_t,
-                             uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t);
+                             uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, Epilogue);
+
+// How a layer of a chain is wired (hac_forward); all zero for a plain dot call.
+//   xt_in : the input is already feature-major (written by the layer before): no re-layout
+//   yt_out: write the result feature-major for the layer after (sparse route only)
+//   bias, relu: applied to every finished sum
+struct ChainIO {
+    const float* xt_in;
+    float* yt_out;
+    const float* bias;
+    uint32_t relu;
+};
+
+__global__ void __launch_bounds__(256)
+bias_act_kernel(float* __restrict__ Y, uint32_t B, uint32_t m, uint64_t ldy, const float* __restrict__ bias, uint32_t relu)
+{
+    const uint64_t total = (uint64_t)B * m;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t b = (uint32_t)(i / m), c = (uint32_t)(i - (uint64_t)b * m);
+        float v = Y[(uint64_t)b * ldy + c];
+        if (bias) v += bias[c];
+        if (relu) v = fmaxf(v, 0.0f);
+        Y[(uint64_t)b * ldy + c] = v;
+    }
+}
+
+void launch_bias_act(float* d_Y, uint32_t B, uint32_t m, uint64_t ldy, const float* bias, uint32_t relu, hipStream_t stream)
+{
+    if (!bias && !relu) return;
+    const uint64_t total = (uint64_t)B * m;
+    const uint32_t grid = (uint32_t)std::min<uint64_t>((total + 255) / 256, 4096);
+    hipLaunchKernelGGL(bias_act_kernel, dim3(grid), dim3(256), 0, stream, d_Y, B, m, ldy, bias, relu);
+}
 
 template <bool SHAC>
 batch_kern_t pick_batch_kernel(uint32_t nb, bool multipass)
@@ -1040,14 +1098,19 @@ batch_kern_t pick_batch_kernel(uint32_t nb, bool multipass)
 
 int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
              const float* d_X, int64_t B, int64_t ldx, float* d_Y, int64_t ldy,
-             void* d_ws, size_t ws_bytes, const hac_launch_t* launch, hac_stream_t stream_)
+             void* d_ws, size_t ws_bytes, const hac_launch_t* launch, hac_stream_t stream_,
+             const ChainIO* io = nullptr)
 {
     DevBlob d;
     int rc = make_dev(desc, d_blob, format, d);
     if (rc) return rc;
     if (B < 0 || B > 0x7fffffffll) return HAC_EINVAL;
     if (B == 0) return HAC_OK;
-    if (!d_X || !d_Y || ldx < (int64_t)desc->n || ldy < (int64_t)desc->m) return HAC_EINVAL;
+    const ChainIO none = { nullptr, nullptr, nullptr, 0u };
+    if (!io) io = &none;
+    if (!io->xt_in && (!d_X || ldx < (int64_t)desc->n)) return HAC_EINVAL;
+    if (!io->yt_out && (!d_Y || ldy < (int64_t)desc->m)) return HAC_EINVAL;
+    const Epilogue epi = { io->bias, io->yt_out, io->relu };
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     uint32_t cpw = default_cpw(desc), wpb = 0, list_cap = 0, sbuf_words = 0, pass_w = 32, tile_b = kDefaultTile;
     bool reuse_xt = false, list_kernel = false;
@@ -1078,6 +1141,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     const DenseRoute dr = dense_route(desc, B, launch);
     if (launch && (launch->variant & HAC_LAUNCH_DENSE_ROUTE) && !dr.use) return HAC_EINVAL;   // too many symbols
     if (dr.use) {
+        if (io->xt_in || io->yt_out) return HAC_EINVAL;       // the dense route reads and writes row-major
         if (!d_ws || ws_bytes < dr.bytes) return HAC_EWORKSPACE;
         if (reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
         // 1. all pointers 0, 2. the pointer of every non-zero, 3. tiles on the matrix cores
@@ -1099,11 +1163,14 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(d_ws) + dr.idx_bytes);
         e = hac_internal::launch_index_gemm(d_X, (uint64_t)ldx, (uint32_t)B, d_ws, dr.idx_bits, dr.pitch, d.codebook,
                                             d.k_sym, is_shac, d.n, d.m, d_Y, (uint64_t)ldy, part, stream);
+        if (e != hipSuccess) return hip_fail(e);
+        launch_bias_act(d_Y, (uint32_t)B, d.m, (uint64_t)ldy, io->bias, io->relu, stream);
+        e = hipGetLastError();
         return e == hipSuccess ? HAC_OK : hip_fail(e);
     }
     const BatchShape bs = batch_shape(B, pass_w, tile_b);
-    const float* XT = d_X;                                   // B = 1: X is its own feature-major copy
-    if (B > 1) {
+    const float* XT = io->xt_in ? io->xt_in : d_X;           // B = 1: X is its own feature-major copy
+    if (B > 1 && !io->xt_in) {
         const size_t need = 4ull * d.n * bs.Bp;
         if (!d_ws || ws_bytes < need) return HAC_EWORKSPACE;
         if (reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
@@ -1150,7 +1217,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         if (lds > kLdsLimit) return HAC_EINVAL;
         const uint32_t nblocks = (nwaves + wpb - 1) / wpb;
         const uint32_t grid = (nblocks + 7) / 8 * 8;
-        typedef void (*small_kern_t)(DevBlob, const float*, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t, uint32_t);
+        typedef void (*small_kern_t)(DevBlob, const float*, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t, uint32_t, Epilogue);
         small_kern_t k;
         if (bs.nb == 1) k = shac ? dot_small_kernel<true, 1> : dot_small_kernel<false, 1>;
         else if (bs.nb == 2) k = shac ? dot_small_kernel<true, 2> : dot_small_kernel<false, 2>;
@@ -1161,7 +1228,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
             if (e != hipSuccess) return hip_fail(e);
         }
         hipLaunchKernelGGL(k, dim3(grid), dim3(wpb * kWave), lds, stream,
-                           d, XT, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, sbuf_words, sum_words, nblocks);
+                           d, XT, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, sbuf_words, sum_words, nblocks, epi);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? HAC_OK : hip_fail(e);
     }
@@ -1203,7 +1270,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     }
     hipLaunchKernelGGL(k, dim3(grid), dim3(wpb * kWave), lds, stream,
                        d, XT, bs.Bp, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, bs.gw, bs.npass, list_cap, sbuf_words, part_words, nblocks,
-                       sync_passes);
+                       sync_passes, epi);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? HAC_OK : hip_fail(e);
 }
@@ -1228,11 +1295,13 @@ extern "C" int hac_dot_route(const hac_desc_t* desc, int64_t B, const hac_launch
     return dense_route(desc, B, launch).use ? HAC_ROUTE_DENSE : HAC_ROUTE_SPARSE;
 }
 
-extern "C" int im_dot(const hac_desc_t* desc, const void* d_blob, const float* d_X, int64_t B, int64_t ldx,
-                      float* d_Y, int64_t ldy, void* d_ws, size_t ws_bytes,
-                      const hac_launch_t* launch, hac_stream_t stream)
+namespace {
+
+int im_dot_impl(const hac_desc_t* desc, const void* d_blob, const float* d_X, int64_t B, int64_t ldx,
+                float* d_Y, int64_t ldy, void* d_ws, size_t ws_bytes, hac_stream_t stream,
+                const float* bias, uint32_t relu)
 {
-    if (!desc || !d_blob || launch) return HAC_EINVAL;
+    if (!desc || !d_blob) return HAC_EINVAL;
     if (desc->magic != 0x31434148u || desc->version != 2 || desc->format != HAC_FORMAT_IM) return HAC_EINVAL;
     if (reinterpret_cast<uintptr_t>(d_blob) % 256) return HAC_EINVAL;
     if (desc->n > 0x7fffffffull || desc->m > 0x7fffffffull) return HAC_EINVAL;
@@ -1246,11 +1315,112 @@ extern "C" int im_dot(const hac_desc_t* desc, const void* d_blob, const float* d
     if (need && (!d_ws || ws_bytes < need)) return HAC_EWORKSPACE;
     if (need && reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
     const uint8_t* b = static_cast<const uint8_t*>(d_blob);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
     hipError_t e = hac_internal::launch_index_gemm(d_X, (uint64_t)ldx, (uint32_t)B, b + desc->off_stream, desc->ent_bits,
                                                    desc->idx_pitch, reinterpret_cast<const float*>(b + desc->off_codebook),
                                                    desc->k_sym, 0u, (uint32_t)desc->n, (uint32_t)desc->m, d_Y,
-                                                   (uint64_t)ldy, static_cast<float*>(d_ws), static_cast<hipStream_t>(stream));
+                                                   (uint64_t)ldy, static_cast<float*>(d_ws), hs);
+    if (e != hipSuccess) return hip_fail(e);
+    launch_bias_act(d_Y, (uint32_t)B, (uint32_t)desc->m, (uint64_t)ldy, bias, relu, hs);
+    e = hipGetLastError();
     return e == hipSuccess ? HAC_OK : hip_fail(e);
+}
+
+// ---- chain of layers -------------------------------------------------------------------
+// Between two layers that both take the sparse route the activations stay feature-major (the
+// layout the FMA phase gathers from), so only the chain's input is re-laid out; a layer on the
+// dense route (or an index map) reads and writes row-major.
+struct ChainPlan {
+    uint32_t Bp;
+    size_t act_bytes;            // one activation buffer (there are two)
+    size_t scratch_bytes;        // the largest per-layer workspace
+    bool sparse[256];            // kMaxChain entries
+};
+constexpr uint32_t kMaxChain = 256;
+
+bool layer_sparse(const hac_desc_t* desc, int64_t B)
+{
+    return desc->format != HAC_FORMAT_IM && !dense_route(desc, B, nullptr).use;
+}
+
+int plan_chain(const hac_layer_t* layers, uint32_t L, int64_t B, ChainPlan& P)
+{
+    if (!layers || L < 1 || L > kMaxChain || B < 0 || B > 0x7fffffffll) return HAC_EINVAL;
+    P.Bp = B ? batch_shape(B, 32, kDefaultTile).Bp : 0;
+    P.act_bytes = 0; P.scratch_bytes = 0;
+    for (uint32_t l = 0; l < L; ++l) {
+        const hac_desc_t* d = layers[l].desc;
+        if (!d || !layers[l].d_blob || layers[l].activation > HAC_ACT_RELU || layers[l].reserved) return HAC_EINVAL;
+        if (d->magic != 0x31434148u || d->version != 2) return HAC_EINVAL;
+        if (d->format != HAC_FORMAT_HAC && d->format != HAC_FORMAT_SHAC && d->format != HAC_FORMAT_IM) return HAC_EINVAL;
+        if (d->n < 1 || d->m < 1 || d->n > 0x7fffffffull || d->m > 0x7fffffffull) return HAC_EINVAL;
+        if (l && d->n != layers[l - 1].desc->m) return HAC_EINVAL;
+    }
+    if (!B) return HAC_OK;
+    for (uint32_t l = 0; l < L; ++l) {
+        const hac_desc_t* d = layers[l].desc;
+        P.sparse[l] = layer_sparse(d, B);
+        if (l + 1 < L) P.act_bytes = std::max<size_t>(P.act_bytes, (size_t)4 * P.Bp * (size_t)d->m);
+    }
+    P.act_bytes = (P.act_bytes + 255) / 256 * 256;
+    for (uint32_t l = 0; l < L; ++l) {
+        const bool fed = l && P.sparse[l - 1] && P.sparse[l];        // input arrives feature-major
+        const size_t need = fed ? 0 : hac_workspace_bytes_for(layers[l].desc, B, nullptr);
+        P.scratch_bytes = std::max(P.scratch_bytes, (need + 255) / 256 * 256);
+    }
+    return HAC_OK;
+}
+
+} // namespace
+
+extern "C" int im_dot(const hac_desc_t* desc, const void* d_blob, const float* d_X, int64_t B, int64_t ldx,
+                      float* d_Y, int64_t ldy, void* d_ws, size_t ws_bytes,
+                      const hac_launch_t* launch, hac_stream_t stream)
+{
+    if (launch) return HAC_EINVAL;
+    return im_dot_impl(desc, d_blob, d_X, B, ldx, d_Y, ldy, d_ws, ws_bytes, stream, nullptr, 0u);
+}
+
+extern "C" size_t hac_forward_workspace_bytes(const hac_layer_t* layers, uint32_t n_layers, int64_t B)
+{
+    ChainPlan P;
+    if (plan_chain(layers, n_layers, B, P) != HAC_OK || !B) return 0;
+    return (n_layers > 1 ? 2 * P.act_bytes : 0) + P.scratch_bytes;
+}
+
+extern "C" int hac_forward(const hac_layer_t* layers, uint32_t n_layers, const float* d_X, int64_t B, int64_t ldx,
+                           float* d_Y, int64_t ldy, void* d_ws, size_t ws_bytes, hac_stream_t stream)
+{
+    ChainPlan P;
+    int rc = plan_chain(layers, n_layers, B, P);
+    if (rc) return rc;
+    if (B == 0) return HAC_OK;
+    if (!d_X || !d_Y || ldx < (int64_t)layers[0].desc->n || ldy < (int64_t)layers[n_layers - 1].desc->m) return HAC_EINVAL;
+    const size_t need = (n_layers > 1 ? 2 * P.act_bytes : 0) + P.scratch_bytes;
+    if (need && (!d_ws || ws_bytes < need)) return HAC_EWORKSPACE;
+    if (need && reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
+    uint8_t* ws = static_cast<uint8_t*>(d_ws);
+    float* act[2] = { reinterpret_cast<float*>(ws), reinterpret_cast<float*>(ws + P.act_bytes) };
+    void* scratch = P.scratch_bytes ? ws + (n_layers > 1 ? 2 * P.act_bytes : 0) : nullptr;
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const hac_layer_t& ly = layers[l];
+        const hac_desc_t* d = ly.desc;
+        const bool fed = l && P.sparse[l - 1] && P.sparse[l];
+        const bool feeds = l + 1 < n_layers && P.sparse[l] && P.sparse[l + 1];
+        const float* in = l ? act[(l - 1) & 1] : d_X;
+        const int64_t ld_in = l ? (int64_t)d->n : ldx;
+        float* out = l + 1 < n_layers ? act[l & 1] : d_Y;
+        const int64_t ld_out = l + 1 < n_layers ? (int64_t)d->m : ldy;
+        const uint32_t relu = ly.activation == HAC_ACT_RELU ? 1u : 0u;
+        if (d->format == HAC_FORMAT_IM) {
+            rc = im_dot_impl(d, ly.d_blob, in, B, ld_in, out, ld_out, scratch, P.scratch_bytes, stream, ly.d_bias, relu);
+        } else {
+            const ChainIO io = { fed ? in : nullptr, feeds ? out : nullptr, ly.d_bias, relu };
+            rc = dot_impl(d->format, d, ly.d_blob, in, B, ld_in, out, ld_out, scratch, P.scratch_bytes, nullptr, stream, &io);
+        }
+        if (rc) return rc;
+    }
+    return HAC_OK;
 }
 
 extern "C" size_t hac_workspace_bytes(const hac_desc_t* desc, int64_t B)

@@ -133,6 +133,55 @@ def make_layer(n: int, m: int, sigma: float, prune: float, k: int, quant: str,
     return w
 
 
+def make_network(shapes, sigmas, prunes, k: int, quant: str, seed: int):
+    """Layers pruned one by one (magnitude, fraction prunes[l]) and then weight-shared
+    together: the survivors of all layers are quantized as one set with k representatives,
+    the paper's "unified" quantization (Sect. V-H).  shapes[l] = (n_l, m_l), m_l = n_{l+1}."""
+    rng = np.random.default_rng(seed)
+    raw, keeps = [], []
+    for (n, m), sigma, prune in zip(shapes, sigmas, prunes):
+        w0 = (rng.standard_normal((n, m), dtype=np.float32) * np.float32(sigma)).astype(np.float32)
+        raw.append(w0)
+        keeps.append(prune_magnitude(w0, prune))
+    pooled = np.concatenate([w0[keep] for w0, keep in zip(raw, keeps)])
+    shared = share_uniform(pooled, k) if quant == "uniform" else share_kmeans(pooled, k)
+    if shared.size and np.any(shared == 0.0):
+        raise ValueError("a shared value rounded to 0.0; pick another k or seed")
+    out, at = [], 0
+    for w0, keep in zip(raw, keeps):
+        w = np.zeros(w0.shape, dtype=np.float32)
+        cnt = int(keep.sum())
+        w[keep] = shared[at:at + cnt]
+        at += cnt
+        out.append(w)
+    return out
+
+
+def make_biases(shapes, seed: int):
+    """One fp32 bias vector per layer, N(0, 0.1)."""
+    rng = np.random.default_rng(seed)
+    return [(rng.standard_normal(m, dtype=np.float32) * np.float32(0.1)).astype(np.float32) for _, m in shapes]
+
+
+# Fully connected blocks for the chain of layers.  "vgg19-fc" has the shapes of the matrices the
+# paper times (Sect. V-G: 512x4096, 4096x4096, 4096x10); "vgg16-fc" starts from the graded layer.
+NETWORKS = {
+    "tiny-fc": dict(shapes=((500, 300), (300, 120), (120, 10)), sigmas=(0.05, 0.06, 0.1),
+                    prunes=(0.7, 0.7, 0.5), k=16, quant="uniform", seed=5001),
+    "vgg19-fc": dict(shapes=((512, 4096), (4096, 4096), (4096, 10)), sigmas=(0.03, 0.01, 0.02),
+                     prunes=(0.9, 0.96, 0.8), k=32, quant="uniform", seed=5002),
+    "vgg16-fc": dict(shapes=((25088, 4096), (4096, 4096), (4096, 1000)), sigmas=(0.005, 0.01, 0.02),
+                     prunes=(0.98, 0.96, 0.9), k=32, quant="uniform", seed=5003),
+}
+
+
+def network(name: str):
+    """(layers, biases) of a named fully connected block."""
+    c = NETWORKS[name]
+    return (make_network(c["shapes"], c["sigmas"], c["prunes"], c["k"], c["quant"], c["seed"]),
+            make_biases(c["shapes"], c["seed"] + 1))
+
+
 def make_batch(B: int, n: int, seed: int) -> np.ndarray:
     """ReLU(N(0,1)) fp32 batch, B x n row-major."""
     rng = np.random.default_rng(seed)
