@@ -193,6 +193,40 @@ def extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, iters):
                     "nonzeros_per_s": round(nnz / ms * 1e3, 1),
                     "stream_bits_per_s": round(int(blob.desc.total_bits) / ms * 1e3, 1)})
     out["decode_only"] = dec
+    # a fully connected block as one chain (hac_forward) on a network blob with one shared dictionary,
+    # against the same layers multiplied one call at a time with bias and ReLU as separate passes
+    import workloads
+    Ws, bs = workloads.network("vgg16-fc")
+    fmts = [hac.hac_choose_format(w.shape[0], w.shape[1], int(np.count_nonzero(w)), 32) for w in Ws]
+    nb = hac.hac_net_encode(Ws, fmts)
+    own = [(hac.hac_encode if f == hac.HAC_FORMAT_HAC else hac.shac_encode)(w) for f, w in zip(fmts, Ws)]
+    dls = nb.to_device(dev)
+    dbias = [torch.from_numpy(b).to(dev) for b in bs]
+    relu = [True, True, False]
+    layers = list(zip(dls, dbias, relu))
+    chain = []
+    for B in sorted({c.B for c in calls}):
+        X = torch.from_numpy(workloads.make_batch(B, Ws[0].shape[0], 31)).to(dev)
+        Y = torch.empty((B, Ws[-1].shape[1]), dtype=torch.float32, device=dev)
+        ws = torch.empty(max(hac.hac_forward_workspace_bytes(layers, B), 256), dtype=torch.uint8, device=dev)
+        ms_chain = time_region(torch, lambda i: hac.hac_forward(layers, X, Y=Y, workspace=ws), iters, 5, use_graph, 4)
+        wss = [torch.empty(max(hac.hac_workspace_bytes(dl.desc, B), 256), dtype=torch.uint8, device=dev) for dl in dls]
+        Ys = [torch.empty((B, w.shape[1]), dtype=torch.float32, device=dev) for w in Ws]
+
+        def separate(i):
+            A = X
+            for l, (dl, f) in enumerate(zip(dls, fmts)):
+                (hac.hac_dot if f == hac.HAC_FORMAT_HAC else hac.shac_dot)(dl, A, Y=Ys[l], workspace=wss[l])
+                Ys[l].add_(dbias[l])
+                if relu[l]:
+                    Ys[l].clamp_min_(0.0)
+                A = Ys[l]
+
+        ms_sep = time_region(torch, separate, iters, 5, use_graph, 4)
+        chain.append({"B": B, "chain_ms": round(ms_chain, 5), "one_call_per_layer_ms": round(ms_sep, 5)})
+    out["chain_vgg16_fc"] = {"layers": [list(w.shape) for w in Ws], "formats": fmts,
+                             "network_blob_bytes": nb.nbytes, "separate_blob_bytes": sum(b.nbytes for b in own),
+                             "calls": chain}
     # CPU context on this host
     from oracle import cnative
     import scipy.sparse as sp
