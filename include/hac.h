@@ -339,10 +339,11 @@ int hac_choose_format(int64_t n, int64_t m, uint64_t nnz, uint32_t k);
 /* Encode on the device: W (n x m, row-major, leading dimension ldw >= m) is in
  * device memory and so is the blob that comes out, byte for byte the blob
  * hac_encode / shac_encode (format = HAC_FORMAT_HAC / HAC_FORMAT_SHAC) build on
- * the host with the same options; opts->ri_coding must be HAC_RI_FIELDS.  The
- * value histogram, the code bits and the bit packing run on the GPU; the Huffman
- * code and the prefix sums over columns are made on the host in between, so the
- * call synchronises `stream` (twice) and returns with the blob complete.
+ * the host with the same options (Rice-coded row gaps included).  The value
+ * histogram, the code bits, the gap bits for every Rice parameter and the bit
+ * packing run on the GPU; the Huffman code, the choice of the parameter and the
+ * prefix sums over columns are made on the host in between, so the call
+ * synchronises `stream` (two or three times) and returns with the blob complete.
  * d_ws: hac_encode_dev_workspace_bytes(n, m) bytes, 256-byte aligned.  *desc
  * receives the header.  If d_blob is NULL or blob_capacity < desc->blob_bytes the
  * call returns HAC_EWORKSPACE with desc filled in: allocate desc->blob_bytes

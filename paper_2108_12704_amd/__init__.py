@@ -429,7 +429,7 @@ def shac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=N
 
 
 def hac_encode_dev(W, fmt: int = HAC_FORMAT_HAC, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0,
-                   stream=None) -> DeviceBlob:
+                   ri_coding: int = 0, stream=None) -> DeviceBlob:
     """Encode a device matrix (2-D float32 CUDA tensor, unit column stride) on the device.
 
     Calls the library twice: once to learn the blob's size, once to fill it.  Synchronises the stream.
@@ -441,7 +441,7 @@ def hac_encode_dev(W, fmt: int = HAC_FORMAT_HAC, chunk_nnz: int = 0, ri_bits: in
     n, m = W.shape
     ldw = W.stride(0) if n > 1 else max(m, 1)
     ws = torch.empty(lib.hac_encode_dev_workspace_bytes(n, m), dtype=torch.uint8, device=W.device)
-    opts = Opts(chunk_nnz, ri_bits, lut_bits, 0)
+    opts = Opts(chunk_nnz, ri_bits, lut_bits, ri_coding)
     desc = Desc()
     sh = _stream_handle(stream)
     rc = lib.hac_encode_dev(fmt, W.data_ptr(), n, m, ldw, C.byref(opts), None, 0, C.byref(desc), ws.data_ptr(), ws.numel(), sh)

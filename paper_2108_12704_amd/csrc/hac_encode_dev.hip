@@ -4,16 +4,22 @@
 //
 // The steps of the host encoder, split between device and host:
 //   1. device  histogram of the distinct fp32 values (a hash table keyed by bit pattern, privatised
-//              in LDS per block) and the number of non-zeros of every (row segment, column);
-//   2. host    alphabet in value order, Huffman lengths, canonical code, decode tables;
-//   3. device  code bits and last non-zero row of every (row segment, column);
-//   4. host    prefix sums along each column: first stream bit / CSC position of every segment and
-//              column, where the non-zero before a segment ended, chunk counts, section offsets;
+//              in LDS per block), and the number of non-zeros and the last non-zero row of every
+//              (row segment, column);
+//   2. host    alphabet in value order, Huffman lengths, canonical code, decode tables; the row
+//              after the last non-zero above every segment;
+//   3. device  code bits of every (row segment, column); with Rice-coded row gaps also the gap
+//              bits for every parameter k = 0..15, per (segment, column) and in total;
+//   4. host    the Rice parameter; prefix sums along each column: first stream bit / CSC position
+//              of every segment and column, where the non-zero before a segment ended, chunk
+//              counts, section offsets;
 //   5. device  one thread per (row segment, column) walks its rows and writes codewords (and
-//              row-index fields) with atomic ORs into the zeroed stream, and the chunk entries.
+//              row-index fields or gap codewords) with atomic ORs into the zeroed stream, and the
+//              chunk entries.
 // A thread owns one column of a segment of 1024 rows, so the 64 lanes of a wave read 64
 // neighbouring columns of one row: coalesced reads of the row-major matrix in all three passes.
-// The call synchronises the stream twice (steps 2 and 4 need the device's results).
+// The call synchronises the stream twice (steps 2 and 4 need the device's results), three times
+// with Rice-coded gaps.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -61,20 +67,20 @@ __device__ void table_add(uint32_t* keys, uint32_t* cnts, uint32_t* flags, uint3
 // step 1
 __global__ void __launch_bounds__(256)
 enc_scan_kernel(const float* __restrict__ W, uint32_t n, uint32_t m, uint64_t ldw,
-                uint32_t* keys, uint32_t* cnts, uint32_t* seg_nnz, uint32_t* flags)
+                uint32_t* keys, uint32_t* cnts, uint32_t* seg_nnz, uint32_t* seg_last, uint32_t* flags)
 {
     __shared__ uint32_t lk[kLocalSlots], lc[kLocalSlots];
     for (uint32_t i = threadIdx.x; i < kLocalSlots; i += 256) { lk[i] = 0u; lc[i] = 0u; }
     __syncthreads();
     const uint32_t j = blockIdx.x * 256 + threadIdx.x, seg = blockIdx.y;
     const uint32_t r0 = seg * kSegRows, r1 = r0 + kSegRows < n ? r0 + kSegRows : n;
-    uint32_t count = 0;
+    uint32_t count = 0, last = 0xffffffffu;
     if (j < m) {
         for (uint32_t r = r0; r < r1; ++r) {
             const float v = W[(uint64_t)r * ldw + j];
             if (v == 0.0f) continue;                                 // +0.0 and -0.0 are the null entry
             if (!isfinite(v)) { atomicOr(flags, kFlagNonFinite); continue; }
-            ++count;
+            ++count; last = r;
             const uint32_t key = __float_as_uint(v);
             uint32_t h = mix32(key) & (kLocalSlots - 1);
             bool done = false;
@@ -86,6 +92,7 @@ enc_scan_kernel(const float* __restrict__ W, uint32_t n, uint32_t m, uint64_t ld
             if (!done) table_add(keys, cnts, flags, key, 1u);        // the block's table is crowded
         }
         seg_nnz[(uint64_t)seg * m + j] = count;
+        seg_last[(uint64_t)seg * m + j] = last;
     }
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < kLocalSlots; i += 256)
@@ -103,24 +110,51 @@ __device__ __forceinline__ uint32_t symbol_of(const uint32_t* __restrict__ keys,
     return 0u;
 }
 
-// step 3
+__device__ __forceinline__ uint32_t rice_len(uint32_t d, uint32_t k)
+{
+    const uint32_t q = d >> k;
+    return q < kRiceEscape ? q + 1 + k : kRiceEscape + 1 + 32;
+}
+
+// step 3.  gap_bits (Rice-coded gaps only, else nullptr): [k][segment][column] bits of the gap
+// codewords for k = 0..15; gap_total: their 16 sums over the matrix.
 __global__ void __launch_bounds__(256)
 enc_bits_kernel(const float* __restrict__ W, uint32_t n, uint32_t m, uint64_t ldw,
                 const uint32_t* __restrict__ keys, const uint32_t* __restrict__ slot_sym,
-                const uint8_t* __restrict__ lens, uint32_t* seg_codebits, uint32_t* seg_last)
+                const uint8_t* __restrict__ lens, uint32_t* seg_codebits,
+                const uint32_t* __restrict__ seg_prev_row1, uint32_t* gap_bits, unsigned long long* gap_total,
+                uint64_t seg_cols)
 {
     const uint32_t j = blockIdx.x * 256 + threadIdx.x, seg = blockIdx.y;
-    if (j >= m) return;
     const uint32_t r0 = seg * kSegRows, r1 = r0 + kSegRows < n ? r0 + kSegRows : n;
-    uint32_t bits = 0, last = 0xffffffffu;
-    for (uint32_t r = r0; r < r1; ++r) {
-        const float v = W[(uint64_t)r * ldw + j];
-        if (v == 0.0f) continue;
-        bits += lens[symbol_of(keys, slot_sym, __float_as_uint(v))];
-        last = r;
+    const uint64_t at = (uint64_t)seg * m + j;
+    uint32_t bits = 0;
+    uint32_t g[kRiceKMax + 1];
+#pragma unroll
+    for (uint32_t k = 0; k <= kRiceKMax; ++k) g[k] = 0;
+    if (j < m) {
+        uint32_t next = gap_bits ? seg_prev_row1[at] : 0u;           // the row the next gap counts from
+        for (uint32_t r = r0; r < r1; ++r) {
+            const float v = W[(uint64_t)r * ldw + j];
+            if (v == 0.0f) continue;
+            bits += lens[symbol_of(keys, slot_sym, __float_as_uint(v))];
+            if (gap_bits) {
+                const uint32_t d = r - next;
+#pragma unroll
+                for (uint32_t k = 0; k <= kRiceKMax; ++k) g[k] += rice_len(d, k);
+                next = r + 1;
+            }
+        }
+        seg_codebits[at] = bits;
     }
-    seg_codebits[(uint64_t)seg * m + j] = bits;
-    seg_last[(uint64_t)seg * m + j] = last;
+    if (!gap_bits) return;
+#pragma unroll
+    for (uint32_t k = 0; k <= kRiceKMax; ++k) {
+        if (j < m) gap_bits[(uint64_t)k * seg_cols + at] = g[k];
+        unsigned long long t = g[k];                                  // lanes past m hold 0
+        for (int off = 32; off >= 1; off >>= 1) t += __shfl_down(t, off, 64);
+        if ((threadIdx.x & 63) == 0 && t) atomicAdd(&gap_total[k], t);
+    }
 }
 
 // `len` bits of `code` (right-justified), MSB first, at stream bit `bit`; the words start zeroed
@@ -141,6 +175,7 @@ struct EmitArgs {
     const uint32_t* col_bit; const uint32_t* col_pos; const uint32_t* col_chunk;
     uint32_t* stream; void* ent; uint32_t* ri;
     uint32_t shac, has_zero, zcode, zlen, chunk, ent_bits, row_bits, ri_bits;
+    uint32_t rice, rice_k;                                              // sHAC with Rice-coded gaps in the stream
 };
 
 // step 5
@@ -168,7 +203,12 @@ __global__ void __launch_bounds__(256) enc_emit_kernel(EmitArgs a)
         const uint32_t q = pos - cpos0;
         if (q % a.chunk == 0) {
             const uint32_t g = cchunk0 + q / a.chunk;
-            if (a.shac) {
+            if (a.rice) {
+                // the chunk starts at its first gap codeword; the gap counts from the row after the non-zero before
+                const uint32_t rel = bit - cbit0;
+                if (a.ent_bits == 32) static_cast<uint32_t*>(a.ent)[g] = (rel << a.row_bits) | prow;
+                else { static_cast<uint32_t*>(a.ent)[2 * (uint64_t)g] = prow; static_cast<uint32_t*>(a.ent)[2 * (uint64_t)g + 1] = rel; }
+            } else if (a.shac) {
                 const uint32_t rel = bit - cbit0;
                 if (a.ent_bits == 16) static_cast<uint16_t*>(a.ent)[g] = (uint16_t)rel;
                 else static_cast<uint32_t*>(a.ent)[g] = rel;
@@ -178,17 +218,28 @@ __global__ void __launch_bounds__(256) enc_emit_kernel(EmitArgs a)
                 else { static_cast<uint32_t*>(a.ent)[2 * (uint64_t)g] = prow; static_cast<uint32_t*>(a.ent)[2 * (uint64_t)g + 1] = rel; }
             }
         }
+        if (a.rice) {
+            const uint32_t d = r - prow, k = a.rice_k, qq = d >> k;
+            if (qq < kRiceEscape) {
+                put_bits(a.stream, (uint64_t)bit + qq, (1u << k) | (d & ((1u << k) - 1u)), k + 1);
+                bit += qq + 1 + k;
+            } else {
+                put_bits(a.stream, (uint64_t)bit + kRiceEscape, 1u, 1);
+                put_bits(a.stream, (uint64_t)bit + kRiceEscape + 1, d, 32);
+                bit += kRiceEscape + 1 + 32;
+            }
+        }
         put_bits(a.stream, bit, a.codes[sym], len);
         bit += len;
         pend = bit; prow = r + 1;
-        if (a.shac) put_bits(a.ri, (uint64_t)pos * a.ri_bits, r, a.ri_bits);
+        if (a.shac && !a.rice) put_bits(a.ri, (uint64_t)pos * a.ri_bits, r, a.ri_bits);
         ++pos;
     }
 }
 
 struct WsLayout {
     size_t keys, cnts, flags, seg_nnz, seg_codebits, seg_last, seg_bit0, seg_pos0, seg_prev_end, seg_prev_row1,
-           slot_sym, codes, lens, total;
+           slot_sym, codes, lens, gap_bits, total;
 };
 
 WsLayout ws_layout(uint64_t n, uint64_t m)
@@ -201,6 +252,7 @@ WsLayout ws_layout(uint64_t n, uint64_t m)
     L.seg_nnz = take(4 * S * m); L.seg_codebits = take(4 * S * m); L.seg_last = take(4 * S * m);
     L.seg_bit0 = take(4 * S * m); L.seg_pos0 = take(4 * S * m); L.seg_prev_end = take(4 * S * m); L.seg_prev_row1 = take(4 * S * m);
     L.slot_sym = take(4ull * kHashSlots); L.codes = take(4ull * 65537); L.lens = take(65537);
+    L.gap_bits = take(4 * S * m * (kRiceKMax + 1));                  // used with Rice-coded gaps only
     L.total = c;
     return L;
 }
@@ -226,11 +278,12 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
     if ((n + kSegRows - 1) / kSegRows > 65535) return HAC_ERANGE;     // one grid row per segment of 1024 rows
     int rc = check_opts(opts);
     if (rc) return rc;
-    if (opts && opts->ri_coding) return HAC_EINVAL;                   // Rice-coded gaps: host encoder only
     const bool shac = format == HAC_FORMAT_SHAC;
+    const bool rice = opts && opts->ri_coding == HAC_RI_RICE;
+    if (rice && (!shac || opts->ri_bits)) return HAC_EINVAL;          // as the host encoders
     const uint32_t need_bits = std::max<uint32_t>(ceil_log2((uint64_t)n), 1);
     uint32_t ri_bits = 0;
-    if (shac) {
+    if (shac && !rice) {
         ri_bits = opts && opts->ri_bits ? opts->ri_bits : need_bits;
         if (ri_bits < need_bits || ri_bits > 32) return HAC_EINVAL;
     }
@@ -249,14 +302,15 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         // ---- step 1 ----
         hipLaunchKernelGGL(fill_zero_kernel, dim3(512), dim3(256), 0, stream, dptr(L.keys), (uint64_t)(L.seg_nnz - L.keys) / 4);
         hipLaunchKernelGGL(enc_scan_kernel, grid, dim3(256), 0, stream, d_W, (uint32_t)n, (uint32_t)m, (uint64_t)ldw,
-                           dptr(L.keys), dptr(L.cnts), dptr(L.seg_nnz), dptr(L.flags));
+                           dptr(L.keys), dptr(L.cnts), dptr(L.seg_nnz), dptr(L.seg_last), dptr(L.flags));
         if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
-        std::vector<uint32_t> keys(kHashSlots), cnts(kHashSlots), seg_nnz(SM);
+        std::vector<uint32_t> keys(kHashSlots), cnts(kHashSlots), seg_nnz(SM), seg_last(SM);
         uint32_t flags = 0;
         if ((e = hipMemcpyAsync(keys.data(), dptr(L.keys), 4ull * kHashSlots, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
         if ((e = hipMemcpyAsync(cnts.data(), dptr(L.cnts), 4ull * kHashSlots, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
         if ((e = hipMemcpyAsync(&flags, dptr(L.flags), 4, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
         if ((e = hipMemcpyAsync(seg_nnz.data(), dptr(L.seg_nnz), 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(seg_last.data(), dptr(L.seg_last), 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
         if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
         if (flags & kFlagNonFinite) return HAC_EINVAL;
         if (flags & kFlagTableFull) return HAC_ERANGE;
@@ -296,14 +350,41 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         if ((e = hipMemcpyAsync(dptr(L.slot_sym), slot_sym.data(), 4ull * kHashSlots, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
         if (!nz_len.empty() && (e = hipMemcpyAsync(ws + L.lens, nz_len.data(), nz_len.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
 
+        // the row after the last non-zero above every segment (0 at a column's top)
+        std::vector<uint32_t> seg_prev_row1(SM);
+        for (int64_t j = 0; j < m; ++j) {
+            uint32_t prev_row1 = 0;
+            for (uint32_t s = 0; s < S; ++s) {
+                const size_t at = (size_t)s * m + j;
+                seg_prev_row1[at] = prev_row1;
+                if (seg_nnz[at]) prev_row1 = seg_last[at] + 1;
+            }
+        }
+        if ((e = hipMemcpyAsync(dptr(L.seg_prev_row1), seg_prev_row1.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+
         // ---- step 3 ----
+        unsigned long long* d_gap_total = reinterpret_cast<unsigned long long*>(ws + L.flags + 64);   // zeroed with the flags
         hipLaunchKernelGGL(enc_bits_kernel, grid, dim3(256), 0, stream, d_W, (uint32_t)n, (uint32_t)m, (uint64_t)ldw,
-                           dptr(L.keys), dptr(L.slot_sym), ws + L.lens, dptr(L.seg_codebits), dptr(L.seg_last));
+                           dptr(L.keys), dptr(L.slot_sym), ws + L.lens, dptr(L.seg_codebits), dptr(L.seg_prev_row1),
+                           rice ? dptr(L.gap_bits) : static_cast<uint32_t*>(nullptr), d_gap_total, (uint64_t)SM);
         if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
-        std::vector<uint32_t> seg_codebits(SM), seg_last(SM);
+        std::vector<uint32_t> seg_codebits(SM), seg_gapbits;
+        unsigned long long gap_total[kRiceKMax + 1] = { 0 };
         if ((e = hipMemcpyAsync(seg_codebits.data(), dptr(L.seg_codebits), 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(seg_last.data(), dptr(L.seg_last), 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if (rice && (e = hipMemcpyAsync(gap_total, d_gap_total, sizeof gap_total, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
         if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
+        // the Rice parameter: fewest gap bits, the smaller k on ties
+        uint32_t rice_k = 0; uint64_t gap_bits = 0;
+        if (rice) {
+            gap_bits = ~0ull;
+            for (uint32_t k = 0; k <= kRiceKMax; ++k) if (gap_total[k] < gap_bits) { gap_bits = gap_total[k]; rice_k = k; }
+            if (nnz == 0) { gap_bits = 0; rice_k = 0; }
+            seg_gapbits.resize(SM);
+            if ((e = hipMemcpyAsync(seg_gapbits.data(), dptr(L.gap_bits) + (size_t)rice_k * SM, 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+            if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
+            total_bits += gap_bits;
+            if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
+        }
 
         // ---- step 4 ----
         uint64_t max_col_nnz = 0;
@@ -313,23 +394,22 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         for (int64_t j = 0; j < m; ++j) max_col_nnz = std::max(max_col_nnz, col_nnz[(size_t)j]);
         const uint32_t Cn = pick_chunk(opts, max_col_nnz);
         std::vector<uint32_t> col_bit((size_t)m + 1), col_pos((size_t)m + 1), col_chunk((size_t)m + 1);
-        std::vector<uint32_t> seg_bit0(SM), seg_pos0(SM), seg_prev_end(SM), seg_prev_row1(SM);
+        std::vector<uint32_t> seg_bit0(SM), seg_pos0(SM), seg_prev_end(SM);
         uint64_t bit = 0, pos = 0, chunks = 0, max_col_bits = 0;
         for (int64_t j = 0; j < m; ++j) {
             col_bit[(size_t)j] = (uint32_t)bit; col_pos[(size_t)j] = (uint32_t)pos; col_chunk[(size_t)j] = (uint32_t)chunks;
             const uint64_t bit_j = bit;
-            uint64_t prev_end = bit, prev_row1 = 0;
+            uint64_t prev_end = bit;
             for (uint32_t s = 0; s < S; ++s) {
                 const size_t at = (size_t)s * m + j;
                 const uint64_t r0 = (uint64_t)s * kSegRows, r1 = std::min<uint64_t>(r0 + kSegRows, (uint64_t)n);
                 seg_bit0[at] = (uint32_t)bit; seg_pos0[at] = (uint32_t)pos;
-                seg_prev_end[at] = (uint32_t)prev_end; seg_prev_row1[at] = (uint32_t)prev_row1;
+                seg_prev_end[at] = (uint32_t)prev_end;
                 const uint64_t cnt = seg_nnz[at];
-                const uint64_t seg_bits = seg_codebits[at] + (shac ? 0 : (r1 - r0 - cnt) * zlen);
+                const uint64_t seg_bits = seg_codebits[at] + (shac ? 0 : (r1 - r0 - cnt) * zlen) + (rice ? seg_gapbits[at] : 0);
                 if (cnt) {
                     const uint64_t trailing = r1 - 1 - seg_last[at];                 // zeros after the segment's last non-zero
                     prev_end = bit + seg_bits - (shac ? 0 : trailing * zlen);
-                    prev_row1 = (uint64_t)seg_last[at] + 1;
                 }
                 bit += seg_bits; pos += cnt;
             }
@@ -346,7 +426,12 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         d.n = (uint64_t)n; d.m = (uint64_t)m; d.nnz = nnz; d.total_bits = total_bits; d.n_words = (total_bits + 31) / 32;
         d.k_sym = (uint32_t)codebook.size(); d.lmax = lmax; d.lut_bits = lut_bits;
         d.chunk = Cn; d.n_chunks = chunks; d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
-        if (shac) {
+        if (rice) {
+            const uint32_t brel_bits = std::max<uint32_t>(ceil_log2(max_col_bits + 1), 1);
+            d.ent_bits = need_bits + brel_bits <= 32 ? 32 : 64;
+            d.row_bits = d.ent_bits == 32 ? need_bits : 0;
+            d.ri_coding = HAC_RI_RICE; d.rice_k = rice_k; d.gap_bits = gap_bits;
+        } else if (shac) {
             d.ri_bits = ri_bits;
             d.ent_bits = max_col_bits < 65536 ? 16 : 32;
             if (nnz * (uint64_t)ri_bits > 0xfffffff0ull * 32ull) return HAC_ERANGE;
@@ -376,7 +461,6 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         if ((e = hipMemcpyAsync(dptr(L.seg_bit0), seg_bit0.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
         if ((e = hipMemcpyAsync(dptr(L.seg_pos0), seg_pos0.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
         if ((e = hipMemcpyAsync(dptr(L.seg_prev_end), seg_prev_end.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(dptr(L.seg_prev_row1), seg_prev_row1.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
         // step 5 looks codes and lengths up by symbol
         if (!t.code.empty() && (e = hipMemcpyAsync(dptr(L.codes), t.code.data(), 4 * t.code.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
         if (!len.empty() && (e = hipMemcpyAsync(ws + L.lens, len.data(), len.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
@@ -391,7 +475,8 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         a.col_chunk = reinterpret_cast<const uint32_t*>(blob + d.off_col_chunk);
         a.stream = reinterpret_cast<uint32_t*>(blob + d.off_stream);
         a.ent = blob + d.off_chunk_ent;
-        a.ri = shac ? reinterpret_cast<uint32_t*>(blob + d.off_ri) : nullptr;
+        a.ri = (shac && !rice) ? reinterpret_cast<uint32_t*>(blob + d.off_ri) : nullptr;
+        a.rice = rice ? 1u : 0u; a.rice_k = rice_k;
         a.shac = shac ? 1u : 0u; a.has_zero = has_zero ? 1u : 0u; a.zcode = zcode; a.zlen = zlen;
         a.chunk = Cn; a.ent_bits = d.ent_bits; a.row_bits = d.row_bits; a.ri_bits = ri_bits;
         hipLaunchKernelGGL(enc_emit_kernel, grid, dim3(256), 0, stream, a);

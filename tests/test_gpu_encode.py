@@ -57,6 +57,18 @@ def test_device_blob_equals_host_blob(hac, name, W):
     sb = hac.hac_encode_dev(Wd, hac.HAC_FORMAT_SHAC, ri_bits=32)
     torch.cuda.synchronize()
     assert np.array_equal(sb.tensor.cpu().numpy(), hac.shac_encode(W, ri_bits=32).data)
+    # sHAC with Rice-coded row gaps: the parameter k, the gap bits and every byte as on the host
+    for kw in (dict(), dict(chunk_nnz=5)):
+        print(f"[case] encode_dev {name} {W.shape} rice {kw}", flush=True)
+        host = hac.shac_encode(W, ri_coding=hac.RI_RICE, **kw)
+        gb = hac.hac_encode_dev(Wd, hac.HAC_FORMAT_SHAC, ri_coding=hac.RI_RICE, **kw)
+        torch.cuda.synchronize()
+        assert (gb.desc.rice_k, gb.desc.gap_bits) == (host.desc.rice_k, host.desc.gap_bits)
+        assert bytes(gb.desc) == bytes(host.desc)
+        got = gb.tensor.cpu().numpy()
+        if not np.array_equal(got, host.data):
+            diff = np.flatnonzero(got != host.data)
+            raise AssertionError(f"{name} rice {kw}: {diff.size} bytes differ, first at {int(diff[0])}")
 
 
 def test_device_blob_decodes_to_the_oracle_symbols_and_multiplies(hac):
@@ -96,7 +108,9 @@ def test_strided_matrix_and_argument_checks(hac):
     n, m = 300, 90
     ws = torch.empty(lib.hac_encode_dev_workspace_bytes(n, m), dtype=torch.uint8, device=dev())
     desc = hac.Desc()
-    rice = hac.Opts(0, 0, 0, hac.RI_RICE)
+    rice = hac.Opts(0, 0, 0, hac.RI_RICE)                                          # gaps belong to sHAC, and exclude ri_bits
+    assert lib.hac_encode_dev(1, Wbig.data_ptr(), n, m, m, C.byref(rice), None, 0, C.byref(desc), ws.data_ptr(), ws.numel(), None) == -1
+    rice.ri_bits = 12
     assert lib.hac_encode_dev(2, Wbig.data_ptr(), n, m, m, C.byref(rice), None, 0, C.byref(desc), ws.data_ptr(), ws.numel(), None) == -1
     assert lib.hac_encode_dev(7, Wbig.data_ptr(), n, m, m, None, None, 0, C.byref(desc), ws.data_ptr(), ws.numel(), None) == -1
     assert lib.hac_encode_dev(1, Wbig.data_ptr(), n, m, m, None, None, 0, C.byref(desc), ws.data_ptr(), 1024, None) == -6
