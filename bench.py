@@ -227,6 +227,29 @@ def extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, iters):
     out["chain_vgg16_fc"] = {"layers": [list(w.shape) for w in Ws], "formats": fmts,
                              "network_blob_bytes": nb.nbytes, "separate_blob_bytes": sum(b.nbytes for b in own),
                              "calls": chain}
+    # GPU context: the same product with W decompressed to dense fp32 (torch.matmul, the vendor's
+    # GEMM) and as an uncompressed CSR matrix (torch.sparse, the vendor's SpMM); neither is the
+    # paper's method, both need W in HBM at 4 bytes (dense) or 8 bytes (CSR) per stored entry
+    Wd = torch.from_numpy(W).to(dev)
+    gpu_ctx = {"dense_bytes": int(W.size * 4), "csr_bytes": int(np.count_nonzero(W)) * 8 + 4 * (W.shape[0] + 1), "calls": []}
+    try:
+        Wt_csr = Wd.t().contiguous().to_sparse_csr()                  # Y^T = W^T . X^T
+    except Exception:                                                 # sparse CSR unavailable in this build
+        Wt_csr = None
+    for B in sorted({c.B for c in calls}):
+        X = torch.from_numpy(Xhost[:B]).to(dev)
+        Yd = torch.empty((B, W.shape[1]), dtype=torch.float32, device=dev)
+        ms_dense = time_region(torch, lambda i: torch.matmul(X, Wd, out=Yd), 20, 3, False, 1)
+        row = {"B": B, "dense_fp32_matmul_ms": round(ms_dense, 4)}
+        if Wt_csr is not None:
+            try:
+                Xt = X.t().contiguous()
+                row["csr_spmm_ms"] = round(time_region(torch, lambda i: torch.sparse.mm(Wt_csr, Xt), 20, 3, False, 1), 4)
+            except Exception:
+                row["csr_spmm_ms"] = None
+        gpu_ctx["calls"].append(row)
+    out["gpu_context"] = gpu_ctx
+    del Wd, Wt_csr
     # CPU context on this host
     from oracle import cnative
     import scipy.sparse as sp
