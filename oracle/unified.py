@@ -23,13 +23,25 @@ The paper does not say what is pooled when HAC and sHAC layers are mixed; the
 reading above makes the shared code optimal for the concatenation of all the
 streams that are written with it.
 
+Index-map layers (the hybrid of Sect. V-K: index map for the convolutional part,
+HAC / sHAC for the fully connected part, "sharing the same representatives"):
+an index-map layer (Sect. III-C1) writes no codewords, so it adds nothing to the
+pooled source; its pointers index the network's one value list, which is the
+shared alphabet followed by the values that occur in index-map layers only
+(0.0 first if it is one of them, then ascending).  A pointer takes 8 bits when
+the list has at most 256 entries, else 16.  Size: bbar*n*m per index-map layer,
+and b bits per extra value (they are in no dictionary, only in the value vector,
+as in the paper's index-map accounting).
+
 Chain of layers (not in the paper, which gives the product of one layer only):
 X_0 = X,  X_{l+1} = act_l(X_l . W_l + b_l)  with act_l the identity or
 max(., 0), b_l an optional row vector; evaluated in fp64.  `chain_bound`
 propagates the element-wise error a path may make when each of its products is
 within rel * (|X|.|W|) of the exact one.
 
-Pins (tests/test_oracle_unified.py): a two-layer example worked by hand,
+Pins (tests/test_oracle_unified.py): index-map layers reduce to oracle.indexmap
+when alone, point below the list's length, decode to W, leave the code of the
+other layers untouched, and cost bbar*n*m + b per extra value; a two-layer example worked by hand,
 pooled counts against a direct count, optimality of the shared code for the
 pooled source and sub-optimality per layer (never shorter than the layer's own
 code, equal when the layers have proportional histograms), bit-exact round
@@ -47,6 +59,7 @@ import numpy as np
 
 from . import formats, huffman
 from .formats import HAC, SHAC, WORD_BITS
+from .indexmap import IndexMap
 
 
 @dataclass
@@ -54,8 +67,15 @@ class Unified:
     values: np.ndarray            # shared fp32 alphabet
     freqs: np.ndarray             # pooled counts
     code: huffman.HuffmanCode     # the one code
-    kinds: List[str]              # "hac" / "shac" per layer
-    layers: list                  # HAC / SHAC structures whose values/code are the shared ones
+    kinds: List[str]              # "hac" / "shac" / "im" per layer
+    layers: list                  # HAC / SHAC structures whose values/code are the shared ones; IndexMap
+    extras: np.ndarray = None     # values that occur in index-map layers only
+
+    @property
+    def value_list(self) -> np.ndarray:
+        if self.extras is None or self.extras.size == 0:
+            return self.values
+        return np.concatenate([self.values, self.extras]).astype(np.float32)
 
 
 def layer_source(kind: str, W: np.ndarray) -> np.ndarray:
@@ -65,7 +85,9 @@ def layer_source(kind: str, W: np.ndarray) -> np.ndarray:
         return formats.column_order(W)
     if kind == "shac":
         return formats.csc_arrays(W)[0]
-    raise ValueError("kind must be 'hac' or 'shac'")
+    if kind == "im":
+        return np.zeros(0, dtype=np.float32)         # pointers, no codewords
+    raise ValueError("kind must be 'hac', 'shac' or 'im'")
 
 
 def pooled_alphabet(kinds: Sequence[str], Ws: Sequence[np.ndarray]) -> Tuple[np.ndarray, np.ndarray]:
@@ -80,11 +102,27 @@ def unified_encode(kinds: Sequence[str], Ws: Sequence[np.ndarray], reference_pac
     values, freqs = pooled_alphabet(kinds, Ws)
     code = huffman.build(freqs.tolist())
     packer = formats.pack_stream_reference if reference_packer else formats.pack_stream
+    # values of index-map layers that no stream holds: appended to the list, 0.0 first, then ascending
+    im_vals = [np.unique(huffman.normalise_values(W)) for kind, W in zip(kinds, Ws) if kind == "im"]
+    extras = np.zeros(0, dtype=np.float32)
+    if im_vals:
+        cand = np.unique(np.concatenate(im_vals))
+        cand = cand[~np.isin(cand, values)]
+        extras = np.concatenate([cand[cand == 0], cand[cand != 0]]).astype(np.float32)
+    value_list = np.concatenate([values, extras]).astype(np.float32)
+    if value_list.size > 65536 and im_vals:
+        raise ValueError("more than 65536 values for 16-bit pointers")
+    bbar = 8 if value_list.size <= 256 else 16
     layers = []
     for kind, W in zip(kinds, Ws):
         W = huffman.normalise_values(W)
         n, m = W.shape
-        if kind == "hac":
+        if kind == "im":
+            pi = np.empty((n, m), dtype=np.uint8 if bbar == 8 else np.uint16)
+            for idx, v in enumerate(value_list):
+                pi[W == v] = idx
+            layers.append(IndexMap(n=n, m=m, c=value_list, pi=pi, bbar=bbar))
+        elif kind == "hac":
             sym = formats.symbol_indices(formats.column_order(W), values)
             words, nbits = packer(sym, code)
             layers.append(HAC(n, m, values, freqs, code, words, nbits))
@@ -93,19 +131,23 @@ def unified_encode(kinds: Sequence[str], Ws: Sequence[np.ndarray], reference_pac
             sym = formats.symbol_indices(nz, values)
             words, nbits = packer(sym, code)
             layers.append(SHAC(n, m, values, freqs, code, words, nbits, ri, cb))
-    return Unified(values, freqs, code, list(kinds), layers)
+    return Unified(values, freqs, code, list(kinds), layers, extras)
 
 
 def unified_decode(u: Unified, layer: int) -> np.ndarray:
     s = u.layers[layer]
+    if u.kinds[layer] == "im":
+        return s.c[s.pi.astype(np.int64)]
     return formats.hac_decode(s) if u.kinds[layer] == "hac" else formats.shac_decode(s)
 
 
 def unified_paper_bits(u: Unified, b: int = WORD_BITS) -> int:
     """Stored size with the dictionaries counted once."""
-    total = 6 * len(u.values) * b
+    total = 6 * len(u.values) * b + (0 if u.extras is None else len(u.extras)) * b
     for kind, s in zip(u.kinds, u.layers):
-        if kind == "hac":
+        if kind == "im":
+            total += s.bbar * s.n * s.m
+        elif kind == "hac":
             total += s.N * b
         else:
             total += s.N1 * b + b * (s.q + s.m + 1)
@@ -115,8 +157,11 @@ def unified_paper_bits(u: Unified, b: int = WORD_BITS) -> int:
 def separate_paper_bits(kinds: Sequence[str], Ws: Sequence[np.ndarray], b: int = WORD_BITS) -> int:
     """Stored size when every layer keeps a code and dictionaries of its own."""
     total = 0
+    from . import indexmap
     for kind, W in zip(kinds, Ws):
-        if kind == "hac":
+        if kind == "im":
+            total += indexmap.im_bits(indexmap.im_encode(W), b)
+        elif kind == "hac":
             total += formats.hac_paper_bits(formats.hac_encode(W), b)
         else:
             total += formats.shac_paper_bits(formats.shac_encode(W), b)

@@ -120,6 +120,46 @@ def test_dictionary_counted_once():
     assert unified_words >= separate_words - len(Ws)      # rounding to whole words per layer
 
 
+def test_index_map_layers_share_the_value_list():
+    from oracle import indexmap
+    rng = np.random.default_rng(12)
+    Ws = small_layers(seed=41, shapes=((30, 20), (20, 16), (16, 9)), k=6, prune=0.6)
+    conv = rng.choice(np.array([-0.75, -0.1, 0.3, 0.9, Ws[0][Ws[0] != 0][0]], dtype=np.float32), size=(27, 30))  # unpruned, one value shared
+    kinds = ["im", "hac", "shac", "hac"]
+    layers = [conv] + Ws
+    u = unified.unified_encode(kinds, layers)
+    # the code and the streams are those of the network without the index-map layer
+    u0 = unified.unified_encode(kinds[1:], Ws)
+    assert np.array_equal(u.values, u0.values) and np.array_equal(u.freqs, u0.freqs)
+    assert u.code.lengths == u0.code.lengths
+    for a, b in zip(u.layers[1:], u0.layers):
+        assert np.array_equal(a.words, b.words)
+    # extras: exactly the values no stream holds, ascending, appended after the alphabet
+    assert u.extras.tolist() == sorted(set(np.unique(conv).tolist()) - set(u.values.tolist()))
+    assert len(u.extras) == 4 and u.value_list.size == u.values.size + 4
+    im = u.layers[0]
+    assert im.bbar == 8 and int(im.pi.max()) < u.value_list.size
+    assert np.array_equal(unified.unified_decode(u, 0), conv)
+    assert np.array_equal(u.value_list[im.pi.astype(np.int64)], conv)
+    x = rng.normal(size=(3, 27))
+    assert np.allclose(indexmap.dot_im(im, x), x @ conv.astype(np.float64), rtol=0, atol=1e-12)
+    # size: the other layers as before, bbar*n*m for the map, b per extra value
+    assert unified.unified_paper_bits(u) == unified.unified_paper_bits(u0) + 8 * conv.size + 32 * 4
+    # an extra 0.0 goes first among the extras; more than 256 values need 16-bit pointers
+    convz = conv.copy(); convz[0, 0] = 0.0
+    uz = unified.unified_encode(["im", "shac"], [convz, Ws[1]])
+    assert uz.extras[0] == 0.0 and np.all(np.diff(uz.extras[1:]) > 0)
+    assert np.array_equal(unified.unified_decode(uz, 0), convz)
+    many = (np.arange(1, 301, dtype=np.float32) / 7).reshape(20, 15)
+    um = unified.unified_encode(["im", "hac"], [many, Ws[0]])
+    assert um.layers[0].bbar == 16 and np.array_equal(unified.unified_decode(um, 0), many)
+    # alone, an index-map layer is the plain index map of Sect. III-C1
+    alone = unified.unified_encode(["im"], [convz])
+    ref = indexmap.im_encode(convz)
+    assert alone.values.size == 0 and np.array_equal(alone.value_list, ref.c) and np.array_equal(alone.layers[0].pi, ref.pi)
+    assert unified.unified_paper_bits(alone) == indexmap.im_bits(ref)
+
+
 def test_chain_against_nested_products_and_linear_collapse():
     rng = np.random.default_rng(4)
     Ws = small_layers(seed=21, shapes=((25, 18), (18, 11), (11, 7)))
