@@ -266,6 +266,15 @@ int hac_decode_host(const void *blob, size_t bytes, float *W_out, int32_t *sym_o
  * say what is pooled when HAC and sHAC layers are mixed; this makes the code
  * optimal for all streams together.)
  *
+ * A layer may also be an index map (the hybrid of Sect. V-K: index map for the
+ * convolutional part, HAC / sHAC for the fully connected part, all sharing the
+ * same representatives).  It writes no codewords and so adds nothing to the
+ * pooled source; its pointers index the network's one value list: the k_sym
+ * shared symbols followed by the values that occur in index-map layers only
+ * (0.0 first if it is one of them, then ascending), k_values entries in all.
+ * Pointers take 8 bits when k_values <= 256, else 16.  In such a layer's header
+ * k_sym = k_values and has_zero = 0; the layer is multiplied with im_dot.
+ *
  * Layout: this 256-byte header, L layer headers (hac_desc_t with dict_shared =
  * 1), the shared tables, then every layer's own sections (stream, per-column
  * arrays, chunk entries, ri).  All offsets count from the start of the network
@@ -282,7 +291,10 @@ typedef struct {
     uint64_t off_layers;    /* hac_desc_t[L]                                               */
     uint64_t off_codebook, off_codelen, off_canon, off_symsort, off_lut;   /* as in hac_desc_t */
     uint32_t k_sym, lmax, lut_bits, has_zero;                              /* as in hac_desc_t */
-    uint64_t reserved[21];
+    uint32_t k_values;      /* entries of the value list at off_codebook: the k_sym shared
+                               symbols, then the values only index-map layers hold         */
+    uint32_t reserved32;
+    uint64_t reserved[20];
 } hac_net_t;
 
 typedef struct {
@@ -294,15 +306,17 @@ typedef struct {
     uint64_t table_bytes;      /* the one dictionary                                       */
     uint64_t blob_bytes;
     uint64_t paper_bits;       /* the layers' words (+ ri, cb for sHAC) as in hac_stats_t,
-                                  plus 6*32*k ONCE for the two dictionaries                */
+                                  8 or 16 bits per entry of an index-map layer, plus
+                                  6*32*k_sym ONCE for the two dictionaries and 32 bits per
+                                  value only index-map layers hold                         */
     double   entropy_bits;     /* entropy of the pooled source per symbol                  */
     double   avg_code_bits;    /* bits spent on value codewords / symbols: H <= avg <= H+1 */
     double   psi;              /* blob_bytes / (4 * entries)                               */
 } hac_net_stats_t;
 
 /* Encode L layers with one shared dictionary.  formats[l] is HAC_FORMAT_HAC or
- * HAC_FORMAT_SHAC; W[l] is n[l] x m[l], row-major, leading dimension ldw[l] (all
- * host).  opts (may be NULL) applies to every layer: chunk_nnz and ri_bits = 0
+ * HAC_FORMAT_SHAC or HAC_FORMAT_IM; W[l] is n[l] x m[l], row-major, leading
+ * dimension ldw[l] (all host).  opts (may be NULL) applies to every layer: chunk_nnz and ri_bits = 0
  * are chosen per layer, ri_coding affects the sHAC layers only.  Ownership and
  * errors as for hac_encode; L > 65536 gives HAC_EINVAL. */
 int hac_net_encode(uint32_t n_layers, const uint32_t *formats, const float *const *W,

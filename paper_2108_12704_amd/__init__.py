@@ -78,7 +78,7 @@ class Net(C.Structure):
                 ("off_codebook", C.c_uint64), ("off_codelen", C.c_uint64), ("off_canon", C.c_uint64),
                 ("off_symsort", C.c_uint64), ("off_lut", C.c_uint64),
                 ("k_sym", C.c_uint32), ("lmax", C.c_uint32), ("lut_bits", C.c_uint32), ("has_zero", C.c_uint32),
-                ("reserved", C.c_uint64 * 21)]
+                ("k_values", C.c_uint32), ("reserved32", C.c_uint32), ("reserved", C.c_uint64 * 20)]
 
 
 class NetStats(C.Structure):
@@ -275,7 +275,7 @@ class NetBlob:
         f32p, i32p = C.POINTER(C.c_float), C.POINTER(C.c_int32)
         wp = W.ctypes.data_as(f32p) if want_w else None
         lib = load_library()
-        if d.format == HAC_FORMAT_HAC:
+        if d.format in (HAC_FORMAT_HAC, HAC_FORMAT_IM):
             sym = np.empty(n * m, dtype=np.int32)
             _check(lib.hac_net_decode_host(self.data.ctypes.data, self.data.size, layer, wp,
                                            sym.ctypes.data_as(i32p), None, None), "hac_net_decode_host")
@@ -299,7 +299,8 @@ RI_FIELDS, RI_RICE = 0, 1
 
 def hac_net_encode(Ws, formats, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0,
                    ri_coding: int = RI_FIELDS) -> NetBlob:
-    """Layers Ws[l] (n_l x m_l float32, host), formats[l] in (HAC_FORMAT_HAC, HAC_FORMAT_SHAC) -> network blob."""
+    """Layers Ws[l] (n_l x m_l float32, host), formats[l] in (HAC_FORMAT_HAC, HAC_FORMAT_SHAC, HAC_FORMAT_IM)
+    -> network blob."""
     lib = load_library()
     L = len(Ws)
     if L != len(formats):

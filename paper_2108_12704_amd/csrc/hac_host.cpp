@@ -220,10 +220,10 @@ uint32_t ceil_log2(uint64_t v) { uint32_t b = 0; while (((uint64_t)1 << b) < v) 
 
 // Section offsets and total size from the counts already in the header.  One order for all
 // formats: code tables, stream, per-column arrays, chunk entries, and ri when it is stored as fields.
-void place_tables(hac_desc_t& d, uint64_t& cursor)
+void place_tables(hac_desc_t& d, uint64_t& cursor, uint32_t k_values)
 {
     auto place = [&](uint64_t bytes) { const uint64_t o = align_up(cursor); cursor = o + bytes; return o; };
-    d.off_codebook = place(4ull * d.k_sym);
+    d.off_codebook = place(4ull * (k_values > d.k_sym ? k_values : d.k_sym));
     d.off_codelen = place(d.k_sym);
     d.off_canon = place(3 * 33 * 4);
     d.off_symsort = place(4ull * d.k_sym);
@@ -245,7 +245,7 @@ void place_layer(hac_desc_t& d, uint64_t& cursor)
 void place_sections(hac_desc_t& d)
 {
     uint64_t cursor = sizeof(hac_desc_t);
-    place_tables(d, cursor);
+    place_tables(d, cursor, 0);
     place_layer(d, cursor);
     d.blob_bytes = align_up(cursor);
 }
@@ -672,7 +672,7 @@ extern "C" int hac_net_encode(uint32_t n_layers, const uint32_t* formats, const 
     int rc = check_opts(opts);
     if (rc) return rc;
     for (uint32_t l = 0; l < n_layers; ++l) {
-        if (formats[l] != HAC_FORMAT_HAC && formats[l] != HAC_FORMAT_SHAC) return HAC_EINVAL;
+        if (formats[l] != HAC_FORMAT_HAC && formats[l] != HAC_FORMAT_SHAC && formats[l] != HAC_FORMAT_IM) return HAC_EINVAL;
         void* dummy_blob; size_t dummy_bytes;
         if ((rc = check_args(W[l], n[l], m[l], ldw[l], &dummy_blob, &dummy_bytes))) return rc;
         if (formats[l] == HAC_FORMAT_SHAC) {
@@ -689,6 +689,7 @@ extern "C" int hac_net_encode(uint32_t n_layers, const uint32_t* formats, const 
         uint64_t zeros = 0;
         for (uint32_t l = 0; l < n_layers; ++l) {
             const Scan& s = scans[l];
+            if (formats[l] == HAC_FORMAT_IM) continue;        // pointers, no codewords
             if (formats[l] == HAC_FORMAT_HAC) zeros += s.zeros;
             for (size_t i = 0; i < s.values.size(); ++i) pool.emplace_back(s.values[i], s.freq[i]);
         }
@@ -704,16 +705,56 @@ extern "C" int hac_net_encode(uint32_t n_layers, const uint32_t* formats, const 
         }
         if ((rc = finish_dict(D, opts))) return rc;
         const uint32_t first = D.has_zero ? 1u : 0u;
+        const uint32_t k_sym = (uint32_t)D.codebook.size();
+        auto coded_symbol = [&](float v, uint32_t& sym) {
+            const auto it = std::lower_bound(D.codebook.begin() + first, D.codebook.end(), v);
+            if (it == D.codebook.end() || *it != v) return false;
+            sym = (uint32_t)(it - D.codebook.begin());
+            return true;
+        };
+        // values that only index-map layers hold: behind the shared symbols, 0.0 first, then ascending
+        std::vector<float> extras;
+        bool extra_zero = false, any_im = false;
+        for (uint32_t l = 0; l < n_layers; ++l) {
+            if (formats[l] != HAC_FORMAT_IM) continue;
+            any_im = true;
+            if (scans[l].zeros && !D.has_zero) extra_zero = true;
+            uint32_t sym;
+            for (float v : scans[l].values) if (!coded_symbol(v, sym)) extras.push_back(v);
+        }
+        std::sort(extras.begin(), extras.end());
+        extras.erase(std::unique(extras.begin(), extras.end()), extras.end());
+        if (extra_zero) extras.insert(extras.begin(), 0.0f);
+        const uint64_t k_values = (uint64_t)k_sym + extras.size();
+        if (any_im && (k_values > 65536 || k_values < 1)) return HAC_ERANGE;
+        const uint32_t im_bits = k_values <= 256 ? 8 : 16;
+        const uint32_t extra_first = extra_zero ? 1u : 0u;
+        auto list_index = [&](float v) {                      // position of a non-zero value in the value list
+            uint32_t sym;
+            if (coded_symbol(v, sym)) return sym;
+            const auto it = std::lower_bound(extras.begin() + extra_first, extras.end(), v);
+            return k_sym + (uint32_t)(it - extras.begin());
+        };
 
         std::vector<LayerPlan> plans(n_layers);
         for (uint32_t l = 0; l < n_layers; ++l) {
             const Scan& s = scans[l];
             LayerPlan& P = plans[l];
             P.map.resize(s.values.size());
-            for (size_t i = 0; i < s.values.size(); ++i) {
-                const auto it = std::lower_bound(D.codebook.begin() + first, D.codebook.end(), s.values[i]);
-                P.map[i] = (uint32_t)(it - D.codebook.begin());
+            if (formats[l] == HAC_FORMAT_IM) {
+                for (size_t i = 0; i < s.values.size(); ++i) P.map[i] = list_index(s.values[i]);
+                hac_desc_t& d = P.d;
+                d.magic = kMagic; d.version = kVersion; d.format = HAC_FORMAT_IM; d.header_bytes = 256;
+                d.n = (uint64_t)s.n; d.m = (uint64_t)s.m; d.nnz = s.ri.size();
+                d.ent_bits = im_bits; d.k_sym = (uint32_t)k_values;
+                d.idx_pitch = ((uint64_t)s.m + 15) / 16 * 16;
+                d.total_bits = (uint64_t)im_bits * d.n * d.m;
+                if (d.n * d.idx_pitch * (im_bits / 8) > 0xffffffff00ull) return HAC_ERANGE;
+                d.dict_shared = 1;
+                continue;
             }
+            uint32_t sym = 0;
+            for (size_t i = 0; i < s.values.size(); ++i) { coded_symbol(s.values[i], sym); P.map[i] = sym; }
             rc = formats[l] == HAC_FORMAT_HAC ? plan_hac(s, D, opts, P) : plan_shac(s, D, opts, P);
             if (rc) return rc;
             P.d.has_zero = D.has_zero;
@@ -725,14 +766,23 @@ extern "C" int hac_net_encode(uint32_t n_layers, const uint32_t* formats, const 
         net.magic = kNetMagic; net.version = kNetVersion; net.header_bytes = 256; net.n_layers = n_layers;
         net.off_layers = sizeof(hac_net_t);
         uint64_t cursor = net.off_layers + (uint64_t)n_layers * sizeof(hac_desc_t);
-        hac_desc_t tables = plans[0].d;
-        place_tables(tables, cursor);
+        hac_desc_t tables;
+        std::memset(&tables, 0, sizeof tables);
+        tables.k_sym = k_sym; tables.lut_bits = D.lut_bits;
+        place_tables(tables, cursor, (uint32_t)k_values);
         net.off_codebook = tables.off_codebook; net.off_codelen = tables.off_codelen; net.off_canon = tables.off_canon;
         net.off_symsort = tables.off_symsort; net.off_lut = tables.off_lut;
-        net.k_sym = tables.k_sym; net.lmax = D.lmax; net.lut_bits = D.lut_bits; net.has_zero = D.has_zero;
+        net.k_sym = k_sym; net.lmax = D.lmax; net.lut_bits = D.lut_bits; net.has_zero = D.has_zero;
+        net.k_values = (uint32_t)k_values;
         for (uint32_t l = 0; l < n_layers; ++l) {
             hac_desc_t& d = plans[l].d;
-            d.off_codebook = tables.off_codebook; d.off_codelen = tables.off_codelen; d.off_canon = tables.off_canon;
+            d.off_codebook = tables.off_codebook;
+            if (d.format == HAC_FORMAT_IM) {                  // the index map, n rows of idx_pitch pointers
+                d.off_stream = align_up(cursor);
+                cursor = d.off_stream + d.n * d.idx_pitch * (d.ent_bits / 8) + kTailPad;
+                continue;
+            }
+            d.off_codelen = tables.off_codelen; d.off_canon = tables.off_canon;
             d.off_symsort = tables.off_symsort; d.off_lut = tables.off_lut;
             place_layer(d, cursor);
         }
@@ -742,9 +792,31 @@ extern "C" int hac_net_encode(uint32_t n_layers, const uint32_t* formats, const 
         uint8_t* base = static_cast<uint8_t*>(std::calloc(1, (size_t)net.blob_bytes));
         if (!base) return HAC_ENOMEM;
         std::memcpy(base, &net, sizeof net);
-        write_tables(base, plans[0].d, D.codebook, D.len, D.t, D.lut);
+        write_tables(base, tables, D.codebook, D.len, D.t, D.lut);
+        if (!extras.empty()) std::memcpy(base + net.off_codebook + 4ull * k_sym, extras.data(), 4 * extras.size());
+        // pointer of the value 0.0 (index-map layers only): the shared symbol 0, or the first extra
+        const uint32_t zero_ptr = D.has_zero ? 0u : k_sym;
         for (uint32_t l = 0; l < n_layers; ++l) {
             std::memcpy(base + net.off_layers + (uint64_t)l * sizeof(hac_desc_t), &plans[l].d, sizeof(hac_desc_t));
+            if (formats[l] == HAC_FORMAT_IM) {
+                const hac_desc_t& d = plans[l].d;
+                const Scan& s = scans[l];
+                uint8_t* p8 = base + d.off_stream;
+                uint16_t* p16 = reinterpret_cast<uint16_t*>(base + d.off_stream);
+                if (zero_ptr)                                 // the map starts as all zero bytes: pointer 0
+                    for (uint64_t i = 0; i < d.n; ++i)
+                        for (uint64_t j = 0; j < d.m; ++j) {
+                            if (d.ent_bits == 8) p8[i * d.idx_pitch + j] = (uint8_t)zero_ptr;
+                            else p16[i * d.idx_pitch + j] = (uint16_t)zero_ptr;
+                        }
+                for (int64_t j = 0; j < s.m; ++j)
+                    for (uint64_t p = s.cb[(size_t)j]; p < s.cb[(size_t)j + 1]; ++p) {
+                        const uint64_t at = (uint64_t)s.ri[(size_t)p] * d.idx_pitch + (uint64_t)j;
+                        const uint32_t v = plans[l].map[s.sym[(size_t)p]];
+                        if (d.ent_bits == 8) p8[at] = (uint8_t)v; else p16[at] = (uint16_t)v;
+                    }
+                continue;
+            }
             rc = formats[l] == HAC_FORMAT_HAC ? write_hac(base, scans[l], D, plans[l]) : write_shac(base, scans[l], D, plans[l]);
             if (rc) { std::free(base); return rc; }
         }
@@ -826,14 +898,14 @@ int check_desc(const hac_desc_t& d, size_t bytes, bool in_net)
 {
     if (d.magic != kMagic || d.version != kVersion || d.header_bytes != 256) return HAC_EFORMAT;
     if (d.dict_shared != (in_net ? 1u : 0u)) return HAC_EFORMAT;
-    if (in_net && d.format == HAC_FORMAT_IM) return HAC_EFORMAT;
+
     if (d.format != HAC_FORMAT_HAC && d.format != HAC_FORMAT_SHAC && d.format != HAC_FORMAT_IM) return HAC_EFORMAT;
     if (d.blob_bytes > bytes || d.blob_bytes < sizeof(hac_desc_t)) return HAC_EFORMAT;
     if (d.n < 1 || d.m < 1 || d.n > 0x7fffffffull || d.m > 0x7fffffffull) return HAC_EFORMAT;
     if (d.reserved[0] || d.reserved[1]) return HAC_EFORMAT;
     if (d.format == HAC_FORMAT_IM) {
         if (d.ent_bits != 8 && d.ent_bits != 16) return HAC_EFORMAT;
-        if (d.k_sym < 1 || d.k_sym > (d.ent_bits == 8 ? 256u : 65536u) || d.has_zero > 1) return HAC_EFORMAT;
+        if (d.k_sym < 1 || d.k_sym > (d.ent_bits == 8 ? 256u : 65536u) || d.has_zero > (in_net ? 0u : 1u)) return HAC_EFORMAT;
         if (d.idx_pitch != (d.m + 15) / 16 * 16) return HAC_EFORMAT;
         if (d.nnz > d.n * d.m || d.total_bits != (uint64_t)d.ent_bits * d.n * d.m) return HAC_EFORMAT;
         if (d.n_words || d.lmax || d.lut_bits || d.zero_len || d.chunk || d.ri_bits || d.n_chunks || d.off_codelen ||
@@ -1158,16 +1230,20 @@ inline uint32_t im_pointer(const hac_desc_t& d, const uint8_t* base, uint64_t i,
 
 // representatives finite and ascending after the optional 0.0; every pointer below k; padding 0;
 // nnz = number of pointers to a value other than 0.0
+// A layer of a network blob (dict_shared): the value list is checked once for the network, and
+// a non-zero is a pointer to a value other than 0.0, wherever 0.0 sits in the list.
 int check_index_map(const void* blob, const hac_desc_t& d, bool deep)
 {
     const uint8_t* base = static_cast<const uint8_t*>(blob);
     const float* cb = reinterpret_cast<const float*>(base + d.off_codebook);
-    for (uint32_t s = 0; s < d.k_sym; ++s) {
-        if (!std::isfinite(cb[s])) return HAC_EFORMAT;
-        if (s > d.has_zero && !(cb[s - 1] < cb[s])) return HAC_EFORMAT;
-        if ((cb[s] == 0.0f) != (d.has_zero && s == 0)) return HAC_EFORMAT;
+    if (!d.dict_shared) {
+        for (uint32_t s = 0; s < d.k_sym; ++s) {
+            if (!std::isfinite(cb[s])) return HAC_EFORMAT;
+            if (s > d.has_zero && !(cb[s - 1] < cb[s])) return HAC_EFORMAT;
+            if ((cb[s] == 0.0f) != (d.has_zero && s == 0)) return HAC_EFORMAT;
+        }
+        if (d.has_zero && float_bits(cb[0]) != 0) return HAC_EFORMAT;
     }
-    if (d.has_zero && float_bits(cb[0]) != 0) return HAC_EFORMAT;
     if (!deep) return HAC_OK;
     uint64_t nnz = 0;
     for (uint64_t i = 0; i < d.n; ++i)
@@ -1175,7 +1251,7 @@ int check_index_map(const void* blob, const hac_desc_t& d, bool deep)
             const uint32_t p = im_pointer(d, base, i, j);
             if (j >= d.m) { if (p) return HAC_EFORMAT; continue; }
             if (p >= d.k_sym) return HAC_EFORMAT;
-            if (!(d.has_zero && p == 0)) ++nnz;
+            if (d.dict_shared ? cb[p] != 0.0f : !(d.has_zero && p == 0)) ++nnz;
         }
     return nnz == d.nnz ? HAC_OK : HAC_EFORMAT;
 }
@@ -1228,6 +1304,20 @@ uint64_t layer_paper_bits(const hac_desc_t& d)
     if (d.format == HAC_FORMAT_HAC) return 32 * d.n_words;
     const bool rice = d.ri_coding == HAC_RI_RICE;
     return 32 * d.n_words + 32 * ((rice ? 0 : d.nnz) + d.m + 1);
+}
+
+// a validated index map: W_out row-major, sym_out the pointers in column order
+int decode_index_map(const void* blob, const hac_desc_t& d, float* W_out, int32_t* sym_out)
+{
+    const uint8_t* base = static_cast<const uint8_t*>(blob);
+    const float* cb = reinterpret_cast<const float*>(base + d.off_codebook);
+    for (uint64_t i = 0; i < d.n; ++i)
+        for (uint64_t j = 0; j < d.m; ++j) {
+            const uint32_t p = im_pointer(d, base, i, j);
+            if (sym_out) sym_out[j * d.n + i] = (int32_t)p;
+            if (W_out) W_out[i * d.m + j] = cb[p];
+        }
+    return HAC_OK;
 }
 
 // the library's sequential decoder over one validated layer
@@ -1346,15 +1436,7 @@ extern "C" int hac_decode_host(const void* blob, size_t bytes, float* W_out, int
     if (d.format == HAC_FORMAT_IM) {
         if (row_out || col_out) return HAC_EINVAL;
         if ((rc = check_index_map(blob, d, true))) return rc;
-        const uint8_t* base = static_cast<const uint8_t*>(blob);
-        const float* cb = reinterpret_cast<const float*>(base + d.off_codebook);
-        for (uint64_t i = 0; i < d.n; ++i)
-            for (uint64_t j = 0; j < d.m; ++j) {
-                const uint32_t p = im_pointer(d, base, i, j);
-                if (sym_out) sym_out[j * d.n + i] = (int32_t)p;
-                if (W_out) W_out[i * d.m + j] = cb[p];
-            }
-        return HAC_OK;
+        return decode_index_map(blob, d, W_out, sym_out);
     }
     View v; make_view(blob, d, v);
     if ((rc = check_tables(v))) return rc;
@@ -1379,6 +1461,40 @@ int check_net_header(const void* blob, size_t bytes, hac_net_t& net)
     if (net.off_layers != sizeof(hac_net_t)) return HAC_EFORMAT;
     if (net.off_layers + (uint64_t)net.n_layers * sizeof(hac_desc_t) > net.blob_bytes) return HAC_EFORMAT;
     if (net.has_zero > 1 || net.lmax > 32 || net.lut_bits < 1 || net.lut_bits > 12) return HAC_EFORMAT;
+    if (net.reserved32 || net.k_values < net.k_sym || net.k_values > net.k_sym + 65536u) return HAC_EFORMAT;
+    if (net.has_zero > net.k_sym) return HAC_EFORMAT;
+    return HAC_OK;
+}
+
+// The network's tables, checked once: the shared code (as for a layer blob) and the value list
+// behind it (the values only index-map layers hold: finite, 0.0 first if present, then ascending,
+// none of them a shared symbol's value).
+int check_net_tables(const void* blob, const hac_net_t& net)
+{
+    hac_desc_t d;
+    std::memset(&d, 0, sizeof d);
+    d.format = HAC_FORMAT_SHAC;                               // zero_len is a HAC layer's own field
+    d.k_sym = net.k_sym; d.lmax = net.lmax; d.lut_bits = net.lut_bits; d.has_zero = net.has_zero;
+    d.off_codebook = net.off_codebook; d.off_codelen = net.off_codelen; d.off_canon = net.off_canon;
+    d.off_symsort = net.off_symsort; d.off_lut = net.off_lut; d.blob_bytes = net.blob_bytes;
+    const size_t tot = (size_t)net.blob_bytes;
+    const uint64_t first = net.off_layers + (uint64_t)net.n_layers * sizeof(hac_desc_t);
+    if (net.off_codebook < first || net.off_codelen < first || net.off_canon < first || net.off_symsort < first ||
+        net.off_lut < first) return HAC_EFORMAT;
+    if (!section_ok(d, d.off_codebook, 4ull * net.k_values, tot) || !section_ok(d, d.off_codelen, d.k_sym, tot) ||
+        !section_ok(d, d.off_canon, 3 * 33 * 4, tot) || !section_ok(d, d.off_symsort, 4ull * d.k_sym, tot) ||
+        !section_ok(d, d.off_lut, 4ull << d.lut_bits, tot)) return HAC_EFORMAT;
+    View v; make_view(blob, d, v);
+    int rc = check_tables(v);
+    if (rc) return rc;
+    const float* cb = v.codebook;
+    const uint32_t k = net.k_sym, kv = net.k_values;
+    for (uint32_t s = k; s < kv; ++s) {
+        if (!std::isfinite(cb[s])) return HAC_EFORMAT;
+        if (cb[s] == 0.0f && (s != k || net.has_zero || float_bits(cb[s]) != 0)) return HAC_EFORMAT;
+        if (s > k && cb[s - 1] != 0.0f && !(cb[s - 1] < cb[s])) return HAC_EFORMAT;
+        if (cb[s] != 0.0f && std::binary_search(cb + net.has_zero, cb + k, cb[s])) return HAC_EFORMAT;
+    }
     return HAC_OK;
 }
 
@@ -1390,6 +1506,9 @@ int net_layer_desc(const void* blob, const hac_net_t& net, uint32_t l, hac_desc_
     if (d.blob_bytes != net.blob_bytes) return HAC_EFORMAT;
     int rc = check_desc(d, (size_t)net.blob_bytes, true);
     if (rc) return rc;
+    const uint64_t behind = net.off_layers + (uint64_t)net.n_layers * sizeof(hac_desc_t);
+    if (d.format == HAC_FORMAT_IM)
+        return (d.off_codebook == net.off_codebook && d.k_sym == net.k_values && d.off_stream >= behind) ? HAC_OK : HAC_EFORMAT;
     if (d.off_codebook != net.off_codebook || d.off_codelen != net.off_codelen || d.off_canon != net.off_canon ||
         d.off_symsort != net.off_symsort || d.off_lut != net.off_lut || d.k_sym != net.k_sym || d.lmax != net.lmax ||
         d.lut_bits != net.lut_bits || d.has_zero != net.has_zero) return HAC_EFORMAT;
@@ -1423,13 +1542,16 @@ extern "C" int hac_net_validate(const void* blob, size_t bytes, int deep)
     int rc = check_net_header(blob, bytes, net);
     if (rc) return rc;
     try {
+        if ((rc = check_net_tables(blob, net))) return rc;
         for (uint32_t l = 0; l < net.n_layers; ++l) {
             hac_desc_t d;
             if ((rc = net_layer_desc(blob, net, l, d))) return rc;
-            View v; make_view(blob, d, v);
-            if (l == 0 || d.format != HAC_FORMAT_SHAC) {          // the tables are the same for every layer;
-                if ((rc = check_tables(v))) return rc;            // zero_len is a HAC header's own field
+            if (d.format == HAC_FORMAT_IM) {
+                if ((rc = check_index_map(blob, d, deep != 0))) return rc;
+                continue;
             }
+            View v; make_view(blob, d, v);
+            if (d.format == HAC_FORMAT_HAC && (rc = check_tables(v))) return rc;   // zero_len against the code
             if ((rc = check_index_shallow(v))) return rc;
             if (deep && (rc = check_deep(v))) return rc;
         }
@@ -1448,12 +1570,22 @@ extern "C" int hac_net_stats(const void* blob, size_t bytes, hac_net_stats_t* ou
     try {
         std::memset(out, 0, sizeof *out);
         std::vector<uint64_t> cnt(net.k_sym, 0);
-        uint64_t gap_bits = 0;
+        uint64_t gap_bits = 0, map_bits = 0;
+        if ((rc = check_net_tables(blob, net))) return rc;
         for (uint32_t l = 0; l < net.n_layers; ++l) {
             hac_desc_t d;
             if ((rc = net_layer_desc(blob, net, l, d))) return rc;
+            if (d.format == HAC_FORMAT_IM) {
+                if ((rc = check_index_map(blob, d, true))) return rc;
+                out->entries += d.n * d.m;
+                out->nnz += d.nnz;
+                out->stream_bits += d.total_bits;
+                out->paper_bits += d.total_bits;              // bbar * n * m
+                map_bits += d.total_bits;
+                continue;
+            }
             View v; make_view(blob, d, v);
-            if ((rc = check_tables(v))) return rc;
+            if (d.format == HAC_FORMAT_HAC && (rc = check_tables(v))) return rc;
             if ((rc = check_index_shallow(v))) return rc;
             if ((rc = count_symbols(v, cnt))) return rc;
             out->entries += d.n * d.m;
@@ -1464,14 +1596,14 @@ extern "C" int hac_net_stats(const void* blob, size_t bytes, hac_net_stats_t* ou
             gap_bits += d.gap_bits;
         }
         out->n_layers = net.n_layers;
-        out->paper_bits += 6ull * 32 * net.k_sym;
-        out->table_bytes = 4ull * net.k_sym + net.k_sym + 3 * 33 * 4 + 4ull * net.k_sym + (4ull << net.lut_bits);
+        out->paper_bits += 6ull * 32 * net.k_sym + 32ull * (net.k_values - net.k_sym);
+        out->table_bytes = 4ull * net.k_values + net.k_sym + 3 * 33 * 4 + 4ull * net.k_sym + (4ull << net.lut_bits);
         out->blob_bytes = net.blob_bytes;
         double H = 0.0;
         for (uint32_t s = 0; s < net.k_sym; ++s)
             if (cnt[s]) { const double p = (double)cnt[s] / (double)out->symbols; H -= p * std::log2(p); }
         out->entropy_bits = H;
-        out->avg_code_bits = out->symbols ? (double)(out->stream_bits - gap_bits) / (double)out->symbols : 0.0;
+        out->avg_code_bits = out->symbols ? (double)(out->stream_bits - gap_bits - map_bits) / (double)out->symbols : 0.0;
         out->psi = (double)net.blob_bytes / (4.0 * (double)out->entries);
     } catch (const std::bad_alloc&) {
         return HAC_ENOMEM;
@@ -1487,8 +1619,14 @@ extern "C" int hac_net_decode_host(const void* blob, size_t bytes, uint32_t laye
     if (rc) return rc;
     hac_desc_t d;
     if ((rc = net_layer_desc(blob, net, layer, d))) return rc;
+    if ((rc = check_net_tables(blob, net))) return rc;
+    if (d.format == HAC_FORMAT_IM) {
+        if (row_out || col_out) return HAC_EINVAL;
+        if ((rc = check_index_map(blob, d, true))) return rc;
+        return decode_index_map(blob, d, W_out, sym_out);
+    }
     View v; make_view(blob, d, v);
-    if ((rc = check_tables(v))) return rc;
+    if (d.format == HAC_FORMAT_HAC && (rc = check_tables(v))) return rc;
     if ((rc = check_index_shallow(v))) return rc;
     return decode_layer(v, W_out, sym_out, row_out, col_out);
 }

@@ -43,7 +43,7 @@ uint32_t rice_length(uint32_t d, uint32_t k);
 // Offsets of all sections and blob_bytes, from the counts already in the header
 // (place_tables, then place_layer, from the end of the header).
 void place_sections(hac_desc_t& d);
-void place_tables(hac_desc_t& d, uint64_t& cursor);
+void place_tables(hac_desc_t& d, uint64_t& cursor, uint32_t k_values);   // k_values: entries of the value list when above k_sym
 void place_layer(hac_desc_t& d, uint64_t& cursor);
 int write_tables(uint8_t* base, const hac_desc_t& d, const std::vector<float>& codebook,
                  const std::vector<uint8_t>& len, const CodeTables& t, const std::vector<uint32_t>& lut);

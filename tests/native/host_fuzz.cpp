@@ -79,16 +79,20 @@ static void fuzz_networks(std::mt19937& rng, int& failures, long& cases)
     for (const auto& sh : shapes)
         for (double density : { 0.0, 0.1, 0.7 })
             for (int k : { 1, 5, 120 })
-                for (int f = 0; f < 6; ++f) {
+                for (int f = 0; f < 9; ++f) {
                     const int64_t ns[2] = { sh[0], sh[1] }, ms[2] = { sh[1], sh[2] };
                     std::vector<float> W0 = make_matrix(rng, sh[0], sh[1], density, k);
                     std::vector<float> W1 = make_matrix(rng, sh[1], sh[2], f % 2 ? density : 1.0 - density, k + 2);
                     const std::vector<float>* expect[2] = { &W0, &W1 };
                     const float* Ws[2] = { W0.data(), W1.data() };
-                    const uint32_t fm[2] = { (uint32_t)(f & 1 ? HAC_FORMAT_SHAC : HAC_FORMAT_HAC),
-                                             (uint32_t)(f & 2 ? HAC_FORMAT_SHAC : HAC_FORMAT_HAC) };
+                    // f = 0..5: HAC / sHAC pairs (4, 5 with Rice-coded gaps); 6..8: an index map beside them
+                    uint32_t fm[2] = { (uint32_t)(f & 1 ? HAC_FORMAT_SHAC : HAC_FORMAT_HAC),
+                                       (uint32_t)(f & 2 ? HAC_FORMAT_SHAC : HAC_FORMAT_HAC) };
+                    if (f == 6) fm[0] = HAC_FORMAT_IM;
+                    if (f == 7) fm[1] = HAC_FORMAT_IM;
+                    if (f == 8) fm[0] = fm[1] = HAC_FORMAT_IM;
                     hac_opts_t o; std::memset(&o, 0, sizeof o);
-                    o.ri_coding = f >= 4 ? HAC_RI_RICE : HAC_RI_FIELDS;
+                    o.ri_coding = (f == 4 || f == 5) ? HAC_RI_RICE : HAC_RI_FIELDS;
                     o.chunk_nnz = (uint32_t)(rng() % 3 == 0 ? 1 + rng() % 9 : 0);
                     void* blob = nullptr; size_t bytes = 0;
                     const int rc = hac_net_encode(2, fm, Ws, ns, ms, ms, &o, &blob, &bytes);

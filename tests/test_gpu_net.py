@@ -137,6 +137,30 @@ def test_chain_of_separate_blobs_with_an_index_map_in_the_middle(hac):
         assert torch.equal(Y, Yseq)
 
 
+def test_hybrid_network_blob_index_map_then_compressed_layers(hac):
+    # Sect. V-K: an unpruned layer as index map and pruned layers as HAC / sHAC, one value list
+    rng = np.random.default_rng(3)
+    Ws, bs = workloads.network("tiny-fc")
+    reps = np.concatenate([np.unique(Ws[0][Ws[0] != 0])[:3], np.array([-0.31, 0.07, 0.5], dtype=np.float32)])
+    conv = rng.choice(reps, size=(260, 500)).astype(np.float32)                 # 260 -> 500 in front of tiny-fc
+    layers = [conv] + Ws
+    fmts = (3, HAC, SHAC, HAC)
+    nb = hac.hac_net_encode(layers, fmts)
+    assert nb.validate(deep=True) == 0 and nb.net.k_values > nb.net.k_sym
+    dls = nb.to_device(dev())
+    bs = [None] + bs
+    relu = [True, True, True, False]
+    for B in (1, 9, 64, 300):
+        X = workloads.make_batch(B, 260, 51)
+        Y0 = hac.im_dot(dls[0], torch.from_numpy(X).to(dev()))
+        torch.cuda.synchronize()
+        check_y(Y0, X, conv, f"index-map layer of the network blob, B {B}")
+        Y = hac.hac_forward(_layers(hac, dls, bs, relu), torch.from_numpy(X).to(dev()))
+        torch.cuda.synchronize()
+        check_chain(Y, X, layers, bs, relu, f"hybrid chain B {B}")
+        assert torch.equal(Y, _one_call_at_a_time(hac, fmts, dls, bs, relu, X))
+
+
 def test_single_layer_chain_equals_dot_with_epilogue(hac):
     W = workloads.layer(1)
     b = workloads.make_biases(((W.shape[0], W.shape[1]),), 3)[0]

@@ -10,7 +10,7 @@ from oracle import formats, gapcode, huffman, unified
 from test_library_host import codes_from_blob, header_fields, oracle_decode_bits
 from test_oracle_unified import small_layers
 
-KIND = {hac.HAC_FORMAT_HAC: "hac", hac.HAC_FORMAT_SHAC: "shac"}
+KIND = {hac.HAC_FORMAT_HAC: "hac", hac.HAC_FORMAT_SHAC: "shac", hac.HAC_FORMAT_IM: "im"}
 
 
 def test_net_structs_match_binding():
@@ -86,6 +86,113 @@ def test_net_blob_against_oracle(fmts, ri_coding):
         assert st.stream_bits == sum(s.nbits for s in u.layers)
 
 
+def hybrid_layers(seed=12, zero_in_map=False):
+    """An unpruned 'convolutional' matrix over a few representatives (one of them shared with the
+    pruned layers) in front of three pruned layers."""
+    rng = np.random.default_rng(seed)
+    Ws = small_layers(seed=41, shapes=((30, 20), (20, 16), (16, 9)), k=6, prune=0.6)
+    reps = np.array([-0.75, -0.1, 0.3, 0.9, Ws[0][Ws[0] != 0][0]], dtype=np.float32)
+    conv = rng.choice(reps, size=(27, 30))
+    if zero_in_map:
+        conv[rng.random(conv.shape) < 0.1] = 0.0
+    return [conv] + Ws
+
+
+@pytest.mark.parametrize("fmts,zero_in_map", [((3, 1, 2, 1), False), ((3, 2, 2, 2), True), ((3, 1, 1, 2), True),
+                                               ((3, 3, 2, 2), False)])
+def test_index_map_layers_in_a_network_blob(fmts, zero_in_map):
+    layers = hybrid_layers(zero_in_map=zero_in_map)
+    nb = hac.hac_net_encode(layers, fmts)
+    assert nb.validate(deep=True) == 0
+    u = unified.unified_encode([KIND[f] for f in fmts], layers)
+    net = nb.net
+    assert net.k_sym == len(u.values) and net.k_values == u.value_list.size
+    assert np.array_equal(nb.section(nb.layers[0], "off_codebook", np.float32, int(net.k_values)), u.value_list)
+    for l, (f, W, d) in enumerate(zip(fmts, layers, nb.layers)):
+        if f != hac.HAC_FORMAT_IM:
+            assert np.array_equal(nb.decode_host(l)[0], W)
+            assert d.total_bits == u.layers[l].nbits
+            continue
+        im = u.layers[l]
+        assert d.dict_shared == 1 and d.k_sym == net.k_values and d.ent_bits == im.bbar
+        assert d.total_bits == im.bbar * W.size and d.nnz == np.count_nonzero(W)
+        Wd, ptr = nb.decode_host(l)
+        assert np.array_equal(Wd, W)
+        assert np.array_equal(ptr.reshape(W.shape[1], W.shape[0]).T, im.pi)
+        # padding columns of the map hold 0
+        pitch = int(d.idx_pitch)
+        raw = nb.section(d, "off_stream", np.uint8 if d.ent_bits == 8 else np.uint16, W.shape[0] * pitch).reshape(W.shape[0], pitch)
+        assert np.array_equal(raw[:, :W.shape[1]], im.pi) and not raw[:, W.shape[1]:].any()
+    st = nb.stats()
+    assert st.paper_bits == unified.unified_paper_bits(u)
+    assert st.entries == sum(W.size for W in layers) and st.symbols == int(u.freqs.sum())
+    if u.freqs.size:
+        assert abs(st.entropy_bits - huffman.entropy_bits(u.freqs)) < 1e-12
+
+
+def test_network_of_index_maps_only_and_wide_pointers():
+    from oracle import indexmap
+    conv = hybrid_layers(zero_in_map=True)[0]
+    nb = hac.hac_net_encode([conv, conv.T.copy()], (3, 3))
+    assert nb.validate(deep=True) == 0 and nb.net.k_sym == 0
+    ref = indexmap.im_encode(conv)
+    assert np.array_equal(nb.section(nb.layers[0], "off_codebook", np.float32, int(nb.net.k_values)), ref.c)
+    assert np.array_equal(nb.decode_host(0)[1].reshape(conv.shape[1], conv.shape[0]).T, ref.pi)
+    many = (np.arange(1, 301, dtype=np.float32) / 7).reshape(20, 15)
+    W = small_layers(seed=3, shapes=((15, 8),))[0]
+    nb = hac.hac_net_encode([many, W], (3, 1))
+    assert nb.validate(deep=True) == 0 and nb.layers[0].ent_bits == 16
+    assert np.array_equal(nb.decode_host(0)[0], many) and np.array_equal(nb.decode_host(1)[0], W)
+    u = unified.unified_encode(["im", "hac"], [many, W])
+    assert nb.stats().paper_bits == unified.unified_paper_bits(u)
+
+
+def test_damaged_value_list_and_index_map_are_rejected():
+    lib = hac.load_library()
+    layers = hybrid_layers(zero_in_map=True)
+    nb = hac.hac_net_encode(layers, (3, 2, 2, 2))
+    good = nb.data
+    assert nb.net.k_values > nb.net.k_sym and nb.net.has_zero == 0
+
+    def check(mutate, deep=1):
+        b = good.copy()
+        mutate(b)
+        return lib.hac_net_validate(b.ctypes.data, b.size, deep)
+
+    cb_off, k, kv = int(nb.net.off_codebook), int(nb.net.k_sym), int(nb.net.k_values)
+
+    def poke_value(i, v):
+        def f(b): b[cb_off + 4 * i:cb_off + 4 * i + 4].view(np.float32)[0] = v
+        return f
+
+    cb = good[cb_off:cb_off + 4 * kv].view(np.float32)
+    assert cb[k] == 0.0                                              # the extra 0.0 comes first
+    assert check(poke_value(k + 1, np.nan), 0) == -3
+    assert check(poke_value(k + 2, cb[k + 1]), 0) == -3              # not ascending
+    assert check(poke_value(kv - 1, cb[0]), 0) == -3                 # repeats a shared symbol's value
+    assert check(poke_value(kv - 1, 0.0), 0) == -3                   # 0.0 anywhere but first
+    d0 = nb.layers[0]
+    off = int(d0.off_stream)
+
+    def poke_map(at, v):
+        def f(b): b[off + at] = v
+        return f
+
+    assert check(poke_map(0, kv)) == -3                              # pointer past the list
+    assert check(poke_map(int(d0.m), 1)) == -3                       # padding column not 0
+    first_nz = int(np.flatnonzero(layers[0][0] != 0)[0])
+    assert check(poke_map(first_nz, k)) == -3                        # a non-zero turned into 0.0: nnz no longer matches
+    net_off = {f[0]: getattr(hac.Net, f[0]).offset for f in hac.Net._fields_}
+
+    def set_u32(o, v):
+        def f(b): b[o:o + 4].view(np.uint32)[0] = v
+        return f
+
+    assert check(set_u32(net_off["k_values"], kv + 1)) == -3
+    assert check(set_u32(net_off["k_values"], k - 1 if k else 0xffffffff)) == -3
+    assert check(set_u32(net_off["reserved32"], 1)) == -3
+
+
 def test_single_layer_net_has_the_layers_own_stream():
     W = small_layers(seed=2)[0]
     for fmt, enc in ((hac.HAC_FORMAT_HAC, hac.hac_encode), (hac.HAC_FORMAT_SHAC, hac.shac_encode)):
@@ -124,7 +231,7 @@ def test_argument_and_format_errors():
     lib = hac.load_library()
     W = small_layers(seed=1)[0]
     with pytest.raises(hac.HacError):
-        hac.hac_net_encode([W], [hac.HAC_FORMAT_IM])
+        hac.hac_net_encode([W], [4])
     with pytest.raises(hac.HacError):
         hac.hac_net_encode([W], [hac.HAC_FORMAT_SHAC], ri_bits=2)           # too narrow for 40 rows
     bad = W.copy(); bad[0, 0] = np.inf
