@@ -232,8 +232,11 @@ def extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, iters):
     # paper's method, both need W in HBM at 4 bytes (dense) or 8 bytes (CSR) per stored entry
     Wd = torch.from_numpy(W).to(dev)
     gpu_ctx = {"dense_bytes": int(W.size * 4), "csr_bytes": int(np.count_nonzero(W)) * 8 + 4 * (W.shape[0] + 1), "calls": []}
+    import warnings
     try:
-        Wt_csr = Wd.t().contiguous().to_sparse_csr()                  # Y^T = W^T . X^T
+        with warnings.catch_warnings():
+            warnings.simplefilter("ignore")                           # torch announces that sparse CSR is in beta
+            Wt_csr = Wd.t().contiguous().to_sparse_csr()              # Y^T = W^T . X^T
     except Exception:                                                 # sparse CSR unavailable in this build
         Wt_csr = None
     for B in sorted({c.B for c in calls}):
