@@ -161,6 +161,41 @@ def test_hybrid_network_blob_index_map_then_compressed_layers(hac):
         assert torch.equal(Y, _one_call_at_a_time(hac, fmts, dls, bs, relu, X))
 
 
+def test_randomized_chains(hac):
+    # seeded sweep: 1-5 layers of random widths (1 included), densities (0 and 1 included), formats
+    # (HAC, sHAC with fields or Rice-coded gaps, index map), biases, activations and batch sizes,
+    # as one network blob or as separate blobs
+    rng = np.random.default_rng(20240607)
+    for case in range(40):
+        L = int(rng.integers(1, 6))
+        widths = [int(rng.choice([1, 2, 7, 33, 64, 129, 300])) for _ in range(L + 1)]
+        k = int(rng.choice([1, 3, 17, 200]))
+        reps = np.unique((rng.normal(0, 0.2, k) + 0.01).astype(np.float32))
+        reps = reps[reps != 0]
+        Ws = []
+        for l in range(L):
+            dens = float(rng.choice([0.0, 0.02, 0.3, 1.0]))
+            W = reps[rng.integers(0, reps.size, size=(widths[l], widths[l + 1]))].astype(np.float32)
+            W[rng.random(W.shape) >= dens] = 0.0
+            Ws.append(np.ascontiguousarray(W))
+        fmts = [int(rng.choice([HAC, SHAC, 3])) for _ in range(L)]
+        rice = int(rng.integers(0, 2))
+        bs = [None if rng.random() < 0.4 else rng.normal(0, 0.1, widths[l + 1]).astype(np.float32) for l in range(L)]
+        relu = [bool(rng.integers(0, 2)) for _ in range(L)]
+        B = int(rng.choice([1, 2, 3, 4, 6, 31, 32, 33, 100, 257, 600]))
+        print(f"[case] chain {case}: widths {widths} fmts {fmts} rice {rice} B {B}", flush=True)
+        if rng.random() < 0.5:
+            dls = hac.hac_net_encode(Ws, fmts, ri_coding=rice).to_device(dev())
+        else:
+            enc = {HAC: lambda W: hac.hac_encode(W), SHAC: lambda W: hac.shac_encode(W, ri_coding=rice), 3: hac.im_encode}
+            dls = [enc[f](W).to_device(dev()) for f, W in zip(fmts, Ws)]
+        X = workloads.make_batch(B, widths[0], 1000 + case)
+        Y = hac.hac_forward(_layers(hac, dls, bs, relu), torch.from_numpy(X).to(dev()))
+        torch.cuda.synchronize()
+        check_chain(Y, X, Ws, bs, relu, f"case {case}")
+        assert torch.equal(Y, _one_call_at_a_time(hac, fmts, dls, bs, relu, X)), f"case {case}"
+
+
 def test_single_layer_chain_equals_dot_with_epilogue(hac):
     W = workloads.layer(1)
     b = workloads.make_biases(((W.shape[0], W.shape[1]),), 3)[0]
