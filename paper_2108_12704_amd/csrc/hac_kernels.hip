@@ -26,6 +26,7 @@
 #include "../../include/hac.h"
 #include "hac_internal.h"
 #include "hac_hostlib.h"
+#include "hac_device.h"
 
 // Optional phase timing (build with -DHAC_PHASE_TIMING): lane 0 of each wave of the dot
 // kernels stores a 100 MHz clock at phase boundaries; hac_debug_phases() copies them out.
@@ -37,301 +38,6 @@ __device__ unsigned long long g_phase[16384 * 8];
 #endif
 
 namespace {
-
-constexpr int kWave = 64;
-constexpr uint32_t kCodebookLdsMax = 1024;   // symbols whose values are staged in LDS
-
-typedef __attribute__((address_space(3))) const uint32_t lds_cu32;
-typedef __attribute__((address_space(3))) const float lds_cf32;
-
-struct DevBlob {
-    const float* codebook;
-    const uint32_t* canon;      // first_code[33], count[33], first_index[33]
-    const uint32_t* symsort;
-    const uint32_t* lut;
-    const uint32_t* stream;
-    const uint32_t* colchunk;   // m + 1
-    const uint32_t* colpos;     // m + 1 (sHAC: cb)
-    const uint32_t* colbit;     // m + 1
-    const void* ent;            // chunk entries
-    const uint32_t* ri;         // sHAC
-    uint32_t n, m, nnz, k_sym, lmax, lut_bits, has_zero, zero_len, chunk, ri_bits, ent_bits, row_bits, n_chunks;
-    uint32_t rice, rice_k;      // sHAC whose row gaps are Rice-coded in front of each value's codeword
-};
-
-// (relative bit offset, first row) of chunk g
-__device__ __forceinline__ void load_entry(const DevBlob& d, uint32_t g, uint32_t& rel, uint32_t& row)
-{
-    row = 0;
-    if (d.ent_bits == 32) {
-        const uint32_t e = static_cast<const uint32_t*>(d.ent)[g];
-        rel = e >> d.row_bits;                       // sHAC: row_bits = 0
-        row = e & ((1u << d.row_bits) - 1u);
-    } else if (d.ent_bits == 16) {
-        rel = static_cast<const uint16_t*>(d.ent)[g];
-    } else {
-        const uint2 e = static_cast<const uint2*>(d.ent)[g];
-        row = e.x; rel = e.y;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// word sources: the blob's stream / ri words in global memory, or a copy staged
-// in LDS that starts at word `wbase`
-// ---------------------------------------------------------------------------
-template <bool LDS>
-struct WordSrc {
-    const uint32_t* w;
-    uint32_t wbase;
-    __device__ __forceinline__ uint32_t word(uint32_t i) const {
-        if (LDS) return ((lds_cu32*)w)[i - wbase];
-        return w[i];
-    }
-    // bits [bp, bp + 32), left-aligned
-    __device__ __forceinline__ uint32_t peek32(uint32_t bp) const {
-        const uint32_t wi = bp >> 5, off = bp & 31;
-        const uint32_t w0 = word(wi), w1 = word(wi + 1);
-        return off ? __builtin_amdgcn_alignbit(w0, w1, 32 - off) : w0;
-    }
-    // a `bits`-wide field (1..32) that starts at bit position bp
-    __device__ __forceinline__ uint32_t field(uint64_t bp, uint32_t bits) const {
-        const uint32_t wi = (uint32_t)(bp >> 5), off = (uint32_t)(bp & 31);
-        const uint32_t w0 = word(wi), w1 = word(wi + 1);
-        const uint32_t top = off ? __builtin_amdgcn_alignbit(w0, w1, 32 - off) : w0;
-        return top >> (32 - bits);
-    }
-};
-
-// Decode tables of one block in LDS.  Layout (uint32 words):
-//   lut2[2^lut_bits][2] | canon[99] (+1 pad) | codebook[k4] | symsort[k4]     k4 = k_sym rounded up to 4
-// lut2 pairs the blob's first-level entry with the shared value of its symbol, so a short
-// codeword costs one 64-bit LDS read.  codebook / symsort sit in LDS only when
-// k_sym <= kCodebookLdsMax; otherwise the (rare) long codewords read them from the blob.
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef __attribute__((address_space(3))) const u32x2 lds_cu2;
-
-struct Tables {
-    const uint2* lut2;          // LDS
-    const uint32_t* canon;      // LDS
-    const float* cb;            // LDS when small, else the blob's copy
-    const uint32_t* symsort;    // likewise
-    bool small;                 // k_sym <= kCodebookLdsMax (uniform)
-};
-
-// Code longer than the first-level table: canonical search by length.
-// Returns {(symbol << 6) | length, value bits}.
-__device__ __noinline__ uint2 decode_long(const uint32_t* canon_, const uint32_t* symsort, const float* cb, bool small,
-                                          uint32_t top, uint32_t lut_bits, uint32_t lmax)
-{
-    lds_cu32* canon = (lds_cu32*)canon_;
-    for (uint32_t l = lut_bits + 1; l <= lmax; ++l) {
-        const uint32_t code = top >> (32 - l);
-        const uint32_t rel = code - canon[l];
-        if (rel < canon[33 + l]) {
-            const uint32_t idx = canon[66 + l] + rel;
-            const uint32_t sy = small ? ((lds_cu32*)symsort)[idx] : symsort[idx];
-            const float v = small ? ((lds_cf32*)cb)[sy] : cb[sy];
-            return make_uint2((sy << 6) | l, __float_as_uint(v));
-        }
-    }
-    return make_uint2(lmax ? lmax : 1, 0u);   // unreachable for a validated blob; still makes progress
-}
-
-struct Decoded { uint32_t sym, len; float val; };
-
-__device__ __forceinline__ Decoded decode_symbol(const DevBlob& d, const Tables& t, uint32_t top)
-{
-    const u32x2 raw = ((lds_cu2*)t.lut2)[top >> (32 - d.lut_bits)];
-    uint2 e = make_uint2(raw.x, raw.y);
-    if ((e.x & 63u) == 0) e = decode_long(t.canon, t.symsort, t.cb, t.small, top, d.lut_bits, d.lmax);
-    Decoded r;
-    r.len = e.x & 63u; r.sym = e.x >> 6; r.val = __uint_as_float(e.y);
-    return r;
-}
-
-__device__ __forceinline__ uint32_t table_words_dev(const DevBlob& d)
-{
-    const uint32_t k4 = (d.k_sym + 3u) & ~3u;
-    return ((2u << d.lut_bits) + 100u + (d.k_sym <= kCodebookLdsMax ? 2u * k4 : 0u) + 3u) & ~3u;
-}
-
-// All threads of the block copy the tables; the caller synchronises afterwards.
-__device__ __forceinline__ Tables load_tables(const DevBlob& d, uint32_t* smem)
-{
-    const uint32_t nl = 1u << d.lut_bits;
-    const uint32_t k4 = (d.k_sym + 3u) & ~3u;
-    uint2* s_lut2 = reinterpret_cast<uint2*>(smem);
-    uint32_t* s_canon = smem + 2 * nl;
-    float* s_cb = reinterpret_cast<float*>(s_canon + 100);
-    uint32_t* s_sort = reinterpret_cast<uint32_t*>(s_cb) + k4;
-    for (uint32_t i = threadIdx.x; i < nl; i += blockDim.x) {
-        const uint32_t e = d.lut[i];
-        s_lut2[i] = make_uint2(e, (e & 63u) ? __float_as_uint(d.codebook[e >> 6]) : 0u);
-    }
-    for (uint32_t i = threadIdx.x; i < 99u; i += blockDim.x) s_canon[i] = d.canon[i];
-    Tables t;
-    t.lut2 = s_lut2; t.canon = s_canon; t.small = d.k_sym <= kCodebookLdsMax;
-    if (t.small) {
-        for (uint32_t i = threadIdx.x; i < d.k_sym; i += blockDim.x) { s_cb[i] = d.codebook[i]; s_sort[i] = d.symsort[i]; }
-        t.cb = s_cb; t.symsort = s_sort;
-    } else {
-        t.cb = d.codebook; t.symsort = d.symsort;
-    }
-    return t;
-}
-
-// ---------------------------------------------------------------------------
-// one lane's progress through one chunk
-// ---------------------------------------------------------------------------
-struct ChunkState {
-    uint32_t bp;      // next stream bit
-    uint32_t row;     // HAC: row of the next symbol
-    uint32_t wpos;    // CSC position of the next non-zero this lane will emit
-    uint32_t wend;    // one past the chunk's last non-zero
-};
-
-// HAC: emit non-zeros until wpos reaches `limit` (<= wend).  Zeros only move `row`.
-// When the zero symbol's codeword is the single bit 0, a run of zeros is a run of
-// 0 bits and is skipped with a count-leading-zeros.
-template <class Src, class Emit>
-__device__ __forceinline__ void hac_advance(const DevBlob& d, const Tables& tb, const Src& src,
-                                            ChunkState& st, uint32_t limit, Emit emit)
-{
-    const bool zfast = d.zero_len == 1;
-    while (st.wpos < limit) {
-        uint32_t top = src.peek32(st.bp);
-        if (zfast) {
-            if (top == 0) { st.bp += 32; st.row += 32; continue; }     // a non-zero follows, so the run ends
-            const uint32_t z = (uint32_t)__builtin_clz(top);
-            if (z) {
-                st.bp += z; st.row += z;
-                top = z + d.lmax <= 32 ? top << z : src.peek32(st.bp);
-            }
-        }
-        const Decoded q = decode_symbol(d, tb, top);
-        st.bp += q.len;
-        if (d.has_zero && q.sym == 0) { st.row++; continue; }
-        emit(st.wpos, st.row, q.sym, q.val);
-        st.row++; st.wpos++;
-    }
-}
-
-// HAC, zero symbol = the single bit 0, words staged in LDS.  One pass of the loop per
-// non-zero: 128 stream bits are fetched at once, a count-leading-zeros over the first
-// 64 skips the zero run, and the codeword is taken from the same fetch.  Only a run
-// of 64 or more zeros takes an extra pass.
-template <class Emit>
-__device__ __forceinline__ void hac_advance_zrun(const DevBlob& d, const Tables& tb, const WordSrc<true>& src,
-                                                 ChunkState& st, uint32_t limit, Emit emit)
-{
-    lds_cu32* sw = (lds_cu32*)src.w;
-    while (st.wpos < limit) {
-        const uint32_t wi = (st.bp >> 5) - src.wbase, off = st.bp & 31;
-        const uint32_t w0 = sw[wi], w1 = sw[wi + 1], w2 = sw[wi + 2], w3 = sw[wi + 3];
-        const uint32_t hi = (uint32_t)(((((uint64_t)w0 << 32) | w1) << off) >> 32);
-        const uint32_t mid = (uint32_t)(((((uint64_t)w1 << 32) | w2) << off) >> 32);
-        if ((hi | mid) == 0) { st.bp += 64; st.row += 64; continue; }     // a non-zero follows, so the run ends
-        const uint32_t lo = (uint32_t)(((((uint64_t)w2 << 32) | w3) << off) >> 32);
-        const uint32_t z = hi ? (uint32_t)__builtin_clz(hi) : 32u + (uint32_t)__builtin_clz(mid);
-        const uint32_t x0 = z < 32 ? hi : mid, x1 = z < 32 ? mid : lo;
-        const uint32_t top = (uint32_t)(((((uint64_t)x0 << 32) | x1) << (z & 31)) >> 32);
-        const Decoded q = decode_symbol(d, tb, top);
-        st.row += z;
-        st.bp += z + q.len;
-        emit(st.wpos, st.row, q.sym, q.val);
-        st.row++; st.wpos++;
-    }
-}
-
-// sHAC: every symbol is a non-zero.
-template <class Src, class Emit>
-__device__ __forceinline__ void shac_advance(const DevBlob& d, const Tables& tb, const Src& src,
-                                             ChunkState& st, uint32_t limit, Emit emit)
-{
-    while (st.wpos < limit) {
-        const Decoded q = decode_symbol(d, tb, src.peek32(st.bp));
-        st.bp += q.len;
-        emit(st.wpos, 0u, q.sym, q.val);
-        st.wpos++;
-    }
-}
-
-// sHAC with Rice-coded row gaps: gap codeword, then the value's codeword.  Gap d with
-// q = d >> k: q zeros, a one, k low bits of d; from q = 31 on: 31 zeros, a one, d in 32 bits.
-// st.row is the row the next gap counts from.  Words staged in LDS: one fetch of 128 bits
-// serves the unary part (count-leading-zeros), the remainder and the value's codeword.
-template <class Emit>
-__device__ __forceinline__ void gap_advance(const DevBlob& d, const Tables& tb, const WordSrc<true>& src,
-                                            ChunkState& st, uint32_t limit, Emit emit)
-{
-    lds_cu32* sw = (lds_cu32*)src.w;
-    const uint32_t k = d.rice_k;
-    while (st.wpos < limit) {
-        const uint32_t wi = (st.bp >> 5) - src.wbase, off = st.bp & 31;
-        const uint32_t w0 = sw[wi], w1 = sw[wi + 1], w2 = sw[wi + 2], w3 = sw[wi + 3];
-        const uint32_t hi = (uint32_t)(((((uint64_t)w0 << 32) | w1) << off) >> 32);
-        const uint32_t mid = (uint32_t)(((((uint64_t)w1 << 32) | w2) << off) >> 32);
-        const uint32_t lo = (uint32_t)(((((uint64_t)w2 << 32) | w3) << off) >> 32);
-        const uint32_t z = hi ? (uint32_t)__builtin_clz(hi) : 31u;        // a valid stream has a one within 32 bits
-        const uint32_t s1 = z + 1;                                        // 1..32
-        const uint32_t p0 = (uint32_t)(((((uint64_t)hi << 32) | mid) << s1) >> 32);
-        const uint32_t p1 = (uint32_t)(((((uint64_t)mid << 32) | lo) << s1) >> 32);
-        uint32_t gapv, top, used;
-        if (z < 31) {
-            const uint64_t w = (((uint64_t)p0 << 32) | p1) << k;          // k <= 15
-            gapv = (z << k) | (uint32_t)(((uint64_t)p0 << k) >> 32);
-            top = (uint32_t)(w >> 32);
-            used = s1 + k;
-        } else {
-            gapv = p0; top = p1; used = s1 + 32;
-        }
-        const Decoded q = decode_symbol(d, tb, top);
-        const uint32_t row = st.row + gapv;
-        st.bp += used + q.len;
-        st.row = row + 1;
-        emit(st.wpos, row, q.sym, q.val);
-        st.wpos++;
-    }
-}
-
-// The same from any word source, one field at a time (streams too long to stage, and the
-// test-only decode kernel).
-template <class Src, class Emit>
-__device__ __forceinline__ void gap_advance_slow(const DevBlob& d, const Tables& tb, const Src& src,
-                                                 ChunkState& st, uint32_t limit, Emit emit)
-{
-    const uint32_t k = d.rice_k;
-    while (st.wpos < limit) {
-        const uint32_t hi = src.peek32(st.bp);
-        const uint32_t z = hi ? (uint32_t)__builtin_clz(hi) : 31u;
-        st.bp += z + 1;
-        uint32_t gapv;
-        if (z < 31) {
-            gapv = (z << k) | (k ? src.peek32(st.bp) >> (32 - k) : 0u);
-            st.bp += k;
-        } else {
-            gapv = src.peek32(st.bp);
-            st.bp += 32;
-        }
-        const Decoded q = decode_symbol(d, tb, src.peek32(st.bp));
-        st.bp += q.len;
-        const uint32_t row = st.row + gapv;
-        st.row = row + 1;
-        emit(st.wpos, row, q.sym, q.val);
-        st.wpos++;
-    }
-}
-
-// column that owns chunk g: largest j with colchunk[j] <= g (global memory search)
-__device__ __forceinline__ uint32_t column_of_chunk(const DevBlob& d, uint32_t g)
-{
-    uint32_t lo = 0, hi = d.m;               // invariant: colchunk[lo] <= g < colchunk[hi]
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (d.colchunk[mid] <= g) lo = mid; else hi = mid;
-    }
-    return lo;
-}
 
 // XCD-aware block order: hardware deals consecutive block ids round-robin to the
 // 8 XCDs; this gives every XCD (hence every L2) one contiguous range of columns.
