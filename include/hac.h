@@ -17,6 +17,12 @@
  *        number the values like the HAC alphabet: 0.0 first when it occurs,
  *        then ascending.
  *
+ *   Network blobs (Sect. V-H, V-K): all layers of a network written with one
+ *        shared dictionary, index-map layers sharing its value list; see
+ *        hac_net_encode below.
+ *   Chain of layers (an extension): hac_forward evaluates
+ *        A <- act(A.W_l + b_l) layer after layer; see below.
+ *
  * An extension beyond the paper, selected with hac_opts_t.ri_coding =
  * HAC_RI_RICE: sHAC whose row-index vector ri is replaced by Golomb-Rice coded
  * row gaps written into the stream itself.  For the non-zero at CSC position p
