@@ -99,3 +99,4 @@ def test_dense_route_and_chain_replayed_from_a_graph(hac):
 
         replay_and_compare(hac, lambda X, Y, wsc=wsc: hac.hac_forward(layers, X, Y=Y, workspace=wsc), make_chain_input,
                            f"chain B={Bc}")
+
