@@ -296,3 +296,51 @@ def test_damaged_network_blobs_are_rejected():
     cb = b[int(nb.net.off_codebook):int(nb.net.off_codebook) + 4 * int(nb.net.k_sym)].view(np.float32)
     cb[1], cb[2] = cb[2], cb[1]
     assert lib.hac_net_validate(b.ctypes.data, b.size, 0) == -3
+
+
+def _layer_structs(descs, acts=None):
+    arr = (hac.Layer * len(descs))()
+    for i, d in enumerate(descs):
+        arr[i].desc = C.pointer(d)
+        arr[i].d_blob = 256                      # never dereferenced by the calls below
+        arr[i].activation = 0 if acts is None else acts[i]
+    return arr
+
+
+def test_chain_workspace_and_argument_checks_on_the_host():
+    """What hac_forward decides before it touches the GPU: shapes, workspace, argument errors."""
+    lib = hac.load_library()
+    Ws = small_layers(seed=6, shapes=((300, 200), (200, 120), (120, 10)))
+    nb = hac.hac_net_encode(Ws, (1, 2, 1))
+    descs = nb.layers
+    arr = _layer_structs(descs)
+    # B = 1: a row is its own feature-major copy, so only the two activation buffers remain
+    need1 = lib.hac_forward_workspace_bytes(arr, 3, 1)
+    assert need1 == 2 * 256 * ((4 * 1 * 200 + 255) // 256)
+    # B = 40 -> padded to 64 batch columns; the input of layer 0 is re-laid out, the others arrive feature-major
+    need = lib.hac_forward_workspace_bytes(arr, 3, 40)
+    act = 256 * ((4 * 64 * 200 + 255) // 256)
+    assert need == 2 * act + hac.hac_workspace_bytes(descs[0], 40)
+    # one layer: exactly the dot's workspace
+    assert lib.hac_forward_workspace_bytes(arr, 1, 40) == hac.hac_workspace_bytes(descs[0], 40)
+    assert lib.hac_forward_workspace_bytes(arr, 3, 0) == 0
+    # argument errors (all found before any device work)
+    assert lib.hac_forward_workspace_bytes(None, 3, 8) == 0
+    assert lib.hac_forward_workspace_bytes(arr, 0, 8) == 0 and lib.hac_forward_workspace_bytes(arr, 257, 8) == 0
+    assert lib.hac_forward(arr, 3, 256, 0, 300, 256, 10, None, 0, None) == 0                    # B = 0: nothing to do
+    assert lib.hac_forward(None, 3, 256, 8, 300, 256, 10, None, 0, None) == -1
+    assert lib.hac_forward(arr, 3, None, 8, 300, 256, 10, 256, need, None) == -1                # no X
+    assert lib.hac_forward(arr, 3, 256, 8, 299, 256, 10, 256, need, None) == -1                 # ldx < n
+    assert lib.hac_forward(arr, 3, 256, 8, 300, 256, 9, 256, need, None) == -1                  # ldy < m
+    assert lib.hac_forward(arr, 3, 256, 8, 300, 256, 10, None, 0, None) == -6                   # no workspace
+    assert lib.hac_forward(arr, 3, 256, -1, 300, 256, 10, 256, need, None) == -1
+    swapped = _layer_structs([descs[1], descs[0], descs[2]])
+    assert lib.hac_forward_workspace_bytes(swapped, 3, 8) == 0                                   # shapes do not chain
+    assert lib.hac_forward(swapped, 3, 256, 8, 200, 256, 10, 256, need, None) == -1
+    bad = _layer_structs(descs, acts=[0, 7, 0])
+    assert lib.hac_forward(bad, 3, 256, 8, 300, 256, 10, 256, need, None) == -1
+    arr[2].reserved = 1
+    assert lib.hac_forward(arr, 3, 256, 8, 300, 256, 10, 256, need, None) == -1
+    arr[2].reserved = 0
+    arr[1].d_blob = None
+    assert lib.hac_forward(arr, 3, 256, 8, 300, 256, 10, 256, need, None) == -1
