@@ -213,6 +213,12 @@ typedef struct {
  * lanes that each own batch columns).  Same result up to summation order. */
 #define HAC_LAUNCH_LIST_KERNEL 0x200u
 
+/* Batches of 2 to 8 rows with a short X (n * B' <= 8192, B' = B rounded up to
+ * a power of two) normally run without a re-layout pass and without workspace:
+ * every block copies X into LDS.  This flag sends them the other way (re-layout
+ * in the workspace first).  Same result up to summation order. */
+#define HAC_LAUNCH_NO_X_LDS 0x1000u
+
 /* Force one of the two routes of hac_dot / shac_dot (not both). */
 #define HAC_LAUNCH_SPARSE_ROUTE 0x400u
 #define HAC_LAUNCH_DENSE_ROUTE  0x800u

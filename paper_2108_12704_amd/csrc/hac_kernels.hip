@@ -209,6 +209,14 @@ template <> struct VecLoad<1> { static __device__ __forceinline__ void ld(const 
 template <> struct VecLoad<2> { static __device__ __forceinline__ void ld(const float* p, float* v) { const float2 t = *reinterpret_cast<const float2*>(p); v[0] = t.x; v[1] = t.y; } };
 template <> struct VecLoad<4> { static __device__ __forceinline__ void ld(const float* p, float* v) { const float4 t = *reinterpret_cast<const float4*>(p); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; } };
 
+// the same from a copy of X in LDS
+template <int NB> struct VecLoadLds {
+    static __device__ __forceinline__ void ld(lds_cf32* p, float* v) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) v[i] = p[i];
+    }
+};
+
 __device__ __forceinline__ void wave_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -507,9 +515,14 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
 // NB floats per row of W (B = 1: X itself).  Lane sums are added over the lanes
 // of a column with a segmented shuffle reduction (columns own contiguous lanes),
 // then over chunk batches in LDS (colsum), always in the same order.
-template <bool SHAC, int NB>
+//
+// XLDS: XT is X itself (B x n, row-major, leading dimension ldx) and every block first copies it,
+// feature-major with NB floats per row of W, into LDS behind the tables (x_words words): no
+// re-layout launch, and the rows of X are then fetched from LDS.  For X of at most ~128 KB.
+template <bool SHAC, int NB, bool XLDS>
 __global__ void __launch_bounds__(1024)
-dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __restrict__ Y, uint64_t ldy,
+dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, uint64_t ldx, uint32_t x_words,
+                 float* __restrict__ Y, uint64_t ldy,
                  uint32_t cpw, uint32_t sbuf_words, uint32_t sum_words, uint32_t nblocks, Epilogue epi)
 {
     extern __shared__ uint32_t smem[];
@@ -530,6 +543,17 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __r
             cbit_l = d.colbit[c0 + lane];
         }
     }
+    float* xs = reinterpret_cast<float*>(smem + table_words_dev(d));      // XLDS: [row of W][NB]
+    if (XLDS) {
+        // a thread takes whole rows of W: NB coalesced reads (one per batch row), one contiguous store
+        for (uint32_t r = threadIdx.x; r < d.n; r += blockDim.x) {
+            float v[NB];
+#pragma unroll
+            for (int i = 0; i < NB; ++i) v[i] = (uint32_t)i < B ? XT[(uint64_t)i * ldx + r] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < NB; ++i) xs[(uint64_t)r * NB + i] = v[i];
+        }
+    }
     const Tables tb = load_tables(d, smem);
     __syncthreads();
     if (!live) return;
@@ -541,8 +565,9 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __r
     const uint32_t bit_lo = (uint32_t)__shfl((int)cbit_l, 0, kWave);
     const uint32_t bit_hi = (uint32_t)__shfl((int)cbit_l, (int)ncols, kWave);
 
-    uint32_t* sbuf = smem + table_words_dev(d) + (uint64_t)wib * (sbuf_words + sum_words);
+    uint32_t* sbuf = smem + table_words_dev(d) + (XLDS ? x_words : 0u) + (uint64_t)wib * (sbuf_words + sum_words);
     float* colsum = reinterpret_cast<float*>(sbuf + sbuf_words);          // [column][NB]
+    lds_cf32* xs_lds = (lds_cf32*)xs;
     for (uint32_t i = lane; i < ncols * NB; i += kWave) colsum[i] = 0.0f;
 
     const uint32_t swlo = (bit_lo >> 5) & ~3u;
@@ -595,7 +620,8 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, float* __r
                 }
 #pragma unroll
                 for (int i = 0; i < NB; ++i) a[i] = fmaf(px[i], pv, a[i]);
-                VecLoad<NB>::ld(XT + (uint64_t)row * NB, px);
+                if constexpr (XLDS) VecLoadLds<NB>::ld(xs_lds + row * NB, px);
+                else VecLoad<NB>::ld(XT + (uint64_t)row * NB, px);
                 pv = v;
             };
             if (staged) {
@@ -802,6 +828,54 @@ batch_kern_t pick_batch_kernel(uint32_t nb, bool multipass)
     return multipass ? dot_batch_kernel<SHAC, 4, true> : dot_batch_kernel<SHAC, 4, false>;
 }
 
+// per-wave LDS words for the stream (and ri) words of a wave's columns
+uint32_t default_staging_words(const hac_desc_t* desc, uint32_t cpw)
+{
+    const bool ri_fields = desc->format == HAC_FORMAT_SHAC && desc->ri_coding == HAC_RI_FIELDS;
+    double est = ((double)desc->max_col_bits / 32.0 + 2.0) * cpw + 16.0;
+    if (ri_fields) est += ((double)desc->max_col_nnz * desc->ri_bits / 32.0 + 2.0) * cpw + 12.0;
+    return round_up((uint32_t)(est < 8192.0 ? est : 8192.0), 16);
+}
+
+// Batches of 2 to 8 rows and a short X (at most 32 KB once padded to a power of two of rows):
+// every block keeps its own feature-major copy of X in LDS, so there is no re-layout launch and
+// no workspace.  Measured on 512 x 4096 layers: 7-8 us against 9-10 (4 rows), 10 against 13-14
+// (8 rows); with X of 64 KB or more the copies and the lost occupancy cost more than the launch
+// (4096 x 4096, 8 rows: 25 against 17 us), and 8 rows with more than half a million non-zeros are
+// better off with the list kernel.
+struct XldsPlan { bool use; uint32_t nb, wpb, x_words; size_t lds; };
+
+XldsPlan xlds_plan(const hac_desc_t* desc, int64_t B, const hac_launch_t* launch)
+{
+    XldsPlan p = { false, 0, 0, 0, 0 };
+    if (B < 2 || B > 8 || desc->format == HAC_FORMAT_IM) return p;
+    uint32_t cpw = default_cpw(desc), wpb = 0, sbuf_words = 0;
+    if (launch) {
+        if (launch->variant & (HAC_LAUNCH_NO_X_LDS | HAC_LAUNCH_LIST_KERNEL | HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_DENSE_ROUTE)) return p;
+        if (launch->cols_per_wave) cpw = launch->cols_per_wave;
+        wpb = launch->waves_per_block;
+        sbuf_words = launch->staging_words;
+    }
+    if (!sbuf_words) sbuf_words = default_staging_words(desc, cpw);
+    p.nb = B <= 2 ? 2u : B <= 4 ? 4u : 8u;
+    if (desc->n * p.nb > 8192) return p;
+    if (p.nb == 8 && desc->nnz > (1u << 19)) return p;
+    p.x_words = round_up((uint32_t)desc->n * p.nb, 4);
+    const uint32_t k4 = (desc->k_sym + 3u) & ~3u;
+    const size_t tbl = 4ull * (((2u << desc->lut_bits) + 100u + (desc->k_sym <= kCodebookLdsMax ? 2u * k4 : 0u) + 3u) & ~3u);
+    const size_t per_wave = 4ull * (sbuf_words + round_up(cpw * p.nb, 4));
+    const size_t fixed = tbl + 4ull * p.x_words;
+    const uint32_t nwaves = (uint32_t)((desc->m + cpw - 1) / cpw);
+    if (!wpb) {
+        for (wpb = 16; wpb > 4 && fixed + wpb * per_wave > kLdsLimit; wpb >>= 1) {}
+        while (wpb > 4 && (nwaves + wpb - 1) / wpb < 256) wpb >>= 1;
+    }
+    p.wpb = wpb;
+    p.lds = fixed + (size_t)wpb * per_wave;
+    p.use = p.lds <= kLdsLimit;
+    return p;
+}
+
 int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
              const float* d_X, int64_t B, int64_t ldx, float* d_Y, int64_t ldy,
              void* d_ws, size_t ws_bytes, const hac_launch_t* launch, hac_stream_t stream_,
@@ -827,7 +901,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         reuse_xt = (launch->variant & HAC_LAUNCH_REUSE_XT) != 0;
         list_kernel = (launch->variant & HAC_LAUNCH_LIST_KERNEL) != 0;
         const uint32_t routes = HAC_LAUNCH_SPARSE_ROUTE | HAC_LAUNCH_DENSE_ROUTE;
-        if (launch->variant & ~(HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_LIST_KERNEL | routes)) return HAC_EINVAL;
+        if (launch->variant & ~(HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_LIST_KERNEL | HAC_LAUNCH_NO_X_LDS | routes)) return HAC_EINVAL;
         if ((launch->variant & routes) == routes) return HAC_EINVAL;
         list_cap = launch->list_entries;
         sbuf_words = launch->staging_words;
@@ -874,6 +948,29 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         e = hipGetLastError();
         return e == hipSuccess ? HAC_OK : hip_fail(e);
     }
+    const XldsPlan xp = io->xt_in ? XldsPlan{ false, 0, 0, 0, 0 } : xlds_plan(desc, B, launch);
+    if (xp.use) {
+        // 2 to 8 batch rows and a short X: the block's own copy of X in LDS, lanes multiply what they decode
+        if (!sbuf_words) sbuf_words = default_staging_words(desc, cpw);
+        const uint32_t sum_words = round_up(cpw * xp.nb, 4);
+        const uint32_t nblocks = (nwaves + xp.wpb - 1) / xp.wpb;
+        const uint32_t grid = (nblocks + 7) / 8 * 8;
+        typedef void (*xlds_kern_t)(DevBlob, const float*, uint32_t, uint64_t, uint32_t, float*, uint64_t,
+                                    uint32_t, uint32_t, uint32_t, uint32_t, Epilogue);
+        xlds_kern_t k;
+        if (xp.nb == 2) k = shac ? dot_small_kernel<true, 2, true> : dot_small_kernel<false, 2, true>;
+        else if (xp.nb == 4) k = shac ? dot_small_kernel<true, 4, true> : dot_small_kernel<false, 4, true>;
+        else k = shac ? dot_small_kernel<true, 8, true> : dot_small_kernel<false, 8, true>;
+        if (xp.lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)xp.lds);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        hipLaunchKernelGGL(k, dim3(grid), dim3(xp.wpb * kWave), xp.lds, stream,
+                           d, d_X, (uint32_t)B, (uint64_t)ldx, xp.x_words, d_Y, (uint64_t)ldy, cpw, sbuf_words, sum_words, nblocks, epi);
+        hipError_t e = hipGetLastError();
+        return e == hipSuccess ? HAC_OK : hip_fail(e);
+    }
     const BatchShape bs = batch_shape(B, pass_w, tile_b);
     const float* XT = io->xt_in ? io->xt_in : d_X;           // B = 1: X is its own feature-major copy
     if (B > 1 && !io->xt_in) {
@@ -898,11 +995,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         }
     }
     // per-wave LDS: the stream (and ri) words of the wave's columns, and the list of one batch's non-zeros
-    if (!sbuf_words) {
-        double est = ((double)desc->max_col_bits / 32.0 + 2.0) * cpw + 16.0;
-        if (shac) est += ((double)desc->max_col_nnz * desc->ri_bits / 32.0 + 2.0) * cpw + 12.0;
-        sbuf_words = round_up((uint32_t)(est < 8192.0 ? est : 8192.0), 16);
-    }
+    if (!sbuf_words) sbuf_words = default_staging_words(desc, cpw);
     if (!list_cap) {
         double est = (double)desc->max_col_nnz * cpw;
         const double one_batch = 64.0 * desc->chunk;
@@ -923,18 +1016,19 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         if (lds > kLdsLimit) return HAC_EINVAL;
         const uint32_t nblocks = (nwaves + wpb - 1) / wpb;
         const uint32_t grid = (nblocks + 7) / 8 * 8;
-        typedef void (*small_kern_t)(DevBlob, const float*, uint32_t, float*, uint64_t, uint32_t, uint32_t, uint32_t, uint32_t, Epilogue);
+        typedef void (*small_kern_t)(DevBlob, const float*, uint32_t, uint64_t, uint32_t, float*, uint64_t,
+                                     uint32_t, uint32_t, uint32_t, uint32_t, Epilogue);
         small_kern_t k;
-        if (bs.nb == 1) k = shac ? dot_small_kernel<true, 1> : dot_small_kernel<false, 1>;
-        else if (bs.nb == 2) k = shac ? dot_small_kernel<true, 2> : dot_small_kernel<false, 2>;
-        else k = shac ? dot_small_kernel<true, 4> : dot_small_kernel<false, 4>;
+        if (bs.nb == 1) k = shac ? dot_small_kernel<true, 1, false> : dot_small_kernel<false, 1, false>;
+        else if (bs.nb == 2) k = shac ? dot_small_kernel<true, 2, false> : dot_small_kernel<false, 2, false>;
+        else k = shac ? dot_small_kernel<true, 4, false> : dot_small_kernel<false, 4, false>;
         if (lds > 64 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return hip_fail(e);
         }
         hipLaunchKernelGGL(k, dim3(grid), dim3(wpb * kWave), lds, stream,
-                           d, XT, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, sbuf_words, sum_words, nblocks, epi);
+                           d, XT, (uint32_t)B, (uint64_t)0, 0u, d_Y, (uint64_t)ldy, cpw, sbuf_words, sum_words, nblocks, epi);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? HAC_OK : hip_fail(e);
     }
@@ -991,6 +1085,7 @@ extern "C" size_t hac_workspace_bytes_for(const hac_desc_t* desc, int64_t B, con
     const DenseRoute dr = dense_route(desc, B, launch);
     if (dr.use) return dr.bytes;
     if (B == 1) return 0;                                    // a single row is its own feature-major copy
+    if (xlds_plan(desc, B, launch).use) return 0;            // X is copied into LDS by every block
     const BatchShape bs = batch_shape(B, 32, kDefaultTile);
     return (size_t)4 * (size_t)desc->n * bs.Bp;
 }
@@ -1040,7 +1135,8 @@ struct ChainPlan {
     uint32_t Bp;
     size_t act_bytes;            // one activation buffer (there are two)
     size_t scratch_bytes;        // the largest per-layer workspace
-    bool sparse[256];            // kMaxChain entries
+    bool sparse[256];            // kMaxChain entries: the layer takes the sparse route
+    bool wants_xt[256];          // ... and gathers from a feature-major copy of its input in global memory
 };
 constexpr uint32_t kMaxChain = 256;
 
@@ -1066,11 +1162,12 @@ int plan_chain(const hac_layer_t* layers, uint32_t L, int64_t B, ChainPlan& P)
     for (uint32_t l = 0; l < L; ++l) {
         const hac_desc_t* d = layers[l].desc;
         P.sparse[l] = layer_sparse(d, B);
+        P.wants_xt[l] = P.sparse[l] && !xlds_plan(d, B, nullptr).use;
         if (l + 1 < L) P.act_bytes = std::max<size_t>(P.act_bytes, (size_t)4 * P.Bp * (size_t)d->m);
     }
     P.act_bytes = (P.act_bytes + 255) / 256 * 256;
     for (uint32_t l = 0; l < L; ++l) {
-        const bool fed = l && P.sparse[l - 1] && P.sparse[l];        // input arrives feature-major
+        const bool fed = l && P.sparse[l - 1] && P.wants_xt[l];      // input arrives feature-major
         const size_t need = fed ? 0 : hac_workspace_bytes_for(layers[l].desc, B, nullptr);
         P.scratch_bytes = std::max(P.scratch_bytes, (need + 255) / 256 * 256);
     }
@@ -1111,8 +1208,8 @@ extern "C" int hac_forward(const hac_layer_t* layers, uint32_t n_layers, const f
     for (uint32_t l = 0; l < n_layers; ++l) {
         const hac_layer_t& ly = layers[l];
         const hac_desc_t* d = ly.desc;
-        const bool fed = l && P.sparse[l - 1] && P.sparse[l];
-        const bool feeds = l + 1 < n_layers && P.sparse[l] && P.sparse[l + 1];
+        const bool fed = l && P.sparse[l - 1] && P.wants_xt[l];
+        const bool feeds = l + 1 < n_layers && P.sparse[l] && P.wants_xt[l + 1];
         const float* in = l ? act[(l - 1) & 1] : d_X;
         const int64_t ld_in = l ? (int64_t)d->n : ldx;
         float* out = l + 1 < n_layers ? act[l & 1] : d_Y;

@@ -182,6 +182,45 @@ def test_dot_other_encoder_options(hac):
             check_y(Y, X, W, f.__name__)
 
 
+def test_short_x_kept_in_lds_matches_the_relayout_route(hac):
+    """2 to 8 batch rows over a short X run with X copied into LDS by every block and no workspace;
+    HAC_LAUNCH_NO_X_LDS (0x1000) sends them through the re-layout instead.  Same kernel arithmetic up to
+    4 rows (bitwise equal), another summation order from 5 rows on."""
+    no_lds = hac.Launch(variant=0x1000)
+    for name, W in (("cfg1", workloads.layer(1)), ("cfg2-1000x77", workloads.scaled(2, 1000, 77)),
+                    ("cfg5-640x33", workloads.scaled(5, 640, 33)), ("cfg3-4096x50", workloads.scaled(3, 4096, 50))):
+        n = W.shape[0]
+        for enc, dot, kw in ((hac.hac_encode, hac.hac_dot, {}), (hac.shac_encode, hac.shac_dot, {}),
+                             (hac.shac_encode, hac.shac_dot, dict(ri_coding=hac.RI_RICE))):
+            blob = enc(W, **kw)
+            db = blob.to_device(dev())
+            for B in (2, 3, 4, 5, 8):
+                in_lds = hac.hac_workspace_bytes(blob.desc, B) == 0
+                assert in_lds == (n * (2 if B <= 2 else 4 if B <= 4 else 8) <= 8192), (name, B)
+                assert hac.hac_workspace_bytes(blob.desc, B, no_lds) > 0
+                X = workloads.make_batch(B, n, 60 + B) - np.float32(0.2)
+                Xd = torch.from_numpy(X).to(dev())
+                print(f"[case] x in lds {name} {dot.__name__} {kw} B={B} in_lds={in_lds}", flush=True)
+                Y = dot(db, Xd)
+                Yold = dot(db, Xd, launch=no_lds)
+                torch.cuda.synchronize()
+                check_y(Y, X, W, f"{name} B={B}")
+                check_y(Yold, X, W, f"{name} B={B} re-layout")
+                if B <= 4:
+                    assert torch.equal(Y, Yold), (name, B)
+    # strided X and Y
+    W = workloads.layer(1)
+    db = hac.shac_encode(W).to_device(dev())
+    X = workloads.make_batch(6, W.shape[0], 9)
+    Xp = torch.zeros((6, W.shape[0] + 7), device=dev())
+    Xp[:, :W.shape[0]] = torch.from_numpy(X).to(dev())
+    Yp = torch.full((6, W.shape[1] + 3), -3.0, device=dev())
+    hac.shac_dot(db, Xp[:, :W.shape[0]], Y=Yp[:, :W.shape[1]])
+    torch.cuda.synchronize()
+    check_y(Yp[:, :W.shape[1]], X, W, "strided")
+    assert torch.all(Yp[:, W.shape[1]:] == -3.0)
+
+
 def test_launch_overrides_do_not_change_the_result(hac):
     W = workloads.scaled(5, 900, 77)          # ~360 non-zeros per column
     n, m = W.shape
@@ -273,8 +312,12 @@ def test_error_paths(hac):
     assert e.value.status == -1
     small = torch.empty(256, dtype=torch.uint8, device=dev())
     with pytest.raises(hac.HacError) as e:
-        hac.hac_dot(hb, X, workspace=small)
+        hac.hac_dot(hb, torch.zeros((40, 100), device=dev()), workspace=small)     # 40 rows need a re-laid-out copy
     assert e.value.status == -6
+    with pytest.raises(hac.HacError) as e:
+        hac.hac_dot(hb, X, workspace=small, launch=hac.Launch(variant=0x1000))    # so do 4 rows when X may not go to LDS
+    assert e.value.status == -6
+    assert hac.hac_workspace_bytes(hb.desc, 4) == 0 and hac.hac_workspace_bytes(hb.desc, 4, hac.Launch(variant=0x1000)) > 0
     Y = torch.empty((4, 20), device=dev())
     args = (C.byref(hb.desc), hb.tensor.data_ptr(), X.data_ptr(), 4, 50, Y.data_ptr(), 20, None, 0, None, None)
     assert lib.hac_dot(*args) == -1                        # ldx < n
