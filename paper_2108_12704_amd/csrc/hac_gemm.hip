@@ -255,6 +255,121 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
     }
 }
 
+// ---------------------------------------------------------------------------
+// Small batches (at most 8 rows of X): nothing for the matrix cores to do; the index map is
+// read once, straight through, and every pointer is used for all batch rows.  A block of 256
+// threads owns 256 columns and a range of rows of W: thread (c, g) walks the rows g, g + 4, ...
+// of the range for the four columns 4c .. 4c + 3 (one 4- or 8-byte load per row; a wavefront
+// reads 256 neighbouring pointers of one row), with the range's X values in LDS (one broadcast
+// read per row) and the representatives in LDS.  The four row groups of a block are added in
+// LDS, the row ranges by splitk_reduce_kernel: a fixed order.
+// ---------------------------------------------------------------------------
+constexpr int SB_NB = 8, SB_COLS = 256, SB_GROUPS = 4;
+constexpr uint32_t kSmallMaxRows = 1024;           // rows of W per block (32 KB of X in LDS)
+
+template <typename IdxT> struct Ptr4;
+template <> struct Ptr4<uint8_t> {
+    static __device__ __forceinline__ void ld(const uint8_t* p, uint32_t* out) {
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(p);
+        out[0] = w & 255u; out[1] = (w >> 8) & 255u; out[2] = (w >> 16) & 255u; out[3] = w >> 24;
+    }
+};
+template <> struct Ptr4<uint16_t> {
+    static __device__ __forceinline__ void ld(const uint16_t* p, uint32_t* out) {
+        const uint2 w = *reinterpret_cast<const uint2*>(p);
+        out[0] = w.x & 65535u; out[1] = w.x >> 16; out[2] = w.y & 65535u; out[3] = w.y >> 16;
+    }
+};
+
+template <typename IdxT, bool LUT_LDS>
+__global__ void __launch_bounds__(256)
+index_small_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
+                   const IdxT* __restrict__ idx, uint64_t pitch,
+                   const float* __restrict__ codebook, uint32_t k_sym, uint32_t zero_first,
+                   uint32_t n, uint32_t m, uint32_t rows_per_split, uint32_t tiles_m, uint32_t splits,
+                   float* __restrict__ Y, uint64_t ldy, float* __restrict__ part)
+{
+    extern __shared__ float lds[];
+    float* xs = lds;                                               // [rows_per_split][SB_NB]
+    float* red = xs + (size_t)rows_per_split * SB_NB;              // [SB_GROUPS][SB_NB][SB_COLS]
+    float* lut = red + SB_GROUPS * SB_NB * SB_COLS;                // [k_sym + zero_first] when LUT_LDS
+    const uint32_t tile = blockIdx.x % tiles_m, split = blockIdx.x / tiles_m;
+    const uint32_t c = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const uint32_t j = tile * SB_COLS + 4 * c;                     // first of this thread's four columns
+    const uint32_t r0 = split * rows_per_split;
+    const uint32_t rows = r0 < n ? (n - r0 < rows_per_split ? n - r0 : rows_per_split) : 0u;
+    const uint32_t k_tot = k_sym + zero_first;
+    if (LUT_LDS) {
+        for (uint32_t i = threadIdx.x; i < k_tot; i += 256)
+            lut[i] = (zero_first && i == 0) ? 0.0f : codebook[i - zero_first];
+    }
+    // a thread stages whole rows: SB_NB coalesced reads (one per batch row), one contiguous store
+    for (uint32_t i = threadIdx.x; i < rows; i += 256) {
+        float v[SB_NB];
+#pragma unroll
+        for (int b = 0; b < SB_NB; ++b) v[b] = (uint32_t)b < B ? X[(uint64_t)b * ldx + r0 + i] : 0.0f;
+#pragma unroll
+        for (int b = 0; b < SB_NB; ++b) xs[(size_t)i * SB_NB + b] = v[b];
+    }
+    __syncthreads();
+    auto value_of = [&](uint32_t p) -> float {
+        if (LUT_LDS) return lut[p];
+        return (zero_first && p == 0) ? 0.0f : codebook[p - zero_first];
+    };
+    float acc[4][SB_NB];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int b = 0; b < SB_NB; ++b) acc[u][b] = 0.0f;
+    // the pitch is a multiple of 16 and j of 4: four pointers from j on lie inside the row; those of
+    // columns past m are padding (pointer 0) and their sums are never stored
+    if (j < pitch) {
+        const IdxT* col = idx + (uint64_t)r0 * pitch + j;
+        auto row_step = [&](uint32_t i, const uint32_t* p) {
+            const float* xr = xs + (size_t)i * SB_NB;
+            float x[SB_NB];
+#pragma unroll
+            for (int b = 0; b < SB_NB; ++b) x[b] = xr[b];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float w = value_of(p[u]);
+#pragma unroll
+                for (int b = 0; b < SB_NB; ++b) acc[u][b] = fmaf(w, x[b], acc[u][b]);
+            }
+        };
+        uint32_t i = g;
+        // four rows at a time: their pointers are requested together, so that a thread with few
+        // rows does not pay one trip to memory per row
+        for (; i + 3 * SB_GROUPS < rows; i += 4 * SB_GROUPS) {
+            uint32_t p[4][4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) Ptr4<IdxT>::ld(col + (uint64_t)(i + q * SB_GROUPS) * pitch, p[q]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) row_step(i + q * SB_GROUPS, p[q]);
+        }
+        for (; i < rows; i += SB_GROUPS) {
+            uint32_t p[4];
+            Ptr4<IdxT>::ld(col + (uint64_t)i * pitch, p);
+            row_step(i, p);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int b = 0; b < SB_NB; ++b) red[(g * SB_NB + b) * SB_COLS + 4 * c + u] = acc[u][b];
+    __syncthreads();
+    // thread t adds the four groups of column tile * 256 + t
+    const uint32_t jc = tile * SB_COLS + threadIdx.x;
+    if (jc < m) {
+        for (uint32_t b = 0; b < B; ++b) {
+            float v = red[b * SB_COLS + threadIdx.x];
+            for (int q = 1; q < SB_GROUPS; ++q) v += red[(q * SB_NB + b) * SB_COLS + threadIdx.x];
+            if (splits == 1) Y[(uint64_t)b * ldy + jc] = v;
+            else part[((uint64_t)split * B + b) * m + jc] = v;
+        }
+    }
+}
+
 // Y = part[0] + part[1] + ... in that order (bitwise reproducible).
 __global__ void __launch_bounds__(256)
 splitk_reduce_kernel(const float* __restrict__ part, uint32_t splits, uint32_t B, uint32_t m,
@@ -264,7 +379,13 @@ splitk_reduce_kernel(const float* __restrict__ part, uint32_t splits, uint32_t B
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         float v = part[i];
-        for (uint32_t s = 1; s < splits; ++s) v += part[(uint64_t)s * total + i];
+        uint32_t s = 1;
+        for (; s + 3 < splits; s += 4) {                   // four loads in flight, added in order
+            const float a = part[(uint64_t)s * total + i], b = part[(uint64_t)(s + 1) * total + i];
+            const float c = part[(uint64_t)(s + 2) * total + i], d = part[(uint64_t)(s + 3) * total + i];
+            v += a; v += b; v += c; v += d;
+        }
+        for (; s < splits; ++s) v += part[(uint64_t)s * total + i];
         const uint64_t row = i / m;
         Y[row * ldy + (i - row * m)] = v;
     }
@@ -282,6 +403,23 @@ static size_t index_gemm_lds_bytes(uint32_t k_tot, int rt)
 GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m)
 {
     GemmPlan p;
+    p.small = B <= (uint32_t)SB_NB;
+    if (p.small) {
+        // blocks of 256 columns x a range of rows: about 512 blocks, at most 32 ranges (the pass that
+        // adds them walks them one after the other) unless the rows of a range would not fit LDS
+        const uint32_t tiles_m = (m + SB_COLS - 1) / SB_COLS;
+        uint32_t splits = (512 + tiles_m - 1) / tiles_m;
+        const uint32_t most = (n + 31) / 32, least = (n + kSmallMaxRows - 1) / kSmallMaxRows;
+        if (splits > 32) splits = 32;
+        if (splits > most) splits = most;
+        if (splits < least) splits = least;
+        if (splits < 1) splits = 1;
+        p.steps_per_split = ((n + splits - 1) / splits + 3) / 4 * 4;          // rows per block
+        p.splits = (n + p.steps_per_split - 1) / p.steps_per_split;
+        p.steps = n; p.rt = 0; p.tiles = tiles_m;
+        p.part_bytes = p.splits > 1 ? (size_t)p.splits * B * m * sizeof(float) : 0;
+        return p;
+    }
     const uint64_t tiles_n = (m + BN - 1) / BN;
     const uint32_t steps = (n + BK - 1) / BK;
     // Row tiles per block: the time of a launch goes like (rounds of tiles over the CUs) x (rows per
@@ -359,6 +497,29 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
 {
     const uint32_t tiles_n = (m + BN - 1) / BN;
     const GemmPlan plan = plan_index_gemm(B, n, m);
+    if (plan.small) {
+        if (plan.splits > 1 && !d_part) return hipErrorInvalidValue;
+        if (idx_bits != 8 && idx_bits != 16) return hipErrorInvalidValue;
+        const uint64_t blocks = plan.tiles * plan.splits;
+        if (blocks > 0x7ffffff0ull) return hipErrorInvalidValue;
+        const uint32_t k_tot = k_sym + zero_first;
+        const bool lut_lds = k_tot <= kLutLdsMax;
+        const size_t lds = sizeof(float) * ((size_t)plan.steps_per_split * SB_NB + SB_GROUPS * SB_NB * SB_COLS + (lut_lds ? k_tot : 0));
+        const dim3 grid((uint32_t)blocks);
+#define HAC_LAUNCH_SMALL(T, L)                                                                                       \
+        hipLaunchKernelGGL((index_small_kernel<T, L>), grid, dim3(256), lds, stream, d_X, ldx, B,                    \
+                           static_cast<const T*>(d_idx), pitch, d_codebook, k_sym, zero_first, n, m,                 \
+                           plan.steps_per_split, (uint32_t)plan.tiles, plan.splits, d_Y, ldy, d_part)
+        if (idx_bits == 8) { if (lut_lds) HAC_LAUNCH_SMALL(uint8_t, true); else HAC_LAUNCH_SMALL(uint8_t, false); }
+        else { if (lut_lds) HAC_LAUNCH_SMALL(uint16_t, true); else HAC_LAUNCH_SMALL(uint16_t, false); }
+#undef HAC_LAUNCH_SMALL
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess || plan.splits == 1) return e;
+        const uint64_t total = (uint64_t)B * m;
+        const uint32_t rgrid = (uint32_t)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(rgrid), dim3(256), 0, stream, d_part, plan.splits, B, m, d_Y, ldy);
+        return hipGetLastError();
+    }
     const uint64_t items64 = plan.tiles * plan.splits;
     if (items64 > 0x7ffffff0ull) return hipErrorInvalidValue;
     if (plan.splits > 1 && !d_part) return hipErrorInvalidValue;

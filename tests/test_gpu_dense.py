@@ -58,7 +58,7 @@ def dense_layers():
 
 LAYERS = list(dense_layers())
 IDS = [c[0] for c in LAYERS]
-BATCHES = [1, 5, 64, 127, 128, 129, 300]
+BATCHES = [1, 2, 5, 8, 9, 64, 127, 128, 129, 300]
 
 
 @pytest.mark.parametrize("name,W", LAYERS, ids=IDS)
@@ -79,15 +79,16 @@ def test_im_dot_parity(hac, name, W):
 def test_im_dot_strided_and_unaligned(hac):
     W = workloads.scaled(5, 301, 70)
     db = hac.im_encode(W).to_device(dev())
-    Xbig = torch.from_numpy(workloads.make_batch(40, 310, 2)).to(dev())
-    Ybig = torch.full((40, 90), 3.0, device=dev())
-    for shift in (0, 1, 4):
-        X = Xbig[:, shift:shift + 301]                       # ldx = 310, pointer offset by `shift` floats
-        Y = Ybig[:, 7:77]
-        hac.im_dot(db, X, Y=Y)
-        torch.cuda.synchronize()
-        check_y(Y, X.cpu().numpy(), W, f"shift {shift}")
-        assert torch.all(Ybig[:, :7] == 3.0) and torch.all(Ybig[:, 77:] == 3.0)
+    for rows in (40, 6):                                          # the matrix-core kernel, and the one for small batches
+        Xbig = torch.from_numpy(workloads.make_batch(rows, 310, 2)).to(dev())
+        Ybig = torch.full((rows, 90), 3.0, device=dev())
+        for shift in (0, 1, 4):
+            X = Xbig[:, shift:shift + 301]                       # ldx = 310, pointer offset by `shift` floats
+            Y = Ybig[:, 7:77]
+            hac.im_dot(db, X, Y=Y)
+            torch.cuda.synchronize()
+            check_y(Y, X.cpu().numpy(), W, f"rows {rows} shift {shift}")
+            assert torch.all(Ybig[:, :7] == 3.0) and torch.all(Ybig[:, 77:] == 3.0)
 
 
 @pytest.mark.parametrize("name,W", LAYERS, ids=IDS)
@@ -98,7 +99,7 @@ def test_dense_route_matches_the_oracle(hac, name, W):
              ("hac c=3", hac.hac_dot, hac.hac_encode(W, chunk_nnz=3))]
     for what, f, blob in blobs:
         db = blob.to_device(dev())
-        for B in (1, 33, 128, 200):
+        for B in (1, 3, 8, 9, 33, 128, 200):
             print(f"[case] dense route {what} {name} {W.shape} B={B}", flush=True)
             X = workloads.make_batch(B, n, 3 + B) - np.float32(0.2)
             Y = f(db, torch.from_numpy(X).to(dev()), launch=hac.Launch(variant=DENSE))
