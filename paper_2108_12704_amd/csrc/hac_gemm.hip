@@ -256,8 +256,9 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
 }
 
 // ---------------------------------------------------------------------------
-// Small batches (at most 8 rows of X): nothing for the matrix cores to do; the index map is
-// read once, straight through, and every pointer is used for all batch rows.  A block of 256
+// Small batches (at most 32 rows of X, in groups of 8 along the grid's y): nothing much for the
+// matrix cores to do; the index map is read straight through, once per group of 8 batch rows
+// (from L2 after the first), and every pointer is used for the group's rows.  A block of 256
 // threads owns 256 columns and a range of rows of W: thread (c, g) walks the rows g, g + 4, ...
 // of the range for the four columns 4c .. 4c + 3 (one 4- or 8-byte load per row; a wavefront
 // reads 256 neighbouring pointers of one row), with the range's X values in LDS (one broadcast
@@ -294,6 +295,8 @@ index_small_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
     float* red = xs + (size_t)rows_per_split * SB_NB;              // [SB_GROUPS][SB_NB][SB_COLS]
     float* lut = red + SB_GROUPS * SB_NB * SB_COLS;                // [k_sym + zero_first] when LUT_LDS
     const uint32_t tile = blockIdx.x % tiles_m, split = blockIdx.x / tiles_m;
+    const uint32_t b0 = blockIdx.y * SB_NB;                        // this block's batch rows b0 .. b0 + 7
+    const uint32_t nb = B - b0 < (uint32_t)SB_NB ? B - b0 : (uint32_t)SB_NB;
     const uint32_t c = threadIdx.x & 63, g = threadIdx.x >> 6;
     const uint32_t j = tile * SB_COLS + 4 * c;                     // first of this thread's four columns
     const uint32_t r0 = split * rows_per_split;
@@ -307,7 +310,7 @@ index_small_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
     for (uint32_t i = threadIdx.x; i < rows; i += 256) {
         float v[SB_NB];
 #pragma unroll
-        for (int b = 0; b < SB_NB; ++b) v[b] = (uint32_t)b < B ? X[(uint64_t)b * ldx + r0 + i] : 0.0f;
+        for (int b = 0; b < SB_NB; ++b) v[b] = (uint32_t)b < nb ? X[(uint64_t)(b0 + b) * ldx + r0 + i] : 0.0f;
 #pragma unroll
         for (int b = 0; b < SB_NB; ++b) xs[(size_t)i * SB_NB + b] = v[b];
     }
@@ -361,11 +364,11 @@ index_small_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
     // thread t adds the four groups of column tile * 256 + t
     const uint32_t jc = tile * SB_COLS + threadIdx.x;
     if (jc < m) {
-        for (uint32_t b = 0; b < B; ++b) {
+        for (uint32_t b = 0; b < nb; ++b) {
             float v = red[b * SB_COLS + threadIdx.x];
             for (int q = 1; q < SB_GROUPS; ++q) v += red[(q * SB_NB + b) * SB_COLS + threadIdx.x];
-            if (splits == 1) Y[(uint64_t)b * ldy + jc] = v;
-            else part[((uint64_t)split * B + b) * m + jc] = v;
+            if (splits == 1) Y[(uint64_t)(b0 + b) * ldy + jc] = v;
+            else part[((uint64_t)split * B + b0 + b) * m + jc] = v;
         }
     }
 }
@@ -403,12 +406,13 @@ static size_t index_gemm_lds_bytes(uint32_t k_tot, int rt)
 GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m)
 {
     GemmPlan p;
-    p.small = B <= (uint32_t)SB_NB;
+    p.small = B <= 4u * SB_NB;
     if (p.small) {
         // blocks of 256 columns x a range of rows: about 512 blocks, at most 32 ranges (the pass that
         // adds them walks them one after the other) unless the rows of a range would not fit LDS
         const uint32_t tiles_m = (m + SB_COLS - 1) / SB_COLS;
-        uint32_t splits = (512 + tiles_m - 1) / tiles_m;
+        const uint32_t groups = (B + SB_NB - 1) / SB_NB;
+        uint32_t splits = (512 + tiles_m * groups - 1) / (tiles_m * groups);
         const uint32_t most = (n + 31) / 32, least = (n + kSmallMaxRows - 1) / kSmallMaxRows;
         if (splits > 32) splits = 32;
         if (splits > most) splits = most;
@@ -505,7 +509,7 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
         const uint32_t k_tot = k_sym + zero_first;
         const bool lut_lds = k_tot <= kLutLdsMax;
         const size_t lds = sizeof(float) * ((size_t)plan.steps_per_split * SB_NB + SB_GROUPS * SB_NB * SB_COLS + (lut_lds ? k_tot : 0));
-        const dim3 grid((uint32_t)blocks);
+        const dim3 grid((uint32_t)blocks, (B + SB_NB - 1) / SB_NB);
 #define HAC_LAUNCH_SMALL(T, L)                                                                                       \
         hipLaunchKernelGGL((index_small_kernel<T, L>), grid, dim3(256), lds, stream, d_X, ldx, B,                    \
                            static_cast<const T*>(d_idx), pitch, d_codebook, k_sym, zero_first, n, m,                 \
