@@ -333,6 +333,10 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
     const uint32_t c0 = wave * cpw;
     const uint32_t tile_b = gw * NB * npass;                 // batch columns per block
     if (tile * tile_b >= B) return;                          // padding of the grid, or a tile of padding only
+    // passes that hold at least one real batch row: the last tile (or a batch that is not a power
+    // of two) ends before the block's npass panels do
+    const uint32_t rows_here = B - tile * tile_b < tile_b ? B - tile * tile_b : tile_b;
+    const uint32_t live_passes = MP ? (rows_here + gw * NB - 1) / (gw * NB) : 1u;
     const bool live = c0 < d.m;
     HAC_MARK(0);
     // Per-column index of this wave's columns: lane l keeps column c0 + l (l <= ncols).
@@ -351,7 +355,7 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
     __syncthreads();
     if (!live) {
         // sync_passes: every wave of the block meets at a barrier once per pass (see accumulate)
-        if (MP && sync_passes) for (uint32_t p = 0; p < npass; ++p) __syncthreads();
+        if (MP && sync_passes) for (uint32_t p = 0; p < live_passes; ++p) __syncthreads();
         return;
     }
     HAC_MARK(1);
@@ -401,7 +405,7 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
     // hold partial sums of this column in `part`; `last`: the column ends here, so the sums are
     // reduced over the lane groups and stored, else they are parked in `part`.
     auto accumulate = [&](uint32_t winbase, uint32_t hi, bool carried, bool last) {
-        const uint32_t passes = MP ? npass : 1u;
+        const uint32_t passes = live_passes;
         for (uint32_t p = 0; p < passes; ++p) {
             // Keeping the block's waves on the same pass keeps the panels of XT they gather from few
             // enough to stay in L2.  Only set when every wave calls this exactly once (one column per
