@@ -985,7 +985,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         XT = xt;
         if (!reuse_xt) {
             if (bs.gw * bs.nb == 32) {
-                dim3 grid((d.n + 127) / 128, bs.Bp / 32);
+                dim3 grid((d.n + 127) / 128, (uint32_t)((B + 31) / 32));     // panels of padding only are never read
                 const uint32_t vec = (reinterpret_cast<uintptr_t>(d_X) % 16 == 0 && ldx % 4 == 0) ? 1u : 0u;
                 hipLaunchKernelGGL(transpose_panel32_kernel, grid, dim3(256), 0, stream,
                                    d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt, vec);

@@ -221,6 +221,23 @@ def test_short_x_kept_in_lds_matches_the_relayout_route(hac):
     assert torch.all(Yp[:, W.shape[1]:] == -3.0)
 
 
+def test_workspace_left_overs_do_not_reach_the_result(hac):
+    """Panels of the re-laid-out X that hold only padding rows are neither written nor read: a
+    workspace full of NaN must not show in Y (batches that are not a multiple of 32 or of 256)."""
+    W = workloads.scaled(3, 900, 130)
+    n = W.shape[0]
+    for enc, dot in ((hac.hac_encode, hac.hac_dot), (hac.shac_encode, hac.shac_dot)):
+        blob = enc(W)
+        db = blob.to_device(dev())
+        for B in (9, 33, 70, 129, 257, 300):
+            X = workloads.make_batch(B, n, 80 + B)
+            ws = torch.full((hac.hac_workspace_bytes(blob.desc, B) // 4,), float("nan"), device=dev())
+            Y = dot(db, torch.from_numpy(X).to(dev()), workspace=ws.view(torch.uint8))
+            torch.cuda.synchronize()
+            assert not torch.isnan(Y).any(), (dot.__name__, B)
+            check_y(Y, X, W, f"{dot.__name__} B={B}")
+
+
 def test_launch_overrides_do_not_change_the_result(hac):
     W = workloads.scaled(5, 900, 77)          # ~360 non-zeros per column
     n, m = W.shape
