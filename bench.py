@@ -227,6 +227,27 @@ def extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, iters):
     out["chain_vgg16_fc"] = {"layers": [list(w.shape) for w in Ws], "formats": fmts,
                              "network_blob_bytes": nb.nbytes, "separate_blob_bytes": sum(b.nbytes for b in own),
                              "calls": chain}
+    # the paper's own timing set-up (Sect. V-G): 8 input vectors against the three fully connected
+    # matrices of VGG19 (synthetic layers of those shapes, k = 32), every format of this library
+    # beside the vendor's dense GEMM on the decoded matrix; psi = stored bytes / dense bytes
+    shapes = []
+    for (n_, m_) in ((512, 4096), (4096, 4096), (4096, 10)):
+        for prune in (0.9, 0.99):
+            Wp = workloads.make_layer(n_, m_, 0.02, prune, 32, "uniform", 4242)
+            Xp = torch.from_numpy(workloads.make_batch(8, n_, 3)).to(dev)
+            Yp = torch.empty((8, m_), dtype=torch.float32, device=dev)
+            row = {"shape": [n_, m_], "pruned": prune}
+            for name, enc, dot in (("hac", hac.hac_encode, hac.hac_dot), ("shac", hac.shac_encode, hac.shac_dot),
+                                   ("im", hac.im_encode, hac.im_dot)):
+                b_ = enc(Wp)
+                db_ = b_.to_device(dev)
+                ws_ = torch.empty(max(hac.hac_workspace_bytes(b_.desc, 8), 256), dtype=torch.uint8, device=dev)
+                row[name + "_us"] = round(1e3 * time_region(torch, lambda i: dot(db_, Xp, Y=Yp, workspace=ws_), iters, 5, use_graph, 8), 2)
+                row[name + "_psi"] = round(b_.nbytes / (4.0 * n_ * m_), 4)
+            Wpd = torch.from_numpy(Wp).to(dev)
+            row["dense_fp32_matmul_us"] = round(1e3 * time_region(torch, lambda i: torch.matmul(Xp, Wpd, out=Yp), iters, 5, use_graph, 8), 2)
+            shapes.append(row)
+    out["paper_shapes_8_vectors"] = shapes
     # GPU context: the same product with W decompressed to dense fp32 (torch.matmul, the vendor's
     # GEMM) and as an uncompressed CSR matrix (torch.sparse, the vendor's SpMM); neither is the
     # paper's method, both need W in HBM at 4 bytes (dense) or 8 bytes (CSR) per stored entry
