@@ -146,7 +146,7 @@ def kernel_name(fmt, B, dense=False, idx_bits=8):
         # (pointer type, table in LDS, row tiles per block, aligned X): the last three depend on the launch
         return f"index_gemm_kernel<unsigned {'char' if idx_bits == 8 else 'short'}, ...>"
     if B <= 4:
-        return f"dot_small_kernel<{shac}, {1 if B == 1 else 2 if B == 2 else 4}>"
+        return f"dot_small_kernel<{shac}, {1 if B == 1 else 2 if B == 2 else 4}, false>"
     return f"dot_batch_kernel<{shac}, 4, {'true' if B > 32 else 'false'}>"
 
 
