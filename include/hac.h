@@ -380,9 +380,10 @@ int hac_encode_dev(uint32_t format, const float *d_W, int64_t n, int64_t m, int6
                    void *d_ws, size_t ws_bytes, hac_stream_t stream);
 
 /* Bytes of device workspace hac_dot / shac_dot need for a batch of B rows with
- * default launch settings (0 when none is needed).  The workspace holds X re-laid
- * out feature-major, or, on the dense route (see hac_dot), the decoded index map
- * of W.  A launch that forces the other route may need more: size the workspace
+ * default launch settings (0 when none is needed: a single row, or a few rows
+ * over a short X, see HAC_LAUNCH_NO_X_LDS).  The workspace holds X re-laid out
+ * feature-major, or, on the dense route (see hac_dot), the decoded index map
+ * of W.  A launch that forces another way may need more: size the workspace
  * with hac_workspace_bytes_for(). */
 size_t hac_workspace_bytes(const hac_desc_t *desc, int64_t B);
 size_t hac_workspace_bytes_for(const hac_desc_t *desc, int64_t B, const hac_launch_t *launch);
@@ -452,11 +453,12 @@ int hac_forward(const hac_layer_t *layers, uint32_t n_layers,
                 const float *d_X, int64_t B, int64_t ldx, float *d_Y, int64_t ldy,
                 void *d_ws, size_t ws_bytes, hac_stream_t stream);
 
-/* Y = X . W for an index-map blob (Sect. III-C1): pointers are expanded through
- * the representatives tile by tile and multiplied on the matrix cores (fp32 in,
- * fp32 accumulate).  The workspace (hac_workspace_bytes(), 0 for large batches)
- * holds partial tiles when the K loop is split; launch must be NULL.  Otherwise
- * as hac_dot. */
+/* Y = X . W for an index-map blob (Sect. III-C1).  Up to 32 rows of X the map is
+ * streamed once per group of 8 rows and multiplied by vector FMAs; beyond that,
+ * pointers are expanded through the representatives tile by tile and multiplied
+ * on the matrix cores (fp32 in, fp32 accumulate).  The workspace
+ * (hac_workspace_bytes(), 0 for large batches) holds partial sums when the rows
+ * of W are split over blocks; launch must be NULL.  Otherwise as hac_dot. */
 int im_dot(const hac_desc_t *desc, const void *d_blob,
            const float *d_X, int64_t B, int64_t ldx,
            float *d_Y, int64_t ldy,
