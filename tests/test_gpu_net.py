@@ -256,7 +256,7 @@ def test_chain_argument_checks(hac):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("B", [1, 32, 256])
+@pytest.mark.parametrize("B", [1, 3, 6, 32, 256])
 def test_chain_full_size_vgg19_block(hac, B):
     # the fully connected block whose matrices the paper times (512x4096, 4096x4096, 4096x10)
     Ws, bs = workloads.network("vgg19-fc")
