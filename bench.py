@@ -39,6 +39,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0                 # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3         # MI355X dense fp32 matrix peak
+L2_GATHER_PEAK_TBPS = round(64 * 256 * 2.4e9 / 1e12, 1)      # 39.3: what the 256 L1s can take from the L2s
 LLC_BYTES = 256 << 20                 # last-level (Infinity) cache to rotate past
 
 
@@ -428,6 +429,14 @@ def main():
             "traffic": traffic,
             "launch_ms": dom["kernel_ms"], "algorithmic_bytes": dom["bytes"],
         }
+        # What binds this kernel in practice is not HBM but the vector memory path from the L2s: every
+        # non-zero fetches 4 bytes of X per (padded) batch column.  Peak: 64 bytes per clock and CU from
+        # L1, 256 CUs at 2.4 GHz.
+        Bpad = (dom["B"] + 31) // 32 * 32 if dom["B"] > 4 else dom["B"]
+        gather = 4.0 * int(dom_desc.nnz) * Bpad
+        roofline["l2_gather"] = {"bytes": int(gather), "achieved_TBps": round(gather / dom["kernel_ms"] / 1e9, 2),
+                                 "peak_TBps": L2_GATHER_PEAK_TBPS,
+                                 "frac": round(gather / dom["kernel_ms"] / 1e9 / L2_GATHER_PEAK_TBPS, 4)}
 
     out = {
         "metric": "compressed X.W throughput: algorithmic HBM GB/s", "value": round(value, 2), "unit": "GB/s",
