@@ -314,7 +314,9 @@ __device__ __forceinline__ void stage_words(uint32_t* dst, const uint32_t* src, 
 // words per wave for partial sums of a column that does not fit one list window
 // (npass * 64 * NB, or 0 when the launch guarantees that no column is split).
 // MP: several passes (npass > 1); the single-pass variant has no pass loop and no barrier.
-template <bool SHAC, int NB, bool MP>
+// EPI: the epilogue (bias, max(., 0), feature-major output) is compiled in; a plain product runs
+// the variant without it, which needs fewer registers (the single-pass kernel would spill one).
+template <bool SHAC, int NB, bool MP, bool EPI>
 __global__ void __launch_bounds__((BatchTraits<NB>::kMaxThreads))
 dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t B,
                  float* __restrict__ Y, uint64_t ldy, uint32_t cpw, uint32_t gw, uint32_t npass,
@@ -414,7 +416,9 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
             float a[NB];
 #pragma unroll
             for (int i = 0; i < NB; ++i) a[i] = (carried && part_words) ? part[(p * NB + i) * kWave + lane] : 0.0f;
-            if (t < hi) fma_entries<NB, BatchTraits<NB>::kPipe>(list, winbase, t, hi, ng, grp, xt + p * panel, pass_w, a);
+            // (the single-pass kernel with the epilogue compiled in keeps one fetch fewer in flight: with ten it spills)
+            constexpr int kPipe = BatchTraits<NB>::kPipe - ((EPI && !MP && NB == 4) ? 1 : 0);
+            if (t < hi) fma_entries<NB, kPipe>(list, winbase, t, hi, ng, grp, xt + p * panel, pass_w, a);
             if (last) {
 #pragma unroll
                 for (int i = 0; i < NB; ++i) {
@@ -422,10 +426,14 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
                     for (uint32_t off = 32; off >= gw; off >>= 1) v += __shfl_xor(v, (int)off, kWave);
                     const uint32_t b = boff + p * pass_w + i;
                     if (grp == 0) {
-                        if (epi.yt)
-                            epi.yt[((uint64_t)(b / pass_w) * d.m + cc) * pass_w + (b % pass_w)] =
-                                b < B ? epilogue_apply(epi, v, cc) : 0.0f;
-                        else if (b < B) Y[(uint64_t)b * ldy + cc] = epilogue_apply(epi, v, cc);
+                        if constexpr (EPI) {
+                            if (epi.yt)
+                                epi.yt[((uint64_t)(b / pass_w) * d.m + cc) * pass_w + (b % pass_w)] =
+                                    b < B ? epilogue_apply(epi, v, cc) : 0.0f;
+                            else if (b < B) Y[(uint64_t)b * ldy + cc] = epilogue_apply(epi, v, cc);
+                        } else {
+                            if (b < B) Y[(uint64_t)b * ldy + cc] = v;
+                        }
                     }
                 }
             } else if (part_words) {                       // always true here: the host sizes `part` whenever a split can occur
@@ -824,12 +832,12 @@ void launch_bias_act(float* d_Y, uint32_t B, uint32_t m, uint64_t ldy, const flo
     hipLaunchKernelGGL(bias_act_kernel, dim3(grid), dim3(256), 0, stream, d_Y, B, m, ldy, bias, relu);
 }
 
-template <bool SHAC>
+template <bool SHAC, bool EPI>
 batch_kern_t pick_batch_kernel(uint32_t nb, bool multipass)
 {
-    if (nb == 1) return dot_batch_kernel<SHAC, 1, false>;
-    if (nb == 2) return dot_batch_kernel<SHAC, 2, false>;
-    return multipass ? dot_batch_kernel<SHAC, 4, true> : dot_batch_kernel<SHAC, 4, false>;
+    if (nb == 1) return dot_batch_kernel<SHAC, 1, false, EPI>;
+    if (nb == 2) return dot_batch_kernel<SHAC, 2, false, EPI>;
+    return multipass ? dot_batch_kernel<SHAC, 4, true, EPI> : dot_batch_kernel<SHAC, 4, false, EPI>;
 }
 
 // per-wave LDS words for the stream (and ri) words of a wave's columns
@@ -1066,7 +1074,10 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     const uint64_t items = (uint64_t)nblocks * bs.tiles;
     if (items > 0x7ffffff0ull) return HAC_EINVAL;
     const uint32_t grid = (uint32_t)((items + 7) / 8 * 8);
-    batch_kern_t k = shac ? pick_batch_kernel<true>(bs.nb, bs.npass > 1) : pick_batch_kernel<false>(bs.nb, bs.npass > 1);
+    const bool with_epilogue = io->bias || io->relu || io->yt_out;
+    batch_kern_t k = with_epilogue
+        ? (shac ? pick_batch_kernel<true, true>(bs.nb, bs.npass > 1) : pick_batch_kernel<false, true>(bs.nb, bs.npass > 1))
+        : (shac ? pick_batch_kernel<true, false>(bs.nb, bs.npass > 1) : pick_batch_kernel<false, false>(bs.nb, bs.npass > 1));
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
