@@ -148,7 +148,7 @@ def kernel_name(fmt, B, dense=False, idx_bits=8):
         return f"index_gemm_kernel<unsigned {'char' if idx_bits == 8 else 'short'}, ...>"
     if B <= 4:
         return f"dot_small_kernel<{shac}, {1 if B == 1 else 2 if B == 2 else 4}, false>"
-    return f"dot_batch_kernel<{shac}, 4, {'true' if B > 32 else 'false'}>"
+    return f"dot_batch_kernel<{shac}, 4, {'true' if B > 32 else 'false'}, false>"
 
 
 def extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, iters):
