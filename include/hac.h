@@ -39,7 +39,7 @@
  *     row-major fp32 with leading dimensions ldx >= n, ldy >= m (in elements).
  *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
  *     memory of the current device.  The library never allocates or frees
- *     device memory and never synchronises a stream.
+ *     device memory; only hac_encode_dev synchronises a stream (it says so).
  *   - Every function returns HAC_OK (0) or a negative hac_status; nothing
  *     throws across this boundary.  No global mutable state; calls on distinct
  *     arguments may run concurrently from several threads.

@@ -301,6 +301,47 @@ def test_results_are_bitwise_reproducible(hac):
             assert torch.equal(a, b)
 
 
+def test_calls_from_several_threads_on_their_own_streams(hac):
+    # the header promises that calls on distinct arguments may run concurrently: four host threads,
+    # each with its own stream, blob, X, Y and workspace, must each reproduce the single-thread bits
+    import threading
+    jobs = []
+    for t, (enc, f, B) in enumerate(((hac.hac_encode, hac.hac_dot, 1), (hac.shac_encode, hac.shac_dot, 3),
+                                     (hac.hac_encode, hac.hac_dot, 40), (hac.shac_encode, hac.shac_dot, 300))):
+        W = workloads.scaled(4, 1500 + 100 * t, 90 + t)
+        blob = enc(W)
+        db = blob.to_device(dev())
+        X = torch.from_numpy(workloads.make_batch(B, W.shape[0], 50 + t)).to(dev())
+        ws = torch.empty(max(hac.hac_workspace_bytes(blob.desc, B), 256), dtype=torch.uint8, device=dev())
+        expect = f(db, X, workspace=ws).clone()
+        torch.cuda.synchronize()
+        check_y(expect, X.cpu().numpy(), W, f"{f.__name__} B={B}")
+        jobs.append((f, db, X, ws, expect, torch.cuda.Stream()))
+    failures = []
+
+    def worker(f, db, X, ws, expect, stream):
+        try:
+            Y = torch.empty_like(expect)
+            for _ in range(25):
+                Y.fill_(float("nan"))
+                stream.wait_stream(torch.cuda.current_stream())
+                f(db, X, Y=Y, workspace=ws, stream=stream)
+                stream.synchronize()
+                if not torch.equal(Y, expect):
+                    failures.append(f.__name__)
+                    return
+        except Exception as e:                            # a thread's exception would otherwise be lost
+            failures.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=j) for j in jobs]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not failures, failures
+
+
 def test_strided_x_and_y(hac):
     W = workloads.scaled(1, 200, 40)
     Xbig = torch.from_numpy(workloads.make_batch(16, 260, 4)).to(dev())

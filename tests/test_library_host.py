@@ -491,6 +491,30 @@ def test_invalid_arguments():
     lib.hac_free(None)
 
 
+def test_encoders_run_concurrently_from_threads():
+    # no global mutable state: eight threads encoding different layers (the foreign calls release
+    # the interpreter lock) must produce the bytes of the same encodes done one after the other
+    import threading
+    work = []
+    for t in range(8):
+        W = workloads.make_layer(300 + 17 * t, 40 + t, 0.02, 0.8, 8 + t, "uniform", 900 + t)
+        enc = (hac.hac_encode, hac.shac_encode, hac.im_encode)[t % 3]
+        work.append((enc, W, enc(W).data.tobytes()))
+    wrong = []
+
+    def worker(enc, W, expect):
+        for _ in range(5):
+            if enc(W).data.tobytes() != expect:
+                wrong.append(enc.__name__)
+
+    threads = [threading.Thread(target=worker, args=w) for w in work]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not wrong, wrong
+
+
 def test_negative_zero_is_stored_as_zero():
     W = np.array([[-0.0, 1.0], [0.0, -0.0]], dtype=np.float32)
     for enc in (hac.hac_encode, hac.shac_encode):
