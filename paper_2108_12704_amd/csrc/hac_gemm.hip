@@ -13,13 +13,18 @@
 // (RT = 2..8, chosen per launch so that the tiles fill the 256 CUs evenly) and
 // walks K = n in steps of 32; wavefront w owns the 32 columns [32 w, 32 w + 32)
 // of the tile and all its rows, as RT MFMA tiles (16 RT accumulator registers).
-// LDS holds the X tile k-major (lanes read 32 consecutive batch rows of one k)
-// and the decoded W tile k-major (32 consecutive columns of one k); both are
-// double buffered, the next tile's global loads are issued before the MFMA loop
-// of the current one and stored during its second half.
+// LDS holds the X tile row-major (a batch row's 32 k values side by side, rows 36
+// floats apart) and the decoded W tile k-major (32 consecutive columns of one k);
+// both are double buffered, the next tile's global loads are issued before the
+// MFMA loop of the current one and stored during its second half.
 // Lane layout of the instruction (checked on the device): A operand lane l holds
 // A[i = l % 32][k = l / 32], B operand lane l holds B[k = l / 32][j = l % 32],
 // accumulator register v of lane l is D[(v % 4) + 8 (v / 4) + 4 (l / 32)][l % 32].
+// The order of k inside a step is free as long as both operands agree: matrix
+// instruction kk of a step multiplies k = kk (lanes 0..31) and k = 16 + kk (lanes
+// 32..63), so a lane's 16 A values of a step are 16 consecutive floats of its row:
+// four 128-bit LDS reads instead of sixteen 32-bit ones, and the thread that
+// fetched four consecutive k of a row from X stores them with one 128-bit write.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -29,6 +34,8 @@ namespace {
 
 constexpr int BN = 128, BK = 32;
 constexpr int LDB = BN + 4;                        // LDS row pitch of the W tile (floats)
+constexpr int LDA = BK + 4;                        // LDS row pitch of the X tile: 36 floats, so that 16 lanes'
+                                                   // 128-bit accesses to 16 rows fall on 64 different banks
 constexpr int kMinRT = 2, kMaxRT = 8;              // row tiles of 32 per block
 constexpr uint32_t kLutLdsMax = 4096;              // representatives kept in LDS
 
@@ -54,10 +61,10 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
                   uint32_t tiles_n, uint32_t tiles, uint32_t x_vec,
                   uint32_t splits, uint32_t steps_per_split, float* __restrict__ part)
 {
-    constexpr int BM = 32 * RT, LDA = BM + 4;
+    constexpr int BM = 32 * RT;
     extern __shared__ float lds[];
-    float* As = lds;                                   // [2][BK][LDA]
-    float* Bs = lds + 2 * BK * LDA;                    // [2][BK][LDB]
+    float* As = lds;                                   // [2][BM][LDA]
+    float* Bs = lds + 2 * BM * LDA;                    // [2][BK][LDB]
     float* lut = Bs + 2 * BK * LDB;                    // [k_sym + zero_first] when LUT_LDS
     // work item = (tile, K split); with more than one split a block writes its partial tile to
     // part[split][B][m] and a second kernel adds the splits in order
@@ -85,17 +92,16 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
     struct Stage { float4 ra[RT]; IdxRegs<IdxT> rb; };
     const uint32_t a_row = t >> 3, a_kq = t & 7;       // rows a_row + 32 r, k = 4 a_kq .. 4 a_kq + 3
     const uint32_t b_k = t >> 3, b_seg = t & 7;        // idx row b_k, columns 16 b_seg .. 16 b_seg + 15
-    // Rows past B and index columns past the pitch are read from a clamped, valid address and
-    // masked when they are stored to LDS: a K step that lies wholly inside n then issues the same
-    // loads on every path, and the wait before a tile's stores can leave the younger tile's loads
-    // in flight.  Only the last, partial K step takes the guarded path.
-    bool row_ok[RT];
+    // Rows past B and index columns past the pitch are read from a clamped, valid address: a K
+    // step that lies wholly inside n then issues the same loads on every path, and the wait before
+    // a tile's stores can leave the younger tile's loads in flight.  A row past B multiplies a copy
+    // of row B - 1; rows of the product are independent and those are never stored.  Only the
+    // last, partial K step takes the guarded path.
     const float* xrow[RT];
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
         const uint32_t row = m0 + a_row + 32 * r;
-        row_ok[r] = row < B;
-        xrow[r] = X + (uint64_t)(row_ok[r] ? row : B - 1) * ldx + 4 * a_kq;
+        xrow[r] = X + (uint64_t)(row < B ? row : B - 1) * ldx + 4 * a_kq;
     }
     const bool col_ok = n0 + 16 * b_seg < pitch;
     const IdxT* icol = idx + (col_ok ? n0 + 16 * b_seg : 0);
@@ -139,15 +145,12 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
     };
     // registers -> LDS in pieces, so that the work can be spread over the MFMA loop
     auto store_a = [&](uint32_t buf, int r, const Stage& st) {          // rows a_row + 32 r of the X tile
-        float* a = As + buf * BK * LDA;
-        const uint32_t row = a_row + 32 * r;
-        a[(4 * a_kq + 0) * LDA + row] = row_ok[r] ? st.ra[r].x : 0.0f;
-        a[(4 * a_kq + 1) * LDA + row] = row_ok[r] ? st.ra[r].y : 0.0f;
-        a[(4 * a_kq + 2) * LDA + row] = row_ok[r] ? st.ra[r].z : 0.0f;
-        a[(4 * a_kq + 3) * LDA + row] = row_ok[r] ? st.ra[r].w : 0.0f;
+        float* a = As + buf * BM * LDA + (a_row + 32 * r) * LDA + 4 * a_kq;
+        *reinterpret_cast<float4*>(a) = make_float4(st.ra[r].x, st.ra[r].y, st.ra[r].z, st.ra[r].w);
     };
-    auto store_b = [&](uint32_t buf, int q, const Stage& st) {          // columns 16 b_seg + 4 q .. + 3 of the W tile
-        float* b = Bs + buf * BK * LDB + b_k * LDB + 16 * b_seg;
+    // pointers -> values (columns 16 b_seg + 4 q .. + 3 of the W tile), then values -> LDS: two steps,
+    // so that the table lookups can be issued some matrix instructions before their results are stored
+    auto lookup_b = [&](int q, const Stage& st) -> float4 {
         float4 o;
         if constexpr (sizeof(IdxT) == 1) {
             const uint32_t u = q == 0 ? st.rb.v[0].x : q == 1 ? st.rb.v[0].y : q == 2 ? st.rb.v[0].z : st.rb.v[0].w;
@@ -159,6 +162,10 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
             o.x = value_of(u0 & 65535u); o.y = value_of(u0 >> 16);
             o.z = value_of(u1 & 65535u); o.w = value_of(u1 >> 16);
         }
+        return o;
+    };
+    auto store_b = [&](uint32_t buf, int q, const float4& o) {
+        float* b = Bs + buf * BK * LDB + b_k * LDB + 16 * b_seg;
         *reinterpret_cast<float4*>(b + 4 * q) = o;
     };
 
@@ -176,40 +183,60 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
     // other buffer (nobody reads it during this step), a piece at a time between the matrix
     // instructions.
     auto multiply = [&](uint32_t buf, bool store, const Stage& st) {
-        const float* a = As + buf * BK * LDA + l32 + half * LDA;
-        const float* b = Bs + buf * BK * LDB + wave * 32 + l32 + half * LDB;
-        // operands of step kk + 1 are fetched from LDS before the matrix instructions of step kk issue
-        float av[RT], bv = b[0];
+        const float* a = As + buf * BM * LDA + l32 * LDA + 16 * half;
+        const float* b = Bs + buf * BK * LDB + wave * 32 + l32 + 16 * half * LDB;
+        // a quarter step's operands (4 k per lane) are fetched from LDS before the matrix
+        // instructions of the quarter before issue
+        float4 av[RT];
+        float bv[4];
+        float4 wv[4];                                  // the next W tile's values between lookup and store
 #pragma unroll
-        for (int i = 0; i < RT; ++i) av[i] = a[32 * i];
+        for (int q = 0; q < 4; ++q) wv[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 #pragma unroll
-        for (int kk = 0; kk < BK / 2; ++kk) {
-            float nav[RT], nbv = 0.0f;
+        for (int i = 0; i < RT; ++i) av[i] = *reinterpret_cast<const float4*>(a + 32 * i * LDA);
 #pragma unroll
-            for (int i = 0; i < RT; ++i) nav[i] = 0.0f;
-            if (kk + 1 < BK / 2) {
+        for (int j = 0; j < 4; ++j) bv[j] = b[j * LDB];
 #pragma unroll
-                for (int i = 0; i < RT; ++i) nav[i] = a[(2 * kk + 2) * LDA + 32 * i];
-                nbv = b[(2 * kk + 2) * LDB];
+        for (int qd = 0; qd < 4; ++qd) {
+            float4 nav[RT];
+            float nbv[4];
+#pragma unroll
+            for (int i = 0; i < RT; ++i) nav[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) nbv[j] = 0.0f;
+            if (qd + 1 < 4) {
+#pragma unroll
+                for (int i = 0; i < RT; ++i) nav[i] = *reinterpret_cast<const float4*>(a + 32 * i * LDA + 4 * (qd + 1));
+#pragma unroll
+                for (int j = 0; j < 4; ++j) nbv[j] = b[(4 * (qd + 1) + j) * LDB];
             }
-            __builtin_amdgcn_sched_barrier(0);         // keep these LDS reads ahead of the matrix instructions
 #pragma unroll
-            for (int i = 0; i < RT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv, acc[i], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int j = 0; j < 4; ++j) {
+                const int kk = 4 * qd + j;
+                __builtin_amdgcn_sched_barrier(0);     // keep the LDS reads ahead of the matrix instructions
+#pragma unroll
+                for (int i = 0; i < RT; ++i) {
+                    const float ak = j == 0 ? av[i].x : j == 1 ? av[i].y : j == 2 ? av[i].z : av[i].w;
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(ak, bv[j], acc[i], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (store) {
+                    if (kk >= 2 && kk - 2 < RT) store_a(buf ^ 1, kk - 2, st);
+                    if (kk >= 6 && kk < 10) wv[kk - 6] = lookup_b(kk - 6, st);
+                    if (kk >= 8 && kk < 12) store_b(buf ^ 1, kk - 8, wv[kk - 8]);
+                }
+            }
 #pragma unroll
             for (int i = 0; i < RT; ++i) av[i] = nav[i];
-            bv = nbv;
-            if (store) {
-                if (kk >= 4 && kk - 4 < RT) store_a(buf ^ 1, kk - 4, st);
-                if (kk >= 12) store_b(buf ^ 1, kk - 12, st);
-            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bv[j] = nbv[j];
         }
     };
     auto store_all = [&](uint32_t buf, const Stage& st) {
 #pragma unroll
         for (int r = 0; r < RT; ++r) store_a(buf, r, st);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) store_b(buf, q, st);
+        for (int q = 0; q < 4; ++q) store_b(buf, q, lookup_b(q, st));
     };
 
     // Full K steps [kt0, kfull) are pipelined: while tile kt is multiplied, tile kt + 1 (requested a
@@ -400,7 +427,7 @@ namespace hac_internal {
 
 static size_t index_gemm_lds_bytes(uint32_t k_tot, int rt)
 {
-    return sizeof(float) * (2 * BK * (32 * rt + 4) + 2 * BK * LDB + (k_tot <= kLutLdsMax ? k_tot : 0));
+    return sizeof(float) * (2 * 32 * rt * LDA + 2 * BK * LDB + (k_tot <= kLutLdsMax ? k_tot : 0));
 }
 
 GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m)

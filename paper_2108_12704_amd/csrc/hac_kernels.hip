@@ -766,7 +766,7 @@ uint32_t default_cpw(const hac_desc_t* desc)
 //           memory path, about 22 TB/s over the whole chip and 140 GB/s per busy CU (a block covers
 //           16 columns of W and up to 256 batch columns), plus the re-layout of X and ~12 us;
 //   dense : ~35 non-zeros per ns to decode into the index map, then the contraction at about
-//           80 TFLOP/s, but never faster than its serial K loop (3 us per step of 32 per round of
+//           95 TFLOP/s, but never faster than its serial K loop (3 us per step of 32 per round of
 //           512 work items), plus the pass that adds the K splits.
 struct DenseRoute { bool use; uint32_t idx_bits; uint64_t pitch; size_t idx_bytes, bytes; };
 
@@ -791,7 +791,7 @@ DenseRoute dense_route(const hac_desc_t* desc, int64_t B, const hac_launch_t* la
     const double sparse_us = 12.0 + nnz * bp * 4.0 / rate + b * n * 8.0 / 3e6;
     const double items = (double)plan.tiles * plan.splits;
     const double rounds = (double)(uint64_t)((items + 511.0) / 512.0);
-    const double flops_us = 2.0 * b * n * m / 8e7, serial_us = plan.steps_per_split * 3.0 * rounds;
+    const double flops_us = 2.0 * b * n * m / 9.5e7, serial_us = plan.steps_per_split * 3.0 * rounds;
     const double dense_us = 10.0 + nnz / 35e3 + (flops_us > serial_us ? flops_us : serial_us) + (double)plan.part_bytes / 2e6;
     r.use = dense_us < sparse_us;
     return r;
