@@ -124,6 +124,33 @@ def time_region(torch, body, iters, warmup, use_graph, rot):
     return t0.elapsed_time(t1) / iters
 
 
+def time_spread(torch, body, replays, use_graph, rot):
+    """(min, median) milliseconds per body(i) call over `replays` groups of `rot` calls, each group
+    (one graph replay, or rot eager calls) between its own pair of events; everything is queued
+    before the first wait, so the groups run back to back.  Beside time_region's mean, not instead."""
+    stream = torch.cuda.current_stream()
+    graph = None
+    if use_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for j in range(rot):
+                body(j)
+        graph.replay()
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(replays + 1)]
+    marks[0].record(stream)
+    for r in range(replays):
+        if graph is not None:
+            graph.replay()
+        else:
+            for j in range(rot):
+                body(j)
+        marks[r + 1].record(stream)
+    torch.cuda.synchronize()
+    per_call = sorted(marks[r].elapsed_time(marks[r + 1]) / rot for r in range(replays))
+    return per_call[0], per_call[len(per_call) // 2]
+
+
 def measured_traffic(cfg_id, fmt, B):
     """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by the copy calibration) from the
     committed rocprofv3 counter summary, or None when that summary has no line for this kernel."""
@@ -384,6 +411,7 @@ def main():
             c.run(i)
 
     ms_step = time_region(torch, step, args.steps, args.warmup, use_graph, rot)
+    step_min, step_med = time_spread(torch, step, 30, use_graph, rot)      # after the timed region, not part of it
     step_bytes = sum(c.bytes for c in calls)
     value = step_bytes / (ms_step * 1e-3) / 1e9
     dense_flop = sum(2.0 * c.B * cfg.n * cfg.m for c in calls)
@@ -397,8 +425,10 @@ def main():
         reuse.variant = 0x100                       # feature-major X already in the workspace: dot kernel alone
         ms_k = ms if c.B == 1 else time_region(torch, lambda i, c=c: c.run(i, reuse), max(args.steps, 50), 5,
                                                use_graph, rot)
+        ms_min, ms_med = time_spread(torch, lambda i, c=c: c.run(i), 30, use_graph, rot)
         detail.append({
-            "format": c.fmt, "B": c.B, "ms": round(ms, 5), "kernel_ms": round(ms_k, 5),
+            "format": c.fmt, "B": c.B, "ms": round(ms, 5), "min_ms": round(ms_min, 5), "median_ms": round(ms_med, 5),
+            "kernel_ms": round(ms_k, 5),
             "bytes": c.bytes, "GBps": round(c.bytes / ms / 1e6, 1),
             "hbm_frac": round(c.bytes / ms / 1e6 / HBM_PEAK_GBS, 4),
             "kernel_hbm_frac": round(c.bytes / ms_k / 1e6 / HBM_PEAK_GBS, 4),
@@ -442,6 +472,7 @@ def main():
     out = {
         "metric": "compressed X.W throughput: algorithmic HBM GB/s", "value": round(value, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 5),
+        "step_ms_min": round(step_min, 5), "step_ms_median": round(step_med, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {
             "workload": f"cfg{cfg.cfg} {cfg.name}: W {cfg.n}x{cfg.m} N(0,{cfg.sigma}) pruned {cfg.prune:.0%}, "
