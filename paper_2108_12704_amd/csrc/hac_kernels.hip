@@ -105,38 +105,96 @@ decode_kernel(DevBlob d, float* vals, int32_t* sym, int32_t* row_out, int32_t* c
 // occurs); sHAC, whose alphabet has no 0.0: pointer = symbol + 1.  One lane per chunk.
 template <typename IdxT>
 __global__ void __launch_bounds__(256)
-decode_to_index_kernel(DevBlob d, IdxT* idx, uint64_t pitch, uint32_t shac)
+decode_to_index_kernel(DevBlob d, IdxT* idx, uint64_t pitch, uint32_t shac, uint32_t s_words, uint32_t r_words,
+                       uint32_t c_words)
 {
     extern __shared__ uint32_t smem[];
+    __shared__ uint32_t range[4];                       // the block's stream words [0], [1) and CSC positions [2], [3)
     const Tables tb = load_tables(d, smem);
-    __syncthreads();
-    const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
-    if (g >= d.n_chunks) return;
-    const uint32_t col = column_of_chunk(d, g);
-    uint32_t rel, row0;
-    load_entry(d, g, rel, row0);
-    ChunkState st;
-    st.bp = d.colbit[col] + rel;
-    st.row = row0;
-    st.wpos = d.colpos[col] + (g - d.colchunk[col]) * d.chunk;
-    const uint32_t cend = d.colpos[col + 1];
-    st.wend = st.wpos + d.chunk < cend ? st.wpos + d.chunk : cend;
-    WordSrc<false> src = { d.stream, 0 };
-    if (shac && d.rice) {
-        gap_advance_slow(d, tb, src, st, st.wend, [&](uint32_t, uint32_t row, uint32_t s, float) {
-            idx[(uint64_t)row * pitch + col] = (IdxT)(s + 1);
-        });
-    } else if (shac) {
-        WordSrc<false> rsrc = { d.ri, 0 };
-        shac_advance(d, tb, src, st, st.wend, [&](uint32_t p, uint32_t, uint32_t s, float) {
-            const uint32_t row = rsrc.field((uint64_t)p * d.ri_bits, d.ri_bits);
-            idx[(uint64_t)row * pitch + col] = (IdxT)(s + 1);
-        });
-    } else {
-        hac_advance(d, tb, src, st, st.wend, [&](uint32_t, uint32_t row, uint32_t s, float) {
-            idx[(uint64_t)row * pitch + col] = (IdxT)s;
-        });
+    uint32_t* sstage = smem + table_words_dev(d);       // s_words: the stream words of the block's chunks
+    uint32_t* rstage = sstage + s_words;                // r_words: their ri fields (sHAC with fields)
+    uint32_t* cstage = rstage + r_words;                // c_words: colchunk[0 .. m], or nothing when it is too long
+    const uint32_t g0 = blockIdx.x * blockDim.x, g = g0 + threadIdx.x;
+    const uint32_t glast = g0 + blockDim.x - 1 < d.n_chunks - 1 ? g0 + blockDim.x - 1 : d.n_chunks - 1;
+    const bool live = g < d.n_chunks;
+    // which column owns a chunk: a binary search over colchunk, from a copy in LDS when it fits
+    // (a dozen dependent reads per lane, tens of cycles each instead of hundreds)
+    if (c_words) {
+        for (uint32_t i = threadIdx.x; i <= d.m; i += blockDim.x) cstage[i] = d.colchunk[i];
+        __syncthreads();
     }
+    auto owner = [&](uint32_t chunk) -> uint32_t {
+        if (!c_words) return column_of_chunk(d, chunk);
+        uint32_t lo = 0, hi = d.m;                       // invariant: colchunk[lo] <= chunk < colchunk[hi]
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (((lds_cu32*)cstage)[mid] <= chunk) lo = mid; else hi = mid;
+        }
+        return lo;
+    };
+    uint32_t col = 0;
+    ChunkState st = { 0, 0, 0, 0 };
+    if (live) {
+        col = owner(g);
+        uint32_t rel, row0;
+        load_entry(d, g, rel, row0);
+        st.bp = d.colbit[col] + rel;
+        st.row = row0;
+        st.wpos = d.colpos[col] + (g - d.colchunk[col]) * d.chunk;
+        const uint32_t cend = d.colpos[col + 1];
+        st.wend = st.wpos + d.chunk < cend ? st.wpos + d.chunk : cend;
+    }
+    // The chunks of a block follow one another in the stream: from the first one's start to the
+    // start of the chunk after the last one (or the end of the stream) is one contiguous range.
+    if (threadIdx.x == 0) { range[0] = st.bp >> 5; range[2] = st.wpos; }
+    if (g == glast) {
+        uint32_t endbit = d.colbit[d.m];
+        if (glast + 1 < d.n_chunks) {
+            uint32_t rel2, row2;
+            load_entry(d, glast + 1, rel2, row2);
+            endbit = d.colbit[owner(glast + 1)] + rel2;
+        }
+        range[1] = (endbit + 31) >> 5;
+        range[3] = st.wend;
+    }
+    __syncthreads();                                    // tables and range complete
+    // Stage the range in LDS when it fits (a lane's walk is a chain of dependent reads: tens of
+    // cycles each from LDS, hundreds from L2 with 64 lanes on 64 different lines); else read the blob.
+    const uint32_t wlo = range[0] & ~3u;
+    const uint32_t nw = range[1] >= wlo ? range[1] - wlo + 8 : 0xffffffffu;     // 128-bit windows read past the last bit
+    const uint64_t rlo_bit = (uint64_t)range[2] * d.ri_bits, rhi_bit = (uint64_t)range[3] * d.ri_bits;
+    const uint32_t rwlo = (uint32_t)(rlo_bit >> 5) & ~3u;
+    const bool fields = shac && !d.rice;
+    const uint32_t rnw = fields ? (uint32_t)((rhi_bit + 31) >> 5) - rwlo + 4 : 0;
+    const bool staged = nw <= s_words && rnw <= r_words && range[3] >= range[2];
+    if (staged) {
+        const uint4* s4 = reinterpret_cast<const uint4*>(d.stream + wlo);
+        for (uint32_t i = threadIdx.x; i * 4 < nw; i += blockDim.x) reinterpret_cast<uint4*>(sstage)[i] = s4[i];
+        if (fields) {
+            const uint4* r4 = reinterpret_cast<const uint4*>(d.ri + rwlo);
+            for (uint32_t i = threadIdx.x; i * 4 < rnw; i += blockDim.x) reinterpret_cast<uint4*>(rstage)[i] = r4[i];
+        }
+    }
+    __syncthreads();
+    if (!live) return;
+    auto walk = [&](auto src, auto rsrc) {
+        if (shac && d.rice) {
+            gap_advance_slow(d, tb, src, st, st.wend, [&](uint32_t, uint32_t row, uint32_t s, float) {
+                idx[(uint64_t)row * pitch + col] = (IdxT)(s + 1);
+            });
+        } else if (shac) {
+            shac_advance(d, tb, src, st, st.wend, [&](uint32_t p, uint32_t, uint32_t s, float) {
+                const uint32_t row = rsrc.field((uint64_t)p * d.ri_bits, d.ri_bits);
+                idx[(uint64_t)row * pitch + col] = (IdxT)(s + 1);
+            });
+        } else {
+            hac_advance(d, tb, src, st, st.wend, [&](uint32_t, uint32_t row, uint32_t s, float) {
+                idx[(uint64_t)row * pitch + col] = (IdxT)s;
+            });
+        }
+    };
+    if (staged) walk(WordSrc<true>{ sstage, wlo }, WordSrc<true>{ rstage, rwlo });
+    else walk(WordSrc<false>{ d.stream, 0 }, WordSrc<false>{ d.ri, 0 });
 }
 
 // ---------------------------------------------------------------------------
@@ -939,16 +997,25 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         // 1. all pointers 0, 2. the pointer of every non-zero, 3. tiles on the matrix cores
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, stream, static_cast<uint32_t*>(d_ws),
                            (uint64_t)(dr.idx_bytes / 4), 0u);
-        const size_t lds = 4ull * table_words(d);
+        // LDS beside the tables: room for the stream words (and ri fields) of a block's chunks
+        const uint32_t s_words = 6144, r_words = (format == HAC_FORMAT_SHAC && !d.rice) ? 6144u : 0u;
+        const uint32_t c_words = d.m + 1 <= 8192 ? round_up(d.m + 1, 4) : 0u;       // colchunk, for the owner search
+        const size_t lds = 4ull * (table_words(d) + s_words + r_words + c_words);
         const uint32_t grid = (d.n_chunks + 255) / 256;
         const uint32_t is_shac = format == HAC_FORMAT_SHAC ? 1u : 0u;
         if (grid) {
+            if (lds > 64 * 1024) {
+                const void* f = dr.idx_bits == 8 ? reinterpret_cast<const void*>(decode_to_index_kernel<uint8_t>)
+                                                 : reinterpret_cast<const void*>(decode_to_index_kernel<uint16_t>);
+                hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (e != hipSuccess) return hip_fail(e);
+            }
             if (dr.idx_bits == 8)
                 hipLaunchKernelGGL(decode_to_index_kernel<uint8_t>, dim3(grid), dim3(256), lds, stream, d,
-                                   static_cast<uint8_t*>(d_ws), dr.pitch, is_shac);
+                                   static_cast<uint8_t*>(d_ws), dr.pitch, is_shac, s_words, r_words, c_words);
             else
                 hipLaunchKernelGGL(decode_to_index_kernel<uint16_t>, dim3(grid), dim3(256), lds, stream, d,
-                                   static_cast<uint16_t*>(d_ws), dr.pitch, is_shac);
+                                   static_cast<uint16_t*>(d_ws), dr.pitch, is_shac, s_words, r_words, c_words);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);

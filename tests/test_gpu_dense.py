@@ -107,6 +107,27 @@ def test_dense_route_matches_the_oracle(hac, name, W):
             check_y(Y, X, W, f"{what} dense {name} B={B}")
 
 
+def test_dense_route_decode_without_its_lds_copies(hac):
+    # the decode kernel keeps a block's stream words, ri fields and the column index in LDS when
+    # they fit; these layers do not fit: 256 chunks of a very sparse, tall HAC layer span more
+    # stream words than the staging area, 256 chunks of 100 non-zeros carry more ri bits than
+    # theirs, and a layer with more than 8191 columns has too long an index
+    tall = workloads.make_layer(30000, 24, 0.02, 0.999, 8, "uniform", 71)
+    fat = workloads.make_layer(2000, 300, 0.02, 0.5, 16, "uniform", 72)
+    wide = workloads.make_layer(24, 9000, 0.02, 0.7, 8, "uniform", 73)
+    cases = [("tall", tall, hac.hac_encode(tall), hac.hac_dot), ("tall/rice", tall, hac.shac_encode(tall, ri_coding=1), hac.shac_dot),
+             ("fat ri", fat, hac.shac_encode(fat, chunk_nnz=100), hac.shac_dot),
+             ("wide", wide, hac.hac_encode(wide), hac.hac_dot), ("wide", wide, hac.shac_encode(wide), hac.shac_dot)]
+    for what, W, blob, f in cases:
+        db = blob.to_device(dev())
+        for B in (1, 33):
+            print(f"[case] dense route, decode from the blob: {what} {W.shape} B={B}", flush=True)
+            X = workloads.make_batch(B, W.shape[0], 9 + B) - np.float32(0.2)
+            Y = f(db, torch.from_numpy(X).to(dev()), launch=hac.Launch(variant=DENSE))
+            torch.cuda.synchronize()
+            check_y(Y, X, W, f"{what} B={B}")
+
+
 def test_route_selection_and_workspace(hac):
     W = workloads.scaled(5, 2100, 70)                        # 40 % non-zero
     n, m = W.shape
