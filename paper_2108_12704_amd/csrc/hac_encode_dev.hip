@@ -16,7 +16,8 @@
 //   5. device  one thread per (row segment, column) walks its rows and writes codewords (and
 //              row-index fields or gap codewords) with atomic ORs into the zeroed stream, and the
 //              chunk entries.
-// A thread owns one column of a segment of 1024 rows, so the 64 lanes of a wave read 64
+// A thread owns one column of a segment of rows (1024 on large matrices, down to 32 on small ones, so
+// that there are threads enough to fill the chip), so the 64 lanes of a wave read 64
 // neighbouring columns of one row: coalesced reads of the row-major matrix in all three passes.
 // The call synchronises the stream twice (steps 2 and 4 need the device's results), three times
 // with Rice-coded gaps.
@@ -36,7 +37,17 @@ namespace {
 using namespace hac_internal;
 
 constexpr uint32_t kHashSlots = 1u << 17;          // distinct values <= 65536 keep the load below 1/2
-constexpr uint32_t kSegRows = 1024;
+constexpr uint32_t kSegRowsMax = 1024, kSegRowsMin = 32;
+
+// Rows per segment: 1024 on a large matrix, fewer on a small one, so that there are about 128 K
+// (segment, column) threads to fill the chip; a power of two, and at most 65535 segments (grid rows).
+__host__ inline uint32_t seg_rows_for(uint64_t n, uint64_t m)
+{
+    const uint64_t want = (n * m + 131071) / 131072;
+    uint32_t r = kSegRowsMin;
+    while (r < kSegRowsMax && (r < want || (n + r - 1) / r > 65535)) r <<= 1;
+    return r;
+}
 constexpr uint32_t kLocalSlots = 1024;
 constexpr uint32_t kFlagNonFinite = 1u, kFlagTableFull = 2u;
 
@@ -64,22 +75,37 @@ __device__ void table_add(uint32_t* keys, uint32_t* cnts, uint32_t* flags, uint3
     atomicOr(flags, kFlagTableFull);
 }
 
+// Rows r0 .. r1 - 1 of column j, in order: eight loads are issued before the first value is used, so
+// that a thread has eight rows in flight instead of one (the walk itself is sequential).
+template <class F>
+__device__ __forceinline__ void for_rows(const float* __restrict__ W, uint64_t ldw, uint32_t j, uint32_t r0, uint32_t r1, F f)
+{
+    uint32_t r = r0;
+    for (; r + 8 <= r1; r += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = W[(uint64_t)(r + u) * ldw + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) f(r + u, v[u]);
+    }
+    for (; r < r1; ++r) f(r, W[(uint64_t)r * ldw + j]);
+}
+
 // step 1
 __global__ void __launch_bounds__(256)
-enc_scan_kernel(const float* __restrict__ W, uint32_t n, uint32_t m, uint64_t ldw,
+enc_scan_kernel(const float* __restrict__ W, uint32_t n, uint32_t m, uint64_t ldw, uint32_t seg_rows,
                 uint32_t* keys, uint32_t* cnts, uint32_t* seg_nnz, uint32_t* seg_last, uint32_t* flags)
 {
     __shared__ uint32_t lk[kLocalSlots], lc[kLocalSlots];
     for (uint32_t i = threadIdx.x; i < kLocalSlots; i += 256) { lk[i] = 0u; lc[i] = 0u; }
     __syncthreads();
     const uint32_t j = blockIdx.x * 256 + threadIdx.x, seg = blockIdx.y;
-    const uint32_t r0 = seg * kSegRows, r1 = r0 + kSegRows < n ? r0 + kSegRows : n;
+    const uint32_t r0 = seg * seg_rows, r1 = r0 + seg_rows < n ? r0 + seg_rows : n;
     uint32_t count = 0, last = 0xffffffffu;
     if (j < m) {
-        for (uint32_t r = r0; r < r1; ++r) {
-            const float v = W[(uint64_t)r * ldw + j];
-            if (v == 0.0f) continue;                                 // +0.0 and -0.0 are the null entry
-            if (!isfinite(v)) { atomicOr(flags, kFlagNonFinite); continue; }
+        for_rows(W, ldw, j, r0, r1, [&](uint32_t r, float v) {
+            if (v == 0.0f) return;                                   // +0.0 and -0.0 are the null entry
+            if (!isfinite(v)) { atomicOr(flags, kFlagNonFinite); return; }
             ++count; last = r;
             const uint32_t key = __float_as_uint(v);
             uint32_t h = mix32(key) & (kLocalSlots - 1);
@@ -90,7 +116,7 @@ enc_scan_kernel(const float* __restrict__ W, uint32_t n, uint32_t m, uint64_t ld
                 h = (h + 1) & (kLocalSlots - 1);
             }
             if (!done) table_add(keys, cnts, flags, key, 1u);        // the block's table is crowded
-        }
+        });
         seg_nnz[(uint64_t)seg * m + j] = count;
         seg_last[(uint64_t)seg * m + j] = last;
     }
@@ -110,6 +136,78 @@ __device__ __forceinline__ uint32_t symbol_of(const uint32_t* __restrict__ keys,
     return 0u;
 }
 
+// Rows r0 .. r1 - 1 of column j with each non-zero's symbol (+ shift), code length and, when
+// `codes` is given, codeword.  The lookups of eight rows travel together: first the eight
+// values, then their eight hash probes, their symbols, their lengths and codewords -- five trips
+// to memory per eight rows instead of five per non-zero (some lane of a wave holds a non-zero in
+// almost every row, so the whole wave pays for each trip).
+// NZ_ONLY: f sees the non-zero rows only (in order).  They pass through a queue of the thread's own
+// in LDS (queue[(8 entries x 3 words) x 256 threads]), so that a wave runs f as often as its
+// fullest lane has non-zeros among the eight rows, not once for every row in which any lane has one.
+template <bool NZ_ONLY, class F>
+__device__ __forceinline__ void for_rows_coded(const float* __restrict__ W, uint64_t ldw, uint32_t j, uint32_t r0, uint32_t r1,
+                                               const uint32_t* __restrict__ keys, const uint32_t* __restrict__ slot_sym,
+                                               uint32_t shift, const uint8_t* __restrict__ lens,
+                                               const uint32_t* __restrict__ codes, uint32_t* queue, F f)
+{
+    uint32_t r = r0;
+    for (; r + 8 <= r1; r += 8) {
+        float v[8];
+        uint32_t h[8], got[8], sym[8], len[8], code[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = W[(uint64_t)(r + u) * ldw + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t key = __float_as_uint(v[u]);
+            h[u] = mix32(key) & (kHashSlots - 1);
+            got[u] = v[u] != 0.0f ? keys[h[u]] : key;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {                                // the key is in the table: step 1 put it there
+            const uint32_t key = __float_as_uint(v[u]);
+            for (uint32_t probe = 0; got[u] != key && probe < kHashSlots; ++probe) {
+                h[u] = (h[u] + 1) & (kHashSlots - 1);
+                got[u] = keys[h[u]];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sym[u] = v[u] != 0.0f ? slot_sym[h[u]] + shift : 0u;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            len[u] = v[u] != 0.0f ? lens[sym[u]] : 0u;
+            code[u] = (codes && v[u] != 0.0f) ? codes[sym[u]] : 0u;
+        }
+        // All of the above has arrived before the first row is applied: f may issue stores and atomics,
+        // and a wait for a load that was issued before them would wait for them too (one counter).
+        __builtin_amdgcn_s_waitcnt(0x0f70);                          // vmcnt(0), the other counters untouched
+        if constexpr (NZ_ONLY) {
+            uint32_t* q = queue + threadIdx.x;
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (v[u] != 0.0f) {
+                    q[(cnt * 3 + 0) * 256] = r + u; q[(cnt * 3 + 1) * 256] = len[u]; q[(cnt * 3 + 2) * 256] = code[u];
+                    ++cnt;
+                }
+            }
+            for (uint32_t i = 0; i < cnt; ++i) f(q[(i * 3 + 0) * 256], 1.0f, 0u, q[(i * 3 + 1) * 256], q[(i * 3 + 2) * 256]);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) f(r + u, v[u], sym[u], len[u], code[u]);
+        }
+    }
+    for (; r < r1; ++r) {
+        const float v = W[(uint64_t)r * ldw + j];
+        uint32_t sym = 0, len = 0, code = 0;
+        if (v != 0.0f) {
+            sym = symbol_of(keys, slot_sym, __float_as_uint(v)) + shift;
+            len = lens[sym];
+            if (codes) code = codes[sym];
+        }
+        if (!NZ_ONLY || v != 0.0f) f(r, v, sym, len, code);
+    }
+}
+
 __device__ __forceinline__ uint32_t rice_len(uint32_t d, uint32_t k)
 {
     const uint32_t q = d >> k;
@@ -123,10 +221,10 @@ enc_bits_kernel(const float* __restrict__ W, uint32_t n, uint32_t m, uint64_t ld
                 const uint32_t* __restrict__ keys, const uint32_t* __restrict__ slot_sym,
                 const uint8_t* __restrict__ lens, uint32_t* seg_codebits,
                 const uint32_t* __restrict__ seg_prev_row1, uint32_t* gap_bits, unsigned long long* gap_total,
-                uint64_t seg_cols)
+                uint64_t seg_cols, uint32_t seg_rows)
 {
     const uint32_t j = blockIdx.x * 256 + threadIdx.x, seg = blockIdx.y;
-    const uint32_t r0 = seg * kSegRows, r1 = r0 + kSegRows < n ? r0 + kSegRows : n;
+    const uint32_t r0 = seg * seg_rows, r1 = r0 + seg_rows < n ? r0 + seg_rows : n;
     const uint64_t at = (uint64_t)seg * m + j;
     uint32_t bits = 0;
     uint32_t g[kRiceKMax + 1];
@@ -134,17 +232,17 @@ enc_bits_kernel(const float* __restrict__ W, uint32_t n, uint32_t m, uint64_t ld
     for (uint32_t k = 0; k <= kRiceKMax; ++k) g[k] = 0;
     if (j < m) {
         uint32_t next = gap_bits ? seg_prev_row1[at] : 0u;           // the row the next gap counts from
-        for (uint32_t r = r0; r < r1; ++r) {
-            const float v = W[(uint64_t)r * ldw + j];
-            if (v == 0.0f) continue;
-            bits += lens[symbol_of(keys, slot_sym, __float_as_uint(v))];
+        for_rows_coded<false>(W, ldw, j, r0, r1, keys, slot_sym, 0u, lens, nullptr, nullptr,
+                              [&](uint32_t r, float v, uint32_t, uint32_t len, uint32_t) {
+            if (v == 0.0f) return;
+            bits += len;
             if (gap_bits) {
                 const uint32_t d = r - next;
 #pragma unroll
                 for (uint32_t k = 0; k <= kRiceKMax; ++k) g[k] += rice_len(d, k);
                 next = r + 1;
             }
-        }
+        });
         seg_codebits[at] = bits;
     }
     if (!gap_bits) return;
@@ -176,30 +274,22 @@ struct EmitArgs {
     uint32_t* stream; void* ent; uint32_t* ri;
     uint32_t shac, has_zero, zcode, zlen, chunk, ent_bits, row_bits, ri_bits;
     uint32_t rice, rice_k;                                              // sHAC with Rice-coded gaps in the stream
+    uint32_t seg_rows;
 };
 
 // step 5
 __global__ void __launch_bounds__(256) enc_emit_kernel(EmitArgs a)
 {
+    __shared__ uint32_t queue[8 * 3 * 256];
     const uint32_t j = blockIdx.x * 256 + threadIdx.x, seg = blockIdx.y;
     if (j >= a.m) return;
-    const uint32_t r0 = seg * kSegRows, r1 = r0 + kSegRows < a.n ? r0 + kSegRows : a.n;
+    const uint32_t r0 = seg * a.seg_rows, r1 = r0 + a.seg_rows < a.n ? r0 + a.seg_rows : a.n;
     const uint64_t at = (uint64_t)seg * a.m + j;
     uint32_t bit = a.seg_bit0[at], pos = a.seg_pos0[at];
     uint32_t pend = a.seg_prev_end[at], prow = a.seg_prev_row1[at];   // HAC: where the non-zero before this one ended
     const uint32_t cbit0 = a.col_bit[j], cpos0 = a.col_pos[j], cchunk0 = a.col_chunk[j];
     const uint32_t shift = (!a.shac && a.has_zero) ? 1u : 0u;          // HAC numbers 0.0 as symbol 0
-    for (uint32_t r = r0; r < r1; ++r) {
-        const float v = a.W[(uint64_t)r * a.ldw + j];
-        if (v == 0.0f) {
-            if (!a.shac) {
-                if (a.zcode) put_bits(a.stream, bit, a.zcode, a.zlen);  // an all-zero codeword is already there
-                bit += a.zlen;
-            }
-            continue;
-        }
-        const uint32_t sym = symbol_of(a.keys, a.slot_sym, __float_as_uint(v)) + shift;
-        const uint32_t len = a.lens[sym];
+    auto on_nonzero = [&](uint32_t r, uint32_t len, uint32_t code) {
         const uint32_t q = pos - cpos0;
         if (q % a.chunk == 0) {
             const uint32_t g = cchunk0 + q / a.chunk;
@@ -229,11 +319,32 @@ __global__ void __launch_bounds__(256) enc_emit_kernel(EmitArgs a)
                 bit += kRiceEscape + 1 + 32;
             }
         }
-        put_bits(a.stream, bit, a.codes[sym], len);
+        put_bits(a.stream, bit, code, len);
         bit += len;
         pend = bit; prow = r + 1;
         if (a.shac && !a.rice) put_bits(a.ri, (uint64_t)pos * a.ri_bits, r, a.ri_bits);
         ++pos;
+    };
+    if (a.shac || a.zcode == 0) {
+        // zeros write nothing (sHAC has none in its stream; an all-zero codeword is what the cleared
+        // stream already holds): only the non-zeros are visited, a run of zeros just moves `bit`
+        uint32_t next_row = r0;
+        for_rows_coded<true>(a.W, a.ldw, j, r0, r1, a.keys, a.slot_sym, shift, a.lens, a.codes, queue,
+                             [&](uint32_t r, float, uint32_t, uint32_t len, uint32_t code) {
+            if (!a.shac) bit += (r - next_row) * a.zlen;
+            next_row = r + 1;
+            on_nonzero(r, len, code);
+        });
+    } else {
+        for_rows_coded<false>(a.W, a.ldw, j, r0, r1, a.keys, a.slot_sym, shift, a.lens, a.codes, nullptr,
+                              [&](uint32_t r, float v, uint32_t, uint32_t len, uint32_t code) {
+            if (v == 0.0f) {
+                put_bits(a.stream, bit, a.zcode, a.zlen);
+                bit += a.zlen;
+                return;
+            }
+            on_nonzero(r, len, code);
+        });
     }
 }
 
@@ -244,7 +355,7 @@ struct WsLayout {
 
 WsLayout ws_layout(uint64_t n, uint64_t m)
 {
-    const uint64_t S = (n + kSegRows - 1) / kSegRows;
+    const uint64_t seg_rows = seg_rows_for(n, m), S = (n + seg_rows - 1) / seg_rows;
     WsLayout L;
     size_t c = 0;
     auto take = [&](size_t bytes) { const size_t o = c; c = (c + bytes + 255) / 256 * 256; return o; };
@@ -275,7 +386,8 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
     if (format != HAC_FORMAT_HAC && format != HAC_FORMAT_SHAC) return HAC_EINVAL;
     if (n < 1 || m < 1 || ldw < m) return HAC_EINVAL;
     if (n > 0x7fffffffll || m > 0x7fffffffll) return HAC_ERANGE;
-    if ((n + kSegRows - 1) / kSegRows > 65535) return HAC_ERANGE;     // one grid row per segment of 1024 rows
+    const uint32_t seg_rows = seg_rows_for((uint64_t)n, (uint64_t)m);
+    if ((n + seg_rows - 1) / seg_rows > 65535) return HAC_ERANGE;       // one grid row per segment of rows
     int rc = check_opts(opts);
     if (rc) return rc;
     const bool shac = format == HAC_FORMAT_SHAC;
@@ -294,14 +406,14 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
     hac_internal::set_last_hip_error(0);
     uint8_t* ws = static_cast<uint8_t*>(d_ws);
     auto dptr = [&](size_t off) { return reinterpret_cast<uint32_t*>(ws + off); };
-    const uint32_t S = (uint32_t)(((uint64_t)n + kSegRows - 1) / kSegRows);
+    const uint32_t S = (uint32_t)(((uint64_t)n + seg_rows - 1) / seg_rows);
     const size_t SM = (size_t)S * (size_t)m;
     const dim3 grid((uint32_t)((m + 255) / 256), S);
     hipError_t e;
     try {
         // ---- step 1 ----
         hipLaunchKernelGGL(fill_zero_kernel, dim3(512), dim3(256), 0, stream, dptr(L.keys), (uint64_t)(L.seg_nnz - L.keys) / 4);
-        hipLaunchKernelGGL(enc_scan_kernel, grid, dim3(256), 0, stream, d_W, (uint32_t)n, (uint32_t)m, (uint64_t)ldw,
+        hipLaunchKernelGGL(enc_scan_kernel, grid, dim3(256), 0, stream, d_W, (uint32_t)n, (uint32_t)m, (uint64_t)ldw, seg_rows,
                            dptr(L.keys), dptr(L.cnts), dptr(L.seg_nnz), dptr(L.seg_last), dptr(L.flags));
         if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
         std::vector<uint32_t> keys(kHashSlots), cnts(kHashSlots), seg_nnz(SM), seg_last(SM);
@@ -366,7 +478,7 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         unsigned long long* d_gap_total = reinterpret_cast<unsigned long long*>(ws + L.flags + 64);   // zeroed with the flags
         hipLaunchKernelGGL(enc_bits_kernel, grid, dim3(256), 0, stream, d_W, (uint32_t)n, (uint32_t)m, (uint64_t)ldw,
                            dptr(L.keys), dptr(L.slot_sym), ws + L.lens, dptr(L.seg_codebits), dptr(L.seg_prev_row1),
-                           rice ? dptr(L.gap_bits) : static_cast<uint32_t*>(nullptr), d_gap_total, (uint64_t)SM);
+                           rice ? dptr(L.gap_bits) : static_cast<uint32_t*>(nullptr), d_gap_total, (uint64_t)SM, seg_rows);
         if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
         std::vector<uint32_t> seg_codebits(SM), seg_gapbits;
         unsigned long long gap_total[kRiceKMax + 1] = { 0 };
@@ -402,7 +514,7 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
             uint64_t prev_end = bit;
             for (uint32_t s = 0; s < S; ++s) {
                 const size_t at = (size_t)s * m + j;
-                const uint64_t r0 = (uint64_t)s * kSegRows, r1 = std::min<uint64_t>(r0 + kSegRows, (uint64_t)n);
+                const uint64_t r0 = (uint64_t)s * seg_rows, r1 = std::min<uint64_t>(r0 + seg_rows, (uint64_t)n);
                 seg_bit0[at] = (uint32_t)bit; seg_pos0[at] = (uint32_t)pos;
                 seg_prev_end[at] = (uint32_t)prev_end;
                 const uint64_t cnt = seg_nnz[at];
@@ -477,6 +589,7 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         a.ent = blob + d.off_chunk_ent;
         a.ri = (shac && !rice) ? reinterpret_cast<uint32_t*>(blob + d.off_ri) : nullptr;
         a.rice = rice ? 1u : 0u; a.rice_k = rice_k;
+        a.seg_rows = seg_rows;
         a.shac = shac ? 1u : 0u; a.has_zero = has_zero ? 1u : 0u; a.zcode = zcode; a.zlen = zlen;
         a.chunk = Cn; a.ent_bits = d.ent_bits; a.row_bits = d.row_bits; a.ri_bits = ri_bits;
         hipLaunchKernelGGL(enc_emit_kernel, grid, dim3(256), 0, stream, a);

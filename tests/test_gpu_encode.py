@@ -34,6 +34,9 @@ def cases():
         yield name, W
     for name, W in workloads.random_cases(12, seed=5):
         yield name, W
+    # zeros are rare here, so their HAC codeword is long and not all zero bits: the device encoder
+    # then writes every zero's codeword instead of skipping over runs of zeros
+    yield "few-zeros-700x40", workloads.make_layer(700, 40, 0.02, 0.05, 4, "uniform", 77)
 
 
 CASES = list(cases())
