@@ -400,6 +400,11 @@ int hac_dot_route(const hac_desc_t *desc, int64_t B, const hac_launch_t *launch)
  * B = 0 is a no-op.  fp32 accumulation; the order of the additions is fixed,
  * so results are bitwise reproducible run to run.
  *
+ * The device calls check desc and their arguments, not the bytes of the blob:
+ * d_blob must hold a blob that hac_validate (deep) accepts, as every encoder
+ * returns.  On other bytes a walk still ends (rows are bounded by n), but the
+ * result and the addresses it reads from X are undefined.
+ *
  * Two routes.  Sparse: every non-zero is decoded and applied to the batch by
  * vector FMAs.  Dense: the stream is decoded once into an index map
  * (Sect. III-C1) in the workspace and multiplied tile by tile on the matrix

@@ -173,7 +173,11 @@ __device__ __forceinline__ void hac_advance(const DevBlob& d, const Tables& tb, 
     while (st.wpos < limit) {
         uint32_t top = src.peek32(st.bp);
         if (zfast) {
-            if (top == 0) { st.bp += 32; st.row += 32; continue; }     // a non-zero follows, so the run ends
+            if (top == 0) {                                            // a non-zero follows, so the run ends
+                st.bp += 32; st.row += 32;
+                st.wpos = st.row > d.n ? limit : st.wpos;              // ... unless the stream is damaged: end the walk
+                continue;
+            }
             const uint32_t z = (uint32_t)__builtin_clz(top);
             if (z) {
                 st.bp += z; st.row += z;
@@ -182,7 +186,11 @@ __device__ __forceinline__ void hac_advance(const DevBlob& d, const Tables& tb, 
         }
         const Decoded q = decode_symbol(d, tb, top);
         st.bp += q.len;
-        if (d.has_zero && q.sym == 0) { st.row++; continue; }
+        if (d.has_zero && q.sym == 0) {
+            st.row++;
+            st.wpos = st.row > d.n ? limit : st.wpos;                  // a damaged stream: end the walk
+            continue;
+        }
         emit(st.wpos, st.row, q.sym, q.val);
         st.row++; st.wpos++;
     }
@@ -202,7 +210,11 @@ __device__ __forceinline__ void hac_advance_zrun(const DevBlob& d, const Tables&
         const uint32_t w0 = sw[wi], w1 = sw[wi + 1], w2 = sw[wi + 2], w3 = sw[wi + 3];
         const uint32_t hi = (uint32_t)(((((uint64_t)w0 << 32) | w1) << off) >> 32);
         const uint32_t mid = (uint32_t)(((((uint64_t)w1 << 32) | w2) << off) >> 32);
-        if ((hi | mid) == 0) { st.bp += 64; st.row += 64; continue; }     // a non-zero follows, so the run ends
+        if ((hi | mid) == 0) {                                             // a non-zero follows, so the run ends
+            st.bp += 64; st.row += 64;
+            st.wpos = st.row > d.n ? limit : st.wpos;                      // ... unless the stream is damaged: end the walk
+            continue;
+        }
         const uint32_t lo = (uint32_t)(((((uint64_t)w2 << 32) | w3) << off) >> 32);
         const uint32_t z = hi ? (uint32_t)__builtin_clz(hi) : 32u + (uint32_t)__builtin_clz(mid);
         const uint32_t x0 = z < 32 ? hi : mid, x1 = z < 32 ? mid : lo;
