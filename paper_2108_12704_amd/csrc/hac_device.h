@@ -199,7 +199,8 @@ __device__ __forceinline__ void hac_advance(const DevBlob& d, const Tables& tb, 
 // HAC, zero symbol = the single bit 0, words staged in LDS.  One pass of the loop per
 // non-zero: 128 stream bits are fetched at once, a count-leading-zeros over the first
 // 64 skips the zero run, and the codeword is taken from the same fetch.  Only a run
-// of 64 or more zeros takes an extra pass.
+// of 64 or more zeros takes an extra pass (which steps over 96 bits when they are all zero:
+// the lanes of a wave walk independently, and the wave runs as long as its slowest lane).
 template <class Emit>
 __device__ __forceinline__ void hac_advance_zrun(const DevBlob& d, const Tables& tb, const WordSrc<true>& src,
                                                  ChunkState& st, uint32_t limit, Emit emit)
@@ -210,12 +211,13 @@ __device__ __forceinline__ void hac_advance_zrun(const DevBlob& d, const Tables&
         const uint32_t w0 = sw[wi], w1 = sw[wi + 1], w2 = sw[wi + 2], w3 = sw[wi + 3];
         const uint32_t hi = (uint32_t)(((((uint64_t)w0 << 32) | w1) << off) >> 32);
         const uint32_t mid = (uint32_t)(((((uint64_t)w1 << 32) | w2) << off) >> 32);
+        const uint32_t lo = (uint32_t)(((((uint64_t)w2 << 32) | w3) << off) >> 32);
         if ((hi | mid) == 0) {                                             // a non-zero follows, so the run ends
-            st.bp += 64; st.row += 64;
+            const uint32_t skip = lo ? 64u : 96u;                          // all 96 fetched bits may be zeros
+            st.bp += skip; st.row += skip;
             st.wpos = st.row > d.n ? limit : st.wpos;                      // ... unless the stream is damaged: end the walk
             continue;
         }
-        const uint32_t lo = (uint32_t)(((((uint64_t)w2 << 32) | w3) << off) >> 32);
         const uint32_t z = hi ? (uint32_t)__builtin_clz(hi) : 32u + (uint32_t)__builtin_clz(mid);
         const uint32_t x0 = z < 32 ? hi : mid, x1 = z < 32 ? mid : lo;
         const uint32_t top = (uint32_t)(((((uint64_t)x0 << 32) | x1) << (z & 31)) >> 32);
