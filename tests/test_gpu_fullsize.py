@@ -62,7 +62,9 @@ def test_full_size_dot(hac, cfg):
     gb = hac.shac_encode(W, ri_coding=hac.RI_RICE)          # Rice-coded row gaps (extension)
     assert hb.validate(deep=False) == 0 and sb.validate(deep=False) == 0 and gb.validate(deep=False) == 0
     dh, ds, dg = hb.to_device(dev), sb.to_device(dev), gb.to_device(dev)
-    for B in c.batches:
+    # beside the benchmark's batches, on the large layer: a ragged small batch (two lanes per row
+    # group) and one that ends in a tile with two of its eight passes
+    for B in list(c.batches) + ([5, 300] if cfg == 4 else []):
         print(f"[case] full cfg{cfg} B={B}", flush=True)
         X = workloads.make_batch(B, c.n, 1000 * cfg + 1)
         rows = np.arange(B) if B <= 256 else np.unique(np.concatenate((rng.choice(B, 254, replace=False), [0, B - 1])))
