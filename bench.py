@@ -226,6 +226,37 @@ def extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, iters):
                     "nonzeros_per_s": round(nnz / ms * 1e3, 1),
                     "stream_bits_per_s": round(int(blob.desc.total_bits) / ms * 1e3, 1)})
     out["decode_only"] = dec
+    # the GPU-side encoder (the step before the path): W already on the device -> blob on the device,
+    # against the host encoder on the same matrix; one library call per encode, buffers allocated before
+    import ctypes as C
+    lib = hac.load_library()
+    Wd_enc = torch.from_numpy(W).to(dev)
+    n_, m_ = W.shape
+    ws_enc = torch.empty(lib.hac_encode_dev_workspace_bytes(n_, m_), dtype=torch.uint8, device=dev)
+    enc = {}
+    for name, fmt, host_enc, host_blob in (("hac", hac.HAC_FORMAT_HAC, hac.hac_encode, hb), ("shac", hac.HAC_FORMAT_SHAC, hac.shac_encode, sb)):
+        t = time.perf_counter()
+        host_enc(W)
+        host_ms = 1e3 * (time.perf_counter() - t)
+        out_blob = torch.empty(host_blob.nbytes, dtype=torch.uint8, device=dev)
+        d_ = hac.Desc()
+
+        def encode_once():
+            rc = lib.hac_encode_dev(fmt, Wd_enc.data_ptr(), n_, m_, m_, None, out_blob.data_ptr(), out_blob.numel(),
+                                    C.byref(d_), ws_enc.data_ptr(), ws_enc.numel(), None)
+            if rc:
+                raise RuntimeError(f"hac_encode_dev: {rc}")
+
+        encode_once()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(5):
+            encode_once()                               # the call synchronises by itself
+        dev_ms = 1e3 * (time.perf_counter() - t) / 5
+        enc[name] = {"device_ms": round(dev_ms, 3), "host_ms": round(host_ms, 1),
+                     "identical_to_host_blob": bool(np.array_equal(out_blob.cpu().numpy(), host_blob.data))}
+    out["gpu_encoder"] = enc
+    del Wd_enc, ws_enc, out_blob
     # a fully connected block as one chain (hac_forward) on a network blob with one shared dictionary,
     # against the same layers multiplied one call at a time with bias and ReLU as separate passes
     import workloads
