@@ -292,7 +292,7 @@ index_gemm_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
 // read per row) and the representatives in LDS.  The four row groups of a block are added in
 // LDS, the row ranges by splitk_reduce_kernel: a fixed order.
 // ---------------------------------------------------------------------------
-constexpr int SB_NB = 8, SB_COLS = 256, SB_GROUPS = 4;
+constexpr int SB_NB = 8, SB_COLS = 256, SB_GROUPS = 4;     // widest layout: 64 column lanes x 4 row groups
 constexpr uint32_t kSmallMaxRows = 1024;           // rows of W per block (32 KB of X in LDS)
 
 template <typename IdxT> struct Ptr4;
@@ -309,23 +309,28 @@ template <> struct Ptr4<uint16_t> {
     }
 };
 
-template <typename IdxT, bool LUT_LDS>
+template <typename IdxT, bool LUT_LDS, bool WIDE>
 __global__ void __launch_bounds__(256)
 index_small_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
                    const IdxT* __restrict__ idx, uint64_t pitch,
                    const float* __restrict__ codebook, uint32_t k_sym, uint32_t zero_first,
                    uint32_t n, uint32_t m, uint32_t rows_per_split, uint32_t tiles_m, uint32_t splits,
-                   float* __restrict__ Y, uint64_t ldy, float* __restrict__ part)
+                   uint32_t cl_log2_arg, float* __restrict__ Y, uint64_t ldy, float* __restrict__ part)
 {
+    const uint32_t cl_log2 = WIDE ? 6u : cl_log2_arg;              // the widest layout with compile-time shapes
+    // 2^cl_log2 column lanes (4 columns each) x 256 / 2^cl_log2 row groups: 64 x 4 for a map of 129
+    // columns or more, fewer lanes and more row groups for a narrow one, so that its rows are spread
+    // over the block's threads instead of leaving most of them idle
+    const uint32_t cl = 1u << cl_log2, cols = 4u << cl_log2, groups = 256u >> cl_log2;
     extern __shared__ float lds[];
     float* xs = lds;                                               // [rows_per_split][SB_NB]
-    float* red = xs + (size_t)rows_per_split * SB_NB;              // [SB_GROUPS][SB_NB][SB_COLS]
+    float* red = xs + (size_t)rows_per_split * SB_NB;              // [groups][SB_NB][cols]: 8192 floats in every layout
     float* lut = red + SB_GROUPS * SB_NB * SB_COLS;                // [k_sym + zero_first] when LUT_LDS
     const uint32_t tile = blockIdx.x % tiles_m, split = blockIdx.x / tiles_m;
     const uint32_t b0 = blockIdx.y * SB_NB;                        // this block's batch rows b0 .. b0 + 7
     const uint32_t nb = B - b0 < (uint32_t)SB_NB ? B - b0 : (uint32_t)SB_NB;
-    const uint32_t c = threadIdx.x & 63, g = threadIdx.x >> 6;
-    const uint32_t j = tile * SB_COLS + 4 * c;                     // first of this thread's four columns
+    const uint32_t c = threadIdx.x & (cl - 1), g = threadIdx.x >> cl_log2;
+    const uint32_t j = tile * cols + 4 * c;                        // first of this thread's four columns
     const uint32_t r0 = split * rows_per_split;
     const uint32_t rows = r0 < n ? (n - r0 < rows_per_split ? n - r0 : rows_per_split) : 0u;
     const uint32_t k_tot = k_sym + zero_first;
@@ -370,14 +375,14 @@ index_small_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
         uint32_t i = g;
         // four rows at a time: their pointers are requested together, so that a thread with few
         // rows does not pay one trip to memory per row
-        for (; i + 3 * SB_GROUPS < rows; i += 4 * SB_GROUPS) {
+        for (; i + 3 * groups < rows; i += 4 * groups) {
             uint32_t p[4][4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) Ptr4<IdxT>::ld(col + (uint64_t)(i + q * SB_GROUPS) * pitch, p[q]);
+            for (int q = 0; q < 4; ++q) Ptr4<IdxT>::ld(col + (uint64_t)(i + q * groups) * pitch, p[q]);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) row_step(i + q * SB_GROUPS, p[q]);
+            for (int q = 0; q < 4; ++q) row_step(i + q * groups, p[q]);
         }
-        for (; i < rows; i += SB_GROUPS) {
+        for (; i < rows; i += groups) {
             uint32_t p[4];
             Ptr4<IdxT>::ld(col + (uint64_t)i * pitch, p);
             row_step(i, p);
@@ -386,17 +391,18 @@ index_small_kernel(const float* __restrict__ X, uint64_t ldx, uint32_t B,
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
-        for (int b = 0; b < SB_NB; ++b) red[(g * SB_NB + b) * SB_COLS + 4 * c + u] = acc[u][b];
+        for (int b = 0; b < SB_NB; ++b) red[(g * SB_NB + b) * cols + 4 * c + u] = acc[u][b];
     __syncthreads();
-    // thread t adds the four groups of column tile * 256 + t
-    const uint32_t jc = tile * SB_COLS + threadIdx.x;
-    if (jc < m) {
-        for (uint32_t b = 0; b < nb; ++b) {
-            float v = red[b * SB_COLS + threadIdx.x];
-            for (int q = 1; q < SB_GROUPS; ++q) v += red[(q * SB_NB + b) * SB_COLS + threadIdx.x];
-            if (splits == 1) Y[(uint64_t)(b0 + b) * ldy + jc] = v;
-            else part[((uint64_t)split * B + b0 + b) * m + jc] = v;
-        }
+    // every (batch row, column) of the block: its row groups added in order, the outputs dealt to
+    // the threads (256 columns x 8 rows in the widest layout, 16 x 8 with 64 row groups in the narrowest)
+    for (uint32_t o = threadIdx.x; o < cols * nb; o += 256) {
+        const uint32_t jl = o & (cols - 1), b = o >> (cl_log2 + 2);
+        const uint32_t jc = tile * cols + jl;
+        if (jc >= m) continue;
+        float v = red[b * cols + jl];
+        for (uint32_t q = 1; q < groups; ++q) v += red[(q * SB_NB + b) * cols + jl];
+        if (splits == 1) Y[(uint64_t)(b0 + b) * ldy + jc] = v;
+        else part[((uint64_t)split * B + b0 + b) * m + jc] = v;
     }
 }
 
@@ -437,7 +443,11 @@ GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m)
     if (p.small) {
         // blocks of 256 columns x a range of rows: about 512 blocks, at most 32 ranges (the pass that
         // adds them walks them one after the other) unless the rows of a range would not fit LDS
-        const uint32_t tiles_m = (m + SB_COLS - 1) / SB_COLS;
+        // column lanes per row group: 64 (256 columns a block) from 129 columns on, else the power of
+        // two that covers the map, at least 4 (p.rt carries its logarithm in this mode)
+        uint32_t cl_log2 = 6;
+        if (m <= 128) { cl_log2 = 2; while ((4u << cl_log2) < m) ++cl_log2; }
+        const uint32_t tiles_m = (m + (4u << cl_log2) - 1) / (4u << cl_log2);
         const uint32_t groups = (B + SB_NB - 1) / SB_NB;
         uint32_t splits = (512 + tiles_m * groups - 1) / (tiles_m * groups);
         const uint32_t most = (n + 31) / 32, least = (n + kSmallMaxRows - 1) / kSmallMaxRows;
@@ -447,7 +457,7 @@ GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m)
         if (splits < 1) splits = 1;
         p.steps_per_split = ((n + splits - 1) / splits + 3) / 4 * 4;          // rows per block
         p.splits = (n + p.steps_per_split - 1) / p.steps_per_split;
-        p.steps = n; p.rt = 0; p.tiles = tiles_m;
+        p.steps = n; p.rt = cl_log2; p.tiles = tiles_m;
         p.part_bytes = p.splits > 1 ? (size_t)p.splits * B * m * sizeof(float) : 0;
         return p;
     }
@@ -538,9 +548,14 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
         const size_t lds = sizeof(float) * ((size_t)plan.steps_per_split * SB_NB + SB_GROUPS * SB_NB * SB_COLS + (lut_lds ? k_tot : 0));
         const dim3 grid((uint32_t)blocks, (B + SB_NB - 1) / SB_NB);
 #define HAC_LAUNCH_SMALL(T, L)                                                                                       \
-        hipLaunchKernelGGL((index_small_kernel<T, L>), grid, dim3(256), lds, stream, d_X, ldx, B,                    \
+        if (plan.rt == 6)                                                                                            \
+            hipLaunchKernelGGL((index_small_kernel<T, L, true>), grid, dim3(256), lds, stream, d_X, ldx, B,          \
+                               static_cast<const T*>(d_idx), pitch, d_codebook, k_sym, zero_first, n, m,             \
+                               plan.steps_per_split, (uint32_t)plan.tiles, plan.splits, plan.rt, d_Y, ldy, d_part);  \
+        else                                                                                                         \
+        hipLaunchKernelGGL((index_small_kernel<T, L, false>), grid, dim3(256), lds, stream, d_X, ldx, B,             \
                            static_cast<const T*>(d_idx), pitch, d_codebook, k_sym, zero_first, n, m,                 \
-                           plan.steps_per_split, (uint32_t)plan.tiles, plan.splits, d_Y, ldy, d_part)
+                           plan.steps_per_split, (uint32_t)plan.tiles, plan.splits, plan.rt, d_Y, ldy, d_part)
         if (idx_bits == 8) { if (lut_lds) HAC_LAUNCH_SMALL(uint8_t, true); else HAC_LAUNCH_SMALL(uint8_t, false); }
         else { if (lut_lds) HAC_LAUNCH_SMALL(uint16_t, true); else HAC_LAUNCH_SMALL(uint16_t, false); }
 #undef HAC_LAUNCH_SMALL

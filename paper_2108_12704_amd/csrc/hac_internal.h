@@ -12,8 +12,9 @@ namespace hac_internal {
 // `splits` ranges of steps_per_split; with more than one split the partial tiles go through a buffer
 // of part_bytes bytes (splits x B x m floats) and are added in order by a second kernel.
 // A block covers 32 * rt batch rows (rt = 2..8) and 128 columns.
-// small (at most 32 batch rows): no matrix cores; `tiles` blocks of 64 columns, the rows of W cut
-// into `splits` ranges of steps_per_split rows, partial sums through the same buffer.
+// small (at most 32 batch rows): no matrix cores; `tiles` blocks of 4 << rt columns (256 for maps of
+// 129 columns or more), the rows of W cut into `splits` ranges of steps_per_split rows, partial sums
+// through the same buffer.
 struct GemmPlan { uint64_t tiles; uint32_t steps, splits, steps_per_split, rt; size_t part_bytes; bool small; };
 GemmPlan plan_index_gemm(uint32_t B, uint32_t n, uint32_t m);
 
