@@ -360,7 +360,7 @@ WsLayout ws_layout(uint64_t n, uint64_t m)
     size_t c = 0;
     auto take = [&](size_t bytes) { const size_t o = c; c = (c + bytes + 255) / 256 * 256; return o; };
     L.keys = take(4ull * kHashSlots); L.cnts = take(4ull * kHashSlots); L.flags = take(256);
-    L.seg_nnz = take(4 * S * m); L.seg_codebits = take(4 * S * m); L.seg_last = take(4 * S * m);
+    L.seg_nnz = take(4 * S * m); L.seg_last = take(4 * S * m); L.seg_codebits = take(4 * S * m);   // keys .. seg_last: one copy back
     L.seg_bit0 = take(4 * S * m); L.seg_pos0 = take(4 * S * m); L.seg_prev_end = take(4 * S * m); L.seg_prev_row1 = take(4 * S * m);
     L.slot_sym = take(4ull * kHashSlots); L.codes = take(4ull * 65537); L.lens = take(65537);
     L.gap_bits = take(4 * S * m * (kRiceKMax + 1));                  // used with Rice-coded gaps only
@@ -416,14 +416,16 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         hipLaunchKernelGGL(enc_scan_kernel, grid, dim3(256), 0, stream, d_W, (uint32_t)n, (uint32_t)m, (uint64_t)ldw, seg_rows,
                            dptr(L.keys), dptr(L.cnts), dptr(L.seg_nnz), dptr(L.seg_last), dptr(L.flags));
         if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
-        std::vector<uint32_t> keys(kHashSlots), cnts(kHashSlots), seg_nnz(SM), seg_last(SM);
-        uint32_t flags = 0;
-        if ((e = hipMemcpyAsync(keys.data(), dptr(L.keys), 4ull * kHashSlots, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(cnts.data(), dptr(L.cnts), 4ull * kHashSlots, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(&flags, dptr(L.flags), 4, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(seg_nnz.data(), dptr(L.seg_nnz), 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(seg_last.data(), dptr(L.seg_last), 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        // the hash table, the flags and the two per-segment arrays lie side by side in the workspace:
+        // one copy back, read through pointers at the same offsets
+        std::vector<uint32_t> step1((L.seg_last - L.keys) / 4 + SM);
+        if ((e = hipMemcpyAsync(step1.data(), dptr(L.keys), 4 * step1.size(), hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
         if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
+        const uint32_t* keys = step1.data();
+        const uint32_t* cnts = step1.data() + (L.cnts - L.keys) / 4;
+        const uint32_t flags = step1[(L.flags - L.keys) / 4];
+        const uint32_t* seg_nnz = step1.data() + (L.seg_nnz - L.keys) / 4;
+        const uint32_t* seg_last = step1.data() + (L.seg_last - L.keys) / 4;
         if (flags & kFlagNonFinite) return HAC_EINVAL;
         if (flags & kFlagTableFull) return HAC_ERANGE;
 
@@ -464,12 +466,14 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
 
         // the row after the last non-zero above every segment (0 at a column's top)
         std::vector<uint32_t> seg_prev_row1(SM);
-        for (int64_t j = 0; j < m; ++j) {
-            uint32_t prev_row1 = 0;
+        {
+            std::vector<uint32_t> prev_row1((size_t)m, 0);                           // per column, walking the segments in storage order
             for (uint32_t s = 0; s < S; ++s) {
-                const size_t at = (size_t)s * m + j;
-                seg_prev_row1[at] = prev_row1;
-                if (seg_nnz[at]) prev_row1 = seg_last[at] + 1;
+                const size_t row = (size_t)s * m;
+                for (int64_t j = 0; j < m; ++j) {
+                    seg_prev_row1[row + j] = prev_row1[(size_t)j];
+                    if (seg_nnz[row + j]) prev_row1[(size_t)j] = seg_last[row + j] + 1;
+                }
             }
         }
         if ((e = hipMemcpyAsync(dptr(L.seg_prev_row1), seg_prev_row1.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
@@ -499,34 +503,62 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         }
 
         // ---- step 4 ----
-        uint64_t max_col_nnz = 0;
-        std::vector<uint64_t> col_nnz((size_t)m, 0);
-        for (uint32_t s = 0; s < S; ++s)
-            for (int64_t j = 0; j < m; ++j) col_nnz[(size_t)j] += seg_nnz[(size_t)s * m + j];
-        for (int64_t j = 0; j < m; ++j) max_col_nnz = std::max(max_col_nnz, col_nnz[(size_t)j]);
+        // All loops below walk the (segment, column) arrays in storage order (segment-major).
+        uint64_t max_col_nnz = 0, max_col_bits = 0;
+        std::vector<uint64_t> col_nnz((size_t)m, 0), col_bits((size_t)m, 0);
+        auto seg_bits_at = [&](uint32_t s, size_t at) -> uint64_t {
+            const uint64_t r0 = (uint64_t)s * seg_rows, r1 = std::min<uint64_t>(r0 + seg_rows, (uint64_t)n);
+            return seg_codebits[at] + (shac ? 0 : (r1 - r0 - seg_nnz[at]) * zlen) + (rice ? seg_gapbits[at] : 0);
+        };
+        for (uint32_t s = 0; s < S; ++s) {
+            const size_t row = (size_t)s * m;
+            for (int64_t j = 0; j < m; ++j) {
+                col_nnz[(size_t)j] += seg_nnz[row + j];
+                col_bits[(size_t)j] += seg_bits_at(s, row + j);
+            }
+        }
+        for (int64_t j = 0; j < m; ++j) {
+            max_col_nnz = std::max(max_col_nnz, col_nnz[(size_t)j]);
+            max_col_bits = std::max(max_col_bits, col_bits[(size_t)j]);
+        }
         const uint32_t Cn = pick_chunk(opts, max_col_nnz);
-        std::vector<uint32_t> col_bit((size_t)m + 1), col_pos((size_t)m + 1), col_chunk((size_t)m + 1);
-        std::vector<uint32_t> seg_bit0(SM), seg_pos0(SM), seg_prev_end(SM);
-        uint64_t bit = 0, pos = 0, chunks = 0, max_col_bits = 0;
+        // the three per-column arrays sit side by side in the blob (256-byte aligned sections): one
+        // host buffer with the same spacing, one copy; likewise the three per-segment arrays of step 5
+        const size_t col_stride = (4 * ((size_t)m + 1) + 255) / 256 * 256 / 4;       // words from one array to the next
+        std::vector<uint32_t> col_arrays(3 * col_stride, 0);
+        uint32_t* col_chunk = col_arrays.data();
+        uint32_t* col_pos = col_chunk + col_stride;
+        uint32_t* col_bit = col_pos + col_stride;
+        uint64_t bit = 0, pos = 0, chunks = 0;
         for (int64_t j = 0; j < m; ++j) {
             col_bit[(size_t)j] = (uint32_t)bit; col_pos[(size_t)j] = (uint32_t)pos; col_chunk[(size_t)j] = (uint32_t)chunks;
-            const uint64_t bit_j = bit;
-            uint64_t prev_end = bit;
-            for (uint32_t s = 0; s < S; ++s) {
-                const size_t at = (size_t)s * m + j;
-                const uint64_t r0 = (uint64_t)s * seg_rows, r1 = std::min<uint64_t>(r0 + seg_rows, (uint64_t)n);
-                seg_bit0[at] = (uint32_t)bit; seg_pos0[at] = (uint32_t)pos;
-                seg_prev_end[at] = (uint32_t)prev_end;
-                const uint64_t cnt = seg_nnz[at];
-                const uint64_t seg_bits = seg_codebits[at] + (shac ? 0 : (r1 - r0 - cnt) * zlen) + (rice ? seg_gapbits[at] : 0);
-                if (cnt) {
-                    const uint64_t trailing = r1 - 1 - seg_last[at];                 // zeros after the segment's last non-zero
-                    prev_end = bit + seg_bits - (shac ? 0 : trailing * zlen);
-                }
-                bit += seg_bits; pos += cnt;
-            }
+            bit += col_bits[(size_t)j]; pos += col_nnz[(size_t)j];
             chunks += (col_nnz[(size_t)j] + Cn - 1) / Cn;
-            max_col_bits = std::max(max_col_bits, bit - bit_j);
+        }
+        const size_t seg_stride = (4 * SM + 255) / 256 * 256 / 4;
+        std::vector<uint32_t> seg_arrays(3 * seg_stride, 0);
+        uint32_t* seg_bit0 = seg_arrays.data();
+        uint32_t* seg_pos0 = seg_bit0 + seg_stride;
+        uint32_t* seg_prev_end = seg_pos0 + seg_stride;
+        {
+            // running state per column: next stream bit, next CSC position, where its last non-zero ended
+            std::vector<uint64_t> cur_bit((size_t)m), cur_pos((size_t)m), cur_end((size_t)m);
+            for (int64_t j = 0; j < m; ++j) { cur_bit[(size_t)j] = col_bit[(size_t)j]; cur_pos[(size_t)j] = col_pos[(size_t)j]; cur_end[(size_t)j] = col_bit[(size_t)j]; }
+            for (uint32_t s = 0; s < S; ++s) {
+                const size_t row = (size_t)s * m;
+                const uint64_t r0 = (uint64_t)s * seg_rows, r1 = std::min<uint64_t>(r0 + seg_rows, (uint64_t)n);
+                for (int64_t j = 0; j < m; ++j) {
+                    const size_t at = row + j;
+                    seg_bit0[at] = (uint32_t)cur_bit[(size_t)j]; seg_pos0[at] = (uint32_t)cur_pos[(size_t)j];
+                    seg_prev_end[at] = (uint32_t)cur_end[(size_t)j];
+                    const uint64_t cnt = seg_nnz[at], seg_bits = seg_bits_at(s, at);
+                    if (cnt) {
+                        const uint64_t trailing = r1 - 1 - seg_last[at];             // zeros after the segment's last non-zero
+                        cur_end[(size_t)j] = cur_bit[(size_t)j] + seg_bits - (shac ? 0 : trailing * zlen);
+                    }
+                    cur_bit[(size_t)j] += seg_bits; cur_pos[(size_t)j] += cnt;
+                }
+            }
         }
         col_bit[(size_t)m] = (uint32_t)bit; col_pos[(size_t)m] = (uint32_t)pos; col_chunk[(size_t)m] = (uint32_t)chunks;
         if (bit != total_bits || pos != nnz) return HAC_EFORMAT;
@@ -567,12 +599,10 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(blob + d.off_stream),
                            (uint64_t)(d.blob_bytes - d.off_stream) / 4);
         if ((e = hipMemcpyAsync(blob, head.data(), head_bytes, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(blob + d.off_col_chunk, col_chunk.data(), 4 * ((size_t)m + 1), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(blob + d.off_col_pos, col_pos.data(), 4 * ((size_t)m + 1), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(blob + d.off_col_bit, col_bit.data(), 4 * ((size_t)m + 1), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(dptr(L.seg_bit0), seg_bit0.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(dptr(L.seg_pos0), seg_pos0.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(dptr(L.seg_prev_end), seg_prev_end.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if (d.off_col_pos - d.off_col_chunk != 4 * col_stride || d.off_col_bit - d.off_col_pos != 4 * col_stride ||
+            L.seg_pos0 - L.seg_bit0 != 4 * seg_stride || L.seg_prev_end - L.seg_pos0 != 4 * seg_stride) return HAC_EFORMAT;
+        if ((e = hipMemcpyAsync(blob + d.off_col_chunk, col_chunk, 4 * (2 * col_stride + (size_t)m + 1), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(dptr(L.seg_bit0), seg_bit0, 4 * (2 * seg_stride + SM), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
         // step 5 looks codes and lengths up by symbol
         if (!t.code.empty() && (e = hipMemcpyAsync(dptr(L.codes), t.code.data(), 4 * t.code.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
         if (!len.empty() && (e = hipMemcpyAsync(ws + L.lens, len.data(), len.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
