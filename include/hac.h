@@ -384,7 +384,8 @@ int hac_encode_dev(uint32_t format, const float *d_W, int64_t n, int64_t m, int6
  * over a short X, see HAC_LAUNCH_NO_X_LDS).  The workspace holds X re-laid out
  * feature-major, or, on the dense route (see hac_dot), the decoded index map
  * of W.  A launch that forces another way may need more: size the workspace
- * with hac_workspace_bytes_for(). */
+ * with hac_workspace_bytes_for().  Both return 0 for B <= 0 and for a header
+ * that no encoder could have written (zero sizes, unknown format). */
 size_t hac_workspace_bytes(const hac_desc_t *desc, int64_t B);
 size_t hac_workspace_bytes_for(const hac_desc_t *desc, int64_t B, const hac_launch_t *launch);
 

@@ -1159,9 +1159,24 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
 
 } // namespace
 
+namespace {
+
+// What the planning calls need of a header before they divide by its fields (the device calls
+// check more, in make_dev and im_dot_impl).
+bool desc_plausible(const hac_desc_t* d)
+{
+    if (!d || d->magic != 0x31434148u || d->version != 2) return false;
+    if (d->format != HAC_FORMAT_HAC && d->format != HAC_FORMAT_SHAC && d->format != HAC_FORMAT_IM) return false;
+    if (d->n < 1 || d->m < 1 || d->n > 0x7fffffffull || d->m > 0x7fffffffull) return false;
+    if (d->format != HAC_FORMAT_IM && (d->chunk < 1 || d->chunk > 65536 || d->lut_bits < 1 || d->lut_bits > 12)) return false;
+    return true;
+}
+
+} // namespace
+
 extern "C" size_t hac_workspace_bytes_for(const hac_desc_t* desc, int64_t B, const hac_launch_t* launch)
 {
-    if (!desc || B <= 0 || B > 0x7fffffffll) return 0;
+    if (!desc_plausible(desc) || B <= 0 || B > 0x7fffffffll) return 0;
     if (desc->format == HAC_FORMAT_IM)
         return hac_internal::plan_index_gemm((uint32_t)B, (uint32_t)desc->n, (uint32_t)desc->m).part_bytes;
     const DenseRoute dr = dense_route(desc, B, launch);
@@ -1174,7 +1189,7 @@ extern "C" size_t hac_workspace_bytes_for(const hac_desc_t* desc, int64_t B, con
 
 extern "C" int hac_dot_route(const hac_desc_t* desc, int64_t B, const hac_launch_t* launch)
 {
-    if (!desc || B < 0 || (desc->format != HAC_FORMAT_HAC && desc->format != HAC_FORMAT_SHAC)) return HAC_EINVAL;
+    if (!desc_plausible(desc) || B < 0 || B > 0x7fffffffll || desc->format == HAC_FORMAT_IM) return HAC_EINVAL;
     return dense_route(desc, B, launch).use ? HAC_ROUTE_DENSE : HAC_ROUTE_SPARSE;
 }
 
@@ -1237,7 +1252,7 @@ int plan_chain(const hac_layer_t* layers, uint32_t L, int64_t B, ChainPlan& P)
         if (!d || !layers[l].d_blob || layers[l].activation > HAC_ACT_RELU || layers[l].reserved) return HAC_EINVAL;
         if (d->magic != 0x31434148u || d->version != 2) return HAC_EINVAL;
         if (d->format != HAC_FORMAT_HAC && d->format != HAC_FORMAT_SHAC && d->format != HAC_FORMAT_IM) return HAC_EINVAL;
-        if (d->n < 1 || d->m < 1 || d->n > 0x7fffffffull || d->m > 0x7fffffffull) return HAC_EINVAL;
+        if (!desc_plausible(d)) return HAC_EINVAL;
         if (l && d->n != layers[l - 1].desc->m) return HAC_EINVAL;
     }
     if (!B) return HAC_OK;

@@ -515,6 +515,40 @@ def test_encoders_run_concurrently_from_threads():
     assert not wrong, wrong
 
 
+def test_planning_calls_survive_implausible_headers():
+    # hac_workspace_bytes / hac_dot_route / hac_forward_workspace_bytes size launches from header
+    # fields; a header with zero or absurd fields must give "no answer", not a division by zero
+    import random
+    rnd = random.Random(5)
+    W = workloads.make_layer(60, 20, 0.02, 0.7, 8, "uniform", 3)
+    good = {"hac": hac.hac_encode(W).desc, "shac": hac.shac_encode(W).desc, "im": hac.im_encode(W).desc}
+    lib = hac.load_library()
+    for name, d0 in good.items():
+        assert hac.hac_workspace_bytes(d0, 40) >= 0
+        for field, _ in hac.Desc._fields_:
+            for value in (0, 1, 0xffffffff, 0x7fffffff, rnd.getrandbits(31)):
+                d = hac.Desc.from_buffer_copy(bytes(d0))
+                try:
+                    setattr(d, field, value)
+                except (TypeError, ValueError):           # array fields
+                    continue
+                for B in (1, 8, 40, 300):
+                    lib.hac_workspace_bytes(C.byref(d), B)
+                    lib.hac_dot_route(C.byref(d), B, None)
+                    layer = hac.Layer()
+                    layer.desc = C.pointer(d)
+                    layer.d_blob = 256                    # never dereferenced by the size query
+                    lib.hac_forward_workspace_bytes(C.byref(layer), 1, B)
+        for field in ("n", "m", "chunk", "magic", "version"):
+            d = hac.Desc.from_buffer_copy(bytes(d0))
+            setattr(d, field, 0)
+            if field == "chunk" and name == "im":
+                continue
+            assert lib.hac_workspace_bytes(C.byref(d), 40) == 0, (name, field)
+            if name != "im":
+                assert lib.hac_dot_route(C.byref(d), 40, None) < 0, (name, field)
+
+
 def test_negative_zero_is_stored_as_zero():
     W = np.array([[-0.0, 1.0], [0.0, -0.0]], dtype=np.float32)
     for enc in (hac.hac_encode, hac.shac_encode):
