@@ -740,9 +740,20 @@ thread_local int g_last_hip_error = 0;
 
 int hip_fail(hipError_t e) { g_last_hip_error = (int)e; return HAC_EHIP; }
 
+// What the planning calls need of a header before they divide by its fields (the device calls
+// check more, in make_dev and im_dot_impl).
+bool desc_plausible(const hac_desc_t* d)
+{
+    if (!d || d->magic != 0x31434148u || d->version != 2) return false;
+    if (d->format != HAC_FORMAT_HAC && d->format != HAC_FORMAT_SHAC && d->format != HAC_FORMAT_IM) return false;
+    if (d->n < 1 || d->m < 1 || d->n > 0x7fffffffull || d->m > 0x7fffffffull) return false;
+    if (d->format != HAC_FORMAT_IM && (d->chunk < 1 || d->chunk > 65536 || d->lut_bits < 1 || d->lut_bits > 12)) return false;
+    return true;
+}
+
 int make_dev(const hac_desc_t* desc, const void* d_blob, uint32_t format, DevBlob& d)
 {
-    if (!desc || !d_blob) return HAC_EINVAL;
+    if (!desc || !d_blob || !desc_plausible(desc)) return HAC_EINVAL;
     if (desc->magic != 0x31434148u || desc->version != 2 || desc->format != format) return HAC_EINVAL;
     if (reinterpret_cast<uintptr_t>(d_blob) % 256) return HAC_EINVAL;
     if (desc->lut_bits < 1 || desc->lut_bits > 12 || desc->lmax > 32) return HAC_EINVAL;
@@ -1159,21 +1170,6 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
 
 } // namespace
 
-namespace {
-
-// What the planning calls need of a header before they divide by its fields (the device calls
-// check more, in make_dev and im_dot_impl).
-bool desc_plausible(const hac_desc_t* d)
-{
-    if (!d || d->magic != 0x31434148u || d->version != 2) return false;
-    if (d->format != HAC_FORMAT_HAC && d->format != HAC_FORMAT_SHAC && d->format != HAC_FORMAT_IM) return false;
-    if (d->n < 1 || d->m < 1 || d->n > 0x7fffffffull || d->m > 0x7fffffffull) return false;
-    if (d->format != HAC_FORMAT_IM && (d->chunk < 1 || d->chunk > 65536 || d->lut_bits < 1 || d->lut_bits > 12)) return false;
-    return true;
-}
-
-} // namespace
-
 extern "C" size_t hac_workspace_bytes_for(const hac_desc_t* desc, int64_t B, const hac_launch_t* launch)
 {
     if (!desc_plausible(desc) || B <= 0 || B > 0x7fffffffll) return 0;
@@ -1199,8 +1195,8 @@ int im_dot_impl(const hac_desc_t* desc, const void* d_blob, const float* d_X, in
                 float* d_Y, int64_t ldy, void* d_ws, size_t ws_bytes, hac_stream_t stream,
                 const float* bias, uint32_t relu)
 {
-    if (!desc || !d_blob) return HAC_EINVAL;
-    if (desc->magic != 0x31434148u || desc->version != 2 || desc->format != HAC_FORMAT_IM) return HAC_EINVAL;
+    if (!desc || !d_blob || !desc_plausible(desc)) return HAC_EINVAL;
+    if (desc->format != HAC_FORMAT_IM) return HAC_EINVAL;
     if (reinterpret_cast<uintptr_t>(d_blob) % 256) return HAC_EINVAL;
     if (desc->n > 0x7fffffffull || desc->m > 0x7fffffffull) return HAC_EINVAL;
     if ((desc->ent_bits != 8 && desc->ent_bits != 16) || desc->k_sym < 1 || desc->k_sym > 65536) return HAC_EINVAL;

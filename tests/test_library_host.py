@@ -547,6 +547,10 @@ def test_planning_calls_survive_implausible_headers():
             assert lib.hac_workspace_bytes(C.byref(d), 40) == 0, (name, field)
             if name != "im":
                 assert lib.hac_dot_route(C.byref(d), 40, None) < 0, (name, field)
+            # the device calls turn such a header down before anything is launched (fake, aligned
+            # pointers: they are never dereferenced on the host)
+            f = {"hac": lib.hac_dot, "shac": lib.shac_dot, "im": lib.im_dot}[name]
+            assert f(C.byref(d), 4096, 8192, 40, 100, 12288, 100, 16384, 1 << 20, None, None) == -1, (name, field)
 
 
 def test_negative_zero_is_stored_as_zero():
