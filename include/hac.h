@@ -184,7 +184,8 @@ typedef struct {
 
 /* Optional launch overrides for the dot calls (NULL = library defaults).  Any
  * field left 0 keeps its default.  Values outside the documented range give
- * HAC_EINVAL; they never change the result, only how the work is split. */
+ * HAC_EINVAL.  They change how the work is split, never what is computed; where
+ * a split changes the order of the fp32 additions, the flag says so. */
 typedef struct {
     uint32_t cols_per_wave;   /* columns of W one wavefront handles, 1..32                 */
     uint32_t waves_per_block; /* 1..16                                                     */
