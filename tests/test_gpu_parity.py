@@ -342,6 +342,23 @@ def test_calls_from_several_threads_on_their_own_streams(hac):
     assert not failures, failures
 
 
+def test_batch_beyond_65536_rows_on_both_routes(hac):
+    # more batch rows than a grid dimension has entries: 257 tiles of 256 batch columns on the sparse
+    # route, 2049 row tiles on the matrix cores, the index map's small layout left far behind
+    W = workloads.layer(1)
+    B = 65537
+    X = workloads.make_batch(B, W.shape[0], 77) - np.float32(0.25)
+    Xd = torch.from_numpy(X).to(dev())
+    for name, enc, f in (("hac", hac.hac_encode, hac.hac_dot), ("shac", hac.shac_encode, hac.shac_dot),
+                         ("im", hac.im_encode, hac.im_dot)):
+        db = enc(W).to_device(dev())
+        for variant in ((0,) if name == "im" else (0x400, 0x800)):
+            print(f"[case] {name} B={B} variant={variant:#x}", flush=True)
+            Y = f(db, Xd) if name == "im" else f(db, Xd, launch=hac.Launch(variant=variant))
+            torch.cuda.synchronize()
+            check_y(Y, X, W, f"{name} B={B} variant={variant:#x}")
+
+
 def test_strided_x_and_y(hac):
     W = workloads.scaled(1, 200, 40)
     Xbig = torch.from_numpy(workloads.make_batch(16, 260, 4)).to(dev())
