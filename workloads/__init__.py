@@ -267,6 +267,11 @@ def stress_cases() -> Dict[str, np.ndarray]:
             rows = s0 + np.flatnonzero(rng.random(900) < 0.7)
             cl[rows, j] = rng.choice(np.array([-2.0, -1.0, 0.5, 1.5], dtype=np.float32), size=rows.size)
     out["clustered_rows_300000x3"] = cl
+    # very wide and short: tens of thousands of columns of a few non-zeros each, many of them empty
+    wide = np.zeros((24, 20000), dtype=np.float32)
+    mask = rng.random(wide.shape) < 0.08
+    wide[mask] = rng.choice(np.array([-3.0, -0.75, 0.125, 0.5, 2.5], dtype=np.float32), size=int(mask.sum()))
+    out["wide_24x20000"] = wide
     return out
 
 
