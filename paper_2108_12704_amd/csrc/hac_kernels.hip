@@ -332,21 +332,26 @@ __device__ __forceinline__ void fma_entries(const uint2* list, uint32_t winbase,
             for (int i2 = 0; i2 < NB; ++i2) acc[i2] = fmaf(G.x[k][i2], wv, acc[i2]);
         }
     }
-    // last, partial group: entries past the end read entry `idx` again and are not added
+    // last, partial group: only the entries that exist are fetched (a lane that is switched off asks
+    // the memory path for nothing; a repeated fetch of some valid row would cost it a line like any other)
     const uint32_t rest = count - full * kPipe;
     if (rest) {
         EntryGroup<NB, kPipe> G;
 #pragma unroll
-        for (int k = 0; k < kPipe; ++k) G.e[k] = list[idx + ((uint32_t)k < rest ? k * ng : 0u)];
+        for (int k = 0; k < kPipe; ++k) {
+            G.e[k] = make_uint2(0u, 0u);
 #pragma unroll
-        for (int k = 0; k < kPipe; ++k) VecLoad<NB>::ld(xt + (uint64_t)G.e[k].x * Bp, G.x[k]);
+            for (int i2 = 0; i2 < NB; ++i2) G.x[k][i2] = 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < kPipe; ++k) if ((uint32_t)k < rest) G.e[k] = list[idx + k * ng];
+#pragma unroll
+        for (int k = 0; k < kPipe; ++k) if ((uint32_t)k < rest) VecLoad<NB>::ld(xt + (uint64_t)G.e[k].x * Bp, G.x[k]);
 #pragma unroll
         for (int k = 0; k < kPipe; ++k) {
-            if ((uint32_t)k < rest) {
-                const float wv = __uint_as_float(G.e[k].y);
+            const float wv = __uint_as_float(G.e[k].y);          // 0.0 for an entry that does not exist
 #pragma unroll
-                for (int i2 = 0; i2 < NB; ++i2) acc[i2] = fmaf(G.x[k][i2], wv, acc[i2]);
-            }
+            for (int i2 = 0; i2 < NB; ++i2) acc[i2] = fmaf(G.x[k][i2], wv, acc[i2]);
         }
     }
 }
