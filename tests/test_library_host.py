@@ -606,3 +606,52 @@ def test_damaged_blobs_are_rejected(enc):
     b = good.copy()
     b[int(d.off_stream):int(d.off_stream) + 8] ^= 0xff
     assert lib.hac_validate(b.ctypes.data, b.size, 1) in (0, -3)
+
+
+def test_random_damage_never_crashes_validation_or_decode():
+    """Random bit and byte damage anywhere in a blob (half of it in the header and tables): the deep
+    check either rejects the blob or accepts it, and what it accepts the sequential decoder walks
+    without leaving the matrix (an out-of-range row, column or symbol would write outside the buffers
+    this test hands it and bring the process down)."""
+    lib = hac.load_library()
+    rng = np.random.default_rng(20240611)
+    W = workloads.scaled(1, 120, 17)
+    blobs = [hac.hac_encode(W), hac.shac_encode(W), hac.shac_encode(W, ri_coding=hac.RI_RICE), hac.im_encode(W),
+             hac.hac_encode(W, chunk_nnz=4), hac.shac_encode(W, ri_bits=32)]
+
+    def damage(b):
+        for _ in range(int(rng.integers(1, 4))):
+            pos = int(rng.integers(0, min(4096, b.size))) if rng.random() < 0.5 else int(rng.integers(0, b.size))
+            if rng.random() < 0.3:
+                b[pos] = np.uint8(rng.integers(0, 256))
+            else:
+                b[pos] ^= np.uint8(1 << int(rng.integers(0, 8)))
+
+    accepted = 0
+    for blob in blobs:
+        for _ in range(1500):
+            b = blob.data.copy()
+            damage(b)
+            rc = lib.hac_validate(b.ctypes.data, b.size, 1)
+            assert rc in (0, -3)
+            if rc == 0:
+                accepted += 1
+                got = hac.Blob(b)
+                if (int(got.desc.n), int(got.desc.m)) != W.shape:
+                    # only the row count of an address-map blob can change and stay consistent: the same
+                    # non-zeros in a taller matrix (every other format codes all n * m entries)
+                    assert got.desc.format == hac.HAC_FORMAT_SHAC and int(got.desc.m) == W.shape[1]
+                    continue
+                assert got.decode_host()[0].shape == W.shape
+    net = hac.hac_net_encode([W, workloads.scaled(2, 17, 9)], [hac.HAC_FORMAT_HAC, hac.HAC_FORMAT_SHAC])
+    for _ in range(1500):
+        b = net.data.copy()
+        damage(b)
+        rc = lib.hac_net_validate(b.ctypes.data, b.size, 1)
+        assert rc in (0, -3)
+        if rc == 0:
+            accepted += 1
+            got = hac.NetBlob(b)
+            for l in range(len(got.layers)):
+                got.decode_host(l)
+    assert accepted > 100                                              # damage in padding and in stream bits that still decode
