@@ -32,19 +32,32 @@ struct DevBlob {
 };
 
 // (relative bit offset, first row) of chunk g
+// request_entry only loads; entry_fields takes the loaded bits apart.  A kernel that has other
+// loads to issue calls the two apart, so that no wait sits between its loads.
+__device__ __forceinline__ uint2 request_entry(const DevBlob& d, uint32_t g)
+{
+    uint2 raw = make_uint2(0u, 0u);
+    if (d.ent_bits == 32) raw.x = static_cast<const uint32_t*>(d.ent)[g];
+    else if (d.ent_bits == 16) raw.x = static_cast<const uint16_t*>(d.ent)[g];
+    else raw = static_cast<const uint2*>(d.ent)[g];
+    return raw;
+}
+
+__device__ __forceinline__ void entry_fields(const DevBlob& d, const uint2& raw, uint32_t& rel, uint32_t& row)
+{
+    if (d.ent_bits == 32) {
+        rel = raw.x >> d.row_bits;                   // sHAC: row_bits = 0
+        row = raw.x & ((1u << d.row_bits) - 1u);
+    } else if (d.ent_bits == 16) {
+        rel = raw.x; row = 0;
+    } else {
+        row = raw.x; rel = raw.y;
+    }
+}
+
 __device__ __forceinline__ void load_entry(const DevBlob& d, uint32_t g, uint32_t& rel, uint32_t& row)
 {
-    row = 0;
-    if (d.ent_bits == 32) {
-        const uint32_t e = static_cast<const uint32_t*>(d.ent)[g];
-        rel = e >> d.row_bits;                       // sHAC: row_bits = 0
-        row = e & ((1u << d.row_bits) - 1u);
-    } else if (d.ent_bits == 16) {
-        rel = static_cast<const uint16_t*>(d.ent)[g];
-    } else {
-        const uint2 e = static_cast<const uint2*>(d.ent)[g];
-        row = e.x; rel = e.y;
-    }
+    entry_fields(d, request_entry(d, g), rel, row);
 }
 
 // ---------------------------------------------------------------------------
@@ -128,7 +141,48 @@ __device__ __forceinline__ uint32_t table_words_dev(const DevBlob& d)
 }
 
 // All threads of the block copy the tables; the caller synchronises afterwards.
-__device__ __forceinline__ Tables load_tables(const DevBlob& d, uint32_t* smem)
+//
+// The copy is split in three so that every trip to memory carries as many loads as possible and a
+// kernel can put its own loads beside them: request_tables issues everything that depends on
+// nothing (first-level entries, canonical table, codebook, symbol order), request_table_values the
+// shared values of the first-level entries (they depend on the entries), store_tables writes LDS.
+// A loop of load / store pairs would pay one trip per turn and per table instead.  Loads of the
+// first kTabTurns turns of every loop are issued from clamped, valid indices on every thread;
+// what a small block or a long table leaves over is copied the plain way.
+constexpr int kTabTurns = 4;                        // (the asm statement in store_tables names four values)
+struct TableRegs { uint32_t e[kTabTurns], v[kTabTurns]; uint32_t canon, cb, sort; };
+
+__device__ __forceinline__ TableRegs request_tables(const DevBlob& d)
+{
+    TableRegs r;
+    const uint32_t nl = 1u << d.lut_bits;
+#pragma unroll
+    for (int k = 0; k < kTabTurns; ++k) {
+        const uint32_t i = threadIdx.x + k * blockDim.x;
+        r.e[k] = d.lut[i < nl ? i : nl - 1u];
+        r.v[k] = 0u;
+    }
+    r.canon = d.canon[threadIdx.x < 99u ? threadIdx.x : 98u];
+    // no branch around a load: the number of loads in flight is then the same on every path, and a
+    // later wait for these can leave younger loads travelling.  Without symbols (an empty address
+    // map) the canonical table stands in as a valid address.
+    const uint32_t* cbp = d.k_sym ? reinterpret_cast<const uint32_t*>(d.codebook) : d.canon;
+    const uint32_t* sop = d.k_sym ? d.symsort : d.canon;
+    const uint32_t last = d.k_sym ? d.k_sym - 1u : 0u;
+    const uint32_t i = threadIdx.x < last ? threadIdx.x : last;
+    r.cb = cbp[i];
+    r.sort = sop[i];
+    return r;
+}
+
+__device__ __forceinline__ void request_table_values(const DevBlob& d, TableRegs& r)
+{
+    const uint32_t* cbp = d.k_sym ? reinterpret_cast<const uint32_t*>(d.codebook) : d.canon;
+#pragma unroll
+    for (int k = 0; k < kTabTurns; ++k) r.v[k] = cbp[(r.e[k] & 63u) ? r.e[k] >> 6 : 0u];
+}
+
+__device__ __forceinline__ Tables store_tables(const DevBlob& d, uint32_t* smem, TableRegs& r)
 {
     const uint32_t nl = 1u << d.lut_bits;
     const uint32_t k4 = (d.k_sym + 3u) & ~3u;
@@ -136,20 +190,38 @@ __device__ __forceinline__ Tables load_tables(const DevBlob& d, uint32_t* smem)
     uint32_t* s_canon = smem + 2 * nl;
     float* s_cb = reinterpret_cast<float*>(s_canon + 100);
     uint32_t* s_sort = reinterpret_cast<uint32_t*>(s_cb) + k4;
-    for (uint32_t i = threadIdx.x; i < nl; i += blockDim.x) {
+    // The values pass through an empty asm statement first: their loads then stay where they were
+    // issued (the compiler would otherwise move a load down beside the guarded store that uses it,
+    // behind every load issued since).
+    asm volatile("" : "+v"(r.v[0]), "+v"(r.v[1]), "+v"(r.v[2]), "+v"(r.v[3]));
+#pragma unroll
+    for (int k = 0; k < kTabTurns; ++k) {
+        const uint32_t i = threadIdx.x + k * blockDim.x;
+        if (i < nl) s_lut2[i] = make_uint2(r.e[k], (r.e[k] & 63u) ? r.v[k] : 0u);
+    }
+    for (uint32_t i = threadIdx.x + kTabTurns * blockDim.x; i < nl; i += blockDim.x) {
         const uint32_t e = d.lut[i];
         s_lut2[i] = make_uint2(e, (e & 63u) ? __float_as_uint(d.codebook[e >> 6]) : 0u);
     }
-    for (uint32_t i = threadIdx.x; i < 99u; i += blockDim.x) s_canon[i] = d.canon[i];
+    if (threadIdx.x < 99u) s_canon[threadIdx.x] = r.canon;
+    for (uint32_t i = threadIdx.x + blockDim.x; i < 99u; i += blockDim.x) s_canon[i] = d.canon[i];
     Tables t;
     t.lut2 = s_lut2; t.canon = s_canon; t.small = d.k_sym <= kCodebookLdsMax;
     if (t.small) {
-        for (uint32_t i = threadIdx.x; i < d.k_sym; i += blockDim.x) { s_cb[i] = d.codebook[i]; s_sort[i] = d.symsort[i]; }
+        if (threadIdx.x < d.k_sym) { s_cb[threadIdx.x] = __uint_as_float(r.cb); s_sort[threadIdx.x] = r.sort; }
+        for (uint32_t i = threadIdx.x + blockDim.x; i < d.k_sym; i += blockDim.x) { s_cb[i] = d.codebook[i]; s_sort[i] = d.symsort[i]; }
         t.cb = s_cb; t.symsort = s_sort;
     } else {
         t.cb = d.codebook; t.symsort = d.symsort;
     }
     return t;
+}
+
+__device__ __forceinline__ Tables load_tables(const DevBlob& d, uint32_t* smem)
+{
+    TableRegs r = request_tables(d);
+    request_table_values(d, r);
+    return store_tables(d, smem, r);
 }
 
 // ---------------------------------------------------------------------------

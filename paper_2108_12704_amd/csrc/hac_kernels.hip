@@ -361,12 +361,94 @@ template <int NB> struct BatchTraits {
     static constexpr int kMaxThreads = 1024;
 };
 
-// Copy words [wlo, wlo + nw) of `src` (wlo a multiple of 4) to LDS with 128-bit loads.
-__device__ __forceinline__ void stage_words(uint32_t* dst, const uint32_t* src, uint32_t wlo, uint32_t nw, uint32_t lane)
+// The loaded values pass through an empty asm statement: all the loads above it are issued before
+// the first wait, and none of them is moved down into the guarded store that uses it (the compiler
+// would otherwise turn load, load, ..., store, store, ... back into load / wait / store turns).
+#define HAC_PIN_U4(q) "+v"((q).x), "+v"((q).y), "+v"((q).z), "+v"((q).w)
+__device__ __forceinline__ void pin_loads(uint4 (&a)[4])
+{
+    asm volatile("" : HAC_PIN_U4(a[0]), HAC_PIN_U4(a[1]), HAC_PIN_U4(a[2]), HAC_PIN_U4(a[3]));
+}
+
+// Copy words [wlo, wlo + nw) of `src` (wlo and nw multiples of 4, nw >= 4) to LDS with 128-bit
+// loads, four per lane in flight (4 KB per wave and trip to memory): the loads of a turn are issued
+// from clamped indices before the first is stored.  Starts at 16-byte piece `first`.
+__device__ __forceinline__ void stage_words(uint32_t* dst, const uint32_t* src, uint32_t wlo, uint32_t nw, uint32_t lane,
+                                            uint32_t first = 0)
 {
     const uint4* s4 = reinterpret_cast<const uint4*>(src + wlo);
     uint4* d4 = reinterpret_cast<uint4*>(dst);
-    for (uint32_t i = lane; i * 4 < nw; i += kWave) d4[i] = s4[i];
+    const uint32_t n4 = nw >> 2;
+    for (uint32_t base = first; base < n4; base += 4 * kWave) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t i = base + lane + k * kWave;
+            v[k] = s4[i < n4 ? i : n4 - 1u];
+        }
+        pin_loads(v);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t i = base + lane + k * kWave;
+            if (i < n4) d4[i] = v[k];
+        }
+    }
+}
+
+// A wave's stream words and, with RI, its ri words, in two steps: request_stage issues the loads of
+// the first turn(s) of the copies, finish_stage stores them and copies what is left.  In between a
+// kernel can finish other work whose loads are older (the decode tables and the block's barrier
+// behind them) while these travel.  First trip: 4 KB of a HAC stream (a column of the largest
+// layer here has 3.5 KB); with ri words, 1 KB of the stream and 1 KB of ri (the codewords of the
+// non-zeros alone are short).  Every load instruction of a wave occupies the address path for its
+// 64 lanes whatever they ask for, so turns that are rarely needed are left to the second step.
+// `staged` false (nothing to stage, or more than fits): the loads are still issued, from `safe`
+// (16 valid, aligned bytes), so that the number of loads in flight does not depend on the path.
+template <bool RI> struct StageRegs { static constexpr int kTurns = RI ? 1 : 4; uint4 s[4], r; };
+
+template <bool RI>
+__device__ __forceinline__ void request_stage(StageRegs<RI>& q, bool staged, const uint32_t* safe,
+                                              const uint32_t* stream, uint32_t swlo, uint32_t snw,
+                                              const uint32_t* ri, uint32_t rwlo, uint32_t rnw, uint32_t lane)
+{
+    const uint4* s4 = reinterpret_cast<const uint4*>(staged ? stream + swlo : safe);
+    const uint32_t sn4 = staged ? snw >> 2 : 1u, rn4 = staged ? rnw >> 2 : 1u;
+#pragma unroll
+    for (int k = 0; k < StageRegs<RI>::kTurns; ++k) {
+        const uint32_t i = lane + k * kWave;
+        q.s[k] = s4[i < sn4 ? i : sn4 - 1u];
+    }
+    if constexpr (RI) {
+        const uint4* r4 = reinterpret_cast<const uint4*>(staged ? ri + rwlo : safe);
+        q.r = r4[lane < rn4 ? lane : rn4 - 1u];
+    }
+}
+
+template <bool RI>
+__device__ __forceinline__ void finish_stage(StageRegs<RI>& q, uint32_t* sdst, const uint32_t* stream, uint32_t swlo, uint32_t snw,
+                                             uint32_t* rdst, const uint32_t* ri, uint32_t rwlo, uint32_t rnw, uint32_t lane)
+{
+    const uint32_t sn4 = snw >> 2, rn4 = rnw >> 2;
+    if constexpr (RI) asm volatile("" : HAC_PIN_U4(q.s[0]), HAC_PIN_U4(q.r));
+    else pin_loads(q.s);
+#pragma unroll
+    for (int k = 0; k < StageRegs<RI>::kTurns; ++k) {
+        const uint32_t i = lane + k * kWave;
+        if (i < sn4) reinterpret_cast<uint4*>(sdst)[i] = q.s[k];
+    }
+    if constexpr (RI) {
+        if (lane < rn4) reinterpret_cast<uint4*>(rdst)[lane] = q.r;
+    }
+    stage_words(sdst, stream, swlo, snw, lane, StageRegs<RI>::kTurns * kWave);
+    if constexpr (RI) stage_words(rdst, ri, rwlo, rnw, lane, kWave);
+}
+
+// Barrier of the block that orders LDS only: loads from global memory stay in flight across it.
+__device__ __forceinline__ void block_sync_lds()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // gw: lanes per group (power of two); a pass over the list covers gw * NB batch
@@ -416,14 +498,10 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
             cbit_l = d.colbit[c0 + lane];
         }
     }
-    const Tables tb = load_tables(d, smem);
-    __syncthreads();
-    if (!live) {
-        // sync_passes: every wave of the block meets at a barrier once per pass (see accumulate)
-        if (MP && sync_passes) for (uint32_t p = 0; p < live_passes; ++p) __syncthreads();
-        return;
-    }
-    HAC_MARK(1);
+    // Two trips to memory before the first codeword is decoded: (1) the column index above and
+    // what the tables need first, (2) chunk entries, stream (and ri) words and the values of the
+    // first-level table.  One barrier then covers the tables and the staged words.
+    TableRegs tr = request_tables(d);
     const uint32_t c1 = c0 + ncols;
     const uint32_t gfirst = (uint32_t)__shfl((int)cchunk_l, 0, kWave);
     const uint32_t g1 = (uint32_t)__shfl((int)cchunk_l, (int)ncols, kWave);
@@ -444,12 +522,20 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
     const uint32_t rnw = SHAC ? ((((uint32_t)(rb_hi >> 5) + 2) - rwlo + 4) & ~3u) : 0u;
     const bool staged = posend > posbase && snw + rnw <= sbuf_words;
     // index entries of the first batch of chunks (requested together with the staging loads)
-    uint32_t ent_rel = 0, ent_row = 0;
-    if (gfirst + lane < g1) load_entry(d, gfirst + lane, ent_rel, ent_row);
-    if (staged) {
-        stage_words(sbuf, d.stream, swlo, snw, lane);
-        if (SHAC) stage_words(sbuf + snw, d.ri, rwlo, rnw, lane);
+    uint2 ent_raw = make_uint2(0u, 0u);
+    if (gfirst + lane < g1) ent_raw = request_entry(d, gfirst + lane);
+    request_table_values(d, tr);
+    StageRegs<SHAC> sq;
+    request_stage<SHAC>(sq, staged, d.canon, d.stream, swlo, snw, d.ri, rwlo, rnw, lane);
+    const Tables tb = store_tables(d, smem, tr);
+    block_sync_lds();                                        // the tables; the staged words are still on their way
+    if (!live) {
+        // sync_passes: every wave of the block meets at a barrier once per pass (see accumulate)
+        if (MP && sync_passes) for (uint32_t p = 0; p < live_passes; ++p) __syncthreads();
+        return;
     }
+    HAC_MARK(1);
+    if (staged) finish_stage<SHAC>(sq, sbuf, d.stream, swlo, snw, sbuf + snw, d.ri, rwlo, rnw, lane);
     wave_sync();
     HAC_MARK(2);
     const WordSrc<true> s_lds = { sbuf, swlo };
@@ -518,6 +604,8 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
         const uint32_t col_pos1 = (uint32_t)__shfl((int)cpos_l, (int)rel + 1, kWave);
         const uint32_t col_bit0 = (uint32_t)__shfl((int)cbit_l, (int)rel, kWave);
         ChunkState st;
+        uint32_t ent_rel, ent_row;
+        entry_fields(d, ent_raw, ent_rel, ent_row);
         st.bp = col_bit0 + ent_rel;
         st.row = ent_row;
         st.wpos = col_pos0 + (g - col_chunk0) * d.chunk;
@@ -526,7 +614,7 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
         const uint32_t pbeg = (uint32_t)__shfl((int)st.wpos, 0, kWave);
         const uint32_t pend = (uint32_t)__shfl((int)st.wend, (int)(nact - 1), kWave);
         // entries of the next batch travel while this one is decoded
-        if (gb + kWave + lane < g1) load_entry(d, gb + kWave + lane, ent_rel, ent_row);
+        if (gb + kWave + lane < g1) ent_raw = request_entry(d, gb + kWave + lane);
 
         for (uint32_t winbase = pbeg; winbase < pend; winbase += list_cap) {
             const uint32_t winend = winbase + list_cap < pend ? winbase + list_cap : pend;
@@ -618,6 +706,8 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, uint64_t l
             cbit_l = d.colbit[c0 + lane];
         }
     }
+    // two trips to memory before the first codeword is decoded, as in the batch kernel
+    TableRegs tr = request_tables(d);
     float* xs = reinterpret_cast<float*>(smem + table_words_dev(d));      // XLDS: [row of W][NB]
     if (XLDS) {
         // a thread takes whole rows of W: NB coalesced reads (one per batch row), one contiguous store
@@ -629,10 +719,6 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, uint64_t l
             for (int i = 0; i < NB; ++i) xs[(uint64_t)r * NB + i] = v[i];
         }
     }
-    const Tables tb = load_tables(d, smem);
-    __syncthreads();
-    if (!live) return;
-    HAC_MARK(1);
     const uint32_t gfirst = (uint32_t)__shfl((int)cchunk_l, 0, kWave);
     const uint32_t g1 = (uint32_t)__shfl((int)cchunk_l, (int)ncols, kWave);
     const uint32_t posbase = (uint32_t)__shfl((int)cpos_l, 0, kWave);
@@ -643,7 +729,6 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, uint64_t l
     uint32_t* sbuf = smem + table_words_dev(d) + (XLDS ? x_words : 0u) + (uint64_t)wib * (sbuf_words + sum_words);
     float* colsum = reinterpret_cast<float*>(sbuf + sbuf_words);          // [column][NB]
     lds_cf32* xs_lds = (lds_cf32*)xs;
-    for (uint32_t i = lane; i < ncols * NB; i += kWave) colsum[i] = 0.0f;
 
     const uint32_t swlo = (bit_lo >> 5) & ~3u;
     const uint32_t snw = (((bit_hi >> 5) + 4) - swlo + 4) & ~3u;
@@ -651,12 +736,18 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, uint64_t l
     const uint32_t rwlo = (uint32_t)(rb_lo >> 5) & ~3u;
     const uint32_t rnw = SHAC ? ((((uint32_t)(rb_hi >> 5) + 2) - rwlo + 4) & ~3u) : 0u;
     const bool staged = posend > posbase && snw + rnw <= sbuf_words;
-    uint32_t ent_rel = 0, ent_row = 0;
-    if (gfirst + lane < g1) load_entry(d, gfirst + lane, ent_rel, ent_row);
-    if (staged) {
-        stage_words(sbuf, d.stream, swlo, snw, lane);
-        if (SHAC) stage_words(sbuf + snw, d.ri, rwlo, rnw, lane);
-    }
+    uint2 ent_raw = make_uint2(0u, 0u);
+    if (gfirst + lane < g1) ent_raw = request_entry(d, gfirst + lane);
+    request_table_values(d, tr);
+    StageRegs<SHAC> sq;
+    request_stage<SHAC>(sq, staged, d.canon, d.stream, swlo, snw, d.ri, rwlo, rnw, lane);
+    const Tables tb = store_tables(d, smem, tr);
+    for (uint32_t i = lane; i < ncols * NB; i += kWave) colsum[i] = 0.0f;
+    if (XLDS) __syncthreads();                               // the block's copy of X came through plain loads
+    else block_sync_lds();                                   // the tables; the staged words are still on their way
+    if (!live) return;
+    HAC_MARK(1);
+    if (staged) finish_stage<SHAC>(sq, sbuf, d.stream, swlo, snw, sbuf + snw, d.ri, rwlo, rnw, lane);
     wave_sync();
     HAC_MARK(2);
     const WordSrc<true> s_lds = { sbuf, swlo };
@@ -675,12 +766,14 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, uint64_t l
         const uint32_t col_pos1 = (uint32_t)__shfl((int)cpos_l, (int)rel + 1, kWave);
         const uint32_t col_bit0 = (uint32_t)__shfl((int)cbit_l, (int)rel, kWave);
         ChunkState st;
+        uint32_t ent_rel, ent_row;
+        entry_fields(d, ent_raw, ent_rel, ent_row);
         st.bp = col_bit0 + ent_rel;
         st.row = ent_row;
         st.wpos = col_pos0 + (g - col_chunk0) * d.chunk;
         st.wend = st.wpos + d.chunk < col_pos1 ? st.wpos + d.chunk : col_pos1;
         if (!active) { st.wpos = 0; st.wend = 0; }
-        if (gb + kWave + lane < g1) load_entry(d, gb + kWave + lane, ent_rel, ent_row);
+        if (gb + kWave + lane < g1) ent_raw = request_entry(d, gb + kWave + lane);
 
         // a[] += pv * px[] is applied when the next non-zero has been decoded, just before px is
         // fetched again, so the fetch of X for one non-zero travels during a whole decode step
