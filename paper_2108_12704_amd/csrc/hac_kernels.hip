@@ -209,9 +209,16 @@ transpose_pad_kernel(const float* __restrict__ X, uint32_t B, uint32_t n, uint64
     __shared__ float tile[32][33];
     const uint32_t tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
     const uint32_t r0 = blockIdx.x * 32, b0 = blockIdx.y * 32;
-    for (uint32_t k = 0; k < 32; k += 8) {
-        const uint32_t b = b0 + ty + k, r = r0 + tx;
-        tile[ty + k][tx] = (b < B && r < n) ? X[(uint64_t)b * ldx + r] : 0.0f;
+    float v[4];                                        // clamped addresses: four loads in flight, zeros put in afterwards
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k) {
+        const uint32_t b = b0 + ty + 8 * k, r = r0 + tx;
+        v[k] = X[(uint64_t)(b < B ? b : B - 1) * ldx + (r < n ? r : n - 1)];
+    }
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k) {
+        const uint32_t b = b0 + ty + 8 * k, r = r0 + tx;
+        tile[ty + 8 * k][tx] = (b < B && r < n) ? v[k] : 0.0f;
     }
     __syncthreads();
     for (uint32_t k = 0; k < 32; k += 8) {
@@ -229,21 +236,38 @@ transpose_panel32_kernel(const float* __restrict__ X, uint32_t B, uint32_t n, ui
 {
     __shared__ float tile[32][129];
     const uint32_t r0 = blockIdx.x * 128, b0 = blockIdx.y * 32;
+    // All loads of a thread are issued before the first is used: rows past B and features past n
+    // are read from a clamped, valid address and replaced by zero afterwards (a guarded load would
+    // be compiled into load / wait / store turns, one trip to memory each).
     if (vec && r0 + 128 <= n) {
+        float4 v[4];
 #pragma unroll
         for (uint32_t i = 0; i < 4; ++i) {
             const uint32_t idx = threadIdx.x + 256 * i;          // float4 index: 32 rows x 32 quads
+            const uint32_t b = b0 + (idx >> 5), q = idx & 31;
+            v[i] = *reinterpret_cast<const float4*>(X + (uint64_t)(b < B ? b : B - 1) * ldx + r0 + 4 * q);
+        }
+#pragma unroll
+        for (uint32_t i = 0; i < 4; ++i) {
+            const uint32_t idx = threadIdx.x + 256 * i;
             const uint32_t b = idx >> 5, q = idx & 31;
-            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (b0 + b < B) v = *reinterpret_cast<const float4*>(X + (uint64_t)(b0 + b) * ldx + r0 + 4 * q);
-            tile[b][4 * q + 0] = v.x; tile[b][4 * q + 1] = v.y; tile[b][4 * q + 2] = v.z; tile[b][4 * q + 3] = v.w;
+            const bool ok = b0 + b < B;
+            tile[b][4 * q + 0] = ok ? v[i].x : 0.0f; tile[b][4 * q + 1] = ok ? v[i].y : 0.0f;
+            tile[b][4 * q + 2] = ok ? v[i].z : 0.0f; tile[b][4 * q + 3] = ok ? v[i].w : 0.0f;
         }
     } else {
+        float v[16];
+#pragma unroll
+        for (uint32_t i = 0; i < 16; ++i) {
+            const uint32_t idx = threadIdx.x + 256 * i;
+            const uint32_t b = b0 + (idx >> 7), r = r0 + (idx & 127);
+            v[i] = X[(uint64_t)(b < B ? b : B - 1) * ldx + (r < n ? r : n - 1)];
+        }
 #pragma unroll
         for (uint32_t i = 0; i < 16; ++i) {
             const uint32_t idx = threadIdx.x + 256 * i;
             const uint32_t b = idx >> 7, r = idx & 127;
-            tile[b][r] = (b0 + b < B && r0 + r < n) ? X[(uint64_t)(b0 + b) * ldx + r0 + r] : 0.0f;
+            tile[b][r] = (b0 + b < B && r0 + r < n) ? v[i] : 0.0f;
         }
     }
     __syncthreads();
