@@ -103,6 +103,29 @@ decode_kernel(DevBlob d, float* vals, int32_t* sym, int32_t* row_out, int32_t* c
 // Dense route, step 1: write the pointer of every non-zero into an index map (n rows of
 // `pitch` pointers, pre-filled with 0).  HAC: pointer = symbol (0.0 is symbol 0 when it
 // occurs); sHAC, whose alphabet has no 0.0: pointer = symbol + 1.  One lane per chunk.
+// Copy n4 16-byte pieces from global memory to LDS with all threads of the block, four loads per
+// thread in flight: the loads of a turn are issued from clamped indices before the first store
+// (the values pass through an empty asm statement, or the compiler pairs every load with its
+// guarded store again and waits in between).
+__device__ __forceinline__ void block_copy_u4(uint4* dst, const uint4* src, uint32_t n4)
+{
+    for (uint32_t base = 0; base < n4; base += 4 * blockDim.x) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t i = base + threadIdx.x + k * blockDim.x;
+            v[k] = src[i < n4 ? i : n4 - 1u];
+        }
+        asm volatile("" : "+v"(v[0].x), "+v"(v[0].y), "+v"(v[0].z), "+v"(v[0].w), "+v"(v[1].x), "+v"(v[1].y), "+v"(v[1].z), "+v"(v[1].w),
+                          "+v"(v[2].x), "+v"(v[2].y), "+v"(v[2].z), "+v"(v[2].w), "+v"(v[3].x), "+v"(v[3].y), "+v"(v[3].z), "+v"(v[3].w));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t i = base + threadIdx.x + k * blockDim.x;
+            if (i < n4) dst[i] = v[k];
+        }
+    }
+}
+
 template <typename IdxT>
 __global__ void __launch_bounds__(256)
 decode_to_index_kernel(DevBlob d, IdxT* idx, uint64_t pitch, uint32_t shac, uint32_t s_words, uint32_t r_words,
@@ -110,19 +133,25 @@ decode_to_index_kernel(DevBlob d, IdxT* idx, uint64_t pitch, uint32_t shac, uint
 {
     extern __shared__ uint32_t smem[];
     __shared__ uint32_t range[4];                       // the block's stream words [0], [1) and CSC positions [2], [3)
-    const Tables tb = load_tables(d, smem);
+    TableRegs tr = request_tables(d);
     uint32_t* sstage = smem + table_words_dev(d);       // s_words: the stream words of the block's chunks
     uint32_t* rstage = sstage + s_words;                // r_words: their ri fields (sHAC with fields)
     uint32_t* cstage = rstage + r_words;                // c_words: colchunk[0 .. m], or nothing when it is too long
     const uint32_t g0 = blockIdx.x * blockDim.x, g = g0 + threadIdx.x;
     const uint32_t glast = g0 + blockDim.x - 1 < d.n_chunks - 1 ? g0 + blockDim.x - 1 : d.n_chunks - 1;
     const bool live = g < d.n_chunks;
+    // this chunk's index entry, and for the block's last chunk the entry after it (the end of the
+    // block's stream range): requested with the tables
+    uint2 ent_raw = make_uint2(0u, 0u), ent_next = make_uint2(0u, 0u);
+    if (live) ent_raw = request_entry(d, g);
+    if (g == glast && glast + 1 < d.n_chunks) ent_next = request_entry(d, glast + 1);
+    request_table_values(d, tr);
     // which column owns a chunk: a binary search over colchunk, from a copy in LDS when it fits
-    // (a dozen dependent reads per lane, tens of cycles each instead of hundreds)
-    if (c_words) {
-        for (uint32_t i = threadIdx.x; i <= d.m; i += blockDim.x) cstage[i] = d.colchunk[i];
-        __syncthreads();
-    }
+    // (a dozen dependent reads per lane, tens of cycles each instead of hundreds); colchunk sits
+    // in a 256-byte aligned section with room behind its m + 1 words
+    if (c_words) block_copy_u4(reinterpret_cast<uint4*>(cstage), reinterpret_cast<const uint4*>(d.colchunk), (d.m + 4) >> 2);
+    const Tables tb = store_tables(d, smem, tr);
+    if (c_words) __syncthreads();
     auto owner = [&](uint32_t chunk) -> uint32_t {
         if (!c_words) return column_of_chunk(d, chunk);
         uint32_t lo = 0, hi = d.m;                       // invariant: colchunk[lo] <= chunk < colchunk[hi]
@@ -137,7 +166,7 @@ decode_to_index_kernel(DevBlob d, IdxT* idx, uint64_t pitch, uint32_t shac, uint
     if (live) {
         col = owner(g);
         uint32_t rel, row0;
-        load_entry(d, g, rel, row0);
+        entry_fields(d, ent_raw, rel, row0);
         st.bp = d.colbit[col] + rel;
         st.row = row0;
         st.wpos = d.colpos[col] + (g - d.colchunk[col]) * d.chunk;
@@ -151,7 +180,7 @@ decode_to_index_kernel(DevBlob d, IdxT* idx, uint64_t pitch, uint32_t shac, uint
         uint32_t endbit = d.colbit[d.m];
         if (glast + 1 < d.n_chunks) {
             uint32_t rel2, row2;
-            load_entry(d, glast + 1, rel2, row2);
+            entry_fields(d, ent_next, rel2, row2);
             endbit = d.colbit[owner(glast + 1)] + rel2;
         }
         range[1] = (endbit + 31) >> 5;
@@ -168,12 +197,8 @@ decode_to_index_kernel(DevBlob d, IdxT* idx, uint64_t pitch, uint32_t shac, uint
     const uint32_t rnw = fields ? (uint32_t)((rhi_bit + 31) >> 5) - rwlo + 4 : 0;
     const bool staged = nw <= s_words && rnw <= r_words && range[3] >= range[2];
     if (staged) {
-        const uint4* s4 = reinterpret_cast<const uint4*>(d.stream + wlo);
-        for (uint32_t i = threadIdx.x; i * 4 < nw; i += blockDim.x) reinterpret_cast<uint4*>(sstage)[i] = s4[i];
-        if (fields) {
-            const uint4* r4 = reinterpret_cast<const uint4*>(d.ri + rwlo);
-            for (uint32_t i = threadIdx.x; i * 4 < rnw; i += blockDim.x) reinterpret_cast<uint4*>(rstage)[i] = r4[i];
-        }
+        block_copy_u4(reinterpret_cast<uint4*>(sstage), reinterpret_cast<const uint4*>(d.stream + wlo), (nw + 3) >> 2);
+        if (fields) block_copy_u4(reinterpret_cast<uint4*>(rstage), reinterpret_cast<const uint4*>(d.ri + rwlo), (rnw + 3) >> 2);
     }
     __syncthreads();
     if (!live) return;
