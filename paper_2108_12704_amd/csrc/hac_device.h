@@ -193,6 +193,7 @@ __device__ __forceinline__ Tables store_tables(const DevBlob& d, uint32_t* smem,
     // The values pass through an empty asm statement first: their loads then stay where they were
     // issued (the compiler would otherwise move a load down beside the guarded store that uses it,
     // behind every load issued since).
+    static_assert(kTabTurns == 4, "the asm statement below names four values");
     asm volatile("" : "+v"(r.v[0]), "+v"(r.v[1]), "+v"(r.v[2]), "+v"(r.v[3]));
 #pragma unroll
     for (int k = 0; k < kTabTurns; ++k) {
