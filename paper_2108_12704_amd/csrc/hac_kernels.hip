@@ -1245,7 +1245,9 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         const size_t per_wave_s = 4ull * (sbuf_words + sum_words);
         const size_t tbl = 4ull * table_words(d);
         if (!wpb) {
-            for (wpb = 16; wpb > 1 && tbl + wpb * per_wave_s > kLdsLimit; wpb >>= 1) {}
+            // blocks of 4 waves: the barrier behind the tables then waits for 4 waves instead of 16
+            // (the largest layer here at B = 1: 15.7 -> 15.2 us, address map 11.8 -> 11.3 us)
+            for (wpb = 4; wpb > 1 && tbl + wpb * per_wave_s > kLdsLimit; wpb >>= 1) {}
             // a narrow matrix: smaller blocks, so that they reach more of the 256 CUs
             while (wpb > 4 && (nwaves + wpb - 1) / wpb < 256) wpb >>= 1;
         }
@@ -1287,6 +1289,10 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
             if (waves > best_waves) { best_waves = waves; wpb = w; }
         }
         if (!wpb) wpb = 1;
+        // a single pass has no barrier between passes to keep in step: two blocks of 8 waves per CU
+        // do slightly better than one of 16 (22.4 against 23.0 us at B = 32), the multi-pass kernel
+        // does worse with them (107.3 against 103.6 us at B = 256)
+        if (bs.npass == 1 && wpb == 16 && (uint32_t)(kLdsLimit / (tbl + 8 * per_wave)) * 8 >= best_waves) wpb = 8;
         // a narrow matrix: smaller blocks, so that they reach more of the 256 CUs (each CU gathers
         // through its own vector memory path; measured on a 4096 x 1000 layer at B = 64: 27 -> 17 us)
         while (wpb > 4 && (uint64_t)((nwaves + wpb - 1) / wpb) * bs.tiles < 256) wpb >>= 1;
