@@ -580,7 +580,7 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
     block_sync_lds();                                        // the tables; the staged words are still on their way
     if (!live) {
         // sync_passes: every wave of the block meets at a barrier once per pass (see accumulate)
-        if (MP && sync_passes) for (uint32_t p = 0; p < live_passes; ++p) __syncthreads();
+        if (MP && sync_passes) for (uint32_t p = 1; p < live_passes; ++p) __syncthreads();
         return;
     }
     HAC_MARK(1);
@@ -609,8 +609,9 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
         for (uint32_t p = 0; p < passes; ++p) {
             // Keeping the block's waves on the same pass keeps the panels of XT they gather from few
             // enough to stay in L2.  Only set when every wave calls this exactly once (one column per
-            // wave, no column split over windows).
-            if (MP && sync_passes) __syncthreads();
+            // wave, no column split over windows).  The first pass starts without waiting: a wave
+            // that has decoded its column early gathers while the others still decode.
+            if (MP && sync_passes && p > 0) __syncthreads();
             float a[NB];
 #pragma unroll
             for (int i = 0; i < NB; ++i) a[i] = (carried && part_words) ? part[(p * NB + i) * kWave + lane] : 0.0f;
