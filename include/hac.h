@@ -430,6 +430,22 @@ int shac_dot(const hac_desc_t *desc, const void *d_blob,
              void *d_ws, size_t ws_bytes,
              const hac_launch_t *launch, hac_stream_t stream);
 
+/* For callers that cannot allocate device memory or must not call an allocator (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): hac_dot / shac_dot
+ * (picked by desc->format) with the workspace taken from a fixed array of
+ * HAC_NOALLOC_WORKSPACE_BYTES inside the library's device image instead of from the caller.
+ * The call allocates and frees nothing, on the host or on the device.  A product whose
+ * workspace (hac_workspace_bytes_for(desc, B, launch)) exceeds the array returns
+ * HAC_EWORKSPACE and launches nothing.  Each GPU holds one such array until the process ends;
+ * every call on that GPU uses it, so calls that may overlap on one GPU (different streams or
+ * threads) race on it: order them.  Nothing is kept in the array between calls (each call
+ * writes what it reads).  Otherwise as hac_dot. */
+#define HAC_NOALLOC_WORKSPACE_BYTES (16u << 20)
+int hac_dot_noalloc(const hac_desc_t *desc, const void *d_blob,
+                    const float *d_X, int64_t B, int64_t ldx,
+                    float *d_Y, int64_t ldy,
+                    const hac_launch_t *launch, hac_stream_t stream);
+
 /* A chain of layers (not in the paper, which gives the product of one layer):
  *     A_0 = X,   A_{l+1} = act_l(A_l . W_l + bias_l),   Y = A_L
  * with W_l given compressed (HAC, sHAC or IM; layer blobs of their own or the

@@ -26,7 +26,7 @@ EXPORTS = (
     "shac_decode_dev", "hac_strerror", "hac_last_hip_error", "im_encode", "im_dot",
     "hac_encode_dev", "hac_encode_dev_workspace_bytes", "hac_choose_format",
     "hac_net_encode", "hac_net_describe", "hac_net_layer", "hac_net_validate", "hac_net_stats",
-    "hac_net_decode_host", "hac_forward", "hac_forward_workspace_bytes",
+    "hac_net_decode_host", "hac_forward", "hac_forward_workspace_bytes", "hac_dot_noalloc",
 )
 
 
@@ -152,6 +152,7 @@ def load_library() -> C.CDLL:
     lib.hac_dot.argtypes = dot_args
     lib.shac_dot.argtypes = dot_args
     lib.im_dot.argtypes = dot_args
+    lib.hac_dot_noalloc.argtypes = [C.POINTER(Desc), vp, vp, C.c_int64, C.c_int64, vp, C.c_int64, C.POINTER(Launch), vp]
     lib.hac_decode_dev.argtypes = [C.POINTER(Desc), vp, vp, vp, vp]
     lib.shac_decode_dev.argtypes = [C.POINTER(Desc), vp, vp, vp, vp, vp, vp]
     lib.hac_strerror.argtypes = [C.c_int]
@@ -427,6 +428,29 @@ def hac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=No
 def shac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=None):
     """Y = X . W for an sHAC blob on the device (asynchronous on the stream)."""
     return _dot("shac_dot", dblob, X, Y, workspace, launch, stream)
+
+
+NOALLOC_WORKSPACE_BYTES = 16 << 20
+
+
+def hac_dot_noalloc(dblob: DeviceBlob, X, Y, launch: Optional[Launch] = None, stream=None):
+    """hac_dot / shac_dot (by the blob's format) with the workspace inside the library: the call
+    allocates nothing, so X and Y must be given, contiguous along their rows."""
+    import torch
+    lib = load_library()
+    if X.dtype != torch.float32 or X.dim() != 2 or not X.is_cuda or X.stride(1) != 1:
+        raise TypeError("X must be a 2-D float32 CUDA tensor with unit column stride")
+    B, n = X.shape
+    if n != dblob.n:
+        raise ValueError("X has the wrong width")
+    if Y.dtype != torch.float32 or Y.shape != (B, dblob.m) or Y.stride(1) != 1 or not Y.is_cuda:
+        raise TypeError("Y must be a B x m float32 CUDA tensor with unit column stride")
+    ldx = X.stride(0) if B > 1 else max(n, 1)
+    ldy = Y.stride(0) if B > 1 else max(dblob.m, 1)
+    rc = lib.hac_dot_noalloc(C.byref(dblob.desc), dblob.tensor.data_ptr(), X.data_ptr(), B, ldx, Y.data_ptr(), ldy,
+                             C.byref(launch) if launch is not None else None, _stream_handle(stream))
+    _check(rc, "hac_dot_noalloc")
+    return Y
 
 
 def hac_encode_dev(W, fmt: int = HAC_FORMAT_HAC, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0,

@@ -22,6 +22,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <atomic>
 
 #include "../../include/hac.h"
 #include "hac_internal.h"
@@ -1492,6 +1493,52 @@ extern "C" int shac_dot(const hac_desc_t* desc, const void* d_blob, const float*
                         const hac_launch_t* launch, hac_stream_t stream)
 {
     return dot_impl(HAC_FORMAT_SHAC, desc, d_blob, d_X, B, ldx, d_Y, ldy, d_ws, ws_bytes, launch, stream);
+}
+
+// ---- a dot call for callers that cannot allocate ------------------------------------------
+// The workspace of hac_dot / shac_dot (the feature-major copy of X, or the dense route's index
+// map and partial sums) lives in this file-scope device array instead of caller memory.  Every
+// GPU holds its own copy of the array at its own address: host code asks the runtime for that
+// address once per device and passes it on like any other workspace pointer; the array's name
+// itself is never handed to a kernel.
+constexpr size_t kStaticWsBytes = HAC_NOALLOC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Address of `scratch` on the current device (looked up on the first call there, then kept).
+int static_workspace(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return HAC_EINVAL;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e != hipSuccess ? e : hipErrorInvalidSymbol);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // two threads racing here store the same address
+    }
+    *out = p;
+    return HAC_OK;
+}
+} // namespace
+
+extern "C" int hac_dot_noalloc(const hac_desc_t* desc, const void* d_blob, const float* d_X, int64_t B, int64_t ldx,
+                               float* d_Y, int64_t ldy, const hac_launch_t* launch, hac_stream_t stream)
+{
+    if (!desc_plausible(desc) || (desc->format != HAC_FORMAT_HAC && desc->format != HAC_FORMAT_SHAC)) return HAC_EINVAL;
+    if (B < 0 || B > 0x7fffffffll) return HAC_EINVAL;
+    const size_t need = hac_workspace_bytes_for(desc, B, launch);
+    if (need > kStaticWsBytes) return HAC_EWORKSPACE;
+    void* ws = nullptr;
+    if (need) {
+        const int rc = static_workspace(&ws);
+        if (rc) return rc;
+    }
+    return dot_impl(desc->format, desc, d_blob, d_X, B, ldx, d_Y, ldy, ws, need ? kStaticWsBytes : 0, launch, stream);
 }
 
 extern "C" int hac_decode_dev(const hac_desc_t* desc, const void* d_blob, float* d_W, int32_t* d_sym,
