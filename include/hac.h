@@ -89,9 +89,14 @@ typedef struct {
     uint32_t lut_bits;    /* width of the first-level decode table, 1..12 [min(Lmax,10)]  */
     uint32_t ri_coding;   /* sHAC: HAC_RI_FIELDS [default] or HAC_RI_RICE (ri_bits must
                              then be 0); hac_encode requires 0                             */
+    uint32_t chunk_rows;  /* rows of W per entry of the row index (see hac_desc_t), a multiple
+                             of 4 when below n; 0 = no row index [default];
+                             HAC_CHUNK_ROWS_AUTO = about 8 non-zeros per entry.  Not with
+                             HAC_RI_RICE                                                   */
 } hac_opts_t;
 
 enum { HAC_RI_FIELDS = 0, HAC_RI_RICE = 1 };
+#define HAC_CHUNK_ROWS_AUTO 0xffffffffu
 
 /* Blob header == descriptor.  All offsets are bytes from the start of the blob.
  *
@@ -103,7 +108,18 @@ enum { HAC_RI_FIELDS = 0, HAC_RI_RICE = 1 };
  * for HAC the row of the first symbol decoded there.  Chunk k of column j
  * holds the non-zeros col_pos[j] + k*chunk ... and, for HAC, starts right
  * after the codeword of the non-zero before them (at the column's first bit
- * for k = 0), so the zeros in front of its first non-zero belong to it. */
+ * for k = 0), so the zeros in front of its first non-zero belong to it.
+ *
+ * Row index (optional, hac_opts_t.chunk_rows): a second index that cuts every
+ * column at the same rows, so that a block of the large-batch kernel can own a
+ * range of rows of W for a group of columns and keep the matching rows of X in
+ * LDS.  With nq = ceil(n / chunk_rows), column j has nq + 1 entries, stored
+ * column after column; entry q < nq says where the column's rows >= q*chunk_rows
+ * begin: rel_bit, the stream bit relative to col_bit[j] of the first codeword
+ * decoded for them (HAC: the codeword of entry (q*chunk_rows, j) itself; sHAC:
+ * the codeword of the first non-zero in those rows), and rel_pos, the number of
+ * the column's non-zeros in rows < q*chunk_rows.  Entry nq holds the column's
+ * length in bits and its number of non-zeros. */
 typedef struct {
     uint32_t magic;        /* 'HAC1' = 0x31434148                                          */
     uint32_t version;      /* 2                                                            */
@@ -155,7 +171,15 @@ typedef struct {
     uint64_t gap_bits;     /* HAC_RI_RICE: part of total_bits spent on the gap codewords   */
     uint64_t idx_pitch;    /* IM: elements from one row of the index map to the next, a
                               multiple of 16; the columns past m hold 0                    */
-    uint64_t reserved[2];
+    uint64_t off_row_ent;  /* row index: m * (nq + 1) entries of rent_bits bits (+ >= 8 bytes
+                              of zeros): (rel_bit << rpos_bits) | rel_pos as one uint32, or
+                              the uint32 pair {rel_pos, rel_bit}; 0 without a row index      */
+    uint32_t chunk_rows;   /* rows per entry of the row index; 0 = the blob has none        */
+    uint8_t  rent_bits;    /* 32 or 64                                                      */
+    uint8_t  rpos_bits;    /* rent_bits = 32: low bits of an entry that hold rel_pos        */
+    uint16_t max_tile_nnz; /* most non-zeros in a tile of 16 columns x 4 entries of the row
+                              index (columns 16a .. 16a+15, rows 4b*chunk_rows ...), or
+                              65535 when that is more                                       */
 } hac_desc_t;
 
 /* An IM blob uses the header like this: format = HAC_FORMAT_IM; k_sym
@@ -180,6 +204,8 @@ typedef struct {
     double   entropy_bits;     /* source entropy H per symbol                              */
     double   avg_code_bits;    /* total_bits / symbols, H <= avg <= H + 1                  */
     double   psi;              /* blob_bytes / (4 n m): occupancy ratio of what is stored  */
+    uint64_t row_index_bytes;  /* the optional row index (0 without one); a dot call reads
+                                  either it or the chunk entries counted in index_bytes   */
 } hac_stats_t;
 
 /* Optional launch overrides for the dot calls (NULL = library defaults).  Any
@@ -201,6 +227,10 @@ typedef struct {
     uint32_t tile_width;      /* batch columns one block covers: 32 / 64 / 128 / 256, not
                                  below pass_width; every column of W is decoded once per
                                  such tile of the batch [256]                              */
+    uint32_t sessions_per_block; /* row-blocked kernel: groups of 4 row-index entries one block
+                                 works off before it writes its sums [so that there is
+                                 about one block per compute unit]; changes the order of
+                                 the additions                                             */
 } hac_launch_t;
 
 /* The workspace already holds the feature-major copy of this very X (same B,
@@ -219,6 +249,14 @@ typedef struct {
  * every block copies X into LDS.  This flag sends them the other way (re-layout
  * in the workspace first).  Same result up to summation order. */
 #define HAC_LAUNCH_NO_X_LDS 0x1000u
+
+/* Blobs with a row index (hac_opts_t.chunk_rows) and batches of more than 128 rows run the
+ * row-blocked kernel: a block owns 256 columns of W, up to 256 batch rows and a range of rows,
+ * keeps the matching rows of X in LDS and the sums of all its columns in registers; ranges are
+ * added by a second kernel in a fixed order, through the workspace.  The first flag sends any
+ * batch that way (given a row index), the second none.  Same result up to summation order. */
+#define HAC_LAUNCH_ROWS_KERNEL    0x2000u
+#define HAC_LAUNCH_NO_ROWS_KERNEL 0x4000u
 
 /* Force one of the two routes of hac_dot / shac_dot (not both). */
 #define HAC_LAUNCH_SPARSE_ROUTE 0x400u

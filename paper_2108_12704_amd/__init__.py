@@ -42,7 +42,7 @@ class HacError(RuntimeError):
 
 class Opts(C.Structure):
     _fields_ = [("chunk_nnz", C.c_uint32), ("ri_bits", C.c_uint32),
-                ("lut_bits", C.c_uint32), ("ri_coding", C.c_uint32)]
+                ("lut_bits", C.c_uint32), ("ri_coding", C.c_uint32), ("chunk_rows", C.c_uint32)]
 
 
 class Desc(C.Structure):
@@ -61,7 +61,9 @@ class Desc(C.Structure):
                 ("blob_bytes", C.c_uint64), ("max_col_bits", C.c_uint64), ("max_col_nnz", C.c_uint64),
                 ("row_bits", C.c_uint32), ("ri_coding", C.c_uint32),
                 ("rice_k", C.c_uint32), ("dict_shared", C.c_uint32),
-                ("gap_bits", C.c_uint64), ("idx_pitch", C.c_uint64), ("reserved", C.c_uint64 * 2)]
+                ("gap_bits", C.c_uint64), ("idx_pitch", C.c_uint64), ("off_row_ent", C.c_uint64),
+                ("chunk_rows", C.c_uint32), ("rent_bits", C.c_uint8), ("rpos_bits", C.c_uint8),
+                ("max_tile_nnz", C.c_uint16)]
 
 
 class Stats(C.Structure):
@@ -69,7 +71,8 @@ class Stats(C.Structure):
                 ("table_bytes", C.c_uint64), ("index_bytes", C.c_uint64),
                 ("ri_bytes", C.c_uint64), ("cb_bytes", C.c_uint64), ("blob_bytes", C.c_uint64),
                 ("paper_bits", C.c_uint64), ("bound_bits", C.c_double),
-                ("entropy_bits", C.c_double), ("avg_code_bits", C.c_double), ("psi", C.c_double)]
+                ("entropy_bits", C.c_double), ("avg_code_bits", C.c_double), ("psi", C.c_double),
+                ("row_index_bytes", C.c_uint64)]
 
 
 class Net(C.Structure):
@@ -99,7 +102,8 @@ ACT_NONE, ACT_RELU = 0, 1
 class Launch(C.Structure):
     _fields_ = [("cols_per_wave", C.c_uint32), ("waves_per_block", C.c_uint32),
                 ("variant", C.c_uint32), ("list_entries", C.c_uint32), ("staging_words", C.c_uint32),
-                ("pass_width", C.c_uint32), ("free_running", C.c_uint32), ("tile_width", C.c_uint32)]
+                ("pass_width", C.c_uint32), ("free_running", C.c_uint32), ("tile_width", C.c_uint32),
+                ("sessions_per_block", C.c_uint32)]
 
 
 assert C.sizeof(Desc) == 256
@@ -298,8 +302,11 @@ class NetBlob:
 RI_FIELDS, RI_RICE = 0, 1
 
 
+CHUNK_ROWS_AUTO = 0xFFFFFFFF
+
+
 def hac_net_encode(Ws, formats, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0,
-                   ri_coding: int = RI_FIELDS) -> NetBlob:
+                   ri_coding: int = RI_FIELDS, chunk_rows: int = 0) -> NetBlob:
     """Layers Ws[l] (n_l x m_l float32, host), formats[l] in (HAC_FORMAT_HAC, HAC_FORMAT_SHAC, HAC_FORMAT_IM)
     -> network blob."""
     lib = load_library()
@@ -317,7 +324,7 @@ def hac_net_encode(Ws, formats, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: 
     fm = (C.c_uint32 * L)(*[int(f) for f in formats])
     ns = (C.c_int64 * L)(*[W.shape[0] for W in keep])
     ms = (C.c_int64 * L)(*[W.shape[1] for W in keep])
-    opts = Opts(chunk_nnz, ri_bits, lut_bits, ri_coding)
+    opts = Opts(chunk_nnz, ri_bits, lut_bits, ri_coding, chunk_rows)
     out, size = C.c_void_p(), C.c_size_t()
     _check(lib.hac_net_encode(L, fm, ptrs, ns, ms, ms, C.byref(opts), C.byref(out), C.byref(size)), "hac_net_encode")
     try:
@@ -327,7 +334,7 @@ def hac_net_encode(Ws, formats, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: 
     return NetBlob(data)
 
 
-def _encode(fn_name: str, W: np.ndarray, chunk_nnz=0, ri_bits=0, lut_bits=0, ri_coding=0) -> Blob:
+def _encode(fn_name: str, W: np.ndarray, chunk_nnz=0, ri_bits=0, lut_bits=0, ri_coding=0, chunk_rows=0) -> Blob:
     lib = load_library()
     W = np.asarray(W)
     if W.dtype != np.float32 or W.ndim != 2:
@@ -335,7 +342,7 @@ def _encode(fn_name: str, W: np.ndarray, chunk_nnz=0, ri_bits=0, lut_bits=0, ri_
     if W.strides[1] != 4 or W.strides[0] % 4 or W.strides[0] < 4 * W.shape[1]:
         W = np.ascontiguousarray(W)
     ldw = W.strides[0] // 4
-    opts = Opts(chunk_nnz, ri_bits, lut_bits, ri_coding)
+    opts = Opts(chunk_nnz, ri_bits, lut_bits, ri_coding, chunk_rows)
     out = C.c_void_p()
     size = C.c_size_t()
     rc = getattr(lib, fn_name)(W.ctypes.data_as(C.POINTER(C.c_float)), W.shape[0], W.shape[1], ldw,
@@ -348,15 +355,16 @@ def _encode(fn_name: str, W: np.ndarray, chunk_nnz=0, ri_bits=0, lut_bits=0, ri_
     return Blob(data)
 
 
-def hac_encode(W: np.ndarray, chunk_nnz: int = 0, lut_bits: int = 0) -> Blob:
+def hac_encode(W: np.ndarray, chunk_nnz: int = 0, lut_bits: int = 0, chunk_rows: int = 0) -> Blob:
     """W (n x m float32, host) -> HAC blob."""
-    return _encode("hac_encode", W, chunk_nnz=chunk_nnz, lut_bits=lut_bits)
+    return _encode("hac_encode", W, chunk_nnz=chunk_nnz, lut_bits=lut_bits, chunk_rows=chunk_rows)
 
 
 def shac_encode(W: np.ndarray, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0,
-                ri_coding: int = RI_FIELDS) -> Blob:
+                ri_coding: int = RI_FIELDS, chunk_rows: int = 0) -> Blob:
     """W (n x m float32, host) -> sHAC blob."""
-    return _encode("shac_encode", W, chunk_nnz=chunk_nnz, ri_bits=ri_bits, lut_bits=lut_bits, ri_coding=ri_coding)
+    return _encode("shac_encode", W, chunk_nnz=chunk_nnz, ri_bits=ri_bits, lut_bits=lut_bits, ri_coding=ri_coding,
+                   chunk_rows=chunk_rows)
 
 
 def im_encode(W: np.ndarray) -> Blob:

@@ -390,6 +390,7 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
     if ((n + seg_rows - 1) / seg_rows > 65535) return HAC_ERANGE;       // one grid row per segment of rows
     int rc = check_opts(opts);
     if (rc) return rc;
+    if (opts && opts->chunk_rows) return HAC_EINVAL;                   // the row index is built by the host encoders only
     const bool shac = format == HAC_FORMAT_SHAC;
     const bool rice = opts && opts->ri_coding == HAC_RI_RICE;
     if (rice && (!shac || opts->ri_bits)) return HAC_EINVAL;          // as the host encoders

@@ -218,6 +218,23 @@ namespace hac_internal {
 
 uint32_t ceil_log2(uint64_t v) { uint32_t b = 0; while (((uint64_t)1 << b) < v) ++b; return b; }
 
+// entries of the row index: nq + 1 per column, nq = ceil(n / chunk_rows)
+uint64_t row_index_entries(const hac_desc_t& d)
+{
+    return d.chunk_rows ? d.m * ((d.n + d.chunk_rows - 1) / d.chunk_rows + 1) : 0;
+}
+
+// Rows per entry of the row index: 0 (none), the caller's value, or about 8 non-zeros per entry.
+uint32_t pick_chunk_rows(const hac_opts_t* opts, uint64_t n, uint64_t m, uint64_t nnz)
+{
+    if (!opts || !opts->chunk_rows) return 0;
+    if (opts->chunk_rows != HAC_CHUNK_ROWS_AUTO) return opts->chunk_rows;
+    const uint64_t per8 = nnz ? (8 * n * m + nnz - 1) / nnz : n;         // rows that hold 8 non-zeros of a column on average
+    uint64_t r = std::max<uint64_t>(per8, 16);
+    r = (r + 3) / 4 * 4;
+    return (uint32_t)std::min<uint64_t>(r, n);
+}
+
 // Section offsets and total size from the counts already in the header.  One order for all
 // formats: code tables, stream, per-column arrays, chunk entries, and ri when it is stored as fields.
 void place_tables(hac_desc_t& d, uint64_t& cursor, uint32_t k_values)
@@ -240,6 +257,7 @@ void place_layer(hac_desc_t& d, uint64_t& cursor)
     d.off_chunk_ent = place(d.n_chunks * (d.ent_bits / 8) + 8);
     if (d.format == HAC_FORMAT_SHAC && d.ri_coding == HAC_RI_FIELDS)
         d.off_ri = place(4 * ((d.nnz * d.ri_bits + 31) / 32) + kTailPad);
+    if (d.chunk_rows) d.off_row_ent = place(row_index_entries(d) * (d.rent_bits / 8) + 8);
 }
 
 void place_sections(hac_desc_t& d)
@@ -282,6 +300,7 @@ int check_opts(const hac_opts_t* opts)
 {
     if (!opts) return HAC_OK;
     if (opts->lut_bits > 12 || opts->chunk_nnz > 65536 || opts->ri_coding > HAC_RI_RICE) return HAC_EINVAL;
+    if (opts->chunk_rows && opts->ri_coding == HAC_RI_RICE) return HAC_EINVAL;
     return HAC_OK;
 }
 
@@ -375,6 +394,55 @@ void plan_common(const Scan& s, const Dict& D, uint32_t format, LayerPlan& P)
     d.k_sym = (uint32_t)D.codebook.size(); d.lmax = D.lmax; d.lut_bits = D.lut_bits;
 }
 
+// Row index: header fields (entry width, the fullest tile).  Needs n, m, nnz, max_col_bits and
+// max_col_nnz in the header.
+int plan_row_index(const Scan& s, const hac_opts_t* opts, hac_desc_t& d)
+{
+    const uint32_t cr = pick_chunk_rows(opts, d.n, d.m, d.nnz);
+    if (!cr) return HAC_OK;
+    if (d.ri_coding == HAC_RI_RICE) return HAC_EINVAL;
+    if (cr > d.n || (cr < d.n && cr % 4)) return HAC_EINVAL;
+    const uint64_t nq = (d.n + cr - 1) / cr;
+    if (d.m * (nq + 1) > 0x7ffffff0ull) return HAC_ERANGE;
+    d.chunk_rows = cr;
+    const uint32_t pos_bits = std::max<uint32_t>(ceil_log2(d.max_col_nnz + 1), 1);
+    const uint32_t bit_bits = std::max<uint32_t>(ceil_log2(d.max_col_bits + 1), 1);
+    d.rent_bits = pos_bits + bit_bits <= 32 ? 32 : 64;
+    d.rpos_bits = d.rent_bits == 32 ? (uint8_t)pos_bits : 0;
+    // the fullest tile of 16 columns x 4 entries
+    uint64_t worst = 0;
+    const uint64_t span = 4ull * cr;
+    std::vector<uint64_t> tile((size_t)((d.n + span - 1) / span));
+    for (uint64_t j0 = 0; j0 < d.m; j0 += 16) {
+        std::fill(tile.begin(), tile.end(), 0);
+        const uint64_t j1 = std::min<uint64_t>(j0 + 16, d.m);
+        for (uint64_t p = s.cb[(size_t)j0]; p < s.cb[(size_t)j1]; ++p) tile[(size_t)(s.ri[(size_t)p] / span)]++;
+        for (uint64_t t : tile) worst = std::max(worst, t);
+    }
+    d.max_tile_nnz = (uint16_t)std::min<uint64_t>(worst, 65535);
+    return HAC_OK;
+}
+
+// One column's entries of the row index.  rel_bit_of(q): stream bit, relative to the column's first,
+// at which the rows >= q * chunk_rows begin; rel_pos: non-zeros of the column above that row.
+template <class BitOf>
+void write_row_index_column(uint8_t* base, const hac_desc_t& d, const Scan& s, uint64_t j, uint64_t col_bits, BitOf rel_bit_of)
+{
+    const uint64_t nq = (d.n + d.chunk_rows - 1) / d.chunk_rows;
+    uint32_t* ent = reinterpret_cast<uint32_t*>(base + d.off_row_ent);
+    const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
+    uint64_t p = p0;
+    for (uint64_t q = 0; q <= nq; ++q) {
+        const uint64_t row = q * d.chunk_rows;
+        while (p < pend && s.ri[(size_t)p] < row) ++p;
+        const uint64_t rel_pos = q == nq ? pend - p0 : p - p0;
+        const uint64_t rel_bit = q == nq ? col_bits : rel_bit_of(q, p);
+        const uint64_t e = j * (nq + 1) + q;
+        if (d.rent_bits == 32) ent[e] = (uint32_t)((rel_bit << d.rpos_bits) | rel_pos);
+        else { ent[2 * e] = (uint32_t)rel_pos; ent[2 * e + 1] = (uint32_t)rel_bit; }
+    }
+}
+
 // HAC (Sect. IV-B): every entry of W, zeros included, gets a codeword.
 int plan_hac(const Scan& s, const Dict& D, const hac_opts_t* opts, LayerPlan& P)
 {
@@ -405,7 +473,7 @@ int plan_hac(const Scan& s, const Dict& D, const hac_opts_t* opts, LayerPlan& P)
     d.chunk = Cn; d.ri_bits = 0;
     d.ent_bits = ent_bits; d.row_bits = ent_bits == 32 ? row_bits : 0; d.n_chunks = P.ci.n_chunks;
     d.max_col_bits = max_col_bits; d.max_col_nnz = max_col_nnz;
-    return HAC_OK;
+    return plan_row_index(s, opts, d);
 }
 
 void write_column_arrays(uint8_t* base, const hac_desc_t& d, const ColumnIndex& ci)
@@ -430,11 +498,13 @@ int write_hac(uint8_t* base, const Scan& s, const Dict& D, LayerPlan& P)
         else for (uint64_t r = 0; r < count; ++r) bw.put(zcode, zlen);
     };
     uint64_t chunk = 0;
+    std::vector<uint64_t> nz_bit;                            // row index: where each non-zero's codeword starts
     for (int64_t j = 0; j < m; ++j) {
         uint64_t row = 0;                                    // next row to be written
         const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
         P.ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
         const uint64_t col_bit0 = bw.bitpos;
+        if (d.chunk_rows) nz_bit.assign((size_t)(pend - p0), 0);
         for (uint64_t p = p0; p < pend; ++p) {
             if ((p - p0) % Cn == 0) {                        // a chunk starts before this non-zero's zero run
                 const uint64_t rel = bw.bitpos - col_bit0;
@@ -443,11 +513,22 @@ int write_hac(uint8_t* base, const Scan& s, const Dict& D, LayerPlan& P)
                 ++chunk;
             }
             put_zeros(s.ri[(size_t)p] - row);
+            if (d.chunk_rows) nz_bit[(size_t)(p - p0)] = bw.bitpos - col_bit0;
             const uint32_t sy = P.map[s.sym[(size_t)p]];
             bw.put(D.t.code[sy], D.len[sy]);
             row = (uint64_t)s.ri[(size_t)p] + 1;
         }
         put_zeros((uint64_t)n - row);
+        if (d.chunk_rows) {
+            // the codeword of entry (q * chunk_rows, j): the zeros between it and the next non-zero below
+            // (or the column's end) lie in front of that non-zero's codeword (or of the column's end)
+            const uint64_t col_bits = bw.bitpos - col_bit0;
+            write_row_index_column(base, d, s, (uint64_t)j, col_bits, [&](uint64_t q, uint64_t p) {
+                const uint64_t r = q * d.chunk_rows;
+                if (p < pend) return nz_bit[(size_t)(p - p0)] - (s.ri[(size_t)p] - r) * zlen;
+                return col_bits - ((uint64_t)n - r) * zlen;
+            });
+        }
     }
     P.ci.col_bit[(size_t)m] = (uint32_t)bw.bitpos;
     write_column_arrays(base, d, P.ci);
@@ -519,7 +600,7 @@ int plan_shac(const Scan& s, const Dict& D, const hac_opts_t* opts, LayerPlan& P
         d.max_col_bits = max_col_bits;
     }
     d.total_bits = total_bits; d.n_words = (total_bits + 31) / 32;
-    return HAC_OK;
+    return plan_row_index(s, opts, d);
 }
 
 int write_shac(uint8_t* base, const Scan& s, const Dict& D, LayerPlan& P)
@@ -563,19 +644,28 @@ int write_shac(uint8_t* base, const Scan& s, const Dict& D, LayerPlan& P)
         BitWriter rw = { reinterpret_cast<uint32_t*>(base + d.off_ri), 0 };
         uint16_t* ent16 = reinterpret_cast<uint16_t*>(base + d.off_chunk_ent);
         uint32_t* ent32 = reinterpret_cast<uint32_t*>(base + d.off_chunk_ent);
+        std::vector<uint64_t> nz_bit;
         for (int64_t j = 0; j < m; ++j) {
             const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
             P.ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
             const uint64_t col_bit0 = bw.bitpos;
+            if (d.chunk_rows) nz_bit.assign((size_t)(pend - p0), 0);
             for (uint64_t p = p0; p < pend; ++p) {
                 if ((p - p0) % Cn == 0) {
                     const uint64_t rel = bw.bitpos - col_bit0;
                     if (ent_bits == 16) ent16[chunk] = (uint16_t)rel; else ent32[chunk] = (uint32_t)rel;
                     ++chunk;
                 }
+                if (d.chunk_rows) nz_bit[(size_t)(p - p0)] = bw.bitpos - col_bit0;
                 const uint32_t sy = P.map[s.sym[(size_t)p]];
                 bw.put(D.t.code[sy], D.len[sy]);
                 rw.put(s.ri[(size_t)p], d.ri_bits);
+            }
+            if (d.chunk_rows) {
+                const uint64_t col_bits = bw.bitpos - col_bit0;
+                write_row_index_column(base, d, s, (uint64_t)j, col_bits, [&](uint64_t, uint64_t p) {
+                    return p < pend ? nz_bit[(size_t)(p - p0)] : col_bits;
+                });
             }
         }
     }
@@ -902,7 +992,8 @@ int check_desc(const hac_desc_t& d, size_t bytes, bool in_net)
     if (d.format != HAC_FORMAT_HAC && d.format != HAC_FORMAT_SHAC && d.format != HAC_FORMAT_IM) return HAC_EFORMAT;
     if (d.blob_bytes > bytes || d.blob_bytes < sizeof(hac_desc_t)) return HAC_EFORMAT;
     if (d.n < 1 || d.m < 1 || d.n > 0x7fffffffull || d.m > 0x7fffffffull) return HAC_EFORMAT;
-    if (d.reserved[0] || d.reserved[1]) return HAC_EFORMAT;
+    if (!d.chunk_rows && (d.off_row_ent || d.rent_bits || d.rpos_bits || d.max_tile_nnz)) return HAC_EFORMAT;
+    if (d.chunk_rows && (d.format == HAC_FORMAT_IM || d.ri_coding == HAC_RI_RICE)) return HAC_EFORMAT;
     if (d.format == HAC_FORMAT_IM) {
         if (d.ent_bits != 8 && d.ent_bits != 16) return HAC_EFORMAT;
         if (d.k_sym < 1 || d.k_sym > (d.ent_bits == 8 ? 256u : 65536u) || d.has_zero > (in_net ? 0u : 1u)) return HAC_EFORMAT;
@@ -969,6 +1060,16 @@ int check_desc(const hac_desc_t& d, size_t bytes, bool in_net)
         if (!section_ok(d, d.off_ri, 4 * ((d.nnz * d.ri_bits + 31) / 32) + kTailPad, tot)) return HAC_EFORMAT;
     }
     if (!section_ok(d, d.off_chunk_ent, d.n_chunks * (d.ent_bits / 8) + 8, tot)) return HAC_EFORMAT;
+    if (d.chunk_rows) {
+        if (d.chunk_rows > d.n || (d.chunk_rows < d.n && d.chunk_rows % 4)) return HAC_EFORMAT;
+        if (d.rent_bits != 32 && d.rent_bits != 64) return HAC_EFORMAT;
+        const uint32_t pos_bits = std::max<uint32_t>(ceil_log2(d.max_col_nnz + 1), 1);
+        if (d.rent_bits == 32 ? (d.rpos_bits != pos_bits || pos_bits + std::max<uint32_t>(ceil_log2(d.max_col_bits + 1), 1) > 32)
+                              : d.rpos_bits != 0) return HAC_EFORMAT;
+        const uint64_t nq = (d.n + d.chunk_rows - 1) / d.chunk_rows;
+        if (d.m * (nq + 1) > 0x7ffffff0ull) return HAC_EFORMAT;
+        if (!section_ok(d, d.off_row_ent, row_index_entries(d) * (d.rent_bits / 8) + 8, tot)) return HAC_EFORMAT;
+    }
     return HAC_OK;
 }
 
@@ -987,6 +1088,13 @@ struct View {
     const uint32_t* lut; const uint32_t* stream;
     const uint32_t* colchunk; const uint32_t* colpos; const uint32_t* colbit;
     const uint8_t* ent; const uint32_t* ri;
+    const uint32_t* rent;              // row index, or nullptr
+
+    // entry e of the row index
+    void row_entry(uint64_t e, uint64_t& rel_bit, uint64_t& rel_pos) const {
+        if (d.rent_bits == 32) { rel_bit = rent[e] >> d.rpos_bits; rel_pos = rent[e] & ((1u << d.rpos_bits) - 1u); }
+        else { rel_pos = rent[2 * e]; rel_bit = rent[2 * e + 1]; }
+    }
 
     // (relative bit offset, first row) of chunk g
     void entry(uint64_t g, uint64_t& rel, uint64_t& row) const {
@@ -1017,6 +1125,7 @@ void make_view(const void* blob, const hac_desc_t& d, View& v)
     v.ent = v.base + d.off_chunk_ent;
     v.ri = (d.format == HAC_FORMAT_SHAC && d.ri_coding == HAC_RI_FIELDS)
                ? reinterpret_cast<const uint32_t*>(v.base + d.off_ri) : nullptr;
+    v.rent = d.chunk_rows ? reinterpret_cast<const uint32_t*>(v.base + d.off_row_ent) : nullptr;
 }
 
 // code tables must describe a complete canonical prefix code consistent with the lengths
@@ -1136,6 +1245,24 @@ int check_index_shallow(const View& v)
         }
     }
     if (max_nnz != d.max_col_nnz || max_bits != d.max_col_bits) return HAC_EFORMAT;
+    if (d.chunk_rows) {
+        // row index: every column starts at (0, 0), ends at (its bits, its non-zeros), never steps back,
+        // and no entry claims more non-zeros than rows passed
+        const uint64_t nq = (d.n + d.chunk_rows - 1) / d.chunk_rows;
+        for (uint64_t j = 0; j < d.m; ++j) {
+            const uint64_t bits = v.colbit[j + 1] - v.colbit[j], cnt = v.colpos[j + 1] - v.colpos[j];
+            uint64_t pb = 0, pp = 0;
+            for (uint64_t q = 0; q <= nq; ++q) {
+                uint64_t rb, rp;
+                v.row_entry(j * (nq + 1) + q, rb, rp);
+                if (q == 0 && (rb || rp)) return HAC_EFORMAT;
+                if (rb < pb || rp < pp || rb > bits || rp > cnt) return HAC_EFORMAT;
+                if (rp - pp > d.chunk_rows) return HAC_EFORMAT;
+                if (q == nq && (rb != bits || rp != cnt)) return HAC_EFORMAT;
+                pb = rb; pp = rp;
+            }
+        }
+    }
     return HAC_OK;
 }
 
@@ -1143,6 +1270,21 @@ int check_deep(const View& v)
 {
     const hac_desc_t& d = v.d;
     SeqDecoder dec(v);
+    // row index: every entry against the sequential decode, and the fullest tile of 16 columns x 4 entries
+    const uint64_t cr = d.chunk_rows, nq = cr ? (d.n + cr - 1) / cr : 0;
+    std::vector<uint64_t> tile(cr ? (size_t)((d.n + 4 * cr - 1) / (4 * cr)) : 0, 0);
+    uint64_t worst_tile = 0;
+    auto row_entry_is = [&](uint64_t j, uint64_t q, uint64_t bit, uint64_t pos) {
+        uint64_t rb, rp;
+        v.row_entry(j * (nq + 1) + q, rb, rp);
+        return rb == bit - v.colbit[j] && rp == pos - v.colpos[j];
+    };
+    auto tile_add = [&](uint64_t row) { if (cr) tile[(size_t)(row / (4 * cr))]++; };
+    auto tile_column_done = [&](uint64_t j) {
+        if (cr && ((j & 15) == 15 || j + 1 == d.m)) {
+            for (uint64_t& t : tile) { worst_tile = std::max(worst_tile, t); t = 0; }
+        }
+    };
     if (d.format == HAC_FORMAT_HAC) {
         uint64_t pos = 0;
         for (uint64_t j = 0; j < d.m; ++j) {
@@ -1150,11 +1292,11 @@ int check_deep(const View& v)
             uint64_t g = v.colchunk[j];
             uint64_t last_bit = dec.bitpos, last_row = 0;     // where the next chunk would start
             for (uint64_t i = 0; i < d.n; ++i) {
-                const uint64_t before = dec.bitpos;
-                (void)before;
+                if (cr && i % cr == 0 && !row_entry_is(j, i / cr, dec.bitpos, pos)) return HAC_EFORMAT;
                 const int64_t s = dec.next();
                 if (s < 0) return HAC_EFORMAT;
                 if (d.has_zero && s == 0) continue;
+                tile_add(i);
                 if ((pos - v.colpos[j]) % d.chunk == 0) {     // first non-zero of a chunk
                     uint64_t rel, row;
                     if (g >= v.colchunk[j + 1]) return HAC_EFORMAT;
@@ -1166,6 +1308,7 @@ int check_deep(const View& v)
                 last_bit = dec.bitpos; last_row = i + 1;
             }
             if (g != v.colchunk[j + 1]) return HAC_EFORMAT;
+            tile_column_done(j);
         }
         if (pos != d.nnz || dec.bitpos != d.total_bits) return HAC_EFORMAT;
     } else if (d.ri_coding == HAC_RI_RICE) {
@@ -1199,6 +1342,7 @@ int check_deep(const View& v)
             if (v.colbit[j] != dec.bitpos) return HAC_EFORMAT;
             uint64_t g = v.colchunk[j];
             int64_t prev = -1;
+            uint64_t q = 0;                                   // next entry of the row index to check
             for (uint64_t p = v.colpos[j]; p < v.colpos[j + 1]; ++p) {
                 if ((p - v.colpos[j]) % d.chunk == 0) {
                     uint64_t rel, row;
@@ -1206,14 +1350,21 @@ int check_deep(const View& v)
                     if (rel != dec.bitpos - v.colbit[j]) return HAC_EFORMAT;
                     ++g;
                 }
-                if (dec.next() < 0) return HAC_EFORMAT;
                 const uint32_t r = ri_field(v.ri, p, d.ri_bits);
                 if (r >= d.n || (int64_t)r <= prev) return HAC_EFORMAT;
+                for (; cr && q < nq && q * cr <= r; ++q)
+                    if (!row_entry_is(j, q, dec.bitpos, p)) return HAC_EFORMAT;
+                if (dec.next() < 0) return HAC_EFORMAT;
+                tile_add(r);
                 prev = r;
             }
+            for (; cr && q < nq; ++q)
+                if (!row_entry_is(j, q, dec.bitpos, v.colpos[j + 1])) return HAC_EFORMAT;
+            tile_column_done(j);
         }
         if (dec.bitpos != d.total_bits) return HAC_EFORMAT;
     }
+    if (cr && d.max_tile_nnz != std::min<uint64_t>(worst_tile, 65535)) return HAC_EFORMAT;
     return HAC_OK;
 }
 
@@ -1402,6 +1553,7 @@ extern "C" int hac_stats(const void* blob, size_t bytes, hac_stats_t* out)
     const double nm = (double)d.n * (double)d.m;
     const double k = (double)std::max<uint32_t>(d.k_sym, 1);
     const uint64_t ent_bytes = d.n_chunks * (d.ent_bits / 8);
+    out->row_index_bytes = row_index_entries(d) * (d.rent_bits / 8);
     if (d.format == HAC_FORMAT_HAC) {
         out->index_bytes = 3 * 4 * (d.m + 1) + ent_bytes;
         out->paper_bits = layer_paper_bits(d) + 6ull * 32 * d.k_sym;

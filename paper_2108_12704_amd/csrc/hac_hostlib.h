@@ -35,6 +35,8 @@ void canonical_codes(const std::vector<uint8_t>& len, CodeTables& t);
 void build_lut(const std::vector<uint8_t>& len, const CodeTables& t, uint32_t lut_bits, std::vector<uint32_t>& lut);
 
 uint32_t ceil_log2(uint64_t v);
+uint64_t row_index_entries(const hac_desc_t& d);     // m * (nq + 1), or 0 without a row index
+uint32_t pick_chunk_rows(const hac_opts_t* opts, uint64_t n, uint64_t m, uint64_t nnz);
 uint32_t pick_lut_bits(const hac_opts_t* opts, uint32_t lmax);
 uint32_t pick_chunk(const hac_opts_t* opts, uint64_t max_col_nnz);
 int check_opts(const hac_opts_t* opts);

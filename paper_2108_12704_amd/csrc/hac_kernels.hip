@@ -1015,6 +1015,18 @@ DenseRoute dense_route(const hac_desc_t* desc, int64_t B, const hac_launch_t* la
     return r;
 }
 
+} // namespace
+
+#include "hac_rows.h"
+
+namespace {
+
+size_t table_bytes_of(const hac_desc_t* desc)
+{
+    const uint32_t k4 = (desc->k_sym + 3u) & ~3u;
+    return 4ull * (((2u << desc->lut_bits) + 100u + (desc->k_sym <= kCodebookLdsMax ? 2u * k4 : 0u) + 3u) & ~3u);
+}
+
 typedef void (*batch_kern_t)(DevBlob, const float*, uint32_t, uint32_t, float*, uint64_t,
                              uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t, Epilogue);
 
@@ -1131,8 +1143,10 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         reuse_xt = (launch->variant & HAC_LAUNCH_REUSE_XT) != 0;
         list_kernel = (launch->variant & HAC_LAUNCH_LIST_KERNEL) != 0;
         const uint32_t routes = HAC_LAUNCH_SPARSE_ROUTE | HAC_LAUNCH_DENSE_ROUTE;
-        if (launch->variant & ~(HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_LIST_KERNEL | HAC_LAUNCH_NO_X_LDS | routes)) return HAC_EINVAL;
-        if ((launch->variant & routes) == routes) return HAC_EINVAL;
+        const uint32_t rowsk = HAC_LAUNCH_ROWS_KERNEL | HAC_LAUNCH_NO_ROWS_KERNEL;
+        if (launch->variant & ~(HAC_LAUNCH_REUSE_XT | HAC_LAUNCH_LIST_KERNEL | HAC_LAUNCH_NO_X_LDS | routes | rowsk)) return HAC_EINVAL;
+        if ((launch->variant & routes) == routes || (launch->variant & rowsk) == rowsk) return HAC_EINVAL;
+        if (launch->sessions_per_block > 65536) return HAC_EINVAL;
         list_cap = launch->list_entries;
         sbuf_words = launch->staging_words;
         if (list_cap && (list_cap < 64 || list_cap > 4096)) return HAC_EINVAL;
@@ -1185,6 +1199,32 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         if (e != hipSuccess) return hip_fail(e);
         launch_bias_act(d_Y, (uint32_t)B, d.m, (uint64_t)ldy, io->bias, io->relu, stream);
         e = hipGetLastError();
+        return e == hipSuccess ? HAC_OK : hip_fail(e);
+    }
+    const bool plain = !io->xt_in && !io->yt_out && !io->bias && !io->relu;
+    const RowsPlan rk = plain ? plan_rows(desc, B, launch, table_bytes_of(desc)) : RowsPlan{};
+    if (launch && (launch->variant & HAC_LAUNCH_ROWS_KERNEL) && !rk.use) return HAC_EINVAL;   // no row index, or it does not fit
+    if (rk.use) {
+        if (rk.part_bytes) {
+            if (!d_ws || ws_bytes < rk.part_bytes) return HAC_EWORKSPACE;
+            if (reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
+        }
+        RowsParams rp = rk.rp;
+        rp.rent = static_cast<const uint8_t*>(d_blob) + desc->off_row_ent;
+        rp.vecx = (reinterpret_cast<uintptr_t>(d_X) % 16 == 0 && ldx % 4 == 0) ? 1u : 0u;
+        auto k = shac ? dot_rows_kernel<true> : dot_rows_kernel<false>;
+        if (rk.lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)rk.lds);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        float* part = static_cast<float*>(d_ws);
+        hipLaunchKernelGGL(k, dim3(rk.grid), dim3(kRowsWaves * 64), rk.lds, stream, d, rp, d_X, (uint64_t)ldx, (uint32_t)B,
+                           part, d_Y, (uint64_t)ldy);
+        if (rp.nparts > 1)
+            hipLaunchKernelGGL(rows_reduce_kernel, dim3((d.m + 15) / 16, rp.tiles), dim3(256), 0, stream,
+                               part, rp.nparts, d.m, (uint32_t)B, d_Y, (uint64_t)ldy);
+        hipError_t e = hipGetLastError();
         return e == hipSuccess ? HAC_OK : hip_fail(e);
     }
     const XldsPlan xp = io->xt_in ? XldsPlan{ false, 0, 0, 0, 0 } : xlds_plan(desc, B, launch);
@@ -1332,6 +1372,8 @@ extern "C" size_t hac_workspace_bytes_for(const hac_desc_t* desc, int64_t B, con
         return hac_internal::plan_index_gemm((uint32_t)B, (uint32_t)desc->n, (uint32_t)desc->m).part_bytes;
     const DenseRoute dr = dense_route(desc, B, launch);
     if (dr.use) return dr.bytes;
+    const RowsPlan rk = plan_rows(desc, B, launch, table_bytes_of(desc));
+    if (rk.use) return rk.part_bytes;
     if (B == 1) return 0;                                    // a single row is its own feature-major copy
     if (xlds_plan(desc, B, launch).use) return 0;            // X is copied into LDS by every block
     const BatchShape bs = batch_shape(B, 32, kDefaultTile);

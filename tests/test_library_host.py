@@ -655,3 +655,104 @@ def test_random_damage_never_crashes_validation_or_decode():
             for l in range(len(got.layers)):
                 got.decode_host(l)
     assert accepted > 100                                              # damage in padding and in stream bits that still decode
+
+
+# ---- the optional row index (hac_opts_t.chunk_rows) -----------------------------------------
+
+def row_index_entries(blob):
+    """(rel_bit, rel_pos) arrays of shape (m, nq + 1) from a blob's row index."""
+    d = blob.desc
+    n, m, cr = int(d.n), int(d.m), int(d.chunk_rows)
+    nq = -(-n // cr)
+    if int(d.rent_bits) == 32:
+        raw = blob.section("off_row_ent", np.uint32, m * (nq + 1)).reshape(m, nq + 1)
+        pb = int(d.rpos_bits)
+        return (raw >> pb).astype(np.int64), (raw & ((1 << pb) - 1)).astype(np.int64)
+    raw = blob.section("off_row_ent", np.uint32, 2 * m * (nq + 1)).reshape(m, nq + 1, 2)
+    return raw[:, :, 1].astype(np.int64), raw[:, :, 0].astype(np.int64)
+
+
+def fullest_tile(W, cr):
+    n, m = W.shape
+    worst = 0
+    for j0 in range(0, m, 16):
+        for r0 in range(0, n, 4 * cr):
+            worst = max(worst, int(np.count_nonzero(W[r0:r0 + 4 * cr, j0:j0 + 16])))
+    return min(worst, 65535)
+
+
+@pytest.mark.parametrize("name,W", LAYERS, ids=IDS)
+@pytest.mark.parametrize("cr", [4, 12, "auto", "n"])
+def test_row_index_against_oracle(name, W, cr):
+    """Entry q of column j: the bits the oracle's symbols of rows < q*chunk_rows occupy under the blob's
+    code lengths, and how many of them are non-zero; the header's fullest tile by direct count."""
+    n, m = W.shape
+    want = hac.CHUNK_ROWS_AUTO if cr == "auto" else n if cr == "n" else cr
+    if isinstance(cr, int) and cr > n:
+        pytest.skip("chunk_rows above n is refused")
+    values, sym = formats.hac_symbols(W)
+    svalues, ssym, srow, scol = formats.shac_symbols(W)
+    for fmt in ("hac", "shac"):
+        blob = hac.hac_encode(W, chunk_rows=want) if fmt == "hac" else hac.shac_encode(W, chunk_rows=want)
+        assert blob.validate(deep=True) == 0
+        d = blob.desc
+        crr = int(d.chunk_rows)
+        assert 1 <= crr <= n and (crr == n or crr % 4 == 0)
+        if isinstance(cr, int):
+            assert crr == cr
+        nq = -(-n // crr)
+        rel_bit, rel_pos = row_index_entries(blob)
+        lens, _ = codes_from_blob(blob)
+        colbit = blob.section("off_col_bit", np.uint32, m + 1).astype(np.int64)
+        for j in range(m):
+            rows_nz = np.flatnonzero(W[:, j])
+            if fmt == "hac":
+                cum = np.concatenate(([0], np.cumsum(lens[sym[j * n:(j + 1) * n]])))
+            else:
+                cum_nz = np.concatenate(([0], np.cumsum(lens[ssym[scol == j]])))
+            for q in range(nq + 1):
+                r = min(q * crr, n)
+                above = int(np.searchsorted(rows_nz, r))
+                assert rel_pos[j, q] == above, (fmt, j, q)
+                assert rel_bit[j, q] == (cum[r] if fmt == "hac" else cum_nz[above]), (fmt, j, q)
+            assert rel_bit[j, nq] == colbit[j + 1] - colbit[j]
+        assert int(d.max_tile_nnz) == fullest_tile(W, crr)
+        assert blob.stats().row_index_bytes == m * (nq + 1) * int(d.rent_bits) // 8
+        # the blob without the option is the same blob minus that section
+        plain = hac.hac_encode(W) if fmt == "hac" else hac.shac_encode(W)
+        assert int(plain.desc.chunk_rows) == 0 and plain.stats().row_index_bytes == 0
+        assert np.array_equal(plain.decode_host()[1], blob.decode_host()[1])
+
+
+def test_row_index_options_and_damage():
+    W = workloads.scaled(2, 96, 40)
+    for bad in (3, 6, 97, 1000):                              # not a multiple of 4, or above n
+        with pytest.raises(hac.HacError) as err:
+            hac.hac_encode(W, chunk_rows=bad)
+        assert err.value.status == -1
+    with pytest.raises(hac.HacError) as err:                   # Rice-coded gaps carry no row index
+        hac.shac_encode(W, ri_coding=hac.RI_RICE, chunk_rows=8)
+    assert err.value.status == -1
+    for enc in (hac.hac_encode, hac.shac_encode):
+        blob = enc(W, chunk_rows=8)
+        off = int(blob.desc.off_row_ent)
+        for at in (off + 4, off + 4 * 13, off + 4 * (13 * 9)):
+            data = blob.data.copy()
+            data[at] ^= 0x10
+            rc = hac.load_library().hac_validate(data.ctypes.data, data.size, 1)
+            assert rc == -3, at
+        # the header's fullest tile is checked by the deep validation
+        data = blob.data.copy()
+        view = hac.Desc.from_buffer(data)
+        view.max_tile_nnz += 1
+        assert hac.load_library().hac_validate(data.ctypes.data, data.size, 0) == 0
+        assert hac.load_library().hac_validate(data.ctypes.data, data.size, 1) == -3
+
+
+def test_network_blob_layers_carry_the_row_index():
+    Ws, _ = workloads.network("tiny-fc")
+    nb = hac.hac_net_encode(Ws, (hac.HAC_FORMAT_HAC, hac.HAC_FORMAT_SHAC, hac.HAC_FORMAT_HAC), chunk_rows=hac.CHUNK_ROWS_AUTO)
+    assert nb.validate(deep=True) == 0
+    for l, d in enumerate(nb.layers):
+        assert int(d.chunk_rows) > 0 and int(d.off_row_ent) > 0
+        assert int(d.max_tile_nnz) == fullest_tile(Ws[l], int(d.chunk_rows))
