@@ -101,8 +101,8 @@ enum { HAC_RI_FIELDS = 0, HAC_RI_RICE = 1 };
 /* Blob header == descriptor.  All offsets are bytes from the start of the blob.
  *
  * The index added for the GPU (not part of the paper's formats; its conclusions
- * suggest "the vector of the offsets in the bitstring denoting the beginning of
- * each column"): per column its first stream bit, its first CSC position and
+ * propose per-column bit offsets so that columns can be decoded in parallel):
+ * per column its first stream bit, its first CSC position and
  * its first chunk; per chunk of `chunk` consecutive non-zeros of a column the
  * bit at which its decoding starts, relative to the column's first bit, and
  * for HAC the row of the first symbol decoded there.  Chunk k of column j

@@ -546,19 +546,31 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
         const uint32_t k_tot = k_sym + zero_first;
         const bool lut_lds = k_tot <= kLutLdsMax;
         const size_t lds = sizeof(float) * ((size_t)plan.steps_per_split * SB_NB + SB_GROUPS * SB_NB * SB_COLS + (lut_lds ? k_tot : 0));
+        if (lds > 160 * 1024) return hipErrorInvalidValue;           // (the plan keeps a range at kSmallMaxRows rows: 32 + 64 + 16 KB at most)
         const dim3 grid((uint32_t)blocks, (B + SB_NB - 1) / SB_NB);
-#define HAC_LAUNCH_SMALL(T, L)                                                                                       \
-        if (plan.rt == 6)                                                                                            \
-            hipLaunchKernelGGL((index_small_kernel<T, L, true>), grid, dim3(256), lds, stream, d_X, ldx, B,          \
-                               static_cast<const T*>(d_idx), pitch, d_codebook, k_sym, zero_first, n, m,             \
-                               plan.steps_per_split, (uint32_t)plan.tiles, plan.splits, plan.rt, d_Y, ldy, d_part);  \
-        else                                                                                                         \
-        hipLaunchKernelGGL((index_small_kernel<T, L, false>), grid, dim3(256), lds, stream, d_X, ldx, B,             \
-                           static_cast<const T*>(d_idx), pitch, d_codebook, k_sym, zero_first, n, m,                 \
-                           plan.steps_per_split, (uint32_t)plan.tiles, plan.splits, plan.rt, d_Y, ldy, d_part)
-        if (idx_bits == 8) { if (lut_lds) HAC_LAUNCH_SMALL(uint8_t, true); else HAC_LAUNCH_SMALL(uint8_t, false); }
-        else { if (lut_lds) HAC_LAUNCH_SMALL(uint16_t, true); else HAC_LAUNCH_SMALL(uint16_t, false); }
-#undef HAC_LAUNCH_SMALL
+        // (the rows of a range, the partial sums of the row groups and the table can exceed the 64 KB a
+        // kernel gets without asking)
+        hipError_t attr = hipSuccess;
+        auto launch_small = [&](auto kern, auto idxp) {
+            if (lds > 64 * 1024) {
+                attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (attr != hipSuccess) return;
+            }
+            hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, d_X, ldx, B,
+                               idxp, pitch, d_codebook, k_sym, zero_first, n, m,
+                               plan.steps_per_split, (uint32_t)plan.tiles, plan.splits, plan.rt, d_Y, ldy, d_part);
+        };
+        const bool narrow = plan.rt == 6;
+        const uint8_t* i8 = static_cast<const uint8_t*>(d_idx);
+        const uint16_t* i16 = static_cast<const uint16_t*>(d_idx);
+        if (idx_bits == 8) {
+            if (lut_lds) { if (narrow) launch_small(index_small_kernel<uint8_t, true, true>, i8); else launch_small(index_small_kernel<uint8_t, true, false>, i8); }
+            else { if (narrow) launch_small(index_small_kernel<uint8_t, false, true>, i8); else launch_small(index_small_kernel<uint8_t, false, false>, i8); }
+        } else {
+            if (lut_lds) { if (narrow) launch_small(index_small_kernel<uint16_t, true, true>, i16); else launch_small(index_small_kernel<uint16_t, true, false>, i16); }
+            else { if (narrow) launch_small(index_small_kernel<uint16_t, false, true>, i16); else launch_small(index_small_kernel<uint16_t, false, false>, i16); }
+        }
+        if (attr != hipSuccess) return attr;
         hipError_t e = hipGetLastError();
         if (e != hipSuccess || plan.splits == 1) return e;
         const uint64_t total = (uint64_t)B * m;

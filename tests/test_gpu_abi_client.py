@@ -20,8 +20,7 @@ def test_c_abi_client_without_python_or_torch(hac):
     """tests/native/abi_client.cpp: a C++ client of include/hac.h that allocates with hipMalloc and
     checks hac_dot, shac_dot and hac_forward against host loops; here only its entry point is called."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "native", "libabi_client.so")
-    if not os.path.exists(path):
-        pytest.skip("tests/native/libabi_client.so is not built (python __graft_entry__.py builds it)")
+    assert os.path.exists(path), "tests/native/libabi_client.so is not built (python __graft_entry__.py builds it)"
     torch.cuda.synchronize()
     client = C.CDLL(path)
     client.abi_client_run.argtypes = [C.c_char_p, C.c_size_t]

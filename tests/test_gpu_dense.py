@@ -76,6 +76,30 @@ def test_im_dot_parity(hac, name, W):
         check_y(Y, X, W, f"im {name} B={B}")
 
 
+def test_im_dot_small_batch_on_a_tall_map_with_a_long_value_list(hac):
+    """At most 32 rows of X against a tall index map: the blocks of the small-batch kernel then hold
+    close to a thousand rows of X, the partial sums of their row groups and the representatives in
+    LDS, more than a kernel gets without asking for it."""
+    W = workloads.make_layer(25088, 64, 0.02, 0.0, 256, "kmeans", 77)
+    blob = hac.im_encode(W)
+    assert int(blob.desc.k_sym) >= 200
+    db = blob.to_device(dev())
+    for B in (32, 9):
+        print(f"[case] im_dot tall map B={B}", flush=True)
+        X = workloads.make_batch(B, W.shape[0], 12 + B)
+        Y = hac.im_dot(db, torch.from_numpy(X).to(dev()))
+        torch.cuda.synchronize()
+        check_y(Y, X, W, f"tall map B={B}")
+    # the same shape as the dense route of a pruned layer forced at a small batch
+    Wp = workloads.make_layer(25088, 64, 0.02, 0.6, 256, "kmeans", 78)
+    dbp = hac.hac_encode(Wp).to_device(dev())
+    X = workloads.make_batch(32, Wp.shape[0], 5)
+    print("[case] dense route forced at B=32 on a tall layer", flush=True)
+    Y = hac.hac_dot(dbp, torch.from_numpy(X).to(dev()), launch=hac.Launch(variant=DENSE))
+    torch.cuda.synchronize()
+    check_y(Y, X, Wp, "dense route tall")
+
+
 def test_im_dot_strided_and_unaligned(hac):
     W = workloads.scaled(5, 301, 70)
     db = hac.im_encode(W).to_device(dev())
