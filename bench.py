@@ -72,7 +72,7 @@ def algorithmic_bytes(stats, desc, B):
 class Call:
     """One (format, B) product with its rotating device buffers."""
 
-    def __init__(self, hac, fmt, blob, B, rot, Xhost, dev, torch):
+    def __init__(self, hac, fmt, blob, B, rot, Xhost, dev, torch, launch=None):
         self.fmt, self.B = fmt, B
         self.fn = hac.hac_dot if fmt == "hac" else hac.shac_dot
         self.stats = blob.stats()
@@ -81,7 +81,7 @@ class Call:
         self.blobs = [blob.to_device(dev) for _ in range(rot)]
         self.X = [torch.from_numpy(Xhost[:B]).to(dev).clone() for _ in range(rot)]
         self.Y = [torch.empty((B, int(blob.desc.m)), dtype=torch.float32, device=dev) for _ in range(rot)]
-        need = hac.hac_workspace_bytes(blob.desc, B)
+        need = hac.hac_workspace_bytes(blob.desc, B, launch)
         self.ws = [torch.empty(max(need, 256), dtype=torch.uint8, device=dev) for _ in range(rot)]
         self.rot = rot
         # the dot kernel can be timed alone (X already feature-major in the workspace) only where a
@@ -91,6 +91,11 @@ class Call:
     def run(self, i, launch=None):
         j = i % self.rot
         self.fn(self.blobs[j], self.X[j], Y=self.Y[j], workspace=self.ws[j], launch=launch)
+
+    def kernels(self, hac, launch=None):
+        """Names of the kernels one call launches, as the library reports them after an eager call."""
+        self.run(0, launch)
+        return hac.hac_last_kernels()
 
 
 def time_region(torch, body, iters, warmup, use_graph, rot):
@@ -170,19 +175,6 @@ def measured_traffic(cfg_id, fmt, B):
     return None
 
 
-def kernel_name(fmt, B, dense=False, idx_bits=8, xlds=False):
-    """Name of the dot kernel a (format, B) call launches with default settings."""
-    shac = "true" if fmt == "shac" else "false"
-    if dense:
-        # (pointer type, table in LDS, row tiles per block, aligned X): the last three depend on the launch
-        return f"index_gemm_kernel<unsigned {'char' if idx_bits == 8 else 'short'}, ...>"
-    if xlds:                                      # 2 to 8 rows and a short X: the kernel that keeps X in LDS
-        return f"dot_small_kernel<{shac}, {2 if B <= 2 else 4 if B <= 4 else 8}, true>"
-    if B <= 4:
-        return f"dot_small_kernel<{shac}, {1 if B == 1 else 2 if B == 2 else 4}, false>"
-    return f"dot_batch_kernel<{shac}, 4, {'true' if B > 32 else 'false'}, false>"
-
-
 def extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, iters):
     """Figures that are context for the headline number, not part of it."""
     out = {}
@@ -210,6 +202,19 @@ def extras(torch, hac, calls, hb, sb, W, Xhost, dev, use_graph, iters):
     out["shac_rice_gaps"] = {"blob_bytes": gb.nbytes, "rice_k": int(gb.desc.rice_k),
                              "gap_bits_per_nonzero": round(int(gb.desc.gap_bits) / max(int(gb.desc.nnz), 1), 3),
                              "calls": rice}
+    # the row-blocked kernel (blobs with a row index; rows of X in LDS, column sums in registers): on
+    # request only, because it is slower on this layer; timed here so that the record stays current
+    rows_k = []
+    rows_launch = hac.Launch(variant=0x2000)
+    Bmax = max(c.B for c in calls)
+    for fmt, enc in (("hac", hac.hac_encode), ("shac", hac.shac_encode)):
+        rb_ = enc(W_, chunk_rows=hac.CHUNK_ROWS_AUTO)
+        c = Call(hac, fmt, rb_, Bmax, rot, Xhost, dev_, torch, launch=rows_launch)
+        ms = time_region(torch, lambda i, c=c: c.run(i, rows_launch), iters, 5, use_graph, rot)
+        rows_k.append({"format": fmt, "B": Bmax, "ms": round(ms, 5), "chunk_rows": int(rb_.desc.chunk_rows),
+                       "row_index_bytes": int(rb_.stats().row_index_bytes), "kernels": c.kernels(hac, rows_launch)})
+        del c
+    out["row_blocked_kernel"] = rows_k
     # decode-only kernels (test entry points): symbols and stream bits per second
     dec = []
     for fmt, blob in (("hac", hb), ("shac", sb)):
@@ -397,6 +402,40 @@ def cpu_baseline(W, Xs, cores):
     }
 
 
+def cpu_baseline_b(W, Xhost, batches, cores):
+    """The variant the paper's conclusions propose, in the oracle's plain C: per-column bit offsets
+    (found once, not timed: they belong to the stored form like the library's index), every codeword
+    decoded once per product and applied to all rows of X, threads over ranges of columns.  The whole
+    step (every batch size, both formats), fp64 accumulation."""
+    from oracle import cnative
+    n, m = W.shape
+    total_bytes, total_s, rows = 0, 0.0, []
+    for name, enc in (("hac", cnative.hac_encode), ("shac", cnative.shac_encode)):
+        st = enc(W)
+        t = time.perf_counter()
+        colbit = cnative.column_offsets(st)
+        t_off = time.perf_counter() - t
+        k = len(st.values)
+        for B in batches:
+            X = np.ascontiguousarray(Xhost[:B])
+            t = time.perf_counter()
+            cnative.coldot(st, X, q=cores, colbit=colbit)
+            dt = time.perf_counter() - t
+            by = 4 * len(st.words) + 12 * k + 8 * (m + 1) + 4 * B * n + 8 * B * m
+            if name == "shac":
+                by += 8 * st.q + 8 * (m + 1)
+            total_bytes += by
+            total_s += dt
+            rows.append({"format": name, "B": B, "ms": round(1e3 * dt, 2)})
+        rows.append({"format": name, "column_offsets_ms_one_core_not_timed": round(1e3 * t_off, 1)})
+    return {
+        "value": round(total_bytes / total_s / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "sample": "the whole step: decode once per product, all rows of X per non-zero, threads over column ranges "
+                  "from per-column bit offsets",
+        "step_ms": round(1e3 * total_s, 1), "products": rows,
+    }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -471,30 +510,38 @@ def main():
             "dense_equiv_gflops": round(2.0 * c.B * cfg.n * cfg.m / ms / 1e6, 1),
             "true_gflops": round(2.0 * c.B * int(c.desc.nnz) / ms / 1e6, 1),
         })
+    for c, d in zip(calls, detail):
+        d["kernels"] = c.kernels(hac)
+    torch.cuda.synchronize()
     dom = max(detail, key=lambda d: d["kernel_ms"])
     dom_desc = hb.desc if dom["format"] == "hac" else sb.desc
     dense = hac.hac_dot_route(dom_desc, dom["B"]) == 1
     traffic = measured_traffic(cfg.cfg, dom["format"], dom["B"])
+    traffic_source = (f"profiles/pmc_hbm_traffic_cfg{cfg.cfg}.md (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, each scaled by a "
+                      "copy of known size; a committed summary, not collected in this run)") if traffic is not None else None
+    # the dot kernel proper is the last launch of the call (a re-layout or decode pass may come first)
+    kname = [k for k in dom["kernels"] if "reduce" not in k][-1] if dom["kernels"] else "?"
     if dense:
-        # the dense route's dominant kernel is a contraction on the matrix cores: its flops are those of
-        # the dense product it computes; the decode kernels before it are part of kernel_ms
-        k_tot = int(dom_desc.k_sym) + (1 if dom["format"] == "shac" else 0)
-        kname = kernel_name(dom["format"], dom["B"], True, 8 if k_tot <= 256 else 16)
+        # the dense route's dominant kernel is a contraction on the matrix cores: beside the flops of the
+        # dense product it runs, the flops the method itself needs (2 B nnz) are reported: the method is
+        # not credited with multiplications by zero
         flops = 2.0 * dom["B"] * cfg.n * cfg.m
+        true_flops = 2.0 * dom["B"] * int(dom_desc.nnz)
         roofline = {
             "bound": "mfma", "kernel": f"{kname} ({dom['format']}_dot dense route, B={dom['B']})",
-            "achieved": round(flops / dom["kernel_ms"] / 1e9, 2), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(flops / dom["kernel_ms"] / 1e9 / MFMA_FP32_PEAK_TFLOPS, 4),
-            "traffic": traffic, "launch_ms": dom["kernel_ms"], "algorithmic_flops": flops,
+            "achieved": round(true_flops / dom["kernel_ms"] / 1e9, 2), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(true_flops / dom["kernel_ms"] / 1e9 / MFMA_FP32_PEAK_TFLOPS, 4),
+            "traffic": traffic, "traffic_source": traffic_source, "launch_ms": dom["kernel_ms"],
+            "algorithmic_flops": true_flops, "executed_flops": flops,
+            "executed_frac": round(flops / dom["kernel_ms"] / 1e9 / MFMA_FP32_PEAK_TFLOPS, 4),
         }
     else:
         xlds = 2 <= dom["B"] <= 8 and hac.hac_workspace_bytes(dom_desc, dom["B"]) == 0
-        kname = kernel_name(dom["format"], dom["B"], xlds=xlds)
         roofline = {
             "bound": "hbm", "kernel": f"{kname} ({dom['format']}_dot, B={dom['B']})",
             "achieved": round(dom["bytes"] / dom["kernel_ms"] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(dom["bytes"] / dom["kernel_ms"] / 1e6 / HBM_PEAK_GBS, 4),
-            "traffic": traffic,
+            "traffic": traffic, "traffic_source": traffic_source,
             "launch_ms": dom["kernel_ms"], "algorithmic_bytes": dom["bytes"],
         }
         # What binds this kernel in practice is not HBM but the vector memory path from the L2s: every
@@ -533,6 +580,7 @@ def main():
     if not args.no_cpu_baseline:
         cores = min(len(os.sched_getaffinity(0)), 16)
         out["cpu_baseline"] = cpu_baseline(W, Xhost, cores)
+        out["cpu_baseline_b"] = cpu_baseline_b(W, Xhost, batches, cores)
     print(json.dumps(out))
 
 

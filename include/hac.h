@@ -537,6 +537,12 @@ int shac_decode_dev(const hac_desc_t *desc, const void *d_blob,
                     float *d_nz, int32_t *d_sym, int32_t *d_row, int32_t *d_col,
                     hac_stream_t stream);
 
+/* The kernels launched by the calling thread's most recent successful hac_dot / shac_dot /
+ * im_dot / hac_dot_noalloc call, in launch order, separated by "; ", spelled as a profiler prints
+ * them without their namespace (e.g. "transpose_panel32_kernel; dot_batch_kernel<false, 4, true,
+ * false>").  For attributing profiler rows to calls; never NULL. */
+const char *hac_last_kernels(void);
+
 /* Text for a status code; never NULL. */
 const char *hac_strerror(int status);
 

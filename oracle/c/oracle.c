@@ -266,3 +266,143 @@ int oracle_pardot_shac(const uint32_t *C, int64_t N1, const int64_t *ri, const i
     p.values = values; p.X = X; p.ldx = ldx; p.n = n; p.m = m; p.out = out;
     return pardot(p, rows, q);
 }
+
+/* ---- decode once, all rows of X at a time, threads over ranges of columns ----
+ *
+ * The paper's conclusions propose to store the bit offset at which every
+ * column begins, so that columns can be handed to different threads.  This is
+ * that variant, written plainly: one sequential pass finds the offsets; then
+ * thread t takes a contiguous range of columns, walks each column's codewords
+ * from its offset (one tree step per bit, as above) and adds x[b][row] * value
+ * to the column's B sums for every non-zero it meets.  X is transposed first
+ * (xt[row][b]) so that the B products of one non-zero touch consecutive
+ * memory.  fp64 accumulation, rows in ascending order: the result is the
+ * dense product up to rounding, and does not depend on the thread count. */
+
+static int bit_at(const uint32_t *C, int64_t pos)
+{
+    return (int)((C[pos / 32] >> (31 - (int)(pos % 32))) & 1u);
+}
+
+/* symbol whose codeword starts at bit *pos; advances *pos past it */
+static int next_symbol(const uint32_t *C, int64_t *pos, const tree_t *t)
+{
+    int32_t node = t->root;
+    if (t->k == 1) { (*pos)++; return 0; }           /* one symbol: codeword "0" */
+    while (node >= t->k) {
+        node = bit_at(C, *pos) ? t->right[node - t->k] : t->left[node - t->k];
+        (*pos)++;
+    }
+    return node;
+}
+
+/* HAC: colbit[j] = first bit of column j (m + 1 entries, colbit[m] = stream length). */
+int oracle_hac_column_offsets(const uint32_t *C, int64_t nbits,
+                              const int32_t *left, const int32_t *right, int32_t k, int32_t root,
+                              int64_t n, int64_t m, int64_t *colbit)
+{
+    tree_t t = { left, right, k, root };
+    int64_t pos = 0;
+    for (int64_t j = 0; j < m; ++j) {
+        colbit[j] = pos;
+        for (int64_t i = 0; i < n; ++i) {
+            if (pos >= nbits) return -1;
+            (void)next_symbol(C, &pos, &t);
+        }
+    }
+    colbit[m] = pos;
+    return pos == nbits ? 0 : -1;
+}
+
+/* sHAC: colbit[j] = first bit of the codeword of nz[cb[j]]. */
+int oracle_shac_column_offsets(const uint32_t *C, int64_t nbits, const int64_t *cb,
+                               const int32_t *left, const int32_t *right, int32_t k, int32_t root,
+                               int64_t m, int64_t *colbit)
+{
+    tree_t t = { left, right, k, root };
+    int64_t pos = 0;
+    for (int64_t j = 0; j < m; ++j) {
+        colbit[j] = pos;
+        for (int64_t p = cb[j]; p < cb[j + 1]; ++p) {
+            if (pos >= nbits) return -1;
+            (void)next_symbol(C, &pos, &t);
+        }
+    }
+    colbit[m] = pos;
+    return pos == nbits ? 0 : -1;
+}
+
+typedef struct {
+    int shac;
+    const uint32_t *C; const int64_t *colbit;
+    const int64_t *ri, *cb;
+    tree_t tree;
+    const float *values;
+    const float *xt;          /* n x B */
+    int64_t B, n, m;
+    double *out;              /* B x m */
+    double *sums;             /* this thread's B sums */
+    int64_t c0, c1;
+} col_job;
+
+static void *col_worker(void *arg)
+{
+    col_job *j = (col_job *)arg;
+    for (int64_t col = j->c0; col < j->c1; ++col) {
+        int64_t pos = j->colbit[col];
+        for (int64_t b = 0; b < j->B; ++b) j->sums[b] = 0.0;
+        if (j->shac) {
+            for (int64_t p = j->cb[col]; p < j->cb[col + 1]; ++p) {
+                const double v = (double)j->values[next_symbol(j->C, &pos, &j->tree)];
+                const float *x = j->xt + j->ri[p] * j->B;
+                for (int64_t b = 0; b < j->B; ++b) j->sums[b] += (double)x[b] * v;
+            }
+        } else {
+            for (int64_t i = 0; i < j->n; ++i) {
+                const float w = j->values[next_symbol(j->C, &pos, &j->tree)];
+                if (w == 0.0f) continue;
+                const float *x = j->xt + i * j->B;
+                for (int64_t b = 0; b < j->B; ++b) j->sums[b] += (double)x[b] * (double)w;
+            }
+        }
+        for (int64_t b = 0; b < j->B; ++b) j->out[b * j->m + col] = j->sums[b];
+    }
+    return NULL;
+}
+
+/* out[B x m] = X[B x n] . W, W given as a HAC (ri = cb = NULL) or sHAC stream with its column offsets. */
+int oracle_coldot(const uint32_t *C, const int64_t *colbit, const int64_t *ri, const int64_t *cb,
+                  const int32_t *left, const int32_t *right, int32_t k, int32_t root,
+                  const float *values, const float *X, int64_t B, int64_t ldx,
+                  int64_t n, int64_t m, int32_t q, double *out)
+{
+    if (B <= 0 || m <= 0) return 0;
+    if (q < 1) q = 1;
+    if (q > m) q = (int32_t)m;
+    float *xt = (float *)malloc(sizeof(float) * (size_t)n * (size_t)B);
+    double *sums = (double *)malloc(sizeof(double) * (size_t)B * (size_t)q);
+    pthread_t *th = (pthread_t *)malloc(sizeof(pthread_t) * (size_t)q);
+    col_job *jobs = (col_job *)malloc(sizeof(col_job) * (size_t)q);
+    int rc = 0, started = 0;
+    if (!xt || !sums || !th || !jobs) { rc = -3; goto done; }
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t i = 0; i < n; ++i) xt[i * B + b] = X[b * ldx + i];
+    {
+        const int64_t chunk = (m + q - 1) / q;
+        for (int32_t t = 0; t < q; ++t) {
+            const int64_t c0 = (int64_t)t * chunk, c1 = c0 + chunk < m ? c0 + chunk : m;
+            if (c0 >= m) break;
+            col_job *j = &jobs[started];
+            j->shac = cb != NULL; j->C = C; j->colbit = colbit; j->ri = ri; j->cb = cb;
+            j->tree.left = left; j->tree.right = right; j->tree.k = k; j->tree.root = root;
+            j->values = values; j->xt = xt; j->B = B; j->n = n; j->m = m; j->out = out;
+            j->sums = sums + (size_t)started * (size_t)B; j->c0 = c0; j->c1 = c1;
+            if (pthread_create(&th[started], NULL, col_worker, j)) { rc = -3; break; }
+            started++;
+        }
+    }
+    for (int t = 0; t < started; ++t) pthread_join(th[t], NULL);
+done:
+    free(xt); free(sums); free(th); free(jobs);
+    return rc;
+}

@@ -3,7 +3,8 @@
 TEST INFRASTRUCTURE -- see oracle/__init__.py.  Used where Python loops are
 too slow (full-size layers, the benchmark's cpu_baseline leg).  The Huffman
 code always comes from oracle.huffman; the C side only packs, unpacks and
-runs Algorithms 1-3.
+runs Algorithms 1-3, plus the variant the paper's conclusions propose
+(per-column bit offsets, threads over columns: column_offsets, coldot).
 """
 from __future__ import annotations
 
@@ -146,4 +147,67 @@ def pardot(struct, X: np.ndarray, q: int = 1) -> np.ndarray:
                                       _p(ri, C.c_int64), _p(cb, C.c_int64), *common)
     if rc:
         raise RuntimeError(f"oracle pardot failed: {rc}")
+    return out
+
+
+def column_offsets(struct) -> np.ndarray:
+    """Bit offset at which every column's codewords begin (m + 1 entries; the last is the stream's
+    length): the per-column offsets the paper's conclusions propose, found by one sequential pass."""
+    code = struct.code
+    out = np.zeros(struct.m + 1, dtype=np.int64)
+    if code.k == 0:
+        return out
+    left, right = _tree(code)
+    words = np.ascontiguousarray(struct.words, dtype=np.uint32)
+    if words.size == 0:
+        words = np.zeros(1, dtype=np.uint32)
+    tree = (_p(left, C.c_int32), _p(right, C.c_int32), C.c_int32(code.k), C.c_int32(code.root))
+    if isinstance(struct, HAC):
+        rc = lib().oracle_hac_column_offsets(_p(words, C.c_uint32), C.c_int64(struct.nbits), *tree,
+                                             C.c_int64(struct.n), C.c_int64(struct.m), _p(out, C.c_int64))
+    else:
+        cb = np.ascontiguousarray(struct.cb, dtype=np.int64)
+        rc = lib().oracle_shac_column_offsets(_p(words, C.c_uint32), C.c_int64(struct.nbits), _p(cb, C.c_int64), *tree,
+                                              C.c_int64(struct.m), _p(out, C.c_int64))
+    if rc:
+        raise RuntimeError("column offsets: the stream does not hold the expected number of codewords")
+    return out
+
+
+def coldot(struct, X: np.ndarray, q: int = 1, colbit: Optional[np.ndarray] = None) -> np.ndarray:
+    """Y = X.W with every codeword decoded once and applied to all rows of X, q threads over ranges
+    of columns (each starts at its column's bit offset).  X is B x n fp32, the result B x m fp64."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    if X.ndim == 1:
+        X = X[None, :]
+    rows, n = X.shape
+    if n != struct.n:
+        raise ValueError("X has the wrong width")
+    out = np.zeros((rows, struct.m), dtype=np.float64)
+    code = struct.code
+    if rows == 0 or struct.m == 0 or code.k == 0:
+        return out
+    if colbit is None:
+        colbit = column_offsets(struct)
+    colbit = np.ascontiguousarray(colbit, dtype=np.int64)
+    left, right = _tree(code)
+    values = np.ascontiguousarray(struct.values, dtype=np.float32)
+    words = np.ascontiguousarray(struct.words, dtype=np.uint32)
+    if words.size == 0:
+        words = np.zeros(1, dtype=np.uint32)
+    if isinstance(struct, HAC):
+        ri_p, cb_p, keep = None, None, ()
+    else:
+        ri = np.ascontiguousarray(struct.ri, dtype=np.int64)
+        if ri.size == 0:
+            ri = np.zeros(1, dtype=np.int64)
+        cb = np.ascontiguousarray(struct.cb, dtype=np.int64)
+        ri_p, cb_p, keep = _p(ri, C.c_int64), _p(cb, C.c_int64), (ri, cb)
+    rc = lib().oracle_coldot(_p(words, C.c_uint32), _p(colbit, C.c_int64), ri_p, cb_p,
+                             _p(left, C.c_int32), _p(right, C.c_int32), C.c_int32(code.k), C.c_int32(code.root),
+                             _p(values, C.c_float), _p(X, C.c_float), C.c_int64(rows), C.c_int64(n),
+                             C.c_int64(struct.n), C.c_int64(struct.m), C.c_int32(q), _p(out, C.c_double))
+    del keep
+    if rc:
+        raise RuntimeError(f"oracle coldot failed: {rc}")
     return out

@@ -26,7 +26,7 @@ EXPORTS = (
     "shac_decode_dev", "hac_strerror", "hac_last_hip_error", "im_encode", "im_dot",
     "hac_encode_dev", "hac_encode_dev_workspace_bytes", "hac_choose_format",
     "hac_net_encode", "hac_net_describe", "hac_net_layer", "hac_net_validate", "hac_net_stats",
-    "hac_net_decode_host", "hac_forward", "hac_forward_workspace_bytes", "hac_dot_noalloc",
+    "hac_net_decode_host", "hac_forward", "hac_forward_workspace_bytes", "hac_dot_noalloc", "hac_last_kernels",
 )
 
 
@@ -162,6 +162,8 @@ def load_library() -> C.CDLL:
     lib.hac_strerror.argtypes = [C.c_int]
     lib.hac_strerror.restype = C.c_char_p
     lib.hac_last_hip_error.argtypes = []
+    lib.hac_last_kernels.argtypes = []
+    lib.hac_last_kernels.restype = C.c_char_p
     for name in EXPORTS:
         getattr(lib, name)
     _lib = lib
@@ -436,6 +438,12 @@ def hac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=No
 def shac_dot(dblob: DeviceBlob, X, Y=None, workspace=None, launch=None, stream=None):
     """Y = X . W for an sHAC blob on the device (asynchronous on the stream)."""
     return _dot("shac_dot", dblob, X, Y, workspace, launch, stream)
+
+
+def hac_last_kernels() -> list:
+    """Names of the kernels this thread's last dot call launched, in order."""
+    text = load_library().hac_last_kernels().decode()
+    return [t for t in text.split("; ") if t]
 
 
 NOALLOC_WORKSPACE_BYTES = 16 << 20

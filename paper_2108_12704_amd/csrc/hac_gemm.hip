@@ -513,6 +513,8 @@ void launch_one(dim3 grid, size_t lds, hipStream_t stream, hipError_t& err,
     }
     hipLaunchKernelGGL(k, grid, dim3(256), lds, stream, d_X, ldx, B, static_cast<const IdxT*>(d_idx), pitch, d_codebook,
                        k_sym, zero_first, n, m, d_Y, ldy, tiles_n, tiles, x_vec, splits, steps_per_split, d_part);
+    note_kernel("index_gemm_kernel<unsigned %s, %s, %d, %s>", sizeof(IdxT) == 1 ? "char" : "short", LUT_LDS ? "true" : "false", RT,
+                x_vec ? "true" : "false");
     err = hipGetLastError();
 }
 
@@ -559,6 +561,8 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
             hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, d_X, ldx, B,
                                idxp, pitch, d_codebook, k_sym, zero_first, n, m,
                                plan.steps_per_split, (uint32_t)plan.tiles, plan.splits, plan.rt, d_Y, ldy, d_part);
+            note_kernel("index_small_kernel<unsigned %s, %s, %s>", idx_bits == 8 ? "char" : "short", lut_lds ? "true" : "false",
+                        plan.rt == 6 ? "true" : "false");
         };
         const bool narrow = plan.rt == 6;
         const uint8_t* i8 = static_cast<const uint8_t*>(d_idx);
@@ -576,6 +580,7 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
         const uint64_t total = (uint64_t)B * m;
         const uint32_t rgrid = (uint32_t)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3(rgrid), dim3(256), 0, stream, d_part, plan.splits, B, m, d_Y, ldy);
+        note_kernel("splitk_reduce_kernel");
         return hipGetLastError();
     }
     const uint64_t items64 = plan.tiles * plan.splits;
@@ -604,6 +609,7 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
     const uint64_t total = (uint64_t)B * m;
     const uint32_t rgrid = (uint32_t)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3(rgrid), dim3(256), 0, stream, d_part, plan.splits, B, m, d_Y, ldy);
+    note_kernel("splitk_reduce_kernel");
     return hipGetLastError();
 }
 

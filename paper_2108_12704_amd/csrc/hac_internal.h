@@ -26,6 +26,11 @@ hipError_t launch_index_gemm(const float* d_X, uint64_t ldx, uint32_t B, const v
                              uint64_t pitch, const float* d_codebook, uint32_t k_sym, uint32_t zero_first,
                              uint32_t n, uint32_t m, float* d_Y, uint64_t ldy, float* d_part, hipStream_t stream);
 
+// The kernels the calling thread's most recent dot call launched, by the names a profiler shows
+// (see hac_last_kernels): note_reset() at the start of a call, note_kernel() at every launch.
+void note_reset();
+void note_kernel(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
+
 } // namespace hac_internal
 
 #endif

@@ -23,6 +23,8 @@
 
 #include <algorithm>
 #include <atomic>
+#include <cstdarg>
+#include <cstdio>
 
 #include "../../include/hac.h"
 #include "hac_internal.h"
@@ -1129,7 +1131,9 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     if (B < 0 || B > 0x7fffffffll) return HAC_EINVAL;
     if (B == 0) return HAC_OK;
     const ChainIO none = { nullptr, nullptr, nullptr, 0u };
-    if (!io) io = &none;
+    if (!io) { io = &none; hac_internal::note_reset(); }
+    using hac_internal::note_kernel;
+    const char* const tf[2] = { "false", "true" };
     if (!io->xt_in && (!d_X || ldx < (int64_t)desc->n)) return HAC_EINVAL;
     if (!io->yt_out && (!d_Y || ldy < (int64_t)desc->m)) return HAC_EINVAL;
     const Epilogue epi = { io->bias, io->yt_out, io->relu };
@@ -1171,6 +1175,8 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         // 1. all pointers 0, 2. the pointer of every non-zero, 3. tiles on the matrix cores
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, stream, static_cast<uint32_t*>(d_ws),
                            (uint64_t)(dr.idx_bytes / 4), 0u);
+        note_kernel("fill_u32_kernel");
+        note_kernel("decode_to_index_kernel<unsigned %s>", dr.idx_bits == 8 ? "char" : "short");
         // LDS beside the tables: room for the stream words (and ri fields) of a block's chunks
         const uint32_t s_words = 6144, r_words = (format == HAC_FORMAT_SHAC && !d.rice) ? 6144u : 0u;
         const uint32_t c_words = d.m + 1 <= 8192 ? round_up(d.m + 1, 4) : 0u;       // colchunk, for the owner search
@@ -1221,9 +1227,12 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         float* part = static_cast<float*>(d_ws);
         hipLaunchKernelGGL(k, dim3(rk.grid), dim3(kRowsWaves * 64), rk.lds, stream, d, rp, d_X, (uint64_t)ldx, (uint32_t)B,
                            part, d_Y, (uint64_t)ldy);
-        if (rp.nparts > 1)
+        note_kernel("dot_rows_kernel<%s>", tf[shac]);
+        if (rp.nparts > 1) {
             hipLaunchKernelGGL(rows_reduce_kernel, dim3((d.m + 15) / 16, rp.tiles), dim3(256), 0, stream,
                                part, rp.nparts, d.m, (uint32_t)B, d_Y, (uint64_t)ldy);
+            note_kernel("rows_reduce_kernel");
+        }
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? HAC_OK : hip_fail(e);
     }
@@ -1247,6 +1256,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         }
         hipLaunchKernelGGL(k, dim3(grid), dim3(xp.wpb * kWave), xp.lds, stream,
                            d, d_X, (uint32_t)B, (uint64_t)ldx, xp.x_words, d_Y, (uint64_t)ldy, cpw, sbuf_words, sum_words, nblocks, epi);
+        note_kernel("dot_small_kernel<%s, %u, true>", tf[shac], xp.nb);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? HAC_OK : hip_fail(e);
     }
@@ -1264,10 +1274,12 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
                 const uint32_t vec = (reinterpret_cast<uintptr_t>(d_X) % 16 == 0 && ldx % 4 == 0) ? 1u : 0u;
                 hipLaunchKernelGGL(transpose_panel32_kernel, grid, dim3(256), 0, stream,
                                    d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt, vec);
+                note_kernel("transpose_panel32_kernel");
             } else {
                 dim3 grid((d.n + 31) / 32, (bs.Bp + 31) / 32);
                 hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, stream,
                                    d_X, (uint32_t)B, d.n, (uint64_t)ldx, xt, bs.Bp, bs.gw * bs.nb);
+                note_kernel("transpose_pad_kernel");
             }
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return hip_fail(e);
@@ -1310,6 +1322,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
         }
         hipLaunchKernelGGL(k, dim3(grid), dim3(wpb * kWave), lds, stream,
                            d, XT, (uint32_t)B, (uint64_t)0, 0u, d_Y, (uint64_t)ldy, cpw, sbuf_words, sum_words, nblocks, epi);
+        note_kernel("dot_small_kernel<%s, %u, false>", tf[shac], bs.nb);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? HAC_OK : hip_fail(e);
     }
@@ -1359,6 +1372,7 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     hipLaunchKernelGGL(k, dim3(grid), dim3(wpb * kWave), lds, stream,
                        d, XT, bs.Bp, (uint32_t)B, d_Y, (uint64_t)ldy, cpw, bs.gw, bs.npass, list_cap, sbuf_words, part_words, nblocks,
                        sync_passes, epi);
+    note_kernel("dot_batch_kernel<%s, %u, %s, %s>", tf[shac], bs.nb, tf[bs.nb == 4 && bs.npass > 1], tf[with_epilogue]);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? HAC_OK : hip_fail(e);
 }
@@ -1402,6 +1416,7 @@ int im_dot_impl(const hac_desc_t* desc, const void* d_blob, const float* d_X, in
     if (B == 0) return HAC_OK;
     if (!d_X || !d_Y || ldx < (int64_t)desc->n || ldy < (int64_t)desc->m) return HAC_EINVAL;
     g_last_hip_error = 0;
+    if (!bias && !relu) hac_internal::note_reset();
     const size_t need = hac_internal::plan_index_gemm((uint32_t)B, (uint32_t)desc->n, (uint32_t)desc->m).part_bytes;
     if (need && (!d_ws || ws_bytes < need)) return HAC_EWORKSPACE;
     if (need && reinterpret_cast<uintptr_t>(d_ws) % 256) return HAC_EINVAL;
@@ -1619,6 +1634,23 @@ extern "C" int shac_decode_dev(const hac_desc_t* desc, const void* d_blob, float
 }
 
 extern "C" int hac_last_hip_error(void) { return g_last_hip_error; }
+
+namespace { thread_local char g_kernels[512]; thread_local size_t g_kernels_len = 0; }
+
+void hac_internal::note_reset() { g_kernels[0] = 0; g_kernels_len = 0; }
+
+void hac_internal::note_kernel(const char* fmt, ...)
+{
+    if (g_kernels_len + 4 >= sizeof g_kernels) return;
+    if (g_kernels_len) { memcpy(g_kernels + g_kernels_len, "; ", 3); g_kernels_len += 2; }
+    va_list ap;
+    va_start(ap, fmt);
+    const int w = vsnprintf(g_kernels + g_kernels_len, sizeof g_kernels - g_kernels_len, fmt, ap);
+    va_end(ap);
+    if (w > 0) g_kernels_len = std::min(sizeof g_kernels - 1, g_kernels_len + (size_t)w);
+}
+
+extern "C" const char* hac_last_kernels(void) { return g_kernels; }
 
 void hac_internal::set_last_hip_error(int e) { g_last_hip_error = e; }
 

@@ -116,3 +116,52 @@ def test_ncw_null_when_codeword_straddles_words():
     assert z is None and rem == "11" and oset == 32
     oset, rem, z = dot.ncw("0" + "1" * 31, rem, 0, Hinv)
     assert z == 2 and rem == "" and oset == 1
+
+
+# ---- decode once, threads over columns (the per-column offsets of the paper's conclusions) ----
+
+def test_column_offsets_are_the_cumulated_code_lengths():
+    W = workloads.scaled(1, 70, 23)
+    n, m = W.shape
+    h = cnative.hac_encode(W)
+    lens = np.array([l for _, l in h.code.codes], dtype=np.int64)
+    values, sym = formats.hac_symbols(W)
+    per_col = lens[sym].reshape(m, n).sum(axis=1)
+    assert cnative.column_offsets(h).tolist() == np.concatenate(([0], np.cumsum(per_col))).tolist()
+    s = cnative.shac_encode(W)
+    slens = np.array([l for _, l in s.code.codes], dtype=np.int64)
+    svalues, ssym, srow, scol = formats.shac_symbols(W)
+    per_col = np.bincount(scol, weights=slens[ssym], minlength=m).astype(np.int64)
+    assert cnative.column_offsets(s).tolist() == np.concatenate(([0], np.cumsum(per_col))).tolist()
+    assert cnative.column_offsets(h)[-1] == h.nbits and cnative.column_offsets(s)[-1] == s.nbits
+
+
+@pytest.mark.parametrize("name", sorted(workloads.edge_cases()) + ["cfg1-slice", "cfg5-slice"])
+def test_column_parallel_dot_is_the_dense_product(name):
+    if name == "cfg1-slice":
+        W = workloads.scaled(1, 120, 37)
+    elif name == "cfg5-slice":
+        W = workloads.scaled(5, 90, 21)
+    else:
+        W = workloads.edge_cases()[name]
+    X = workloads.make_batch(5, W.shape[0], 31)
+    X[2] = -X[2]                                              # signs on both sides
+    ref = dot.dense_dot(X, W)
+    for enc in (cnative.hac_encode, cnative.shac_encode):
+        st = enc(W)
+        one = cnative.coldot(st, X, q=1)
+        np.testing.assert_allclose(one, ref, rtol=0, atol=1e-12 * max(1.0, float(np.abs(ref).max())))
+        for q in (2, 3, 64):                                  # the split over threads changes nothing, bit for bit
+            assert np.array_equal(cnative.coldot(st, X, q=q), one)
+        # and it is Algorithm 3's result (same products, same order within a column)
+        np.testing.assert_allclose(one, cnative.pardot(st, X, q=2), rtol=0, atol=1e-12 * max(1.0, float(np.abs(ref).max())))
+
+
+def test_column_parallel_dot_identity_and_shape():
+    W = workloads.edge_cases()["empty_columns"]
+    eye = np.eye(W.shape[0], dtype=np.float32)
+    for enc in (cnative.hac_encode, cnative.shac_encode):
+        assert np.array_equal(cnative.coldot(enc(W), eye, q=3), W.astype(np.float64))
+    W = workloads.scaled(2, 33, 7)                             # n != m: a transposed operand cannot pass
+    X = workloads.make_batch(4, 33, 2)
+    assert cnative.coldot(cnative.hac_encode(W), X, q=2).shape == (4, 7)
