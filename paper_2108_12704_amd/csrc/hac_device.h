@@ -85,6 +85,20 @@ struct WordSrc {
         const uint32_t top = off ? __builtin_amdgcn_alignbit(w0, w1, 32 - off) : w0;
         return top >> (32 - bits);
     }
+    // The staged copy only.  Bits [rel, rel + 32) with rel counted from the copy's first word and
+    // handed over as rel - 1: the pair of words is then taken one word early when rel is a multiple
+    // of 32, the funnel shift (which takes its amount modulo 32) by -rel = ~(rel - 1) is right in
+    // every case, and nothing is selected.  At rel == 0 the word in front of the copy is read and
+    // not used: every kernel keeps its tables (or other staged words) there.
+    __device__ __forceinline__ uint32_t peek32_rm1(int32_t rm1) const {
+        static_assert(LDS, "positions relative to the staged copy");
+        lds_cu32* sw = (lds_cu32*)w;
+        const int32_t q = rm1 >> 5;
+        return __builtin_amdgcn_alignbit(sw[q], sw[q + 1], ~(uint32_t)rm1);
+    }
+    __device__ __forceinline__ uint32_t field_rel(uint32_t rel, uint32_t bits) const {
+        return peek32_rm1((int32_t)rel - 1) >> (32 - bits);
+    }
 };
 
 // Decode tables of one block in LDS.  Layout (uint32 words):
@@ -274,32 +288,48 @@ __device__ __forceinline__ void hac_advance(const DevBlob& d, const Tables& tb, 
 // 64 skips the zero run, and the codeword is taken from the same fetch.  Only a run
 // of 64 or more zeros takes an extra pass (which steps over 96 bits when they are all zero:
 // the lanes of a wave walk independently, and the wave runs as long as its slowest lane).
+// The position is kept relative to the staged copy, less one (see WordSrc::peek32_rm1): three
+// funnel shifts give the 96 bits, no 64-bit shift and no select on the bit offset.
+__device__ __forceinline__ uint32_t leading_zeros_raw(uint32_t x)        // 0xffffffff for x == 0, as the instruction counts
+{
+    uint32_t r;
+    asm("v_ffbh_u32 %0, %1" : "=v"(r) : "v"(x));
+    return r;
+}
+
 template <class Emit>
 __device__ __forceinline__ void hac_advance_zrun(const DevBlob& d, const Tables& tb, const WordSrc<true>& src,
                                                  ChunkState& st, uint32_t limit, Emit emit)
 {
     lds_cu32* sw = (lds_cu32*)src.w;
+    int32_t rm1 = (int32_t)(st.bp - (src.wbase << 5)) - 1;
     while (st.wpos < limit) {
-        const uint32_t wi = (st.bp >> 5) - src.wbase, off = st.bp & 31;
-        const uint32_t w0 = sw[wi], w1 = sw[wi + 1], w2 = sw[wi + 2], w3 = sw[wi + 3];
-        const uint32_t hi = (uint32_t)(((((uint64_t)w0 << 32) | w1) << off) >> 32);
-        const uint32_t mid = (uint32_t)(((((uint64_t)w1 << 32) | w2) << off) >> 32);
-        const uint32_t lo = (uint32_t)(((((uint64_t)w2 << 32) | w3) << off) >> 32);
+        const int32_t q = rm1 >> 5;
+        const uint32_t s = ~(uint32_t)rm1;
+        const uint32_t w0 = sw[q], w1 = sw[q + 1], w2 = sw[q + 2], w3 = sw[q + 3];
+        const uint32_t hi = __builtin_amdgcn_alignbit(w0, w1, s);
+        const uint32_t mid = __builtin_amdgcn_alignbit(w1, w2, s);
+        const uint32_t lo = __builtin_amdgcn_alignbit(w2, w3, s);
         if ((hi | mid) == 0) {                                             // a non-zero follows, so the run ends
             const uint32_t skip = lo ? 64u : 96u;                          // all 96 fetched bits may be zeros
-            st.bp += skip; st.row += skip;
+            rm1 += (int32_t)skip; st.row += skip;
             st.wpos = st.row > d.n ? limit : st.wpos;                      // ... unless the stream is damaged: end the walk
             continue;
         }
-        const uint32_t z = hi ? (uint32_t)__builtin_clz(hi) : 32u + (uint32_t)__builtin_clz(mid);
-        const uint32_t x0 = z < 32 ? hi : mid, x1 = z < 32 ? mid : lo;
-        const uint32_t top = (uint32_t)(((((uint64_t)x0 << 32) | x1) << (z & 31)) >> 32);
-        const Decoded q = decode_symbol(d, tb, top);
+        // hi == 0 counts as 0xffffffff and loses against 32 + (zeros of mid); mid == 0 with hi != 0 wraps to
+        // 31, which is never below the zeros of hi
+        const uint32_t zh = leading_zeros_raw(hi), zm = leading_zeros_raw(mid) + 32u;
+        const uint32_t z = zh < zm ? zh : zm;
+        const uint32_t x0 = z < 32u ? hi : mid, x1 = z < 32u ? mid : lo;
+        const uint32_t zz = z & 31u;
+        const uint32_t top = (x0 << zz) | ((x1 >> 1) >> (zz ^ 31u));
+        const Decoded sy = decode_symbol(d, tb, top);
         st.row += z;
-        st.bp += z + q.len;
-        emit(st.wpos, st.row, q.sym, q.val);
+        rm1 += (int32_t)(z + sy.len);
+        emit(st.wpos, st.row, sy.sym, sy.val);
         st.row++; st.wpos++;
     }
+    st.bp = (uint32_t)(rm1 + 1) + (src.wbase << 5);
 }
 
 // sHAC: every symbol is a non-zero.
@@ -313,6 +343,21 @@ __device__ __forceinline__ void shac_advance(const DevBlob& d, const Tables& tb,
         emit(st.wpos, 0u, q.sym, q.val);
         st.wpos++;
     }
+}
+
+// The same over the staged copy: one funnel shift per codeword.
+template <class Emit>
+__device__ __forceinline__ void shac_advance(const DevBlob& d, const Tables& tb, const WordSrc<true>& src,
+                                             ChunkState& st, uint32_t limit, Emit emit)
+{
+    int32_t rm1 = (int32_t)(st.bp - (src.wbase << 5)) - 1;
+    while (st.wpos < limit) {
+        const Decoded sy = decode_symbol(d, tb, src.peek32_rm1(rm1));
+        rm1 += (int32_t)sy.len;
+        emit(st.wpos, 0u, sy.sym, sy.val);
+        st.wpos++;
+    }
+    st.bp = (uint32_t)(rm1 + 1) + (src.wbase << 5);
 }
 
 // sHAC with Rice-coded row gaps: gap codeword, then the value's codeword.  Gap d with

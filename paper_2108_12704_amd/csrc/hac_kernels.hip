@@ -594,6 +594,7 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
     const WordSrc<false> s_glb = { d.stream, 0 };
     const WordSrc<true> r_lds = { sbuf + snw, rwlo };
     const WordSrc<false> r_glb = { d.ri, 0 };
+    const uint32_t ri_rel0 = (uint32_t)(rb_lo - 32ull * rwlo);          // bit of CSC position posbase in the staged ri words
 
     const uint32_t ng = kWave / gw;
     const uint32_t grp = lane / gw, lig = lane % gw;
@@ -693,8 +694,8 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
             if (SHAC) {
                 // row indices: fixed-width fields, unpacked by all lanes side by side
                 for (uint32_t p = winbase + lane; p < winend; p += kWave) {
-                    const uint64_t fb = (uint64_t)p * d.ri_bits;
-                    list[p - winbase].x = staged ? r_lds.field(fb, d.ri_bits) : r_glb.field(fb, d.ri_bits);
+                    list[p - winbase].x = staged ? r_lds.field_rel(__umul24(p - posbase, d.ri_bits) + ri_rel0, d.ri_bits)
+                                                 : r_glb.field((uint64_t)p * d.ri_bits, d.ri_bits);
                 }
             }
             wave_sync();
@@ -807,6 +808,7 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, uint64_t l
     const WordSrc<false> s_glb = { d.stream, 0 };
     const WordSrc<true> r_lds = { sbuf + snw, rwlo };
     const WordSrc<false> r_glb = { d.ri, 0 };
+    const uint32_t ri_rel0 = (uint32_t)(rb_lo - 32ull * rwlo);          // bit of CSC position posbase in the staged ri words
 
     for (uint32_t gb = gfirst; gb < g1; gb += kWave) {
         const uint32_t nact = g1 - gb < (uint32_t)kWave ? g1 - gb : (uint32_t)kWave;
@@ -836,8 +838,8 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, uint64_t l
         if (active) {
             auto emit = [&](uint32_t p, uint32_t row, uint32_t, float v) {
                 if (SHAC) {
-                    const uint64_t fb = (uint64_t)p * d.ri_bits;
-                    row = staged ? r_lds.field(fb, d.ri_bits) : r_glb.field(fb, d.ri_bits);
+                    if (staged) row = r_lds.field_rel(__umul24(p - posbase, d.ri_bits) + ri_rel0, d.ri_bits);
+                    else row = r_glb.field((uint64_t)p * d.ri_bits, d.ri_bits);
                 }
 #pragma unroll
                 for (int i = 0; i < NB; ++i) a[i] = fmaf(px[i], pv, a[i]);

@@ -285,11 +285,12 @@ dot_rows_kernel(DevBlob d, RowsParams rp, const float* __restrict__ X, uint64_t 
             const uint32_t cshift = 8u * (ci & 3u), cword = 4u * h + (ci >> 2);
             const WordSrc<true> r_lds = { sbuf + soff + snw, rwlo };
             const WordSrc<false> r_glb = { d.ri, 0 };
+            const uint32_t ri_rel0 = (uint32_t)(rb_lo - 32ull * rwlo);   // bit of the session's first row index in the staged words
             const uint32_t gpos0 = colpos + pos0;                     // CSC position of the piece's first non-zero
             auto emit = [&](uint32_t p, uint32_t row, uint32_t, float v) {
                 if (SHAC) {
-                    const uint64_t fb = (uint64_t)(gpos0 + (p - base)) * d.ri_bits;
-                    row = staged ? r_lds.field(fb, d.ri_bits) : r_glb.field(fb, d.ri_bits);
+                    if (staged) row = r_lds.field_rel(__umul24(pos0 - poss0 + (p - base), d.ri_bits) + ri_rel0, d.ri_bits);
+                    else row = r_glb.field((uint64_t)(gpos0 + (p - base)) * d.ri_bits, d.ri_bits);
                 }
                 uint32_t rr = row - row0;
                 rr = rr < rend - row0 ? rr : 0u;                      // (a damaged stream: stay inside the buffers)
