@@ -5,22 +5,29 @@
 // The steps of the host encoder, split between device and host:
 //   1. device  histogram of the distinct fp32 values (a hash table keyed by bit pattern, privatised
 //              in LDS per block), and the number of non-zeros and the last non-zero row of every
-//              (row segment, column);
-//   2. host    alphabet in value order, Huffman lengths, canonical code, decode tables; the row
-//              after the last non-zero above every segment;
+//              (row segment, column); the occupied slots of the table are gathered into a list,
+//              and a thread per column walks its segments for the row after the last non-zero
+//              above each;
+//   2. host    alphabet in value order, Huffman lengths, canonical code, decode tables (all of
+//              the size of the alphabet);
 //   3. device  code bits of every (row segment, column); with Rice-coded row gaps also the gap
-//              bits for every parameter k = 0..15, per (segment, column) and in total;
-//   4. host    the Rice parameter; prefix sums along each column: first stream bit / CSC position
-//              of every segment and column, where the non-zero before a segment ended, chunk
-//              counts, section offsets;
+//              bits for every parameter k = 0..15, per (segment, column) and in total; then the
+//              bits and non-zeros of every column (the Rice parameter, picked on the host from
+//              the 16 totals, says which gap bits count);
+//   4. host    chunk size, prefix sums over the columns (first stream bit, CSC position, first
+//              chunk of every column), section offsets, header;
+//      device  a thread per column walks its segments again: first stream bit / CSC position of
+//              every segment, and where the non-zero before it ended;
 //   5. device  one thread per (row segment, column) walks its rows and writes codewords (and
 //              row-index fields or gap codewords) with atomic ORs into the zeroed stream, and the
 //              chunk entries.
 // A thread owns one column of a segment of rows (1024 on large matrices, down to 32 on small ones, so
 // that there are threads enough to fill the chip), so the 64 lanes of a wave read 64
-// neighbouring columns of one row: coalesced reads of the row-major matrix in all three passes.
-// The call synchronises the stream twice (steps 2 and 4 need the device's results), three times
-// with Rice-coded gaps.
+// neighbouring columns of one row: coalesced reads of the row-major matrix in all three passes;
+// the per-column walks read the (segment, column) arrays the same way.
+// What crosses the bus is of the size of the alphabet and of the number of columns, never of the
+// matrix.  The call synchronises the stream twice before its final wait (steps 2 and 4 need the
+// device's results), three times with Rice-coded gaps.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -348,9 +355,96 @@ __global__ void __launch_bounds__(256) enc_emit_kernel(EmitArgs a)
     }
 }
 
+// step 1, second part: the occupied slots of the table as a list of (key, count, slot), in no
+// particular order (the host sorts by value); *n_list counts them, entries past `cap` are dropped
+// (the host then sees n_list > cap and gives up: more than 65536 distinct values)
+__global__ void __launch_bounds__(256)
+enc_gather_kernel(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ cnts, uint32_t* list, uint32_t cap, uint32_t* n_list)
+{
+    const uint32_t h = blockIdx.x * 256 + threadIdx.x;
+    if (h >= kHashSlots) return;
+    const uint32_t key = keys[h];
+    if (!key) return;
+    const uint32_t i = atomicAdd(n_list, 1u);
+    if (i < cap) { list[3 * (uint64_t)i] = key; list[3 * (uint64_t)i + 1] = cnts[h]; list[3 * (uint64_t)i + 2] = h; }
+}
+
+// the row after the last non-zero above every segment (0 at a column's top); a thread per column
+__global__ void __launch_bounds__(256)
+enc_prev_row_kernel(const uint32_t* __restrict__ seg_nnz, const uint32_t* __restrict__ seg_last, uint32_t S, uint32_t m,
+                    uint32_t* __restrict__ seg_prev_row1)
+{
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= m) return;
+    uint32_t prev = 0;
+    for (uint32_t s = 0; s < S; ++s) {
+        const uint64_t at = (uint64_t)s * m + j;
+        seg_prev_row1[at] = prev;
+        if (seg_nnz[at]) prev = seg_last[at] + 1;
+    }
+}
+
+// step 2 -> 3: slot_sym[slot of list entry i] = sym[i] (index among the non-zero values)
+__global__ void __launch_bounds__(256)
+enc_slot_sym_kernel(const uint32_t* __restrict__ list, const uint32_t* __restrict__ sym, uint32_t count, uint32_t* __restrict__ slot_sym)
+{
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i < count) slot_sym[list[3 * (uint64_t)i + 2]] = sym[i];
+}
+
+struct SegBits {
+    const uint32_t* seg_nnz; const uint32_t* seg_codebits; const uint32_t* seg_gapbits;   // gap bits of the chosen k, or nullptr
+    uint32_t n, m, seg_rows, zlen, shac;
+    // stream bits of segment s of the column at index `at`
+    __device__ __forceinline__ uint64_t bits(uint32_t s, uint64_t at) const {
+        const uint64_t r0 = (uint64_t)s * seg_rows, r1 = r0 + seg_rows < n ? r0 + seg_rows : n;
+        return (uint64_t)seg_codebits[at] + (shac ? 0ull : (r1 - r0 - seg_nnz[at]) * zlen) + (seg_gapbits ? seg_gapbits[at] : 0u);
+    }
+};
+
+// step 3, second part: non-zeros and stream bits of every column
+__global__ void __launch_bounds__(256)
+enc_col_sums_kernel(SegBits sb, uint32_t S, uint32_t* __restrict__ col_nnz, unsigned long long* __restrict__ col_bits)
+{
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= sb.m) return;
+    uint32_t nnz = 0;
+    unsigned long long bits = 0;
+    for (uint32_t s = 0; s < S; ++s) {
+        const uint64_t at = (uint64_t)s * sb.m + j;
+        nnz += sb.seg_nnz[at];
+        bits += sb.bits(s, at);
+    }
+    col_nnz[j] = nnz; col_bits[j] = bits;
+}
+
+// step 4, device part: running state per column over its segments
+__global__ void __launch_bounds__(256)
+enc_seg_walk_kernel(SegBits sb, uint32_t S, const uint32_t* __restrict__ seg_last,
+                    const uint32_t* __restrict__ col_bit, const uint32_t* __restrict__ col_pos,
+                    uint32_t* __restrict__ seg_bit0, uint32_t* __restrict__ seg_pos0, uint32_t* __restrict__ seg_prev_end)
+{
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= sb.m) return;
+    uint64_t cur_bit = col_bit[j], cur_pos = col_pos[j], cur_end = col_bit[j];
+    for (uint32_t s = 0; s < S; ++s) {
+        const uint64_t at = (uint64_t)s * sb.m + j;
+        const uint64_t r0 = (uint64_t)s * sb.seg_rows, r1 = r0 + sb.seg_rows < sb.n ? r0 + sb.seg_rows : sb.n;
+        seg_bit0[at] = (uint32_t)cur_bit; seg_pos0[at] = (uint32_t)cur_pos; seg_prev_end[at] = (uint32_t)cur_end;
+        const uint64_t cnt = sb.seg_nnz[at], seg_bits = sb.bits(s, at);
+        if (cnt) {
+            const uint64_t trailing = r1 - 1 - seg_last[at];                 // zeros after the segment's last non-zero
+            cur_end = cur_bit + seg_bits - (sb.shac ? 0ull : trailing * sb.zlen);
+        }
+        cur_bit += seg_bits; cur_pos += cnt;
+    }
+}
+
+constexpr uint32_t kListCap = 65536 + 64;          // one more than the largest alphabet is enough to see "too many"
+
 struct WsLayout {
     size_t keys, cnts, flags, seg_nnz, seg_codebits, seg_last, seg_bit0, seg_pos0, seg_prev_end, seg_prev_row1,
-           slot_sym, codes, lens, gap_bits, total;
+           slot_sym, codes, lens, gap_bits, list, sym, col_nnz, col_bits, total;
 };
 
 WsLayout ws_layout(uint64_t n, uint64_t m)
@@ -364,6 +458,8 @@ WsLayout ws_layout(uint64_t n, uint64_t m)
     L.seg_bit0 = take(4 * S * m); L.seg_pos0 = take(4 * S * m); L.seg_prev_end = take(4 * S * m); L.seg_prev_row1 = take(4 * S * m);
     L.slot_sym = take(4ull * kHashSlots); L.codes = take(4ull * 65537); L.lens = take(65537);
     L.gap_bits = take(4 * S * m * (kRiceKMax + 1));                  // used with Rice-coded gaps only
+    L.list = take(12ull * kListCap); L.sym = take(4ull * kListCap);
+    L.col_nnz = take(4 * m); L.col_bits = take(8 * m);
     L.total = c;
     return L;
 }
@@ -412,31 +508,45 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
     const dim3 grid((uint32_t)((m + 255) / 256), S);
     hipError_t e;
     try {
+        const dim3 cgrid((uint32_t)((m + 255) / 256));               // a thread per column
         // ---- step 1 ----
+        uint32_t* d_flags = dptr(L.flags);                           // [0] flags, [1] length of the list, +64 bytes: gap totals
+        uint32_t* d_n_list = d_flags + 1;
         hipLaunchKernelGGL(fill_zero_kernel, dim3(512), dim3(256), 0, stream, dptr(L.keys), (uint64_t)(L.seg_nnz - L.keys) / 4);
         hipLaunchKernelGGL(enc_scan_kernel, grid, dim3(256), 0, stream, d_W, (uint32_t)n, (uint32_t)m, (uint64_t)ldw, seg_rows,
-                           dptr(L.keys), dptr(L.cnts), dptr(L.seg_nnz), dptr(L.seg_last), dptr(L.flags));
+                           dptr(L.keys), dptr(L.cnts), dptr(L.seg_nnz), dptr(L.seg_last), d_flags);
+        hipLaunchKernelGGL(enc_gather_kernel, dim3(kHashSlots / 256), dim3(256), 0, stream, dptr(L.keys), dptr(L.cnts),
+                           dptr(L.list), kListCap, d_n_list);
+        hipLaunchKernelGGL(enc_prev_row_kernel, cgrid, dim3(256), 0, stream, dptr(L.seg_nnz), dptr(L.seg_last), S, (uint32_t)m,
+                           dptr(L.seg_prev_row1));
         if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
-        // the hash table, the flags and the two per-segment arrays lie side by side in the workspace:
-        // one copy back, read through pointers at the same offsets
-        std::vector<uint32_t> step1((L.seg_last - L.keys) / 4 + SM);
-        if ((e = hipMemcpyAsync(step1.data(), dptr(L.keys), 4 * step1.size(), hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        // flags and the length of the list first (they sit side by side), then as much of the list
+        // as is in use; a small alphabet arrives with the first copy
+        constexpr uint32_t kFirst = 1024;
+        std::vector<uint32_t> list(3 * (size_t)kFirst);
+        uint32_t head2[2] = { 0, 0 };
+        if ((e = hipMemcpyAsync(head2, d_flags, 8, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(list.data(), dptr(L.list), 12 * (size_t)kFirst, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
         if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
-        const uint32_t* keys = step1.data();
-        const uint32_t* cnts = step1.data() + (L.cnts - L.keys) / 4;
-        const uint32_t flags = step1[(L.flags - L.keys) / 4];
-        const uint32_t* seg_nnz = step1.data() + (L.seg_nnz - L.keys) / 4;
-        const uint32_t* seg_last = step1.data() + (L.seg_last - L.keys) / 4;
+        const uint32_t flags = head2[0], n_list = head2[1];
         if (flags & kFlagNonFinite) return HAC_EINVAL;
         if (flags & kFlagTableFull) return HAC_ERANGE;
+        if (n_list > 65536) return HAC_ERANGE;
+        if (n_list > kFirst) {
+            list.resize(3 * (size_t)n_list);
+            if ((e = hipMemcpyAsync(list.data(), dptr(L.list), 12 * (size_t)n_list, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+            if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
+        }
 
         // ---- step 2 ----
-        struct Val { float v; uint32_t slot; uint64_t f; };
-        std::vector<Val> vals;
+        struct Val { float v; uint32_t at; uint64_t f; };             // at: position in the list
+        std::vector<Val> vals(n_list);
         uint64_t nnz = 0;
-        for (uint32_t h = 0; h < kHashSlots; ++h)
-            if (keys[h]) { Val x; std::memcpy(&x.v, &keys[h], 4); x.slot = h; x.f = cnts[h]; vals.push_back(x); nnz += cnts[h]; }
-        if (vals.size() > 65536) return HAC_ERANGE;
+        for (uint32_t i = 0; i < n_list; ++i) {
+            std::memcpy(&vals[i].v, &list[3 * (size_t)i], 4);
+            vals[i].at = i; vals[i].f = list[3 * (size_t)i + 1];
+            nnz += vals[i].f;
+        }
         if (nnz > 0xfffffff0ull) return HAC_ERANGE;
         std::sort(vals.begin(), vals.end(), [](const Val& a, const Val& b) { return a.v < b.v; });
         const uint64_t zeros = (uint64_t)n * (uint64_t)m - nnz;
@@ -457,27 +567,17 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         std::vector<uint32_t> lut; build_lut(len, t, lut_bits, lut);
         const uint32_t zlen = has_zero ? len[0] : 0, zcode = has_zero ? t.code[0] : 0;
 
-        std::vector<uint32_t> slot_sym(kHashSlots, 0);
-        for (size_t i = 0; i < vals.size(); ++i) slot_sym[vals[i].slot] = (uint32_t)i;      // index among the non-zero values
         // the device looks lengths up by "index among the non-zero values" in step 3 and by symbol in step 5
+        std::vector<uint32_t> sym_of_entry(std::max<size_t>(n_list, 1), 0);
+        for (size_t i = 0; i < vals.size(); ++i) sym_of_entry[vals[i].at] = (uint32_t)i;
         std::vector<uint8_t> nz_len(vals.size());
         for (size_t i = 0; i < vals.size(); ++i) nz_len[i] = len[i + shift];
-        if ((e = hipMemcpyAsync(dptr(L.slot_sym), slot_sym.data(), 4ull * kHashSlots, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-        if (!nz_len.empty() && (e = hipMemcpyAsync(ws + L.lens, nz_len.data(), nz_len.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-
-        // the row after the last non-zero above every segment (0 at a column's top)
-        std::vector<uint32_t> seg_prev_row1(SM);
-        {
-            std::vector<uint32_t> prev_row1((size_t)m, 0);                           // per column, walking the segments in storage order
-            for (uint32_t s = 0; s < S; ++s) {
-                const size_t row = (size_t)s * m;
-                for (int64_t j = 0; j < m; ++j) {
-                    seg_prev_row1[row + j] = prev_row1[(size_t)j];
-                    if (seg_nnz[row + j]) prev_row1[(size_t)j] = seg_last[row + j] + 1;
-                }
-            }
+        if (n_list) {
+            if ((e = hipMemcpyAsync(dptr(L.sym), sym_of_entry.data(), 4ull * n_list, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+            if ((e = hipMemcpyAsync(ws + L.lens, nz_len.data(), nz_len.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+            hipLaunchKernelGGL(enc_slot_sym_kernel, dim3((n_list + 255) / 256), dim3(256), 0, stream, dptr(L.list), dptr(L.sym), n_list,
+                               dptr(L.slot_sym));
         }
-        if ((e = hipMemcpyAsync(dptr(L.seg_prev_row1), seg_prev_row1.data(), 4 * SM, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
 
         // ---- step 3 ----
         unsigned long long* d_gap_total = reinterpret_cast<unsigned long long*>(ws + L.flags + 64);   // zeroed with the flags
@@ -485,46 +585,40 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
                            dptr(L.keys), dptr(L.slot_sym), ws + L.lens, dptr(L.seg_codebits), dptr(L.seg_prev_row1),
                            rice ? dptr(L.gap_bits) : static_cast<uint32_t*>(nullptr), d_gap_total, (uint64_t)SM, seg_rows);
         if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
-        std::vector<uint32_t> seg_codebits(SM), seg_gapbits;
-        unsigned long long gap_total[kRiceKMax + 1] = { 0 };
-        if ((e = hipMemcpyAsync(seg_codebits.data(), dptr(L.seg_codebits), 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
-        if (rice && (e = hipMemcpyAsync(gap_total, d_gap_total, sizeof gap_total, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
         // the Rice parameter: fewest gap bits, the smaller k on ties
         uint32_t rice_k = 0; uint64_t gap_bits = 0;
         if (rice) {
+            unsigned long long gap_total[kRiceKMax + 1] = { 0 };
+            if ((e = hipMemcpyAsync(gap_total, d_gap_total, sizeof gap_total, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+            if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
             gap_bits = ~0ull;
             for (uint32_t k = 0; k <= kRiceKMax; ++k) if (gap_total[k] < gap_bits) { gap_bits = gap_total[k]; rice_k = k; }
             if (nnz == 0) { gap_bits = 0; rice_k = 0; }
-            seg_gapbits.resize(SM);
-            if ((e = hipMemcpyAsync(seg_gapbits.data(), dptr(L.gap_bits) + (size_t)rice_k * SM, 4 * SM, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
-            if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
             total_bits += gap_bits;
             if (total_bits > 0xfffffff0ull) return HAC_ERANGE;
         }
+        SegBits sb;
+        sb.seg_nnz = dptr(L.seg_nnz); sb.seg_codebits = dptr(L.seg_codebits);
+        sb.seg_gapbits = rice ? dptr(L.gap_bits) + (size_t)rice_k * SM : nullptr;
+        sb.n = (uint32_t)n; sb.m = (uint32_t)m; sb.seg_rows = seg_rows; sb.zlen = zlen; sb.shac = shac ? 1u : 0u;
+        unsigned long long* d_col_bits = reinterpret_cast<unsigned long long*>(ws + L.col_bits);
+        hipLaunchKernelGGL(enc_col_sums_kernel, cgrid, dim3(256), 0, stream, sb, S, dptr(L.col_nnz), d_col_bits);
+        if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e);
+        std::vector<uint32_t> col_nnz((size_t)m);
+        std::vector<unsigned long long> col_bits((size_t)m);
+        if ((e = hipMemcpyAsync(col_nnz.data(), dptr(L.col_nnz), 4 * (size_t)m, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipMemcpyAsync(col_bits.data(), d_col_bits, 8 * (size_t)m, hipMemcpyDeviceToHost, stream)) != hipSuccess) return hip_fail(e);
+        if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e);
 
         // ---- step 4 ----
-        // All loops below walk the (segment, column) arrays in storage order (segment-major).
         uint64_t max_col_nnz = 0, max_col_bits = 0;
-        std::vector<uint64_t> col_nnz((size_t)m, 0), col_bits((size_t)m, 0);
-        auto seg_bits_at = [&](uint32_t s, size_t at) -> uint64_t {
-            const uint64_t r0 = (uint64_t)s * seg_rows, r1 = std::min<uint64_t>(r0 + seg_rows, (uint64_t)n);
-            return seg_codebits[at] + (shac ? 0 : (r1 - r0 - seg_nnz[at]) * zlen) + (rice ? seg_gapbits[at] : 0);
-        };
-        for (uint32_t s = 0; s < S; ++s) {
-            const size_t row = (size_t)s * m;
-            for (int64_t j = 0; j < m; ++j) {
-                col_nnz[(size_t)j] += seg_nnz[row + j];
-                col_bits[(size_t)j] += seg_bits_at(s, row + j);
-            }
-        }
         for (int64_t j = 0; j < m; ++j) {
-            max_col_nnz = std::max(max_col_nnz, col_nnz[(size_t)j]);
-            max_col_bits = std::max(max_col_bits, col_bits[(size_t)j]);
+            max_col_nnz = std::max<uint64_t>(max_col_nnz, col_nnz[(size_t)j]);
+            max_col_bits = std::max<uint64_t>(max_col_bits, col_bits[(size_t)j]);
         }
         const uint32_t Cn = pick_chunk(opts, max_col_nnz);
         // the three per-column arrays sit side by side in the blob (256-byte aligned sections): one
-        // host buffer with the same spacing, one copy; likewise the three per-segment arrays of step 5
+        // host buffer with the same spacing, one copy
         const size_t col_stride = (4 * ((size_t)m + 1) + 255) / 256 * 256 / 4;       // words from one array to the next
         std::vector<uint32_t> col_arrays(3 * col_stride, 0);
         uint32_t* col_chunk = col_arrays.data();
@@ -535,31 +629,6 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
             col_bit[(size_t)j] = (uint32_t)bit; col_pos[(size_t)j] = (uint32_t)pos; col_chunk[(size_t)j] = (uint32_t)chunks;
             bit += col_bits[(size_t)j]; pos += col_nnz[(size_t)j];
             chunks += (col_nnz[(size_t)j] + Cn - 1) / Cn;
-        }
-        const size_t seg_stride = (4 * SM + 255) / 256 * 256 / 4;
-        std::vector<uint32_t> seg_arrays(3 * seg_stride, 0);
-        uint32_t* seg_bit0 = seg_arrays.data();
-        uint32_t* seg_pos0 = seg_bit0 + seg_stride;
-        uint32_t* seg_prev_end = seg_pos0 + seg_stride;
-        {
-            // running state per column: next stream bit, next CSC position, where its last non-zero ended
-            std::vector<uint64_t> cur_bit((size_t)m), cur_pos((size_t)m), cur_end((size_t)m);
-            for (int64_t j = 0; j < m; ++j) { cur_bit[(size_t)j] = col_bit[(size_t)j]; cur_pos[(size_t)j] = col_pos[(size_t)j]; cur_end[(size_t)j] = col_bit[(size_t)j]; }
-            for (uint32_t s = 0; s < S; ++s) {
-                const size_t row = (size_t)s * m;
-                const uint64_t r0 = (uint64_t)s * seg_rows, r1 = std::min<uint64_t>(r0 + seg_rows, (uint64_t)n);
-                for (int64_t j = 0; j < m; ++j) {
-                    const size_t at = row + j;
-                    seg_bit0[at] = (uint32_t)cur_bit[(size_t)j]; seg_pos0[at] = (uint32_t)cur_pos[(size_t)j];
-                    seg_prev_end[at] = (uint32_t)cur_end[(size_t)j];
-                    const uint64_t cnt = seg_nnz[at], seg_bits = seg_bits_at(s, at);
-                    if (cnt) {
-                        const uint64_t trailing = r1 - 1 - seg_last[at];             // zeros after the segment's last non-zero
-                        cur_end[(size_t)j] = cur_bit[(size_t)j] + seg_bits - (shac ? 0 : trailing * zlen);
-                    }
-                    cur_bit[(size_t)j] += seg_bits; cur_pos[(size_t)j] += cnt;
-                }
-            }
         }
         col_bit[(size_t)m] = (uint32_t)bit; col_pos[(size_t)m] = (uint32_t)pos; col_chunk[(size_t)m] = (uint32_t)chunks;
         if (bit != total_bits || pos != nnz) return HAC_EFORMAT;
@@ -600,10 +669,11 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(blob + d.off_stream),
                            (uint64_t)(d.blob_bytes - d.off_stream) / 4);
         if ((e = hipMemcpyAsync(blob, head.data(), head_bytes, hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-        if (d.off_col_pos - d.off_col_chunk != 4 * col_stride || d.off_col_bit - d.off_col_pos != 4 * col_stride ||
-            L.seg_pos0 - L.seg_bit0 != 4 * seg_stride || L.seg_prev_end - L.seg_pos0 != 4 * seg_stride) return HAC_EFORMAT;
+        if (d.off_col_pos - d.off_col_chunk != 4 * col_stride || d.off_col_bit - d.off_col_pos != 4 * col_stride) return HAC_EFORMAT;
         if ((e = hipMemcpyAsync(blob + d.off_col_chunk, col_chunk, 4 * (2 * col_stride + (size_t)m + 1), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
-        if ((e = hipMemcpyAsync(dptr(L.seg_bit0), seg_bit0, 4 * (2 * seg_stride + SM), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
+        hipLaunchKernelGGL(enc_seg_walk_kernel, cgrid, dim3(256), 0, stream, sb, S, dptr(L.seg_last),
+                           reinterpret_cast<const uint32_t*>(blob + d.off_col_bit), reinterpret_cast<const uint32_t*>(blob + d.off_col_pos),
+                           dptr(L.seg_bit0), dptr(L.seg_pos0), dptr(L.seg_prev_end));
         // step 5 looks codes and lengths up by symbol
         if (!t.code.empty() && (e = hipMemcpyAsync(dptr(L.codes), t.code.data(), 4 * t.code.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
         if (!len.empty() && (e = hipMemcpyAsync(ws + L.lens, len.data(), len.size(), hipMemcpyHostToDevice, stream)) != hipSuccess) return hip_fail(e);
