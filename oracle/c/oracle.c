@@ -3,7 +3,10 @@
  * TEST INFRASTRUCTURE.  Written from the paper (arXiv 2108.12704, Sect. IV);
  * shares nothing with the HIP library.  Same readings as the Python oracle:
  * b = 32-bit words, first stream bit = most significant bit of word 0,
- * decoders stop on the symbol count, fp64 accumulation.
+ * decoders stop on the symbol count, fp64 accumulation.  The sequential dot
+ * routines are written as what they compute -- the columns of W summed as
+ * their codewords are read off the stream by a bit-serial tree walk -- not as
+ * a transcription of the paper's listings.
  *
  * The Huffman code itself is built by the Python oracle and handed in as
  *   - values[k], code[k], len[k]      for encoding (H_W), and
@@ -91,25 +94,28 @@ int oracle_shac_encode(const float *W, int64_t n, int64_t m,
     return 0;
 }
 
-/* ---- next code word: walk the tree one bit at a time ----
- * `node` plays the role of `rem` (what has been read of a codeword that is
- * not complete yet); `oset` is the bit offset inside the current word S.
- * Returns the symbol, or -1 ("null") when S is used up first. */
+/* ---- the code tree and a bit-serial reader ----
+ * The stream is one long run of bits, bit p being bit (31 - p % 32) of word
+ * p / 32; a codeword may straddle two words.  A symbol is read by walking the
+ * tree from the root, one edge per bit (0 left, 1 right), down to a leaf. */
 typedef struct { const int32_t *left, *right; int32_t k, root; } tree_t;
 
-static int ncw(uint32_t S, int *oset, int32_t *node, const tree_t *t)
+static int bit_at(const uint32_t *C, int64_t pos)
 {
-    while (*oset < 32) {
-        int bit = (S >> (31 - *oset)) & 1u;
-        (*oset)++;
-        *node = bit ? t->right[*node - t->k] : t->left[*node - t->k];
-        if (*node < t->k) {
-            int z = *node;
-            *node = t->root;
-            return z;
-        }
+    return (int)((C[pos / 32] >> (31 - (int)(pos % 32))) & 1u);
+}
+
+/* symbol whose codeword starts at bit *pos; advances *pos past it.  Never reads
+ * past bit `end`: returns -1 when the codeword does not end before it. */
+static int next_symbol(const uint32_t *C, int64_t *pos, int64_t end, const tree_t *t)
+{
+    int32_t node = t->root;
+    while (node >= t->k) {
+        if (*pos >= end) return -1;
+        node = bit_at(C, *pos) ? t->right[node - t->k] : t->left[node - t->k];
+        (*pos)++;
     }
-    return -1;
+    return node;
 }
 
 int oracle_unpack(const uint32_t *words, int64_t N, int64_t count,
@@ -117,70 +123,56 @@ int oracle_unpack(const uint32_t *words, int64_t N, int64_t count,
                   int32_t *sym_out)
 {
     tree_t t = { left, right, k, root };
-    int32_t node = root;
-    int64_t got = 0;
-    for (int64_t i = 0; i < N && got < count; ++i) {
-        int oset = 0, z;
-        while (got < count && (z = ncw(words[i], &oset, &node, &t)) >= 0)
-            sym_out[got++] = z;
+    int64_t pos = 0;
+    for (int64_t got = 0; got < count; ++got) {
+        int z = next_symbol(words, &pos, N * 32, &t);
+        if (z < 0) return -1;
+        sym_out[got] = z;
     }
-    return got == count ? 0 : -1;
+    return 0;
 }
 
-/* Algorithm 1 (Dot_HAC): out[m] = x^T W, x has n entries. */
+/* x^T W from a HAC stream (what Algorithm 1 returns): the stream is W column
+ * after column, every entry a codeword, so column j is the next n symbols;
+ * each is multiplied with its row's x as it is read.  out[m], x has n entries. */
 int oracle_dot_hac(const uint32_t *C, int64_t N,
                    const int32_t *left, const int32_t *right, int32_t k, int32_t root,
-                   const float *Hinv_values, const float *x, int64_t n, int64_t m, double *out)
+                   const float *value, const float *x, int64_t n, int64_t m, double *out)
 {
     tree_t t = { left, right, k, root };
-    int64_t row = 0, col = 0, remaining = n * m;
-    double sum = 0.0;
-    int32_t node = root;
-    for (int64_t j = 0; j < m; ++j) out[j] = 0.0;
-    for (int64_t i = 0; i < N && remaining > 0; ++i) {
-        uint32_t S = C[i];
-        int oset = 0, z;
-        while (remaining > 0 && (z = ncw(S, &oset, &node, &t)) >= 0) {
-            remaining--;
-            sum += (double)x[row] * (double)Hinv_values[z];
-            row++;
-            if (row == n) {
-                row = 0;
-                out[col] = sum;
-                col++;
-                sum = 0.0;
-            }
+    int64_t pos = 0;
+    for (int64_t j = 0; j < m; ++j) {
+        double sum = 0.0;
+        for (int64_t i = 0; i < n; ++i) {
+            int z = next_symbol(C, &pos, N * 32, &t);
+            if (z < 0) return -1;
+            sum += (double)x[i] * (double)value[z];
         }
+        out[j] = sum;
     }
-    return remaining == 0 ? 0 : -1;
+    return 0;
 }
 
-/* Algorithm 2 (Dot_sHAC). */
+/* x^T W from the sHAC triple (what Algorithm 2 returns): the stream holds the
+ * non-zeros only, in CSC order; column j owns positions cb[j] .. cb[j+1] - 1
+ * (none for an empty column, whose sum stays 0) and position p is in row ri[p]. */
 int oracle_dot_shac(const uint32_t *C, int64_t N1, const int64_t *ri, const int64_t *cb,
                     const int32_t *left, const int32_t *right, int32_t k, int32_t root,
-                    const float *Hinv_values, const float *x, int64_t n, int64_t m, double *out)
+                    const float *value, const float *x, int64_t n, int64_t m, double *out)
 {
     tree_t t = { left, right, k, root };
-    int64_t pos = 0, col = 0, q = cb[m];
-    double sum = 0.0;
-    int32_t node = root;
+    int64_t pos = 0;
     (void)n;
-    for (int64_t j = 0; j < m; ++j) out[j] = 0.0;
-    for (int64_t i = 0; i < N1 && pos < q; ++i) {
-        uint32_t S = C[i];
-        int oset = 0, z;
-        while (pos < q && (z = ncw(S, &oset, &node, &t)) >= 0) {
-            while (cb[col + 1] == pos) col++;              /* empty columns */
-            sum += (double)x[ri[pos]] * (double)Hinv_values[z];
-            pos++;
-            if (cb[col + 1] == pos) {
-                out[col] = sum;
-                sum = 0.0;
-                col++;
-            }
+    for (int64_t j = 0; j < m; ++j) {
+        double sum = 0.0;
+        for (int64_t p = cb[j]; p < cb[j + 1]; ++p) {
+            int z = next_symbol(C, &pos, N1 * 32, &t);
+            if (z < 0) return -1;
+            sum += (double)x[ri[p]] * (double)value[z];
         }
+        out[j] = sum;
     }
-    return pos == q ? 0 : -1;
+    return 0;
 }
 
 /* Algorithm 3 (ParDot): rows of X in q chunks of ceil(rows/q), one thread per
@@ -279,23 +271,6 @@ int oracle_pardot_shac(const uint32_t *C, int64_t N1, const int64_t *ri, const i
  * memory.  fp64 accumulation, rows in ascending order: the result is the
  * dense product up to rounding, and does not depend on the thread count. */
 
-static int bit_at(const uint32_t *C, int64_t pos)
-{
-    return (int)((C[pos / 32] >> (31 - (int)(pos % 32))) & 1u);
-}
-
-/* symbol whose codeword starts at bit *pos; advances *pos past it */
-static int next_symbol(const uint32_t *C, int64_t *pos, const tree_t *t)
-{
-    int32_t node = t->root;
-    if (t->k == 1) { (*pos)++; return 0; }           /* one symbol: codeword "0" */
-    while (node >= t->k) {
-        node = bit_at(C, *pos) ? t->right[node - t->k] : t->left[node - t->k];
-        (*pos)++;
-    }
-    return node;
-}
-
 /* HAC: colbit[j] = first bit of column j (m + 1 entries, colbit[m] = stream length). */
 int oracle_hac_column_offsets(const uint32_t *C, int64_t nbits,
                               const int32_t *left, const int32_t *right, int32_t k, int32_t root,
@@ -305,10 +280,8 @@ int oracle_hac_column_offsets(const uint32_t *C, int64_t nbits,
     int64_t pos = 0;
     for (int64_t j = 0; j < m; ++j) {
         colbit[j] = pos;
-        for (int64_t i = 0; i < n; ++i) {
-            if (pos >= nbits) return -1;
-            (void)next_symbol(C, &pos, &t);
-        }
+        for (int64_t i = 0; i < n; ++i)
+            if (next_symbol(C, &pos, nbits, &t) < 0) return -1;
     }
     colbit[m] = pos;
     return pos == nbits ? 0 : -1;
@@ -323,10 +296,8 @@ int oracle_shac_column_offsets(const uint32_t *C, int64_t nbits, const int64_t *
     int64_t pos = 0;
     for (int64_t j = 0; j < m; ++j) {
         colbit[j] = pos;
-        for (int64_t p = cb[j]; p < cb[j + 1]; ++p) {
-            if (pos >= nbits) return -1;
-            (void)next_symbol(C, &pos, &t);
-        }
+        for (int64_t p = cb[j]; p < cb[j + 1]; ++p)
+            if (next_symbol(C, &pos, nbits, &t) < 0) return -1;
     }
     colbit[m] = pos;
     return pos == nbits ? 0 : -1;
@@ -343,23 +314,29 @@ typedef struct {
     double *out;              /* B x m */
     double *sums;             /* this thread's B sums */
     int64_t c0, c1;
+    int status;
 } col_job;
 
 static void *col_worker(void *arg)
 {
     col_job *j = (col_job *)arg;
+    const int64_t end = j->colbit[j->m];          /* the stream's length in bits */
     for (int64_t col = j->c0; col < j->c1; ++col) {
         int64_t pos = j->colbit[col];
         for (int64_t b = 0; b < j->B; ++b) j->sums[b] = 0.0;
         if (j->shac) {
             for (int64_t p = j->cb[col]; p < j->cb[col + 1]; ++p) {
-                const double v = (double)j->values[next_symbol(j->C, &pos, &j->tree)];
+                const int z = next_symbol(j->C, &pos, end, &j->tree);
+                if (z < 0) { j->status = -1; return NULL; }
+                const double v = (double)j->values[z];
                 const float *x = j->xt + j->ri[p] * j->B;
                 for (int64_t b = 0; b < j->B; ++b) j->sums[b] += (double)x[b] * v;
             }
         } else {
             for (int64_t i = 0; i < j->n; ++i) {
-                const float w = j->values[next_symbol(j->C, &pos, &j->tree)];
+                const int z = next_symbol(j->C, &pos, end, &j->tree);
+                if (z < 0) { j->status = -1; return NULL; }
+                const float w = j->values[z];
                 if (w == 0.0f) continue;
                 const float *x = j->xt + i * j->B;
                 for (int64_t b = 0; b < j->B; ++b) j->sums[b] += (double)x[b] * (double)w;
@@ -396,12 +373,15 @@ int oracle_coldot(const uint32_t *C, const int64_t *colbit, const int64_t *ri, c
             j->shac = cb != NULL; j->C = C; j->colbit = colbit; j->ri = ri; j->cb = cb;
             j->tree.left = left; j->tree.right = right; j->tree.k = k; j->tree.root = root;
             j->values = values; j->xt = xt; j->B = B; j->n = n; j->m = m; j->out = out;
-            j->sums = sums + (size_t)started * (size_t)B; j->c0 = c0; j->c1 = c1;
+            j->sums = sums + (size_t)started * (size_t)B; j->c0 = c0; j->c1 = c1; j->status = 0;
             if (pthread_create(&th[started], NULL, col_worker, j)) { rc = -3; break; }
             started++;
         }
     }
-    for (int t = 0; t < started; ++t) pthread_join(th[t], NULL);
+    for (int t = 0; t < started; ++t) {
+        pthread_join(th[t], NULL);
+        if (jobs[t].status) rc = jobs[t].status;
+    }
 done:
     free(xt); free(sums); free(th); free(jobs);
     return rc;

@@ -1,18 +1,22 @@
-"""Dot procedures on the compressed formats (paper Algorithms 1, 2 and 3).
+"""Dot procedures on the compressed formats (what the paper's Algorithms 1, 2 and 3 return).
 
 TEST INFRASTRUCTURE -- see oracle/__init__.py.
 
 The result of all three is the plain product with the decoded matrix
-(each algorithm's "Output" line): dense_dot below is that definition in fp64.
-Algorithms 1-3 are also taken step by step, with the paper's variable names,
-as a second route to the same numbers.  Accumulation is fp64 throughout.
+(each algorithm's "Output" line): dense_dot below is that definition in fp64
+and the parity reference.  dot_hac / dot_shac reach the same numbers straight
+from the compressed form, without materialising W: a bit-serial walk of the
+code tree hands out one symbol per codeword, and the columns of W are summed
+as their symbols arrive (HAC: n symbols per column; sHAC: cb[j+1] - cb[j]
+symbols, rows from ri).  Accumulation is fp64 throughout, in stream order.
 """
 from __future__ import annotations
 
-from typing import Dict, Optional, Tuple
+from typing import Iterator
 
 import numpy as np
 
+from . import huffman
 from .formats import HAC, SHAC, WORD_BITS
 
 
@@ -26,96 +30,62 @@ def abs_dot(X: np.ndarray, W: np.ndarray) -> np.ndarray:
     return np.abs(np.asarray(X, dtype=np.float64)) @ np.abs(np.asarray(W, dtype=np.float64))
 
 
-def get_binary_seq(word: int) -> str:
-    """Binary representation S of one memory word, first stream bit first."""
-    return format(int(word), "b").zfill(WORD_BITS)
+def codewords(words: np.ndarray, code: huffman.HuffmanCode) -> Iterator[int]:
+    """The symbols of a stream, one per codeword, for as long as the caller asks.
 
-
-def ncw(S: str, rem: str, oset: int, Hinv: Dict[str, int]) -> Tuple[int, str, Optional[int]]:
-    """Next code word (Sect. IV-B, "Dot product").
-
-    Extends the unprocessed bits `rem` with bits of S from offset `oset`, one
-    at a time, searching the decoding dictionary after every bit.  Returns
-    (oset, rem, z): z is the decoded symbol and rem is empty again, or z is
-    None (the paper's "null") when S is exhausted first -- the codeword
-    continues in the next memory word and rem holds the bits read so far.
+    The words are one long run of bits (first stream bit = most significant bit
+    of word 0; a codeword may straddle two words).  Every bit moves one edge
+    down the code tree -- 0 left, 1 right -- and a leaf ends the codeword.  The
+    zero padding behind the last codeword is only reached by a caller that asks
+    for more symbols than were stored.
     """
-    cur = rem
-    while oset < len(S):
-        cur += S[oset]
-        oset += 1
-        if cur in Hinv:
-            return oset, "", Hinv[cur]
-    return oset, cur, None
+    k = code.k
+    node = code.root
+    for w in words:
+        w = int(w)
+        for t in range(WORD_BITS - 1, -1, -1):
+            node = code.right[node - k] if (w >> t) & 1 else code.left[node - k]
+            if node < k:
+                yield node
+                node = code.root
 
 
 def dot_hac(h: HAC, x: np.ndarray) -> np.ndarray:
-    """Algorithm 1 (Dot_HAC): x^T W from the HAC stream, one codeword at a time."""
-    n, m = h.n, h.m
-    Hinv = h.code.decoding_dictionary()
-    Hval = h.values.astype(np.float64)
+    """x^T W from the HAC stream (Sect. IV-B): the stream is W column after column, every
+    entry a codeword, so column j is the next n symbols; each is multiplied with its row's x
+    as it is decoded."""
+    value = h.values.astype(np.float64)
     x = np.asarray(x, dtype=np.float64)
-    out = np.zeros(m, dtype=np.float64)
-    row, col = 0, 0
-    acc = 0.0
-    rem, oset = "", 0
-    left = n * m                       # symbols still to decode: the padding is never read as data
-    for i in range(h.N):
-        if left == 0:
-            break
-        S = get_binary_seq(h.words[i])
-        oset = 0
-        while left > 0:
-            oset, rem, z = ncw(S, rem, oset, Hinv)
-            if z is None:
-                break
-            left -= 1
-            acc += x[row] * Hval[z]
-            row += 1
-            if row == n:
-                row = 0
-                out[col] = acc
-                col += 1
-                acc = 0.0
+    stream = codewords(h.words, h.code)
+    out = np.zeros(h.m, dtype=np.float64)
+    for j in range(h.m):
+        total = 0.0
+        for i in range(h.n):
+            total += x[i] * value[next(stream)]
+        out[j] = total
     return out
 
 
 def dot_shac(s: SHAC, x: np.ndarray) -> np.ndarray:
-    """Algorithm 2 (Dot_sHAC): x^T W from the sHAC triple (C_HAC(nz), ri, cb)."""
-    m = s.m
-    Hinv = s.code.decoding_dictionary()
-    Hval = s.values.astype(np.float64)
+    """x^T W from the sHAC triple (Sect. IV-C): the stream holds the non-zeros only, in CSC
+    order; column j owns positions cb[j] .. cb[j+1] - 1 (none for an empty column) and
+    position p sits in row ri[p]."""
+    value = s.values.astype(np.float64)
     x = np.asarray(x, dtype=np.float64)
-    out = np.zeros(m, dtype=np.float64)          # empty columns keep the value 0
-    cb, ri = s.cb, s.ri
-    pos, col = 0, 0
-    acc = 0.0
-    rem, oset = "", 0
-    q = s.q
-    for i in range(s.N1):
-        if pos == q:
-            break
-        S = get_binary_seq(s.words[i])
-        oset = 0
-        while pos < q:
-            oset, rem, z = ncw(S, rem, oset, Hinv)
-            if z is None:
-                break
-            while cb[col + 1] == pos:            # skip empty columns
-                col += 1
-            acc += x[ri[pos]] * Hval[z]
-            pos += 1
-            if cb[col + 1] == pos:               # last non-zero of this column
-                out[col] = acc
-                acc = 0.0
-                col += 1
+    stream = codewords(s.words, s.code)
+    out = np.zeros(s.m, dtype=np.float64)          # empty columns keep the value 0
+    for j in range(s.m):
+        total = 0.0
+        for p in range(int(s.cb[j]), int(s.cb[j + 1])):
+            total += x[s.ri[p]] * value[next(stream)]
+        out[j] = total
     return out
 
 
 def pardot(struct, X: np.ndarray, q: int = 1) -> np.ndarray:
-    """Algorithm 3 (ParDot): the rows of X are split into q chunks of
-    k = ceil(rows / q); every row goes through Dot on the whole compressed W.
-    (The chunks are independent; here they simply run one after the other.)"""
+    """Algorithm 3 (ParDot): the rows of X are dealt to q workers in runs of
+    ceil(rows / q) consecutive rows; every row goes through the single-vector procedure on
+    the whole compressed W.  (The runs are independent; here they simply follow each other.)"""
     X = np.asarray(X)
     rows = X.shape[0]
     dot = dot_hac if isinstance(struct, HAC) else dot_shac

@@ -13,7 +13,7 @@ import pytest
 import scipy.sparse
 
 import workloads
-from oracle import cnative, dot, formats
+from oracle import cnative, dot, formats, huffman
 
 
 def example_matrix(golden):
@@ -108,14 +108,13 @@ def test_pardot_chunking_covers_every_row_once():
         np.testing.assert_allclose(dot.pardot(hp, X, q=q), ref, rtol=0, atol=1e-12)
 
 
-def test_ncw_null_when_codeword_straddles_words():
-    Hinv = {"0": 0, "10": 1, "110": 2, "111": 3}
-    S = "0" * 30 + "11"
-    oset, rem, z = 30, "", None
-    oset, rem, z = dot.ncw(S, rem, oset, Hinv)
-    assert z is None and rem == "11" and oset == 32
-    oset, rem, z = dot.ncw("0" + "1" * 31, rem, 0, Hinv)
-    assert z == 2 and rem == "" and oset == 1
+def test_codeword_straddling_two_words_is_decoded_once():
+    # 30 one-bit codewords, then "110" across the word boundary, then "10"
+    code = huffman.HuffmanCode(4, [2, 1, 0], [3, 4, 5], 6, [(0, 1), (2, 2), (6, 3), (7, 3)])
+    assert code.decoding_dictionary() == {"0": 0, "10": 1, "110": 2, "111": 3}
+    words = np.array([0b11, 0b010 << 29], dtype=np.uint32)
+    stream = dot.codewords(words, code)
+    assert [next(stream) for _ in range(32)] == [0] * 30 + [2, 1]
 
 
 # ---- decode once, threads over columns (the per-column offsets of the paper's conclusions) ----
