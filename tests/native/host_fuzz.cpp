@@ -133,6 +133,13 @@ int main()
                     void* blob = nullptr; size_t bytes = 0;
                     hac_opts_t o; std::memset(&o, 0, sizeof o);
                     o.chunk_nnz = (uint32_t)(rng() % 3 == 0 ? 1 + rng() % 9 : 0);
+                    // half of the HAC and sHAC blobs carry the row index (rows per entry: automatic,
+                    // a small multiple of 4, or the whole column)
+                    if (f < 2 && rng() % 2 == 0) {
+                        const uint32_t pick = (uint32_t)(rng() % 3);
+                        o.chunk_rows = pick == 0 ? HAC_CHUNK_ROWS_AUTO : pick == 1 ? (uint32_t)n : 4u * (1u + (uint32_t)(rng() % 4));
+                        if (o.chunk_rows != HAC_CHUNK_ROWS_AUTO && o.chunk_rows > (uint32_t)n) o.chunk_rows = (uint32_t)n;
+                    }
                     int rc;
                     if (f == 0) rc = hac_encode(W.data(), n, m, m, &o, &blob, &bytes);
                     else if (f == 1) rc = shac_encode(W.data(), n, m, m, &o, &blob, &bytes);
