@@ -83,7 +83,10 @@ typedef void *hac_stream_t;
 typedef struct {
     uint32_t chunk_nnz;   /* non-zeros per index entry, restarting at every column; 0 = default
                              [max(4, ceil(most non-zeros in a column / 64))]: one wavefront
-                             then decodes a whole column side by side                       */
+                             then decodes a whole column side by side.
+                             HAC_CHUNK_PER_COLUMN: every column its own chunk size,
+                             max(4, ceil(its non-zeros / 64)), so that every long column
+                             fills the 64 lanes, not only the longest                       */
     uint32_t ri_bits;     /* sHAC row-index field width: 0 = ceil(log2 n) (footnote of
                              Sect. IV-A), 32 = one word per index as in Corollary 2        */
     uint32_t lut_bits;    /* width of the first-level decode table, 1..12 [min(Lmax,10)]  */
@@ -97,6 +100,8 @@ typedef struct {
 
 enum { HAC_RI_FIELDS = 0, HAC_RI_RICE = 1 };
 #define HAC_CHUNK_ROWS_AUTO 0xffffffffu
+#define HAC_CHUNK_PER_COLUMN 0xffffffffu
+#define HAC_CHUNK_FLAG_PER_COLUMN 0x80000000u   /* in hac_desc_t.chunk */
 
 /* Blob header == descriptor.  All offsets are bytes from the start of the blob.
  *
@@ -135,11 +140,13 @@ typedef struct {
     uint32_t has_zero;     /* HAC: 1 when 0.0 occurs in W; it is then symbol 0             */
     uint32_t zero_len;     /* HAC: codeword length of symbol 0 when that codeword is all
                               zero bits (it is one of the shortest), else 0                */
-    uint32_t chunk;        /* non-zeros per chunk                                          */
+    uint32_t chunk;        /* non-zeros per chunk; with HAC_CHUNK_FLAG_PER_COLUMN set the low
+                              bits are the smallest chunk size and column j is cut into chunks of
+                              max(that, ceil(non-zeros of j / 64)) non-zeros                  */
     uint32_t ri_bits;      /* sHAC: width of one row-index field                           */
     uint32_t ent_bits;     /* width of one chunk entry: HAC and Rice-coded sHAC 32 or 64,
                               sHAC with ri fields 16 or 32                                 */
-    uint64_t n_chunks;     /* sum over columns of ceil(non-zeros in the column / chunk)    */
+    uint64_t n_chunks;     /* sum over columns of ceil(non-zeros in the column / its chunk size) */
     uint64_t off_codebook; /* float[k_sym]: symbol -> shared value (H^-1's values)         */
     uint64_t off_codelen;  /* uint8[k_sym]: codeword length per symbol                     */
     uint64_t off_canon;    /* uint32[3][33]: first_code[l], count[l], first_index[l]       */

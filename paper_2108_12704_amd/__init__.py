@@ -305,6 +305,8 @@ RI_FIELDS, RI_RICE = 0, 1
 
 
 CHUNK_ROWS_AUTO = 0xFFFFFFFF
+CHUNK_PER_COLUMN = 0xFFFFFFFF        # Opts.chunk_nnz: every column its own chunk size
+CHUNK_FLAG_PER_COLUMN = 0x80000000   # in Desc.chunk
 
 
 def hac_net_encode(Ws, formats, chunk_nnz: int = 0, ri_bits: int = 0, lut_bits: int = 0,

@@ -295,11 +295,12 @@ __global__ void __launch_bounds__(256) enc_emit_kernel(EmitArgs a)
     uint32_t bit = a.seg_bit0[at], pos = a.seg_pos0[at];
     uint32_t pend = a.seg_prev_end[at], prow = a.seg_prev_row1[at];   // HAC: where the non-zero before this one ended
     const uint32_t cbit0 = a.col_bit[j], cpos0 = a.col_pos[j], cchunk0 = a.col_chunk[j];
+    const uint32_t chunk = hac_internal::chunk_of_column(a.chunk, a.col_pos[j + 1] - cpos0);   // of this column
     const uint32_t shift = (!a.shac && a.has_zero) ? 1u : 0u;          // HAC numbers 0.0 as symbol 0
     auto on_nonzero = [&](uint32_t r, uint32_t len, uint32_t code) {
         const uint32_t q = pos - cpos0;
-        if (q % a.chunk == 0) {
-            const uint32_t g = cchunk0 + q / a.chunk;
+        if (q % chunk == 0) {
+            const uint32_t g = cchunk0 + q / chunk;
             if (a.rice) {
                 // the chunk starts at its first gap codeword; the gap counts from the row after the non-zero before
                 const uint32_t rel = bit - cbit0;
@@ -628,7 +629,8 @@ extern "C" int hac_encode_dev(uint32_t format, const float* d_W, int64_t n, int6
         for (int64_t j = 0; j < m; ++j) {
             col_bit[(size_t)j] = (uint32_t)bit; col_pos[(size_t)j] = (uint32_t)pos; col_chunk[(size_t)j] = (uint32_t)chunks;
             bit += col_bits[(size_t)j]; pos += col_nnz[(size_t)j];
-            chunks += (col_nnz[(size_t)j] + Cn - 1) / Cn;
+            const uint32_t cj = chunk_of_column(Cn, col_nnz[(size_t)j]);
+            chunks += (col_nnz[(size_t)j] + cj - 1) / cj;
         }
         col_bit[(size_t)m] = (uint32_t)bit; col_pos[(size_t)m] = (uint32_t)pos; col_chunk[(size_t)m] = (uint32_t)chunks;
         if (bit != total_bits || pos != nnz) return HAC_EFORMAT;

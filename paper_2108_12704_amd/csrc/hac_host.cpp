@@ -291,6 +291,7 @@ uint32_t pick_lut_bits(const hac_opts_t* opts, uint32_t lmax)
 
 uint32_t pick_chunk(const hac_opts_t* opts, uint64_t max_col_nnz)
 {
+    if (opts && opts->chunk_nnz == HAC_CHUNK_PER_COLUMN) return kChunkPerColumn | kChunkPerColumnLeast;
     if (opts && opts->chunk_nnz) return opts->chunk_nnz;
     const uint64_t c = (max_col_nnz + 63) / 64;              // a 64-lane wavefront covers any column
     return (uint32_t)std::min<uint64_t>(std::max<uint64_t>(c, 4), 65536);
@@ -299,7 +300,8 @@ uint32_t pick_chunk(const hac_opts_t* opts, uint64_t max_col_nnz)
 int check_opts(const hac_opts_t* opts)
 {
     if (!opts) return HAC_OK;
-    if (opts->lut_bits > 12 || opts->chunk_nnz > 65536 || opts->ri_coding > HAC_RI_RICE) return HAC_EINVAL;
+    if (opts->lut_bits > 12 || (opts->chunk_nnz > 65536 && opts->chunk_nnz != HAC_CHUNK_PER_COLUMN) ||
+        opts->ri_coding > HAC_RI_RICE) return HAC_EINVAL;
     if (opts->chunk_rows && opts->ri_coding == HAC_RI_RICE) return HAC_EINVAL;
     return HAC_OK;
 }
@@ -334,7 +336,8 @@ struct ColumnIndex {
             const uint64_t cnt = s.cb[j + 1] - s.cb[j];
             col_chunk[j] = (uint32_t)n_chunks;
             col_pos[j] = (uint32_t)s.cb[j];
-            n_chunks += (cnt + chunk - 1) / chunk;
+            const uint32_t c = chunk_of_column(chunk, cnt);
+            n_chunks += (cnt + c - 1) / c;
         }
         col_chunk[m] = (uint32_t)n_chunks;
         col_pos[m] = (uint32_t)s.cb[m];
@@ -505,8 +508,9 @@ int write_hac(uint8_t* base, const Scan& s, const Dict& D, LayerPlan& P)
         P.ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
         const uint64_t col_bit0 = bw.bitpos;
         if (d.chunk_rows) nz_bit.assign((size_t)(pend - p0), 0);
+        const uint32_t cj = chunk_of_column(Cn, pend - p0);
         for (uint64_t p = p0; p < pend; ++p) {
-            if ((p - p0) % Cn == 0) {                        // a chunk starts before this non-zero's zero run
+            if ((p - p0) % cj == 0) {                        // a chunk starts before this non-zero's zero run
                 const uint64_t rel = bw.bitpos - col_bit0;
                 if (ent_bits == 32) ent[chunk] = (uint32_t)((rel << row_bits) | row);
                 else { ent[2 * chunk] = (uint32_t)row; ent[2 * chunk + 1] = (uint32_t)rel; }
@@ -618,9 +622,10 @@ int write_shac(uint8_t* base, const Scan& s, const Dict& D, LayerPlan& P)
             const uint64_t p0 = s.cb[(size_t)j], pend = s.cb[(size_t)j + 1];
             P.ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
             const uint64_t col_bit0 = bw.bitpos;
+            const uint32_t cj = chunk_of_column(Cn, pend - p0);
             for (uint64_t p = p0; p < pend; ++p) {
                 const uint32_t g = gap_at(s, p, p0);
-                if ((p - p0) % Cn == 0) {
+                if ((p - p0) % cj == 0) {
                     const uint64_t rel = bw.bitpos - col_bit0;
                     const uint64_t row = (uint64_t)s.ri[(size_t)p] - g;      // the row the gap counts from
                     if (ent_bits == 32) ent[chunk] = (uint32_t)((rel << row_bits) | row);
@@ -650,8 +655,9 @@ int write_shac(uint8_t* base, const Scan& s, const Dict& D, LayerPlan& P)
             P.ci.col_bit[(size_t)j] = (uint32_t)bw.bitpos;
             const uint64_t col_bit0 = bw.bitpos;
             if (d.chunk_rows) nz_bit.assign((size_t)(pend - p0), 0);
+            const uint32_t cj = chunk_of_column(Cn, pend - p0);
             for (uint64_t p = p0; p < pend; ++p) {
-                if ((p - p0) % Cn == 0) {
+                if ((p - p0) % cj == 0) {
                     const uint64_t rel = bw.bitpos - col_bit0;
                     if (ent_bits == 16) ent16[chunk] = (uint16_t)rel; else ent32[chunk] = (uint32_t)rel;
                     ++chunk;
@@ -1016,7 +1022,7 @@ int check_desc(const hac_desc_t& d, size_t bytes, bool in_net)
     if (!in_net && d.k_sym > d.n * d.m) return HAC_EFORMAT;
     if (in_net ? (d.k_sym == 0 && d.total_bits != 0) : ((d.k_sym == 0) != (d.total_bits == 0))) return HAC_EFORMAT;
     if (d.k_sym > 0 && (d.lmax < 1)) return HAC_EFORMAT;
-    if (d.chunk < 1 || d.chunk > 65536) return HAC_EFORMAT;
+    if (chunk_base(d.chunk) < 1 || chunk_base(d.chunk) > 65536) return HAC_EFORMAT;
     if (d.ri_coding > HAC_RI_RICE) return HAC_EFORMAT;
     if (d.max_col_bits > d.total_bits || d.max_col_nnz > d.nnz || d.max_col_nnz > d.n) return HAC_EFORMAT;
     const size_t tot = (size_t)d.blob_bytes;
@@ -1229,7 +1235,8 @@ int check_index_shallow(const View& v)
         if (v.colpos[j] > v.colpos[j + 1] || v.colbit[j] > v.colbit[j + 1]) return HAC_EFORMAT;
         const uint64_t cnt = v.colpos[j + 1] - v.colpos[j];
         if (cnt > d.n) return HAC_EFORMAT;
-        if ((uint64_t)v.colchunk[j + 1] - v.colchunk[j] != (cnt + d.chunk - 1) / d.chunk) return HAC_EFORMAT;
+        const uint32_t cj = chunk_of_column(d.chunk, cnt);
+        if ((uint64_t)v.colchunk[j + 1] - v.colchunk[j] != (cnt + cj - 1) / cj) return HAC_EFORMAT;
         max_nnz = std::max(max_nnz, cnt);
         const uint64_t bits = v.colbit[j + 1] - v.colbit[j];
         max_bits = std::max<uint64_t>(max_bits, bits);
@@ -1297,7 +1304,7 @@ int check_deep(const View& v)
                 if (s < 0) return HAC_EFORMAT;
                 if (d.has_zero && s == 0) continue;
                 tile_add(i);
-                if ((pos - v.colpos[j]) % d.chunk == 0) {     // first non-zero of a chunk
+                if ((pos - v.colpos[j]) % chunk_of_column(d.chunk, v.colpos[j + 1] - v.colpos[j]) == 0) {     // first non-zero of a chunk
                     uint64_t rel, row;
                     if (g >= v.colchunk[j + 1]) return HAC_EFORMAT;
                     v.entry(g, rel, row);
@@ -1318,7 +1325,7 @@ int check_deep(const View& v)
             uint64_t g = v.colchunk[j];
             int64_t prev = -1;
             for (uint64_t p = v.colpos[j]; p < v.colpos[j + 1]; ++p) {
-                if ((p - v.colpos[j]) % d.chunk == 0) {
+                if ((p - v.colpos[j]) % chunk_of_column(d.chunk, v.colpos[j + 1] - v.colpos[j]) == 0) {
                     uint64_t rel, row;
                     v.entry(g, rel, row);
                     if (rel != dec.bitpos - v.colbit[j] || row != (uint64_t)(prev + 1)) return HAC_EFORMAT;
@@ -1344,7 +1351,7 @@ int check_deep(const View& v)
             int64_t prev = -1;
             uint64_t q = 0;                                   // next entry of the row index to check
             for (uint64_t p = v.colpos[j]; p < v.colpos[j + 1]; ++p) {
-                if ((p - v.colpos[j]) % d.chunk == 0) {
+                if ((p - v.colpos[j]) % chunk_of_column(d.chunk, v.colpos[j + 1] - v.colpos[j]) == 0) {
                     uint64_t rel, row;
                     v.entry(g, rel, row);
                     if (rel != dec.bitpos - v.colbit[j]) return HAC_EFORMAT;

@@ -39,6 +39,25 @@ uint64_t row_index_entries(const hac_desc_t& d);     // m * (nq + 1), or 0 witho
 uint32_t pick_chunk_rows(const hac_opts_t* opts, uint64_t n, uint64_t m, uint64_t nnz);
 uint32_t pick_lut_bits(const hac_opts_t* opts, uint32_t lmax);
 uint32_t pick_chunk(const hac_opts_t* opts, uint64_t max_col_nnz);
+// hac_desc_t.chunk: the chunk size, or with bit 31 set the smallest chunk size of a blob whose
+// columns have chunk sizes of their own: column j is cut into chunks of
+// max(smallest, ceil(non-zeros of j / 64)) non-zeros, so that no column has more than 64 chunks
+// and a long column fills the 64 lanes of the wavefront that decodes it
+constexpr uint32_t kChunkPerColumn = 0x80000000u;
+constexpr uint32_t kChunkPerColumnLeast = 4;
+#if defined(__HIP__)
+#define HAC_HOST_DEVICE __host__ __device__
+#else
+#define HAC_HOST_DEVICE
+#endif
+HAC_HOST_DEVICE inline uint32_t chunk_base(uint32_t c) { return c & ~kChunkPerColumn; }
+HAC_HOST_DEVICE inline uint32_t chunk_of_column(uint32_t c, uint64_t col_nnz)
+{
+    const uint32_t base = c & ~kChunkPerColumn;
+    if (!(c & kChunkPerColumn)) return base;
+    const uint64_t per = (col_nnz + 63) / 64;
+    return per > base ? (uint32_t)per : base;
+}
 int check_opts(const hac_opts_t* opts);
 uint32_t rice_length(uint32_t d, uint32_t k);
 

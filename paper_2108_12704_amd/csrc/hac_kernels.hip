@@ -75,9 +75,10 @@ decode_kernel(DevBlob d, float* vals, int32_t* sym, int32_t* row_out, int32_t* c
     ChunkState st;
     st.bp = d.colbit[col] + rel;
     st.row = row0;
-    st.wpos = d.colpos[col] + (g - d.colchunk[col]) * d.chunk;
     const uint32_t cend = d.colpos[col + 1];
-    st.wend = st.wpos + d.chunk < cend ? st.wpos + d.chunk : cend;
+    const uint32_t chunk = hac_internal::chunk_of_column(d.chunk, cend - d.colpos[col]);
+    st.wpos = d.colpos[col] + (g - d.colchunk[col]) * chunk;
+    st.wend = st.wpos + chunk < cend ? st.wpos + chunk : cend;
     WordSrc<false> src = { d.stream, 0 };
     if (SHAC && d.rice) {
         gap_advance_slow(d, tb, src, st, st.wend, [&](uint32_t p, uint32_t row, uint32_t s, float v) {
@@ -172,9 +173,10 @@ decode_to_index_kernel(DevBlob d, IdxT* idx, uint64_t pitch, uint32_t shac, uint
         entry_fields(d, ent_raw, rel, row0);
         st.bp = d.colbit[col] + rel;
         st.row = row0;
-        st.wpos = d.colpos[col] + (g - d.colchunk[col]) * d.chunk;
         const uint32_t cend = d.colpos[col + 1];
-        st.wend = st.wpos + d.chunk < cend ? st.wpos + d.chunk : cend;
+        const uint32_t chunk = hac_internal::chunk_of_column(d.chunk, cend - d.colpos[col]);
+        st.wpos = d.colpos[col] + (g - d.colchunk[col]) * chunk;
+        st.wend = st.wpos + chunk < cend ? st.wpos + chunk : cend;
     }
     // The chunks of a block follow one another in the stream: from the first one's start to the
     // start of the chunk after the last one (or the end of the stream) is one contiguous range.
@@ -662,8 +664,9 @@ dot_batch_kernel(DevBlob d, const float* __restrict__ XT, uint32_t Bp, uint32_t 
         entry_fields(d, ent_raw, ent_rel, ent_row);
         st.bp = col_bit0 + ent_rel;
         st.row = ent_row;
-        st.wpos = col_pos0 + (g - col_chunk0) * d.chunk;
-        st.wend = st.wpos + d.chunk < col_pos1 ? st.wpos + d.chunk : col_pos1;
+        const uint32_t chunk = hac_internal::chunk_of_column(d.chunk, col_pos1 - col_pos0);
+        st.wpos = col_pos0 + (g - col_chunk0) * chunk;
+        st.wend = st.wpos + chunk < col_pos1 ? st.wpos + chunk : col_pos1;
         if (!active) { st.wpos = 0; st.wend = 0; }
         const uint32_t pbeg = (uint32_t)__shfl((int)st.wpos, 0, kWave);
         const uint32_t pend = (uint32_t)__shfl((int)st.wend, (int)(nact - 1), kWave);
@@ -825,8 +828,9 @@ dot_small_kernel(DevBlob d, const float* __restrict__ XT, uint32_t B, uint64_t l
         entry_fields(d, ent_raw, ent_rel, ent_row);
         st.bp = col_bit0 + ent_rel;
         st.row = ent_row;
-        st.wpos = col_pos0 + (g - col_chunk0) * d.chunk;
-        st.wend = st.wpos + d.chunk < col_pos1 ? st.wpos + d.chunk : col_pos1;
+        const uint32_t chunk = hac_internal::chunk_of_column(d.chunk, col_pos1 - col_pos0);
+        st.wpos = col_pos0 + (g - col_chunk0) * chunk;
+        st.wend = st.wpos + chunk < col_pos1 ? st.wpos + chunk : col_pos1;
         if (!active) { st.wpos = 0; st.wend = 0; }
         if (gb + kWave + lane < g1) ent_raw = request_entry(d, gb + kWave + lane);
 
@@ -900,7 +904,7 @@ bool desc_plausible(const hac_desc_t* d)
     if (!d || d->magic != 0x31434148u || d->version != 2) return false;
     if (d->format != HAC_FORMAT_HAC && d->format != HAC_FORMAT_SHAC && d->format != HAC_FORMAT_IM) return false;
     if (d->n < 1 || d->m < 1 || d->n > 0x7fffffffull || d->m > 0x7fffffffull) return false;
-    if (d->format != HAC_FORMAT_IM && (d->chunk < 1 || d->chunk > 65536 || d->lut_bits < 1 || d->lut_bits > 12)) return false;
+    if (d->format != HAC_FORMAT_IM && (hac_internal::chunk_base(d->chunk) < 1 || hac_internal::chunk_base(d->chunk) > 65536 || d->lut_bits < 1 || d->lut_bits > 12)) return false;
     return true;
 }
 
@@ -911,7 +915,7 @@ int make_dev(const hac_desc_t* desc, const void* d_blob, uint32_t format, DevBlo
     if (reinterpret_cast<uintptr_t>(d_blob) % 256) return HAC_EINVAL;
     if (desc->lut_bits < 1 || desc->lut_bits > 12 || desc->lmax > 32) return HAC_EINVAL;
     if (desc->n > 0x7fffffffull || desc->m > 0x7fffffffull || desc->nnz > 0xfffffff0ull ||
-        desc->n_chunks > 0xfffffff0ull || desc->chunk < 1 || desc->chunk > 65536) return HAC_EINVAL;
+        desc->n_chunks > 0xfffffff0ull || hac_internal::chunk_base(desc->chunk) < 1 || hac_internal::chunk_base(desc->chunk) > 65536) return HAC_EINVAL;
     if (desc->ent_bits != 16 && desc->ent_bits != 32 && desc->ent_bits != 64) return HAC_EINVAL;
     if (desc->row_bits > 31 || desc->ri_bits > 32) return HAC_EINVAL;
     const bool rice = format == HAC_FORMAT_SHAC && desc->ri_coding == HAC_RI_RICE;
@@ -1291,7 +1295,9 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     if (!sbuf_words) sbuf_words = default_staging_words(desc, cpw);
     if (!list_cap) {
         double est = (double)desc->max_col_nnz * cpw;
-        const double one_batch = 64.0 * desc->chunk;
+        // (with chunk sizes per column a column has at most 64 chunks: a batch then never holds more than the longest column)
+        const double one_batch = (desc->chunk & hac_internal::kChunkPerColumn) ? (double)desc->max_col_nnz * cpw
+                                                                               : 64.0 * desc->chunk;
         if (est > one_batch) est = one_batch;
         list_cap = round_up((uint32_t)(est < 2048.0 ? (est > 1.0 ? est : 1.0) : 2048.0), 64);
     }
@@ -1330,7 +1336,10 @@ int dot_impl(uint32_t format, const hac_desc_t* desc, const void* d_blob,
     }
     // a column that exceeds the list window (or the 64 chunks of one batch) parks partial sums in LDS
     // (no split is possible when all chunks of a wave fit one batch of 64 and all its non-zeros one window)
-    const uint64_t col_chunks = (desc->max_col_nnz + desc->chunk - 1) / desc->chunk;
+    // most chunks in one column (with chunk sizes per column: never more than 64)
+    const uint32_t chunk_least = hac_internal::chunk_base(desc->chunk);
+    uint64_t col_chunks = (desc->max_col_nnz + chunk_least - 1) / chunk_least;
+    if ((desc->chunk & hac_internal::kChunkPerColumn) && col_chunks > 64) col_chunks = 64;
     const bool may_split = (uint64_t)cpw * col_chunks > 64 || (uint64_t)cpw * desc->max_col_nnz > list_cap;
     const uint32_t part_words = may_split ? bs.npass * bs.nb * 64u : 0u;
     const size_t per_wave = 4ull * sbuf_words + 8ull * list_cap + 4ull * part_words;

@@ -149,7 +149,7 @@ def test_randomized_parity(hac):
     rng = np.random.default_rng(99)
     for name, W in workloads.random_cases(40, seed=77):
         n, m = W.shape
-        chunk = int(rng.choice([0, 0, 1, 7, 200]))
+        chunk = int(rng.choice([0, 0, 1, 7, 200, hac.CHUNK_PER_COLUMN]))
         blobs = [(hac.hac_dot, hac.hac_encode(W, chunk_nnz=chunk)), (hac.shac_dot, hac.shac_encode(W, chunk_nnz=chunk)),
                  (hac.shac_dot, hac.shac_encode(W, chunk_nnz=chunk, ri_coding=1)), (hac.im_dot, hac.im_encode(W))]
         for B in (1, int(rng.integers(2, 5)), int(rng.integers(5, 140))):

@@ -756,3 +756,86 @@ def test_network_blob_layers_carry_the_row_index():
     for l, d in enumerate(nb.layers):
         assert int(d.chunk_rows) > 0 and int(d.off_row_ent) > 0
         assert int(d.max_tile_nnz) == fullest_tile(Ws[l], int(d.chunk_rows))
+
+
+# ---- chunk sizes per column (hac_opts_t.chunk_nnz = HAC_CHUNK_PER_COLUMN) ----
+
+def uneven_columns():
+    """columns of very different lengths: empty, short (chunks of 4), and long ones whose chunk size
+    is ceil(non-zeros / 64)"""
+    rng = np.random.default_rng(77)
+    n, m = 1500, 11
+    dens = [0.0, 0.01, 0.05, 0.17, 0.171, 0.3, 0.5, 0.8, 1.0, 0.0, 0.43]
+    W = np.zeros((n, m), dtype=np.float32)
+    vals = np.array([-1.5, -0.25, 0.5, 0.75, 2.0], dtype=np.float32)
+    for j, p in enumerate(dens):
+        mask = rng.random(n) < p
+        W[mask, j] = vals[rng.integers(0, len(vals), int(mask.sum()))]
+    return W
+
+
+def chunk_size_of(desc, cnt):
+    c = int(desc.chunk)
+    base = c & 0x7fffffff
+    return max(base, -(-int(cnt) // 64)) if c & hac.CHUNK_FLAG_PER_COLUMN else base
+
+
+def test_per_column_chunk_sizes_against_oracle():
+    W = uneven_columns()
+    n, m = W.shape
+    counts = np.count_nonzero(W, axis=0)
+    assert counts.max() > 64 * 4 and len({max(4, -(-int(c) // 64)) for c in counts}) >= 5
+    # HAC
+    blob = hac.hac_encode(W, chunk_nnz=hac.CHUNK_PER_COLUMN)
+    assert blob.validate(deep=True) == 0
+    d = blob.desc
+    assert int(d.chunk) == hac.CHUNK_FLAG_PER_COLUMN | 4
+    values, sym = formats.hac_symbols(W)
+    lens, words = codes_from_blob(blob)
+    cum = np.concatenate(([0], np.cumsum(lens[sym])))
+    isnz = values[sym] != 0
+    col_chunk = blob.section("off_col_chunk", np.uint32, m + 1)
+    ents = chunk_entries(blob)
+    g = 0
+    for j in range(m):
+        C = chunk_size_of(d, counts[j])
+        assert C == max(4, -(-int(counts[j]) // 64))
+        assert int(col_chunk[j]) == g and -(-int(counts[j]) // C) <= 64
+        nzidx = np.flatnonzero(isnz[j * n:(j + 1) * n])
+        for k in range(0, len(nzidx), C):
+            start = 0 if k == 0 else nzidx[k - 1] + 1
+            assert ents[g] == (cum[j * n + start] - cum[j * n], start), (j, k)
+            g += 1
+    assert g == int(d.n_chunks) == int(col_chunk[m])
+    Wd, symd = blob.decode_host()
+    assert np.array_equal(Wd.view(np.uint32), W.view(np.uint32)) and np.array_equal(symd, sym)
+    # sHAC with ri fields, and with Rice-coded gaps
+    os_ = formats.shac_encode(W)
+    for kw in ({}, {"ri_coding": hac.RI_RICE}):
+        blob = hac.shac_encode(W, chunk_nnz=hac.CHUNK_PER_COLUMN, **kw)
+        assert blob.validate(deep=True) == 0
+        d = blob.desc
+        col_chunk = blob.section("off_col_chunk", np.uint32, m + 1)
+        expect = np.concatenate(([0], np.cumsum([-(-int(c) // chunk_size_of(d, c)) for c in counts])))
+        assert np.array_equal(col_chunk, expect) and int(d.n_chunks) == expect[-1]
+        Wd, symd, rowd, cold = blob.decode_host()
+        assert np.array_equal(Wd.view(np.uint32), W.view(np.uint32))
+        if not kw:
+            values_s, sym_s, row, col = formats.shac_symbols(W)
+            lens_s = blob.section("off_codelen", np.uint8, len(values_s)).astype(int)
+            cum_s = np.concatenate(([0], np.cumsum(lens_s[sym_s])))
+            ents = chunk_entries(blob)
+            g = 0
+            for j in range(m):
+                for p in range(int(os_.cb[j]), int(os_.cb[j + 1]), chunk_size_of(d, counts[j])):
+                    assert ents[g] == (cum_s[p] - cum_s[os_.cb[j]], 0)
+                    g += 1
+            assert g == int(d.n_chunks)
+    # a damaged chunk count is caught, and the option is refused where it makes no sense
+    bad = hac.hac_encode(W, chunk_nnz=hac.CHUNK_PER_COLUMN)
+    raw = bytearray(bad.data.tobytes())
+    off = int(bad.desc.off_col_chunk) + 4 * 5
+    raw[off] ^= 1
+    assert hac.Blob(np.frombuffer(bytes(raw), dtype=np.uint8).copy()).validate(deep=False) != 0
+    with pytest.raises(hac.HacError):
+        hac.hac_encode(W, chunk_nnz=70000)
